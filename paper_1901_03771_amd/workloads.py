@@ -1,0 +1,158 @@
+"""Seeded synthetic inputs and the NumPy-style user programs run on them.
+
+This module holds no arithmetic of the method (no recording, fusion, code
+generation or kernels) and imports neither the GPU binding nor the CPU
+evaluator: it only draws input arrays and states, as ordinary array
+expressions over an array module ``xp``, the programs a user of a NumPy
+drop-in replacement would write (Section 1 and Section 4.1 of the paper:
+the user changes the import, not the program).  The same program text is
+handed to the lazy GPU module and to the eager CPU evaluator.
+
+The paper's own benchmark inputs are not published (its plots carry no sizes
+or distributions); the configurations below are synthetic stand-ins shaped
+like its samples: a long pointwise chain (Black-Scholes-like), a broadcast
+normalisation, a row softmax, a two-level slice stencil (Jacobi / image
+processing, Listing 6) and a dot-bounded logistic-regression step (the
+MNIST / RNN pattern of Listing 2).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+SEED_BASE = 190103771
+
+# name -> full-size shape parameters; "small" variants keep several tiles and
+# a ragged tail while staying cheap for an op-by-op CPU evaluation.
+FULL = {
+    "chain": dict(n=1 << 20),
+    "normalize": dict(rows=8192, cols=8192),
+    "softmax": dict(rows=16384, cols=4096),
+    "stencil": dict(rows=8192, cols=8192),
+    "logreg": dict(rows=262144, cols=512),
+}
+SMALL = {
+    "chain": dict(n=100_003),
+    "normalize": dict(rows=203, cols=1501),
+    "softmax": dict(rows=67, cols=1000),
+    "stencil": dict(rows=151, cols=1234),
+    "logreg": dict(rows=3001, cols=200),
+}
+CONFIG_INDEX = {"chain": 0, "normalize": 1, "softmax": 2, "stencil": 3, "logreg": 4}
+
+
+def rng_for(name: str, salt: int = 0) -> np.random.Generator:
+    return np.random.default_rng(SEED_BASE + CONFIG_INDEX[name] + 1000 * salt)
+
+
+def make_inputs(name: str, salt: int = 0, **size) -> dict:
+    """Draw the input arrays of configuration ``name`` (float32, C-contiguous)."""
+    p = dict(FULL[name])
+    p.update(size)
+    g = rng_for(name, salt)
+    f32 = np.float32
+    if name == "chain":
+        n = p["n"]
+        return dict(a=g.uniform(-1, 1, n).astype(f32), b=g.uniform(-1, 1, n).astype(f32))
+    if name == "normalize":
+        r, c = p["rows"], p["cols"]
+        return dict(
+            X=g.standard_normal((r, c), dtype=f32),
+            mu=g.uniform(-0.5, 0.5, (1, c)).astype(f32),
+            sigma=g.uniform(0.5, 2.0, (1, c)).astype(f32),
+            gamma=g.uniform(0.5, 1.5, (c,)).astype(f32),
+            beta=g.uniform(0.5, 1.5, (c,)).astype(f32),
+        )
+    if name == "softmax":
+        r, c = p["rows"], p["cols"]
+        # N(0, 4) is read as variance 4, i.e. standard deviation 2.
+        return dict(X=(2.0 * g.standard_normal((r, c), dtype=f32)).astype(f32))
+    if name == "stencil":
+        r, c = p["rows"], p["cols"]
+        return dict(I=(g.random((r, c), dtype=f32) * f32(255.0)).astype(f32))
+    if name == "logreg":
+        r, c = p["rows"], p["cols"]
+        # N(0, 0.05) is read as variance 0.05.
+        return dict(
+            X=g.standard_normal((r, c), dtype=f32),
+            w=(np.sqrt(0.05) * g.standard_normal(c)).astype(f32),
+            y=(g.random(r) < 0.5).astype(f32),
+        )
+    raise KeyError(name)
+
+
+# ---- user programs (array expressions over a NumPy-like module xp) ----------
+
+def chain(xp, a, b):
+    return ((a + b) * (a - b) + 2.5 * a) / (abs(b) + 1.0) - xp.exp(-a * a)
+
+
+def normalize(xp, X, mu, sigma, gamma, beta):
+    return xp.maximum((X - mu) / sigma * gamma + beta, 0)
+
+
+def softmax(xp, X):
+    m = xp.max(X, axis=1, keepdims=True)
+    e = xp.exp(X - m)
+    return e / xp.sum(e, axis=1, keepdims=True)
+
+
+def stencil(xp, I):
+    B = 0.2 * (I[1:-1, 1:-1] + I[:-2, 1:-1] + I[2:, 1:-1] + I[1:-1, :-2] + I[1:-1, 2:])
+    return xp.sqrt((B[1:-1, 2:] - B[1:-1, :-2]) ** 2 + (B[2:, 1:-1] - B[:-2, 1:-1]) ** 2)
+
+
+def logreg(xp, X, w, y):
+    n = X.shape[0]
+    p = 1.0 / (1.0 + xp.exp(-(X @ w)))
+    r = p - y
+    g = (X.T @ r) / n + 1e-4 * w
+    return w - 0.1 * g
+
+
+PROGRAMS = {"chain": chain, "normalize": normalize, "softmax": softmax, "stencil": stencil, "logreg": logreg}
+
+
+def unique_bytes(name: str, **size) -> int:
+    """Unique input bytes + output bytes of one evaluation (the metric's numerator)."""
+    p = dict(FULL[name])
+    p.update(size)
+    if name == "chain":
+        return 12 * p["n"]
+    if name == "normalize":
+        return 8 * p["rows"] * p["cols"] + 16 * p["cols"]
+    if name == "softmax":
+        return 8 * p["rows"] * p["cols"]
+    if name == "stencil":
+        return 4 * p["rows"] * p["cols"] + 4 * (p["rows"] - 4) * (p["cols"] - 4)
+    if name == "logreg":
+        return 4 * p["rows"] * p["cols"] + 4 * p["cols"] + 4 * p["rows"] + 4 * p["cols"]
+    raise KeyError(name)
+
+
+# ---- the paper's own small listings ----------------------------------------
+
+def listing1(xp, x, y):
+    """Listing 1: z = x*x + 2*x*y + y*y on int32 arrays."""
+    return x * x + 2 * x * y + y * y
+
+
+def mnist(xp, W, a, b):
+    """Listing 2, with W of shape (200, 10) so that W.T @ a is defined and
+    the builtin max read as an elementwise maximum."""
+    x = xp.transpose(W).dot(xp.maximum(a, 0)) + b
+    return 1.0 / (1.0 + xp.exp(-x))
+
+
+def jacobi_sweep(xp, grid):
+    """Right-hand side of one sweep of Listing 6 (the slice reads)."""
+    center = grid[1:-1, 1:-1]
+    north = grid[0:-2, 1:-1]
+    east = grid[1:-1, 2:]
+    west = grid[1:-1, 0:-2]
+    south = grid[2:, 1:-1]
+    return 0.2 * (center + north + east + west + south)
+
+
+def inner_product(xp, a, b):
+    """Listing 5: map a[i]*b[i], reduce with +."""
+    return xp.sum(a * b)

@@ -1,0 +1,529 @@
+"""Pins for the CPU oracle (oracle/eager.cpp) against things other than itself:
+the paper's worked example, closed forms, brute force on tiny arrays written
+here as plain Python loops, exact rational arithmetic, and NumPy as a third
+opinion.  A dropped term, a wrong sign or index, or a transposed operand in
+the oracle fails at least one of these."""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle as ora
+from paper_1901_03771_amd import workloads as wl
+from helpers import elementwise_close, ulp_of
+
+f32 = np.float32
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng(seed=0):
+    return np.random.default_rng(1901 + seed)
+
+
+# ---------------------------------------------------------------- broadcast --
+BROADCAST_TABLE = [
+    ((10, 20), (20,), (10, 20)),
+    ((64, 48), (1, 48), (64, 48)),
+    ((64, 48), (48,), (64, 48)),
+    ((32, 16), (32, 1), (32, 16)),
+    ((3, 1), (1, 4), (3, 4)),
+    ((5,), (5,), (5,)),
+    ((0, 3), (1, 3), (0, 3)),
+    ((2, 1, 4), (3, 1), (2, 3, 4)),
+    ((7, 1, 5), (1, 6, 1), (7, 6, 5)),
+    ((2, 3), (2,), None),
+    ((4,), (5,), None),
+    ((2, 3), (3, 2), None),
+]
+
+
+@pytest.mark.parametrize("sa,sb,expect", BROADCAST_TABLE)
+def test_broadcast_table(sa, sb, expect):
+    a = ora.array(np.ones(sa, f32))
+    b = ora.array(np.ones(sb, f32))
+    if expect is None:
+        with pytest.raises(ora.OracleError):
+            ora.add(a, b)
+    else:
+        assert ora.add(a, b).shape == expect
+
+
+def test_broadcast_values_brute_force():
+    # hand loop: out[i][j][k] = a[i][0][k] - b[j][0]
+    g = rng(1)
+    a = g.standard_normal((2, 1, 4)).astype(f32)
+    b = g.standard_normal((3, 1)).astype(f32)
+    got = (ora.array(a) - ora.array(b)).numpy()
+    for i, j, k in itertools.product(range(2), range(3), range(4)):
+        assert got[i, j, k] == f32(a[i, 0, k] - b[j, 0])
+
+
+def test_scalar_broadcast_rank0():
+    a = np.arange(5, dtype=f32)
+    got = (ora.array(a) + 1.5).numpy()
+    assert got.shape == (5,)
+    assert np.array_equal(got, a + f32(1.5))
+
+
+# ------------------------------------------------------ paper's Listing 1 ----
+def _read_golden(name):
+    rows = []
+    with open(os.path.join(GOLDEN, name)) as fh:
+        for line in fh:
+            if line.strip() and not line.startswith("#"):
+                rows.append(np.array(line.split(), dtype=np.int32))
+    return rows
+
+
+def test_listing1_literal_values():
+    x, y, z = _read_golden("listing1_literal.txt")
+    got = wl.listing1(ora, ora.array(x), ora.array(y)).numpy()
+    assert got.dtype == np.int32
+    assert np.array_equal(got, z)
+
+
+def test_listing1_shape_reading_ring_identity_with_wraparound():
+    # Listing 3 reads x as [10][20], y as [20]; z == (x+y)^2 holds exactly in
+    # the ring Z/2^32, overflow included.
+    g = rng(2)
+    x = g.integers(-2**31, 2**31 - 1, (10, 20), dtype=np.int64).astype(np.int32)
+    y = g.integers(-2**31, 2**31 - 1, (20,), dtype=np.int64).astype(np.int32)
+    got = wl.listing1(ora, ora.array(x), ora.array(y)).numpy()
+    # Python big ints, reduced mod 2^32, then reinterpreted as signed
+    for i, j in itertools.product(range(10), range(20)):
+        v = (int(x[i, j]) + int(y[j])) ** 2 % (1 << 32)
+        v = v - (1 << 32) if v >= (1 << 31) else v
+        assert int(got[i, j]) == v
+
+
+def test_int32_abs_neg_edge():
+    x = np.array([-2**31, -5, 0, 7, 2**31 - 1], dtype=np.int32)
+    assert np.array_equal(abs(ora.array(x)).numpy(), np.array([-2**31, 5, 0, 7, 2**31 - 1], np.int32))
+    assert np.array_equal((-ora.array(x)).numpy(), np.array([-2**31, 5, 0, -7, -(2**31 - 1)], np.int32))
+
+
+def test_float_scalar_with_int_array_is_rejected():
+    with pytest.raises(ora.OracleError):
+        ora.array(np.arange(3, dtype=np.int32)) * 0.5
+    with pytest.raises(ora.OracleError):
+        ora.array(np.arange(3, dtype=np.int32)) + ora.array(np.ones(3, f32))
+
+
+# ----------------------------------------------------------------- identities --
+def test_identities():
+    g = rng(3)
+    x = (g.standard_normal(1000) * 100).astype(f32)
+    X = ora.array(x)
+    assert np.all((X - X).numpy() == 0)
+    assert np.array_equal((X * 1.0).numpy(), x)
+    assert np.array_equal(ora.maximum(X, X).numpy(), x)
+    assert np.array_equal(abs(-X).numpy(), abs(X).numpy())
+    assert np.array_equal(ora.sqrt(ora.square(X)).numpy(), np.abs(x))  # |x| ~ 100: x^2 is far from over/underflow
+    assert np.array_equal((X + 0.0).numpy(), x)
+    assert np.array_equal((X / 1.0).numpy(), x)
+    assert np.array_equal((-(-X)).numpy(), x)
+
+
+def test_sub_is_not_commuted_and_div_is_not_flipped():
+    a, b = ora.array(np.array([7.0], f32)), ora.array(np.array([2.0], f32))
+    assert (a - b).numpy()[0] == 5.0 and (b - a).numpy()[0] == -5.0
+    assert (a / b).numpy()[0] == 3.5 and (b / a).numpy()[0] == f32(2.0) / f32(7.0)
+    assert (10 - a).numpy()[0] == 3.0 and (14 / a).numpy()[0] == 2.0
+
+
+def test_f32_rounding_is_single_op():
+    # 1 + 2^-24 rounds to 1 in binary32 (ties to even); a double-precision
+    # intermediate would keep it.
+    one, tiny = ora.array(np.array([1.0], f32)), ora.array(np.array([2.0**-24], f32))
+    assert ((one + tiny) - one).numpy()[0] == 0.0
+    # scalar 0.2 is rounded to binary32 before use
+    assert (one * 0.2).numpy()[0] == f32(0.2)
+    assert float((one * 0.2).numpy()[0]) != 0.2
+
+
+def test_maximum_nan_and_minimum():
+    a = np.array([1.0, np.nan, 3.0, -0.0, 5.0], f32)
+    b = np.array([2.0, 1.0, np.nan, 0.0, -5.0], f32)
+    mx = ora.maximum(ora.array(a), ora.array(b)).numpy()
+    mn = ora.minimum(ora.array(a), ora.array(b)).numpy()
+    assert mx[0] == 2 and np.isnan(mx[1]) and np.isnan(mx[2]) and mx[3] == 0 and mx[4] == 5
+    assert mn[0] == 1 and np.isnan(mn[1]) and np.isnan(mn[2]) and mn[3] == 0 and mn[4] == -5
+
+
+# ----------------------------------------------- transcendentals, exact pins --
+def _exp_fraction(x: Fraction, terms=60) -> Fraction:
+    s, t = Fraction(0), Fraction(1)
+    for k in range(terms):
+        s += t
+        t = t * x / (k + 1)
+    return s
+
+
+def _round_f32(q: Fraction) -> np.float32:
+    # nearest binary32 to an exact rational (value well inside the normal range)
+    lo = np.float32(float(q))
+    cands = [lo, np.nextafter(lo, f32(np.inf)), np.nextafter(lo, f32(-np.inf))]
+    return min(cands, key=lambda c: abs(Fraction(float(c)) - q))
+
+
+@pytest.mark.parametrize("xv", [0.0, 1.0, -1.0, 0.5, -0.3125, 2.75, -7.5, 0.001953125])
+def test_exp_is_correctly_rounded_on_exact_rational_series(xv):
+    got = ora.exp(ora.array(np.array([xv], f32))).numpy()[0]
+    want = _round_f32(_exp_fraction(Fraction(xv)))
+    assert got == want
+
+
+def test_log_tanh_special_values_and_inverse():
+    x = np.array([0.25, 1.0, 3.0, 10.0], f32)
+    lg = ora.log(ora.array(x)).numpy()
+    assert lg[1] == 0.0
+    assert np.all(elementwise_close(ora.exp(ora.array(lg)).numpy(), x, ulps=4))
+    th = ora.tanh(ora.array(np.array([0.0, 20.0, -20.0, 0.5], f32))).numpy()
+    assert th[0] == 0 and th[1] == 1 and th[2] == -1
+    e1, e2 = np.exp(np.float64(0.5)), np.exp(np.float64(-0.5))
+    assert abs(float(th[3]) - (e1 - e2) / (e1 + e2)) < 1e-7
+    assert np.isnan(ora.log(ora.array(np.array([-1.0], f32))).numpy()[0])
+    assert np.isnan(ora.sqrt(ora.array(np.array([-1.0], f32))).numpy()[0])
+
+
+# ------------------------------------------------------------------- sums ----
+@pytest.mark.parametrize("n", [0, 1, 2, 1000, 5793, 70000])
+def test_sum_arange_int(n):
+    s = ora.sum(ora.array(np.arange(n, dtype=np.int32)))
+    assert s.dtype == np.int64 and s.shape == ()
+    assert int(s.numpy()) == n * (n - 1) // 2
+
+
+@pytest.mark.parametrize("n", [1, 17, 4096, 5793])
+def test_sum_arange_f32_exact(n):
+    s = ora.sum(ora.array(np.arange(n, dtype=f32)))
+    assert s.dtype == f32
+    assert float(s.numpy()) == n * (n - 1) / 2
+
+
+def test_sum_accumulates_in_double():
+    # 2^24 + 1 + 1 ... : a binary32 accumulator would stall at 2^24.
+    x = np.ones(1 << 12, f32)
+    x[0] = 2.0**24
+    assert float(ora.sum(ora.array(x)).numpy()) == float(f32(2.0**24 + (1 << 12) - 1))
+
+
+def test_sum_ones_by_axis_and_keepdims():
+    x = ora.array(np.ones((3, 4, 5), f32))
+    for axis, shape, val in [(0, (4, 5), 3), (1, (3, 5), 4), (2, (3, 4), 5), (-1, (3, 4), 5), ((0, 2), (4,), 15), (None, (), 60)]:
+        r = ora.sum(x, axis=axis)
+        assert r.shape == shape and np.all(r.numpy() == val)
+    assert ora.sum(x, axis=1, keepdims=True).shape == (3, 1, 5)
+    assert ora.sum(x, axis=(0, 2), keepdims=True).shape == (1, 4, 1)
+    with pytest.raises(ora.OracleError):
+        ora.sum(x, axis=3)
+    with pytest.raises(ora.OracleError):
+        ora.sum(x, axis=(1, 1))
+
+
+def test_reduce_brute_force_axes():
+    g = rng(4)
+    x = g.integers(-50, 50, (3, 4, 5)).astype(f32)  # small ints: every order of summation is exact
+    X = ora.array(x)
+    got = ora.sum(X, axis=1).numpy()
+    for i, k in itertools.product(range(3), range(5)):
+        assert got[i, k] == sum(float(x[i, j, k]) for j in range(4))
+    gmx = ora.max(X, axis=(0, 2)).numpy()
+    gmn = ora.min(X, axis=0).numpy()
+    for j in range(4):
+        assert gmx[j] == max(x[i, j, k] for i in range(3) for k in range(5))
+    for j, k in itertools.product(range(4), range(5)):
+        assert gmn[j, k] == min(x[i, j, k] for i in range(3))
+
+
+def test_reduce_empty():
+    e = ora.array(np.zeros((0, 3), f32))
+    assert np.array_equal(ora.sum(e, axis=0).numpy(), np.zeros(3, f32))
+    with pytest.raises(ora.OracleError):
+        ora.max(e, axis=0)
+    assert ora.max(e, axis=1).shape == (0,)
+
+
+def test_reduce_max_propagates_nan():
+    x = np.array([[1.0, np.nan, 2.0], [1.0, 5.0, 2.0]], f32)
+    m = ora.max(ora.array(x), axis=1).numpy()
+    assert np.isnan(m[0]) and m[1] == 5
+
+
+# ------------------------------------------------------------------ slices ---
+def test_slice_brute_force_1d_against_python_range():
+    n = 6
+    x = np.arange(100, 100 + n, dtype=np.int32)
+    X = ora.array(x)
+    vals = [None] + list(range(-n - 1, n + 2))
+    for st, sp, step in itertools.product(vals, vals, (None, 1, 2, 3)):
+        want = [int(x[i]) for i in range(n)[st:sp:step]]
+        got = X[st:sp:step].numpy()
+        assert got.tolist() == want, (st, sp, step)
+
+
+def test_slice_brute_force_2d():
+    x = np.arange(42, dtype=np.int32).reshape(6, 7)
+    X = ora.array(x)
+    g = rng(5)
+    for _ in range(300):
+        r0, r1 = int(g.integers(-8, 9)), int(g.integers(-8, 9))
+        c0, c1 = int(g.integers(-9, 10)), int(g.integers(-9, 10))
+        sr, sc = int(g.integers(1, 4)), int(g.integers(1, 4))
+        got = X[r0:r1:sr, c0:c1:sc].numpy()
+        rows = list(range(6)[r0:r1:sr])
+        cols = list(range(7)[c0:c1:sc])
+        assert got.shape == (len(rows), len(cols))
+        for i, r in enumerate(rows):
+            for j, c in enumerate(cols):
+                assert got[i, j] == r * 7 + c
+    assert X[1:3].shape == (2, 7)           # trailing dims taken whole
+    assert X[2:5][1:, 3:].numpy()[0, 0] == 3 * 7 + 3  # slice of a slice
+    with pytest.raises(ora.OracleError):
+        X[::-1]
+    with pytest.raises(ora.OracleError):
+        X[:, :, :]
+
+
+def test_ops_read_through_views():
+    x = np.arange(30, dtype=f32).reshape(5, 6)
+    X = ora.array(x)
+    got = (X[1:-1, 2:] - X[:-2, :-2]).numpy()
+    for i, j in itertools.product(range(3), range(4)):
+        assert got[i, j] == x[i + 1, j + 2] - x[i, j]
+
+
+# --------------------------------------------------------------- transpose ---
+def test_transpose_rule_and_involution():
+    x = np.arange(12, dtype=np.int32).reshape(3, 4)
+    T = ora.array(x).T
+    assert T.shape == (4, 3)
+    t = T.numpy()
+    for i, j in itertools.product(range(4), range(3)):
+        assert t[i, j] == x[j, i]
+    assert np.array_equal(T.T.numpy(), x)
+    y = np.arange(24, dtype=np.int32).reshape(2, 3, 4)
+    p = ora.transpose(ora.array(y), (1, 2, 0))
+    assert p.shape == (3, 4, 2)
+    pn = p.numpy()
+    for i, j, k in itertools.product(range(3), range(4), range(2)):
+        assert pn[i, j, k] == y[k, i, j]
+    with pytest.raises(ora.OracleError):
+        ora.transpose(ora.array(y), (0, 0, 1))
+
+
+# --------------------------------------------------------------------- dot ---
+def test_dot_ones_onehot_and_hand_loop():
+    g = rng(6)
+    w = g.standard_normal(9).astype(f32)
+    ones = np.ones((4, 9), f32)
+    z = (ora.array(ones) @ ora.array(w)).numpy()
+    exact = float(f32(sum(Fraction(float(v)) for v in w)))  # exactly rounded sum
+    assert np.all(z == f32(exact))
+    sel = np.zeros((5, 9), f32)
+    idx = [3, 0, 8, 8, 2]
+    for i, k in enumerate(idx):
+        sel[i, k] = 1
+    assert np.array_equal((ora.array(sel) @ ora.array(w)).numpy(), w[idx])
+    # non-symmetric hand loop, catches a transposed operand
+    A = g.integers(-4, 5, (3, 5)).astype(f32)
+    v = g.integers(-4, 5, 5).astype(f32)
+    got = ora.dot(ora.array(A), ora.array(v)).numpy()
+    for i in range(3):
+        assert got[i] == sum(float(A[i, k]) * float(v[k]) for k in range(5))
+    u = g.integers(-4, 5, 3).astype(f32)
+    gotT = (ora.array(A).T @ ora.array(u)).numpy()
+    for k in range(5):
+        assert gotT[k] == sum(float(A[i, k]) * float(u[i]) for i in range(3))
+    B = g.integers(-4, 5, (5, 2)).astype(f32)
+    gotM = (ora.array(A) @ ora.array(B)).numpy()
+    for i, j in itertools.product(range(3), range(2)):
+        assert gotM[i, j] == sum(float(A[i, k]) * float(B[k, j]) for k in range(5))
+    with pytest.raises(ora.OracleError):
+        ora.array(A) @ ora.array(u)
+
+
+def test_inner_product_listing5_equals_dot():
+    g = rng(7)
+    a = g.integers(-8, 9, 301).astype(f32)
+    b = g.integers(-8, 9, 301).astype(f32)
+    ip = wl.inner_product(ora, ora.array(a), ora.array(b)).numpy()
+    d = ora.dot(ora.array(a), ora.array(b)).numpy()
+    assert ip.shape == () and d.shape == ()
+    assert float(ip) == float(d) == float(sum(int(x) * int(y) for x, y in zip(a, b)))
+
+
+# ----------------------------------------------------- the five programs ----
+def test_chain_equals_hand_written_scalar_loop():
+    inp = wl.make_inputs("chain", n=257)
+    got = wl.chain(ora, ora.array(inp["a"]), ora.array(inp["b"])).numpy()
+    import math
+    for i in range(257):
+        a, b = f32(inp["a"][i]), f32(inp["b"][i])
+        t = f32(f32(f32(a + b) * f32(a - b)) + f32(f32(2.5) * a))
+        d = f32(f32(abs(b)) + f32(1.0))
+        e = f32(math.exp(float(f32(f32(-a) * a))))
+        assert got[i] == f32(f32(t / d) - e)
+
+
+def test_normalize_against_hand_loop_and_numpy():
+    inp = wl.make_inputs("normalize", rows=7, cols=13)
+    got = wl.normalize(ora, *(ora.array(inp[k]) for k in ("X", "mu", "sigma", "gamma", "beta"))).numpy()
+    for i, j in itertools.product(range(7), range(13)):
+        v = f32(f32(f32(f32(inp["X"][i, j] - inp["mu"][0, j]) / inp["sigma"][0, j]) * inp["gamma"][j]) + inp["beta"][j])
+        assert got[i, j] == (v if v > 0 else f32(0))
+    want = wl.normalize(np, **inp)
+    assert want.dtype == f32 and np.array_equal(got, want)
+
+
+def test_softmax_properties():
+    inp = wl.make_inputs("softmax", rows=9, cols=300)
+    X = inp["X"]
+    out = wl.softmax(ora, ora.array(X)).numpy()
+    assert np.all(np.abs(out.astype(np.float64).sum(axis=1) - 1) < 1e-6)
+    # the row maximum maps to exp(0)/s = 1/s exactly
+    e = np.exp((X - X.max(axis=1, keepdims=True)).astype(np.float64))
+    j = X.argmax(axis=1)
+    s = out[np.arange(9), j]
+    assert np.all(elementwise_close(s, (1.0 / e.sum(axis=1)).astype(f32), ulps=2))
+    # shift invariance by an exactly representable per-row constant
+    shifted = wl.softmax(ora, ora.array((X.astype(np.float64) * 0 + np.round(X * 4) / 4 + 8).astype(f32))).numpy()
+    base = wl.softmax(ora, ora.array((np.round(X * 4) / 4).astype(f32))).numpy()
+    assert np.array_equal(shifted, base)
+    # equal values -> 1/ncols
+    flat = wl.softmax(ora, ora.array(np.full((2, 64), 3.25, f32))).numpy()
+    assert np.all(flat == f32(1.0 / 64))
+
+
+def test_stencil_constant_and_ramp_closed_forms():
+    c = f32(37.5)
+    out = wl.stencil(ora, ora.array(np.full((9, 11), c, f32))).numpy()
+    assert out.shape == (5, 7) and np.all(out == 0)
+    # ramp along columns: every five-term sum is an exact integer, B[r,c] = fl(0.2f*(5c+5));
+    # vertical differences vanish, so out = |B[., q+2] - B[., q]|.
+    R, C = 8, 40
+    ramp = np.tile(np.arange(C, dtype=f32), (R, 1))
+    out = wl.stencil(ora, ora.array(ramp)).numpy()
+    B = np.array([f32(0.2) * f32(5 * c + 5) for c in range(C - 2)], dtype=f32)
+    for q in range(C - 4):
+        d = f32(B[q + 2] - B[q])
+        assert np.all(out[:, q] == f32(np.sqrt(f32(f32(d * d) + f32(0)))))
+    outT = wl.stencil(ora, ora.array(np.ascontiguousarray(ramp.T))).numpy()
+    assert np.array_equal(outT, out.T)
+
+
+def test_stencil_brute_force_13_point():
+    g = rng(8)
+    I = (g.random((7, 8)) * 255).astype(f32)
+    out = wl.stencil(ora, ora.array(I)).numpy()
+    assert out.shape == (3, 4)
+
+    def B(r, c):  # value of the blurred image at its own index (r, c)
+        s = f32(f32(f32(f32(I[r + 1, c + 1] + I[r, c + 1]) + I[r + 2, c + 1]) + I[r + 1, c]) + I[r + 1, c + 2])
+        return f32(f32(0.2) * s)
+
+    for p, q in itertools.product(range(3), range(4)):
+        dx = f32(B(p + 1, q + 2) - B(p + 1, q))
+        dy = f32(B(p + 2, q + 1) - B(p, q + 1))
+        assert out[p, q] == f32(np.sqrt(f32(f32(dx * dx) + f32(dy * dy))))
+
+
+def test_jacobi_sweep_matches_numpy_views():
+    g = rng(9)
+    grid = g.random((12, 9)).astype(f32)
+    got = wl.jacobi_sweep(ora, ora.array(grid)).numpy()
+    want = wl.jacobi_sweep(np, grid)
+    assert want.dtype == f32 and np.array_equal(got, want)
+
+
+def test_logreg_zero_weights_closed_form():
+    inp = wl.make_inputs("logreg", rows=64, cols=8)
+    X, y = inp["X"], inp["y"]
+    w0 = np.zeros(8, f32)
+    got = wl.logreg(ora, ora.array(X), ora.array(w0), ora.array(y)).numpy()
+    # w = 0 -> p = 0.5 exactly, r = 0.5 - y in {+-0.5}; g = X.T r / n; w' = -0.1 g
+    r = (0.5 - y).astype(np.float64)
+    gT = np.array([f32(sum(float(X[i, k]) * r[i] for i in range(64))) for k in range(8)], dtype=f32)
+    want = f32(0) - f32(0.1) * (gT / f32(64) + f32(1e-4) * w0)
+    assert np.array_equal(got, want.astype(f32))
+
+
+def test_logreg_against_float64_reference():
+    inp = wl.make_inputs("logreg", rows=500, cols=40)
+    got = wl.logreg(ora, *(ora.array(inp[k]) for k in ("X", "w", "y"))).numpy()
+    X, w, y = (inp[k].astype(np.float64) for k in ("X", "w", "y"))
+    p = 1 / (1 + np.exp(-(X @ w)))
+    want = w - 0.1 * ((X.T @ (p - y)) / 500 + 1e-4 * w)
+    assert np.max(np.abs(got - want)) < 1e-6
+
+
+def test_mnist_listing2_against_float64():
+    g = rng(10)
+    W = g.standard_normal((200, 10)).astype(f32)
+    a = g.standard_normal(200).astype(f32)
+    b = g.standard_normal(10).astype(f32)
+    got = wl.mnist(ora, ora.array(W), ora.array(a), ora.array(b)).numpy()
+    x = W.astype(np.float64).T @ np.maximum(a, 0).astype(np.float64) + b
+    assert np.max(np.abs(got - 1 / (1 + np.exp(-x)))) < 1e-6
+
+
+# ------------------------------------------------- NumPy as a third opinion --
+def test_numpy_third_opinion_elementwise_bit_exact():
+    g = rng(11)
+    a = (g.standard_normal((33, 65)) * 10).astype(f32)
+    b = (g.standard_normal((65,)) * 10).astype(f32)
+    A, B = ora.array(a), ora.array(b)
+    assert np.array_equal((A + B).numpy(), a + b)
+    assert np.array_equal((A - B).numpy(), a - b)
+    assert np.array_equal((A * B).numpy(), a * b)
+    assert np.array_equal((A / B).numpy(), a / b)
+    assert np.array_equal(abs(A).numpy(), np.abs(a))
+    assert np.array_equal((-A).numpy(), -a)
+    assert np.array_equal(ora.sqrt(abs(A)).numpy(), np.sqrt(np.abs(a)))
+    assert np.array_equal(ora.maximum(A, B).numpy(), np.maximum(a, b))
+    assert np.array_equal(ora.minimum(A, B).numpy(), np.minimum(a, b))
+    assert np.array_equal((A ** 2).numpy(), a ** 2)
+    assert np.all(elementwise_close(ora.exp(A / 10.0).numpy(), np.exp(a / f32(10)), ulps=2))
+    assert np.all(elementwise_close(ora.tanh(A / 10.0).numpy(), np.tanh(a / f32(10)), ulps=2))
+    assert np.all(elementwise_close(ora.log(abs(A) + 1.0).numpy(), np.log(np.abs(a) + f32(1)), ulps=2))
+    i = g.integers(-2**31, 2**31 - 1, (7, 9), dtype=np.int64).astype(np.int32)
+    j = g.integers(-2**31, 2**31 - 1, (9,), dtype=np.int64).astype(np.int32)
+    with np.errstate(over="ignore"):
+        assert np.array_equal((ora.array(i) * ora.array(j) - ora.array(i)).numpy(), i * j - i)
+        assert np.array_equal((ora.array(i) * 3 + 1).numpy(), i * np.int32(3) + np.int32(1))
+
+
+def test_numpy_third_opinion_reductions_and_programs():
+    g = rng(12)
+    x = g.standard_normal((37, 211)).astype(f32)
+    X = ora.array(x)
+    assert np.allclose(ora.sum(X, axis=1).numpy(), x.sum(axis=1, dtype=np.float64), rtol=1e-6, atol=1e-6)
+    assert np.array_equal(ora.max(X, axis=0).numpy(), x.max(axis=0))
+    assert np.array_equal(ora.min(X, axis=1, keepdims=True).numpy(), x.min(axis=1, keepdims=True))
+    for name in ("chain", "softmax", "stencil"):
+        inp = wl.make_inputs(name, **wl.SMALL[name]) if name != "chain" else wl.make_inputs(name, n=4099)
+        if name == "softmax":
+            inp = wl.make_inputs(name, rows=11, cols=257)
+        if name == "stencil":
+            inp = wl.make_inputs(name, rows=23, cols=41)
+        got = wl.PROGRAMS[name](ora, **{k: ora.array(v) for k, v in inp.items()}).numpy()
+        want = wl.PROGRAMS[name](np, **inp)
+        assert want.dtype == f32
+        tol = dict(ulps=4, rel=2e-6)
+        floor = 4 * ulp_of(np.ones(1, f32)) if name == "chain" else None  # final op subtracts two O(1) values
+        assert np.all(elementwise_close(got, want, floor=floor, **tol)), name
+
+
+# ------------------------------------------------------------- threading ----
+def test_threads_do_not_change_results():
+    inp = wl.make_inputs("softmax", rows=40, cols=123)
+    ora.set_threads(1)
+    one = wl.softmax(ora, ora.array(inp["X"])).numpy()
+    ora.set_threads(4)
+    try:
+        four = wl.softmax(ora, ora.array(inp["X"])).numpy()
+    finally:
+        ora.set_threads(1)
+    assert np.array_equal(one, four)
