@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused lazy-array path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload normalize] [--no-extras]
+
+One step = one pass of the whole hot path over one batch of synthetic input:
+wrap the device buffers as leaves, record the NumPy-style program, partition,
+look the kernels up in the cache, launch, mark materialised, release.  The
+headline workload is the 8192x8192 broadcast normalisation; inputs are resident
+in HBM before the timed region and three buffer sets are rotated so that the
+256 MB Infinity Cache cannot serve repeats.  Prints ONE JSON line.
+
+Metric: effective GB/s = (unique input bytes + output bytes) / time.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+ARGNAMES = {"chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
+            "stencil": ("I",), "logreg": ("X", "w", "y")}
+# kernel whose launches dominate each workload, and its algorithmic bytes per launch
+DOMINANT = {"chain": "gr_map", "normalize": "gr_map", "softmax": "gr_rowred", "stencil": "gr_map", "logreg": "gr_gemv"}
+
+
+def out_shape(name, p):
+    return {"chain": lambda: (p["n"],), "normalize": lambda: (p["rows"], p["cols"]), "softmax": lambda: (p["rows"], p["cols"]),
+            "stencil": lambda: (p["rows"] - 4, p["cols"] - 4), "logreg": lambda: (p["cols"],)}[name]()
+
+
+def algorithmic_bytes_per_launch(name, p):
+    """Bytes one launch of the dominant kernel has to move ('Kernels')."""
+    from paper_1901_03771_amd import workloads as wl
+    if name == "logreg":  # each of the two GEMV passes reads X once (+ the small vectors)
+        return 4 * p["rows"] * p["cols"] + 4 * p["rows"] + 4 * p["cols"]
+    return wl.unique_bytes(name, **p)
+
+
+class Workload:
+    """Device-resident buffer sets of one configuration and the step that evaluates it."""
+
+    def __init__(self, name, ctx, nsets, size=None):
+        import torch
+        from paper_1901_03771_amd import lazy as gr, workloads as wl
+        self.name, self.ctx, self.gr, self.wl, self.torch = name, ctx, gr, wl, torch
+        self.p = dict(wl.FULL[name])
+        if size:
+            self.p.update(size)
+        self.sets = []
+        for s in range(nsets):
+            arrays = wl.make_inputs(name, salt=s, **self.p)
+            dev = {k: torch.from_numpy(v).cuda() for k, v in arrays.items()}
+            out = torch.empty(out_shape(name, self.p), dtype=torch.float32, device="cuda")
+            self.sets.append((dev, out))
+        self.i = 0
+        self.unique_bytes = wl.unique_bytes(name, **self.p)
+
+    def step(self):
+        dev, out = self.sets[self.i % len(self.sets)]
+        self.i += 1
+        leaves = {k: self.ctx.array(t) for k, t in dev.items()}
+        self.wl.PROGRAMS[self.name](self.gr, **leaves).materialize_into(out)
+        return out
+
+
+def time_steps(torch, w, steps, warmup):
+    for _ in range(warmup):
+        w.step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    w.ctx.profile_reset()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        w.step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    dev_ms = e0.elapsed_time(e1)
+    return max(dev_ms, 0.0), wall_ms
+
+
+def cpu_baseline(name, target_s=4.0):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload."""
+    import numpy as np
+    import oracle as ora
+    from paper_1901_03771_amd import workloads as wl
+    cores = min(16, len(os.sched_getaffinity(0)))
+    ora.set_threads(cores)
+    full = wl.FULL[name]
+    if name == "chain":
+        size = dict(n=full["n"])
+    else:
+        size = dict(rows=64 if name != "logreg" else 4096, cols=full["cols"])
+
+    def run(sz):
+        arrays = wl.make_inputs(name, **sz)
+        t0 = time.perf_counter()
+        wl.PROGRAMS[name](ora, **{k: ora.array(v) for k, v in arrays.items()}).numpy()
+        return time.perf_counter() - t0
+
+    t = run(size)
+    if name != "chain":  # scale the row count to about target_s of wall time on `cores` threads
+        rows = int(min(full["rows"], max(size["rows"], size["rows"] * target_s / max(t, 1e-3))))
+        size = dict(rows=rows, cols=full["cols"])
+        t = run(size)
+    gbs = wl.unique_bytes(name, **size) / t / 1e9
+    sample = ", ".join(f"{k}={v}" for k, v in size.items())
+    return {"value": round(gbs, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{name} program on {sample} (same recipe, seed and column count as the timed workload), "
+                      f"{t:.2f} s wall on {cores} OpenMP threads"}
+
+
+def traffic_from_profiles(name):
+    """HBM bytes per launch measured with rocprofv3 --pmc, if a summary is committed."""
+    path = os.path.join(ROOT, "profiles", f"{DOMINANT[name]}_{name}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="normalize", choices=sorted(ARGNAMES))
+    ap.add_argument("--sets", type=int, default=3)
+    ap.add_argument("--no-extras", action="store_true", help="skip the supplementary configurations and ceilings")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-launch-events", action="store_true", help="do not bracket launches with HIP events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by rows; see DESIGN.md); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1901_03771_amd import lazy as gr, workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    ctx = gr.Context(device=0)
+
+    name = args.workload
+    w = Workload(name, ctx, args.sets)
+    t0 = time.perf_counter()
+    w.step()
+    torch.cuda.synchronize()
+    cold_ms = (time.perf_counter() - t0) * 1e3  # includes code generation and hipRTC
+
+    ctx.set_option("profile", 0 if args.no_launch_events else 1)
+    dev_ms, wall_ms = time_steps(torch, w, args.steps, args.warmup)
+    ms_per_step = dev_ms / args.steps
+    value = w.unique_bytes / (ms_per_step * 1e-3) / 1e9
+
+    roofline = None
+    if not args.no_launch_events:
+        n, total_ms = ctx.profile_read(DOMINANT[name])
+        per_launch_ms = total_ms / max(n, 1)
+        alg = algorithmic_bytes_per_launch(name, w.p)
+        achieved = alg / (per_launch_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": DOMINANT[name], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_from_profiles(name),
+                    "launches": n, "avg_launch_us": round(per_launch_ms * 1e3, 2), "algorithmic_bytes_per_launch": alg}
+    ctx.set_option("profile", 0)
+
+    result = {
+        "metric": "effective GB/s of fused DAG eval (unique in+out bytes) and % of MI355X HBM peak",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{name}: " + ", ".join(f"{k}={v}" for k, v in w.p.items()), "buffer_sets": args.sets,
+                   "unique_bytes_per_step": w.unique_bytes},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "host_wall_ms_per_step": round(wall_ms / args.steps, 5),
+        "cold_first_call_ms": round(cold_ms, 2),
+        "roofline": roofline,
+    }
+
+    if not args.no_extras:
+        extras = {}
+        # practical ceiling of the box: plain copy and read-only kernels on the same buffers
+        src, dst = w.sets[0][0][ARGNAMES[name][0]], w.sets[1][0][ARGNAMES[name][0]]
+        if src.numel() * 4 % 16 == 0 and src.numel() >= (1 << 22):
+            sink = torch.zeros(4096, device="cuda")
+            for label, fn, nbytes in (("stream_copy", lambda: ctx.stream_copy(dst, src), 2 * src.numel() * 4),
+                                      ("stream_read", lambda: ctx.stream_read(src, sink), src.numel() * 4)):
+                for _ in range(5):
+                    fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(50):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                extras[label + "_GBps"] = round(nbytes / (e0.elapsed_time(e1) / 50 * 1e-3) / 1e9, 1)
+        del w
+        torch.cuda.empty_cache()
+        others = [("chain", None), ("chain", dict(n=1 << 27)), ("softmax", None), ("stencil", None), ("logreg", None), ("normalize", None)]
+        for oname, size in others:
+            if oname == name and size is None:
+                continue
+            ow = Workload(oname, ctx, 3 if size is None else 2, size)
+            k = 1000 if (oname == "chain" and size is None) else 50
+            d_ms, _ = time_steps(torch, ow, k, 10)
+            label = oname if size is None else f"{oname}_n2^27"
+            extras[label + "_GBps"] = round(ow.unique_bytes / (d_ms / k * 1e-3) / 1e9, 1)
+            extras[label + "_us_per_step"] = round(d_ms / k * 1e3, 2)
+            del ow
+            torch.cuda.empty_cache()
+        result["supplementary"] = extras
+
+    result["stats"] = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in ctx.stats().items()}
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(name)
+    ctx.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

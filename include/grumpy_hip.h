@@ -1,0 +1,237 @@
+/*
+ * grumpy_hip.h -- C ABI of the fused lazy-array evaluator for MI355X (gfx950).
+ *
+ * The calls follow the paper's statement of the problem (arxiv 1901.03771):
+ *   - an array handle is one node of the DAG G=(V,E)              (Section 2)
+ *   - input arrays enter as materialised leaves                    (Section 2, Section 4.1)
+ *   - every operation is recorded, not executed; shape and element type of
+ *     the result are inferred with NumPy semantics, broadcast included
+ *                                                                  (Section 1, Section 2)
+ *   - values are produced when asked for: the DAG is walked back to the
+ *     materialised nodes, split into an ordered list of sub-graphs
+ *     (Algorithm 1), and each sub-graph runs as one fused kernel whose point
+ *     function translates output indices back to leaf indices
+ *                                                                  (Section 2, Section 3.1, Section 3.2)
+ *   - the computed node then stays materialised and is a leaf of every
+ *     later request                                                (Section 2)
+ *
+ * Conventions
+ *   - Every function returns a gr_status (0 = GR_OK).  On error nothing is
+ *     recorded, *out is untouched, and gr_last_error(ctx) describes it.
+ *   - "device pointer" = address in the memory of the context's GPU.
+ *     "host pointer" = ordinary process memory.  All shape / stride / axis
+ *     arguments are host pointers and are copied before the call returns.
+ *   - Strides and offsets count ELEMENTS, not bytes.
+ *   - Recording calls never touch the device.  Kernels are launched
+ *     asynchronously on the context's stream by gr_materialize*; the library
+ *     only waits inside gr_sync and gr_ctx_destroy.
+ *   - A context is not thread-safe.
+ *   - Supported element types: f32 and i32 for computation; i64 only as the
+ *     result of an i32 sum (NumPy's default on Linux).  Mixed i32/f32
+ *     arithmetic would promote to f64 in NumPy and is refused
+ *     (GR_ERR_DTYPE).
+ */
+#ifndef GRUMPY_HIP_H
+#define GRUMPY_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gr_ctx gr_ctx;
+typedef uint64_t gr_array; /* opaque node id; 0 is never a valid handle */
+
+typedef enum {
+  GR_OK = 0,
+  GR_ERR_HANDLE = 1,      /* unknown or released handle */
+  GR_ERR_SHAPE = 2,       /* shapes do not broadcast / inner dimensions differ */
+  GR_ERR_DTYPE = 3,       /* element types not combinable without f64 */
+  GR_ERR_AXIS = 4,        /* axis out of range or repeated */
+  GR_ERR_UNSUPPORTED = 5, /* valid NumPy, outside this library's vocabulary */
+  GR_ERR_ARG = 6,         /* NULL pointer, bad rank, bad enum, bad size */
+  GR_ERR_COMPILE = 7,     /* run-time compilation of a fused kernel failed */
+  GR_ERR_HIP = 8,         /* a HIP runtime call failed */
+  GR_ERR_OOM = 9,         /* the allocator returned NULL */
+  GR_ERR_ALIAS = 10,      /* output buffer overlaps an input of the request */
+  GR_ERR_NODEVICE = 11    /* context was created without a device */
+} gr_status;
+
+typedef enum { GR_F32 = 0, GR_I32 = 1, GR_I64 = 2 } gr_dtype;
+
+typedef enum {
+  /* unary (Section 1 / Section 2: pointwise NumPy operations) */
+  GR_NEG = 0, GR_ABS = 1, GR_EXP = 2, GR_LOG = 3, GR_SQRT = 4, GR_SQUARE = 5, GR_TANH = 6,
+  /* binary, NumPy broadcasting */
+  GR_ADD = 16, GR_SUB = 17, GR_MUL = 18, GR_DIV = 19, GR_MAXIMUM = 20, GR_MINIMUM = 21,
+  /* reductions (Section 3.2: associative and commutative binary operator) */
+  GR_SUM = 32, GR_MAX = 33, GR_MIN = 34
+} gr_op;
+
+#define GR_MAX_NDIM 8
+
+/* ---- context ------------------------------------------------------------ */
+
+/* Creates a context bound to HIP device `device` and to `hip_stream`
+ * (a hipStream_t passed as void*, borrowed; NULL = the default stream).
+ * device = -1 creates a device-less context: recording, partitioning and
+ * code generation work, gr_materialize* return GR_ERR_NODEVICE. */
+gr_status gr_ctx_create(gr_ctx** out, int device, void* hip_stream);
+
+/* Waits for the stream, releases every node, buffer, module and workspace
+ * the context owns.  Borrowed leaf buffers are not freed. */
+gr_status gr_ctx_destroy(gr_ctx* ctx);
+
+/* Replaces the stream later launches go to (borrowed). */
+gr_status gr_ctx_set_stream(gr_ctx* ctx, void* hip_stream);
+
+/* Installs the device allocator used for materialised results and
+ * workspaces.  alloc(bytes, user) returns a device pointer aligned to at
+ * least 256 bytes or NULL; free_(ptr, user) releases it.  Both may be called
+ * from any library call.  Default: a grow-only pool over hipMalloc that is
+ * emptied by gr_ctx_destroy. */
+gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* user),
+                               void (*free_)(void* ptr, void* user), void* user);
+
+/* Integer options (host string key):
+ *   "fusion"          1 (default) fuse per Algorithm 1 as relaxed below; 0 =
+ *                     one kernel per recorded op, every intermediate stored
+ *                     (the eager execution model the paper starts from)
+ *   "rowred_max_cols" longest row (elements) a reduction may keep resident
+ *                     in registers and still fuse with its consumers
+ *   "map_rows", "map_chunks"   per-lane patch of the map skeleton (0 = auto)
+ *   "profile"         1 = bracket every launch with HIP events (gr_profile_*)
+ * Unknown key: GR_ERR_ARG. */
+gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value);
+
+/* Blocks until all work launched by this context has finished. */
+gr_status gr_sync(gr_ctx* ctx);
+
+/* Text of the last error of this context ("" if none).  The pointer stays
+ * valid until the next failing call on the context.  ctx = NULL returns the
+ * text of the last failed gr_ctx_create. */
+const char* gr_last_error(gr_ctx* ctx);
+
+/* ---- leaves (Section 2: "only the input nodes have the data field non-empty") */
+
+/* Wraps an existing device buffer as a materialised leaf.  `dptr` points at
+ * element (0,..,0); strides_elems = NULL means C-contiguous.  BORROWED: the
+ * caller keeps the memory alive and unmodified until every array that
+ * depends on this leaf has been materialised or released. */
+gr_status gr_array_from_device(gr_ctx* ctx, void* dptr, gr_dtype dtype, int ndim, const int64_t* shape,
+                               const int64_t* strides_elems, gr_array* out);
+
+/* A Python-style number.  It has no element type of its own: in a binary op
+ * it takes the array operand's type (rounded to binary32 first when it meets
+ * f32; an integer-valued one may meet i32; a fractional one with i32 is
+ * GR_ERR_DTYPE).  It cannot be materialised. */
+gr_status gr_scalar(gr_ctx* ctx, double value, int is_integer, gr_array* out);
+
+/* ---- recording (Section 2: nodes with is_materialized = false) ---------- */
+
+gr_status gr_unary(gr_ctx* ctx, gr_op op, gr_array a, gr_array* out);
+gr_status gr_binary(gr_ctx* ctx, gr_op op, gr_array a, gr_array b, gr_array* out);
+
+/* Basic slicing with Python rules on the first `nspec` dimensions (step >= 1;
+ * has_start/has_stop = 0 mean "omitted"); the rest are taken whole.  The
+ * result is a view: an index transformation, no data is moved (Section 3.1). */
+gr_status gr_slice(gr_ctx* ctx, gr_array a, int nspec, const int64_t* start, const int64_t* stop,
+                   const int64_t* step, const uint8_t* has_start, const uint8_t* has_stop, gr_array* out);
+
+/* Axis permutation as a view; perm = NULL reverses the axes, so element
+ * (i,j) of the result is element (j,i) of a 2-D operand (Section 3.1). */
+gr_status gr_transpose(gr_ctx* ctx, gr_array a, const int* perm, gr_array* out);
+
+/* GR_SUM / GR_MAX / GR_MIN over `axes` (naxes = 0: all axes).  Negative axes
+ * count from the end.  i32 sums give i64.  max/min over an empty range:
+ * GR_ERR_SHAPE. */
+gr_status gr_reduce(gr_ctx* ctx, gr_op op, gr_array a, const int* axes, int naxes, int keepdims, gr_array* out);
+
+/* np.dot for f32: (M,K).(K,) -> (M,) and (K,).(K,) -> ().  Either operand
+ * may be any strided view (a transposed matrix is folded into the kernel,
+ * Section 2).  Matrix-matrix products: GR_ERR_UNSUPPORTED. */
+gr_status gr_dot(gr_ctx* ctx, gr_array a, gr_array b, gr_array* out);
+
+/* ---- materialisation (Section 2, Algorithm 1, Section 3) ---------------- */
+
+/* Computes `a` into memory obtained from the context's allocator; the buffer
+ * belongs to the node and is freed when the node dies. */
+gr_status gr_materialize(gr_ctx* ctx, gr_array a);
+
+/* Computes `a` into the caller's C-contiguous device buffer of `bytes` bytes
+ * (must equal count * itemsize).  The buffer must not overlap any leaf the
+ * request reads (GR_ERR_ALIAS) and stays owned by the caller, who keeps it
+ * alive while the node or anything recorded on top of it is in use. */
+gr_status gr_materialize_into(gr_ctx* ctx, gr_array a, void* dptr, size_t bytes);
+
+/* ---- inspection --------------------------------------------------------- */
+
+gr_status gr_ndim(gr_ctx* ctx, gr_array a, int* ndim);
+gr_status gr_shape(gr_ctx* ctx, gr_array a, int64_t* shape /* >= ndim entries */);
+gr_status gr_dtype_of(gr_ctx* ctx, gr_array a, gr_dtype* dtype);
+gr_status gr_is_materialized(gr_ctx* ctx, gr_array a, int* flag);
+/* Device pointer to element (0,..,0) and element strides of a materialised
+ * array (a view of a materialised array counts). */
+gr_status gr_data_ptr(gr_ctx* ctx, gr_array a, void** dptr, int64_t* strides /* >= ndim entries */);
+
+/* ---- lifetime ----------------------------------------------------------- */
+
+/* A node lives while a handle or a node recorded on top of it refers to it. */
+gr_status gr_retain(gr_ctx* ctx, gr_array a);
+gr_status gr_release(gr_ctx* ctx, gr_array a);
+
+/* ---- planning without execution (host only; works without a device) ----- */
+
+/* Writes a text description of the ordered sub-graph list that
+ * gr_materialize(a) would execute (one line per sub-graph: kind, root,
+ * member nodes, leaves) into buf (host, NUL-terminated, truncated to cap).
+ * *needed receives the full length including the NUL. */
+gr_status gr_plan_describe(gr_ctx* ctx, gr_array a, char* buf, size_t cap, size_t* needed);
+
+/* Same for the generated HIP source of sub-graph `index` of that list. */
+gr_status gr_plan_source(gr_ctx* ctx, gr_array a, int index, char* buf, size_t cap, size_t* needed);
+
+/* Compiles every sub-graph of the plan for gfx950 without running it (works
+ * without a device); returns GR_ERR_COMPILE with the compiler log in
+ * gr_last_error on failure. */
+gr_status gr_plan_compile(gr_ctx* ctx, gr_array a);
+
+/* ---- statistics and profiling ------------------------------------------- */
+
+typedef struct {
+  uint64_t nodes_recorded;
+  uint64_t nodes_alive;
+  uint64_t materialize_calls;
+  uint64_t groups_executed;   /* sub-graphs run */
+  uint64_t kernel_launches;
+  uint64_t cache_hits;        /* kernel cache, keyed on the sub-graph signature */
+  uint64_t cache_misses;      /* = run-time compilations */
+  double compile_ms;          /* total time inside the run-time compiler */
+  uint64_t bytes_allocated;   /* by the context's allocator, cumulative */
+} gr_stats_t;
+
+gr_status gr_stats(gr_ctx* ctx, gr_stats_t* out);
+
+/* With option "profile" = 1 every launch is bracketed by two HIP events on
+ * the context's stream.  gr_profile_read waits for the stream and returns,
+ * for the kernel kind whose name starts with `prefix` (host string; "" =
+ * all), the number of launches and their summed duration since the last
+ * gr_profile_reset. */
+gr_status gr_profile_reset(gr_ctx* ctx);
+gr_status gr_profile_read(gr_ctx* ctx, const char* prefix, uint64_t* launches, double* total_ms);
+
+/* ---- plain streaming kernels (practical HBM ceiling of the box) --------- */
+
+/* dst[i] = src[i] for `bytes` bytes (multiple of 16; both device pointers,
+ * 16-byte aligned, not overlapping), launched on the context's stream. */
+gr_status gr_stream_copy(gr_ctx* ctx, void* dst, const void* src, size_t bytes);
+/* Reads `bytes` bytes (multiple of 16) and writes one 4-byte word per
+ * workgroup to `sink` (device pointer, at least 16 KiB). */
+gr_status gr_stream_read(gr_ctx* ctx, const void* src, size_t bytes, void* sink);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRUMPY_HIP_H */

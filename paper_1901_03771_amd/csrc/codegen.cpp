@@ -1,0 +1,754 @@
+// Kernel generator: turns one planned sub-graph into HIP source for gfx950.
+//
+// Section 3 of the paper generates, from a point function and an iteration
+// space, a `map` kernel (one GPU thread per point) or a `map-reduce` kernel
+// (per-block combine in shared memory, second kernel for the block partials).
+// The skeletons below keep that contract (the point function is the SSA
+// program built by the planner) and replace the launch shapes with ones
+// fitted to CDNA4:
+//
+//   MAP     each lane owns a patch of VR rows x UC chunks of 4 consecutive
+//           columns; loads and stores are dwordx4; values shared between the
+//           points of a patch (broadcast operands, overlapping slice views)
+//           are loaded and computed once per patch and stay in registers.
+//   ROWRED  a row is held in registers by 16 / 64 / 256 lanes across all
+//           reduction phases and the final map (wave shuffles, LDS only
+//           across the four waves of a 256-lane row).
+//   REDUCE  generic reduction root: a thread or a workgroup per output.
+//   GEMV    bandwidth-bound contraction kernels (row-dot, and
+//           column-accumulate with a deterministic second combine stage in
+//           the manner of the paper's two-kernel reduction) whose epilogue
+//           is the point function of the dot's pointwise consumers.
+#include "codegen.h"
+
+#include <algorithm>
+#include <functional>
+#include <map>
+#include <sstream>
+
+#include "ctx.h"
+
+namespace gr {
+
+char access_class(const AccessGroup& ag, int dim) {
+  if (ag.structural_zero[dim]) return 'Z';
+  if (ag.coef[dim] == 1 && ag.dtype != GR_I64) return '1';
+  return 'G';
+}
+
+ArgLayout arg_layout(const GroupPlan& g) {
+  ArgLayout L;
+  int s = 0;
+  for (size_t i = 0; i < g.groups.size(); ++i) {
+    bool core = g.kind == GroupKind::GEMV && ((int)i == g.mat_group || (int)i == g.vec_group);
+    int nc = core ? 2 : g.rank;
+    L.ptr.push_back(s++);
+    L.base.push_back(s++);
+    L.coef.push_back(s);
+    L.ncoef.push_back(nc);
+    s += nc;
+  }
+  L.out = s++;
+  L.dims = s;
+  s += g.rank;
+  L.consts = s;
+  s += (int)g.consts.size();
+  L.extra = s;
+  s += 4;
+  L.total = s;
+  return L;
+}
+
+std::string kernel_name(const GroupPlan& g) {
+  switch (g.kind) {
+    case GroupKind::MAP: return "gr_map";
+    case GroupKind::ROWRED: return "gr_rowred";
+    case GroupKind::REDUCE: return "gr_reduce";
+    case GroupKind::GEMV: return g.gemv_mode ? "gr_gemv_colacc" : "gr_gemv_rowdot";
+  }
+  return "gr_kernel";
+}
+
+namespace {
+
+const char* cty(gr_dtype dt) { return dt == GR_F32 ? "float" : (dt == GR_I32 ? "int" : "long long"); }
+const char* vty4(gr_dtype dt) { return dt == GR_F32 ? "f4u" : "i4u"; }
+const char* vty2(gr_dtype dt) { return dt == GR_F32 ? "f2u" : "i2u"; }
+
+struct Em {
+  const GroupPlan& g;
+  ArgLayout L;
+  std::ostringstream o;
+  explicit Em(const GroupPlan& gp) : g(gp), L(arg_layout(gp)) {}
+
+  std::string S(int slot) const { return "((long long)a.s[" + std::to_string(slot) + "])"; }
+  std::string dim(int k) const { return S(L.dims + k); }
+  std::string cst(int cslot) const {
+    const ConstSlot& c = g.consts[cslot];
+    std::string s = "a.s[" + std::to_string(L.consts + cslot) + "]";
+    if (c.dtype == GR_F32) return "__uint_as_float((unsigned)" + s + ")";
+    if (c.dtype == GR_I32) return "((int)" + s + ")";
+    return "((long long)" + s + ")";
+  }
+  std::string coef(int grp, int k) const { return S(L.coef[grp] + k); }
+
+  static std::string unop(int op, gr_dtype dt, const std::string& x) {
+    if (dt == GR_F32) switch (op) {
+      case GR_NEG: return "(-" + x + ")";
+      case GR_ABS: return "__builtin_fabsf(" + x + ")";
+      case GR_EXP: return "expf(" + x + ")";
+      case GR_LOG: return "logf(" + x + ")";
+      case GR_SQRT: return "sqrtf(" + x + ")";
+      case GR_SQUARE: return "(" + x + " * " + x + ")";
+      case GR_TANH: return "tanhf(" + x + ")";
+    }
+    switch (op) {  // i32: two's-complement wrap-around through unsigned arithmetic
+      case GR_NEG: return "((int)(0u - (unsigned)" + x + "))";
+      case GR_ABS: return "(" + x + " < 0 ? (int)(0u - (unsigned)" + x + ") : " + x + ")";
+      case GR_SQUARE: return "((int)((unsigned)" + x + " * (unsigned)" + x + "))";
+    }
+    return "0";
+  }
+  static std::string binop(int op, gr_dtype dt, const std::string& x, const std::string& y) {
+    if (dt == GR_F32) switch (op) {
+      case GR_ADD: return "(" + x + " + " + y + ")";
+      case GR_SUB: return "(" + x + " - " + y + ")";
+      case GR_MUL: return "(" + x + " * " + y + ")";
+      case GR_DIV: return "(" + x + " / " + y + ")";
+      case GR_MAXIMUM: return "gr_maxf(" + x + ", " + y + ")";
+      case GR_MINIMUM: return "gr_minf(" + x + ", " + y + ")";
+    }
+    switch (op) {
+      case GR_ADD: return "((int)((unsigned)" + x + " + (unsigned)" + y + "))";
+      case GR_SUB: return "((int)((unsigned)" + x + " - (unsigned)" + y + "))";
+      case GR_MUL: return "((int)((unsigned)" + x + " * (unsigned)" + y + "))";
+      case GR_MAXIMUM: return "(" + x + " >= " + y + " ? " + x + " : " + y + ")";
+      case GR_MINIMUM: return "(" + x + " <= " + y + " ? " + x + " : " + y + ")";
+    }
+    return "0";
+  }
+
+  // combine(acc, x) for a reduction phase
+  static std::string combine(const Phase& p, const std::string& acc, const std::string& x) {
+    if (p.op == GR_SUM) {
+      if (p.out_dtype == GR_I64) return "(" + acc + " + (long long)" + x + ")";
+      return "(" + acc + " + " + x + ")";
+    }
+    if (p.in_dtype == GR_F32) return std::string(p.op == GR_MAX ? "gr_maxf(" : "gr_minf(") + acc + ", " + x + ")";
+    return "(" + acc + (p.op == GR_MAX ? " >= " : " <= ") + x + " ? " + acc + " : " + x + ")";
+  }
+  static std::string identity(const Phase& p) {
+    if (p.op == GR_SUM) return p.out_dtype == GR_F32 ? "0.0f" : (p.out_dtype == GR_I64 ? "0ll" : "0");
+    if (p.in_dtype == GR_F32) return p.op == GR_MAX ? "(-__builtin_inff())" : "__builtin_inff()";
+    return p.op == GR_MAX ? "(-2147483647 - 1)" : "2147483647";
+  }
+  static std::string zero(gr_dtype dt) { return dt == GR_F32 ? "0.0f" : (dt == GR_I64 ? "0ll" : "0"); }
+};
+
+void prelude(Em& e) {
+  e.o << "typedef float f4 __attribute__((ext_vector_type(4)));\n"
+         "typedef f4 f4u __attribute__((aligned(4)));\n"
+         "typedef float f2 __attribute__((ext_vector_type(2)));\n"
+         "typedef f2 f2u __attribute__((aligned(4)));\n"
+         "typedef int i4 __attribute__((ext_vector_type(4)));\n"
+         "typedef i4 i4u __attribute__((aligned(4)));\n"
+         "typedef int i2 __attribute__((ext_vector_type(2)));\n"
+         "typedef i2 i2u __attribute__((aligned(4)));\n"
+         "struct Args { unsigned long long s[" << e.L.total << "]; };\n"
+         "static __device__ __forceinline__ float gr_maxf(float a, float b) { return (a >= b || a != a) ? a : b; }\n"
+         "static __device__ __forceinline__ float gr_minf(float a, float b) { return (a <= b || a != a) ? a : b; }\n"
+         "static __device__ __forceinline__ float gr_xor(float v, int m) { return __shfl_xor(v, m, 64); }\n"
+         "static __device__ __forceinline__ int gr_xor(int v, int m) { return __shfl_xor(v, m, 64); }\n"
+         "static __device__ __forceinline__ long long gr_xor(long long v, int m) {\n"
+         "  int lo = __shfl_xor((int)(v & 0xffffffffll), m, 64), hi = __shfl_xor((int)(v >> 32), m, 64);\n"
+         "  return ((long long)hi << 32) | (unsigned int)lo;\n}\n";
+}
+
+// Emits gr_comb<ph>(a, b) and the lane / block reduction helpers for a phase.
+void phase_helpers(Em& e, int ph, int lanes) {
+  const Phase& p = e.g.phases[ph];
+  const char* T = cty(p.out_dtype);
+  // combining two partial results never converts (unlike combining an element into an i64 sum)
+  std::string comb;
+  if (p.op == GR_SUM) comb = "(x + y)";
+  else if (p.out_dtype == GR_F32) comb = std::string(p.op == GR_MAX ? "gr_maxf" : "gr_minf") + "(x, y)";
+  else comb = std::string("(x ") + (p.op == GR_MAX ? ">=" : "<=") + " y ? x : y)";
+  e.o << "static __device__ __forceinline__ " << T << " gr_comb" << ph << "(" << T << " x, " << T << " y) { return " << comb << "; }\n";
+  int w = std::min(lanes, 64);
+  e.o << "static __device__ __forceinline__ " << T << " gr_lanes" << ph << "(" << T << " v) {\n";
+  for (int m = w / 2; m > 0; m >>= 1) e.o << "  v = gr_comb" << ph << "(v, gr_xor(v, " << m << "));\n";
+  e.o << "  return v;\n}\n";
+}
+
+// ---- point program emission (scalar) -----------------------------------------
+
+// Emits the instructions of `prog` needed for `want` as scalar statements.
+// load_expr(instr) gives the expression of a LOAD; acc_expr the dot result.
+void emit_scalar_program(Em& e, const std::vector<Instr>& prog, const std::vector<int>& want,
+                         const std::function<std::string(const Instr&, int)>& load_expr, const std::string& acc_expr,
+                         const std::string& prefix, const std::string& indent, std::vector<char>* done_io = nullptr) {
+  std::vector<char> need(prog.size(), 0);
+  std::vector<int> work(want);
+  while (!work.empty()) {
+    int i = work.back();
+    work.pop_back();
+    if (i < 0 || need[i]) continue;
+    if (done_io && (*done_io)[i]) continue;
+    need[i] = 1;
+    if (prog[i].a >= 0) work.push_back(prog[i].a);
+    if (prog[i].b >= 0) work.push_back(prog[i].b);
+  }
+  auto name = [&](int i) { return prefix + std::to_string(i); };
+  for (size_t i = 0; i < prog.size(); ++i) {
+    if (!need[i]) continue;
+    const Instr& in = prog[i];
+    e.o << indent << "const " << cty(in.dtype) << ' ' << name((int)i) << " = ";
+    switch (in.kind) {
+      case IKind::LOAD: e.o << load_expr(in, (int)i); break;
+      case IKind::CONST: e.o << e.cst(in.cslot); break;
+      case IKind::UNARY: e.o << Em::unop(in.op, in.dtype, name(in.a)); break;
+      case IKind::BINARY: e.o << Em::binop(in.op, in.dtype, name(in.a), name(in.b)); break;
+      case IKind::RED: e.o << "red" << in.phase; break;
+      case IKind::ACC: e.o << acc_expr; break;
+    }
+    e.o << ";\n";
+    if (done_io) (*done_io)[i] = 1;
+  }
+}
+
+// Common kernel head: Args, extents.
+void kernel_head(Em& e, const std::string& name) {
+  e.o << "extern \"C\" __global__ __launch_bounds__(256) void " << name << "(Args a) {\n";
+}
+
+// Declares p<g>: pointer of each access group advanced by its base offset.
+void group_pointers(Em& e, const std::string& indent, const std::vector<int>& skip = {}) {
+  for (size_t gi = 0; gi < e.g.groups.size(); ++gi) {
+    if (std::find(skip.begin(), skip.end(), (int)gi) != skip.end()) continue;
+    const AccessGroup& ag = e.g.groups[gi];
+    e.o << indent << "const " << cty(ag.dtype) << "* const q" << gi << " = (const " << cty(ag.dtype) << "*)a.s[" << e.L.ptr[gi]
+        << "] + " << e.S(e.L.base[gi]) << ";\n";
+  }
+}
+
+// ---- MAP ----------------------------------------------------------------------
+
+void gen_map(Em& e) {
+  const GroupPlan& g = e.g;
+  const int rank = g.rank;
+  const int TC = g.BX * 4 * g.UC, TR = g.BY * g.VR;
+  const int cd = rank - 1, rd = rank - 2;
+  prelude(e);
+  kernel_head(e, kernel_name(g));
+  e.o << "  const long long C = " << e.dim(cd) << ";\n";
+  e.o << "  const long long R = " << (rank >= 2 ? e.dim(rd) : std::string("1")) << ";\n";
+  e.o << "  const long long nbx = (C + " << TC - 1 << ") / " << TC << ", nby = (R + " << TR - 1 << ") / " << TR << ";\n";
+  e.o << "  long long tile = blockIdx.x;\n";
+  if (g.xcd_remap) {
+    // consecutive tiles go to the same XCD (workgroups are dealt round-robin over the 8 XCDs),
+    // so tiles that share halo rows also share an L2
+    e.o << "  { long long outer = 1;\n";
+    for (int k = 0; k + 2 < rank; ++k) e.o << "    outer *= " << e.dim(k) << ";\n";
+    e.o << "    const long long ntiles = nbx * nby * outer, per = (ntiles + 7) / 8;\n"
+           "    tile = (long long)(blockIdx.x % 8) * per + blockIdx.x / 8;\n"
+           "    if (tile >= ntiles) return; }\n";
+  }
+  e.o << "  const long long bx = tile % nbx, t2 = tile / nbx, by = t2 % nby, olin = t2 / nby;\n";
+  if (rank > 2) {
+    e.o << "  long long orem = olin;\n";
+    for (int k = rank - 3; k >= 0; --k) e.o << "  const long long i" << k << " = orem % " << e.dim(k) << "; orem /= " << e.dim(k) << ";\n";
+  }
+  e.o << "  const int tx = threadIdx.x % " << g.BX << ", ty = threadIdx.x / " << g.BX << ";\n";
+  e.o << "  const long long r0 = by * " << TR << " + ty * " << g.VR << ", c0 = bx * " << TC << " + tx * 4;\n";
+  group_pointers(e, "  ");
+  for (size_t gi = 0; gi < g.groups.size(); ++gi) {
+    const AccessGroup& ag = g.groups[gi];
+    e.o << "  const " << cty(ag.dtype) << "* const p" << gi << " = q" << gi;
+    for (int k = 0; k + 2 < rank; ++k) if (!ag.structural_zero[k]) e.o << " + i" << k << " * " << e.coef((int)gi, k);
+    if (rank >= 2 && !ag.structural_zero[rd]) e.o << " + r0 * " << e.coef((int)gi, rd);
+    char cc = access_class(ag, cd);
+    if (cc == '1') e.o << " + c0";
+    else if (cc == 'G') e.o << " + c0 * " << e.coef((int)gi, cd);
+    e.o << ";\n";
+  }
+  e.o << "  " << cty(g.out_dtype) << "* const po = (" << cty(g.out_dtype) << "*)a.s[" << e.L.out << "] + (olin * R + r0) * C + c0;\n";
+
+  // static part of a load's address: shifts times runtime coefficients
+  auto shift_expr = [&](const Instr& in, bool with_col) {
+    const AccessGroup& ag = g.groups[in.group];
+    std::ostringstream s;
+    bool any = false;
+    for (int k = 0; k < rank; ++k) {
+      if (in.delta[k] == 0 || ag.structural_zero[k]) continue;
+      if (k == cd) {
+        if (!with_col) continue;
+        if (access_class(ag, cd) == '1') s << (any ? " + " : "") << in.delta[k];
+        else s << (any ? " + " : "") << in.delta[k] << " * " << e.coef(in.group, k);
+      } else s << (any ? " + " : "") << in.delta[k] << " * " << e.coef(in.group, k);
+      any = true;
+    }
+    if (!any) s << "0";
+    return s.str();
+  };
+
+  // ---- interior tiles: the whole patch, straight-line ----
+  e.o << "  if ((by + 1) * " << TR << " <= R && (bx + 1) * " << TC << " <= C) {\n";
+  // group the contiguous loads of the patch program into vector loads
+  std::map<int, std::string> load_name;  // instr -> expression
+  {
+    // key: group + all deltas but the column one
+    std::map<std::vector<int64_t>, std::vector<std::pair<int64_t, int>>> rows;
+    std::vector<char> used(g.prog.size(), 0);
+    {  // only loads reachable from the results
+      std::vector<int> work(g.results.begin(), g.results.end());
+      while (!work.empty()) {
+        int i = work.back();
+        work.pop_back();
+        if (i < 0 || used[i]) continue;
+        used[i] = 1;
+        work.push_back(g.prog[i].a);
+        work.push_back(g.prog[i].b);
+      }
+    }
+    int nl = 0;
+    for (size_t i = 0; i < g.prog.size(); ++i) {
+      const Instr& in = g.prog[i];
+      if (in.kind != IKind::LOAD || !used[i]) continue;
+      const AccessGroup& ag = g.groups[in.group];
+      if (access_class(ag, cd) != '1') {
+        load_name[(int)i] = "p" + std::to_string(in.group) + "[" + shift_expr(in, true) + "]";
+        continue;
+      }
+      std::vector<int64_t> key{in.group};
+      for (int k = 0; k < rank; ++k) if (k != cd) key.push_back(in.delta[k]);
+      rows[key].push_back({in.delta[cd], (int)i});
+    }
+    for (auto& kv : rows) {
+      auto& v = kv.second;
+      std::sort(v.begin(), v.end());
+      const Instr& first = g.prog[v[0].second];
+      const AccessGroup& ag = g.groups[first.group];
+      std::string rowoff = shift_expr(first, false);
+      size_t i = 0;
+      while (i < v.size()) {
+        size_t run = 1;
+        while (i + run < v.size() && v[i + run].first == v[i].first + (int64_t)run) ++run;
+        size_t pos = 0;
+        while (pos < run) {
+          size_t take = run - pos >= 4 ? 4 : (run - pos >= 2 ? 2 : 1);
+          int64_t dc = v[i + pos].first;
+          std::string nm = "L" + std::to_string(nl++);
+          std::string addr = "p" + std::to_string(first.group) + " + (" + rowoff + ") + " + std::to_string(dc);
+          if (take == 4) e.o << "    const " << vty4(ag.dtype) << ' ' << nm << " = *(const " << vty4(ag.dtype) << "*)(" << addr << ");\n";
+          else if (take == 2) e.o << "    const " << vty2(ag.dtype) << ' ' << nm << " = *(const " << vty2(ag.dtype) << "*)(" << addr << ");\n";
+          else e.o << "    const " << cty(ag.dtype) << ' ' << nm << " = *(" << addr << ");\n";
+          for (size_t q = 0; q < take; ++q)
+            load_name[v[i + pos + q].second] = take == 1 ? nm : nm + "[" + std::to_string(q) + "]";
+          pos += take;
+        }
+        i += run;
+      }
+    }
+  }
+  emit_scalar_program(e, g.prog, g.results,
+                      [&](const Instr&, int id) { return load_name[id]; }, "0.0f", "t", "    ");
+  {
+    int ri = 0;
+    for (int v = 0; v < g.VR; ++v)
+      for (int u = 0; u < g.UC; ++u) {
+        std::string off = std::to_string(v) + " * C + " + std::to_string(u * g.BX * 4);
+        if (g.out_dtype == GR_I64) {
+          for (int j = 0; j < 4; ++j) e.o << "    po[" << off << " + " << j << "] = t" << g.results[ri + j] << ";\n";
+        } else {
+          const char* vt = g.out_dtype == GR_F32 ? "f4u" : "i4u";
+          e.o << "    { " << vt << " ov; ov[0] = t" << g.results[ri] << "; ov[1] = t" << g.results[ri + 1] << "; ov[2] = t" << g.results[ri + 2]
+              << "; ov[3] = t" << g.results[ri + 3] << "; *(" << vt << "*)(po + " << off << ") = ov; }\n";
+        }
+        ri += 4;
+      }
+  }
+  // ---- boundary tiles: one guarded point at a time ----
+  e.o << "  } else {\n"
+         "    for (int v = 0; v < " << g.VR << "; ++v)\n"
+         "      for (int u = 0; u < " << g.UC << "; ++u)\n"
+         "        for (int j = 0; j < 4; ++j) {\n"
+         "          const long long cj = (long long)u * " << g.BX * 4 << " + j;\n"
+         "          if (r0 + v < R && c0 + cj < C) {\n";
+  emit_scalar_program(e, g.prog1, {g.result1},
+                      [&](const Instr& in, int) {
+                        const AccessGroup& ag = g.groups[in.group];
+                        std::string s = "p" + std::to_string(in.group) + "[" + shift_expr(in, true);
+                        if (rank >= 2 && !ag.structural_zero[rd]) s += " + v * " + e.coef(in.group, rd);
+                        char cc = access_class(ag, cd);
+                        if (cc == '1') s += " + cj";
+                        else if (cc == 'G') s += " + cj * " + e.coef(in.group, cd);
+                        return s + "]";
+                      },
+                      "0.0f", "s", "            ");
+  e.o << "            po[v * C + cj] = s" << g.result1 << ";\n"
+         "          }\n        }\n  }\n}\n";
+}
+
+// ---- ROWRED -------------------------------------------------------------------
+
+void gen_rowred(Em& e) {
+  const GroupPlan& g = e.g;
+  const int rank = g.rank, cd = rank - 1;
+  const int RT = g.row_threads, NP = g.NP, RB = 256 / RT;
+  const int nph = (int)g.phases.size();
+  prelude(e);
+  for (int ph = 0; ph < nph; ++ph) phase_helpers(e, ph, RT);
+
+  // stage of first computation and liveness across stages
+  const int nstage = nph + 1;
+  std::vector<int> stage_of(g.prog.size(), -1);
+  std::vector<std::vector<int>> stage_instrs(nstage);
+  std::vector<char> keep(g.prog.size(), 0);
+  for (int s = 0; s < nstage; ++s) {
+    int want = s < nph ? g.phases[s].value : (g.results.empty() ? -1 : g.results[0]);
+    std::vector<int> work{want};
+    std::vector<char> seen(g.prog.size(), 0);
+    while (!work.empty()) {
+      int i = work.back();
+      work.pop_back();
+      if (i < 0 || seen[i]) continue;
+      seen[i] = 1;
+      if (stage_of[i] >= 0 && stage_of[i] < s) { keep[i] = 1; continue; }
+      stage_of[i] = s;
+      work.push_back(g.prog[i].a);
+      work.push_back(g.prog[i].b);
+    }
+    for (size_t i = 0; i < g.prog.size(); ++i) if (stage_of[i] == s) stage_instrs[s].push_back((int)i);
+  }
+
+  kernel_head(e, kernel_name(g));
+  e.o << "  const long long C = " << e.dim(cd) << ";\n  long long ROWS = 1;\n";
+  for (int k = 0; k < cd; ++k) e.o << "  ROWS *= " << e.dim(k) << ";\n";
+  e.o << "  const int lane = threadIdx.x % " << RT << ";\n";
+  e.o << "  const long long row = (long long)blockIdx.x * " << RB << " + threadIdx.x / " << RT << ";\n";
+  if (RT == 256) e.o << "  __shared__ " << "long long" << " gr_sm[" << std::max(nph, 1) << "][4];\n";
+  e.o << "  if (row >= ROWS) return;\n";
+  if (cd >= 1) {
+    e.o << "  long long rrem = row;\n";
+    for (int k = cd - 1; k >= 0; --k) e.o << "  const long long i" << k << " = rrem % " << e.dim(k) << "; rrem /= " << e.dim(k) << ";\n";
+  }
+  group_pointers(e, "  ");
+  for (size_t gi = 0; gi < g.groups.size(); ++gi) {
+    const AccessGroup& ag = g.groups[gi];
+    e.o << "  const " << cty(ag.dtype) << "* const p" << gi << " = q" << gi;
+    for (int k = 0; k < cd; ++k) if (!ag.structural_zero[k]) e.o << " + i" << k << " * " << e.coef((int)gi, k);
+    e.o << ";\n";
+  }
+  // kept per-element values live in registers across stages
+  for (size_t i = 0; i < g.prog.size(); ++i)
+    if (keep[i] && !g.prog[i].uniform) e.o << "  " << cty(g.prog[i].dtype) << " k" << i << "[" << NP << "][4];\n";
+  for (int ph = 0; ph < nph; ++ph) e.o << "  " << cty(g.phases[ph].out_dtype) << " red" << ph << ";\n";
+
+  auto shift_expr = [&](const Instr& in) {
+    const AccessGroup& ag = g.groups[in.group];
+    std::ostringstream s;
+    bool any = false;
+    for (int k = 0; k < cd; ++k) {
+      if (in.delta[k] == 0 || ag.structural_zero[k]) continue;
+      s << (any ? " + " : "") << in.delta[k] << " * " << e.coef(in.group, k);
+      any = true;
+    }
+    if (!any) s << "0";
+    return s.str();
+  };
+  auto name = [&](int i, bool in_loop) -> std::string {
+    const Instr& in = g.prog[i];
+    if (in.uniform) return "u" + std::to_string(i);
+    if (keep[i]) return "k" + std::to_string(i) + "[p][j]";
+    (void)in_loop;
+    return "t" + std::to_string(i);
+  };
+  auto expr = [&](int i) -> std::string {
+    const Instr& in = g.prog[i];
+    switch (in.kind) {
+      case IKind::CONST: return e.cst(in.cslot);
+      case IKind::UNARY: return Em::unop(in.op, in.dtype, name(in.a, true));
+      case IKind::BINARY: return Em::binop(in.op, in.dtype, name(in.a, true), name(in.b, true));
+      case IKind::RED: return "red" + std::to_string(in.phase);
+      default: return "0";
+    }
+  };
+
+  const bool exact = false;  // the last position is always emitted in guarded form
+  (void)exact;
+  for (int s = 0; s < nstage; ++s) {
+    const bool final_stage = s == nph;
+    if (final_stage && g.results.empty()) break;
+    e.o << "  // ---- " << (final_stage ? "final map" : "reduction phase") << " " << s << "\n";
+    // row-uniform values first
+    for (int i : stage_instrs[s]) {
+      const Instr& in = g.prog[i];
+      if (!in.uniform) continue;
+      e.o << "  const " << cty(in.dtype) << " u" << i << " = ";
+      if (in.kind == IKind::LOAD) e.o << "p" << in.group << "[" << shift_expr(in) << "]";
+      else e.o << expr(i);
+      e.o << ";\n";
+    }
+    if (final_stage && g.out_per_row) {
+      e.o << "  if (lane == 0) ((" << cty(g.out_dtype) << "*)a.s[" << e.L.out << "])[row] = " << name(g.results[0], false) << ";\n";
+      break;
+    }
+    const Phase* ph = final_stage ? nullptr : &g.phases[s];
+    if (ph) e.o << "  " << cty(ph->out_dtype) << " acc" << s << " = " << Em::identity(*ph) << ";\n";
+    if (final_stage)
+      e.o << "  " << cty(g.out_dtype) << "* const po = (" << cty(g.out_dtype) << "*)a.s[" << e.L.out << "] + row * C;\n";
+    bool any_elem = false;
+    for (int i : stage_instrs[s]) if (!g.prog[i].uniform) any_elem = true;
+    int want = ph ? ph->value : g.results[0];
+    if (!any_elem && !(keep[want] && !g.prog[want].uniform) && g.prog[want].uniform) {
+      // the combined value does not depend on the column: combine it C times
+      // (only sums and extrema exist: a sum of C equal values, an extremum of them)
+      // handled below by the generic loop with the uniform name.
+    }
+    // two bodies: unguarded positions 0..NP-2, guarded last position
+    for (int pass = 0; pass < 2; ++pass) {
+      const bool guarded = pass == 1;
+      if (!guarded && NP == 1) continue;
+      if (!guarded) e.o << "#pragma unroll\n  for (int p = 0; p < " << NP - 1 << "; ++p) {\n";
+      else e.o << "  { const int p = " << NP - 1 << ";\n";
+      e.o << "    const long long c = (long long)p * " << RT * 4 << " + lane * 4;\n";
+      // loads of this stage
+      for (int i : stage_instrs[s]) {
+        const Instr& in = g.prog[i];
+        if (in.kind != IKind::LOAD || in.uniform) continue;
+        const AccessGroup& ag = g.groups[in.group];
+        char cc = access_class(ag, cd);
+        std::string base = "p" + std::to_string(in.group) + " + (" + shift_expr(in) + ")";
+        e.o << "    " << cty(in.dtype) << " l" << i << "[4];\n";
+        std::string idx = cc == '1' ? "(c + " + std::to_string(in.delta[cd]) + ")" : "(c + " + std::to_string(in.delta[cd]) + ") * " + e.coef(in.group, cd);
+        std::string step = cc == '1' ? "1" : e.coef(in.group, cd);
+        if (cc == '1') {
+          if (guarded) e.o << "    if (c + 4 <= C) ";
+          else e.o << "    ";
+          e.o << "{ const " << vty4(in.dtype) << " w = *(const " << vty4(in.dtype) << "*)(" << base << " + " << idx << "); l" << i << "[0] = w[0]; l" << i
+              << "[1] = w[1]; l" << i << "[2] = w[2]; l" << i << "[3] = w[3]; }\n";
+          if (guarded)
+            e.o << "    else { for (int j = 0; j < 4; ++j) l" << i << "[j] = (c + j < C) ? (" << base << ")[" << idx << " + j] : " << Em::zero(in.dtype) << "; }\n";
+        } else {
+          e.o << "    for (int j = 0; j < 4; ++j) l" << i << "[j] = " << (guarded ? "(c + j < C) ? " : "") << "(" << base << ")[" << idx << " + j * " << step << "]"
+              << (guarded ? " : " + Em::zero(in.dtype) : std::string()) << ";\n";
+        }
+      }
+      if (final_stage && g.out_dtype != GR_I64) e.o << "    " << (g.out_dtype == GR_F32 ? "f4u" : "i4u") << " ov;\n";
+      e.o << "#pragma unroll\n    for (int j = 0; j < 4; ++j) {\n";
+      for (int i : stage_instrs[s]) {
+        const Instr& in = g.prog[i];
+        if (in.uniform) continue;
+        std::string rhs = in.kind == IKind::LOAD ? "l" + std::to_string(i) + "[j]" : expr(i);
+        if (keep[i]) e.o << "      k" << i << "[p][j] = " << rhs << ";\n";
+        else e.o << "      const " << cty(in.dtype) << " t" << i << " = " << rhs << ";\n";
+      }
+      if (ph) {
+        std::string upd = "acc" + std::to_string(s) + " = " + Em::combine(*ph, "acc" + std::to_string(s), name(want, true)) + ";";
+        if (guarded) e.o << "      if (c + j < C) " << upd << "\n";
+        else e.o << "      " << upd << "\n";
+      } else {
+        if (g.out_dtype == GR_I64) e.o << "      " << (guarded ? "if (c + j < C) " : "") << "po[c + j] = " << name(want, true) << ";\n";
+        else e.o << "      ov[j] = " << name(want, true) << ";\n";
+      }
+      e.o << "    }\n";
+      if (final_stage && g.out_dtype != GR_I64) {
+        const char* vt = g.out_dtype == GR_F32 ? "f4u" : "i4u";
+        if (guarded) e.o << "    if (c + 4 <= C) *(" << vt << "*)(po + c) = ov; else { for (int j = 0; j < 4; ++j) if (c + j < C) po[c + j] = ov[j]; }\n";
+        else e.o << "    *(" << vt << "*)(po + c) = ov;\n";
+      }
+      e.o << "  }\n";
+    }
+    if (ph) {
+      e.o << "  acc" << s << " = gr_lanes" << s << "(acc" << s << ");\n";
+      if (RT == 256) {
+        const char* T = cty(ph->out_dtype);
+        e.o << "  { " << T << "* sm = (" << T << "*)gr_sm[" << s << "];\n"
+               "    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc" << s << ";\n"
+               "    __syncthreads();\n"
+               "    acc" << s << " = gr_comb" << s << "(gr_comb" << s << "(sm[0], sm[1]), gr_comb" << s << "(sm[2], sm[3])); }\n";
+      }
+      e.o << "  red" << s << " = acc" << s << ";\n";
+    }
+  }
+  e.o << "}\n";
+}
+
+// ---- REDUCE (generic reduction root) --------------------------------------------
+
+void gen_reduce(Em& e) {
+  const GroupPlan& g = e.g;
+  const int rank = g.rank, kr = g.red_kept_rank;
+  const Phase& ph = g.phases[0];
+  const char* T = cty(ph.out_dtype);
+  prelude(e);
+  phase_helpers(e, 0, 64);
+  kernel_head(e, kernel_name(g));
+  e.o << "  const long long NOUT = " << e.S(e.L.extra) << ", LEN = " << e.S(e.L.extra + 1) << ";\n";
+  if (g.red_mode == 0) e.o << "  const long long o = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (o >= NOUT) return;\n";
+  else e.o << "  const long long o = blockIdx.x;\n  __shared__ long long gr_sm[4];\n";
+  e.o << "  long long orem = o;\n";
+  for (int k = kr - 1; k >= 0; --k) e.o << "  const long long i" << k << " = orem % " << e.dim(k) << "; orem /= " << e.dim(k) << ";\n";
+  group_pointers(e, "  ");
+  for (size_t gi = 0; gi < g.groups.size(); ++gi) {
+    const AccessGroup& ag = g.groups[gi];
+    e.o << "  const " << cty(ag.dtype) << "* const p" << gi << " = q" << gi;
+    for (int k = 0; k < kr; ++k) if (!ag.structural_zero[k]) e.o << " + i" << k << " * " << e.coef((int)gi, k);
+    e.o << ";\n";
+  }
+  e.o << "  " << T << " acc = " << Em::identity(ph) << ";\n";
+  if (g.red_mode == 0) e.o << "  for (long long j = 0; j < LEN; ++j) {\n";
+  else e.o << "  for (long long j = threadIdx.x; j < LEN; j += 256) {\n";
+  if (rank > kr) {
+    e.o << "    long long jrem = j;\n";
+    for (int k = rank - 1; k >= kr; --k) {
+      if (k == kr) e.o << "    const long long i" << k << " = jrem;\n";
+      else e.o << "    const long long i" << k << " = jrem % " << e.dim(k) << "; jrem /= " << e.dim(k) << ";\n";
+    }
+  }
+  emit_scalar_program(e, g.prog, {ph.value},
+                      [&](const Instr& in, int) {
+                        const AccessGroup& ag = g.groups[in.group];
+                        std::ostringstream s;
+                        s << "p" << in.group << "[0";
+                        for (int k = 0; k < rank; ++k) {
+                          if (ag.structural_zero[k]) continue;
+                          if (k >= kr) s << " + (i" << k << " + " << in.delta[k] << ") * " << e.coef(in.group, k);
+                          else if (in.delta[k]) s << " + " << in.delta[k] << " * " << e.coef(in.group, k);
+                        }
+                        s << "]";
+                        return s.str();
+                      },
+                      "0.0f", "t", "    ");
+  e.o << "    acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n  }\n";
+  if (g.red_mode == 1) {
+    e.o << "  acc = gr_lanes0(acc);\n"
+           "  { " << T << "* sm = (" << T << "*)gr_sm;\n"
+           "    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;\n"
+           "    __syncthreads();\n"
+           "    acc = gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])); }\n"
+           "  if (threadIdx.x == 0) ((" << T << "*)a.s[" << e.L.out << "])[o] = acc;\n";
+  } else {
+    e.o << "  ((" << T << "*)a.s[" << e.L.out << "])[o] = acc;\n";
+  }
+  e.o << "}\n";
+}
+
+// ---- GEMV -----------------------------------------------------------------------
+
+// Epilogue: the pointwise consumers of the dot, evaluated at output index `idx`.
+void gemv_epilogue(Em& e, const std::string& idx, const std::string& acc, const std::string& indent) {
+  const GroupPlan& g = e.g;
+  emit_scalar_program(e, g.prog, g.results,
+                      [&](const Instr& in, int) {
+                        const AccessGroup& ag = g.groups[in.group];
+                        if (ag.structural_zero[0]) return "q" + std::to_string(in.group) + "[0]";
+                        return "q" + std::to_string(in.group) + "[(" + idx + " + " + std::to_string(in.delta[0]) + ") * " + e.coef(in.group, 0) + "]";
+                      },
+                      acc, "t", indent);
+}
+
+void gen_gemv_rowdot(Em& e) {
+  const GroupPlan& g = e.g;
+  const int LPR = g.LPR, KV = g.KV, RPB = 256 / LPR;
+  const AccessGroup& mg = g.groups[g.mat_group];
+  const AccessGroup& vg = g.groups[g.vec_group];
+  const bool mat_unit = mg.coef[1] == 1, vec_unit = vg.coef[1] == 1;
+  prelude(e);
+  kernel_head(e, kernel_name(g));
+  e.o << "  const long long M = " << e.S(e.L.extra) << ", K = " << e.S(e.L.extra + 1) << ";\n";
+  group_pointers(e, "  ");
+  e.o << "  const float* const A = q" << g.mat_group << "; const float* const V = q" << g.vec_group << ";\n";
+  e.o << "  const long long am = " << e.coef(g.mat_group, 0) << ", ak = " << (mat_unit ? std::string("1") : e.coef(g.mat_group, 1))
+      << ", vk = " << (vec_unit ? std::string("1") : e.coef(g.vec_group, 1)) << ";\n";
+  e.o << "  const int lane = threadIdx.x % " << LPR << ", rib = threadIdx.x / " << LPR << ";\n";
+  e.o << "  float* const out = (float*)a.s[" << e.L.out << "];\n";
+  const int CH = LPR * 4;  // k elements per chunk of one row
+  // one pass if the whole row fits KV chunks, else loop over groups of KV chunks
+  e.o << "  const bool single = K <= " << (long long)CH * KV << ";\n";
+  e.o << "  float wv[" << KV << "][4];\n";
+  e.o << "  if (single) {\n#pragma unroll\n    for (int q = 0; q < " << KV << "; ++q) {\n      const long long k0 = (long long)q * " << CH << " + lane * 4;\n";
+  e.o << "      for (int j = 0; j < 4; ++j) wv[q][j] = (k0 + j < K) ? V[(k0 + j) * vk] : 0.0f;\n    }\n  }\n";
+  e.o << "  for (long long row = (long long)blockIdx.x * " << RPB << " + rib; row < M; row += (long long)gridDim.x * " << RPB << ") {\n";
+  e.o << "    const float* const Ar = A + row * am;\n    float acc = 0.0f;\n";
+  e.o << "    if (single) {\n";
+  e.o << "      float xv[" << KV << "][4];\n#pragma unroll\n      for (int q = 0; q < " << KV << "; ++q) {\n        const long long k0 = (long long)q * " << CH << " + lane * 4;\n";
+  if (mat_unit)
+    e.o << "        if (k0 + 4 <= K) { const f4u w = *(const f4u*)(Ar + k0); xv[q][0] = w[0]; xv[q][1] = w[1]; xv[q][2] = w[2]; xv[q][3] = w[3]; }\n"
+           "        else { for (int j = 0; j < 4; ++j) xv[q][j] = (k0 + j < K) ? Ar[k0 + j] : 0.0f; }\n";
+  else
+    e.o << "        for (int j = 0; j < 4; ++j) xv[q][j] = (k0 + j < K) ? Ar[(k0 + j) * ak] : 0.0f;\n";
+  e.o << "      }\n#pragma unroll\n      for (int q = 0; q < " << KV << "; ++q)\n#pragma unroll\n        for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(xv[q][j], wv[q][j], acc);\n";
+  e.o << "    } else {\n      for (long long kb = 0; kb < K; kb += " << CH << ") {\n        const long long k0 = kb + lane * 4;\n";
+  e.o << "        for (int j = 0; j < 4; ++j) if (k0 + j < K) acc = __builtin_fmaf(Ar[(k0 + j) * ak], V[(k0 + j) * vk], acc);\n      }\n    }\n";
+  for (int m = LPR / 2; m > 0; m >>= 1) e.o << "    acc += gr_xor(acc, " << m << ");\n";
+  e.o << "    if (lane == 0) {\n";
+  gemv_epilogue(e, "row", "acc", "      ");
+  e.o << "      out[row] = t" << g.results[0] << ";\n    }\n  }\n}\n";
+}
+
+void gen_gemv_colacc(Em& e) {
+  const GroupPlan& g = e.g;
+  const int BX = g.BX, BY = g.BY;
+  const AccessGroup& vg = g.groups[g.vec_group];
+  const bool vec_unit = vg.coef[1] == 1;
+  prelude(e);
+  // stage 1: per-slab partial vectors
+  kernel_head(e, kernel_name(g));
+  e.o << "  const long long M = " << e.S(e.L.extra) << ", K = " << e.S(e.L.extra + 1) << ", SLABS = " << e.S(e.L.extra + 3) << ";\n";
+  e.o << "  float* const ws = (float*)a.s[" << e.L.extra + 2 << "];\n";
+  group_pointers(e, "  ");
+  e.o << "  const float* const A = q" << g.mat_group << "; const float* const V = q" << g.vec_group << ";\n";
+  e.o << "  const long long ak = " << e.coef(g.mat_group, 1) << ", vk = " << (vec_unit ? std::string("1") : e.coef(g.vec_group, 1)) << ";\n";
+  e.o << "  const int tx = threadIdx.x % " << BX << ", ty = threadIdx.x / " << BX << ";\n";
+  e.o << "  const long long ncb = (M + " << BX * 4 - 1 << ") / " << BX * 4 << ";\n";
+  e.o << "  const long long cb = blockIdx.x % ncb, slab = blockIdx.x / ncb;\n";
+  e.o << "  const long long m0 = cb * " << BX * 4 << " + tx * 4;\n";
+  e.o << "  const long long ks = (K + SLABS - 1) / SLABS, kbeg = slab * ks, kend = (kbeg + ks < K) ? kbeg + ks : K;\n";
+  e.o << "  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};\n";
+  e.o << "  if (m0 + 4 <= M) {\n"
+         "    long long k = kbeg + ty;\n"
+         "    for (; k + " << 7 * BY << " < kend; k += " << 8 * BY << ") {\n"
+         "      f4u x[8]; float s[8];\n"
+         "#pragma unroll\n      for (int u = 0; u < 8; ++u) { x[u] = *(const f4u*)(A + (k + u * " << BY << ") * ak + m0); s[u] = V[(k + u * " << BY << ") * vk]; }\n"
+         "#pragma unroll\n      for (int u = 0; u < 8; ++u) { acc[0] = __builtin_fmaf(x[u][0], s[u], acc[0]); acc[1] = __builtin_fmaf(x[u][1], s[u], acc[1]); acc[2] = __builtin_fmaf(x[u][2], s[u], acc[2]); acc[3] = __builtin_fmaf(x[u][3], s[u], acc[3]); }\n"
+         "    }\n"
+         "    for (; k < kend; k += " << BY << ") { const f4u x = *(const f4u*)(A + k * ak + m0); const float s = V[k * vk];\n"
+         "      acc[0] = __builtin_fmaf(x[0], s, acc[0]); acc[1] = __builtin_fmaf(x[1], s, acc[1]); acc[2] = __builtin_fmaf(x[2], s, acc[2]); acc[3] = __builtin_fmaf(x[3], s, acc[3]); }\n"
+         "  } else {\n"
+         "    for (long long k = kbeg + ty; k < kend; k += " << BY << ") { const float s = V[k * vk];\n"
+         "      for (int j = 0; j < 4; ++j) if (m0 + j < M) acc[j] = __builtin_fmaf(A[k * ak + m0 + j], s, acc[j]); }\n"
+         "  }\n";
+  e.o << "  __shared__ float sm[" << BY << "][" << BX * 4 << "];\n";
+  e.o << "  for (int j = 0; j < 4; ++j) sm[ty][tx * 4 + j] = acc[j];\n  __syncthreads();\n";
+  e.o << "  if (ty == 0) {\n    for (int j = 0; j < 4; ++j) {\n      float t = sm[0][tx * 4 + j];\n      for (int y = 1; y < " << BY << "; ++y) t += sm[y][tx * 4 + j];\n"
+         "      if (m0 + j < M) ws[slab * M + m0 + j] = t;\n    }\n  }\n}\n";
+  // stage 2: fixed-order combine of the slab partials, then the epilogue
+  kernel_head(e, kernel_name(g) + "_combine");
+  e.o << "  const long long M = " << e.S(e.L.extra) << ", SLABS = " << e.S(e.L.extra + 3) << ";\n";
+  e.o << "  const float* const ws = (const float*)a.s[" << e.L.extra + 2 << "];\n";
+  group_pointers(e, "  ", {g.mat_group, g.vec_group});
+  e.o << "  const int tx = threadIdx.x % 16, sg = threadIdx.x / 16;\n";
+  e.o << "  const long long m = (long long)blockIdx.x * 16 + tx;\n";
+  e.o << "  __shared__ float sm[16][17];\n  float part = 0.0f;\n";
+  e.o << "  if (m < M) for (long long s = sg; s < SLABS; s += 16) part += ws[s * M + m];\n";
+  e.o << "  sm[sg][tx] = part;\n  __syncthreads();\n";
+  e.o << "  if (sg == 0 && m < M) {\n    float acc = sm[0][tx];\n    for (int y = 1; y < 16; ++y) acc += sm[y][tx];\n";
+  gemv_epilogue(e, "m", "acc", "    ");
+  e.o << "    ((float*)a.s[" << e.L.out << "])[m] = t" << g.results[0] << ";\n  }\n}\n";
+}
+
+}  // namespace
+
+std::string generate_source(const GroupPlan& g) {
+  Em e(g);
+  switch (g.kind) {
+    case GroupKind::MAP: gen_map(e); break;
+    case GroupKind::ROWRED: gen_rowred(e); break;
+    case GroupKind::REDUCE: gen_reduce(e); break;
+    case GroupKind::GEMV: if (g.gemv_mode) gen_gemv_colacc(e); else gen_gemv_rowdot(e); break;
+  }
+  return e.o.str();
+}
+
+}  // namespace gr

@@ -1,0 +1,86 @@
+// The context: node table, options, allocator, kernel cache, statistics.
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+
+#include <chrono>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "ir.h"
+
+struct gr_ctx {
+  int device = -1;
+  hipStream_t stream = nullptr;
+  std::string err;
+
+  // nodes
+  std::unordered_map<uint64_t, gr::Node*> nodes;
+  uint64_t next_id = 1;
+
+  // options
+  int64_t opt_fusion = 1;
+  int64_t opt_rowred_max_cols = 16384;
+  int64_t opt_map_rows = 0, opt_map_chunks = 0;
+  int64_t opt_profile = 0;
+
+  // allocator
+  void* (*alloc_fn)(size_t, void*) = nullptr;
+  void (*free_fn)(void*, void*) = nullptr;
+  void* alloc_user = nullptr;
+  std::unordered_map<size_t, std::vector<void*>> pool_free;  // default pool: size -> free blocks
+  std::vector<void*> pool_all;
+
+  // kernel cache: signature -> compiled kernel
+  struct Kernel {
+    hipModule_t module = nullptr;
+    hipFunction_t fn = nullptr;
+    hipFunction_t fn2 = nullptr;  // second stage (column-accumulate GEMV)
+    std::vector<char> code;
+    std::string name;
+  };
+  std::unordered_map<std::string, Kernel> cache;
+
+  // workspace for two-stage kernels
+  void* workspace = nullptr;
+  size_t workspace_bytes = 0;
+
+  // profiling
+  struct ProfRec {
+    std::string name;
+    hipEvent_t e0, e1;
+  };
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> event_pool;
+
+  gr_stats_t stats{};
+};
+
+namespace gr {
+
+gr_status fail(gr_ctx* c, gr_status s, const std::string& msg);
+Node* lookup(gr_ctx* c, gr_array a);
+Node* new_node(gr_ctx* c, Kind kind);
+void node_unref_consumer(gr_ctx* c, Node* n);
+void node_maybe_free(gr_ctx* c, Node* n);
+void drop_inputs(gr_ctx* c, Node* n);
+
+void* ctx_alloc(gr_ctx* c, size_t bytes);
+void ctx_free(gr_ctx* c, void* p, size_t bytes);
+
+// plan.cpp
+gr_status make_plan(gr_ctx* c, Node* root, Plan* plan);
+void clear_planned(Plan* plan);
+std::string describe_plan(const Plan& plan);
+
+// codegen.cpp
+std::string generate_source(const GroupPlan& g);
+std::string kernel_name(const GroupPlan& g);
+
+// runtime.cpp
+gr_status compile_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel** out);
+gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr);
+gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out);
+
+}  // namespace gr

@@ -1,0 +1,176 @@
+// Internal data structures of the lazy-array library: DAG nodes (Section 2 of
+// the paper: attributes operation / data / is_materialized), the context, and
+// the plan handed from the partitioner to the code generator and the runtime.
+#pragma once
+
+#include <cstdint>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <set>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/grumpy_hip.h"
+
+namespace gr {
+
+constexpr int MAXD = GR_MAX_NDIM;
+
+enum class Kind : uint8_t { LEAF, SCALAR, CONST, UNARY, BINARY, SLICE, TRANSPOSE, REDUCE, DOT };
+
+struct Node {
+  uint64_t id = 0;
+  Kind kind = Kind::LEAF;
+  int op = 0;  // gr_op for UNARY / BINARY / REDUCE
+  gr_dtype dtype = GR_F32;
+  int ndim = 0;
+  int64_t shape[MAXD] = {0};
+  std::vector<Node*> in;  // predecessors (each holds one consumer reference)
+  int handle_refs = 0;
+  int consumer_refs = 0;
+
+  // "data" / "is_materialized"
+  bool materialized = false;
+  bool planned = false;  // will be materialised by an earlier sub-graph of the plan being built
+  void* data = nullptr;  // device pointer to element offset 0 of the allocation
+  int64_t strides[MAXD] = {0};
+  int64_t offset = 0;      // elements from `data` to element (0,..,0)
+  bool owns_data = false;  // allocated through the context's allocator
+  size_t alloc_bytes = 0;
+
+  // SCALAR / CONST payload
+  double value = 0.0;
+  bool is_int = false;
+
+  // SLICE: per-dimension start and step (normalised); TRANSPOSE: perm
+  int64_t start[MAXD] = {0};
+  int64_t step[MAXD] = {0};
+  int perm[MAXD] = {0};
+
+  // REDUCE
+  bool red_axis[MAXD] = {false};
+  bool keepdims = false;
+
+  int64_t count() const {
+    int64_t n = 1;
+    for (int d = 0; d < ndim; ++d) n *= shape[d];
+    return n;
+  }
+  bool is_view() const { return kind == Kind::SLICE || kind == Kind::TRANSPOSE; }
+  bool is_compute() const { return kind == Kind::UNARY || kind == Kind::BINARY || kind == Kind::REDUCE || kind == Kind::DOT; }
+  bool has_data() const { return materialized || planned; }
+};
+
+inline size_t itemsize(gr_dtype dt) { return dt == GR_I64 ? 8 : 4; }
+
+// ---- plan --------------------------------------------------------------------
+
+// Index of one operand dimension as an affine function of one iteration-space
+// dimension: scale * i[src] + off  (src < 0: the constant `off`).  This is the
+// index translation of Section 3.1 kept in closed form: broadcast, slicing and
+// transposition all stay inside this class of maps.
+struct DimMap {
+  int src = -1;
+  int64_t scale = 0;
+  int64_t off = 0;
+};
+using IndexMap = std::vector<DimMap>;
+
+enum class IKind : uint8_t { LOAD, CONST, UNARY, BINARY, RED, ACC };
+
+// One SSA instruction of a fused point program.
+struct Instr {
+  IKind kind = IKind::CONST;
+  int op = 0;
+  gr_dtype dtype = GR_F32;
+  int a = -1, b = -1;         // operand instruction ids
+  int group = -1;             // LOAD: access group
+  int64_t delta[MAXD] = {0};  // LOAD: shift in iteration space (original dims; later collapsed dims)
+  int cslot = -1;             // CONST: slot in the constant table
+  int phase = -1;             // RED: index of the reduction phase whose result this is
+  bool uniform = false;       // value does not depend on the innermost iteration dimension
+};
+
+// A set of loads from one buffer that differ only by a shift in iteration space.
+struct AccessGroup {
+  const Node* leaf = nullptr;
+  gr_dtype dtype = GR_F32;
+  std::vector<int64_t> ident;  // numeric identity (see plan.cpp)
+  int64_t base = 0;            // elements from leaf->data to the element read at i = 0, delta = 0
+  int64_t coef[MAXD] = {0};    // elements per unit step of each iteration dimension
+  bool structural_zero[MAXD] = {false};  // no leaf dimension follows this iteration dimension
+  std::set<std::vector<int64_t>> deltas;  // all shifts used (length = iteration rank)
+};
+
+enum class GroupKind : uint8_t { MAP, ROWRED, REDUCE, GEMV };
+
+struct Phase {
+  int op = 0;  // GR_SUM / GR_MAX / GR_MIN
+  gr_dtype in_dtype = GR_F32;
+  gr_dtype out_dtype = GR_F32;
+  int value = -1;  // instruction whose values are combined
+  const Node* node = nullptr;
+};
+
+struct ConstSlot {
+  gr_dtype dtype;
+  double value;
+};
+
+// One sub-graph of the ordered list of Algorithm 1, ready for code generation.
+struct GroupPlan {
+  GroupKind kind = GroupKind::MAP;
+  Node* root = nullptr;
+  std::vector<const Node*> members;  // lazy nodes computed inside this sub-graph
+  std::vector<const Node*> leaves;   // materialised nodes it reads
+  std::string note;                  // human-readable details for gr_plan_describe
+
+  // iteration space (after collapsing)
+  int rank = 0;
+  int64_t dims[MAXD] = {0};
+  int orig_rank = 0;
+  int64_t orig_dims[MAXD] = {0};
+  int collapse_to[MAXD] = {0};  // original dim -> collapsed dim (innermost original of a merged run carries shifts)
+
+  std::vector<Instr> prog;
+  std::vector<int> results;  // MAP: one per patch point; ROWRED/REDUCE/GEMV: single entry (final value) or empty
+  std::vector<AccessGroup> groups;
+  std::vector<ConstSlot> consts;
+  std::vector<Phase> phases;
+
+  // single-point program for boundary tiles (MAP)
+  std::vector<Instr> prog1;
+  int result1 = -1;
+
+  // output
+  gr_dtype out_dtype = GR_F32;
+  bool out_per_row = false;  // ROWRED: one value per row instead of one per element
+
+  // schedule
+  int BX = 64, BY = 4, VR = 1, UC = 1;  // MAP
+  int NP = 1;                            // ROWRED: vec4 positions per lane
+  int row_threads = 64;                  // ROWRED: lanes cooperating on one row (64 or 256)
+  bool xcd_remap = false;
+  int red_mode = 0;                      // REDUCE: 0 thread-per-output, 1 block-per-output
+  int64_t red_out = 0, red_len = 0;      // REDUCE: outputs, reduced elements per output
+  int red_kept_rank = 0;
+
+  // GEMV core
+  int gemv_mode = 0;  // 0: inner stride 1 along k (row-dot); 1: inner stride 1 along m (column-accumulate)
+  int64_t M = 0, K = 0;
+  int mat_group = -1, vec_group = -1;
+  int LPR = 64;       // gemv row-dot: lanes per row
+  int KV = 1;         // gemv row-dot: vec4 per lane along k
+  int slabs = 1;      // gemv column-accumulate: row slabs (first-stage partial vectors)
+
+  std::string signature;
+};
+
+struct Plan {
+  std::vector<std::unique_ptr<GroupPlan>> groups;
+  std::vector<Node*> planned_nodes;
+};
+
+}  // namespace gr

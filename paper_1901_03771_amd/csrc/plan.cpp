@@ -1,0 +1,859 @@
+// Materialiser and fusion partitioner.
+//
+// Section 2 of the paper: on a request the DAG is walked back from the
+// requested node to materialised nodes; Algorithm 1 (create_subgraph) splits
+// the visited sub-DAG into an ordered list of sub-graphs, cutting at nodes that
+// must be materialised (materialize_node: library-grade contractions and
+// reductions), at operands of such library operations
+// (materialize_pred_of_node, with a transposed operand folded into the call),
+// and at nodes that a second sub-graph would otherwise recompute (the
+// multiple-use rule: such a node is materialised once and is a leaf of every
+// user).  This file implements that rule set in closed form:
+//
+//   cut(n) :=  n is the requested root
+//           |  n is a dot node whose consumers cannot run as its epilogue
+//           |  n is the (view-stripped) lazy operand of a dot node
+//           |  n is a reduction that cannot stay resident in registers
+//           |  n is reached from two different cut nodes
+//
+// and every cut node becomes the root of one sub-graph; ascending node ids are
+// a topological order, so the list is in execution order.  Two relaxations of
+// the paper's rules are deliberate: a reduction over the innermost axis whose
+// row fits in registers stays fused with producers and consumers, and
+// pointwise consumers of a dot run as the contraction kernel's epilogue.
+//
+// For each sub-graph the point function of Section 3.1 is built as a flat SSA
+// program: output indices are translated back to leaf indices through
+// broadcast, slice and transpose nodes by composing affine per-dimension maps.
+#include <algorithm>
+#include <cstdio>
+#include <functional>
+#include <sstream>
+
+#include "ctx.h"
+
+namespace gr {
+
+namespace {
+
+int64_t floordiv(int64_t a, int64_t b) { int64_t q = a / b; return (a % b != 0 && ((a < 0) != (b < 0))) ? q - 1 : q; }
+int64_t floormod(int64_t a, int64_t b) { return a - floordiv(a, b) * b; }
+
+const char* op_name(int op) {
+  switch (op) {
+    case GR_NEG: return "neg"; case GR_ABS: return "abs"; case GR_EXP: return "exp"; case GR_LOG: return "log";
+    case GR_SQRT: return "sqrt"; case GR_SQUARE: return "square"; case GR_TANH: return "tanh";
+    case GR_ADD: return "add"; case GR_SUB: return "sub"; case GR_MUL: return "mul"; case GR_DIV: return "div";
+    case GR_MAXIMUM: return "maximum"; case GR_MINIMUM: return "minimum";
+    case GR_SUM: return "sum"; case GR_MAX: return "max"; case GR_MIN: return "min";
+  }
+  return "?";
+}
+
+std::string node_label(const Node* n) {
+  switch (n->kind) {
+    case Kind::LEAF: return "leaf";
+    case Kind::SCALAR: return "scalar";
+    case Kind::CONST: return "const";
+    case Kind::UNARY: case Kind::BINARY: case Kind::REDUCE: return op_name(n->op);
+    case Kind::SLICE: return "slice";
+    case Kind::TRANSPOSE: return "transpose";
+    case Kind::DOT: return "dot";
+  }
+  return "?";
+}
+
+struct Invalid {
+  const Node* node;
+  std::string why;
+};
+
+// Builds the SSA program of one sub-graph.
+struct Builder {
+  GroupPlan* g;
+  const std::set<const Node*>* owned;  // lazy nodes this sub-graph computes
+  int rank = 0;                        // iteration rank (original dims)
+  const int64_t* dims = nullptr;
+  std::vector<Instr>* prog = nullptr;
+
+  std::map<std::pair<uint64_t, std::vector<int64_t>>, int> memo;
+  std::map<std::vector<int64_t>, int> load_ids;   // (group, delta...) -> instr
+  std::map<std::vector<int64_t>, int> value_ids;  // (kind, op, dtype, a, b) -> instr
+  std::map<const Node*, int> phase_of;
+  const Node* dot_core = nullptr;
+  std::vector<Invalid> invalid;
+  std::set<const Node*> leaves_seen, members_seen;
+
+  static std::vector<int64_t> flatten(const IndexMap& m) {
+    std::vector<int64_t> v;
+    v.reserve(m.size() * 3);
+    for (const DimMap& d : m) { v.push_back(d.src); v.push_back(d.scale); v.push_back(d.off); }
+    return v;
+  }
+
+  void canonicalize(const Node* n, IndexMap& m) const {
+    for (int d = 0; d < n->ndim; ++d) {
+      DimMap& e = m[d];
+      if (n->shape[d] == 1) { e = DimMap{-1, 0, 0}; continue; }
+      if (e.src >= 0 && (e.scale == 0 || dims[e.src] == 1)) e = DimMap{-1, 0, e.off};
+    }
+  }
+
+  int push(const Instr& in) {
+    prog->push_back(in);
+    return (int)prog->size() - 1;
+  }
+
+  int value_number(Instr in) {
+    std::vector<int64_t> key{(int64_t)in.kind, in.op, (int64_t)in.dtype, in.a, in.b, in.cslot, in.phase};
+    auto it = value_ids.find(key);
+    if (it != value_ids.end()) return it->second;
+    int id = push(in);
+    value_ids[key] = id;
+    return id;
+  }
+
+  int constant(gr_dtype dt, double v) {
+    int slot = -1;
+    for (size_t i = 0; i < g->consts.size(); ++i)
+      if (g->consts[i].dtype == dt && std::memcmp(&g->consts[i].value, &v, sizeof(double)) == 0) slot = (int)i;
+    if (slot < 0) { g->consts.push_back(ConstSlot{dt, v}); slot = (int)g->consts.size() - 1; }
+    Instr in;
+    in.kind = IKind::CONST; in.dtype = dt; in.cslot = slot; in.uniform = true;
+    return value_number(in);
+  }
+
+  int load(const Node* leaf, const IndexMap& m) {
+    leaves_seen.insert(leaf);
+    std::vector<int64_t> ident{(int64_t)leaf->id};
+    int64_t delta[MAXD] = {0};
+    for (int d = 0; d < leaf->ndim; ++d) {
+      const DimMap& e = m[d];
+      ident.push_back(e.src);
+      ident.push_back(e.scale);
+      if (e.src < 0) ident.push_back(e.off);
+      else { ident.push_back(floormod(e.off, e.scale)); delta[e.src] += floordiv(e.off, e.scale); }
+    }
+    int gid = -1;
+    for (size_t i = 0; i < g->groups.size(); ++i) if (g->groups[i].ident == ident) gid = (int)i;
+    if (gid < 0) {
+      AccessGroup ag;
+      ag.leaf = leaf; ag.dtype = leaf->dtype; ag.ident = ident;
+      ag.base = leaf->offset;
+      for (int k = 0; k < MAXD; ++k) ag.structural_zero[k] = true;
+      for (int d = 0; d < leaf->ndim; ++d) {
+        const DimMap& e = m[d];
+        if (e.src < 0) ag.base += leaf->strides[d] * e.off;
+        else {
+          ag.base += leaf->strides[d] * floormod(e.off, e.scale);
+          ag.coef[e.src] += leaf->strides[d] * e.scale;
+          ag.structural_zero[e.src] = false;
+        }
+      }
+      g->groups.push_back(ag);
+      gid = (int)g->groups.size() - 1;
+    }
+    std::vector<int64_t> dv(delta, delta + rank);
+    g->groups[gid].deltas.insert(dv);
+    std::vector<int64_t> key{gid};
+    key.insert(key.end(), dv.begin(), dv.end());
+    auto it = load_ids.find(key);
+    if (it != load_ids.end()) return it->second;
+    Instr in;
+    in.kind = IKind::LOAD; in.dtype = leaf->dtype; in.group = gid;
+    for (int k = 0; k < rank; ++k) in.delta[k] = delta[k];
+    in.uniform = g->groups[gid].structural_zero[rank - 1];
+    int id = push(in);
+    load_ids[key] = id;
+    return id;
+  }
+
+  static bool is_identity_on(const IndexMap& m, int d, int src, int64_t extent) {
+    if (extent == 1) return true;  // canonicalised to a constant 0
+    return m[d].src == src && m[d].scale == 1 && m[d].off == 0;
+  }
+
+  int eval(const Node* n, IndexMap m) {
+    canonicalize(n, m);
+    auto key = std::make_pair(n->id, flatten(m));
+    auto it = memo.find(key);
+    if (it != memo.end()) return it->second;
+    int id = -1;
+    if (n->kind == Kind::CONST) {
+      id = constant(n->dtype, n->value);
+    } else if (n->has_data()) {
+      id = load(n, m);
+    } else {
+      members_seen.insert(n);
+      switch (n->kind) {
+        case Kind::UNARY: {
+          Instr in;
+          in.kind = IKind::UNARY; in.op = n->op; in.dtype = n->dtype;
+          in.a = eval(n->in[0], m);
+          in.uniform = (*prog)[in.a].uniform;
+          id = value_number(in);
+          break;
+        }
+        case Kind::BINARY: {
+          int ops[2];
+          for (int s = 0; s < 2; ++s) {
+            const Node* o = n->in[s];
+            IndexMap om(o->ndim);
+            for (int d = 0; d < o->ndim; ++d) om[d] = m[d + (n->ndim - o->ndim)];
+            ops[s] = eval(o, om);  // canonicalize() zeroes broadcast (extent-1) dims
+          }
+          Instr in;
+          in.kind = IKind::BINARY; in.op = n->op; in.dtype = n->dtype; in.a = ops[0]; in.b = ops[1];
+          in.uniform = (*prog)[in.a].uniform && (*prog)[in.b].uniform;
+          id = value_number(in);
+          break;
+        }
+        case Kind::SLICE: {
+          IndexMap om(n->ndim);
+          for (int d = 0; d < n->ndim; ++d)
+            om[d] = DimMap{m[d].src, m[d].scale * n->step[d], n->start[d] + n->step[d] * m[d].off};
+          id = eval(n->in[0], om);
+          break;
+        }
+        case Kind::TRANSPOSE: {
+          IndexMap om(n->ndim);
+          for (int d = 0; d < n->ndim; ++d) om[n->perm[d]] = m[d];
+          id = eval(n->in[0], om);
+          break;
+        }
+        case Kind::REDUCE: {
+          id = reduce_result(n, m);
+          break;
+        }
+        case Kind::DOT: {
+          bool ok = g->kind == GroupKind::GEMV && (dot_core == nullptr || dot_core == n);
+          if (ok && n->ndim == 1) ok = is_identity_on(m, 0, 0, n->shape[0]);
+          if (!ok) { invalid.push_back({n, "dot result not usable as an epilogue input"}); id = constant(GR_F32, 0.0); break; }
+          dot_core = n;
+          Instr in;
+          in.kind = IKind::ACC; in.dtype = GR_F32;
+          id = value_number(in);
+          break;
+        }
+        default:
+          invalid.push_back({n, "unexpected lazy node kind"});
+          id = constant(GR_F32, 0.0);
+      }
+    }
+    memo[key] = id;
+    return id;
+  }
+
+  // A reduction met inside a row-resident sub-graph: its value for the current
+  // row is the result of one reduction phase over the row.
+  int reduce_result(const Node* r, const IndexMap& m) {
+    const Node* x = r->in[0];
+    bool ok = g->kind == GroupKind::ROWRED && x->ndim == rank && x->ndim >= 1;
+    if (ok) for (int d = 0; d < x->ndim; ++d) {
+      if (r->red_axis[d] != (d == x->ndim - 1)) ok = false;
+      if (x->shape[d] != dims[d]) ok = false;
+    }
+    if (ok) {
+      int kept = x->ndim - 1;
+      if ((int)m.size() != (r->keepdims ? x->ndim : kept)) ok = false;
+      for (int d = 0; ok && d < kept; ++d) if (!is_identity_on(m, d, d, x->shape[d])) ok = false;
+    }
+    if (!ok) {
+      invalid.push_back({r, "reduction cannot stay row-resident in this sub-graph"});
+      return constant(r->dtype, 0.0);
+    }
+    auto it = phase_of.find(r);
+    int ph;
+    if (it != phase_of.end()) ph = it->second;
+    else {
+      IndexMap full(x->ndim);
+      for (int d = 0; d < x->ndim; ++d) full[d] = DimMap{d, 1, 0};
+      int v = eval(x, full);
+      Phase p;
+      p.op = r->op; p.in_dtype = x->dtype; p.out_dtype = r->dtype; p.value = v; p.node = r;
+      g->phases.push_back(p);
+      ph = (int)g->phases.size() - 1;
+      phase_of[r] = ph;
+    }
+    Instr in;
+    in.kind = IKind::RED; in.dtype = r->dtype; in.phase = ph; in.uniform = true;
+    return value_number(in);
+  }
+};
+
+// Follows views from `n` down to a node with data, composing the index map.
+bool resolve_to_leaf(const Node* n, IndexMap m, const Node** leaf, IndexMap* lm) {
+  while (!n->has_data()) {
+    if (n->kind == Kind::SLICE) {
+      IndexMap om(n->ndim);
+      for (int d = 0; d < n->ndim; ++d) om[d] = DimMap{m[d].src, m[d].scale * n->step[d], n->start[d] + n->step[d] * m[d].off};
+      m = om;
+    } else if (n->kind == Kind::TRANSPOSE) {
+      IndexMap om(n->ndim);
+      for (int d = 0; d < n->ndim; ++d) om[n->perm[d]] = m[d];
+      m = om;
+    } else return false;
+    n = n->in[0];
+  }
+  *leaf = n;
+  *lm = m;
+  return true;
+}
+
+const Node* strip_views(const Node* n) {
+  while (n->is_view() && !n->has_data()) n = n->in[0];
+  return n;
+}
+
+int next_pow2(int64_t v) { int p = 1; while (p < v) p <<= 1; return p; }
+
+void normalize_deltas(GroupPlan* g, std::vector<Instr>* progs[], int nprogs, int rank) {
+  for (size_t gi = 0; gi < g->groups.size(); ++gi) {
+    AccessGroup& ag = g->groups[gi];
+    if (ag.deltas.empty()) continue;
+    std::vector<int64_t> mn(rank, INT64_MAX);
+    for (const auto& d : ag.deltas) for (int k = 0; k < rank; ++k) mn[k] = std::min(mn[k], d[k]);
+    std::set<std::vector<int64_t>> nd;
+    for (auto d : ag.deltas) { for (int k = 0; k < rank; ++k) d[k] -= mn[k]; nd.insert(d); }
+    ag.deltas.swap(nd);
+    for (int k = 0; k < rank; ++k) ag.base += ag.coef[k] * mn[k];
+    for (int p = 0; p < nprogs; ++p)
+      for (Instr& in : *progs[p])
+        if (in.kind == IKind::LOAD && in.group == (int)gi) for (int k = 0; k < rank; ++k) in.delta[k] -= mn[k];
+  }
+}
+
+// Merges adjacent iteration dimensions that every access (and the contiguous
+// output) walks as one linear run.  `barrier[k]` forbids merging dim k with k+1.
+void collapse_dims(GroupPlan* g, const bool* barrier, std::vector<Instr>* progs[], int nprogs) {
+  int n = g->orig_rank;
+  // runs of original dims, extent-1 dims dropped
+  std::vector<std::vector<int>> runs;
+  for (int k = 0; k < n; ++k) {
+    if (g->orig_dims[k] == 1) continue;
+    bool merged = false;
+    if (!runs.empty()) {
+      int prev = runs.back().back();
+      bool blocked = false;
+      for (int j = prev; j < k; ++j) if (barrier[j]) blocked = true;
+      if (!blocked) {
+        // prev (outer) merges with k (inner) if coef[prev] == coef[k] * dims[k] everywhere,
+        // and no access is shifted in the outer dim
+        bool ok = true;
+        for (const AccessGroup& ag : g->groups) {
+          if (ag.coef[prev] != ag.coef[k] * g->orig_dims[k]) ok = false;
+          for (const auto& d : ag.deltas) if (d[prev] != 0) ok = false;
+        }
+        if (ok) { runs.back().push_back(k); merged = true; }
+      }
+    }
+    if (!merged) runs.push_back({k});
+  }
+  if (runs.empty()) runs.push_back({n - 1});
+  // a run (outer..inner) was built by appending inner dims; verify pairwise chain (outer vs next) held
+  g->rank = (int)runs.size();
+  for (int k = 0; k < MAXD; ++k) g->collapse_to[k] = -1;
+  for (int r = 0; r < g->rank; ++r) {
+    int64_t e = 1;
+    for (int k : runs[r]) { e *= g->orig_dims[k]; g->collapse_to[k] = r; }
+    g->dims[r] = e;
+  }
+  for (AccessGroup& ag : g->groups) {
+    int64_t nc[MAXD] = {0};
+    bool nz[MAXD];
+    for (int r = 0; r < g->rank; ++r) { nc[r] = ag.coef[runs[r].back()]; nz[r] = ag.structural_zero[runs[r].back()]; }
+    std::set<std::vector<int64_t>> nd;
+    for (const auto& d : ag.deltas) {
+      std::vector<int64_t> v(g->rank);
+      for (int r = 0; r < g->rank; ++r) v[r] = d[runs[r].back()];
+      nd.insert(v);
+    }
+    ag.deltas.swap(nd);
+    for (int r = 0; r < MAXD; ++r) { ag.coef[r] = r < g->rank ? nc[r] : 0; ag.structural_zero[r] = r < g->rank ? nz[r] : true; }
+  }
+  for (int p = 0; p < nprogs; ++p)
+    for (Instr& in : *progs[p])
+      if (in.kind == IKind::LOAD) {
+        int64_t v[MAXD] = {0};
+        for (int r = 0; r < g->rank; ++r) v[r] = in.delta[runs[r].back()];
+        for (int r = 0; r < MAXD; ++r) in.delta[r] = v[r];
+      }
+}
+
+char coef_class(int64_t c) { return c == 0 ? 'Z' : (c == 1 ? '1' : 'G'); }
+
+void dump_prog(std::ostringstream& s, const std::vector<Instr>& prog, int rank) {
+  for (const Instr& in : prog) {
+    s << (int)in.kind << ':' << in.op << ':' << (int)in.dtype << ':' << in.a << ':' << in.b << ':' << in.group << ':' << in.cslot << ':' << in.phase << ':' << in.uniform;
+    if (in.kind == IKind::LOAD) for (int k = 0; k < rank; ++k) s << ',' << in.delta[k];
+    s << ';';
+  }
+}
+
+void make_signature(GroupPlan* g) {
+  std::ostringstream s;
+  s << "k" << (int)g->kind << " r" << g->rank << " o" << (int)g->out_dtype << " pr" << g->out_per_row
+    << " s" << g->BX << ',' << g->BY << ',' << g->VR << ',' << g->UC << ',' << g->NP << ',' << g->row_threads << ',' << g->xcd_remap
+    << ',' << g->red_mode << ',' << g->red_kept_rank << ',' << g->gemv_mode << ',' << g->LPR << ',' << g->KV << ',' << g->mat_group << ',' << g->vec_group << " G";
+  for (const AccessGroup& ag : g->groups) {
+    s << (int)ag.dtype << coef_class(ag.coef[g->rank - 1]) << (g->rank >= 2 ? coef_class(ag.coef[g->rank - 2]) : '-') << '|';
+  }
+  if (g->kind == GroupKind::GEMV) {
+    const AccessGroup& mg = g->groups[g->mat_group];
+    const AccessGroup& vg = g->groups[g->vec_group];
+    s << " core" << coef_class(mg.coef[0]) << coef_class(mg.coef[1]) << coef_class(vg.coef[1]);
+  }
+  s << " C";
+  for (const ConstSlot& c : g->consts) s << (int)c.dtype;
+  s << " P";
+  for (const Phase& p : g->phases) s << p.op << ':' << (int)p.in_dtype << ':' << (int)p.out_dtype << ':' << p.value << ';';
+  s << " R";
+  for (int r : g->results) s << r << ',';
+  s << " I";
+  dump_prog(s, g->prog, g->rank);
+  s << " J" << g->result1 << ' ';
+  dump_prog(s, g->prog1, g->rank);
+  g->signature = s.str();
+}
+
+struct Planner {
+  gr_ctx* c;
+  Node* root;
+  std::vector<Node*> sub;                 // lazy nodes of the visited sub-DAG, ascending id
+  std::set<const Node*> cuts;
+  std::map<const Node*, const Node*> owner;
+
+  void collect() {
+    std::set<Node*> seen;
+    std::vector<Node*> work{root};
+    while (!work.empty()) {
+      Node* n = work.back();
+      work.pop_back();
+      if (n->materialized || seen.count(n)) continue;  // a materialised node ends the walk (Section 2)
+      seen.insert(n);
+      for (Node* p : n->in) work.push_back(p);
+    }
+    sub.assign(seen.begin(), seen.end());
+    std::sort(sub.begin(), sub.end(), [](Node* a, Node* b) { return a->id < b->id; });
+  }
+
+  void initial_cuts() {
+    cuts.insert(root);
+    for (Node* n : sub) {
+      if (!c->opt_fusion && n->is_compute()) cuts.insert(n);
+      if (n->kind == Kind::DOT) {
+        // operands of a contraction are materialised first; views (a transposed
+        // matrix in particular) are folded into the contraction kernel instead
+        for (Node* o : n->in) {
+          const Node* b = strip_views(o);
+          if (!b->materialized) cuts.insert(b);
+        }
+      }
+      if (n->kind == Kind::REDUCE) {
+        const Node* x = n->in[0];
+        bool last_only = x->ndim >= 1;
+        for (int d = 0; d < x->ndim; ++d) if (n->red_axis[d] != (d == x->ndim - 1)) last_only = false;
+        if (!last_only || x->shape[x->ndim - 1] > std::min<int64_t>(c->opt_rowred_max_cols, 16384)) cuts.insert(n);
+      }
+    }
+  }
+
+  // Returns false (after adding a cut) if some node is reached from two roots.
+  bool assign_owners() {
+    owner.clear();
+    for (Node* r : sub) {
+      if (!cuts.count(r)) continue;
+      std::vector<const Node*> work;
+      std::set<const Node*> seen;
+      for (Node* p : r->in) work.push_back(p);
+      owner[r] = r;
+      while (!work.empty()) {
+        const Node* n = work.back();
+        work.pop_back();
+        if (n->materialized || cuts.count(n) || seen.count(n)) continue;
+        seen.insert(n);
+        if (n->is_compute()) {
+          auto it = owner.find(n);
+          if (it != owner.end() && it->second != r) { cuts.insert(n); return false; }  // multiple-use rule
+          owner[n] = r;
+        }
+        for (Node* p : n->in) work.push_back(p);
+      }
+    }
+    return true;
+  }
+
+  std::set<const Node*> owned_by(const Node* r) const {
+    std::set<const Node*> s;
+    for (const auto& kv : owner) if (kv.second == r) s.insert(kv.first);
+    return s;
+  }
+};
+
+void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
+  int64_t C = g->dims[g->rank - 1];
+  int64_t R = g->rank >= 2 ? g->dims[g->rank - 2] : 1;
+  int64_t outer = 1;
+  for (int k = 0; k + 2 < g->rank; ++k) outer *= g->dims[k];
+  g->BX = std::min(256, std::max(1, next_pow2((C + 3) / 4)));
+  g->BY = 256 / g->BX;
+  bool shifted_rows = false;
+  for (const AccessGroup& ag : g->groups)
+    for (const auto& d : ag.deltas) if (g->rank >= 2 && d[g->rank - 2] != 0) shifted_rows = true;
+  auto tiles = [&](int vr, int uc) {
+    int64_t tc = (int64_t)g->BX * 4 * uc, tr = (int64_t)g->BY * vr;
+    return outer * ((C + tc - 1) / tc) * ((R + tr - 1) / tr);
+  };
+  g->VR = 1; g->UC = 1;
+  if (g->rank == 1 || R == 1) {
+    for (int uc : {4, 2}) if (tiles(1, uc) >= 2048) { g->UC = uc; break; }
+  } else {
+    int want = shifted_rows ? 8 : 4;
+    for (int vr = want; vr >= 2; vr >>= 1) if (tiles(vr, 1) >= 1024 || (shifted_rows && tiles(vr, 1) >= 256)) { g->VR = vr; break; }
+  }
+  if (c->opt_map_rows > 0 && g->rank >= 2) g->VR = (int)std::min<int64_t>(c->opt_map_rows, 16);
+  if (c->opt_map_chunks > 0) g->UC = (int)std::min<int64_t>(c->opt_map_chunks, 8);
+  g->xcd_remap = shifted_rows;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+
+static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std::vector<Invalid>* invalid) {
+  std::set<const Node*> owned = pl.owned_by(r);
+  g->root = r;
+  g->out_dtype = r->dtype;
+
+  // classify
+  const Node* dot = nullptr;
+  std::vector<const Node*> reds;
+  for (const Node* n : owned) {
+    if (n->kind == Kind::DOT) { if (dot) { invalid->push_back({n, "second dot in one sub-graph"}); return GR_OK; } dot = n; }
+    if (n->kind == Kind::REDUCE) reds.push_back(n);
+  }
+  if (dot && !reds.empty()) { invalid->push_back({dot, "dot mixed with a reduction"}); return GR_OK; }
+
+  Builder b;
+  b.g = g;
+  b.owned = &owned;
+
+  if (dot) {
+    // ---- contraction with pointwise epilogue ------------------------------
+    g->kind = GroupKind::GEMV;
+    const Node* A = dot->in[0];
+    const Node* v = dot->in[1];
+    g->K = v->shape[0];
+    g->M = A->ndim == 2 ? A->shape[0] : 1;
+    if (r->ndim != dot->ndim || (dot->ndim == 1 && r->shape[0] != dot->shape[0])) { invalid->push_back({dot, "epilogue changes the shape"}); return GR_OK; }
+    g->orig_rank = 1;
+    g->orig_dims[0] = g->M;
+    b.rank = 1;
+    b.dims = g->orig_dims;
+    b.prog = &g->prog;
+    IndexMap im(r->ndim);
+    for (int d = 0; d < r->ndim; ++d) im[d] = DimMap{d, 1, 0};
+    int res = b.eval(r, im);
+    if (!b.invalid.empty()) { *invalid = b.invalid; return GR_OK; }
+    g->results.push_back(res);
+    // core operands, in the 2-D space (m, k); resolved through views only
+    int64_t core_dims[2] = {g->M, g->K};
+    Builder cb;
+    cb.g = g; cb.owned = &owned; cb.rank = 2; cb.dims = core_dims;
+    std::vector<Instr> scratch;
+    cb.prog = &scratch;
+    const Node* leaf; IndexMap lm;
+    IndexMap am(A->ndim);
+    if (A->ndim == 2) { am[0] = DimMap{0, 1, 0}; am[1] = DimMap{1, 1, 0}; } else am[0] = DimMap{1, 1, 0};
+    cb.canonicalize(A, am);
+    if (!resolve_to_leaf(A, am, &leaf, &lm)) return fail(c, GR_ERR_UNSUPPORTED, "dot: matrix operand is not materialised");
+    // the epilogue's groups use 1-D coefficients; core groups are appended with (m,k) coefficients
+    size_t before = g->groups.size();
+    cb.load(leaf, lm);
+    g->mat_group = (int)g->groups.size() - 1;
+    if (g->groups.size() == before) {  // identical ident as an epilogue group cannot happen (rank differs), keep defensive
+      return fail(c, GR_ERR_UNSUPPORTED, "dot: internal access clash");
+    }
+    IndexMap vm(1);
+    vm[0] = DimMap{1, 1, 0};
+    cb.canonicalize(v, vm);
+    if (!resolve_to_leaf(v, vm, &leaf, &lm)) return fail(c, GR_ERR_UNSUPPORTED, "dot: vector operand is not materialised");
+    before = g->groups.size();
+    cb.load(leaf, lm);
+    g->vec_group = (int)g->groups.size() - 1;
+    if (g->groups.size() == before) {
+      // same leaf, same map as the matrix (a.a for 1-D a): duplicate the group
+      g->groups.push_back(g->groups[g->mat_group]);
+      g->vec_group = (int)g->groups.size() - 1;
+    }
+    for (const Node* l : cb.leaves_seen) b.leaves_seen.insert(l);
+    b.members_seen.insert(dot);
+    g->rank = 1;
+    g->dims[0] = g->M;
+    g->collapse_to[0] = 0;
+    const AccessGroup& mg = g->groups[g->mat_group];
+    if (mg.coef[1] == 1 || g->K == 1) g->gemv_mode = 0;
+    else if (mg.coef[0] == 1) g->gemv_mode = 1;
+    else g->gemv_mode = 0;  // strided both ways: row-dot with scalar loads
+    if (g->gemv_mode == 0) {
+      g->LPR = g->K >= 2048 ? 64 : 16;
+      int64_t per = (g->K + (int64_t)g->LPR * 4 - 1) / ((int64_t)g->LPR * 4);
+      g->KV = (int)std::min<int64_t>(std::max<int64_t>(per, 1), 8);
+    } else {
+      g->BX = std::min(256, std::max(16, next_pow2((g->M + 3) / 4)));  // lanes across the output index
+      g->BY = 256 / g->BX;
+      int64_t colblocks = (g->M + (int64_t)g->BX * 4 - 1) / ((int64_t)g->BX * 4);
+      int64_t rows_per_slab = std::max<int64_t>((int64_t)g->BY * 8, (g->K + 1023) / 1024);
+      int64_t slabs = std::max<int64_t>(1, (g->K + rows_per_slab - 1) / rows_per_slab);
+      slabs = std::min<int64_t>(slabs, std::max<int64_t>(1, 2048 / colblocks));
+      g->slabs = (int)slabs;
+    }
+    std::vector<Instr>* ps[1] = {&g->prog};
+    // epilogue groups only: core groups carry no deltas
+    normalize_deltas(g, ps, 1, 1);
+  } else if (!reds.empty()) {
+    // Decide between row-resident and generic reduction.
+    bool generic = false;
+    if (r->kind == Kind::REDUCE) {
+      const Node* x = r->in[0];
+      bool last_only = x->ndim >= 1;
+      for (int d = 0; d < x->ndim; ++d) if (r->red_axis[d] != (d == x->ndim - 1)) last_only = false;
+      if (!last_only || x->shape[x->ndim - 1] > std::min<int64_t>(c->opt_rowred_max_cols, 16384)) generic = true;
+    }
+    if (generic) {
+      // ---- generic reduction root: kept dims first, reduced dims last -----
+      g->kind = GroupKind::REDUCE;
+      for (const Node* n : reds) if (n != r) { invalid->push_back({n, "nested reduction under a generic reduction"}); }
+      if (!invalid->empty()) return GR_OK;
+      const Node* x = r->in[0];
+      int pos[MAXD];
+      int nk = 0;
+      for (int d = 0; d < x->ndim; ++d) if (!r->red_axis[d]) { pos[d] = nk; g->orig_dims[nk++] = x->shape[d]; }
+      g->red_kept_rank = nk;
+      int nr = nk;
+      for (int d = 0; d < x->ndim; ++d) if (r->red_axis[d]) { pos[d] = nr; g->orig_dims[nr++] = x->shape[d]; }
+      g->orig_rank = nr;
+      if (nr == 0) { g->orig_rank = 1; g->orig_dims[0] = 1; }
+      b.rank = g->orig_rank; b.dims = g->orig_dims; b.prog = &g->prog;
+      IndexMap xm(x->ndim);
+      for (int d = 0; d < x->ndim; ++d) xm[d] = DimMap{pos[d], 1, 0};
+      b.g->kind = GroupKind::REDUCE;
+      int v = b.eval(x, xm);
+      if (!b.invalid.empty()) { *invalid = b.invalid; return GR_OK; }
+      b.members_seen.insert(r);
+      Phase p;
+      p.op = r->op; p.in_dtype = x->dtype; p.out_dtype = r->dtype; p.value = v; p.node = r;
+      g->phases.push_back(p);
+      std::vector<Instr>* ps[1] = {&g->prog};
+      normalize_deltas(g, ps, 1, g->orig_rank);
+      bool barrier[MAXD] = {false};
+      if (nk > 0 && nk < g->orig_rank) barrier[nk - 1] = true;
+      // kept/reduced boundary must survive extent-1 drops: recompute kept rank after collapsing
+      collapse_dims(g, barrier, ps, 1);
+      int kept_rank = 0;
+      for (int k = 0; k < nk; ++k) if (g->collapse_to[k] >= 0) kept_rank = std::max(kept_rank, g->collapse_to[k] + 1);
+      g->red_kept_rank = kept_rank;
+      g->red_out = 1; g->red_len = 1;
+      for (int k = 0; k < g->rank; ++k) (k < kept_rank ? g->red_out : g->red_len) *= g->dims[k];
+      if (nk == g->orig_rank || (kept_rank == g->rank)) {
+        // nothing left to reduce after dropping extent-1 dims: treat the single point as the reduced range
+        g->red_len = 1;
+      }
+      g->red_mode = g->red_out >= 4096 ? 0 : 1;
+    } else {
+      // ---- row-resident reductions fused with producers and consumers -----
+      g->kind = GroupKind::ROWRED;
+      const Node* x = reds[0]->in[0];
+      for (const Node* n : reds) {
+        const Node* xo = n->in[0];
+        bool same = xo->ndim == x->ndim;
+        for (int d = 0; same && d < x->ndim; ++d) if (xo->shape[d] != x->shape[d]) same = false;
+        if (!same) invalid->push_back({n, "reductions over different row spaces"});
+      }
+      if (!invalid->empty()) return GR_OK;
+      int n = x->ndim;
+      g->orig_rank = n;
+      for (int d = 0; d < n; ++d) g->orig_dims[d] = x->shape[d];
+      // root shape must be the row space, or one value per row
+      bool full = r->ndim == n, per_row_keep = r->ndim == n, per_row_drop = r->ndim == n - 1;
+      for (int d = 0; d < n; ++d) {
+        if (full && r->shape[d] != x->shape[d]) full = false;
+        if (per_row_keep && r->shape[d] != (d == n - 1 ? 1 : x->shape[d])) per_row_keep = false;
+        if (per_row_drop && d < n - 1 && r->shape[d] != x->shape[d]) per_row_drop = false;
+      }
+      if (x->shape[n - 1] == 1) per_row_keep = false;  // degenerate: full covers it
+      if (!full && !per_row_keep && !per_row_drop) {
+        for (const Node* q : reds) invalid->push_back({q, "consumer shape differs from the row space"});
+        return GR_OK;
+      }
+      g->out_per_row = !full;
+      b.rank = n; b.dims = g->orig_dims; b.prog = &g->prog;
+      IndexMap im(r->ndim);
+      for (int d = 0; d < r->ndim; ++d) im[d] = DimMap{d, 1, 0};
+      int res = b.eval(r, im);
+      if (!b.invalid.empty()) { *invalid = b.invalid; return GR_OK; }
+      g->results.push_back(res);
+      std::vector<Instr>* ps[1] = {&g->prog};
+      normalize_deltas(g, ps, 1, n);
+      bool barrier[MAXD] = {false};
+      if (n >= 2) barrier[n - 2] = true;  // never merge rows into the reduced axis
+      collapse_dims(g, barrier, ps, 1);
+      // the reduced axis must remain the last collapsed dim even if its extent is 1
+      if (g->orig_dims[n - 1] == 1) {
+        g->dims[g->rank] = 1;
+        g->collapse_to[n - 1] = g->rank;
+        g->rank++;
+        if (g->rank == 2 && g->dims[0] == 1 && g->collapse_to[0] < 0 && n == 1) {}
+      }
+      int64_t C = g->dims[g->rank - 1];
+      g->row_threads = C <= 256 ? 16 : (C <= 4096 ? 64 : 256);
+      g->NP = (int)std::max<int64_t>(1, (C + (int64_t)g->row_threads * 4 - 1) / ((int64_t)g->row_threads * 4));
+    }
+  } else {
+    // ---- map ----------------------------------------------------------------
+    g->kind = GroupKind::MAP;
+    for (const Node* n : reds) invalid->push_back({n, "reduction inside a map sub-graph"});
+    if (!invalid->empty()) return GR_OK;
+    int n = std::max(r->ndim, 1);
+    g->orig_rank = n;
+    if (r->ndim == 0) g->orig_dims[0] = 1;
+    for (int d = 0; d < r->ndim; ++d) g->orig_dims[d] = r->shape[d];
+    IndexMap im(r->ndim);
+    for (int d = 0; d < r->ndim; ++d) im[d] = DimMap{d, 1, 0};
+    // pass 1: single point, to learn the accesses and fix the schedule
+    GroupPlan probe = *g;
+    {
+      Builder pb;
+      pb.g = &probe; pb.owned = &owned; pb.rank = n; pb.dims = g->orig_dims; pb.prog = &probe.prog;
+      pb.eval(r, im);
+      if (!pb.invalid.empty()) { *invalid = pb.invalid; return GR_OK; }
+      std::vector<Instr>* ps[1] = {&probe.prog};
+      normalize_deltas(&probe, ps, 1, n);
+      bool barrier[MAXD] = {false};
+      collapse_dims(&probe, barrier, ps, 1);
+      choose_map_schedule(c, &probe);
+    }
+    g->BX = probe.BX; g->BY = probe.BY; g->VR = probe.VR; g->UC = probe.UC; g->xcd_remap = probe.xcd_remap;
+    // innermost original dims of the last two collapsed dims carry the patch shifts
+    int col_dim = -1, row_dim = -1;
+    for (int k = 0; k < n; ++k) {
+      if (probe.collapse_to[k] == probe.rank - 1) col_dim = k;
+      if (probe.rank >= 2 && probe.collapse_to[k] == probe.rank - 2) row_dim = k;
+    }
+    if (col_dim < 0) col_dim = n - 1;
+    // pass 2: the whole per-lane patch with common subexpressions shared across points
+    b.rank = n; b.dims = g->orig_dims; b.prog = &g->prog;
+    for (int v = 0; v < g->VR; ++v)
+      for (int u = 0; u < g->UC; ++u)
+        for (int j = 0; j < 4; ++j) {
+          IndexMap pm = im;
+          for (int d = 0; d < r->ndim; ++d) {
+            if (d == col_dim) pm[d].off += (int64_t)u * g->BX * 4 + j;
+            if (d == row_dim) pm[d].off += v;
+          }
+          // shifted points are evaluated as if the root were larger; canonicalisation of the
+          // root's own extent-1 dims still applies, which is right: such dims carry no shift
+          g->results.push_back(b.eval(r, pm));
+        }
+    // single-point program for boundary tiles
+    Builder sb;  // shares the group table so that both programs index the same access groups
+    sb.g = g; sb.owned = &owned; sb.rank = n; sb.dims = g->orig_dims; sb.prog = &g->prog1;
+    g->result1 = sb.eval(r, im);
+    std::vector<Instr>* ps[2] = {&g->prog, &g->prog1};
+    normalize_deltas(g, ps, 2, n);
+    bool barrier[MAXD] = {false};
+    // shifts in an outer dim forbid merging it; the patch shifts above touch only col_dim/row_dim,
+    // which are innermost in their runs, so the probe's collapse decision is reproduced
+    collapse_dims(g, barrier, ps, 2);
+    if (g->rank != probe.rank) return fail(c, GR_ERR_UNSUPPORTED, "map: inconsistent dimension collapsing");
+  }
+
+  for (const Node* n : b.members_seen) g->members.push_back(n);
+  std::sort(g->members.begin(), g->members.end(), [](const Node* a, const Node* b2) { return a->id < b2->id; });
+  for (const Node* n : b.leaves_seen) g->leaves.push_back(n);
+  std::sort(g->leaves.begin(), g->leaves.end(), [](const Node* a, const Node* b2) { return a->id < b2->id; });
+  make_signature(g);
+  return GR_OK;
+}
+
+gr_status make_plan(gr_ctx* c, Node* root, Plan* plan) {
+  if (root->kind == Kind::SCALAR) return fail(c, GR_ERR_UNSUPPORTED, "a bare scalar cannot be materialised");
+  Planner pl;
+  pl.c = c;
+  pl.root = root;
+  pl.collect();
+  pl.initial_cuts();
+  for (int iter = 0; iter < 10000; ++iter) {
+    if (!pl.assign_owners()) continue;
+    clear_planned(plan);
+    plan->groups.clear();
+    std::vector<Invalid> invalid;
+    bool restart = false;
+    std::vector<Node*> order;
+    for (Node* n : pl.sub) if (pl.cuts.count(n)) order.push_back(n);
+    if (!pl.cuts.count(root) || root->materialized) order.push_back(root);  // root with data: a plain copy
+    std::sort(order.begin(), order.end(), [](Node* a, Node* b) { return a->id < b->id; });
+    order.erase(std::unique(order.begin(), order.end()), order.end());
+    for (Node* r : order) {
+      std::unique_ptr<GroupPlan> g(new GroupPlan());
+      gr_status st = build_group(c, pl, r, g.get(), &invalid);
+      if (st != GR_OK) { clear_planned(plan); plan->groups.clear(); return st; }
+      if (!invalid.empty()) {
+        bool added = false;
+        for (const Invalid& iv : invalid) if (pl.cuts.insert(iv.node).second) added = true;
+        if (!added) { clear_planned(plan); plan->groups.clear(); return fail(c, GR_ERR_UNSUPPORTED, "cannot plan: " + invalid[0].why); }
+        restart = true;
+        break;
+      }
+      plan->groups.push_back(std::move(g));
+      if (!r->materialized) {
+        // later sub-graphs read this node as a C-contiguous leaf
+        r->planned = true;
+        int64_t s = 1;
+        for (int d = r->ndim - 1; d >= 0; --d) { r->strides[d] = s; s *= r->shape[d]; }
+        r->offset = 0;
+        plan->planned_nodes.push_back(r);
+      }
+    }
+    if (!restart) return GR_OK;
+  }
+  clear_planned(plan);
+  plan->groups.clear();
+  return fail(c, GR_ERR_UNSUPPORTED, "planner did not converge");
+}
+
+void clear_planned(Plan* plan) {
+  for (Node* n : plan->planned_nodes) n->planned = false;
+  plan->planned_nodes.clear();
+}
+
+std::string describe_plan(const Plan& plan) {
+  std::ostringstream s;
+  int i = 0;
+  for (const auto& gp : plan.groups) {
+    const GroupPlan& g = *gp;
+    const char* kn = g.kind == GroupKind::MAP ? "MAP" : g.kind == GroupKind::ROWRED ? "ROWRED" : g.kind == GroupKind::REDUCE ? "REDUCE" : "GEMV";
+    s << '#' << i++ << ' ' << kn << " root=" << g.root->id << " shape=(";
+    for (int d = 0; d < g.root->ndim; ++d) s << (d ? "," : "") << g.root->shape[d];
+    s << ") iter=(";
+    for (int d = 0; d < g.rank; ++d) s << (d ? "," : "") << g.dims[d];
+    s << ") members=[";
+    bool first = true;
+    for (const Node* n : g.members) {
+      if (n->is_view()) continue;
+      s << (first ? "" : ",") << n->id << ':' << node_label(n);
+      first = false;
+    }
+    s << "] leaves=[";
+    first = true;
+    for (const Node* n : g.leaves) { s << (first ? "" : ",") << n->id; first = false; }
+    s << "] loads=" << [&] { int k = 0; for (const Instr& in : (g.kind == GroupKind::MAP ? g.prog1 : g.prog)) if (in.kind == IKind::LOAD) ++k; return k; }();
+    if (g.kind == GroupKind::GEMV) s << " mode=" << (g.gemv_mode ? "column-accumulate" : "row-dot") << " M=" << g.M << " K=" << g.K;
+    if (g.kind == GroupKind::ROWRED) s << " phases=" << g.phases.size() << " row_threads=" << g.row_threads << " NP=" << g.NP;
+    if (g.kind == GroupKind::MAP) s << " tile=" << g.BY * g.VR << "x" << g.BX * 4 * g.UC << " patch=" << g.VR << "x" << g.UC * 4;
+    s << '\n';
+  }
+  return s.str();
+}
+
+}  // namespace gr

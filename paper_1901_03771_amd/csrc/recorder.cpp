@@ -1,0 +1,417 @@
+// DAG recorder: every array operation appends a node with inferred shape and
+// element type instead of executing (Section 1: deferred execution; Section 2:
+// "the size of the tensor represented by each node, and the data type of the
+// tensor elements are computed automatically while the DAG is built").
+// Nothing in this file touches the device.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+
+#include "ctx.h"
+
+namespace gr {
+
+static thread_local std::string g_create_err;
+
+gr_status fail(gr_ctx* c, gr_status s, const std::string& msg) {
+  if (c) c->err = msg; else g_create_err = msg;
+  return s;
+}
+
+Node* lookup(gr_ctx* c, gr_array a) {
+  auto it = c->nodes.find(a);
+  if (it == c->nodes.end() || it->second->handle_refs <= 0) return nullptr;
+  return it->second;
+}
+
+Node* new_node(gr_ctx* c, Kind kind) {
+  Node* n = new Node();
+  n->id = c->next_id++;
+  n->kind = kind;
+  n->handle_refs = 1;
+  c->nodes[n->id] = n;
+  c->stats.nodes_recorded++;
+  c->stats.nodes_alive++;
+  return n;
+}
+
+static void add_input(Node* n, Node* in) {
+  n->in.push_back(in);
+  in->consumer_refs++;
+}
+
+// Frees every node that has lost its last reference, iteratively.
+void node_maybe_free(gr_ctx* c, Node* n0) {
+  std::vector<Node*> work{n0};
+  while (!work.empty()) {
+    Node* n = work.back();
+    work.pop_back();
+    if (n->handle_refs > 0 || n->consumer_refs > 0) continue;
+    for (Node* p : n->in) {
+      // a predecessor is queued exactly once: when it loses its last reference
+      if (--p->consumer_refs == 0 && p->handle_refs == 0) work.push_back(p);
+    }
+    n->in.clear();
+    if (n->owns_data && n->data) ctx_free(c, n->data, n->alloc_bytes);
+    c->nodes.erase(n->id);
+    c->stats.nodes_alive--;
+    delete n;
+  }
+}
+
+// A materialised node no longer needs its predecessors (Section 2: later
+// requests read its data instead of recomputing it).
+void drop_inputs(gr_ctx* c, Node* n) {
+  std::vector<Node*> ins;
+  ins.swap(n->in);
+  for (Node* p : ins)
+    if (--p->consumer_refs == 0 && p->handle_refs == 0) node_maybe_free(c, p);
+}
+
+static void contiguous_strides(Node* n) {
+  int64_t s = 1;
+  for (int d = n->ndim - 1; d >= 0; --d) {
+    n->strides[d] = s;
+    s *= n->shape[d];
+  }
+}
+
+static bool is_unary(int op) { return op >= GR_NEG && op <= GR_TANH; }
+static bool is_binary(int op) { return op >= GR_ADD && op <= GR_MINIMUM; }
+static bool is_reduce(int op) { return op >= GR_SUM && op <= GR_MIN; }
+
+}  // namespace gr
+
+using namespace gr;
+
+extern "C" {
+
+const char* gr_last_error(gr_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
+  if (!ctx || !key) return GR_ERR_ARG;
+  std::string k(key);
+  if (k == "fusion") ctx->opt_fusion = value;
+  else if (k == "rowred_max_cols") ctx->opt_rowred_max_cols = value;
+  else if (k == "map_rows") ctx->opt_map_rows = value;
+  else if (k == "map_chunks") ctx->opt_map_chunks = value;
+  else if (k == "profile") ctx->opt_profile = value;
+  else return fail(ctx, GR_ERR_ARG, "unknown option '" + k + "'");
+  return GR_OK;
+}
+
+gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t, void*), void (*free_)(void*, void*), void* user) {
+  if (!ctx) return GR_ERR_ARG;
+  if ((alloc == nullptr) != (free_ == nullptr)) return fail(ctx, GR_ERR_ARG, "alloc and free must be given together");
+  ctx->alloc_fn = alloc;
+  ctx->free_fn = free_;
+  ctx->alloc_user = user;
+  return GR_OK;
+}
+
+gr_status gr_array_from_device(gr_ctx* ctx, void* dptr, gr_dtype dtype, int ndim, const int64_t* shape,
+                               const int64_t* strides_elems, gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  if (ndim < 0 || ndim > MAXD || (ndim > 0 && !shape)) return fail(ctx, GR_ERR_ARG, "from_device: bad rank or NULL shape");
+  if (dtype != GR_F32 && dtype != GR_I32 && dtype != GR_I64) return fail(ctx, GR_ERR_ARG, "from_device: bad dtype");
+  int64_t n = 1;
+  for (int d = 0; d < ndim; ++d) {
+    if (shape[d] < 0) return fail(ctx, GR_ERR_ARG, "from_device: negative extent");
+    n *= shape[d];
+  }
+  if (n > 0 && !dptr) return fail(ctx, GR_ERR_ARG, "from_device: NULL device pointer");
+  if (((uintptr_t)dptr) % itemsize(dtype)) return fail(ctx, GR_ERR_ARG, "from_device: pointer not aligned to the element size");
+  Node* nd = new_node(ctx, Kind::LEAF);
+  nd->dtype = dtype;
+  nd->ndim = ndim;
+  for (int d = 0; d < ndim; ++d) nd->shape[d] = shape[d];
+  if (strides_elems) for (int d = 0; d < ndim; ++d) nd->strides[d] = strides_elems[d];
+  else contiguous_strides(nd);
+  nd->materialized = true;
+  nd->data = dptr;
+  nd->offset = 0;
+  *out = nd->id;
+  return GR_OK;
+}
+
+gr_status gr_scalar(gr_ctx* ctx, double value, int is_integer, gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  if (is_integer && value != std::floor(value)) return fail(ctx, GR_ERR_ARG, "scalar: is_integer set on a fractional value");
+  Node* nd = new_node(ctx, Kind::SCALAR);
+  nd->value = value;
+  nd->is_int = is_integer != 0;
+  nd->ndim = 0;
+  *out = nd->id;
+  return GR_OK;
+}
+
+gr_status gr_unary(gr_ctx* ctx, gr_op op, gr_array a, gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  if (!is_unary(op)) return fail(ctx, GR_ERR_ARG, "unary: not a unary op");
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "unary: bad handle");
+  if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "unary: operand is a bare scalar");
+  if (x->dtype == GR_I64) return fail(ctx, GR_ERR_UNSUPPORTED, "unary: i64 arithmetic is not supported");
+  if (x->dtype == GR_I32 && !(op == GR_NEG || op == GR_ABS || op == GR_SQUARE))
+    return fail(ctx, GR_ERR_DTYPE, "unary: float function of an i32 array would promote to f64");
+  Node* n = new_node(ctx, Kind::UNARY);
+  n->op = op;
+  n->dtype = x->dtype;
+  n->ndim = x->ndim;
+  for (int d = 0; d < x->ndim; ++d) n->shape[d] = x->shape[d];
+  add_input(n, x);
+  *out = n->id;
+  return GR_OK;
+}
+
+gr_status gr_binary(gr_ctx* ctx, gr_op op, gr_array a, gr_array b, gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  if (!is_binary(op)) return fail(ctx, GR_ERR_ARG, "binary: not a binary op");
+  Node* x = lookup(ctx, a);
+  Node* y = lookup(ctx, b);
+  if (!x || !y) return fail(ctx, GR_ERR_HANDLE, "binary: bad handle");
+  bool wx = x->kind == Kind::SCALAR, wy = y->kind == Kind::SCALAR;
+  if (wx && wy) return fail(ctx, GR_ERR_UNSUPPORTED, "binary: two bare scalars");
+  gr_dtype dt = wx ? y->dtype : x->dtype;
+  if (!wx && !wy && x->dtype != y->dtype) return fail(ctx, GR_ERR_DTYPE, "binary: mixed element types would promote to f64");
+  if (dt == GR_I64) return fail(ctx, GR_ERR_UNSUPPORTED, "binary: i64 arithmetic is not supported");
+  if (dt == GR_I32 && op == GR_DIV) return fail(ctx, GR_ERR_UNSUPPORTED, "binary: integer division is not supported");
+  const Node* w = wx ? x : (wy ? y : nullptr);
+  if (w && dt == GR_I32) {
+    if (!w->is_int) return fail(ctx, GR_ERR_DTYPE, "binary: float scalar with an i32 array would promote to f64");
+    if (w->value < -2147483648.0 || w->value > 2147483647.0) return fail(ctx, GR_ERR_DTYPE, "binary: integer scalar does not fit i32");
+  }
+  // NumPy broadcast: right-align, each pair equal or one of them 1.
+  const Node* ax = wx ? nullptr : x;
+  const Node* ay = wy ? nullptr : y;
+  int nx = ax ? ax->ndim : 0, ny = ay ? ay->ndim : 0;
+  int n = std::max(nx, ny);
+  int64_t shape[MAXD];
+  for (int d = 0; d < n; ++d) {
+    int dx = d - (n - nx), dy = d - (n - ny);
+    int64_t sx = (ax && dx >= 0) ? ax->shape[dx] : 1;
+    int64_t sy = (ay && dy >= 0) ? ay->shape[dy] : 1;
+    if (sx == sy) shape[d] = sx;
+    else if (sx == 1) shape[d] = sy;
+    else if (sy == 1) shape[d] = sx;
+    else return fail(ctx, GR_ERR_SHAPE, "binary: shapes do not broadcast");
+  }
+  Node* r = new_node(ctx, Kind::BINARY);
+  r->op = op;
+  r->dtype = dt;
+  r->ndim = n;
+  for (int d = 0; d < n; ++d) r->shape[d] = shape[d];
+  auto operand = [&](Node* o) -> Node* {
+    if (o->kind != Kind::SCALAR) return o;
+    Node* k = new_node(ctx, Kind::CONST);  // the scalar hardened to this op's element type
+    k->handle_refs = 0;
+    k->dtype = dt;
+    k->ndim = 0;
+    k->is_int = o->is_int;
+    k->value = dt == GR_F32 ? (double)(float)o->value : o->value;
+    return k;
+  };
+  add_input(r, operand(x));
+  add_input(r, operand(y));
+  *out = r->id;
+  return GR_OK;
+}
+
+gr_status gr_slice(gr_ctx* ctx, gr_array a, int nspec, const int64_t* start, const int64_t* stop,
+                   const int64_t* step, const uint8_t* has_start, const uint8_t* has_stop, gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "slice: bad handle");
+  if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "slice: operand is a bare scalar");
+  if (nspec < 0 || nspec > x->ndim) return fail(ctx, GR_ERR_SHAPE, "slice: too many indices");
+  if (nspec > 0 && (!start || !stop || !step || !has_start || !has_stop)) return fail(ctx, GR_ERR_ARG, "slice: NULL argument");
+  int64_t lo[MAXD], st[MAXD], len[MAXD];
+  for (int d = 0; d < x->ndim; ++d) {
+    int64_t n = x->shape[d];
+    if (d >= nspec) { lo[d] = 0; st[d] = 1; len[d] = n; continue; }
+    if (step[d] < 1) return fail(ctx, GR_ERR_UNSUPPORTED, "slice: step must be >= 1");
+    int64_t l = has_start[d] ? start[d] : 0, h = has_stop[d] ? stop[d] : n;
+    if (l < 0) l += n;
+    if (h < 0) h += n;
+    l = std::min(std::max<int64_t>(l, 0), n);
+    h = std::min(std::max<int64_t>(h, 0), n);
+    lo[d] = l;
+    st[d] = step[d];
+    len[d] = h > l ? (h - l + step[d] - 1) / step[d] : 0;
+  }
+  Node* r = new_node(ctx, Kind::SLICE);
+  r->dtype = x->dtype;
+  r->ndim = x->ndim;
+  for (int d = 0; d < x->ndim; ++d) { r->shape[d] = len[d]; r->start[d] = lo[d]; r->step[d] = st[d]; }
+  add_input(r, x);
+  *out = r->id;
+  return GR_OK;
+}
+
+gr_status gr_transpose(gr_ctx* ctx, gr_array a, const int* perm, gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "transpose: bad handle");
+  if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "transpose: operand is a bare scalar");
+  int p[MAXD];
+  bool seen[MAXD] = {false};
+  for (int d = 0; d < x->ndim; ++d) {
+    int v = perm ? perm[d] : x->ndim - 1 - d;
+    if (v < 0) v += x->ndim;
+    if (v < 0 || v >= x->ndim || seen[v]) return fail(ctx, GR_ERR_AXIS, "transpose: not a permutation");
+    seen[v] = true;
+    p[d] = v;
+  }
+  Node* r = new_node(ctx, Kind::TRANSPOSE);
+  r->dtype = x->dtype;
+  r->ndim = x->ndim;
+  for (int d = 0; d < x->ndim; ++d) { r->shape[d] = x->shape[p[d]]; r->perm[d] = p[d]; }
+  add_input(r, x);
+  *out = r->id;
+  return GR_OK;
+}
+
+gr_status gr_reduce(gr_ctx* ctx, gr_op op, gr_array a, const int* axes, int naxes, int keepdims, gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  if (!is_reduce(op)) return fail(ctx, GR_ERR_ARG, "reduce: not a reduction op");
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "reduce: bad handle");
+  if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "reduce: operand is a bare scalar");
+  if (x->dtype == GR_I64) return fail(ctx, GR_ERR_UNSUPPORTED, "reduce: i64 operands are not supported");
+  if (naxes < 0 || naxes > x->ndim || (naxes > 0 && !axes)) return fail(ctx, GR_ERR_AXIS, "reduce: bad axis list");
+  bool red[MAXD];
+  for (int d = 0; d < x->ndim; ++d) red[d] = (naxes == 0);
+  for (int k = 0; k < naxes; ++k) {
+    int ax = axes[k] < 0 ? axes[k] + x->ndim : axes[k];
+    if (ax < 0 || ax >= x->ndim) return fail(ctx, GR_ERR_AXIS, "reduce: axis out of range");
+    if (red[ax]) return fail(ctx, GR_ERR_AXIS, "reduce: repeated axis");
+    red[ax] = true;
+  }
+  int64_t rcount = 1;
+  for (int d = 0; d < x->ndim; ++d) if (red[d]) rcount *= x->shape[d];
+  if (rcount == 0 && op != GR_SUM) return fail(ctx, GR_ERR_SHAPE, "reduce: max/min over an empty range");
+  Node* r = new_node(ctx, Kind::REDUCE);
+  r->op = op;
+  r->dtype = (x->dtype == GR_I32 && op == GR_SUM) ? GR_I64 : x->dtype;
+  r->keepdims = keepdims != 0;
+  int nd = 0;
+  for (int d = 0; d < x->ndim; ++d) {
+    r->red_axis[d] = red[d];
+    if (red[d]) { if (keepdims) r->shape[nd++] = 1; }
+    else r->shape[nd++] = x->shape[d];
+  }
+  r->ndim = nd;
+  add_input(r, x);
+  *out = r->id;
+  return GR_OK;
+}
+
+gr_status gr_dot(gr_ctx* ctx, gr_array a, gr_array b, gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  Node* y = lookup(ctx, b);
+  if (!x || !y) return fail(ctx, GR_ERR_HANDLE, "dot: bad handle");
+  if (x->kind == Kind::SCALAR || y->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "dot: scalar operand");
+  if (x->dtype != GR_F32 || y->dtype != GR_F32) return fail(ctx, GR_ERR_DTYPE, "dot: f32 operands only");
+  if (y->ndim == 2 && (x->ndim == 2 || x->ndim == 1)) return fail(ctx, GR_ERR_UNSUPPORTED, "dot: matrix right operand (matrix-matrix product) is not supported");
+  if (y->ndim != 1 || x->ndim < 1 || x->ndim > 2) return fail(ctx, GR_ERR_UNSUPPORTED, "dot: supported ranks are (M,K).(K,) and (K,).(K,)");
+  if (x->shape[x->ndim - 1] != y->shape[0]) return fail(ctx, GR_ERR_SHAPE, "dot: inner dimensions differ");
+  Node* r = new_node(ctx, Kind::DOT);
+  r->dtype = GR_F32;
+  r->ndim = x->ndim - 1;
+  if (x->ndim == 2) r->shape[0] = x->shape[0];
+  add_input(r, x);
+  add_input(r, y);
+  *out = r->id;
+  return GR_OK;
+}
+
+gr_status gr_ndim(gr_ctx* ctx, gr_array a, int* ndim) {
+  if (!ctx || !ndim) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "ndim: bad handle");
+  *ndim = x->ndim;
+  return GR_OK;
+}
+
+gr_status gr_shape(gr_ctx* ctx, gr_array a, int64_t* shape) {
+  if (!ctx || !shape) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "shape: bad handle");
+  for (int d = 0; d < x->ndim; ++d) shape[d] = x->shape[d];
+  return GR_OK;
+}
+
+gr_status gr_dtype_of(gr_ctx* ctx, gr_array a, gr_dtype* dtype) {
+  if (!ctx || !dtype) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "dtype_of: bad handle");
+  if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "dtype_of: a bare scalar has no element type");
+  *dtype = x->dtype;
+  return GR_OK;
+}
+
+// Resolves a chain of views down to a materialised node, composing offset and
+// strides.  Returns false if the chain ends at a lazy node.
+static bool resolve_view(const Node* n, void** data, int64_t* offset, int64_t* strides) {
+  if (n->materialized) {
+    *data = n->data;
+    *offset = n->offset;
+    for (int d = 0; d < n->ndim; ++d) strides[d] = n->strides[d];
+    return true;
+  }
+  if (!n->is_view()) return false;
+  int64_t st[MAXD];
+  if (!resolve_view(n->in[0], data, offset, st)) return false;
+  if (n->kind == Kind::SLICE) {
+    for (int d = 0; d < n->ndim; ++d) { *offset += n->start[d] * st[d]; strides[d] = st[d] * n->step[d]; }
+  } else {
+    for (int d = 0; d < n->ndim; ++d) strides[d] = st[n->perm[d]];
+  }
+  return true;
+}
+
+gr_status gr_is_materialized(gr_ctx* ctx, gr_array a, int* flag) {
+  if (!ctx || !flag) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "is_materialized: bad handle");
+  void* p; int64_t off, st[MAXD];
+  *flag = (x->kind != Kind::SCALAR && resolve_view(x, &p, &off, st)) ? 1 : 0;
+  return GR_OK;
+}
+
+gr_status gr_data_ptr(gr_ctx* ctx, gr_array a, void** dptr, int64_t* strides) {
+  if (!ctx || !dptr) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "data_ptr: bad handle");
+  void* p; int64_t off, st[MAXD];
+  if (x->kind == Kind::SCALAR || !resolve_view(x, &p, &off, st)) return fail(ctx, GR_ERR_UNSUPPORTED, "data_ptr: array is not materialised");
+  *dptr = (char*)p + off * (int64_t)itemsize(x->dtype);
+  if (strides) for (int d = 0; d < x->ndim; ++d) strides[d] = st[d];
+  return GR_OK;
+}
+
+gr_status gr_retain(gr_ctx* ctx, gr_array a) {
+  if (!ctx) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "retain: bad handle");
+  x->handle_refs++;
+  return GR_OK;
+}
+
+gr_status gr_release(gr_ctx* ctx, gr_array a) {
+  if (!ctx) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "release: bad handle");
+  x->handle_refs--;
+  node_maybe_free(ctx, x);
+  return GR_OK;
+}
+
+gr_status gr_stats(gr_ctx* ctx, gr_stats_t* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  *out = ctx->stats;
+  return GR_OK;
+}
+
+}  // extern "C"

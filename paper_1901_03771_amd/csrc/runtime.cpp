@@ -1,0 +1,449 @@
+// Runtime: context lifetime, device memory pool, run-time compilation through
+// hipRTC with a cache keyed on the sub-graph signature (the paper names JIT
+// compilation as its main overhead, Section 4.2 and Section 6; one compiled
+// kernel serves every request with the same structure, whatever the extents,
+// strides and constants), argument marshalling and launches on the caller's
+// stream, and the materialise entry points (Section 2: the computed node gets
+// its data and is_materialized = true).
+#include <hip/hip_runtime_api.h>
+#include <hip/hiprtc.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
+
+#include "codegen.h"
+#include "ctx.h"
+
+extern "C" void gr_launch_stream_copy(void* stream, void* dst, const void* src, size_t n16);
+extern "C" void gr_launch_stream_read(void* stream, const void* src, size_t n16, void* sink);
+
+namespace gr {
+
+static std::string hip_err(hipError_t e) { return std::string(hipGetErrorName(e)) + ": " + hipGetErrorString(e); }
+
+#define GR_HIP(c, call)                                                                           \
+  do {                                                                                            \
+    hipError_t e_ = (call);                                                                       \
+    if (e_ != hipSuccess) return fail((c), GR_ERR_HIP, std::string(#call) + " -> " + hip_err(e_)); \
+  } while (0)
+
+void* ctx_alloc(gr_ctx* c, size_t bytes) {
+  if (bytes == 0) bytes = 256;
+  c->stats.bytes_allocated += bytes;
+  if (c->alloc_fn) return c->alloc_fn(bytes, c->alloc_user);
+  size_t rounded = (bytes + 255) & ~(size_t)255;
+  auto& fl = c->pool_free[rounded];
+  if (!fl.empty()) {
+    void* p = fl.back();
+    fl.pop_back();
+    return p;
+  }
+  void* p = nullptr;
+  if (hipMalloc(&p, rounded) != hipSuccess) return nullptr;
+  c->pool_all.push_back(p);
+  return p;
+}
+
+void ctx_free(gr_ctx* c, void* p, size_t bytes) {
+  if (!p) return;
+  if (bytes == 0) bytes = 256;
+  if (c->free_fn) { c->free_fn(p, c->alloc_user); return; }
+  // stream order makes reuse safe: every kernel of this context runs on one stream
+  c->pool_free[(bytes + 255) & ~(size_t)255].push_back(p);
+}
+
+gr_status compile_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel** out) {
+  auto it = c->cache.find(g.signature);
+  if (it != c->cache.end()) {
+    c->stats.cache_hits++;
+    *out = &it->second;
+    return GR_OK;
+  }
+  c->stats.cache_misses++;
+  auto t0 = std::chrono::steady_clock::now();
+  std::string src = generate_source(g);
+  if (getenv("GR_LOG")) fprintf(stderr, "---- generated kernel ----\n%s\n", src.c_str());
+  hiprtcProgram prog;
+  if (hiprtcCreateProgram(&prog, src.c_str(), "gr_kernel.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
+    return fail(c, GR_ERR_COMPILE, "hiprtcCreateProgram failed");
+  // No FMA contraction and no fast-math: every recorded op rounds once, as in
+  // eager evaluation.  Packed FP32 instructions are disabled.
+  const char* opts[] = {"--offload-arch=gfx950", "-O3", "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+  int nopts = 7;
+  hiprtcResult r = hiprtcCompileProgram(prog, nopts, opts);
+  if (r != HIPRTC_SUCCESS) {
+    size_t n = 0;
+    hiprtcGetProgramLogSize(prog, &n);
+    std::string log(n, '\0');
+    if (n) hiprtcGetProgramLog(prog, &log[0]);
+    hiprtcDestroyProgram(&prog);
+    if (getenv("GR_LOG")) fprintf(stderr, "%s\n", src.c_str());
+    return fail(c, GR_ERR_COMPILE, "hipRTC: " + log);
+  }
+  size_t cs = 0;
+  hiprtcGetCodeSize(prog, &cs);
+  gr_ctx::Kernel k;
+  k.code.resize(cs);
+  hiprtcGetCode(prog, k.code.data());
+  hiprtcDestroyProgram(&prog);
+  k.name = kernel_name(g);
+  if (c->device >= 0) {
+    GR_HIP(c, hipModuleLoadData(&k.module, k.code.data()));
+    GR_HIP(c, hipModuleGetFunction(&k.fn, k.module, k.name.c_str()));
+    if (g.kind == GroupKind::GEMV && g.gemv_mode == 1)
+      GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, (k.name + "_combine").c_str()));
+  }
+  c->stats.compile_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  auto ins = c->cache.emplace(g.signature, std::move(k));
+  *out = &ins.first->second;
+  return GR_OK;
+}
+
+static gr_status launch(gr_ctx* c, hipFunction_t fn, const std::string& name, int64_t grid, std::vector<uint64_t>& args) {
+  if (grid <= 0) return GR_OK;
+  if (grid > 0x7fffffffLL) return fail(c, GR_ERR_UNSUPPORTED, "launch: grid too large");
+  size_t sz = args.size() * sizeof(uint64_t);
+  void* extra[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, args.data(), HIP_LAUNCH_PARAM_BUFFER_SIZE, &sz, HIP_LAUNCH_PARAM_END};
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (c->opt_profile) {
+    for (hipEvent_t* ev : {&e0, &e1}) {
+      if (!c->event_pool.empty()) { *ev = c->event_pool.back(); c->event_pool.pop_back(); }
+      else GR_HIP(c, hipEventCreate(ev));
+    }
+    GR_HIP(c, hipEventRecord(e0, c->stream));
+  }
+  GR_HIP(c, hipModuleLaunchKernel(fn, (unsigned)grid, 1, 1, 256, 1, 1, 0, c->stream, nullptr, extra));
+  if (c->opt_profile) {
+    GR_HIP(c, hipEventRecord(e1, c->stream));
+    c->prof.push_back({name, e0, e1});
+  }
+  c->stats.kernel_launches++;
+  return GR_OK;
+}
+
+gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr) {
+  ArgLayout L = arg_layout(g);
+  std::vector<uint64_t> s(L.total, 0);
+  for (size_t gi = 0; gi < g.groups.size(); ++gi) {
+    const AccessGroup& ag = g.groups[gi];
+    if (!ag.leaf->data && ag.leaf->count() > 0) return fail(c, GR_ERR_HIP, "launch: a leaf has no data");
+    s[L.ptr[gi]] = (uint64_t)(uintptr_t)ag.leaf->data;
+    s[L.base[gi]] = (uint64_t)ag.base;
+    for (int k2 = 0; k2 < L.ncoef[gi]; ++k2) s[L.coef[gi] + k2] = (uint64_t)ag.coef[k2];
+  }
+  s[L.out] = (uint64_t)(uintptr_t)out_ptr;
+  for (int k2 = 0; k2 < g.rank; ++k2) s[L.dims + k2] = (uint64_t)g.dims[k2];
+  for (size_t i = 0; i < g.consts.size(); ++i) {
+    const ConstSlot& cs = g.consts[i];
+    if (cs.dtype == GR_F32) { float f = (float)cs.value; uint32_t u; std::memcpy(&u, &f, 4); s[L.consts + i] = u; }
+    else if (cs.dtype == GR_I32) s[L.consts + i] = (uint32_t)(int32_t)(int64_t)cs.value;
+    else s[L.consts + i] = (uint64_t)(int64_t)cs.value;
+  }
+  int64_t total = 1;
+  for (int k2 = 0; k2 < g.rank; ++k2) total *= g.dims[k2];
+  switch (g.kind) {
+    case GroupKind::MAP: {
+      if (total == 0) return GR_OK;
+      int64_t C = g.dims[g.rank - 1], R = g.rank >= 2 ? g.dims[g.rank - 2] : 1, outer = 1;
+      for (int k2 = 0; k2 + 2 < g.rank; ++k2) outer *= g.dims[k2];
+      int64_t TC = (int64_t)g.BX * 4 * g.UC, TR = (int64_t)g.BY * g.VR;
+      int64_t ntiles = outer * ((C + TC - 1) / TC) * ((R + TR - 1) / TR);
+      int64_t grid = g.xcd_remap ? 8 * ((ntiles + 7) / 8) : ntiles;
+      return launch(c, k->fn, k->name, grid, s);
+    }
+    case GroupKind::ROWRED: {
+      int64_t rows = 1;
+      for (int k2 = 0; k2 + 1 < g.rank; ++k2) rows *= g.dims[k2];
+      if (rows == 0) return GR_OK;
+      int rb = 256 / g.row_threads;
+      return launch(c, k->fn, k->name, (rows + rb - 1) / rb, s);
+    }
+    case GroupKind::REDUCE: {
+      if (g.red_out == 0) return GR_OK;
+      s[L.extra] = (uint64_t)g.red_out;
+      s[L.extra + 1] = (uint64_t)g.red_len;
+      return launch(c, k->fn, k->name, g.red_mode == 0 ? (g.red_out + 255) / 256 : g.red_out, s);
+    }
+    case GroupKind::GEMV: {
+      if (g.M == 0) return GR_OK;
+      s[L.extra] = (uint64_t)g.M;
+      s[L.extra + 1] = (uint64_t)g.K;
+      if (g.gemv_mode == 0) {
+        int rpb = 256 / g.LPR;
+        int64_t grid = std::min<int64_t>((g.M + rpb - 1) / rpb, 256 * 16);
+        return launch(c, k->fn, k->name, grid, s);
+      }
+      size_t need = (size_t)g.slabs * (size_t)g.M * sizeof(float);
+      if (need > c->workspace_bytes) {
+        if (c->workspace) ctx_free(c, c->workspace, c->workspace_bytes);
+        c->workspace = ctx_alloc(c, need);
+        c->workspace_bytes = c->workspace ? need : 0;
+        if (!c->workspace) return fail(c, GR_ERR_OOM, "workspace allocation failed");
+      }
+      s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+      s[L.extra + 3] = (uint64_t)g.slabs;
+      int64_t ncb = (g.M + (int64_t)g.BX * 4 - 1) / ((int64_t)g.BX * 4);
+      gr_status st = launch(c, k->fn, k->name, ncb * g.slabs, s);
+      if (st != GR_OK) return st;
+      return launch(c, k->fn2, k->name + "_combine", (g.M + 15) / 16, s);
+    }
+  }
+  return GR_OK;
+}
+
+// Address range [lo, hi) touched by a strided array.
+static void extent_of(const Node* n, uintptr_t* lo, uintptr_t* hi) {
+  int64_t mn = n->offset, mx = n->offset;
+  for (int d = 0; d < n->ndim; ++d) {
+    if (n->shape[d] == 0) { *lo = *hi = 0; return; }
+    int64_t span = (n->shape[d] - 1) * n->strides[d];
+    if (span < 0) mn += span; else mx += span;
+  }
+  *lo = (uintptr_t)n->data + mn * itemsize(n->dtype);
+  *hi = (uintptr_t)n->data + (mx + 1) * itemsize(n->dtype);
+}
+
+gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out) {
+  if (c->device < 0) return fail(c, GR_ERR_NODEVICE, "context has no device");
+  if (user_out) {
+    uintptr_t olo = (uintptr_t)user_out, ohi = olo + root->count() * itemsize(root->dtype);
+    for (const auto& g : plan->groups)
+      for (const Node* l : g->leaves) {
+        if (!l->materialized) continue;
+        uintptr_t lo, hi;
+        extent_of(l, &lo, &hi);
+        if (lo < ohi && olo < hi) return fail(c, GR_ERR_ALIAS, "output buffer overlaps an input of the request");
+      }
+  }
+  c->stats.materialize_calls++;
+  for (auto& gp : plan->groups) {
+    GroupPlan& g = *gp;
+    gr_ctx::Kernel* k = nullptr;
+    gr_status st = compile_group(c, g, &k);
+    if (st != GR_OK) return st;
+    Node* r = g.root;
+    void* out = nullptr;
+    size_t bytes = (size_t)r->count() * itemsize(r->dtype);
+    bool own = false;
+    if (r == root && user_out) out = user_out;
+    else {
+      out = ctx_alloc(c, bytes);
+      if (!out) return fail(c, GR_ERR_OOM, "allocator returned NULL");
+      own = true;
+    }
+    st = launch_group(c, g, k, out);
+    if (st != GR_OK) { if (own) ctx_free(c, out, bytes); return st; }
+    c->stats.groups_executed++;
+    if (r->materialized) continue;  // a plain copy of an array that already had data
+    // the node now has data and stays materialised; its predecessors are no longer needed
+    r->data = out;
+    r->owns_data = own;
+    r->alloc_bytes = own ? bytes : 0;
+    r->offset = 0;
+    int64_t sstride = 1;
+    for (int d = r->ndim - 1; d >= 0; --d) { r->strides[d] = sstride; sstride *= r->shape[d]; }
+    r->materialized = true;
+    r->planned = false;
+  }
+  for (auto& gp : plan->groups) drop_inputs(c, gp->root);
+  return GR_OK;
+}
+
+}  // namespace gr
+
+using namespace gr;
+
+extern "C" {
+
+gr_status gr_ctx_create(gr_ctx** out, int device, void* hip_stream) {
+  if (!out) return GR_ERR_ARG;
+  gr_ctx* c = new gr_ctx();
+  c->device = device;
+  c->stream = (hipStream_t)hip_stream;
+  if (device >= 0) {
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess || device >= n) {
+      delete c;
+      return fail(nullptr, GR_ERR_NODEVICE, "no such HIP device");
+    }
+    e = hipSetDevice(device);
+    if (e != hipSuccess) { delete c; return fail(nullptr, GR_ERR_HIP, "hipSetDevice: " + hip_err(e)); }
+  }
+  *out = c;
+  return GR_OK;
+}
+
+gr_status gr_sync(gr_ctx* ctx) {
+  if (!ctx) return GR_ERR_ARG;
+  if (ctx->device < 0) return GR_OK;
+  GR_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return GR_OK;
+}
+
+gr_status gr_ctx_destroy(gr_ctx* ctx) {
+  if (!ctx) return GR_ERR_ARG;
+  if (ctx->device >= 0) (void)hipStreamSynchronize(ctx->stream);
+  std::vector<Node*> all;
+  for (auto& kv : ctx->nodes) all.push_back(kv.second);
+  for (Node* n : all) {
+    if (n->owns_data && n->data) ctx_free(ctx, n->data, n->alloc_bytes);
+    delete n;
+  }
+  ctx->nodes.clear();
+  if (ctx->workspace) ctx_free(ctx, ctx->workspace, ctx->workspace_bytes);
+  for (auto& kv : ctx->cache) if (kv.second.module) (void)hipModuleUnload(kv.second.module);
+  for (auto& p : ctx->prof) { (void)hipEventDestroy(p.e0); (void)hipEventDestroy(p.e1); }
+  for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
+  for (void* p : ctx->pool_all) (void)hipFree(p);
+  delete ctx;
+  return GR_OK;
+}
+
+gr_status gr_ctx_set_stream(gr_ctx* ctx, void* hip_stream) {
+  if (!ctx) return GR_ERR_ARG;
+  ctx->stream = (hipStream_t)hip_stream;
+  return GR_OK;
+}
+
+static bool resolves_to_data(const Node* n) {
+  while (!n->materialized) {
+    if (!n->is_view()) return false;
+    n = n->in[0];
+  }
+  return true;
+}
+
+gr_status gr_materialize(gr_ctx* ctx, gr_array a) {
+  if (!ctx) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "materialize: bad handle");
+  if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "materialize: a bare scalar has no array value");
+  if (resolves_to_data(x)) return GR_OK;
+  if (ctx->device < 0) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
+  Plan plan;
+  gr_status st = make_plan(ctx, x, &plan);
+  if (st != GR_OK) return st;
+  st = execute_plan(ctx, &plan, x, nullptr);
+  clear_planned(&plan);
+  return st;
+}
+
+gr_status gr_materialize_into(gr_ctx* ctx, gr_array a, void* dptr, size_t bytes) {
+  if (!ctx) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "materialize_into: bad handle");
+  if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "materialize_into: a bare scalar has no array value");
+  size_t need = (size_t)x->count() * itemsize(x->dtype);
+  if (bytes != need) return fail(ctx, GR_ERR_ARG, "materialize_into: buffer size does not match the array");
+  if (need > 0 && !dptr) return fail(ctx, GR_ERR_ARG, "materialize_into: NULL buffer");
+  if (((uintptr_t)dptr) % itemsize(x->dtype)) return fail(ctx, GR_ERR_ARG, "materialize_into: buffer not aligned to the element size");
+  if (ctx->device < 0) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
+  Plan plan;
+  gr_status st = make_plan(ctx, x, &plan);
+  if (st != GR_OK) return st;
+  st = execute_plan(ctx, &plan, x, dptr);
+  clear_planned(&plan);
+  return st;
+}
+
+static gr_status copy_out(const std::string& s, char* buf, size_t cap, size_t* needed) {
+  if (needed) *needed = s.size() + 1;
+  if (buf && cap) {
+    size_t n = std::min(cap - 1, s.size());
+    std::memcpy(buf, s.data(), n);
+    buf[n] = '\0';
+  }
+  return GR_OK;
+}
+
+gr_status gr_plan_describe(gr_ctx* ctx, gr_array a, char* buf, size_t cap, size_t* needed) {
+  if (!ctx) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "plan_describe: bad handle");
+  Plan plan;
+  gr_status st = make_plan(ctx, x, &plan);
+  if (st != GR_OK) return st;
+  std::string s = describe_plan(plan);
+  clear_planned(&plan);
+  return copy_out(s, buf, cap, needed);
+}
+
+gr_status gr_plan_source(gr_ctx* ctx, gr_array a, int index, char* buf, size_t cap, size_t* needed) {
+  if (!ctx) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "plan_source: bad handle");
+  Plan plan;
+  gr_status st = make_plan(ctx, x, &plan);
+  if (st != GR_OK) return st;
+  if (index < 0 || index >= (int)plan.groups.size()) { clear_planned(&plan); return fail(ctx, GR_ERR_ARG, "plan_source: no such sub-graph"); }
+  std::string s = generate_source(*plan.groups[index]);
+  clear_planned(&plan);
+  return copy_out(s, buf, cap, needed);
+}
+
+gr_status gr_plan_compile(gr_ctx* ctx, gr_array a) {
+  if (!ctx) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "plan_compile: bad handle");
+  Plan plan;
+  gr_status st = make_plan(ctx, x, &plan);
+  if (st != GR_OK) return st;
+  for (auto& g : plan.groups) {
+    gr_ctx::Kernel* k = nullptr;
+    st = compile_group(ctx, *g, &k);
+    if (st != GR_OK) break;
+  }
+  clear_planned(&plan);
+  return st;
+}
+
+gr_status gr_profile_reset(gr_ctx* ctx) {
+  if (!ctx) return GR_ERR_ARG;
+  if (ctx->device >= 0 && !ctx->prof.empty()) GR_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  for (auto& p : ctx->prof) { ctx->event_pool.push_back(p.e0); ctx->event_pool.push_back(p.e1); }
+  ctx->prof.clear();
+  return GR_OK;
+}
+
+gr_status gr_profile_read(gr_ctx* ctx, const char* prefix, uint64_t* launches, double* total_ms) {
+  if (!ctx || !launches || !total_ms) return GR_ERR_ARG;
+  std::string pre(prefix ? prefix : "");
+  *launches = 0;
+  *total_ms = 0.0;
+  if (ctx->device >= 0) GR_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  for (auto& p : ctx->prof) {
+    if (p.name.compare(0, pre.size(), pre) != 0) continue;
+    float ms = 0.f;
+    GR_HIP(ctx, hipEventElapsedTime(&ms, p.e0, p.e1));
+    *launches += 1;
+    *total_ms += ms;
+  }
+  return GR_OK;
+}
+
+gr_status gr_stream_copy(gr_ctx* ctx, void* dst, const void* src, size_t bytes) {
+  if (!ctx || !dst || !src) return GR_ERR_ARG;
+  if (ctx->device < 0) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
+  if (bytes % 16 || ((uintptr_t)dst % 16) || ((uintptr_t)src % 16)) return fail(ctx, GR_ERR_ARG, "stream_copy: size and pointers must be multiples of 16");
+  uintptr_t d = (uintptr_t)dst, s = (uintptr_t)src;
+  if (d < s + bytes && s < d + bytes) return fail(ctx, GR_ERR_ALIAS, "stream_copy: buffers overlap");
+  if (bytes == 0) return GR_OK;
+  gr_launch_stream_copy(ctx->stream, dst, src, bytes / 16);
+  GR_HIP(ctx, hipGetLastError());
+  return GR_OK;
+}
+
+gr_status gr_stream_read(gr_ctx* ctx, const void* src, size_t bytes, void* sink) {
+  if (!ctx || !src || !sink) return GR_ERR_ARG;
+  if (ctx->device < 0) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
+  if (bytes % 16 || ((uintptr_t)src % 16) || ((uintptr_t)sink % 4)) return fail(ctx, GR_ERR_ARG, "stream_read: size and pointer must be multiples of 16");
+  if (bytes == 0) return GR_OK;
+  gr_launch_stream_read(ctx->stream, src, bytes / 16, sink);
+  GR_HIP(ctx, hipGetLastError());
+  return GR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,421 @@
+"""Thin ctypes binding over the C-ABI library (include/grumpy_hip.h).
+
+Argument marshalling only: every step of the path (recording, shape and
+broadcast inference, partitioning, code generation, kernels) runs inside
+libgrumpy_hip.so.  PyTorch is used for device memory and the stream.  There is
+no CPU fallback: if the library is missing, loading fails.
+
+``Array`` mirrors the part of ``numpy.ndarray`` the paper's programs use
+(Section 4.1: an ndarray object that stands for one DAG node), and the module
+exposes NumPy-named functions so that a program written against ``numpy`` runs
+unchanged with this module passed in its place.
+"""
+from __future__ import annotations
+
+import builtins
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.environ.get("GRUMPY_HIP_LIB", os.path.join(_HERE, "libgrumpy_hip.so"))
+
+GR_F32, GR_I32, GR_I64 = 0, 1, 2
+_UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "square": 5, "tanh": 6}
+_BINARY = {"add": 16, "sub": 17, "mul": 18, "div": 19, "maximum": 20, "minimum": 21}
+_REDUCE = {"sum": 32, "max": 33, "min": 34}
+STATUS = {0: "GR_OK", 1: "GR_ERR_HANDLE", 2: "GR_ERR_SHAPE", 3: "GR_ERR_DTYPE", 4: "GR_ERR_AXIS",
+          5: "GR_ERR_UNSUPPORTED", 6: "GR_ERR_ARG", 7: "GR_ERR_COMPILE", 8: "GR_ERR_HIP", 9: "GR_ERR_OOM",
+          10: "GR_ERR_ALIAS", 11: "GR_ERR_NODEVICE"}
+
+# every symbol include/grumpy_hip.h declares
+SYMBOLS = [
+    "gr_ctx_create", "gr_ctx_destroy", "gr_ctx_set_stream", "gr_ctx_set_allocator", "gr_ctx_set_option", "gr_sync",
+    "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_slice", "gr_transpose",
+    "gr_reduce", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_ndim", "gr_shape", "gr_dtype_of",
+    "gr_is_materialized", "gr_data_ptr", "gr_retain", "gr_release", "gr_plan_describe", "gr_plan_source",
+    "gr_plan_compile", "gr_stats", "gr_profile_reset", "gr_profile_read", "gr_stream_copy", "gr_stream_read",
+]
+
+
+class GrError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{STATUS.get(status, status)}: {msg}")
+        self.status = status
+        self.code = STATUS.get(status, str(status))
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [("nodes_recorded", ctypes.c_uint64), ("nodes_alive", ctypes.c_uint64),
+                ("materialize_calls", ctypes.c_uint64), ("groups_executed", ctypes.c_uint64),
+                ("kernel_launches", ctypes.c_uint64), ("cache_hits", ctypes.c_uint64),
+                ("cache_misses", ctypes.c_uint64), ("compile_ms", ctypes.c_double),
+                ("bytes_allocated", ctypes.c_uint64)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libgrumpy_hip.so (built in-tree by build.py); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no CPU fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    P, I, I64, U64, SZ = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64, ctypes.c_size_t
+    PP = ctypes.POINTER
+    sig = {
+        "gr_ctx_create": [PP(P), I, P], "gr_ctx_destroy": [P], "gr_ctx_set_stream": [P, P],
+        "gr_ctx_set_allocator": [P, P, P, P], "gr_ctx_set_option": [P, ctypes.c_char_p, I64], "gr_sync": [P],
+        "gr_array_from_device": [P, P, I, I, PP(I64), PP(I64), PP(U64)],
+        "gr_scalar": [P, ctypes.c_double, I, PP(U64)],
+        "gr_unary": [P, I, U64, PP(U64)], "gr_binary": [P, I, U64, U64, PP(U64)],
+        "gr_slice": [P, U64, I, PP(I64), PP(I64), PP(I64), PP(ctypes.c_uint8), PP(ctypes.c_uint8), PP(U64)],
+        "gr_transpose": [P, U64, PP(I), PP(U64)],
+        "gr_reduce": [P, I, U64, PP(I), I, I, PP(U64)], "gr_dot": [P, U64, U64, PP(U64)],
+        "gr_materialize": [P, U64], "gr_materialize_into": [P, U64, P, SZ],
+        "gr_ndim": [P, U64, PP(I)], "gr_shape": [P, U64, PP(I64)], "gr_dtype_of": [P, U64, PP(I)],
+        "gr_is_materialized": [P, U64, PP(I)], "gr_data_ptr": [P, U64, PP(P), PP(I64)],
+        "gr_retain": [P, U64], "gr_release": [P, U64],
+        "gr_plan_describe": [P, U64, ctypes.c_char_p, SZ, PP(SZ)],
+        "gr_plan_source": [P, U64, I, ctypes.c_char_p, SZ, PP(SZ)], "gr_plan_compile": [P, U64],
+        "gr_stats": [P, PP(Stats)], "gr_profile_reset": [P],
+        "gr_profile_read": [P, ctypes.c_char_p, PP(U64), PP(ctypes.c_double)],
+        "gr_stream_copy": [P, P, P, SZ], "gr_stream_read": [P, P, SZ, P],
+    }
+    for name, argtypes in sig.items():
+        fn = getattr(L, name)
+        fn.argtypes = argtypes
+        fn.restype = I
+    L.gr_last_error.argtypes = [P]
+    L.gr_last_error.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _torch():
+    import torch
+    return torch
+
+
+class Context:
+    """One gr_ctx.  device=-1 records, plans and generates code without a GPU."""
+
+    def __init__(self, device: Optional[int] = None, stream: Optional[int] = None):
+        L = lib()
+        if device is None:
+            torch = _torch()
+            if not torch.cuda.is_available():
+                raise RuntimeError("no GPU visible; pass device=-1 for a device-less context")
+            device = torch.cuda.current_device()
+        if stream is None and device >= 0:
+            torch = _torch()
+            if torch.cuda.is_available() and device < torch.cuda.device_count():
+                stream = torch.cuda.current_stream(device).cuda_stream
+        self._p = ctypes.c_void_p()
+        st = L.gr_ctx_create(ctypes.byref(self._p), int(device), ctypes.c_void_p(stream or 0))
+        if st:
+            raise GrError(st, L.gr_last_error(None).decode())
+        self.device = int(device)
+        self._keep = {}  # node id -> object that owns the device memory of a leaf
+
+    def close(self):
+        if self._p:
+            lib().gr_ctx_destroy(self._p)
+            self._p = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def check(self, st: int):
+        if st:
+            raise GrError(st, lib().gr_last_error(self._p).decode())
+
+    def set_option(self, key: str, value: int):
+        self.check(lib().gr_ctx_set_option(self._p, key.encode(), int(value)))
+
+    def set_stream(self, stream: int):
+        self.check(lib().gr_ctx_set_stream(self._p, ctypes.c_void_p(stream)))
+
+    def sync(self):
+        self.check(lib().gr_sync(self._p))
+
+    def stats(self) -> dict:
+        s = Stats()
+        self.check(lib().gr_stats(self._p, ctypes.byref(s)))
+        return {k: getattr(s, k) for k, _ in Stats._fields_}
+
+    def profile_reset(self):
+        self.check(lib().gr_profile_reset(self._p))
+
+    def profile_read(self, prefix: str = ""):
+        n, ms = ctypes.c_uint64(), ctypes.c_double()
+        self.check(lib().gr_profile_read(self._p, prefix.encode(), ctypes.byref(n), ctypes.byref(ms)))
+        return int(n.value), float(ms.value)
+
+    # -- leaves ---------------------------------------------------------------
+    def from_device(self, ptr: int, dtype: int, shape: Sequence[int], strides: Optional[Sequence[int]] = None,
+                    owner=None) -> "Array":
+        n = len(shape)
+        shp = (ctypes.c_int64 * builtins.max(n, 1))(*shape)
+        st = None if strides is None else (ctypes.c_int64 * builtins.max(n, 1))(*strides)
+        h = ctypes.c_uint64()
+        self.check(lib().gr_array_from_device(self._p, ctypes.c_void_p(ptr), dtype, n, shp, st, ctypes.byref(h)))
+        a = Array(self, h.value)
+        if owner is not None:
+            self._keep[h.value] = owner
+        return a
+
+    def array(self, t) -> "Array":
+        """Wraps a torch tensor that lives on this context's GPU (borrowed, any strides)."""
+        torch = _torch()
+        if not isinstance(t, torch.Tensor):
+            raise TypeError("expected a torch.Tensor on the GPU")
+        if not t.is_cuda:
+            raise ValueError("tensor must live in device memory")
+        dt = {torch.float32: GR_F32, torch.int32: GR_I32, torch.int64: GR_I64}.get(t.dtype)
+        if dt is None:
+            raise GrError(3, f"unsupported dtype {t.dtype}")
+        return self.from_device(t.data_ptr(), dt, tuple(t.shape), tuple(t.stride()), owner=t)
+
+    def spec(self, shape: Sequence[int], dtype: int = GR_F32, strides: Optional[Sequence[int]] = None) -> "Array":
+        """A leaf with a placeholder address, for planning on a device-less context."""
+        return self.from_device(0x10000, dtype, tuple(shape), strides)
+
+    def scalar(self, v) -> "Array":
+        h = ctypes.c_uint64()
+        if isinstance(v, bool):
+            raise GrError(5, "bool scalars are not supported")
+        is_int = isinstance(v, int) or type(v).__name__.startswith(("int", "uint"))
+        self.check(lib().gr_scalar(self._p, float(v), int(is_int), ctypes.byref(h)))
+        return Array(self, h.value)
+
+    # -- streaming ceiling kernels ----------------------------------------------
+    def stream_copy(self, dst, src):
+        self.check(lib().gr_stream_copy(self._p, ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()),
+                                        src.numel() * src.element_size()))
+
+    def stream_read(self, src, sink):
+        self.check(lib().gr_stream_read(self._p, ctypes.c_void_p(src.data_ptr()), src.numel() * src.element_size(),
+                                        ctypes.c_void_p(sink.data_ptr())))
+
+
+class Array:
+    """Handle of one DAG node."""
+
+    __array_priority__ = 1000
+
+    def __init__(self, ctx: Context, handle: int):
+        self.ctx = ctx
+        self.h = handle
+
+    def __del__(self):
+        try:
+            if self.ctx._p:
+                lib().gr_release(self.ctx._p, ctypes.c_uint64(self.h))
+                self.ctx._keep.pop(self.h, None)
+        except Exception:
+            pass
+
+    # -- inspection -----------------------------------------------------------
+    @property
+    def ndim(self) -> int:
+        n = ctypes.c_int()
+        self.ctx.check(lib().gr_ndim(self.ctx._p, self.h, ctypes.byref(n)))
+        return n.value
+
+    @property
+    def shape(self):
+        n = self.ndim
+        s = (ctypes.c_int64 * builtins.max(n, 1))()
+        self.ctx.check(lib().gr_shape(self.ctx._p, self.h, s))
+        return tuple(int(s[i]) for i in range(n))
+
+    @property
+    def dtype_code(self) -> int:
+        d = ctypes.c_int()
+        self.ctx.check(lib().gr_dtype_of(self.ctx._p, self.h, ctypes.byref(d)))
+        return d.value
+
+    @property
+    def is_materialized(self) -> bool:
+        f = ctypes.c_int()
+        self.ctx.check(lib().gr_is_materialized(self.ctx._p, self.h, ctypes.byref(f)))
+        return bool(f.value)
+
+    def data_ptr(self):
+        p = ctypes.c_void_p()
+        st = (ctypes.c_int64 * 8)()
+        self.ctx.check(lib().gr_data_ptr(self.ctx._p, self.h, ctypes.byref(p), st))
+        return p.value or 0, tuple(int(st[i]) for i in range(self.ndim))
+
+    # -- materialisation --------------------------------------------------------
+    def materialize(self) -> "Array":
+        self.ctx.check(lib().gr_materialize(self.ctx._p, self.h))
+        return self
+
+    def materialize_into(self, t) -> "Array":
+        self.ctx.check(lib().gr_materialize_into(self.ctx._p, self.h, ctypes.c_void_p(t.data_ptr()),
+                                                 t.numel() * t.element_size()))
+        return self
+
+    def torch(self):
+        """Evaluates the node into a fresh torch tensor on the context's device."""
+        torch = _torch()
+        dt = {GR_F32: torch.float32, GR_I32: torch.int32, GR_I64: torch.int64}[self.dtype_code]
+        out = torch.empty(self.shape, dtype=dt, device=f"cuda:{self.ctx.device}")
+        self.materialize_into(out)
+        return out
+
+    def numpy(self):
+        return self.torch().cpu().numpy()
+
+    def plan(self) -> str:
+        need = ctypes.c_size_t()
+        self.ctx.check(lib().gr_plan_describe(self.ctx._p, self.h, None, 0, ctypes.byref(need)))
+        buf = ctypes.create_string_buffer(need.value)
+        self.ctx.check(lib().gr_plan_describe(self.ctx._p, self.h, buf, need.value, ctypes.byref(need)))
+        return buf.value.decode()
+
+    def source(self, index: int = 0) -> str:
+        need = ctypes.c_size_t()
+        self.ctx.check(lib().gr_plan_source(self.ctx._p, self.h, index, None, 0, ctypes.byref(need)))
+        buf = ctypes.create_string_buffer(need.value)
+        self.ctx.check(lib().gr_plan_source(self.ctx._p, self.h, index, buf, need.value, ctypes.byref(need)))
+        return buf.value.decode()
+
+    def compile(self) -> "Array":
+        self.ctx.check(lib().gr_plan_compile(self.ctx._p, self.h))
+        return self
+
+    # -- operators ----------------------------------------------------------------
+    def __add__(self, o): return binary("add", self, o)
+    def __radd__(self, o): return binary("add", o, self)
+    def __sub__(self, o): return binary("sub", self, o)
+    def __rsub__(self, o): return binary("sub", o, self)
+    def __mul__(self, o): return binary("mul", self, o)
+    def __rmul__(self, o): return binary("mul", o, self)
+    def __truediv__(self, o): return binary("div", self, o)
+    def __rtruediv__(self, o): return binary("div", o, self)
+    def __neg__(self): return unary("neg", self)
+    def __abs__(self): return unary("abs", self)
+    def __matmul__(self, o): return dot(self, o)
+
+    def __pow__(self, e):
+        if isinstance(e, int) and e == 2:
+            return unary("square", self)  # NumPy evaluates x**2 as square(x)
+        raise GrError(5, "only **2 is supported")
+
+    def __getitem__(self, key):
+        return slice_(self, key)
+
+    @property
+    def T(self):
+        return transpose(self)
+
+    def sum(self, axis=None, keepdims=False): return reduce("sum", self, axis, keepdims)
+    def max(self, axis=None, keepdims=False): return reduce("max", self, axis, keepdims)
+    def min(self, axis=None, keepdims=False): return reduce("min", self, axis, keepdims)
+    def dot(self, o): return dot(self, o)
+
+
+def _ctx_of(*xs) -> Context:
+    for x in xs:
+        if isinstance(x, Array):
+            return x.ctx
+    raise TypeError("no array operand")
+
+
+def _operand(ctx: Context, x) -> Array:
+    if isinstance(x, Array):
+        if x.ctx is not ctx:
+            raise ValueError("arrays belong to different contexts")
+        return x
+    return ctx.scalar(x)
+
+
+def unary(name: str, a) -> Array:
+    ctx = _ctx_of(a)
+    h = ctypes.c_uint64()
+    ctx.check(lib().gr_unary(ctx._p, _UNARY[name], a.h, ctypes.byref(h)))
+    return Array(ctx, h.value)
+
+
+def binary(name: str, a, b) -> Array:
+    ctx = _ctx_of(a, b)
+    a, b = _operand(ctx, a), _operand(ctx, b)
+    h = ctypes.c_uint64()
+    ctx.check(lib().gr_binary(ctx._p, _BINARY[name], a.h, b.h, ctypes.byref(h)))
+    return Array(ctx, h.value)
+
+
+def slice_(a: Array, key) -> Array:
+    if not isinstance(key, tuple):
+        key = (key,)
+    n = len(key)
+    I64, U8 = ctypes.c_int64 * builtins.max(n, 1), ctypes.c_uint8 * builtins.max(n, 1)
+    start, stop, step, hs, he = I64(), I64(), I64(), U8(), U8()
+    for d, k in enumerate(key):
+        if not isinstance(k, slice):
+            raise GrError(5, "only slice objects are supported as indices")
+        step[d] = 1 if k.step is None else int(k.step)
+        hs[d] = k.start is not None
+        he[d] = k.stop is not None
+        start[d] = 0 if k.start is None else int(k.start)
+        stop[d] = 0 if k.stop is None else int(k.stop)
+    h = ctypes.c_uint64()
+    a.ctx.check(lib().gr_slice(a.ctx._p, a.h, n, start, stop, step, hs, he, ctypes.byref(h)))
+    return Array(a.ctx, h.value)
+
+
+def transpose(a: Array, axes: Optional[Sequence[int]] = None) -> Array:
+    p = None if axes is None else (ctypes.c_int * len(axes))(*axes)
+    h = ctypes.c_uint64()
+    a.ctx.check(lib().gr_transpose(a.ctx._p, a.h, p, ctypes.byref(h)))
+    return Array(a.ctx, h.value)
+
+
+def reduce(name: str, a: Array, axis=None, keepdims=False) -> Array:
+    if axis is None:
+        axes = []
+    elif isinstance(axis, int):
+        axes = [axis]
+    else:
+        axes = list(axis)
+        if not axes:
+            raise GrError(4, "empty axis tuple")
+    arr = (ctypes.c_int * builtins.max(len(axes), 1))(*axes)
+    h = ctypes.c_uint64()
+    a.ctx.check(lib().gr_reduce(a.ctx._p, _REDUCE[name], a.h, arr, len(axes), int(bool(keepdims)), ctypes.byref(h)))
+    return Array(a.ctx, h.value)
+
+
+def dot(a: Array, b: Array) -> Array:
+    h = ctypes.c_uint64()
+    a.ctx.check(lib().gr_dot(a.ctx._p, a.h, b.h, ctypes.byref(h)))
+    return Array(a.ctx, h.value)
+
+
+# NumPy-named functions
+def add(a, b): return binary("add", a, b)
+def subtract(a, b): return binary("sub", a, b)
+def multiply(a, b): return binary("mul", a, b)
+def divide(a, b): return binary("div", a, b)
+def maximum(a, b): return binary("maximum", a, b)
+def minimum(a, b): return binary("minimum", a, b)
+def negative(a): return unary("neg", a)
+def absolute(a): return unary("abs", a)
+def exp(a): return unary("exp", a)
+def log(a): return unary("log", a)
+def sqrt(a): return unary("sqrt", a)
+def square(a): return unary("square", a)
+def tanh(a): return unary("tanh", a)
+def sum(a, axis=None, keepdims=False): return reduce("sum", a, axis, keepdims)  # noqa: A001
+def max(a, axis=None, keepdims=False): return reduce("max", a, axis, keepdims)  # noqa: A001
+def min(a, axis=None, keepdims=False): return reduce("min", a, axis, keepdims)  # noqa: A001

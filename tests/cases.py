@@ -1,0 +1,58 @@
+"""Program tables shared by the GPU parity tests and the host-side planning
+tests: NumPy-style programs over an array module xp, with their inputs."""
+import numpy as np
+
+from paper_1901_03771_amd import workloads as wl
+
+f32 = np.float32
+
+
+def _rand(shape, seed, scale=1.0):
+    return (np.random.default_rng(seed).standard_normal(shape) * scale).astype(f32)
+
+
+ELEMENTWISE_CASES = {
+    "unary_mix": (lambda xp, a: xp.sqrt(abs(a)) + xp.tanh(a) - xp.log(abs(a) + 1.0) + xp.exp(-abs(a)) + (-a) ** 2,
+                  lambda: dict(a=_rand((37, 129), 1))),
+    "bcast_col": (lambda xp, a, b: a * b - b, lambda: dict(a=_rand((45, 33), 2), b=_rand((45, 1), 3))),
+    "bcast_row_col": (lambda xp, a, b: xp.maximum(a, b) + xp.minimum(a, b), lambda: dict(a=_rand((1, 257), 4), b=_rand((19, 1), 5))),
+    "bcast_3d": (lambda xp, a, b, c: (a + b) / (abs(c) + 1.0), lambda: dict(a=_rand((3, 1, 65), 6), b=_rand((5, 1), 7), c=_rand((3, 5, 65), 8))),
+    "scalar_ops": (lambda xp, a: (2.0 - a) / 3.0 + 0.5 * a - 1, lambda: dict(a=_rand((1000,), 9))),
+    "transpose_add": (lambda xp, a, b: a.T + b, lambda: dict(a=_rand((40, 70), 10), b=_rand((70, 40), 11))),
+    "transpose_3d": (lambda xp, a, b: xp.transpose(a, (2, 0, 1)) * b, lambda: dict(a=_rand((4, 5, 6), 12), b=_rand((6, 4, 5), 13))),
+    "slice_step": (lambda xp, a: a[1::2, ::3] - a[:-1:2, 1::3], lambda: dict(a=_rand((40, 60), 14))),
+    "slice_shift_rows": (lambda xp, a: a[1:] - a[:-1], lambda: dict(a=_rand((50, 64), 15))),
+    "slice_of_lazy": (lambda xp, a, b: ((a + b)[2:-3, 5:] * 2.0)[::2], lambda: dict(a=_rand((31, 47), 16), b=_rand((31, 47), 17))),
+    "jacobi": (lambda xp, grid: wl.jacobi_sweep(xp, grid), lambda: dict(grid=_rand((67, 300), 18))),
+    "diamond": (lambda xp, a: (lambda t: t * t + t)(a + 1.0), lambda: dict(a=_rand((513,), 19))),
+    "nan_inf": (lambda xp, a, b: xp.maximum(a, b) / b,
+                lambda: dict(a=np.array([1, np.nan, 3, -np.inf, 0, 5], f32), b=np.array([2, 1, np.nan, 1, 0, np.inf], f32))),
+    "outer": (lambda xp, a, b: a * b, lambda: dict(a=_rand((300, 1), 20), b=_rand((1, 500), 21))),
+}
+
+
+
+REDUCTION_CASES = [((37, 211), 1, True), ((37, 211), 1, False), ((37, 211), 0, False), ((37, 211), None, False),
+                   ((6, 7, 50), (0, 2), True), ((6, 7, 50), 1, False), ((5, 70000), 1, False),
+                   ((20000, 3), 0, False), ((4, 5, 6), (1, 2), False), ((1, 1), None, True)]
+
+ROWRED_PROGRAMS = [
+    lambda xp, a: (a - xp.max(a, axis=1, keepdims=True)) / (xp.sum(abs(a), axis=1, keepdims=True) + 1.0),
+    lambda xp, a: 1.0 / xp.sum(a * a, axis=1, keepdims=True),
+    lambda xp, a: xp.sum(xp.exp(a - xp.max(a, axis=1, keepdims=True)), axis=1),
+    lambda xp, a: a[:, 1:] / (xp.sum(abs(a[:, 1:] - a[:, :-1]), axis=1, keepdims=True) + 1.0),
+    lambda xp, a: xp.max(a, axis=1) - xp.min(a, axis=1),
+    lambda xp, a: a - xp.max(a, axis=1),            # (50,50): the row maxima broadcast along rows, not row-resident
+    lambda xp, a: xp.sum(a, axis=1, keepdims=True) * xp.sum(a, axis=0, keepdims=True),
+]
+
+DOT_CASES = [
+    (lambda xp, A, v, u: A @ v, "row-dot"),
+    (lambda xp, A, v, u: A.T @ u, "column-accumulate"),
+    (lambda xp, A, v, u: xp.dot(v, v), "inner product"),
+    (lambda xp, A, v, u: xp.sum(v * v), "Listing 5 inner product"),
+    (lambda xp, A, v, u: A[::2, 1::2] @ v[1::2], "strided views"),
+    (lambda xp, A, v, u: xp.tanh(A @ (v * 2.0 + 1.0)) + u, "lazy vector operand + epilogue"),
+    (lambda xp, A, v, u: (A @ v) * (A @ v) + u, "dot used twice"),
+    (lambda xp, A, v, u: A.T @ (A @ v), "dot feeding dot"),
+]

@@ -1,0 +1,291 @@
+"""Host logic of the library on a device-less context (no GPU needed): the C
+ABI loads and exports every declared symbol, shapes and element types are
+inferred with NumPy semantics, errors are reported at record time, the
+partitioner produces the sub-graph lists the paper describes, and every
+program used by the GPU parity tests generates HIP source that hipRTC
+compiles for gfx950."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from cases import DOT_CASES, ELEMENTWISE_CASES, REDUCTION_CASES, ROWRED_PROGRAMS
+from paper_1901_03771_amd import lazy as gr, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture()
+def ctx():
+    c = gr.Context(device=-1)
+    yield c
+    c.close()
+
+
+def groups(arr):
+    """[(kind, [op names]), ...] of the planned sub-graph list."""
+    out = []
+    for line in arr.plan().strip().splitlines():
+        kind = line.split()[1]
+        members = re.search(r"members=\[(.*?)\]", line).group(1)
+        out.append((kind, [m.split(":")[1] for m in members.split(",") if m]))
+    return out
+
+
+# ------------------------------------------------------------------ the boundary --
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "grumpy_hip.h")).read()
+    declared = set(re.findall(r"^(?:gr_status|const char\*)\s+(gr_[a-z_0-9]+)\s*\(", header, flags=re.M))
+    assert len(declared) > 25
+    L = ctypes.CDLL(gr.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(L, name), f"{name} declared in the header but not exported"
+    assert declared == set(gr.SYMBOLS), declared ^ set(gr.SYMBOLS)
+
+
+def test_deviceless_context_refuses_to_execute(ctx):
+    a = ctx.spec((4,))
+    with pytest.raises(gr.GrError) as ei:
+        (a + 1.0).materialize()
+    assert ei.value.code == "GR_ERR_NODEVICE"
+    with pytest.raises(gr.GrError):
+        gr.Context(device=9999)
+
+
+# ------------------------------------------------------- shape / dtype inference --
+@pytest.mark.parametrize("sa,sb,expect", [
+    ((10, 20), (20,), (10, 20)), ((8192, 8192), (1, 8192), (8192, 8192)), ((8192, 8192), (8192,), (8192, 8192)),
+    ((16384, 4096), (16384, 1), (16384, 4096)), ((3, 1), (1, 4), (3, 4)), ((), (5,), (5,)), ((0, 3), (1, 3), (0, 3)),
+    ((2, 1, 4), (3, 1), (2, 3, 4)), ((2, 3), (2,), None), ((4,), (5,), None)])
+def test_broadcast_inference(ctx, sa, sb, expect):
+    a, b = ctx.spec(sa), ctx.spec(sb)
+    if expect is None:
+        with pytest.raises(gr.GrError) as ei:
+            a + b
+        assert ei.value.code == "GR_ERR_SHAPE"
+    else:
+        assert (a + b).shape == expect == np.broadcast_shapes(sa, sb)
+
+
+def test_slice_shapes_match_python(ctx):
+    a = ctx.spec((6, 7))
+    vals = [None, -8, -7, -6, -3, -1, 0, 1, 3, 6, 7, 9]
+    for st in vals:
+        for sp in vals:
+            for step in (None, 1, 2, 3):
+                assert a[st:sp:step, ::2].shape == (len(range(6)[st:sp:step]), 4)
+    assert a[1:3].shape == (2, 7)
+    with pytest.raises(gr.GrError) as ei:
+        a[::-1]
+    assert ei.value.code == "GR_ERR_UNSUPPORTED"
+    with pytest.raises(gr.GrError):
+        a[:, :, :]
+
+
+def test_transpose_reduce_dot_shapes_and_errors(ctx):
+    a = ctx.spec((2, 3, 4))
+    assert a.T.shape == (4, 3, 2)
+    assert gr.transpose(a, (1, 2, 0)).shape == (3, 4, 2)
+    with pytest.raises(gr.GrError) as ei:
+        gr.transpose(a, (0, 0, 1))
+    assert ei.value.code == "GR_ERR_AXIS"
+    assert a.sum(axis=1).shape == (2, 4)
+    assert a.sum(axis=(0, 2), keepdims=True).shape == (1, 3, 1)
+    assert a.max().shape == ()
+    assert a.sum(axis=-1).shape == (2, 3)
+    for bad in (3, -4, (1, 1)):
+        with pytest.raises(gr.GrError) as ei:
+            a.sum(axis=bad)
+        assert ei.value.code == "GR_ERR_AXIS"
+    m, v = ctx.spec((5, 7)), ctx.spec((7,))
+    assert (m @ v).shape == (5,) and (v @ v).shape == () and (m.T @ ctx.spec((5,))).shape == (7,)
+    with pytest.raises(gr.GrError) as ei:
+        m @ ctx.spec((5,))
+    assert ei.value.code == "GR_ERR_SHAPE"
+    with pytest.raises(gr.GrError) as ei:
+        m @ ctx.spec((7, 2))
+    assert ei.value.code == "GR_ERR_UNSUPPORTED"
+
+
+def test_dtype_rules(ctx):
+    f, i = ctx.spec((4,), gr.GR_F32), ctx.spec((4,), gr.GR_I32)
+    assert (i * 2 + i).dtype_code == gr.GR_I32
+    assert (f * 2 + 1).dtype_code == gr.GR_F32
+    assert i.sum().dtype_code == gr.GR_I64 and i.max().dtype_code == gr.GR_I32 and f.sum().dtype_code == gr.GR_F32
+    for bad, code in [(lambda: i * 0.5, "GR_ERR_DTYPE"), (lambda: i + f, "GR_ERR_DTYPE"), (lambda: gr.exp(i), "GR_ERR_DTYPE"),
+                      (lambda: i / i, "GR_ERR_UNSUPPORTED"), (lambda: i.sum() + 1, "GR_ERR_UNSUPPORTED"),
+                      (lambda: i * (2 ** 40), "GR_ERR_DTYPE"), (lambda: f ** 3, "GR_ERR_UNSUPPORTED")]:
+        with pytest.raises(gr.GrError) as ei:
+            bad()
+        assert ei.value.code == code
+
+
+def test_failed_record_leaves_the_dag_unchanged(ctx):
+    a, b = ctx.spec((2, 3)), ctx.spec((2,))
+    before = ctx.stats()["nodes_alive"]
+    with pytest.raises(gr.GrError):
+        a + b
+    assert ctx.stats()["nodes_alive"] == before
+    with pytest.raises(gr.GrError) as ei:
+        gr.Array(ctx, 424242).shape
+    assert ei.value.code == "GR_ERR_HANDLE"
+
+
+def test_nodes_are_freed_with_their_last_reference(ctx):
+    a = ctx.spec((8,))
+    base = ctx.stats()["nodes_alive"]
+    z = gr.exp(a * 2.0 + a) - a
+    assert ctx.stats()["nodes_alive"] > base
+    del z
+    assert ctx.stats()["nodes_alive"] == base
+    # a diamond: the shared node must be freed exactly once
+    t = a + 1.0
+    u = t * t + t
+    del t
+    del u
+    assert ctx.stats()["nodes_alive"] == base
+
+
+# ------------------------------------------------------------------ partitioning --
+def test_five_configurations_partition_as_designed(ctx):
+    c1 = wl.chain(gr, ctx.spec((1 << 20,)), ctx.spec((1 << 20,)))
+    assert groups(c1) == [("MAP", ["add", "sub", "mul", "mul", "add", "abs", "add", "div", "neg", "mul", "exp", "sub"])]
+    c2 = wl.normalize(gr, ctx.spec((8192, 8192)), ctx.spec((1, 8192)), ctx.spec((1, 8192)), ctx.spec((8192,)), ctx.spec((8192,)))
+    assert groups(c2) == [("MAP", ["sub", "div", "mul", "add", "maximum"])]
+    c3 = wl.softmax(gr, ctx.spec((16384, 4096)))
+    assert groups(c3) == [("ROWRED", ["max", "sub", "exp", "sum", "div"])]
+    c4 = wl.stencil(gr, ctx.spec((8192, 8192)))
+    g4 = groups(c4)
+    assert len(g4) == 1 and g4[0][0] == "MAP" and "loads=13" in c4.plan()  # the radius-2 diamond of 13 input points
+    c5 = wl.logreg(gr, ctx.spec((262144, 512)), ctx.spec((512,)), ctx.spec((262144,)))
+    g5 = groups(c5)
+    assert [k for k, _ in g5] == ["GEMV", "GEMV"]
+    assert g5[0][1] == ["dot", "neg", "exp", "add", "div", "sub"]       # X@w with the sigmoid/residual epilogue
+    assert g5[1][1] == ["dot", "div", "mul", "add", "mul", "sub"]       # X.T@r with the update epilogue
+    plan = c5.plan().splitlines()
+    assert "row-dot" in plan[0] and "column-accumulate" in plan[1]
+
+
+def test_jacobi_slices_fuse_into_one_kernel(ctx):
+    # Section 4.2: the stencil is fused into a single kernel even when slicing
+    out = wl.jacobi_sweep(gr, ctx.spec((512, 512)))
+    g = groups(out)
+    assert len(g) == 1 and g[0] == ("MAP", ["add", "add", "add", "add", "mul"])
+    assert "leaves=[1]" in out.plan() and "loads=5" in out.plan()
+
+
+def test_mnist_walkthrough(ctx):
+    # Section 2 on Listing 2: max is computed first, the transposed W is folded into the
+    # contraction, and the pointwise tail reads the contraction's result
+    W, a, b = ctx.spec((200, 10)), ctx.spec((200,)), ctx.spec((10,))
+    out = wl.mnist(gr, W, a, b)
+    g = groups(out)
+    assert g[0] == ("MAP", ["maximum"])
+    assert g[1][0] == "GEMV" and g[1][1] == ["dot", "add", "neg", "exp", "add", "div"]
+    assert "column-accumulate" in out.plan().splitlines()[1]
+    assert len(g) == 2
+
+
+def test_unfused_mode_cuts_at_every_op(ctx):
+    ctx.set_option("fusion", 0)
+    out = wl.softmax(gr, ctx.spec((64, 256)))
+    assert [ops for _, ops in groups(out)] == [["max"], ["sub"], ["exp"], ["sum"], ["div"]]
+    ctx.set_option("fusion", 1)
+
+
+def test_multiple_use_across_subgraphs_materialises_once(ctx):
+    a = ctx.spec((100, 64))
+    t = gr.exp(a)                    # used by a non-resident reduction and by the final map
+    s = t.sum(axis=0, keepdims=True)
+    out = t / s
+    g = groups(out)
+    owners = [ops for _, ops in g]
+    assert sum(ops.count("exp") for ops in owners) == 1, "exp must belong to exactly one sub-graph"
+    assert owners == [["exp"], ["sum"], ["div"]]
+    lines = out.plan().splitlines()
+    exp_root = re.search(r"root=(\d+)", lines[0]).group(1)
+    for line in lines[1:]:
+        assert exp_root in re.search(r"leaves=\[(.*?)\]", line).group(1).split(",")
+
+
+def test_leaves_and_only_leaves_are_materialised(ctx):
+    a = ctx.spec((33, 65))
+    out = (a.T @ (a @ ctx.spec((65,)))) * 2.0
+    all_members = []
+    for line in out.plan().splitlines():
+        members = re.search(r"members=\[(.*?)\]", line).group(1)
+        ids = [int(m.split(":")[0]) for m in members.split(",") if m]
+        leaves = [int(x) for x in re.search(r"leaves=\[(.*?)\]", line).group(1).split(",") if x]
+        assert not set(ids) & set(leaves)
+        all_members += ids
+    assert len(all_members) == len(set(all_members)), "a node is computed by exactly one sub-graph"
+
+
+def test_row_resident_limit_turns_reduction_into_a_cut(ctx):
+    x = ctx.spec((8, 20000))
+    out = wl.softmax(gr, x)
+    # max is cut; exp(X-m) feeds both the (cut) sum and the final division, so the
+    # multiple-use rule materialises it once: the paper's own partition of a softmax
+    assert groups(out) == [("REDUCE", ["max"]), ("MAP", ["sub", "exp"]), ("REDUCE", ["sum"]), ("MAP", ["div"])]
+    ctx.set_option("rowred_max_cols", 512)
+    assert [k for k, _ in groups(wl.softmax(gr, ctx.spec((8, 1000))))] == ["REDUCE", "MAP", "REDUCE", "MAP"]
+    assert [k for k, _ in groups(wl.softmax(gr, ctx.spec((8, 512))))] == ["ROWRED"]
+
+
+# ------------------------------------------------- code generation on the host ----
+def _specs(ctx, arrays):
+    code = {np.dtype(np.float32): gr.GR_F32, np.dtype(np.int32): gr.GR_I32}
+    return {k: ctx.spec(v.shape, code[v.dtype]) for k, v in arrays.items()}
+
+
+@pytest.mark.parametrize("name", ["chain", "normalize", "softmax", "stencil", "logreg"])
+@pytest.mark.parametrize("size", ["small", "full"])
+def test_configurations_compile_for_gfx950(ctx, name, size):
+    p = wl.SMALL[name] if size == "small" else wl.FULL[name]
+    shapes = {k: v.shape for k, v in wl.make_inputs(name, **wl.SMALL[name]).items()} if size == "small" else None
+    if size == "full":
+        r, c = p.get("rows"), p.get("cols")
+        shapes = {"chain": dict(a=(p.get("n"),), b=(p.get("n"),)),
+                  "normalize": dict(X=(r, c), mu=(1, c), sigma=(1, c), gamma=(c,), beta=(c,)),
+                  "softmax": dict(X=(r, c)), "stencil": dict(I=(r, c)), "logreg": dict(X=(r, c), w=(c,), y=(r,))}[name]
+    out = wl.PROGRAMS[name](gr, **{k: ctx.spec(s) for k, s in shapes.items()})
+    out.compile()
+    src = out.source(0)
+    assert "extern \"C\" __global__" in src and "f4u" in src
+
+
+@pytest.mark.parametrize("name", sorted(ELEMENTWISE_CASES))
+def test_elementwise_cases_compile(ctx, name):
+    prog, mk = ELEMENTWISE_CASES[name]
+    prog(gr, **_specs(ctx, mk())).compile()
+
+
+@pytest.mark.parametrize("shape,axis,keep", REDUCTION_CASES)
+def test_reduction_cases_compile(ctx, shape, axis, keep):
+    for op in ("sum", "max", "min"):
+        getattr(gr, op)(ctx.spec(shape) * 1.5, axis=axis, keepdims=keep).compile()
+    gr.sum(ctx.spec(shape, gr.GR_I32), axis=axis, keepdims=keep).compile()
+
+
+def test_rowred_and_dot_cases_compile(ctx):
+    for i, p in enumerate(ROWRED_PROGRAMS):
+        p(gr, ctx.spec((50, 50) if i >= 5 else (50, 333))).compile()
+    for prog, what in DOT_CASES:
+        prog(gr, ctx.spec((70, 130)), ctx.spec((130,)), ctx.spec((70,))).compile()
+    wl.mnist(gr, ctx.spec((200, 10)), ctx.spec((200,)), ctx.spec((10,))).compile()
+    wl.listing1(gr, ctx.spec((10, 20), gr.GR_I32), ctx.spec((20,), gr.GR_I32)).compile()
+
+
+def test_same_structure_hits_the_kernel_cache(ctx):
+    (ctx.spec((64, 300)) * 2.0 + 1.0).compile()
+    s0 = ctx.stats()
+    (ctx.spec((80, 500)) * 3.0 + 7.0).compile()
+    s1 = ctx.stats()
+    assert s1["cache_misses"] == s0["cache_misses"] and s1["cache_hits"] == s0["cache_hits"] + 1
+
+
+def test_generated_code_has_no_contraction_or_packed_math(ctx):
+    src = wl.chain(gr, ctx.spec((4096,)), ctx.spec((4096,))).source(0)
+    assert "fmaf" not in src and "__fdividef" not in src and "__expf" not in src
