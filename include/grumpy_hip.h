@@ -102,6 +102,8 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *   "rowred_max_cols" longest row (elements) a reduction may keep resident
  *                     in registers and still fuse with its consumers
  *   "map_rows", "map_chunks"   per-lane patch of the map skeleton (0 = auto)
+ *   "nontemporal"     1 (default) = loads of arrays that are read once carry
+ *                     the non-temporal hint; 0 = none; 2 = every vector load
  *   "profile"         1 = bracket every launch with HIP events (gr_profile_*)
  * Unknown key: GR_ERR_ARG. */
 gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value);
@@ -133,6 +135,12 @@ gr_status gr_scalar(gr_ctx* ctx, double value, int is_integer, gr_array* out);
 
 gr_status gr_unary(gr_ctx* ctx, gr_op op, gr_array a, gr_array* out);
 gr_status gr_binary(gr_ctx* ctx, gr_op op, gr_array a, gr_array b, gr_array* out);
+
+/* gr_binary with a Python-style number as one operand, in one call:
+ * scalar_on_left = 0 records op(a, value), 1 records op(value, a).  Same
+ * typing rule and errors as gr_scalar followed by gr_binary. */
+gr_status gr_binary_scalar(gr_ctx* ctx, gr_op op, gr_array a, double value, int is_integer, int scalar_on_left,
+                           gr_array* out);
 
 /* Basic slicing with Python rules on the first `nspec` dimensions (step >= 1;
  * has_start/has_stop = 0 mean "omitted"); the rest are taken whole.  The

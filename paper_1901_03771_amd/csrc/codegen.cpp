@@ -36,6 +36,21 @@ char access_class(const AccessGroup& ag, int dim) {
   return 'G';
 }
 
+// Arrays that are streamed through once (unit stride, not re-read through shifted
+// views, not broadcast along rows) bypass cache retention; operands that lanes
+// share stay cacheable.
+bool nontemporal_group(const GroupPlan& g, int group) {
+  const AccessGroup& ag = g.groups[group];
+  if (g.nt <= 0 || ag.dtype == GR_I64) return false;
+  if (g.kind == GroupKind::GEMV) return group == g.mat_group;
+  if (access_class(ag, g.rank - 1) != '1') return false;
+  if (g.nt >= 2) return true;
+  if (ag.deltas.size() > 1) return false;
+  bool varies_outside_columns = g.rank < 2;
+  for (int k = 0; k + 1 < g.rank; ++k) if (!ag.structural_zero[k]) varies_outside_columns = true;
+  return varies_outside_columns;
+}
+
 ArgLayout arg_layout(const GroupPlan& g) {
   ArgLayout L;
   int s = 0;
@@ -80,6 +95,12 @@ struct Em {
   ArgLayout L;
   std::ostringstream o;
   explicit Em(const GroupPlan& gp) : g(gp), L(arg_layout(gp)) {}
+
+  // *(const T*)(addr), with the non-temporal hint where the group streams
+  std::string ld(int group, const std::string& type, const std::string& addr) const {
+    if (nontemporal_group(g, group)) return "__builtin_nontemporal_load((const " + type + "*)(" + addr + "))";
+    return "*(const " + type + "*)(" + addr + ")";
+  }
 
   std::string S(int slot) const { return "((long long)a.s[" + std::to_string(slot) + "])"; }
   std::string dim(int k) const { return S(L.dims + k); }
@@ -291,8 +312,8 @@ void gen_map(Em& e) {
     return s.str();
   };
 
-  // ---- interior tiles: the whole patch, straight-line ----
-  e.o << "  if ((by + 1) * " << TR << " <= R && (bx + 1) * " << TC << " <= C) {\n";
+  // ---- lanes whose whole patch lies inside the array: straight-line ----
+  e.o << "  if (r0 + " << g.VR << " <= R && c0 + " << (g.UC - 1) * g.BX * 4 + 4 << " <= C) {\n";
   // group the contiguous loads of the patch program into vector loads
   std::map<int, std::string> load_name;  // instr -> expression
   {
@@ -339,9 +360,8 @@ void gen_map(Em& e) {
           int64_t dc = v[i + pos].first;
           std::string nm = "L" + std::to_string(nl++);
           std::string addr = "p" + std::to_string(first.group) + " + (" + rowoff + ") + " + std::to_string(dc);
-          if (take == 4) e.o << "    const " << vty4(ag.dtype) << ' ' << nm << " = *(const " << vty4(ag.dtype) << "*)(" << addr << ");\n";
-          else if (take == 2) e.o << "    const " << vty2(ag.dtype) << ' ' << nm << " = *(const " << vty2(ag.dtype) << "*)(" << addr << ");\n";
-          else e.o << "    const " << cty(ag.dtype) << ' ' << nm << " = *(" << addr << ");\n";
+          const char* lt = take == 4 ? vty4(ag.dtype) : (take == 2 ? vty2(ag.dtype) : cty(ag.dtype));
+          e.o << "    const " << lt << ' ' << nm << " = " << e.ld(first.group, lt, addr) << ";\n";
           for (size_t q = 0; q < take; ++q)
             load_name[v[i + pos + q].second] = take == 1 ? nm : nm + "[" + std::to_string(q) + "]";
           pos += take;
@@ -367,7 +387,7 @@ void gen_map(Em& e) {
         ri += 4;
       }
   }
-  // ---- boundary tiles: one guarded point at a time ----
+  // ---- lanes on the array's edge: one guarded point at a time ----
   e.o << "  } else {\n"
          "    for (int v = 0; v < " << g.VR << "; ++v)\n"
          "      for (int u = 0; u < " << g.UC << "; ++u)\n"
@@ -525,7 +545,7 @@ void gen_rowred(Em& e) {
         if (cc == '1') {
           if (guarded) e.o << "    if (c + 4 <= C) ";
           else e.o << "    ";
-          e.o << "{ const " << vty4(in.dtype) << " w = *(const " << vty4(in.dtype) << "*)(" << base << " + " << idx << "); l" << i << "[0] = w[0]; l" << i
+          e.o << "{ const " << vty4(in.dtype) << " w = " << e.ld(in.group, vty4(in.dtype), base + " + " + idx) << "; l" << i << "[0] = w[0]; l" << i
               << "[1] = w[1]; l" << i << "[2] = w[2]; l" << i << "[3] = w[3]; }\n";
           if (guarded)
             e.o << "    else { for (int j = 0; j < 4; ++j) l" << i << "[j] = (c + j < C) ? (" << base << ")[" << idx << " + j] : " << Em::zero(in.dtype) << "; }\n";
@@ -674,7 +694,7 @@ void gen_gemv_rowdot(Em& e) {
   e.o << "    if (single) {\n";
   e.o << "      float xv[" << KV << "][4];\n#pragma unroll\n      for (int q = 0; q < " << KV << "; ++q) {\n        const long long k0 = (long long)q * " << CH << " + lane * 4;\n";
   if (mat_unit)
-    e.o << "        if (k0 + 4 <= K) { const f4u w = *(const f4u*)(Ar + k0); xv[q][0] = w[0]; xv[q][1] = w[1]; xv[q][2] = w[2]; xv[q][3] = w[3]; }\n"
+    e.o << "        if (k0 + 4 <= K) { const f4u w = " << e.ld(g.mat_group, "f4u", "Ar + k0") << "; xv[q][0] = w[0]; xv[q][1] = w[1]; xv[q][2] = w[2]; xv[q][3] = w[3]; }\n"
            "        else { for (int j = 0; j < 4; ++j) xv[q][j] = (k0 + j < K) ? Ar[k0 + j] : 0.0f; }\n";
   else
     e.o << "        for (int j = 0; j < 4; ++j) xv[q][j] = (k0 + j < K) ? Ar[(k0 + j) * ak] : 0.0f;\n";
@@ -710,7 +730,7 @@ void gen_gemv_colacc(Em& e) {
          "    long long k = kbeg + ty;\n"
          "    for (; k + " << 7 * BY << " < kend; k += " << 8 * BY << ") {\n"
          "      f4u x[8]; float s[8];\n"
-         "#pragma unroll\n      for (int u = 0; u < 8; ++u) { x[u] = *(const f4u*)(A + (k + u * " << BY << ") * ak + m0); s[u] = V[(k + u * " << BY << ") * vk]; }\n"
+         "#pragma unroll\n      for (int u = 0; u < 8; ++u) { x[u] = " << e.ld(g.mat_group, "f4u", "A + (k + u * " + std::to_string(BY) + ") * ak + m0") << "; s[u] = V[(k + u * " << BY << ") * vk]; }\n"
          "#pragma unroll\n      for (int u = 0; u < 8; ++u) { acc[0] = __builtin_fmaf(x[u][0], s[u], acc[0]); acc[1] = __builtin_fmaf(x[u][1], s[u], acc[1]); acc[2] = __builtin_fmaf(x[u][2], s[u], acc[2]); acc[3] = __builtin_fmaf(x[u][3], s[u], acc[3]); }\n"
          "    }\n"
          "    for (; k < kend; k += " << BY << ") { const f4u x = *(const f4u*)(A + k * ak + m0); const float s = V[k * vk];\n"

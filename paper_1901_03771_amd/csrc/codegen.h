@@ -26,4 +26,7 @@ ArgLayout arg_layout(const GroupPlan& g);
 // 'Z': no leaf dimension follows this iteration dimension; '1': unit stride; 'G': anything else.
 char access_class(const AccessGroup& ag, int dim);
 
+// Whether loads of this access group carry the non-temporal hint.
+bool nontemporal_group(const GroupPlan& g, int group);
+
 }  // namespace gr

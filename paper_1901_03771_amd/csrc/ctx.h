@@ -24,6 +24,7 @@ struct gr_ctx {
   int64_t opt_rowred_max_cols = 16384;
   int64_t opt_map_rows = 0, opt_map_chunks = 0;
   int64_t opt_profile = 0;
+  int64_t opt_nontemporal = 1;
 
   // allocator
   void* (*alloc_fn)(size_t, void*) = nullptr;
@@ -72,6 +73,7 @@ void ctx_free(gr_ctx* c, void* p, size_t bytes);
 // plan.cpp
 gr_status make_plan(gr_ctx* c, Node* root, Plan* plan);
 void clear_planned(Plan* plan);
+gr_status expand_patch(gr_ctx* c, GroupPlan* g);
 std::string describe_plan(const Plan& plan);
 
 // codegen.cpp
@@ -79,7 +81,7 @@ std::string generate_source(const GroupPlan& g);
 std::string kernel_name(const GroupPlan& g);
 
 // runtime.cpp
-gr_status compile_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel** out);
+gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out);
 gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr);
 gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out);
 

@@ -140,7 +140,9 @@ struct GroupPlan {
   std::vector<ConstSlot> consts;
   std::vector<Phase> phases;
 
-  // single-point program for boundary tiles (MAP)
+  // MAP: single-point program (boundary tiles, cache key); `prog` holds the per-lane patch
+  // program and is only built when a kernel has to be generated
+  std::set<const Node*> owned;
   std::vector<Instr> prog1;
   int result1 = -1;
 
@@ -153,6 +155,7 @@ struct GroupPlan {
   int NP = 1;                            // ROWRED: vec4 positions per lane
   int row_threads = 64;                  // ROWRED: lanes cooperating on one row (64 or 256)
   bool xcd_remap = false;
+  int nt = 0;                            // non-temporal load hint: 0 none, 1 arrays read once, 2 all vector loads
   int red_mode = 0;                      // REDUCE: 0 thread-per-output, 1 block-per-output
   int64_t red_out = 0, red_len = 0;      // REDUCE: outputs, reduced elements per output
   int red_kept_rank = 0;

@@ -380,40 +380,43 @@ void collapse_dims(GroupPlan* g, const bool* barrier, std::vector<Instr>* progs[
       }
 }
 
-char coef_class(int64_t c) { return c == 0 ? 'Z' : (c == 1 ? '1' : 'G'); }
+void put(std::string& s, int64_t v) { s.append(reinterpret_cast<const char*>(&v), sizeof(v)); }
 
-void dump_prog(std::ostringstream& s, const std::vector<Instr>& prog, int rank) {
+void dump_prog(std::string& s, const std::vector<Instr>& prog, int rank) {
   for (const Instr& in : prog) {
-    s << (int)in.kind << ':' << in.op << ':' << (int)in.dtype << ':' << in.a << ':' << in.b << ':' << in.group << ':' << in.cslot << ':' << in.phase << ':' << in.uniform;
-    if (in.kind == IKind::LOAD) for (int k = 0; k < rank; ++k) s << ',' << in.delta[k];
-    s << ';';
+    put(s, ((int64_t)in.kind << 48) | ((int64_t)in.op << 32) | ((int64_t)in.dtype << 16) | (int64_t)in.uniform);
+    put(s, ((int64_t)(in.a + 1) << 32) | (int64_t)(in.b + 1));
+    put(s, ((int64_t)(in.group + 1) << 40) | ((int64_t)(in.cslot + 1) << 20) | (int64_t)(in.phase + 1));
+    if (in.kind == IKind::LOAD) for (int k = 0; k < rank; ++k) put(s, in.delta[k]);
   }
 }
 
+// Cache key: everything the generated source depends on, and nothing else (extents,
+// strides, base offsets and constants are kernel arguments).
 void make_signature(GroupPlan* g) {
-  std::ostringstream s;
-  s << "k" << (int)g->kind << " r" << g->rank << " o" << (int)g->out_dtype << " pr" << g->out_per_row
-    << " s" << g->BX << ',' << g->BY << ',' << g->VR << ',' << g->UC << ',' << g->NP << ',' << g->row_threads << ',' << g->xcd_remap
-    << ',' << g->red_mode << ',' << g->red_kept_rank << ',' << g->gemv_mode << ',' << g->LPR << ',' << g->KV << ',' << g->mat_group << ',' << g->vec_group << " G";
+  std::string s;
+  s.reserve(256 + 32 * (g->prog.size() + g->prog1.size()));
+  for (int64_t v : {(int64_t)g->kind, (int64_t)g->rank, (int64_t)g->out_dtype, (int64_t)g->out_per_row, (int64_t)g->BX, (int64_t)g->BY,
+                    (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads, (int64_t)g->xcd_remap, (int64_t)g->red_mode,
+                    (int64_t)g->red_kept_rank, (int64_t)g->gemv_mode, (int64_t)g->LPR, (int64_t)g->KV, (int64_t)g->mat_group,
+                    (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->groups.size()})
+    put(s, v);
   for (const AccessGroup& ag : g->groups) {
-    s << (int)ag.dtype << coef_class(ag.coef[g->rank - 1]) << (g->rank >= 2 ? coef_class(ag.coef[g->rank - 2]) : '-') << '|';
+    int64_t cls = (int64_t)ag.dtype;
+    bool core = g->kind == GroupKind::GEMV;
+    int nd = core ? 2 : g->rank;
+    for (int k = 0; k < nd; ++k) cls = cls * 4 + (ag.structural_zero[k] ? 0 : (ag.coef[k] == 1 ? 1 : 2));
+    put(s, cls);
   }
-  if (g->kind == GroupKind::GEMV) {
-    const AccessGroup& mg = g->groups[g->mat_group];
-    const AccessGroup& vg = g->groups[g->vec_group];
-    s << " core" << coef_class(mg.coef[0]) << coef_class(mg.coef[1]) << coef_class(vg.coef[1]);
-  }
-  s << " C";
-  for (const ConstSlot& c : g->consts) s << (int)c.dtype;
-  s << " P";
-  for (const Phase& p : g->phases) s << p.op << ':' << (int)p.in_dtype << ':' << (int)p.out_dtype << ':' << p.value << ';';
-  s << " R";
-  for (int r : g->results) s << r << ',';
-  s << " I";
-  dump_prog(s, g->prog, g->rank);
-  s << " J" << g->result1 << ' ';
+  put(s, (int64_t)g->consts.size());
+  for (const ConstSlot& c : g->consts) put(s, (int64_t)c.dtype);
+  put(s, (int64_t)g->phases.size());
+  for (const Phase& p : g->phases) put(s, ((int64_t)p.op << 40) | ((int64_t)p.in_dtype << 32) | ((int64_t)p.out_dtype << 24) | (int64_t)p.value);
+  put(s, (int64_t)g->results.size());
+  if (g->kind != GroupKind::MAP) { for (int r : g->results) put(s, r); dump_prog(s, g->prog, g->rank); }
+  put(s, g->result1);
   dump_prog(s, g->prog1, g->rank);
-  g->signature = s.str();
+  g->signature.swap(s);
 }
 
 struct Planner {
@@ -508,7 +511,7 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
   if (g->rank == 1 || R == 1) {
     for (int uc : {4, 2}) if (tiles(1, uc) >= 2048) { g->UC = uc; break; }
   } else {
-    int want = shifted_rows ? 8 : 4;
+    int want = 4;  // measured on MI355X: 4 rows per lane is the best patch for broadcast and stencil programs alike
     for (int vr = want; vr >= 2; vr >>= 1) if (tiles(vr, 1) >= 1024 || (shifted_rows && tiles(vr, 1) >= 256)) { g->VR = vr; break; }
   }
   if (c->opt_map_rows > 0 && g->rank >= 2) g->VR = (int)std::min<int64_t>(c->opt_map_rows, 16);
@@ -524,6 +527,7 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
   std::set<const Node*> owned = pl.owned_by(r);
   g->root = r;
   g->out_dtype = r->dtype;
+  g->nt = (int)c->opt_nontemporal;
 
   // classify
   const Node* dot = nullptr;
@@ -720,52 +724,18 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     for (int d = 0; d < r->ndim; ++d) g->orig_dims[d] = r->shape[d];
     IndexMap im(r->ndim);
     for (int d = 0; d < r->ndim; ++d) im[d] = DimMap{d, 1, 0};
-    // pass 1: single point, to learn the accesses and fix the schedule
-    GroupPlan probe = *g;
-    {
-      Builder pb;
-      pb.g = &probe; pb.owned = &owned; pb.rank = n; pb.dims = g->orig_dims; pb.prog = &probe.prog;
-      pb.eval(r, im);
-      if (!pb.invalid.empty()) { *invalid = pb.invalid; return GR_OK; }
-      std::vector<Instr>* ps[1] = {&probe.prog};
-      normalize_deltas(&probe, ps, 1, n);
-      bool barrier[MAXD] = {false};
-      collapse_dims(&probe, barrier, ps, 1);
-      choose_map_schedule(c, &probe);
-    }
-    g->BX = probe.BX; g->BY = probe.BY; g->VR = probe.VR; g->UC = probe.UC; g->xcd_remap = probe.xcd_remap;
-    // innermost original dims of the last two collapsed dims carry the patch shifts
-    int col_dim = -1, row_dim = -1;
-    for (int k = 0; k < n; ++k) {
-      if (probe.collapse_to[k] == probe.rank - 1) col_dim = k;
-      if (probe.rank >= 2 && probe.collapse_to[k] == probe.rank - 2) row_dim = k;
-    }
-    if (col_dim < 0) col_dim = n - 1;
-    // pass 2: the whole per-lane patch with common subexpressions shared across points
-    b.rank = n; b.dims = g->orig_dims; b.prog = &g->prog;
-    for (int v = 0; v < g->VR; ++v)
-      for (int u = 0; u < g->UC; ++u)
-        for (int j = 0; j < 4; ++j) {
-          IndexMap pm = im;
-          for (int d = 0; d < r->ndim; ++d) {
-            if (d == col_dim) pm[d].off += (int64_t)u * g->BX * 4 + j;
-            if (d == row_dim) pm[d].off += v;
-          }
-          // shifted points are evaluated as if the root were larger; canonicalisation of the
-          // root's own extent-1 dims still applies, which is right: such dims carry no shift
-          g->results.push_back(b.eval(r, pm));
-        }
-    // single-point program for boundary tiles
-    Builder sb;  // shares the group table so that both programs index the same access groups
-    sb.g = g; sb.owned = &owned; sb.rank = n; sb.dims = g->orig_dims; sb.prog = &g->prog1;
-    g->result1 = sb.eval(r, im);
-    std::vector<Instr>* ps[2] = {&g->prog, &g->prog1};
-    normalize_deltas(g, ps, 2, n);
+    // Single-point program: enough to learn the accesses, fix the schedule and key the
+    // kernel cache.  The per-lane patch program is a function of exactly these and is only
+    // built when the cache misses (expand_patch).
+    b.rank = n; b.dims = g->orig_dims; b.prog = &g->prog1;
+    g->result1 = b.eval(r, im);
+    if (!b.invalid.empty()) { *invalid = b.invalid; return GR_OK; }
+    std::vector<Instr>* ps[1] = {&g->prog1};
+    normalize_deltas(g, ps, 1, n);
     bool barrier[MAXD] = {false};
-    // shifts in an outer dim forbid merging it; the patch shifts above touch only col_dim/row_dim,
-    // which are innermost in their runs, so the probe's collapse decision is reproduced
-    collapse_dims(g, barrier, ps, 2);
-    if (g->rank != probe.rank) return fail(c, GR_ERR_UNSUPPORTED, "map: inconsistent dimension collapsing");
+    collapse_dims(g, barrier, ps, 1);
+    choose_map_schedule(c, g);
+    g->owned = owned;
   }
 
   for (const Node* n : b.members_seen) g->members.push_back(n);
@@ -773,6 +743,66 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
   for (const Node* n : b.leaves_seen) g->leaves.push_back(n);
   std::sort(g->leaves.begin(), g->leaves.end(), [](const Node* a, const Node* b2) { return a->id < b2->id; });
   make_signature(g);
+  return GR_OK;
+}
+
+// Builds the patch program of a MAP sub-graph: the point function evaluated at every
+// point of the per-lane patch (VR rows x UC chunks of 4 columns), with values shared
+// between points (broadcast operands, overlapping slice views) computed once.
+gr_status expand_patch(gr_ctx* c, GroupPlan* g) {
+  if (g->kind != GroupKind::MAP || !g->prog.empty()) return GR_OK;
+  Node* r = g->root;
+  const int n = g->orig_rank;
+  // innermost original dims of the last two collapsed dims carry the patch shifts
+  int col_dim = -1, row_dim = -1;
+  for (int k = 0; k < n; ++k) {
+    if (g->collapse_to[k] == g->rank - 1) col_dim = k;
+    if (g->rank >= 2 && g->collapse_to[k] == g->rank - 2) row_dim = k;
+  }
+  if (col_dim < 0) col_dim = n - 1;
+  GroupPlan tmp;
+  tmp.kind = GroupKind::MAP;
+  tmp.root = r;
+  tmp.orig_rank = n;
+  for (int k = 0; k < n; ++k) tmp.orig_dims[k] = g->orig_dims[k];
+  tmp.consts = g->consts;
+  Builder b;
+  b.g = &tmp; b.owned = &g->owned; b.rank = n; b.dims = tmp.orig_dims; b.prog = &tmp.prog;
+  IndexMap im(r->ndim);
+  for (int d = 0; d < r->ndim; ++d) im[d] = DimMap{d, 1, 0};
+  const bool was_planned = r->planned;  // the root is computed here, not read
+  r->planned = false;
+  for (int v = 0; v < g->VR; ++v)
+    for (int u = 0; u < g->UC; ++u)
+      for (int j = 0; j < 4; ++j) {
+        IndexMap pm = im;
+        for (int d = 0; d < r->ndim; ++d) {
+          if (d == col_dim) pm[d].off += (int64_t)u * g->BX * 4 + j;
+          if (d == row_dim) pm[d].off += v;
+        }
+        // shifted points are evaluated as if the root were larger; the root's own extent-1
+        // dims stay canonicalised to index 0, which is right: such dims carry no shift
+        tmp.results.push_back(b.eval(r, pm));
+      }
+  r->planned = was_planned;
+  if (!b.invalid.empty()) return fail(c, GR_ERR_UNSUPPORTED, "map: patch expansion met an unexpected node");
+  std::vector<Instr>* ps[1] = {&tmp.prog};
+  normalize_deltas(&tmp, ps, 1, n);
+  bool barrier[MAXD] = {false};
+  // the patch shifts touch only dims that are innermost in their runs, so the collapse
+  // decision of the single-point program is reproduced
+  collapse_dims(&tmp, barrier, ps, 1);
+  bool same = tmp.rank == g->rank && tmp.groups.size() == g->groups.size() && tmp.consts.size() == g->consts.size();
+  for (size_t i = 0; same && i < tmp.groups.size(); ++i)
+    if (tmp.groups[i].ident != g->groups[i].ident || tmp.groups[i].base != g->groups[i].base) same = false;
+  if (!same) {
+    std::ostringstream m;
+    m << "map: patch expansion disagrees with the single-point program (rank " << tmp.rank << "/" << g->rank << ", groups "
+      << tmp.groups.size() << "/" << g->groups.size() << ", consts " << tmp.consts.size() << "/" << g->consts.size() << ")";
+    return fail(c, GR_ERR_UNSUPPORTED, m.str());
+  }
+  g->prog.swap(tmp.prog);
+  g->results.swap(tmp.results);
   return GR_OK;
 }
 

@@ -96,6 +96,7 @@ gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   else if (k == "map_rows") ctx->opt_map_rows = value;
   else if (k == "map_chunks") ctx->opt_map_chunks = value;
   else if (k == "profile") ctx->opt_profile = value;
+  else if (k == "nontemporal") ctx->opt_nontemporal = value;
   else return fail(ctx, GR_ERR_ARG, "unknown option '" + k + "'");
   return GR_OK;
 }
@@ -215,6 +216,17 @@ gr_status gr_binary(gr_ctx* ctx, gr_op op, gr_array a, gr_array b, gr_array* out
   add_input(r, operand(y));
   *out = r->id;
   return GR_OK;
+}
+
+gr_status gr_binary_scalar(gr_ctx* ctx, gr_op op, gr_array a, double value, int is_integer, int scalar_on_left,
+                           gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  gr_array s = 0;
+  gr_status st = gr_scalar(ctx, value, is_integer, &s);
+  if (st != GR_OK) return st;
+  st = scalar_on_left ? gr_binary(ctx, op, s, a, out) : gr_binary(ctx, op, a, s, out);
+  gr_release(ctx, s);
+  return st;
 }
 
 gr_status gr_slice(gr_ctx* ctx, gr_array a, int nspec, const int64_t* start, const int64_t* stop,

@@ -54,7 +54,7 @@ void ctx_free(gr_ctx* c, void* p, size_t bytes) {
   c->pool_free[(bytes + 255) & ~(size_t)255].push_back(p);
 }
 
-gr_status compile_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel** out) {
+gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
   auto it = c->cache.find(g.signature);
   if (it != c->cache.end()) {
     c->stats.cache_hits++;
@@ -63,6 +63,8 @@ gr_status compile_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel** out) {
   }
   c->stats.cache_misses++;
   auto t0 = std::chrono::steady_clock::now();
+  gr_status est = expand_patch(c, &g);
+  if (est != GR_OK) return est;
   std::string src = generate_source(g);
   if (getenv("GR_LOG")) fprintf(stderr, "---- generated kernel ----\n%s\n", src.c_str());
   hiprtcProgram prog;
@@ -379,6 +381,8 @@ gr_status gr_plan_source(gr_ctx* ctx, gr_array a, int index, char* buf, size_t c
   gr_status st = make_plan(ctx, x, &plan);
   if (st != GR_OK) return st;
   if (index < 0 || index >= (int)plan.groups.size()) { clear_planned(&plan); return fail(ctx, GR_ERR_ARG, "plan_source: no such sub-graph"); }
+  st = expand_patch(ctx, plan.groups[index].get());
+  if (st != GR_OK) { clear_planned(&plan); return st; }
   std::string s = generate_source(*plan.groups[index]);
   clear_planned(&plan);
   return copy_out(s, buf, cap, needed);

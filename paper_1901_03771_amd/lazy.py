@@ -31,7 +31,7 @@ STATUS = {0: "GR_OK", 1: "GR_ERR_HANDLE", 2: "GR_ERR_SHAPE", 3: "GR_ERR_DTYPE", 
 # every symbol include/grumpy_hip.h declares
 SYMBOLS = [
     "gr_ctx_create", "gr_ctx_destroy", "gr_ctx_set_stream", "gr_ctx_set_allocator", "gr_ctx_set_option", "gr_sync",
-    "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_slice", "gr_transpose",
+    "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose",
     "gr_reduce", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_ndim", "gr_shape", "gr_dtype_of",
     "gr_is_materialized", "gr_data_ptr", "gr_retain", "gr_release", "gr_plan_describe", "gr_plan_source",
     "gr_plan_compile", "gr_stats", "gr_profile_reset", "gr_profile_read", "gr_stream_copy", "gr_stream_read",
@@ -54,6 +54,8 @@ class Stats(ctypes.Structure):
 
 
 _lib = None
+_TORCH_DTYPES = {}
+_I64_ARRAYS = [ctypes.c_int64 * builtins.max(n, 1) for n in range(9)]
 
 
 def lib():
@@ -73,6 +75,7 @@ def lib():
         "gr_array_from_device": [P, P, I, I, PP(I64), PP(I64), PP(U64)],
         "gr_scalar": [P, ctypes.c_double, I, PP(U64)],
         "gr_unary": [P, I, U64, PP(U64)], "gr_binary": [P, I, U64, U64, PP(U64)],
+        "gr_binary_scalar": [P, I, U64, ctypes.c_double, I, I, PP(U64)],
         "gr_slice": [P, U64, I, PP(I64), PP(I64), PP(I64), PP(ctypes.c_uint8), PP(ctypes.c_uint8), PP(U64)],
         "gr_transpose": [P, U64, PP(I), PP(U64)],
         "gr_reduce": [P, I, U64, PP(I), I, I, PP(U64)], "gr_dot": [P, U64, U64, PP(U64)],
@@ -120,7 +123,6 @@ class Context:
         if st:
             raise GrError(st, L.gr_last_error(None).decode())
         self.device = int(device)
-        self._keep = {}  # node id -> object that owns the device memory of a leaf
 
     def close(self):
         if self._p:
@@ -163,26 +165,31 @@ class Context:
     def from_device(self, ptr: int, dtype: int, shape: Sequence[int], strides: Optional[Sequence[int]] = None,
                     owner=None) -> "Array":
         n = len(shape)
-        shp = (ctypes.c_int64 * builtins.max(n, 1))(*shape)
-        st = None if strides is None else (ctypes.c_int64 * builtins.max(n, 1))(*strides)
+        T = _I64_ARRAYS[n]
         h = ctypes.c_uint64()
-        self.check(lib().gr_array_from_device(self._p, ctypes.c_void_p(ptr), dtype, n, shp, st, ctypes.byref(h)))
+        st = _lib.gr_array_from_device(self._p, ptr, dtype, n, T(*shape), None if strides is None else T(*strides),
+                                       ctypes.byref(h))
+        if st:
+            self.check(st)
         a = Array(self, h.value)
-        if owner is not None:
-            self._keep[h.value] = owner
+        a._owner = owner  # keeps the device memory of the leaf alive as long as the handle
         return a
 
     def array(self, t) -> "Array":
         """Wraps a torch tensor that lives on this context's GPU (borrowed, any strides)."""
-        torch = _torch()
-        if not isinstance(t, torch.Tensor):
-            raise TypeError("expected a torch.Tensor on the GPU")
+        try:
+            dt = _TORCH_DTYPES[t.dtype]
+        except (KeyError, AttributeError):
+            torch = _torch()
+            if not isinstance(t, torch.Tensor):
+                raise TypeError("expected a torch.Tensor on the GPU")
+            _TORCH_DTYPES.update({torch.float32: GR_F32, torch.int32: GR_I32, torch.int64: GR_I64})
+            if t.dtype not in _TORCH_DTYPES:
+                raise GrError(3, f"unsupported dtype {t.dtype}")
+            dt = _TORCH_DTYPES[t.dtype]
         if not t.is_cuda:
             raise ValueError("tensor must live in device memory")
-        dt = {torch.float32: GR_F32, torch.int32: GR_I32, torch.int64: GR_I64}.get(t.dtype)
-        if dt is None:
-            raise GrError(3, f"unsupported dtype {t.dtype}")
-        return self.from_device(t.data_ptr(), dt, tuple(t.shape), tuple(t.stride()), owner=t)
+        return self.from_device(t.data_ptr(), dt, t.shape, t.stride(), owner=t)
 
     def spec(self, shape: Sequence[int], dtype: int = GR_F32, strides: Optional[Sequence[int]] = None) -> "Array":
         """A leaf with a placeholder address, for planning on a device-less context."""
@@ -211,15 +218,17 @@ class Array:
 
     __array_priority__ = 1000
 
+    __slots__ = ("ctx", "h", "_owner")
+
     def __init__(self, ctx: Context, handle: int):
         self.ctx = ctx
         self.h = handle
 
     def __del__(self):
         try:
-            if self.ctx._p:
-                lib().gr_release(self.ctx._p, ctypes.c_uint64(self.h))
-                self.ctx._keep.pop(self.h, None)
+            p = self.ctx._p
+            if p:
+                _lib.gr_release(p, self.h)
         except Exception:
             pass
 
@@ -261,8 +270,9 @@ class Array:
         return self
 
     def materialize_into(self, t) -> "Array":
-        self.ctx.check(lib().gr_materialize_into(self.ctx._p, self.h, ctypes.c_void_p(t.data_ptr()),
-                                                 t.numel() * t.element_size()))
+        st = _lib.gr_materialize_into(self.ctx._p, self.h, t.data_ptr(), t.numel() * t.element_size())
+        if st:
+            self.ctx.check(st)
         return self
 
     def torch(self):
@@ -343,16 +353,43 @@ def _operand(ctx: Context, x) -> Array:
 def unary(name: str, a) -> Array:
     ctx = _ctx_of(a)
     h = ctypes.c_uint64()
-    ctx.check(lib().gr_unary(ctx._p, _UNARY[name], a.h, ctypes.byref(h)))
+    st = _lib.gr_unary(ctx._p, _UNARY[name], a.h, ctypes.byref(h))
+    if st:
+        ctx.check(st)
     return Array(ctx, h.value)
 
 
 def binary(name: str, a, b) -> Array:
-    ctx = _ctx_of(a, b)
-    a, b = _operand(ctx, a), _operand(ctx, b)
+    op = _BINARY[name]
     h = ctypes.c_uint64()
-    ctx.check(lib().gr_binary(ctx._p, _BINARY[name], a.h, b.h, ctypes.byref(h)))
+    if isinstance(a, Array):
+        ctx = a.ctx
+        if isinstance(b, Array):
+            if b.ctx is not ctx:
+                raise ValueError("arrays belong to different contexts")
+            st = _lib.gr_binary(ctx._p, op, a.h, b.h, ctypes.byref(h))
+        else:
+            st = _lib.gr_binary_scalar(ctx._p, op, a.h, float(_number(b)), _is_int(b), 0, ctypes.byref(h))
+    elif isinstance(b, Array):
+        ctx = b.ctx
+        st = _lib.gr_binary_scalar(ctx._p, op, b.h, float(_number(a)), _is_int(a), 1, ctypes.byref(h))
+    else:
+        raise TypeError("no array operand")
+    if st:
+        ctx.check(st)
     return Array(ctx, h.value)
+
+
+def _number(v):
+    if isinstance(v, bool):
+        raise GrError(5, "bool scalars are not supported")
+    if not isinstance(v, (int, float)) and not hasattr(v, "__float__"):
+        raise TypeError(f"unsupported operand {type(v)}")
+    return v
+
+
+def _is_int(v) -> int:
+    return int(isinstance(v, int) or type(v).__name__.startswith(("int", "uint")))
 
 
 def slice_(a: Array, key) -> Array:
