@@ -138,6 +138,8 @@ def main():
     ap.add_argument("--sets", type=int, default=3)
     ap.add_argument("--no-extras", action="store_true", help="skip the supplementary configurations and ceilings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calibrate", type=int, default=0, metavar="N",
+                    help="also launch the plain copy kernel N times on the workload's first array (reference for rocprofv3 counters)")
     ap.add_argument("--no-launch-events", action="store_true", help="skip the instrumented cross-check pass (one HIP event pair per launch)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -196,6 +198,12 @@ def main():
         "cold_first_call_ms": round(cold_ms, 2),
         "roofline": roofline,
     }
+
+    if args.calibrate:
+        src, dst = w.sets[0][0][ARGNAMES[name][0]], w.sets[1][0][ARGNAMES[name][0]]
+        for _ in range(args.calibrate):
+            ctx.stream_copy(dst, src)
+        torch.cuda.synchronize()
 
     if not args.no_extras:
         extras = {}
