@@ -102,6 +102,11 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *   "rowred_max_cols" longest row (elements) a reduction may keep resident
  *                     in registers and still fuse with its consumers
  *   "map_rows", "map_chunks"   per-lane patch of the map skeleton (0 = auto)
+ *   "map_bx"          lanes of a workgroup along the columns (power of two <= 256; 0 = auto)
+ *   "rowred_threads"  lanes that hold one row: 16, 64, 128 or 256 (0 = auto)
+ *   "gemv_slabs", "gemv_unroll"  column-accumulate contraction: number of row
+ *                     slabs (first-stage partial vectors) and rows in flight
+ *                     per lane, 8 or 16 (0 = auto)
  *   "nontemporal"     1 (default) = loads of arrays that are read once carry
  *                     the non-temporal hint; 0 = none; 2 = every vector load
  *   "profile"         1 = bracket every launch with HIP events (gr_profile_*)

@@ -445,9 +445,18 @@ void gen_rowred(Em& e) {
   e.o << "  const long long C = " << e.dim(cd) << ";\n  long long ROWS = 1;\n";
   for (int k = 0; k < cd; ++k) e.o << "  ROWS *= " << e.dim(k) << ";\n";
   e.o << "  const int lane = threadIdx.x % " << RT << ";\n";
-  e.o << "  const long long row = (long long)blockIdx.x * " << RB << " + threadIdx.x / " << RT << ";\n";
-  if (RT == 256) e.o << "  __shared__ " << "long long" << " gr_sm[" << std::max(nph, 1) << "][4];\n";
-  e.o << "  if (row >= ROWS) return;\n";
+  if (RT <= 64) {
+    // no workgroup barrier in this variant: lanes of rows past the end simply leave
+    e.o << "  const long long row = (long long)blockIdx.x * " << RB << " + threadIdx.x / " << RT << ";\n";
+    e.o << "  if (row >= ROWS) return;\n  const bool row_ok = true;\n";
+  } else {
+    // rows span several waves and combine through LDS behind a barrier every wave reaches:
+    // lanes of a row past the end recompute the last row and skip the stores
+    e.o << "  const long long row_raw = (long long)blockIdx.x * " << RB << " + threadIdx.x / " << RT << ";\n";
+    e.o << "  const bool row_ok = row_raw < ROWS;\n  const long long row = row_ok ? row_raw : ROWS - 1;\n";
+    e.o << "  __shared__ long long gr_sm[" << std::max(nph, 1) << "][4];\n";
+  }
+  e.o << "  (void)row_ok;\n";
   if (cd >= 1) {
     e.o << "  long long rrem = row;\n";
     for (int k = cd - 1; k >= 0; --k) e.o << "  const long long i" << k << " = rrem % " << e.dim(k) << "; rrem /= " << e.dim(k) << ";\n";
@@ -510,7 +519,7 @@ void gen_rowred(Em& e) {
       e.o << ";\n";
     }
     if (final_stage && g.out_per_row) {
-      e.o << "  if (lane == 0) ((" << cty(g.out_dtype) << "*)a.s[" << e.L.out << "])[row] = " << name(g.results[0], false) << ";\n";
+      e.o << "  if (lane == 0 && row_ok) ((" << cty(g.out_dtype) << "*)a.s[" << e.L.out << "])[row] = " << name(g.results[0], false) << ";\n";
       break;
     }
     const Phase* ph = final_stage ? nullptr : &g.phases[s];
@@ -568,25 +577,26 @@ void gen_rowred(Em& e) {
         if (guarded) e.o << "      if (c + j < C) " << upd << "\n";
         else e.o << "      " << upd << "\n";
       } else {
-        if (g.out_dtype == GR_I64) e.o << "      " << (guarded ? "if (c + j < C) " : "") << "po[c + j] = " << name(want, true) << ";\n";
+        if (g.out_dtype == GR_I64) e.o << "      if (row_ok" << (guarded ? " && c + j < C" : "") << ") po[c + j] = " << name(want, true) << ";\n";
         else e.o << "      ov[j] = " << name(want, true) << ";\n";
       }
       e.o << "    }\n";
       if (final_stage && g.out_dtype != GR_I64) {
         const char* vt = g.out_dtype == GR_F32 ? "f4u" : "i4u";
-        if (guarded) e.o << "    if (c + 4 <= C) *(" << vt << "*)(po + c) = ov; else { for (int j = 0; j < 4; ++j) if (c + j < C) po[c + j] = ov[j]; }\n";
-        else e.o << "    *(" << vt << "*)(po + c) = ov;\n";
+        if (guarded) e.o << "    if (row_ok) { if (c + 4 <= C) *(" << vt << "*)(po + c) = ov; else { for (int j = 0; j < 4; ++j) if (c + j < C) po[c + j] = ov[j]; } }\n";
+        else e.o << "    if (row_ok) *(" << vt << "*)(po + c) = ov;\n";
       }
       e.o << "  }\n";
     }
     if (ph) {
       e.o << "  acc" << s << " = gr_lanes" << s << "(acc" << s << ");\n";
-      if (RT == 256) {
+      if (RT > 64) {
         const char* T = cty(ph->out_dtype);
         e.o << "  { " << T << "* sm = (" << T << "*)gr_sm[" << s << "];\n"
                "    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc" << s << ";\n"
-               "    __syncthreads();\n"
-               "    acc" << s << " = gr_comb" << s << "(gr_comb" << s << "(sm[0], sm[1]), gr_comb" << s << "(sm[2], sm[3])); }\n";
+               "    __syncthreads();\n";
+        if (RT == 256) e.o << "    acc" << s << " = gr_comb" << s << "(gr_comb" << s << "(sm[0], sm[1]), gr_comb" << s << "(sm[2], sm[3])); }\n";
+        else e.o << "    const int w0 = (threadIdx.x >> 7) * 2;\n    acc" << s << " = gr_comb" << s << "(sm[w0], sm[w0 + 1]); }\n";
       }
       e.o << "  red" << s << " = acc" << s << ";\n";
     }
@@ -709,7 +719,7 @@ void gen_gemv_rowdot(Em& e) {
 
 void gen_gemv_colacc(Em& e) {
   const GroupPlan& g = e.g;
-  const int BX = g.BX, BY = g.BY;
+  const int BX = g.BX, BY = g.BY, UN = g.unroll;
   const AccessGroup& vg = g.groups[g.vec_group];
   const bool vec_unit = vg.coef[1] == 1;
   prelude(e);
@@ -728,10 +738,10 @@ void gen_gemv_colacc(Em& e) {
   e.o << "  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};\n";
   e.o << "  if (m0 + 4 <= M) {\n"
          "    long long k = kbeg + ty;\n"
-         "    for (; k + " << 7 * BY << " < kend; k += " << 8 * BY << ") {\n"
-         "      f4u x[8]; float s[8];\n"
-         "#pragma unroll\n      for (int u = 0; u < 8; ++u) { x[u] = " << e.ld(g.mat_group, "f4u", "A + (k + u * " + std::to_string(BY) + ") * ak + m0") << "; s[u] = V[(k + u * " << BY << ") * vk]; }\n"
-         "#pragma unroll\n      for (int u = 0; u < 8; ++u) { acc[0] = __builtin_fmaf(x[u][0], s[u], acc[0]); acc[1] = __builtin_fmaf(x[u][1], s[u], acc[1]); acc[2] = __builtin_fmaf(x[u][2], s[u], acc[2]); acc[3] = __builtin_fmaf(x[u][3], s[u], acc[3]); }\n"
+         "    for (; k + " << (UN - 1) * BY << " < kend; k += " << UN * BY << ") {\n"
+         "      f4u x[" << UN << "]; float s[" << UN << "];\n"
+         "#pragma unroll\n      for (int u = 0; u < " << UN << "; ++u) { x[u] = " << e.ld(g.mat_group, "f4u", "A + (k + u * " + std::to_string(BY) + ") * ak + m0") << "; s[u] = V[(k + u * " << BY << ") * vk]; }\n"
+         "#pragma unroll\n      for (int u = 0; u < " << UN << "; ++u) { acc[0] = __builtin_fmaf(x[u][0], s[u], acc[0]); acc[1] = __builtin_fmaf(x[u][1], s[u], acc[1]); acc[2] = __builtin_fmaf(x[u][2], s[u], acc[2]); acc[3] = __builtin_fmaf(x[u][3], s[u], acc[3]); }\n"
          "    }\n"
          "    for (; k < kend; k += " << BY << ") { const f4u x = *(const f4u*)(A + k * ak + m0); const float s = V[k * vk];\n"
          "      acc[0] = __builtin_fmaf(x[0], s, acc[0]); acc[1] = __builtin_fmaf(x[1], s, acc[1]); acc[2] = __builtin_fmaf(x[2], s, acc[2]); acc[3] = __builtin_fmaf(x[3], s, acc[3]); }\n"
@@ -751,7 +761,11 @@ void gen_gemv_colacc(Em& e) {
   e.o << "  const int tx = threadIdx.x % 16, sg = threadIdx.x / 16;\n";
   e.o << "  const long long m = (long long)blockIdx.x * 16 + tx;\n";
   e.o << "  __shared__ float sm[16][17];\n  float part = 0.0f;\n";
-  e.o << "  if (m < M) for (long long s = sg; s < SLABS; s += 16) part += ws[s * M + m];\n";
+  e.o << "  if (m < M) {\n    long long s = sg;\n"
+         "    for (; s + 112 < SLABS; s += 128) {\n      float v[8];\n"
+         "#pragma unroll\n      for (int u = 0; u < 8; ++u) v[u] = ws[(s + 16 * u) * M + m];\n"
+         "#pragma unroll\n      for (int u = 0; u < 8; ++u) part += v[u];\n    }\n"
+         "    for (; s < SLABS; s += 16) part += ws[s * M + m];\n  }\n";
   e.o << "  sm[sg][tx] = part;\n  __syncthreads();\n";
   e.o << "  if (sg == 0 && m < M) {\n    float acc = sm[0][tx];\n    for (int y = 1; y < 16; ++y) acc += sm[y][tx];\n";
   gemv_epilogue(e, "m", "acc", "    ");

@@ -25,6 +25,9 @@ struct gr_ctx {
   int64_t opt_map_rows = 0, opt_map_chunks = 0;
   int64_t opt_profile = 0;
   int64_t opt_nontemporal = 1;
+  int64_t opt_map_bx = 0;
+  int64_t opt_rowred_threads = 0;
+  int64_t opt_gemv_slabs = 0, opt_gemv_unroll = 0;
 
   // allocator
   void* (*alloc_fn)(size_t, void*) = nullptr;

@@ -167,6 +167,7 @@ struct GroupPlan {
   int LPR = 64;       // gemv row-dot: lanes per row
   int KV = 1;         // gemv row-dot: vec4 per lane along k
   int slabs = 1;      // gemv column-accumulate: row slabs (first-stage partial vectors)
+  int unroll = 8;     // gemv column-accumulate: rows in flight per lane
 
   std::string signature;
 };
