@@ -109,6 +109,9 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     per lane, 8 or 16 (0 = auto)
  *   "nontemporal"     1 (default) = loads of arrays that are read once carry
  *                     the non-temporal hint; 0 = none; 2 = every vector load
+ *   "gemv_pair"       1 (default) = a contraction A.v whose epilogue result r
+ *                     feeds the contraction A^T.r runs with it in one pass
+ *                     over A; 0 = two passes
  *   "profile"         1 = bracket every launch with HIP events (gr_profile_*)
  * Unknown key: GR_ERR_ARG. */
 gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value);

@@ -79,7 +79,7 @@ std::string kernel_name(const GroupPlan& g) {
     case GroupKind::MAP: return "gr_map";
     case GroupKind::ROWRED: return "gr_rowred";
     case GroupKind::REDUCE: return "gr_reduce";
-    case GroupKind::GEMV: return g.gemv_mode ? "gr_gemv_colacc" : "gr_gemv_rowdot";
+    case GroupKind::GEMV: return g.gemv_mode == 2 ? "gr_gemv_pair" : (g.gemv_mode ? "gr_gemv_colacc" : "gr_gemv_rowdot");
   }
   return "gr_kernel";
 }
@@ -94,7 +94,11 @@ struct Em {
   const GroupPlan& g;
   ArgLayout L;
   std::ostringstream o;
-  explicit Em(const GroupPlan& gp) : g(gp), L(arg_layout(gp)) {}
+  int slot_base = 0;     // first slot of this sub-graph's block inside the kernel's argument array
+  int total_slots = 0;   // size of the whole argument array
+  std::string qp = "q";  // name prefix of the per-group base pointers
+  explicit Em(const GroupPlan& gp) : g(gp), L(arg_layout(gp)) { total_slots = L.total; }
+  std::string slot(int n) const { return "a.s[" + std::to_string(slot_base + n) + "]"; }
 
   // *(const T*)(addr), with the non-temporal hint where the group streams
   std::string ld(int group, const std::string& type, const std::string& addr) const {
@@ -102,11 +106,11 @@ struct Em {
     return "*(const " + type + "*)(" + addr + ")";
   }
 
-  std::string S(int slot) const { return "((long long)a.s[" + std::to_string(slot) + "])"; }
+  std::string S(int n) const { return "((long long)" + slot(n) + ")"; }
   std::string dim(int k) const { return S(L.dims + k); }
   std::string cst(int cslot) const {
     const ConstSlot& c = g.consts[cslot];
-    std::string s = "a.s[" + std::to_string(L.consts + cslot) + "]";
+    std::string s = slot(L.consts + cslot);
     if (c.dtype == GR_F32) return "__uint_as_float((unsigned)" + s + ")";
     if (c.dtype == GR_I32) return "((int)" + s + ")";
     return "((long long)" + s + ")";
@@ -175,7 +179,7 @@ void prelude(Em& e) {
          "typedef i4 i4u __attribute__((aligned(4)));\n"
          "typedef int i2 __attribute__((ext_vector_type(2)));\n"
          "typedef i2 i2u __attribute__((aligned(4)));\n"
-         "struct Args { unsigned long long s[" << e.L.total << "]; };\n"
+         "struct Args { unsigned long long s[" << e.total_slots << "]; };\n"
          "static __device__ __forceinline__ float gr_maxf(float a, float b) { return (a >= b || a != a) ? a : b; }\n"
          "static __device__ __forceinline__ float gr_minf(float a, float b) { return (a <= b || a != a) ? a : b; }\n"
          "static __device__ __forceinline__ float gr_xor(float v, int m) { return __shfl_xor(v, m, 64); }\n"
@@ -247,8 +251,8 @@ void group_pointers(Em& e, const std::string& indent, const std::vector<int>& sk
   for (size_t gi = 0; gi < e.g.groups.size(); ++gi) {
     if (std::find(skip.begin(), skip.end(), (int)gi) != skip.end()) continue;
     const AccessGroup& ag = e.g.groups[gi];
-    e.o << indent << "const " << cty(ag.dtype) << "* const q" << gi << " = (const " << cty(ag.dtype) << "*)a.s[" << e.L.ptr[gi]
-        << "] + " << e.S(e.L.base[gi]) << ";\n";
+    e.o << indent << "const " << cty(ag.dtype) << "* const " << e.qp << gi << " = (const " << cty(ag.dtype) << "*)" << e.slot(e.L.ptr[gi])
+        << " + " << e.S(e.L.base[gi]) << ";\n";
   }
 }
 
@@ -292,7 +296,7 @@ void gen_map(Em& e) {
     else if (cc == 'G') e.o << " + c0 * " << e.coef((int)gi, cd);
     e.o << ";\n";
   }
-  e.o << "  " << cty(g.out_dtype) << "* const po = (" << cty(g.out_dtype) << "*)a.s[" << e.L.out << "] + (olin * R + r0) * C + c0;\n";
+  e.o << "  " << cty(g.out_dtype) << "* const po = (" << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << " + (olin * R + r0) * C + c0;\n";
 
   // static part of a load's address: shifts times runtime coefficients
   auto shift_expr = [&](const Instr& in, bool with_col) {
@@ -519,13 +523,13 @@ void gen_rowred(Em& e) {
       e.o << ";\n";
     }
     if (final_stage && g.out_per_row) {
-      e.o << "  if (lane == 0 && row_ok) ((" << cty(g.out_dtype) << "*)a.s[" << e.L.out << "])[row] = " << name(g.results[0], false) << ";\n";
+      e.o << "  if (lane == 0 && row_ok) ((" << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << ")[row] = " << name(g.results[0], false) << ";\n";
       break;
     }
     const Phase* ph = final_stage ? nullptr : &g.phases[s];
     if (ph) e.o << "  " << cty(ph->out_dtype) << " acc" << s << " = " << Em::identity(*ph) << ";\n";
     if (final_stage)
-      e.o << "  " << cty(g.out_dtype) << "* const po = (" << cty(g.out_dtype) << "*)a.s[" << e.L.out << "] + row * C;\n";
+      e.o << "  " << cty(g.out_dtype) << "* const po = (" << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << " + row * C;\n";
     bool any_elem = false;
     for (int i : stage_instrs[s]) if (!g.prog[i].uniform) any_elem = true;
     int want = ph ? ph->value : g.results[0];
@@ -657,9 +661,9 @@ void gen_reduce(Em& e) {
            "    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;\n"
            "    __syncthreads();\n"
            "    acc = gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])); }\n"
-           "  if (threadIdx.x == 0) ((" << T << "*)a.s[" << e.L.out << "])[o] = acc;\n";
+           "  if (threadIdx.x == 0) ((" << T << "*)" << e.slot(e.L.out) << ")[o] = acc;\n";
   } else {
-    e.o << "  ((" << T << "*)a.s[" << e.L.out << "])[o] = acc;\n";
+    e.o << "  ((" << T << "*)" << e.slot(e.L.out) << ")[o] = acc;\n";
   }
   e.o << "}\n";
 }
@@ -672,8 +676,8 @@ void gemv_epilogue(Em& e, const std::string& idx, const std::string& acc, const 
   emit_scalar_program(e, g.prog, g.results,
                       [&](const Instr& in, int) {
                         const AccessGroup& ag = g.groups[in.group];
-                        if (ag.structural_zero[0]) return "q" + std::to_string(in.group) + "[0]";
-                        return "q" + std::to_string(in.group) + "[(" + idx + " + " + std::to_string(in.delta[0]) + ") * " + e.coef(in.group, 0) + "]";
+                        if (ag.structural_zero[0]) return e.qp + std::to_string(in.group) + "[0]";
+                        return e.qp + std::to_string(in.group) + "[(" + idx + " + " + std::to_string(in.delta[0]) + ") * " + e.coef(in.group, 0) + "]";
                       },
                       acc, "t", indent);
 }
@@ -692,7 +696,7 @@ void gen_gemv_rowdot(Em& e) {
   e.o << "  const long long am = " << e.coef(g.mat_group, 0) << ", ak = " << (mat_unit ? std::string("1") : e.coef(g.mat_group, 1))
       << ", vk = " << (vec_unit ? std::string("1") : e.coef(g.vec_group, 1)) << ";\n";
   e.o << "  const int lane = threadIdx.x % " << LPR << ", rib = threadIdx.x / " << LPR << ";\n";
-  e.o << "  float* const out = (float*)a.s[" << e.L.out << "];\n";
+  e.o << "  float* const out = (float*)" << e.slot(e.L.out) << ";\n";
   const int CH = LPR * 4;  // k elements per chunk of one row
   // one pass if the whole row fits KV chunks, else loop over groups of KV chunks
   e.o << "  const bool single = K <= " << (long long)CH * KV << ";\n";
@@ -717,6 +721,28 @@ void gen_gemv_rowdot(Em& e) {
   e.o << "      out[row] = t" << g.results[0] << ";\n    }\n  }\n}\n";
 }
 
+// Second stage of the column-accumulate contraction: combines the slab partial vectors in a
+// fixed order (deterministic; the two-kernel reduction of Section 3.2) and applies the epilogue.
+void emit_colacc_combine(Em& e, const std::string& kname) {
+  const GroupPlan& g = e.g;
+  kernel_head(e, kname);
+  e.o << "  const long long M = " << e.S(e.L.extra) << ", SLABS = " << e.S(e.L.extra + 3) << ";\n";
+  e.o << "  const float* const ws = (const float*)" << e.slot(e.L.extra + 2) << ";\n";
+  group_pointers(e, "  ", {g.mat_group, g.vec_group});
+  e.o << "  const int tx = threadIdx.x % 16, sg = threadIdx.x / 16;\n";
+  e.o << "  const long long m = (long long)blockIdx.x * 16 + tx;\n";
+  e.o << "  __shared__ float sm[16][17];\n  float part = 0.0f;\n";
+  e.o << "  if (m < M) {\n    long long s = sg;\n"
+         "    for (; s + 112 < SLABS; s += 128) {\n      float v[8];\n"
+         "#pragma unroll\n      for (int u = 0; u < 8; ++u) v[u] = ws[(s + 16 * u) * M + m];\n"
+         "#pragma unroll\n      for (int u = 0; u < 8; ++u) part += v[u];\n    }\n"
+         "    for (; s < SLABS; s += 16) part += ws[s * M + m];\n  }\n";
+  e.o << "  sm[sg][tx] = part;\n  __syncthreads();\n";
+  e.o << "  if (sg == 0 && m < M) {\n    float acc = sm[0][tx];\n    for (int y = 1; y < 16; ++y) acc += sm[y][tx];\n";
+  gemv_epilogue(e, "m", "acc", "    ");
+  e.o << "    ((float*)" << e.slot(e.L.out) << ")[m] = t" << g.results[0] << ";\n  }\n}\n";
+}
+
 void gen_gemv_colacc(Em& e) {
   const GroupPlan& g = e.g;
   const int BX = g.BX, BY = g.BY, UN = g.unroll;
@@ -726,7 +752,7 @@ void gen_gemv_colacc(Em& e) {
   // stage 1: per-slab partial vectors
   kernel_head(e, kernel_name(g));
   e.o << "  const long long M = " << e.S(e.L.extra) << ", K = " << e.S(e.L.extra + 1) << ", SLABS = " << e.S(e.L.extra + 3) << ";\n";
-  e.o << "  float* const ws = (float*)a.s[" << e.L.extra + 2 << "];\n";
+  e.o << "  float* const ws = (float*)" << e.slot(e.L.extra + 2) << ";\n";
   group_pointers(e, "  ");
   e.o << "  const float* const A = q" << g.mat_group << "; const float* const V = q" << g.vec_group << ";\n";
   e.o << "  const long long ak = " << e.coef(g.mat_group, 1) << ", vk = " << (vec_unit ? std::string("1") : e.coef(g.vec_group, 1)) << ";\n";
@@ -753,23 +779,56 @@ void gen_gemv_colacc(Em& e) {
   e.o << "  for (int j = 0; j < 4; ++j) sm[ty][tx * 4 + j] = acc[j];\n  __syncthreads();\n";
   e.o << "  if (ty == 0) {\n    for (int j = 0; j < 4; ++j) {\n      float t = sm[0][tx * 4 + j];\n      for (int y = 1; y < " << BY << "; ++y) t += sm[y][tx * 4 + j];\n"
          "      if (m0 + j < M) ws[slab * M + m0 + j] = t;\n    }\n  }\n}\n";
-  // stage 2: fixed-order combine of the slab partials, then the epilogue
-  kernel_head(e, kernel_name(g) + "_combine");
-  e.o << "  const long long M = " << e.S(e.L.extra) << ", SLABS = " << e.S(e.L.extra + 3) << ";\n";
-  e.o << "  const float* const ws = (const float*)a.s[" << e.L.extra + 2 << "];\n";
-  group_pointers(e, "  ", {g.mat_group, g.vec_group});
-  e.o << "  const int tx = threadIdx.x % 16, sg = threadIdx.x / 16;\n";
-  e.o << "  const long long m = (long long)blockIdx.x * 16 + tx;\n";
-  e.o << "  __shared__ float sm[16][17];\n  float part = 0.0f;\n";
-  e.o << "  if (m < M) {\n    long long s = sg;\n"
-         "    for (; s + 112 < SLABS; s += 128) {\n      float v[8];\n"
-         "#pragma unroll\n      for (int u = 0; u < 8; ++u) v[u] = ws[(s + 16 * u) * M + m];\n"
-         "#pragma unroll\n      for (int u = 0; u < 8; ++u) part += v[u];\n    }\n"
-         "    for (; s < SLABS; s += 16) part += ws[s * M + m];\n  }\n";
-  e.o << "  sm[sg][tx] = part;\n  __syncthreads();\n";
-  e.o << "  if (sg == 0 && m < M) {\n    float acc = sm[0][tx];\n    for (int y = 1; y < 16; ++y) acc += sm[y][tx];\n";
-  gemv_epilogue(e, "m", "acc", "    ");
-  e.o << "    ((float*)a.s[" << e.L.out << "])[m] = t" << g.results[0] << ";\n  }\n}\n";
+  emit_colacc_combine(e, kernel_name(g) + "_combine");
+}
+
+// Row-dot contraction, its epilogue, and the column-accumulate contraction that consumes the
+// epilogue's result, in one pass over the matrix: a row stays in registers between
+// z = X[i,:].w, r_i = epilogue(z) and g += X[i,:] * r_i.
+void gen_gemv_pair(Em& e, Em& e2) {
+  const GroupPlan& g = e.g;
+  const int LPR = g.LPR, KV = g.KV, RPB = 256 / LPR, CH = LPR * 4;
+  const AccessGroup& mg = g.groups[g.mat_group];
+  const AccessGroup& vg = g.groups[g.vec_group];
+  (void)mg;
+  const bool vec_unit = vg.coef[1] == 1;
+  prelude(e);
+  kernel_head(e, "gr_gemv_pair");
+  e.o << "  const long long M = " << e.S(e.L.extra) << ", K = " << e.S(e.L.extra + 1) << ", SLABS = " << e.S(e.L.extra + 3) << ";\n";
+  e.o << "  float* const ws = (float*)" << e.slot(e.L.extra + 2) << ";\n";
+  group_pointers(e, "  ");
+  e.o << "  const float* const A = q" << g.mat_group << "; const float* const V = q" << g.vec_group << ";\n";
+  e.o << "  const long long am = " << e.coef(g.mat_group, 0) << ", vk = " << (vec_unit ? std::string("1") : e.coef(g.vec_group, 1)) << ";\n";
+  e.o << "  const int lane = threadIdx.x % " << LPR << ", rib = threadIdx.x / " << LPR << ";\n";
+  e.o << "  float* const out = (float*)" << e.slot(e.L.out) << ";\n";
+  e.o << "  const long long rs = ((M + SLABS - 1) / SLABS + " << RPB - 1 << ") / " << RPB << " * " << RPB << ";\n";
+  e.o << "  const long long rbeg = (long long)blockIdx.x * rs, rend = (rbeg + rs < M) ? rbeg + rs : M;\n";
+  e.o << "  float wv[" << KV << "][4], acc[" << KV << "][4];\n";
+  e.o << "#pragma unroll\n  for (int q = 0; q < " << KV << "; ++q) {\n    const long long k0 = (long long)q * " << CH << " + lane * 4;\n"
+         "    for (int j = 0; j < 4; ++j) { wv[q][j] = (k0 + j < K) ? V[(k0 + j) * vk] : 0.0f; acc[q][j] = 0.0f; }\n  }\n";
+  e.o << "  for (long long row = rbeg + rib; row < rend; row += " << RPB << ") {\n";
+  e.o << "    const float* const Ar = A + row * am;\n    float xv[" << KV << "][4];\n";
+  e.o << "#pragma unroll\n    for (int q = 0; q < " << KV << "; ++q) {\n      const long long k0 = (long long)q * " << CH << " + lane * 4;\n"
+         "      if (k0 + 4 <= K) { const f4u w = " << e.ld(g.mat_group, "f4u", "Ar + k0") << "; xv[q][0] = w[0]; xv[q][1] = w[1]; xv[q][2] = w[2]; xv[q][3] = w[3]; }\n"
+         "      else { for (int j = 0; j < 4; ++j) xv[q][j] = (k0 + j < K) ? Ar[k0 + j] : 0.0f; }\n    }\n";
+  e.o << "    float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};\n"
+         "#pragma unroll\n    for (int q = 0; q < " << KV << "; ++q)\n#pragma unroll\n      for (int j = 0; j < 4; ++j) z[j] = __builtin_fmaf(xv[q][j], wv[q][j], z[j]);\n"
+         "    float zz = (z[0] + z[1]) + (z[2] + z[3]);\n";
+  for (int m = LPR / 2; m > 0; m >>= 1) e.o << "    zz += gr_xor(zz, " << m << ");\n";
+  gemv_epilogue(e, "row", "zz", "    ");
+  e.o << "    const float rr = t" << g.results[0] << ";\n    if (lane == 0) out[row] = rr;\n";
+  e.o << "#pragma unroll\n    for (int q = 0; q < " << KV << "; ++q)\n#pragma unroll\n      for (int j = 0; j < 4; ++j) acc[q][j] = __builtin_fmaf(xv[q][j], rr, acc[q][j]);\n  }\n";
+  // lanes with the same position in different row groups of a wave own the same columns
+  e.o << "#pragma unroll\n  for (int q = 0; q < " << KV << "; ++q)\n#pragma unroll\n    for (int j = 0; j < 4; ++j) {\n";
+  for (int m = LPR; m < 64; m <<= 1) e.o << "      acc[q][j] += gr_xor(acc[q][j], " << m << ");\n";
+  e.o << "    }\n";
+  e.o << "  __shared__ float sm[4][" << CH * KV << "];\n";
+  e.o << "  if ((threadIdx.x & 63) < " << LPR << ") {\n#pragma unroll\n    for (int q = 0; q < " << KV << "; ++q)\n      for (int j = 0; j < 4; ++j) sm[threadIdx.x >> 6][q * " << CH << " + lane * 4 + j] = acc[q][j];\n  }\n";
+  e.o << "  __syncthreads();\n";
+  e.o << "  for (int k = threadIdx.x; k < " << CH * KV << "; k += 256)\n    if (k < K) ws[(long long)blockIdx.x * K + k] = ((sm[0][k] + sm[1][k]) + sm[2][k]) + sm[3][k];\n}\n";
+  // second stage with the second sub-graph's epilogue; its argument block follows the first one
+  emit_colacc_combine(e2, "gr_gemv_pair_combine");
+  e.o << e2.o.str();
 }
 
 }  // namespace
@@ -780,7 +839,15 @@ std::string generate_source(const GroupPlan& g) {
     case GroupKind::MAP: gen_map(e); break;
     case GroupKind::ROWRED: gen_rowred(e); break;
     case GroupKind::REDUCE: gen_reduce(e); break;
-    case GroupKind::GEMV: if (g.gemv_mode) gen_gemv_colacc(e); else gen_gemv_rowdot(e); break;
+    case GroupKind::GEMV:
+      if (g.gemv_mode == 2) {
+        Em e2(*g.pair);
+        e2.slot_base = e.L.total;
+        e.total_slots = e2.total_slots = e.L.total + e2.L.total;
+        gen_gemv_pair(e, e2);
+      } else if (g.gemv_mode == 1) gen_gemv_colacc(e);
+      else gen_gemv_rowdot(e);
+      break;
   }
   return e.o.str();
 }

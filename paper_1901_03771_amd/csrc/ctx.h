@@ -28,6 +28,7 @@ struct gr_ctx {
   int64_t opt_map_bx = 0;
   int64_t opt_rowred_threads = 0;
   int64_t opt_gemv_slabs = 0, opt_gemv_unroll = 0;
+  int64_t opt_gemv_pair = 1;
 
   // allocator
   void* (*alloc_fn)(size_t, void*) = nullptr;
@@ -85,7 +86,7 @@ std::string kernel_name(const GroupPlan& g);
 
 // runtime.cpp
 gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out);
-gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr);
+gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr, void* pair_out_ptr);
 gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out);
 
 }  // namespace gr

@@ -161,7 +161,9 @@ struct GroupPlan {
   int red_kept_rank = 0;
 
   // GEMV core
-  int gemv_mode = 0;  // 0: inner stride 1 along k (row-dot); 1: inner stride 1 along m (column-accumulate)
+  int gemv_mode = 0;  // 0: inner stride 1 along k (row-dot); 1: inner stride 1 along m (column-accumulate);
+                      // 2: row-dot fused with the column-accumulate sub-graph in `pair` (one pass over the matrix)
+  std::unique_ptr<GroupPlan> pair;
   int64_t M = 0, K = 0;
   int mat_group = -1, vec_group = -1;
   int LPR = 64;       // gemv row-dot: lanes per row

@@ -94,7 +94,7 @@ gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
   if (c->device >= 0) {
     GR_HIP(c, hipModuleLoadData(&k.module, k.code.data()));
     GR_HIP(c, hipModuleGetFunction(&k.fn, k.module, k.name.c_str()));
-    if (g.kind == GroupKind::GEMV && g.gemv_mode == 1)
+    if (g.kind == GroupKind::GEMV && g.gemv_mode >= 1)
       GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, (k.name + "_combine").c_str()));
   }
   c->stats.compile_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
@@ -125,13 +125,16 @@ static gr_status launch(gr_ctx* c, hipFunction_t fn, const std::string& name, in
   return GR_OK;
 }
 
-gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr) {
-  ArgLayout L = arg_layout(g);
-  std::vector<uint64_t> s(L.total, 0);
+// Fills one sub-graph's block of the kernel argument array.
+// `fresh` / `fresh_ptr`: a node whose buffer is being written by this very launch (the first
+// sub-graph's result inside a fused pair) and therefore has no data pointer yet.
+static gr_status fill_args(gr_ctx* c, const GroupPlan& g, const ArgLayout& L, void* out_ptr, uint64_t* s,
+                           const Node* fresh = nullptr, void* fresh_ptr = nullptr) {
   for (size_t gi = 0; gi < g.groups.size(); ++gi) {
     const AccessGroup& ag = g.groups[gi];
-    if (!ag.leaf->data && ag.leaf->count() > 0) return fail(c, GR_ERR_HIP, "launch: a leaf has no data");
-    s[L.ptr[gi]] = (uint64_t)(uintptr_t)ag.leaf->data;
+    void* data = ag.leaf == fresh ? fresh_ptr : ag.leaf->data;
+    if (!data && ag.leaf->count() > 0) return fail(c, GR_ERR_HIP, "launch: a leaf has no data");
+    s[L.ptr[gi]] = (uint64_t)(uintptr_t)data;
     s[L.base[gi]] = (uint64_t)ag.base;
     for (int k2 = 0; k2 < L.ncoef[gi]; ++k2) s[L.coef[gi] + k2] = (uint64_t)ag.coef[k2];
   }
@@ -143,6 +146,25 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
     else if (cs.dtype == GR_I32) s[L.consts + i] = (uint32_t)(int32_t)(int64_t)cs.value;
     else s[L.consts + i] = (uint64_t)(int64_t)cs.value;
   }
+  return GR_OK;
+}
+
+static gr_status ensure_workspace(gr_ctx* c, size_t need) {
+  if (need <= c->workspace_bytes) return GR_OK;
+  if (c->workspace) ctx_free(c, c->workspace, c->workspace_bytes);
+  c->workspace = ctx_alloc(c, need);
+  c->workspace_bytes = c->workspace ? need : 0;
+  if (!c->workspace) return fail(c, GR_ERR_OOM, "workspace allocation failed");
+  return GR_OK;
+}
+
+gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr, void* pair_out_ptr) {
+  ArgLayout L = arg_layout(g);
+  ArgLayout L2;
+  if (g.pair) L2 = arg_layout(*g.pair);
+  std::vector<uint64_t> s(L.total + (g.pair ? L2.total : 0), 0);
+  gr_status fst = fill_args(c, g, L, out_ptr, s.data());
+  if (fst != GR_OK) return fst;
   int64_t total = 1;
   for (int k2 = 0; k2 < g.rank; ++k2) total *= g.dims[k2];
   switch (g.kind) {
@@ -172,18 +194,32 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       if (g.M == 0) return GR_OK;
       s[L.extra] = (uint64_t)g.M;
       s[L.extra + 1] = (uint64_t)g.K;
+      if (g.gemv_mode == 2) {
+        // one pass over the matrix for both contractions; the second block of arguments is the
+        // column-accumulate sub-graph's (read by the combine kernel)
+        const GroupPlan& p = *g.pair;
+        fst = fill_args(c, p, L2, pair_out_ptr, s.data() + L.total, g.root, out_ptr);
+        if (fst != GR_OK) return fst;
+        gr_status wst = ensure_workspace(c, (size_t)g.slabs * (size_t)g.K * sizeof(float));
+        if (wst != GR_OK) return wst;
+        s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+        s[L.extra + 3] = (uint64_t)g.slabs;
+        uint64_t* s2 = s.data() + L.total;
+        s2[L2.extra] = (uint64_t)p.M;
+        s2[L2.extra + 1] = (uint64_t)p.K;
+        s2[L2.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+        s2[L2.extra + 3] = (uint64_t)g.slabs;
+        gr_status st = launch(c, k->fn, k->name, g.slabs, s);
+        if (st != GR_OK) return st;
+        return launch(c, k->fn2, k->name + "_combine", (p.M + 15) / 16, s);
+      }
       if (g.gemv_mode == 0) {
         int rpb = 256 / g.LPR;
         int64_t grid = std::min<int64_t>((g.M + rpb - 1) / rpb, 256 * 16);
         return launch(c, k->fn, k->name, grid, s);
       }
-      size_t need = (size_t)g.slabs * (size_t)g.M * sizeof(float);
-      if (need > c->workspace_bytes) {
-        if (c->workspace) ctx_free(c, c->workspace, c->workspace_bytes);
-        c->workspace = ctx_alloc(c, need);
-        c->workspace_bytes = c->workspace ? need : 0;
-        if (!c->workspace) return fail(c, GR_ERR_OOM, "workspace allocation failed");
-      }
+      gr_status wst = ensure_workspace(c, (size_t)g.slabs * (size_t)g.M * sizeof(float));
+      if (wst != GR_OK) return wst;
       s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
       s[L.extra + 3] = (uint64_t)g.slabs;
       int64_t ncb = (g.M + (int64_t)g.BX * 4 - 1) / ((int64_t)g.BX * 4);
@@ -212,11 +248,14 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out) {
   if (user_out) {
     uintptr_t olo = (uintptr_t)user_out, ohi = olo + root->count() * itemsize(root->dtype);
     for (const auto& g : plan->groups)
-      for (const Node* l : g->leaves) {
-        if (!l->materialized) continue;
-        uintptr_t lo, hi;
-        extent_of(l, &lo, &hi);
-        if (lo < ohi && olo < hi) return fail(c, GR_ERR_ALIAS, "output buffer overlaps an input of the request");
+      for (const GroupPlan* gp : {g.get(), g->pair.get()}) {
+        if (!gp) continue;
+        for (const Node* l : gp->leaves) {
+          if (!l->materialized) continue;
+          uintptr_t lo, hi;
+          extent_of(l, &lo, &hi);
+          if (lo < ohi && olo < hi) return fail(c, GR_ERR_ALIAS, "output buffer overlaps an input of the request");
+        }
       }
   }
   c->stats.materialize_calls++;
@@ -225,31 +264,47 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out) {
     gr_ctx::Kernel* k = nullptr;
     gr_status st = compile_group(c, g, &k);
     if (st != GR_OK) return st;
-    Node* r = g.root;
-    void* out = nullptr;
-    size_t bytes = (size_t)r->count() * itemsize(r->dtype);
-    bool own = false;
-    if (r == root && user_out) out = user_out;
-    else {
-      out = ctx_alloc(c, bytes);
-      if (!out) return fail(c, GR_ERR_OOM, "allocator returned NULL");
-      own = true;
+    // output buffers: the caller's for the requested root, the allocator's otherwise
+    Node* roots[2] = {g.root, g.pair ? g.pair->root : nullptr};
+    void* outs[2] = {nullptr, nullptr};
+    size_t nbytes[2] = {0, 0};
+    bool own[2] = {false, false};
+    for (int q = 0; q < 2 && roots[q]; ++q) {
+      nbytes[q] = (size_t)roots[q]->count() * itemsize(roots[q]->dtype);
+      if (roots[q] == root && user_out) outs[q] = user_out;
+      else {
+        outs[q] = ctx_alloc(c, nbytes[q]);
+        if (!outs[q]) { if (q == 1 && own[0]) ctx_free(c, outs[0], nbytes[0]); return fail(c, GR_ERR_OOM, "allocator returned NULL"); }
+        own[q] = true;
+      }
     }
-    st = launch_group(c, g, k, out);
-    if (st != GR_OK) { if (own) ctx_free(c, out, bytes); return st; }
-    c->stats.groups_executed++;
-    if (r->materialized) continue;  // a plain copy of an array that already had data
-    // the node now has data and stays materialised; its predecessors are no longer needed
-    r->data = out;
-    r->owns_data = own;
-    r->alloc_bytes = own ? bytes : 0;
-    r->offset = 0;
-    int64_t sstride = 1;
-    for (int d = r->ndim - 1; d >= 0; --d) { r->strides[d] = sstride; sstride *= r->shape[d]; }
-    r->materialized = true;
-    r->planned = false;
+    st = launch_group(c, g, k, outs[0], outs[1]);
+    if (st != GR_OK) {
+      for (int q = 0; q < 2; ++q) if (own[q]) ctx_free(c, outs[q], nbytes[q]);
+      return st;
+    }
+    c->stats.groups_executed += g.pair ? 2 : 1;
+    for (int q = 0; q < 2 && roots[q]; ++q) {
+      Node* r = roots[q];
+      if (r->materialized) continue;  // a plain copy of an array that already had data
+      // the node now has data and stays materialised (Section 2)
+      r->data = outs[q];
+      r->owns_data = own[q];
+      r->alloc_bytes = own[q] ? nbytes[q] : 0;
+      r->offset = 0;
+      int64_t sstride = 1;
+      for (int d = r->ndim - 1; d >= 0; --d) { r->strides[d] = sstride; sstride *= r->shape[d]; }
+      r->materialized = true;
+      r->planned = false;
+    }
   }
-  for (auto& gp : plan->groups) drop_inputs(c, gp->root);
+  // Predecessors of materialised nodes are no longer needed.  Roots are visited in execution
+  // (topological) order: dropping a root's inputs can only free nodes upstream of it, which
+  // includes earlier roots that nothing else refers to, never a root still to be visited.
+  for (auto& gp : plan->groups) {
+    drop_inputs(c, gp->root);
+    if (gp->pair) drop_inputs(c, gp->pair->root);
+  }
   return GR_OK;
 }
 

@@ -243,6 +243,34 @@ def test_dot_variants(env):
         assert_reduction(got, ref, what=what)
 
 
+def test_gemv_pair_matches_two_pass_execution(env):
+    gr, ctx, torch = env
+    ctx2 = gr.Context()
+    ctx2.set_option("gemv_pair", 0)
+    for rows, cols in [(3001, 200), (1000, 1030), (77, 512), (5000, 6)]:
+        arrays = wl.make_inputs("logreg", rows=rows, cols=cols)
+        keep = {k: torch.from_numpy(v).cuda() for k, v in arrays.items()}
+        s0, t0 = ctx.stats(), ctx2.stats()
+        one = wl.logreg(gr, **{k: ctx.array(t) for k, t in keep.items()}).numpy()
+        two = wl.logreg(gr, **{k: ctx2.array(t) for k, t in keep.items()}).numpy()
+        assert ctx.stats()["kernel_launches"] - s0["kernel_launches"] == 2   # fused pass + combine
+        assert ctx2.stats()["kernel_launches"] - t0["kernel_launches"] == 3  # row-dot, column-accumulate, combine
+        ref = wl.logreg(ora, **{k: ora.array(v) for k, v in arrays.items()}).numpy()
+        assert_reduction(one, ref, what=f"fused pair {rows}x{cols}")
+        assert_reduction(two, ref, what=f"two passes {rows}x{cols}")
+    # the intermediate r stays a materialised node either way
+    arrays = wl.make_inputs("logreg", rows=300, cols=40)
+    keep = {k: torch.from_numpy(v).cuda() for k, v in arrays.items()}
+    X, w, y = (ctx.array(keep[k]) for k in ("X", "w", "y"))
+    r = 1.0 / (1.0 + gr.exp(-(X @ w))) - y
+    out = w - 0.1 * ((X.T @ r) / 300 + 1e-4 * w)
+    out.materialize()
+    assert r.is_materialized and out.is_materialized
+    r_ref = (1.0 / (1.0 + ora.exp(-(ora.array(arrays["X"]) @ ora.array(arrays["w"])))) - ora.array(arrays["y"])).numpy()
+    assert_reduction(r.numpy(), r_ref, what="residual written by the fused pass")
+    ctx2.close()
+
+
 def test_mnist_listing2(env):
     g = np.random.default_rng(37)
     arrays = dict(W=g.standard_normal((200, 10)).astype(f32), a=g.standard_normal(200).astype(f32), b=g.standard_normal(10).astype(f32))

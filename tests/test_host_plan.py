@@ -159,6 +159,7 @@ def test_five_configurations_partition_as_designed(ctx):
     c4 = wl.stencil(gr, ctx.spec((8192, 8192)))
     g4 = groups(c4)
     assert len(g4) == 1 and g4[0][0] == "MAP" and "loads=13" in c4.plan()  # the radius-2 diamond of 13 input points
+    ctx.set_option("gemv_pair", 0)
     c5 = wl.logreg(gr, ctx.spec((262144, 512)), ctx.spec((512,)), ctx.spec((262144,)))
     g5 = groups(c5)
     assert [k for k, _ in g5] == ["GEMV", "GEMV"]
@@ -166,6 +167,15 @@ def test_five_configurations_partition_as_designed(ctx):
     assert g5[1][1] == ["dot", "div", "mul", "add", "mul", "sub"]       # X.T@r with the update epilogue
     plan = c5.plan().splitlines()
     assert "row-dot" in plan[0] and "column-accumulate" in plan[1]
+    # by default the two contractions share one pass over X: one kernel group, both sub-graphs listed
+    ctx.set_option("gemv_pair", 1)
+    plan = c5.plan().splitlines()
+    assert len(plan) == 1 and "row-dot+column-accumulate" in plan[0]
+    fused = re.search(r"fused-with=\[root=\d+ members=\[(.*?)\]\]", plan[0]).group(1)
+    assert [m.split(":")[1] for m in fused.split(",")] == ["dot", "div", "mul", "add", "mul", "sub"]
+    # rows too long to stay in registers: two passes
+    far = wl.logreg(gr, ctx.spec((4096, 3000)), ctx.spec((3000,)), ctx.spec((4096,)))
+    assert len(far.plan().splitlines()) == 2
 
 
 def test_jacobi_slices_fuse_into_one_kernel(ctx):
