@@ -102,8 +102,8 @@ struct Em {
 
   // *(const T*)(addr), with the non-temporal hint where the group streams
   std::string ld(int group, const std::string& type, const std::string& addr) const {
-    if (nontemporal_group(g, group)) return "__builtin_nontemporal_load((const " + type + "*)(" + addr + "))";
-    return "*(const " + type + "*)(" + addr + ")";
+    if (nontemporal_group(g, group)) return "__builtin_nontemporal_load((const GM " + type + "*)(" + addr + "))";
+    return "*(const GM " + type + "*)(" + addr + ")";
   }
 
   std::string S(int n) const { return "((long long)" + slot(n) + ")"; }
@@ -171,7 +171,10 @@ struct Em {
 };
 
 void prelude(Em& e) {
-  e.o << "typedef float f4 __attribute__((ext_vector_type(4)));\n"
+  // every pointer the kernels dereference is a global-memory pointer (arguments arrive as
+  // integers, so the address space has to be stated for global_load/global_store to be used)
+  e.o << "#define GM __attribute__((address_space(1)))\n"
+         "typedef float f4 __attribute__((ext_vector_type(4)));\n"
          "typedef f4 f4u __attribute__((aligned(4)));\n"
          "typedef float f2 __attribute__((ext_vector_type(2)));\n"
          "typedef f2 f2u __attribute__((aligned(4)));\n"
@@ -251,7 +254,7 @@ void group_pointers(Em& e, const std::string& indent, const std::vector<int>& sk
   for (size_t gi = 0; gi < e.g.groups.size(); ++gi) {
     if (std::find(skip.begin(), skip.end(), (int)gi) != skip.end()) continue;
     const AccessGroup& ag = e.g.groups[gi];
-    e.o << indent << "const " << cty(ag.dtype) << "* const " << e.qp << gi << " = (const " << cty(ag.dtype) << "*)" << e.slot(e.L.ptr[gi])
+    e.o << indent << "const GM " << cty(ag.dtype) << "* const " << e.qp << gi << " = (const GM " << cty(ag.dtype) << "*)" << e.slot(e.L.ptr[gi])
         << " + " << e.S(e.L.base[gi]) << ";\n";
   }
 }
@@ -267,28 +270,29 @@ void gen_map(Em& e) {
   kernel_head(e, kernel_name(g));
   e.o << "  const long long C = " << e.dim(cd) << ";\n";
   e.o << "  const long long R = " << (rank >= 2 ? e.dim(rd) : std::string("1")) << ";\n";
-  e.o << "  const long long nbx = (C + " << TC - 1 << ") / " << TC << ", nby = (R + " << TR - 1 << ") / " << TR << ";\n";
-  e.o << "  long long tile = blockIdx.x;\n";
+  // tile bookkeeping in 32-bit unsigned arithmetic (the grid has fewer than 2^31 tiles)
+  e.o << "  const unsigned nbx = (unsigned)((C + " << TC - 1 << ") / " << TC << "), nby = (unsigned)((R + " << TR - 1 << ") / " << TR << ");\n";
+  e.o << "  unsigned tile = blockIdx.x;\n";
   if (g.xcd_remap) {
     // consecutive tiles go to the same XCD (workgroups are dealt round-robin over the 8 XCDs),
     // so tiles that share halo rows also share an L2
-    e.o << "  { long long outer = 1;\n";
-    for (int k = 0; k + 2 < rank; ++k) e.o << "    outer *= " << e.dim(k) << ";\n";
-    e.o << "    const long long ntiles = nbx * nby * outer, per = (ntiles + 7) / 8;\n"
-           "    tile = (long long)(blockIdx.x % 8) * per + blockIdx.x / 8;\n"
+    e.o << "  { unsigned outer = 1;\n";
+    for (int k = 0; k + 2 < rank; ++k) e.o << "    outer *= (unsigned)" << e.dim(k) << ";\n";
+    e.o << "    const unsigned ntiles = nbx * nby * outer, per = (ntiles + 7) / 8;\n"
+           "    tile = (blockIdx.x % 8) * per + blockIdx.x / 8;\n"
            "    if (tile >= ntiles) return; }\n";
   }
-  e.o << "  const long long bx = tile % nbx, t2 = tile / nbx, by = t2 % nby, olin = t2 / nby;\n";
+  e.o << "  const unsigned bx = tile % nbx, t2 = tile / nbx, by = t2 % nby, olin = t2 / nby;\n";
   if (rank > 2) {
-    e.o << "  long long orem = olin;\n";
-    for (int k = rank - 3; k >= 0; --k) e.o << "  const long long i" << k << " = orem % " << e.dim(k) << "; orem /= " << e.dim(k) << ";\n";
+    e.o << "  unsigned orem = olin;\n";
+    for (int k = rank - 3; k >= 0; --k) e.o << "  const long long i" << k << " = orem % (unsigned)" << e.dim(k) << "; orem /= (unsigned)" << e.dim(k) << ";\n";
   }
   e.o << "  const int tx = threadIdx.x % " << g.BX << ", ty = threadIdx.x / " << g.BX << ";\n";
-  e.o << "  const long long r0 = by * " << TR << " + ty * " << g.VR << ", c0 = bx * " << TC << " + tx * 4;\n";
+  e.o << "  const long long r0 = (long long)by * " << TR << " + ty * " << g.VR << ", c0 = (long long)bx * " << TC << " + tx * 4;\n";
   group_pointers(e, "  ");
   for (size_t gi = 0; gi < g.groups.size(); ++gi) {
     const AccessGroup& ag = g.groups[gi];
-    e.o << "  const " << cty(ag.dtype) << "* const p" << gi << " = q" << gi;
+    e.o << "  const GM " << cty(ag.dtype) << "* const p" << gi << " = q" << gi;
     for (int k = 0; k + 2 < rank; ++k) if (!ag.structural_zero[k]) e.o << " + i" << k << " * " << e.coef((int)gi, k);
     if (rank >= 2 && !ag.structural_zero[rd]) e.o << " + r0 * " << e.coef((int)gi, rd);
     char cc = access_class(ag, cd);
@@ -296,7 +300,7 @@ void gen_map(Em& e) {
     else if (cc == 'G') e.o << " + c0 * " << e.coef((int)gi, cd);
     e.o << ";\n";
   }
-  e.o << "  " << cty(g.out_dtype) << "* const po = (" << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << " + (olin * R + r0) * C + c0;\n";
+  e.o << "  GM " << cty(g.out_dtype) << "* const po = (GM " << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << " + ((long long)olin * R + r0) * C + c0;\n";
 
   // static part of a load's address: shifts times runtime coefficients
   auto shift_expr = [&](const Instr& in, bool with_col) {
@@ -386,7 +390,7 @@ void gen_map(Em& e) {
         } else {
           const char* vt = g.out_dtype == GR_F32 ? "f4u" : "i4u";
           e.o << "    { " << vt << " ov; ov[0] = t" << g.results[ri] << "; ov[1] = t" << g.results[ri + 1] << "; ov[2] = t" << g.results[ri + 2]
-              << "; ov[3] = t" << g.results[ri + 3] << "; *(" << vt << "*)(po + " << off << ") = ov; }\n";
+              << "; ov[3] = t" << g.results[ri + 3] << "; *(GM " << vt << "*)(po + " << off << ") = ov; }\n";
         }
         ri += 4;
       }
@@ -468,7 +472,7 @@ void gen_rowred(Em& e) {
   group_pointers(e, "  ");
   for (size_t gi = 0; gi < g.groups.size(); ++gi) {
     const AccessGroup& ag = g.groups[gi];
-    e.o << "  const " << cty(ag.dtype) << "* const p" << gi << " = q" << gi;
+    e.o << "  const GM " << cty(ag.dtype) << "* const p" << gi << " = q" << gi;
     for (int k = 0; k < cd; ++k) if (!ag.structural_zero[k]) e.o << " + i" << k << " * " << e.coef((int)gi, k);
     e.o << ";\n";
   }
@@ -523,13 +527,13 @@ void gen_rowred(Em& e) {
       e.o << ";\n";
     }
     if (final_stage && g.out_per_row) {
-      e.o << "  if (lane == 0 && row_ok) ((" << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << ")[row] = " << name(g.results[0], false) << ";\n";
+      e.o << "  if (lane == 0 && row_ok) ((GM " << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << ")[row] = " << name(g.results[0], false) << ";\n";
       break;
     }
     const Phase* ph = final_stage ? nullptr : &g.phases[s];
     if (ph) e.o << "  " << cty(ph->out_dtype) << " acc" << s << " = " << Em::identity(*ph) << ";\n";
     if (final_stage)
-      e.o << "  " << cty(g.out_dtype) << "* const po = (" << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << " + row * C;\n";
+      e.o << "  GM " << cty(g.out_dtype) << "* const po = (GM " << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << " + row * C;\n";
     bool any_elem = false;
     for (int i : stage_instrs[s]) if (!g.prog[i].uniform) any_elem = true;
     int want = ph ? ph->value : g.results[0];
@@ -587,8 +591,8 @@ void gen_rowred(Em& e) {
       e.o << "    }\n";
       if (final_stage && g.out_dtype != GR_I64) {
         const char* vt = g.out_dtype == GR_F32 ? "f4u" : "i4u";
-        if (guarded) e.o << "    if (row_ok) { if (c + 4 <= C) *(" << vt << "*)(po + c) = ov; else { for (int j = 0; j < 4; ++j) if (c + j < C) po[c + j] = ov[j]; } }\n";
-        else e.o << "    if (row_ok) *(" << vt << "*)(po + c) = ov;\n";
+        if (guarded) e.o << "    if (row_ok) { if (c + 4 <= C) *(GM " << vt << "*)(po + c) = ov; else { for (int j = 0; j < 4; ++j) if (c + j < C) po[c + j] = ov[j]; } }\n";
+        else e.o << "    if (row_ok) *(GM " << vt << "*)(po + c) = ov;\n";
       }
       e.o << "  }\n";
     }
@@ -626,7 +630,7 @@ void gen_reduce(Em& e) {
   group_pointers(e, "  ");
   for (size_t gi = 0; gi < g.groups.size(); ++gi) {
     const AccessGroup& ag = g.groups[gi];
-    e.o << "  const " << cty(ag.dtype) << "* const p" << gi << " = q" << gi;
+    e.o << "  const GM " << cty(ag.dtype) << "* const p" << gi << " = q" << gi;
     for (int k = 0; k < kr; ++k) if (!ag.structural_zero[k]) e.o << " + i" << k << " * " << e.coef((int)gi, k);
     e.o << ";\n";
   }
@@ -661,9 +665,9 @@ void gen_reduce(Em& e) {
            "    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;\n"
            "    __syncthreads();\n"
            "    acc = gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])); }\n"
-           "  if (threadIdx.x == 0) ((" << T << "*)" << e.slot(e.L.out) << ")[o] = acc;\n";
+           "  if (threadIdx.x == 0) ((GM " << T << "*)" << e.slot(e.L.out) << ")[o] = acc;\n";
   } else {
-    e.o << "  ((" << T << "*)" << e.slot(e.L.out) << ")[o] = acc;\n";
+    e.o << "  ((GM " << T << "*)" << e.slot(e.L.out) << ")[o] = acc;\n";
   }
   e.o << "}\n";
 }
@@ -692,11 +696,11 @@ void gen_gemv_rowdot(Em& e) {
   kernel_head(e, kernel_name(g));
   e.o << "  const long long M = " << e.S(e.L.extra) << ", K = " << e.S(e.L.extra + 1) << ";\n";
   group_pointers(e, "  ");
-  e.o << "  const float* const A = q" << g.mat_group << "; const float* const V = q" << g.vec_group << ";\n";
+  e.o << "  const GM float* const A = q" << g.mat_group << "; const GM float* const V = q" << g.vec_group << ";\n";
   e.o << "  const long long am = " << e.coef(g.mat_group, 0) << ", ak = " << (mat_unit ? std::string("1") : e.coef(g.mat_group, 1))
       << ", vk = " << (vec_unit ? std::string("1") : e.coef(g.vec_group, 1)) << ";\n";
   e.o << "  const int lane = threadIdx.x % " << LPR << ", rib = threadIdx.x / " << LPR << ";\n";
-  e.o << "  float* const out = (float*)" << e.slot(e.L.out) << ";\n";
+  e.o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
   const int CH = LPR * 4;  // k elements per chunk of one row
   // one pass if the whole row fits KV chunks, else loop over groups of KV chunks
   e.o << "  const bool single = K <= " << (long long)CH * KV << ";\n";
@@ -704,7 +708,7 @@ void gen_gemv_rowdot(Em& e) {
   e.o << "  if (single) {\n#pragma unroll\n    for (int q = 0; q < " << KV << "; ++q) {\n      const long long k0 = (long long)q * " << CH << " + lane * 4;\n";
   e.o << "      for (int j = 0; j < 4; ++j) wv[q][j] = (k0 + j < K) ? V[(k0 + j) * vk] : 0.0f;\n    }\n  }\n";
   e.o << "  for (long long row = (long long)blockIdx.x * " << RPB << " + rib; row < M; row += (long long)gridDim.x * " << RPB << ") {\n";
-  e.o << "    const float* const Ar = A + row * am;\n    float acc = 0.0f;\n";
+  e.o << "    const GM float* const Ar = A + row * am;\n    float acc = 0.0f;\n";
   e.o << "    if (single) {\n";
   e.o << "      float xv[" << KV << "][4];\n#pragma unroll\n      for (int q = 0; q < " << KV << "; ++q) {\n        const long long k0 = (long long)q * " << CH << " + lane * 4;\n";
   if (mat_unit)
@@ -727,7 +731,7 @@ void emit_colacc_combine(Em& e, const std::string& kname) {
   const GroupPlan& g = e.g;
   kernel_head(e, kname);
   e.o << "  const long long M = " << e.S(e.L.extra) << ", SLABS = " << e.S(e.L.extra + 3) << ";\n";
-  e.o << "  const float* const ws = (const float*)" << e.slot(e.L.extra + 2) << ";\n";
+  e.o << "  const GM float* const ws = (const GM float*)" << e.slot(e.L.extra + 2) << ";\n";
   group_pointers(e, "  ", {g.mat_group, g.vec_group});
   e.o << "  const int tx = threadIdx.x % 16, sg = threadIdx.x / 16;\n";
   e.o << "  const long long m = (long long)blockIdx.x * 16 + tx;\n";
@@ -740,7 +744,7 @@ void emit_colacc_combine(Em& e, const std::string& kname) {
   e.o << "  sm[sg][tx] = part;\n  __syncthreads();\n";
   e.o << "  if (sg == 0 && m < M) {\n    float acc = sm[0][tx];\n    for (int y = 1; y < 16; ++y) acc += sm[y][tx];\n";
   gemv_epilogue(e, "m", "acc", "    ");
-  e.o << "    ((float*)" << e.slot(e.L.out) << ")[m] = t" << g.results[0] << ";\n  }\n}\n";
+  e.o << "    ((GM float*)" << e.slot(e.L.out) << ")[m] = t" << g.results[0] << ";\n  }\n}\n";
 }
 
 void gen_gemv_colacc(Em& e) {
@@ -752,9 +756,9 @@ void gen_gemv_colacc(Em& e) {
   // stage 1: per-slab partial vectors
   kernel_head(e, kernel_name(g));
   e.o << "  const long long M = " << e.S(e.L.extra) << ", K = " << e.S(e.L.extra + 1) << ", SLABS = " << e.S(e.L.extra + 3) << ";\n";
-  e.o << "  float* const ws = (float*)" << e.slot(e.L.extra + 2) << ";\n";
+  e.o << "  GM float* const ws = (GM float*)" << e.slot(e.L.extra + 2) << ";\n";
   group_pointers(e, "  ");
-  e.o << "  const float* const A = q" << g.mat_group << "; const float* const V = q" << g.vec_group << ";\n";
+  e.o << "  const GM float* const A = q" << g.mat_group << "; const GM float* const V = q" << g.vec_group << ";\n";
   e.o << "  const long long ak = " << e.coef(g.mat_group, 1) << ", vk = " << (vec_unit ? std::string("1") : e.coef(g.vec_group, 1)) << ";\n";
   e.o << "  const int tx = threadIdx.x % " << BX << ", ty = threadIdx.x / " << BX << ";\n";
   e.o << "  const long long ncb = (M + " << BX * 4 - 1 << ") / " << BX * 4 << ";\n";
@@ -769,7 +773,7 @@ void gen_gemv_colacc(Em& e) {
          "#pragma unroll\n      for (int u = 0; u < " << UN << "; ++u) { x[u] = " << e.ld(g.mat_group, "f4u", "A + (k + u * " + std::to_string(BY) + ") * ak + m0") << "; s[u] = V[(k + u * " << BY << ") * vk]; }\n"
          "#pragma unroll\n      for (int u = 0; u < " << UN << "; ++u) { acc[0] = __builtin_fmaf(x[u][0], s[u], acc[0]); acc[1] = __builtin_fmaf(x[u][1], s[u], acc[1]); acc[2] = __builtin_fmaf(x[u][2], s[u], acc[2]); acc[3] = __builtin_fmaf(x[u][3], s[u], acc[3]); }\n"
          "    }\n"
-         "    for (; k < kend; k += " << BY << ") { const f4u x = *(const f4u*)(A + k * ak + m0); const float s = V[k * vk];\n"
+         "    for (; k < kend; k += " << BY << ") { const f4u x = *(const GM f4u*)(A + k * ak + m0); const float s = V[k * vk];\n"
          "      acc[0] = __builtin_fmaf(x[0], s, acc[0]); acc[1] = __builtin_fmaf(x[1], s, acc[1]); acc[2] = __builtin_fmaf(x[2], s, acc[2]); acc[3] = __builtin_fmaf(x[3], s, acc[3]); }\n"
          "  } else {\n"
          "    for (long long k = kbeg + ty; k < kend; k += " << BY << ") { const float s = V[k * vk];\n"
@@ -795,19 +799,19 @@ void gen_gemv_pair(Em& e, Em& e2) {
   prelude(e);
   kernel_head(e, "gr_gemv_pair");
   e.o << "  const long long M = " << e.S(e.L.extra) << ", K = " << e.S(e.L.extra + 1) << ", SLABS = " << e.S(e.L.extra + 3) << ";\n";
-  e.o << "  float* const ws = (float*)" << e.slot(e.L.extra + 2) << ";\n";
+  e.o << "  GM float* const ws = (GM float*)" << e.slot(e.L.extra + 2) << ";\n";
   group_pointers(e, "  ");
-  e.o << "  const float* const A = q" << g.mat_group << "; const float* const V = q" << g.vec_group << ";\n";
+  e.o << "  const GM float* const A = q" << g.mat_group << "; const GM float* const V = q" << g.vec_group << ";\n";
   e.o << "  const long long am = " << e.coef(g.mat_group, 0) << ", vk = " << (vec_unit ? std::string("1") : e.coef(g.vec_group, 1)) << ";\n";
   e.o << "  const int lane = threadIdx.x % " << LPR << ", rib = threadIdx.x / " << LPR << ";\n";
-  e.o << "  float* const out = (float*)" << e.slot(e.L.out) << ";\n";
+  e.o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
   e.o << "  const long long rs = ((M + SLABS - 1) / SLABS + " << RPB - 1 << ") / " << RPB << " * " << RPB << ";\n";
   e.o << "  const long long rbeg = (long long)blockIdx.x * rs, rend = (rbeg + rs < M) ? rbeg + rs : M;\n";
   e.o << "  float wv[" << KV << "][4], acc[" << KV << "][4];\n";
   e.o << "#pragma unroll\n  for (int q = 0; q < " << KV << "; ++q) {\n    const long long k0 = (long long)q * " << CH << " + lane * 4;\n"
          "    for (int j = 0; j < 4; ++j) { wv[q][j] = (k0 + j < K) ? V[(k0 + j) * vk] : 0.0f; acc[q][j] = 0.0f; }\n  }\n";
   e.o << "  for (long long row = rbeg + rib; row < rend; row += " << RPB << ") {\n";
-  e.o << "    const float* const Ar = A + row * am;\n    float xv[" << KV << "][4];\n";
+  e.o << "    const GM float* const Ar = A + row * am;\n    float xv[" << KV << "][4];\n";
   e.o << "#pragma unroll\n    for (int q = 0; q < " << KV << "; ++q) {\n      const long long k0 = (long long)q * " << CH << " + lane * 4;\n"
          "      if (k0 + 4 <= K) { const f4u w = " << e.ld(g.mat_group, "f4u", "Ar + k0") << "; xv[q][0] = w[0]; xv[q][1] = w[1]; xv[q][2] = w[2]; xv[q][3] = w[3]; }\n"
          "      else { for (int j = 0; j < 4; ++j) xv[q][j] = (k0 + j < K) ? Ar[k0 + j] : 0.0f; }\n    }\n";
