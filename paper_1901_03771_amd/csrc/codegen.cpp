@@ -621,10 +621,18 @@ void gen_reduce(Em& e) {
   const char* T = cty(ph.out_dtype);
   prelude(e);
   phase_helpers(e, 0, 64);
+  // Stage 1 (Section 3.2: map fused with a per-block combine): every output's reduced range is
+  // cut into NSPLIT chunks; a thread (mode 0) or a workgroup (mode 1) combines one chunk.
   kernel_head(e, kernel_name(g));
-  e.o << "  const long long NOUT = " << e.S(e.L.extra) << ", LEN = " << e.S(e.L.extra + 1) << ";\n";
-  if (g.red_mode == 0) e.o << "  const long long o = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (o >= NOUT) return;\n";
-  else e.o << "  const long long o = blockIdx.x;\n  __shared__ long long gr_sm[4];\n";
+  e.o << "  const long long NOUT = " << e.S(e.L.extra) << ", LEN = " << e.S(e.L.extra + 1) << ", NSPLIT = " << e.S(e.L.extra + 3) << ";\n";
+  if (g.red_mode == 0) {
+    e.o << "  const long long blocks_o = (NOUT + 255) / 256;\n"
+           "  const long long o = (long long)(blockIdx.x % blocks_o) * 256 + threadIdx.x, split = blockIdx.x / blocks_o;\n"
+           "  if (o >= NOUT) return;\n";
+  } else {
+    e.o << "  const long long o = blockIdx.x % NOUT, split = blockIdx.x / NOUT;\n  __shared__ long long gr_sm[4];\n";
+  }
+  e.o << "  const long long chunk = (LEN + NSPLIT - 1) / NSPLIT, jbeg = split * chunk, jend = (jbeg + chunk < LEN) ? jbeg + chunk : LEN;\n";
   e.o << "  long long orem = o;\n";
   for (int k = kr - 1; k >= 0; --k) e.o << "  const long long i" << k << " = orem % " << e.dim(k) << "; orem /= " << e.dim(k) << ";\n";
   group_pointers(e, "  ");
@@ -635,8 +643,8 @@ void gen_reduce(Em& e) {
     e.o << ";\n";
   }
   e.o << "  " << T << " acc = " << Em::identity(ph) << ";\n";
-  if (g.red_mode == 0) e.o << "  for (long long j = 0; j < LEN; ++j) {\n";
-  else e.o << "  for (long long j = threadIdx.x; j < LEN; j += 256) {\n";
+  if (g.red_mode == 0) e.o << "#pragma unroll 4\n  for (long long j = jbeg; j < jend; ++j) {\n";
+  else e.o << "#pragma unroll 4\n  for (long long j = jbeg + threadIdx.x; j < jend; j += 256) {\n";
   if (rank > kr) {
     e.o << "    long long jrem = j;\n";
     for (int k = rank - 1; k >= kr; --k) {
@@ -659,17 +667,39 @@ void gen_reduce(Em& e) {
                       },
                       "0.0f", "t", "    ");
   e.o << "    acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n  }\n";
+  e.o << "  GM " << T << "* const dst = NSPLIT > 1 ? (GM " << T << "*)" << e.slot(e.L.extra + 2) << " + split * NOUT : (GM " << T << "*)" << e.slot(e.L.out) << ";\n";
   if (g.red_mode == 1) {
     e.o << "  acc = gr_lanes0(acc);\n"
            "  { " << T << "* sm = (" << T << "*)gr_sm;\n"
            "    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;\n"
            "    __syncthreads();\n"
            "    acc = gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])); }\n"
-           "  if (threadIdx.x == 0) ((GM " << T << "*)" << e.slot(e.L.out) << ")[o] = acc;\n";
+           "  if (threadIdx.x == 0) dst[o] = acc;\n";
   } else {
-    e.o << "  ((GM " << T << "*)" << e.slot(e.L.out) << ")[o] = acc;\n";
+    e.o << "  dst[o] = acc;\n";
   }
   e.o << "}\n";
+  // Stage 2 (Section 3.2: "a separate kernel ... only uses the binary operation"): combines the
+  // NSPLIT partial results of every output in a fixed order.
+  kernel_head(e, kernel_name(g) + "_combine");
+  e.o << "  const long long NOUT = " << e.S(e.L.extra) << ", NSPLIT = " << e.S(e.L.extra + 3) << ";\n";
+  e.o << "  const GM " << T << "* const ws = (const GM " << T << "*)" << e.slot(e.L.extra + 2) << ";\n";
+  e.o << "  GM " << T << "* const out = (GM " << T << "*)" << e.slot(e.L.out) << ";\n";
+  e.o << "  __shared__ long long gr_sm[4];\n";
+  e.o << "  if (NOUT >= 1024) {\n"
+         "    const long long o = (long long)blockIdx.x * 256 + threadIdx.x;\n"
+         "    if (o < NOUT) {\n      " << T << " acc = ws[o];\n"
+         "      for (long long s = 1; s < NSPLIT; ++s) acc = gr_comb0(acc, ws[s * NOUT + o]);\n"
+         "      out[o] = acc;\n    }\n"
+         "  } else {\n"
+         "    const long long o = blockIdx.x;\n    " << T << " acc = " << Em::identity(ph) << ";\n"
+         "    for (long long s = threadIdx.x; s < NSPLIT; s += 256) acc = gr_comb0(acc, ws[s * NOUT + o]);\n"
+         "    acc = gr_lanes0(acc);\n"
+         "    " << T << "* sm = (" << T << "*)gr_sm;\n"
+         "    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;\n"
+         "    __syncthreads();\n"
+         "    if (threadIdx.x == 0) out[o] = gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3]));\n"
+         "  }\n}\n";
 }
 
 // ---- GEMV -----------------------------------------------------------------------

@@ -669,7 +669,19 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
         // nothing left to reduce after dropping extent-1 dims: treat the single point as the reduced range
         g->red_len = 1;
       }
-      g->red_mode = g->red_out >= 4096 ? 0 : 1;
+      // mode 0 (a thread per output) when consecutive outputs are consecutive in memory, mode 1
+      // (a workgroup per output, lanes along the reduced range) when the reduced range is
+      bool kept_unit = false, red_unit = false;
+      for (const AccessGroup& ag : g->groups) {
+        if (kept_rank > 0 && ag.coef[kept_rank - 1] == 1) kept_unit = true;
+        if (g->rank > kept_rank && ag.coef[g->rank - 1] == 1) red_unit = true;
+      }
+      g->red_mode = (kept_unit && !red_unit) ? 0 : ((red_unit && !kept_unit) ? 1 : (g->red_out >= 4096 ? 0 : 1));
+      // split the reduced range so that about 2048 workgroups run (two-stage reduction, Section 3.2)
+      int64_t units = g->red_mode == 0 ? (g->red_out + 255) / 256 : g->red_out;
+      int64_t min_chunk = g->red_mode == 0 ? 64 : 256 * 16;
+      int64_t nsplit = std::min<int64_t>(std::max<int64_t>(1, 2048 / std::max<int64_t>(units, 1)), std::max<int64_t>(1, g->red_len / min_chunk));
+      g->slabs = (int)std::min<int64_t>(nsplit, 4096);
     } else {
       // ---- row-resident reductions fused with producers and consumers -----
       g->kind = GroupKind::ROWRED;

@@ -94,7 +94,7 @@ gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
   if (c->device >= 0) {
     GR_HIP(c, hipModuleLoadData(&k.module, k.code.data()));
     GR_HIP(c, hipModuleGetFunction(&k.fn, k.module, k.name.c_str()));
-    if (g.kind == GroupKind::GEMV && g.gemv_mode >= 1)
+    if ((g.kind == GroupKind::GEMV && g.gemv_mode >= 1) || g.kind == GroupKind::REDUCE)
       GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, (k.name + "_combine").c_str()));
   }
   c->stats.compile_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
@@ -188,7 +188,16 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       if (g.red_out == 0) return GR_OK;
       s[L.extra] = (uint64_t)g.red_out;
       s[L.extra + 1] = (uint64_t)g.red_len;
-      return launch(c, k->fn, k->name, g.red_mode == 0 ? (g.red_out + 255) / 256 : g.red_out, s);
+      s[L.extra + 3] = (uint64_t)g.slabs;
+      if (g.slabs > 1) {
+        gr_status wst = ensure_workspace(c, (size_t)g.slabs * (size_t)g.red_out * itemsize(g.out_dtype));
+        if (wst != GR_OK) return wst;
+        s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+      }
+      int64_t units = g.red_mode == 0 ? (g.red_out + 255) / 256 : g.red_out;
+      gr_status st = launch(c, k->fn, k->name, units * g.slabs, s);
+      if (st != GR_OK || g.slabs <= 1) return st;
+      return launch(c, k->fn2, k->name + "_combine", g.red_out >= 1024 ? (g.red_out + 255) / 256 : g.red_out, s);
     }
     case GroupKind::GEMV: {
       if (g.M == 0) return GR_OK;

@@ -204,6 +204,22 @@ def test_reductions(env, shape, axis, keep, op):
         assert np.array_equal(got, ref)
 
 
+@pytest.mark.parametrize("shape,axis", [((1 << 22,), None), ((50000, 48), 0), ((3, 1 << 20), 1), ((300, 40, 50), (0, 2)), ((2049, 1025), None)])
+def test_two_stage_reductions(env, shape, axis):
+    # long reduced ranges are split over many workgroups and combined by a second kernel
+    a = np.abs(_rand(shape, 50)) + f32(0.25)  # positive terms: the relative bar is meaningful
+    for op in ("sum", "max", "min"):
+        got, ref = run_both(env, lambda xp, a: getattr(xp, op)(xp.sqrt(a), axis=axis), dict(a=a))
+        assert got.shape == ref.shape
+        if op == "sum":
+            assert_reduction(got, ref, what=f"{op} {shape} axis={axis}")
+        else:
+            assert np.array_equal(got, ref)
+    i = np.random.default_rng(51).integers(-2**31, 2**31 - 1, shape, dtype=np.int64).astype(np.int32)
+    got, ref = run_both(env, lambda xp, a: xp.sum(a, axis=axis), dict(a=i))
+    assert got.dtype == np.int64 and np.array_equal(got, ref)
+
+
 def test_int_sum_exact_and_closed_form(env):
     n = 70000
     got, ref = run_both(env, lambda xp, a: xp.sum(a), dict(a=np.arange(n, dtype=np.int32)))

@@ -279,6 +279,16 @@ def test_reduction_cases_compile(ctx, shape, axis, keep):
     gr.sum(ctx.spec(shape, gr.GR_I32), axis=axis, keepdims=keep).compile()
 
 
+def test_long_reductions_are_split_into_two_stages(ctx):
+    full = gr.sum(gr.sqrt(ctx.spec((1 << 22,))))
+    assert [k for k, _ in groups(full)] == ["REDUCE"]
+    src = full.source(0)
+    assert "gr_reduce_combine" in src and "NSPLIT" in src
+    full.compile()
+    gr.sum(ctx.spec((50000, 48)), axis=0).compile()
+    gr.max(ctx.spec((300, 40, 50), gr.GR_I32), axis=(0, 2)).compile()
+
+
 def test_rowred_and_dot_cases_compile(ctx):
     for i, p in enumerate(ROWRED_PROGRAMS):
         p(gr, ctx.spec((50, 50) if i >= 5 else (50, 333))).compile()
