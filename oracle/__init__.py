@@ -73,6 +73,8 @@ def lib():
         L.ora_reduce.argtypes = [I, P, P, I, I]
         L.ora_dot.restype = P
         L.ora_dot.argtypes = [P, P]
+        L.ora_scan.restype = P
+        L.ora_scan.argtypes = [I, P, I]
         L.ora_set_threads.argtypes = [I]
         _lib = L
     return _lib
@@ -156,6 +158,7 @@ class Array:
     def max(self, axis=None, keepdims=False): return reduce("max", self, axis, keepdims)
     def min(self, axis=None, keepdims=False): return reduce("min", self, axis, keepdims)
     def dot(self, o): return dot(self, o)
+    def cumsum(self, axis): return scan("sum", self, axis)
 
 
 def array(x) -> Array:
@@ -224,6 +227,15 @@ def reduce(name: str, a: Array, axis=None, keepdims=False) -> Array:
             raise OracleError("empty axis tuple")
     arr = (ctypes.c_int * builtins.max(len(axes), 1))(*axes)
     return Array(lib().ora_reduce(_REDUCE[name], a._p, arr, len(axes), int(bool(keepdims))))
+
+
+def scan(name: str, a: Array, axis: int) -> Array:
+    return Array(lib().ora_scan(_REDUCE[name], a._p, int(axis)))
+
+
+def cumsum(a, axis): return scan("sum", a, axis)
+def cummax(a, axis): return scan("max", a, axis)
+def cummin(a, axis): return scan("min", a, axis)
 
 
 def dot(a: Array, b: Array) -> Array:

@@ -26,6 +26,9 @@
 //     index order, rounded once to binary32.  sum of i32: exact in int64
 //     (NumPy's default result type on Linux).  max/min: exact.
 //   * dot: binary64 accumulator over k in index order, rounded once.
+//   * cumulative sum / max / min along one axis (the map-scan primitive of
+//     Section 3.2): f32 running sum kept in binary64, every prefix rounded
+//     once to binary32; i32 running sum exact in int64; max/min exact.
 //   * slice / transpose: views (offset + strides), no data touched
 //     (Section 3.1: index translation for slicing and transpose (i,j)->(j,i)).
 //   * a "weak" scalar (a Python number) takes the array operand's dtype:
@@ -383,6 +386,43 @@ Arr* ora_reduce(int op, const Arr* a, const int* axes, int naxes, int keepdims) 
     if (a->dtype == DT_F32) base<float>(r)[lin] = (op == R_SUM) ? (float)facc : fext;
     else if (op == R_SUM) base<int64_t>(r)[lin] = iacc;
     else base<int32_t>(r)[lin] = iext;
+  }
+  return r;
+}
+
+// Inclusive scan along `axis` (np.cumsum / np.maximum.accumulate / np.minimum.accumulate).
+Arr* ora_scan(int op, const Arr* a, int axis) {
+  if (a->dtype != DT_F32 && a->dtype != DT_I32) { g_err = "scan: unsupported dtype"; return nullptr; }
+  if (a->ndim < 1) { g_err = "scan: rank-0 operand"; return nullptr; }
+  if (axis < 0) axis += a->ndim;
+  if (axis < 0 || axis >= a->ndim) { g_err = "scan: bad axis"; return nullptr; }
+  int out_dt = (a->dtype == DT_I32 && op == R_SUM) ? DT_I64 : a->dtype;
+  Arr* r = fresh(out_dt, a->ndim, a->shape);
+  // the lines along `axis`: one per index of the other dimensions
+  int kndim = 0; int64_t kshape[MAXD]; int kaxis[MAXD];
+  for (int d = 0; d < a->ndim; ++d) if (d != axis) { kshape[kndim] = a->shape[d]; kaxis[kndim++] = d; }
+  int64_t lines = 1;
+  for (int d = 0; d < kndim; ++d) lines *= kshape[d];
+  int64_t len = a->shape[axis];
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+  for (int64_t ln = 0; ln < lines; ++ln) {
+    int64_t kidx[MAXD];
+    unravel(ln, kndim, kshape, kidx);
+    int64_t ain = a->offset, rout = 0;
+    for (int d = 0; d < kndim; ++d) { ain += kidx[d] * a->strides[kaxis[d]]; rout += kidx[d] * r->strides[kaxis[d]]; }
+    double facc = 0.0; int64_t iacc = 0; float fext = 0.f; int32_t iext = 0;
+    for (int64_t j = 0; j < len; ++j) {
+      int64_t src = ain + j * a->strides[axis], dst = rout + j * r->strides[axis];
+      if (a->dtype == DT_F32) {
+        float v = base<float>(a)[src];
+        if (op == R_SUM) { facc += (double)v; base<float>(r)[dst] = (float)facc; }
+        else { fext = j == 0 ? v : f32_binary(op == R_MAX ? B_MAXIMUM : B_MINIMUM, fext, v); base<float>(r)[dst] = fext; }
+      } else {
+        int32_t v = base<int32_t>(a)[src];
+        if (op == R_SUM) { iacc += (int64_t)v; base<int64_t>(r)[dst] = iacc; }
+        else { iext = j == 0 ? v : (op == R_MAX ? (iext >= v ? iext : v) : (iext <= v ? iext : v)); base<int32_t>(r)[dst] = iext; }
+      }
+    }
   }
   return r;
 }

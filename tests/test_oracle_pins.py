@@ -252,6 +252,55 @@ def test_reduce_max_propagates_nan():
     assert np.isnan(m[0]) and m[1] == 5
 
 
+# ------------------------------------------------------------------- scans ---
+def test_scan_closed_forms_and_brute_force():
+    # cumsum(ones) = 1..n; cumsum(arange) = triangular numbers (exact in f32 for n <= 5793)
+    n = 5000
+    assert np.array_equal(ora.cumsum(ora.array(np.ones(n, f32)), 0).numpy(), np.arange(1, n + 1, dtype=f32))
+    tri = ora.cumsum(ora.array(np.arange(n, dtype=f32)), 0).numpy()
+    assert np.array_equal(tri, (np.arange(n, dtype=np.int64) * np.arange(1, n + 1, dtype=np.int64) // 2).astype(f32))
+    ti = ora.cumsum(ora.array(np.arange(70000, dtype=np.int32)), 0)
+    assert ti.dtype == np.int64
+    k = np.arange(70000, dtype=np.int64)
+    assert np.array_equal(ti.numpy(), k * (k + 1) // 2)
+    # last prefix equals the reduction; differences of prefixes give the terms back (small ints: exact)
+    g = rng(20)
+    x = g.integers(-9, 10, (4, 5, 6)).astype(f32)
+    for axis in (0, 1, 2, -1):
+        c = ora.cumsum(ora.array(x), axis).numpy()
+        assert c.shape == x.shape
+        ax = axis % 3
+        assert np.array_equal(np.take(c, -1, axis=ax), ora.sum(ora.array(x), axis=ax).numpy())
+        assert np.array_equal(np.diff(c, axis=ax), np.delete(x, 0, axis=ax))
+        # brute force against nested Python loops
+        for idx in itertools.product(range(4), range(5), range(6)):
+            lo = list(idx)
+            s = 0.0
+            for j in range(idx[ax] + 1):
+                lo[ax] = j
+                s += float(x[tuple(lo)])
+            assert c[idx] == s
+    # running extrema against Python's max/min on prefixes, and through a strided view
+    y = g.standard_normal((3, 17)).astype(f32)
+    cm = ora.cummax(ora.array(y), 1).numpy()
+    cn = ora.cummin(ora.array(y)[:, ::2], 1).numpy()
+    for i in range(3):
+        for j in range(17):
+            assert cm[i, j] == max(y[i, :j + 1])
+        for j in range(9):
+            assert cn[i, j] == min(y[i, :2 * j + 1:2])
+    # binary64 accumulation: a binary32 running sum would stall at 2^24
+    big = np.ones(1 << 12, f32)
+    big[0] = 2.0**24
+    assert float(ora.cumsum(ora.array(big), 0).numpy()[-1]) == float(f32(2.0**24 + (1 << 12) - 1))
+    with pytest.raises(ora.OracleError):
+        ora.cumsum(ora.array(x), 3)
+    # NumPy third opinion (NumPy accumulates in binary32, hence a tolerance)
+    z = g.standard_normal((7, 300)).astype(f32)
+    assert np.allclose(ora.cumsum(ora.array(z), 1).numpy(), np.cumsum(z.astype(np.float64), axis=1), rtol=1e-6, atol=1e-5)
+    assert np.array_equal(ora.cummax(ora.array(z), 0).numpy(), np.maximum.accumulate(z, axis=0))
+
+
 # ------------------------------------------------------------------ slices ---
 def test_slice_brute_force_1d_against_python_range():
     n = 6
