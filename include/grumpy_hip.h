@@ -165,6 +165,13 @@ gr_status gr_transpose(gr_ctx* ctx, gr_array a, const int* perm, gr_array* out);
  * GR_ERR_SHAPE. */
 gr_status gr_reduce(gr_ctx* ctx, gr_op op, gr_array a, const int* axes, int naxes, int keepdims, gr_array* out);
 
+/* Inclusive scan along one axis (the map-scan primitive of Section 3.2):
+ * GR_SUM = np.cumsum, GR_MAX / GR_MIN = np.maximum/minimum.accumulate.  The
+ * result has the operand's shape; an i32 running sum gives i64.  A scan is a
+ * fusion boundary on its output side: its operand expression is fused into the
+ * scan kernel, its consumers read the stored result. */
+gr_status gr_scan(gr_ctx* ctx, gr_op op, gr_array a, int axis, gr_array* out);
+
 /* np.dot for f32: (M,K).(K,) -> (M,) and (K,).(K,) -> ().  Either operand
  * may be any strided view (a transposed matrix is folded into the kernel,
  * Section 2).  Matrix-matrix products: GR_ERR_UNSUPPORTED. */

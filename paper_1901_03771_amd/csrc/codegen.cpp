@@ -70,6 +70,8 @@ ArgLayout arg_layout(const GroupPlan& g) {
   s += (int)g.consts.size();
   L.extra = s;
   s += 4;
+  L.ocoef = s;
+  if (g.kind == GroupKind::SCAN) s += g.rank;
   L.total = s;
   return L;
 }
@@ -79,6 +81,7 @@ std::string kernel_name(const GroupPlan& g) {
     case GroupKind::MAP: return "gr_map";
     case GroupKind::ROWRED: return "gr_rowred";
     case GroupKind::REDUCE: return "gr_reduce";
+    case GroupKind::SCAN: return "gr_scan";
     case GroupKind::GEMV: return g.gemv_mode == 2 ? "gr_gemv_pair" : (g.gemv_mode ? "gr_gemv_colacc" : "gr_gemv_rowdot");
   }
   return "gr_kernel";
@@ -702,6 +705,118 @@ void gen_reduce(Em& e) {
          "  }\n}\n";
 }
 
+// ---- SCAN (map-scan) ------------------------------------------------------------
+
+// Inclusive scan of the mapped values along the last iteration dimension.
+//   mode 0: the scanned axis is contiguous.  A workgroup walks one chunk of one line in tiles
+//           of 1024 elements: four elements per lane, a shuffle scan across the wave, 32 bytes
+//           of LDS across the four waves, a running carry between tiles.  Lines longer than
+//           one chunk take three kernels: chunk totals, an exclusive scan of the totals, the
+//           chunks again with their offsets (reduce-then-scan).
+//   mode 1: a thread per line, sequential along the axis (consecutive threads touch
+//           consecutive addresses when an inner dimension is contiguous).
+void gen_scan(Em& e) {
+  const GroupPlan& g = e.g;
+  const int rank = g.rank, sd = rank - 1;
+  const Phase& ph = g.phases[0];
+  const char* TA = cty(ph.out_dtype);  // accumulator = output type (f32, i32 for extrema, i64 for i32 sums)
+  prelude(e);
+  phase_helpers(e, 0, 64);
+  e.o << "static __device__ __forceinline__ float gr_up(float v, int d) { return __shfl_up(v, d, 64); }\n"
+         "static __device__ __forceinline__ int gr_up(int v, int d) { return __shfl_up(v, d, 64); }\n"
+         "static __device__ __forceinline__ long long gr_up(long long v, int d) {\n"
+         "  int lo = __shfl_up((int)(v & 0xffffffffll), d, 64), hi = __shfl_up((int)(v >> 32), d, 64);\n"
+         "  return ((long long)hi << 32) | (unsigned int)lo;\n}\n";
+  const std::string ident = Em::identity(ph);
+  auto conv = [&](const std::string& x) { return ph.out_dtype == GR_I64 && ph.in_dtype == GR_I32 ? "(long long)" + x : x; };
+  auto load_at = [&](const std::string& col) {
+    return [&e, &g, sd, col](const Instr& in, int) {
+      const AccessGroup& ag = g.groups[in.group];
+      std::ostringstream s;
+      s << "p" << in.group << "[0";
+      for (int k = 0; k < sd; ++k) if (!ag.structural_zero[k] && in.delta[k]) s << " + " << in.delta[k] << " * " << e.coef(in.group, k);
+      if (!ag.structural_zero[sd]) s << " + (" << col << " + " << in.delta[sd] << ") * " << e.coef(in.group, sd);
+      s << "]";
+      return s.str();
+    };
+  };
+  // common head: line index -> pointers
+  auto head = [&](bool per_block_line) {
+    e.o << "  const long long LINES = " << e.S(e.L.extra) << ", CH = " << e.S(e.L.extra + 1) << ", NCHUNK = " << e.S(e.L.extra + 3) << ";\n";
+    e.o << "  const long long L = " << e.dim(sd) << ";\n";
+    if (per_block_line) e.o << "  const long long line = blockIdx.x / NCHUNK, chunk = blockIdx.x % NCHUNK;\n";
+    else e.o << "  const long long line = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (line >= LINES) return;\n";
+    e.o << "  long long lrem = line;\n";
+    for (int k = sd - 1; k >= 0; --k) e.o << "  const long long i" << k << " = lrem % " << e.dim(k) << "; lrem /= " << e.dim(k) << ";\n";
+    group_pointers(e, "  ");
+    for (size_t gi = 0; gi < g.groups.size(); ++gi) {
+      const AccessGroup& ag = g.groups[gi];
+      e.o << "  const GM " << cty(ag.dtype) << "* const p" << gi << " = q" << gi;
+      for (int k = 0; k < sd; ++k) if (!ag.structural_zero[k]) e.o << " + i" << k << " * " << e.coef((int)gi, k);
+      e.o << ";\n";
+    }
+    e.o << "  GM " << TA << "* const po = (GM " << TA << "*)" << e.slot(e.L.out);
+    for (int k = 0; k < sd; ++k) e.o << " + i" << k << " * " << e.S(e.L.ocoef + k);
+    e.o << ";\n";
+    e.o << "  GM " << TA << "* const ws = (GM " << TA << "*)" << e.slot(e.L.extra + 2) << ";\n  (void)ws; (void)CH; (void)po; (void)L;\n";
+  };
+
+  if (g.scan_mode == 1) {
+    kernel_head(e, "gr_scan");
+    head(false);
+    e.o << "  const long long ostep = " << e.S(e.L.ocoef + sd) << ";\n  " << TA << " acc = " << ident << ";\n";
+    e.o << "  for (long long j = 0; j < L; ++j) {\n";
+    emit_scalar_program(e, g.prog, {ph.value}, load_at("j"), "0.0f", "t", "    ");
+    e.o << "    acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n    po[j * ostep] = acc;\n  }\n}\n";
+    return;
+  }
+
+  // ---- mode 0, kernel 1 of 3: chunk totals (only launched when a line has several chunks)
+  kernel_head(e, "gr_scan_sums");
+  head(true);
+  e.o << "  __shared__ long long gr_sm[4];\n";
+  e.o << "  const long long cbeg = chunk * CH, cend = (cbeg + CH < L) ? cbeg + CH : L;\n  " << TA << " acc = " << ident << ";\n";
+  e.o << "  for (long long j = cbeg + threadIdx.x; j < cend; j += 256) {\n";
+  emit_scalar_program(e, g.prog, {ph.value}, load_at("j"), "0.0f", "t", "    ");
+  e.o << "    acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n  }\n";
+  e.o << "  acc = gr_lanes0(acc);\n  { " << TA << "* sm = (" << TA << "*)gr_sm;\n    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;\n    __syncthreads();\n"
+         "    if (threadIdx.x == 0) ws[line * NCHUNK + chunk] = gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])); }\n}\n";
+
+  // ---- kernel 2 of 3: exclusive scan of each line's chunk totals, in place (at most 4096 chunks)
+  kernel_head(e, "gr_scan_offsets");
+  e.o << "  const long long NCHUNK = " << e.S(e.L.extra + 3) << ";\n";
+  e.o << "  GM " << TA << "* const w = (GM " << TA << "*)" << e.slot(e.L.extra + 2) << " + (long long)blockIdx.x * NCHUNK;\n";
+  e.o << "  __shared__ long long gr_sm[4];\n";
+  e.o << "  const int per = (int)((NCHUNK + 255) / 256);\n  const long long c0 = (long long)threadIdx.x * per;\n";
+  e.o << "  " << TA << " v[16];\n  " << TA << " tot = " << ident << ";\n";
+  e.o << "  for (int u = 0; u < 16; ++u) { v[u] = (u < per && c0 + u < NCHUNK) ? w[c0 + u] : " << ident << "; tot = gr_comb0(tot, v[u]); }\n";
+  e.o << "  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;\n  " << TA << " x = tot;\n";
+  for (int d = 1; d < 64; d <<= 1) e.o << "  { const " << TA << " y = gr_up(x, " << d << "); if (lane >= " << d << ") x = gr_comb0(y, x); }\n";
+  e.o << "  " << TA << "* sm = (" << TA << "*)gr_sm;\n  if (lane == 63) sm[wave] = x;\n  __syncthreads();\n";
+  e.o << "  " << TA << " off = " << ident << ";\n  for (int q = 0; q < wave; ++q) off = gr_comb0(off, sm[q]);\n";
+  e.o << "  " << TA << " ex = gr_up(x, 1);\n  if (lane == 0) ex = " << ident << ";\n  off = gr_comb0(off, ex);\n";
+  e.o << "  for (int u = 0; u < 16; ++u) if (u < per && c0 + u < NCHUNK) { w[c0 + u] = off; off = gr_comb0(off, v[u]); }\n}\n";
+
+  // ---- kernel 3 of 3 (the only one for single-chunk lines): scan of a chunk with its offset
+  kernel_head(e, "gr_scan");
+  head(true);
+  e.o << "  __shared__ long long gr_sm[2][4];\n";
+  e.o << "  const long long cbeg = chunk * CH, cend = (cbeg + CH < L) ? cbeg + CH : L;\n";
+  e.o << "  " << TA << " carry = NCHUNK > 1 ? ws[line * NCHUNK + chunk] : " << ident << ";\n";
+  e.o << "  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;\n  int buf = 0;\n";
+  e.o << "  for (long long t0 = cbeg; t0 < cend; t0 += 1024) {\n    const long long c = t0 + threadIdx.x * 4;\n    " << TA << " v[4];\n";
+  e.o << "#pragma unroll\n    for (int j = 0; j < 4; ++j) {\n      v[j] = " << ident << ";\n      if (c + j < cend) {\n";
+  emit_scalar_program(e, g.prog, {ph.value}, load_at("(c + j)"), "0.0f", "t", "        ");
+  e.o << "        v[j] = " << conv("t" + std::to_string(ph.value)) << ";\n      }\n    }\n";
+  e.o << "    v[1] = gr_comb0(v[0], v[1]); v[2] = gr_comb0(v[1], v[2]); v[3] = gr_comb0(v[2], v[3]);\n    " << TA << " x = v[3];\n";
+  for (int d = 1; d < 64; d <<= 1) e.o << "    { const " << TA << " y = gr_up(x, " << d << "); if (lane >= " << d << ") x = gr_comb0(y, x); }\n";
+  e.o << "    " << TA << "* sm = (" << TA << "*)gr_sm[buf];\n    if (lane == 63) sm[wave] = x;\n    __syncthreads();\n";
+  e.o << "    " << TA << " base = carry;\n    for (int q = 0; q < wave; ++q) base = gr_comb0(base, sm[q]);\n";
+  e.o << "    { " << TA << " ex = gr_up(x, 1); if (lane != 0) base = gr_comb0(base, ex); }\n";
+  e.o << "    for (int j = 0; j < 4; ++j) if (c + j < cend) po[c + j] = gr_comb0(base, v[j]);\n";
+  e.o << "    carry = gr_comb0(carry, gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])));\n    buf ^= 1;\n  }\n}\n";
+}
+
 // ---- GEMV -----------------------------------------------------------------------
 
 // Epilogue: the pointwise consumers of the dot, evaluated at output index `idx`.
@@ -873,6 +988,7 @@ std::string generate_source(const GroupPlan& g) {
     case GroupKind::MAP: gen_map(e); break;
     case GroupKind::ROWRED: gen_rowred(e); break;
     case GroupKind::REDUCE: gen_reduce(e); break;
+    case GroupKind::SCAN: gen_scan(e); break;
     case GroupKind::GEMV:
       if (g.gemv_mode == 2) {
         Em e2(*g.pair);

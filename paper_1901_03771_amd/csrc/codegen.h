@@ -17,7 +17,9 @@ struct ArgLayout {
   int out = 0;                 // output pointer
   int dims = 0;                // first of `rank` extents
   int consts = 0;              // first constant slot
-  int extra = 0;               // kind-specific: GEMV {M, K, workspace, slabs}; REDUCE {outputs, length}
+  int extra = 0;               // kind-specific: GEMV {M, K, workspace, slabs}; REDUCE {outputs, length, workspace, splits};
+                               // SCAN {lines, chunk length, workspace, chunks}
+  int ocoef = 0;               // SCAN: first of `rank` output strides
   int total = 0;
 };
 

@@ -41,7 +41,8 @@ struct gr_ctx {
   struct Kernel {
     hipModule_t module = nullptr;
     hipFunction_t fn = nullptr;
-    hipFunction_t fn2 = nullptr;  // second stage (column-accumulate GEMV)
+    hipFunction_t fn2 = nullptr;  // second stage (combine kernels; chunk totals of a scan)
+    hipFunction_t fn3 = nullptr;  // scan of the chunk totals
     std::vector<char> code;
     std::string name;
   };

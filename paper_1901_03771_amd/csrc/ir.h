@@ -18,7 +18,7 @@ namespace gr {
 
 constexpr int MAXD = GR_MAX_NDIM;
 
-enum class Kind : uint8_t { LEAF, SCALAR, CONST, UNARY, BINARY, SLICE, TRANSPOSE, REDUCE, DOT };
+enum class Kind : uint8_t { LEAF, SCALAR, CONST, UNARY, BINARY, SLICE, TRANSPOSE, REDUCE, DOT, SCAN };
 
 struct Node {
   uint64_t id = 0;
@@ -59,7 +59,7 @@ struct Node {
     return n;
   }
   bool is_view() const { return kind == Kind::SLICE || kind == Kind::TRANSPOSE; }
-  bool is_compute() const { return kind == Kind::UNARY || kind == Kind::BINARY || kind == Kind::REDUCE || kind == Kind::DOT; }
+  bool is_compute() const { return kind == Kind::UNARY || kind == Kind::BINARY || kind == Kind::REDUCE || kind == Kind::DOT || kind == Kind::SCAN; }
   bool has_data() const { return materialized || planned; }
 };
 
@@ -104,7 +104,7 @@ struct AccessGroup {
   std::set<std::vector<int64_t>> deltas;  // all shifts used (length = iteration rank)
 };
 
-enum class GroupKind : uint8_t { MAP, ROWRED, REDUCE, GEMV };
+enum class GroupKind : uint8_t { MAP, ROWRED, REDUCE, GEMV, SCAN };
 
 struct Phase {
   int op = 0;  // GR_SUM / GR_MAX / GR_MIN
@@ -159,6 +159,14 @@ struct GroupPlan {
   int red_mode = 0;                      // REDUCE: 0 thread-per-output, 1 block-per-output
   int64_t red_out = 0, red_len = 0;      // REDUCE: outputs, reduced elements per output
   int red_kept_rank = 0;
+
+  // SCAN: element stride of the output per iteration dimension (the scanned axis is the last
+  // iteration dimension but need not be the output's last), mode 0 = lanes along the scanned
+  // axis (it is contiguous), 1 = a thread per line; chunking of long lines
+  int64_t out_coef[MAXD] = {0};
+  int scan_mode = 0;
+  int64_t scan_chunk = 0;
+  int scan_nchunk = 1;
 
   // GEMV core
   int gemv_mode = 0;  // 0: inner stride 1 along k (row-dot); 1: inner stride 1 along m (column-accumulate);

@@ -59,6 +59,7 @@ std::string node_label(const Node* n) {
     case Kind::SLICE: return "slice";
     case Kind::TRANSPOSE: return "transpose";
     case Kind::DOT: return "dot";
+    case Kind::SCAN: return std::string("cum") + op_name(n->op);
   }
   return "?";
 }
@@ -235,6 +236,10 @@ struct Builder {
           id = value_number(in);
           break;
         }
+        case Kind::SCAN:
+          invalid.push_back({n, "a scan is always materialised"});
+          id = constant(n->dtype, 0.0);
+          break;
         default:
           invalid.push_back({n, "unexpected lazy node kind"});
           id = constant(GR_F32, 0.0);
@@ -399,7 +404,7 @@ void make_signature(GroupPlan* g) {
   for (int64_t v : {(int64_t)g->kind, (int64_t)g->rank, (int64_t)g->out_dtype, (int64_t)g->out_per_row, (int64_t)g->BX, (int64_t)g->BY,
                     (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads, (int64_t)g->xcd_remap, (int64_t)g->red_mode,
                     (int64_t)g->red_kept_rank, (int64_t)g->gemv_mode, (int64_t)g->LPR, (int64_t)g->KV, (int64_t)g->mat_group,
-                    (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->groups.size()})
+                    (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode, (int64_t)g->groups.size()})
     put(s, v);
   for (const AccessGroup& ag : g->groups) {
     int64_t cls = (int64_t)ag.dtype;
@@ -453,6 +458,7 @@ struct Planner {
           if (!b->materialized) cuts.insert(b);
         }
       }
+      if (n->kind == Kind::SCAN) cuts.insert(n);  // a scan is materialised (materialize_node, Section 2)
       if (n->kind == Kind::REDUCE) {
         const Node* x = n->in[0];
         bool last_only = x->ndim >= 1;
@@ -544,7 +550,76 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
   b.g = g;
   b.owned = &owned;
 
-  if (dot) {
+  if (r->kind == Kind::SCAN) {
+    // ---- map-scan: the operand expression is the map, the scan runs along one axis --------
+    g->kind = GroupKind::SCAN;
+    b.g->kind = GroupKind::SCAN;
+    for (const Node* n : owned) if (n != r && (n->kind == Kind::REDUCE || n->kind == Kind::DOT || n->kind == Kind::SCAN))
+      invalid->push_back({n, "reduction, scan or dot under a scan"});
+    if (!invalid->empty()) return GR_OK;
+    const Node* x = r->in[0];
+    int axis = 0;
+    for (int d = 0; d < x->ndim; ++d) if (r->red_axis[d]) axis = d;
+    // iteration space: the other dimensions in order, the scanned axis last
+    int pos[MAXD], nk = 0;
+    for (int d = 0; d < x->ndim; ++d) if (d != axis) { pos[d] = nk; g->orig_dims[nk++] = x->shape[d]; }
+    pos[axis] = nk;
+    g->orig_dims[nk] = x->shape[axis];
+    const int n = nk + 1;
+    g->orig_rank = n;
+    b.rank = n; b.dims = g->orig_dims; b.prog = &g->prog;
+    IndexMap xm(x->ndim);
+    for (int d = 0; d < x->ndim; ++d) xm[d] = DimMap{pos[d], 1, 0};
+    int v = b.eval(x, xm);
+    if (!b.invalid.empty()) { *invalid = b.invalid; return GR_OK; }
+    b.members_seen.insert(r);
+    Phase p;
+    p.op = r->op; p.in_dtype = x->dtype; p.out_dtype = r->dtype; p.value = v; p.node = r;
+    g->phases.push_back(p);
+    // the C-contiguous output takes part in dimension collapsing as one more access
+    AccessGroup og;
+    og.leaf = nullptr; og.dtype = r->dtype;
+    for (int k = 0; k < MAXD; ++k) og.structural_zero[k] = true;
+    { int64_t st = 1; for (int d = x->ndim - 1; d >= 0; --d) { og.coef[pos[d]] = st; og.structural_zero[pos[d]] = false; st *= x->shape[d]; } }
+    og.deltas.insert(std::vector<int64_t>(n, 0));
+    g->groups.push_back(og);
+    std::vector<Instr>* ps[1] = {&g->prog};
+    normalize_deltas(g, ps, 1, n);
+    bool barrier[MAXD] = {false};
+    if (nk > 0) barrier[nk - 1] = true;
+    collapse_dims(g, barrier, ps, 1);
+    if (g->orig_dims[n - 1] == 1 || g->collapse_to[n - 1] != g->rank - 1 || nk == 0) {
+      // the scanned axis must remain the last collapsed dim even if its extent is 1
+      if (g->orig_dims[n - 1] == 1) {
+        bool only = true;
+        for (int k = 0; k < nk; ++k) if (g->orig_dims[k] != 1) only = false;
+        if (!only) { g->dims[g->rank] = 1; g->collapse_to[n - 1] = g->rank; g->rank++; }
+      }
+    }
+    for (int k = 0; k < g->rank; ++k) g->out_coef[k] = g->groups.back().coef[k];
+    g->groups.pop_back();
+    const int sd = g->rank - 1;
+    int64_t L = g->dims[sd], lines = 1;
+    for (int k = 0; k < sd; ++k) lines *= g->dims[k];
+    bool unit = g->out_coef[sd] == 1 || L == 1;
+    for (const AccessGroup& ag : g->groups) if (!ag.structural_zero[sd] && ag.coef[sd] != 1) unit = false;
+    g->scan_mode = unit ? 0 : 1;
+    g->scan_nchunk = 1;
+    g->scan_chunk = ((L + 1023) / 1024) * 1024;
+    if (g->scan_mode == 0 && lines < 512 && L > 32768) {
+      // long lines and few of them: reduce-then-scan over chunks (Section 3.2 refers to the
+      // work-efficient scan: chunk sums, a scan of the sums, then the chunks with their offsets)
+      int64_t want = std::max<int64_t>(1, 2048 / std::max<int64_t>(lines, 1));
+      int64_t chunk = std::max<int64_t>(8192, (L + want - 1) / want);
+      chunk = ((chunk + 1023) / 1024) * 1024;
+      int64_t nch = (L + chunk - 1) / chunk;
+      if (nch > 4096) { chunk = (((L + 4095) / 4096 + 1023) / 1024) * 1024; nch = (L + chunk - 1) / chunk; }
+      g->scan_chunk = chunk;
+      g->scan_nchunk = (int)nch;
+    }
+    g->red_out = lines;
+    g->red_len = L;
+  } else if (dot) {
     // ---- contraction with pointwise epilogue ------------------------------
     g->kind = GroupKind::GEMV;
     const Node* A = dot->in[0];
@@ -917,7 +992,7 @@ std::string describe_plan(const Plan& plan) {
   int i = 0;
   for (const auto& gp : plan.groups) {
     const GroupPlan& g = *gp;
-    const char* kn = g.kind == GroupKind::MAP ? "MAP" : g.kind == GroupKind::ROWRED ? "ROWRED" : g.kind == GroupKind::REDUCE ? "REDUCE" : "GEMV";
+    const char* kn = g.kind == GroupKind::MAP ? "MAP" : g.kind == GroupKind::ROWRED ? "ROWRED" : g.kind == GroupKind::REDUCE ? "REDUCE" : g.kind == GroupKind::SCAN ? "SCAN" : "GEMV";
     s << '#' << i++ << ' ' << kn << " root=" << g.root->id << " shape=(";
     for (int d = 0; d < g.root->ndim; ++d) s << (d ? "," : "") << g.root->shape[d];
     s << ") iter=(";
@@ -941,6 +1016,7 @@ std::string describe_plan(const Plan& plan) {
       s << "]]";
     }
     if (g.kind == GroupKind::ROWRED) s << " phases=" << g.phases.size() << " row_threads=" << g.row_threads << " NP=" << g.NP;
+    if (g.kind == GroupKind::SCAN) s << " mode=" << (g.scan_mode ? "thread-per-line" : "lanes-along-axis") << " lines=" << g.red_out << " length=" << g.red_len << " chunks=" << g.scan_nchunk;
     if (g.kind == GroupKind::MAP) s << " tile=" << g.BY * g.VR << "x" << g.BX * 4 * g.UC << " patch=" << g.VR << "x" << g.UC * 4;
     s << '\n';
   }

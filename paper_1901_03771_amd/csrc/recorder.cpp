@@ -323,6 +323,26 @@ gr_status gr_reduce(gr_ctx* ctx, gr_op op, gr_array a, const int* axes, int naxe
   return GR_OK;
 }
 
+gr_status gr_scan(gr_ctx* ctx, gr_op op, gr_array a, int axis, gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  if (!is_reduce(op)) return fail(ctx, GR_ERR_ARG, "scan: not a scan op");
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "scan: bad handle");
+  if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "scan: operand is a bare scalar");
+  if (x->dtype == GR_I64) return fail(ctx, GR_ERR_UNSUPPORTED, "scan: i64 operands are not supported");
+  if (x->ndim < 1) return fail(ctx, GR_ERR_AXIS, "scan: rank-0 operand has no axis");
+  int ax = axis < 0 ? axis + x->ndim : axis;
+  if (ax < 0 || ax >= x->ndim) return fail(ctx, GR_ERR_AXIS, "scan: axis out of range");
+  Node* r = new_node(ctx, Kind::SCAN);
+  r->op = op;
+  r->dtype = (x->dtype == GR_I32 && op == GR_SUM) ? GR_I64 : x->dtype;
+  r->ndim = x->ndim;
+  for (int d = 0; d < x->ndim; ++d) { r->shape[d] = x->shape[d]; r->red_axis[d] = d == ax; }
+  add_input(r, x);
+  *out = r->id;
+  return GR_OK;
+}
+
 gr_status gr_dot(gr_ctx* ctx, gr_array a, gr_array b, gr_array* out) {
   if (!ctx || !out) return GR_ERR_ARG;
   Node* x = lookup(ctx, a);

@@ -96,6 +96,10 @@ gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
     GR_HIP(c, hipModuleGetFunction(&k.fn, k.module, k.name.c_str()));
     if ((g.kind == GroupKind::GEMV && g.gemv_mode >= 1) || g.kind == GroupKind::REDUCE)
       GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, (k.name + "_combine").c_str()));
+    if (g.kind == GroupKind::SCAN && g.scan_mode == 0) {
+      GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, "gr_scan_sums"));
+      GR_HIP(c, hipModuleGetFunction(&k.fn3, k.module, "gr_scan_offsets"));
+    }
   }
   c->stats.compile_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
   auto ins = c->cache.emplace(g.signature, std::move(k));
@@ -198,6 +202,24 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       gr_status st = launch(c, k->fn, k->name, units * g.slabs, s);
       if (st != GR_OK || g.slabs <= 1) return st;
       return launch(c, k->fn2, k->name + "_combine", g.red_out >= 1024 ? (g.red_out + 255) / 256 : g.red_out, s);
+    }
+    case GroupKind::SCAN: {
+      if (total == 0) return GR_OK;
+      for (int k2 = 0; k2 < g.rank; ++k2) s[L.ocoef + k2] = (uint64_t)g.out_coef[k2];
+      s[L.extra] = (uint64_t)g.red_out;
+      s[L.extra + 1] = (uint64_t)g.scan_chunk;
+      s[L.extra + 3] = (uint64_t)g.scan_nchunk;
+      if (g.scan_mode == 1) return launch(c, k->fn, k->name, (g.red_out + 255) / 256, s);
+      if (g.scan_nchunk > 1) {
+        gr_status wst = ensure_workspace(c, (size_t)g.red_out * (size_t)g.scan_nchunk * itemsize(g.out_dtype));
+        if (wst != GR_OK) return wst;
+        s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+        gr_status st = launch(c, k->fn2, "gr_scan_sums", g.red_out * g.scan_nchunk, s);
+        if (st != GR_OK) return st;
+        st = launch(c, k->fn3, "gr_scan_offsets", g.red_out, s);
+        if (st != GR_OK) return st;
+      }
+      return launch(c, k->fn, k->name, g.red_out * g.scan_nchunk, s);
     }
     case GroupKind::GEMV: {
       if (g.M == 0) return GR_OK;

@@ -32,7 +32,7 @@ STATUS = {0: "GR_OK", 1: "GR_ERR_HANDLE", 2: "GR_ERR_SHAPE", 3: "GR_ERR_DTYPE", 
 SYMBOLS = [
     "gr_ctx_create", "gr_ctx_destroy", "gr_ctx_set_stream", "gr_ctx_set_allocator", "gr_ctx_set_option", "gr_sync",
     "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose",
-    "gr_reduce", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_ndim", "gr_shape", "gr_dtype_of",
+    "gr_reduce", "gr_scan", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_ndim", "gr_shape", "gr_dtype_of",
     "gr_is_materialized", "gr_data_ptr", "gr_retain", "gr_release", "gr_plan_describe", "gr_plan_source",
     "gr_plan_compile", "gr_stats", "gr_profile_reset", "gr_profile_read", "gr_stream_copy", "gr_stream_read",
 ]
@@ -79,6 +79,7 @@ def lib():
         "gr_slice": [P, U64, I, PP(I64), PP(I64), PP(I64), PP(ctypes.c_uint8), PP(ctypes.c_uint8), PP(U64)],
         "gr_transpose": [P, U64, PP(I), PP(U64)],
         "gr_reduce": [P, I, U64, PP(I), I, I, PP(U64)], "gr_dot": [P, U64, U64, PP(U64)],
+        "gr_scan": [P, I, U64, I, PP(U64)],
         "gr_materialize": [P, U64], "gr_materialize_into": [P, U64, P, SZ],
         "gr_ndim": [P, U64, PP(I)], "gr_shape": [P, U64, PP(I64)], "gr_dtype_of": [P, U64, PP(I)],
         "gr_is_materialized": [P, U64, PP(I)], "gr_data_ptr": [P, U64, PP(P), PP(I64)],
@@ -333,6 +334,7 @@ class Array:
     def max(self, axis=None, keepdims=False): return reduce("max", self, axis, keepdims)
     def min(self, axis=None, keepdims=False): return reduce("min", self, axis, keepdims)
     def dot(self, o): return dot(self, o)
+    def cumsum(self, axis): return scan("sum", self, axis)
 
 
 def _ctx_of(*xs) -> Context:
@@ -431,6 +433,17 @@ def reduce(name: str, a: Array, axis=None, keepdims=False) -> Array:
     h = ctypes.c_uint64()
     a.ctx.check(lib().gr_reduce(a.ctx._p, _REDUCE[name], a.h, arr, len(axes), int(bool(keepdims)), ctypes.byref(h)))
     return Array(a.ctx, h.value)
+
+
+def scan(name: str, a: Array, axis: int) -> Array:
+    h = ctypes.c_uint64()
+    a.ctx.check(lib().gr_scan(a.ctx._p, _REDUCE[name], a.h, int(axis), ctypes.byref(h)))
+    return Array(a.ctx, h.value)
+
+
+def cumsum(a, axis): return scan("sum", a, axis)
+def cummax(a, axis): return scan("max", a, axis)
+def cummin(a, axis): return scan("min", a, axis)
 
 
 def dot(a: Array, b: Array) -> Array:

@@ -56,3 +56,7 @@ DOT_CASES = [
     (lambda xp, A, v, u: (A @ v) * (A @ v) + u, "dot used twice"),
     (lambda xp, A, v, u: A.T @ (A @ v), "dot feeding dot"),
 ]
+
+# (shape, axis): inclusive scans along the contiguous axis, along outer axes, over long lines
+SCAN_CASES = [((1000,), 0), ((37, 211), 1), ((37, 211), 0), ((4, 5, 6), 1), ((4, 5, 6), 0), ((4, 5, 6), -1), ((3, 100000), 1),
+              ((1 << 21,), 0), ((5, 1), 1), ((1, 7), 0), ((1,), 0), ((600, 1030), 1), ((2, 5000), 0)]

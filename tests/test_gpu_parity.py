@@ -14,7 +14,7 @@ import numpy as np
 import pytest
 
 import oracle as ora
-from cases import DOT_CASES, ELEMENTWISE_CASES, REDUCTION_CASES, ROWRED_PROGRAMS, _rand
+from cases import DOT_CASES, ELEMENTWISE_CASES, REDUCTION_CASES, ROWRED_PROGRAMS, SCAN_CASES, _rand
 from helpers import elementwise_close, reduction_close, ulp_of
 from paper_1901_03771_amd import workloads as wl
 
@@ -218,6 +218,33 @@ def test_two_stage_reductions(env, shape, axis):
     i = np.random.default_rng(51).integers(-2**31, 2**31 - 1, shape, dtype=np.int64).astype(np.int32)
     got, ref = run_both(env, lambda xp, a: xp.sum(a, axis=axis), dict(a=i))
     assert got.dtype == np.int64 and np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("shape,axis", SCAN_CASES)
+def test_scans(env, shape, axis):
+    a = _rand(shape, 60)
+    got, ref = run_both(env, lambda xp, a: xp.cumsum(a * 0.5 + 1.0, axis), dict(a=a))  # the map is fused into the scan
+    assert got.shape == ref.shape and got.dtype == ref.dtype
+    assert_reduction(got, ref, what=f"cumsum {shape} axis={axis}")
+    got, ref = run_both(env, lambda xp, a: xp.cummax(a, axis) - xp.cummin(a, axis), dict(a=a))
+    assert np.array_equal(got, ref)
+    i = np.random.default_rng(61).integers(-2**31, 2**31 - 1, shape, dtype=np.int64).astype(np.int32)
+    got, ref = run_both(env, lambda xp, a: xp.cumsum(a, axis), dict(a=i))
+    assert got.dtype == np.int64 and np.array_equal(got, ref)
+
+
+def test_scan_closed_forms_and_consumers(env):
+    gr, ctx, torch = env
+    n = 5000
+    got, _ = run_both(env, lambda xp, a: xp.cumsum(a, 0), dict(a=np.ones(n, f32)))
+    assert np.array_equal(got, np.arange(1, n + 1, dtype=f32))
+    # consumers of a scan read its stored result; a strided view feeds the scan
+    a = _rand((64, 300), 62)
+    got, ref = run_both(env, lambda xp, a: xp.cumsum(a[:, ::2], 1) * 2.0 - a[:, :150], dict(a=a))
+    assert_reduction(got, ref, what="scan with consumers")
+    t = ctx.array(torch.from_numpy(a).cuda())
+    plan = (gr.cumsum(t, 1) + 1.0).plan().splitlines()
+    assert len(plan) == 2 and " SCAN " in plan[0] and " MAP " in plan[1]
 
 
 def test_int_sum_exact_and_closed_form(env):

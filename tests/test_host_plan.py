@@ -11,7 +11,7 @@ import re
 import numpy as np
 import pytest
 
-from cases import DOT_CASES, ELEMENTWISE_CASES, REDUCTION_CASES, ROWRED_PROGRAMS
+from cases import DOT_CASES, ELEMENTWISE_CASES, REDUCTION_CASES, ROWRED_PROGRAMS, SCAN_CASES
 from paper_1901_03771_amd import lazy as gr, workloads as wl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -287,6 +287,31 @@ def test_long_reductions_are_split_into_two_stages(ctx):
     full.compile()
     gr.sum(ctx.spec((50000, 48)), axis=0).compile()
     gr.max(ctx.spec((300, 40, 50), gr.GR_I32), axis=(0, 2)).compile()
+
+
+@pytest.mark.parametrize("shape,axis", SCAN_CASES)
+def test_scan_cases_plan_and_compile(ctx, shape, axis):
+    out = gr.cumsum(ctx.spec(shape) * 0.5 + 1.0, axis)
+    assert out.shape == tuple(shape)
+    assert groups(out) == [("SCAN", ["mul", "add", "cumsum"])]      # map-scan: the operand expression is fused
+    out.compile()
+    (gr.cummax(ctx.spec(shape), axis) - gr.cummin(ctx.spec(shape), axis)).compile()
+    i = gr.cumsum(ctx.spec(shape, gr.GR_I32), axis)
+    assert i.dtype_code == gr.GR_I64
+    i.compile()
+
+
+def test_scan_is_a_cut_and_checks_its_axis(ctx):
+    a = ctx.spec((8, 9))
+    out = gr.exp(gr.cumsum(a, 1)) + a
+    assert [k for k, _ in groups(out)] == ["SCAN", "MAP"]
+    for bad in (2, -3):
+        with pytest.raises(gr.GrError) as ei:
+            gr.cumsum(a, bad)
+        assert ei.value.code == "GR_ERR_AXIS"
+    long_line = gr.cumsum(ctx.spec((1 << 22,)), 0)
+    assert "chunks=512" in long_line.plan()
+    assert "gr_scan_sums" in long_line.source(0) and "gr_scan_offsets" in long_line.source(0)
 
 
 def test_rowred_and_dot_cases_compile(ctx):
