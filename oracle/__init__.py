@@ -75,6 +75,8 @@ def lib():
         L.ora_dot.argtypes = [P, P]
         L.ora_scan.restype = P
         L.ora_scan.argtypes = [I, P, I]
+        L.ora_assign.restype = I
+        L.ora_assign.argtypes = [P, P]
         L.ora_set_threads.argtypes = [I]
         _lib = L
     return _lib
@@ -149,6 +151,11 @@ class Array:
 
     def __getitem__(self, key):
         return slice_(self, key)
+
+    def __setitem__(self, key, value):
+        dst = slice_(self, key)
+        if lib().ora_assign(dst._p, _operand(value)._p):
+            raise OracleError(lib().ora_last_error().decode())
 
     @property
     def T(self):

@@ -29,6 +29,9 @@
 //   * cumulative sum / max / min along one axis (the map-scan primitive of
 //     Section 3.2): f32 running sum kept in binary64, every prefix rounded
 //     once to binary32; i32 running sum exact in int64; max/min exact.
+//   * slice assignment dst[...] = value (Listing 6): the value is a finished
+//     array (eager evaluation), then copied element by element into the view;
+//     every view of the same buffer sees the new contents, as in NumPy.
 //   * slice / transpose: views (offset + strides), no data touched
 //     (Section 3.1: index translation for slicing and transpose (i,j)->(j,i)).
 //   * a "weak" scalar (a Python number) takes the array operand's dtype:
@@ -388,6 +391,26 @@ Arr* ora_reduce(int op, const Arr* a, const int* axes, int naxes, int keepdims) 
     else base<int32_t>(r)[lin] = iext;
   }
   return r;
+}
+
+// dst[...] = value for a view `dst`; value must have dst's shape and element type.
+int ora_assign(Arr* dst, const Arr* value) {
+  if (dst->dtype == DT_WEAK || value->dtype != dst->dtype || value->ndim != dst->ndim) { g_err = "assign: dtype or rank differs"; return 1; }
+  for (int d = 0; d < dst->ndim; ++d) if (dst->shape[d] != value->shape[d]) { g_err = "assign: shape differs"; return 1; }
+  // the value may be a view of the destination's own buffer: finish reading before writing
+  int64_t n = count(dst), isz = itemsize(dst->dtype);
+  std::vector<unsigned char> tmp((size_t)(n > 0 ? n : 1) * isz);
+  ora_copy_out(value, tmp.data());
+  unsigned char* out = dst->buf->data();
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[MAXD];
+    unravel(lin, dst->ndim, dst->shape, idx);
+    int64_t off = dst->offset;
+    for (int d = 0; d < dst->ndim; ++d) off += idx[d] * dst->strides[d];
+    std::memcpy(out + off * isz, tmp.data() + lin * isz, (size_t)isz);
+  }
+  return 0;
 }
 
 // Inclusive scan along `axis` (np.cumsum / np.maximum.accumulate / np.minimum.accumulate).

@@ -336,6 +336,40 @@ def test_slice_brute_force_2d():
         X[:, :, :]
 
 
+def test_slice_assignment_aliases_like_numpy():
+    x = np.arange(30, dtype=f32).reshape(5, 6)
+    X = ora.array(x)
+    V = X[1:-1, 2:]                 # view taken before the write
+    X[1:-1, 2:] = V * 2.0 + 1.0      # reads the destination itself
+    want = x.copy()
+    want[1:-1, 2:] = want[1:-1, 2:] * 2 + 1
+    assert np.array_equal(X.numpy(), want)
+    assert np.array_equal(V.numpy(), want[1:-1, 2:])       # the old view sees the new contents
+    # overlapping source and destination: the right-hand side is finished first
+    y = np.arange(10, dtype=np.int32)
+    Y = ora.array(y)
+    Y[1:] = Y[:-1]
+    want = y.copy(); want[1:] = y[:-1]
+    assert np.array_equal(Y.numpy(), want)
+    with pytest.raises(ora.OracleError):
+        Y[2:5] = Y[:2]
+    # Listing 6: closed form on a constant grid (fixed point) and against NumPy on random data
+    const = ora.array(np.full((9, 11), 2.5, f32))
+    assert np.all(wl.jacobi(ora, const, 3).numpy() == 2.5)
+    g = rng(21)
+    grid = g.random((12, 9)).astype(f32)
+    got = wl.jacobi(ora, ora.array(grid), 4).numpy()
+    ref = grid.copy()
+    assert np.array_equal(got, wl.jacobi(np, ref, 4))
+    # hand loop for one sweep
+    one = wl.jacobi(ora, ora.array(grid), 1).numpy()
+    for i in range(1, 11):
+        for j in range(1, 8):
+            s_ = f32(f32(f32(f32(grid[i, j] + grid[i - 1, j]) + grid[i, j + 1]) + grid[i, j - 1]) + grid[i + 1, j])
+            assert one[i, j] == f32(f32(0.2) * s_)
+    assert np.array_equal(one[0], grid[0]) and np.array_equal(one[:, -1], grid[:, -1])
+
+
 def test_ops_read_through_views():
     x = np.arange(30, dtype=f32).reshape(5, 6)
     X = ora.array(x)
