@@ -189,6 +189,19 @@ gr_status gr_materialize(gr_ctx* ctx, gr_array a);
  * alive while the node or anything recorded on top of it is in use. */
 gr_status gr_materialize_into(gr_ctx* ctx, gr_array a, void* dptr, size_t bytes);
 
+/* Slice assignment dst[...] = value with NumPy semantics (Listing 6 of the
+ * paper: center[:] = 0.2*(center+north+east+west+south)).  `dst` must be a
+ * materialised array or a slice/transpose view of one (the storage is
+ * WRITTEN by the library, also when it is a borrowed leaf); `value` must
+ * have dst's shape and element type.  The right-hand side is finished before
+ * the destination changes: if it reads the destination's storage at other
+ * positions than it writes (a stencil), it is evaluated into a temporary and
+ * copied; otherwise one fused kernel writes the destination directly.
+ * Every view of the storage sees the new contents; recorded but unevaluated
+ * arrays that read the storage are evaluated first, so they keep the values
+ * they had when recorded.  Runs asynchronously on the context's stream. */
+gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value);
+
 /* ---- inspection --------------------------------------------------------- */
 
 gr_status gr_ndim(gr_ctx* ctx, gr_array a, int* ndim);

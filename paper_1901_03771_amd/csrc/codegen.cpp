@@ -71,7 +71,9 @@ ArgLayout arg_layout(const GroupPlan& g) {
   L.extra = s;
   s += 4;
   L.ocoef = s;
-  if (g.kind == GroupKind::SCAN) s += g.rank;
+  if (g.kind == GroupKind::SCAN || g.kind == GroupKind::MAP) s += g.rank;
+  L.obase = s;
+  if (g.kind == GroupKind::MAP) s += 1;
   L.total = s;
   return L;
 }
@@ -303,7 +305,11 @@ void gen_map(Em& e) {
     else if (cc == 'G') e.o << " + c0 * " << e.coef((int)gi, cd);
     e.o << ";\n";
   }
-  e.o << "  GM " << cty(g.out_dtype) << "* const po = (GM " << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << " + ((long long)olin * R + r0) * C + c0;\n";
+  // output strides are arguments: a C-contiguous result or the strided view of a slice assignment
+  e.o << "  const long long oc = " << (g.out_unit ? std::string("1") : e.S(e.L.ocoef + cd)) << ", orow = " << (rank >= 2 ? e.S(e.L.ocoef + rd) : std::string("0")) << ";\n";
+  e.o << "  GM " << cty(g.out_dtype) << "* const po = (GM " << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << " + " << e.S(e.L.obase);
+  for (int k = 0; k + 2 < rank; ++k) e.o << " + i" << k << " * " << e.S(e.L.ocoef + k);
+  e.o << " + r0 * orow + c0 * oc;\n";
 
   // static part of a load's address: shifts times runtime coefficients
   auto shift_expr = [&](const Instr& in, bool with_col) {
@@ -387,9 +393,9 @@ void gen_map(Em& e) {
     int ri = 0;
     for (int v = 0; v < g.VR; ++v)
       for (int u = 0; u < g.UC; ++u) {
-        std::string off = std::to_string(v) + " * C + " + std::to_string(u * g.BX * 4);
-        if (g.out_dtype == GR_I64) {
-          for (int j = 0; j < 4; ++j) e.o << "    po[" << off << " + " << j << "] = t" << g.results[ri + j] << ";\n";
+        std::string off = std::to_string(v) + " * orow + " + std::to_string(u * g.BX * 4) + " * oc";
+        if (g.out_dtype == GR_I64 || !g.out_unit) {
+          for (int j = 0; j < 4; ++j) e.o << "    po[" << off << " + " << j << " * oc] = t" << g.results[ri + j] << ";\n";
         } else {
           const char* vt = g.out_dtype == GR_F32 ? "f4u" : "i4u";
           e.o << "    { " << vt << " ov; ov[0] = t" << g.results[ri] << "; ov[1] = t" << g.results[ri + 1] << "; ov[2] = t" << g.results[ri + 2]
@@ -416,7 +422,7 @@ void gen_map(Em& e) {
                         return s + "]";
                       },
                       "0.0f", "s", "            ");
-  e.o << "            po[v * C + cj] = s" << g.result1 << ";\n"
+  e.o << "            po[v * orow + cj * oc] = s" << g.result1 << ";\n"
          "          }\n        }\n  }\n}\n";
 }
 

@@ -19,7 +19,8 @@ struct ArgLayout {
   int consts = 0;              // first constant slot
   int extra = 0;               // kind-specific: GEMV {M, K, workspace, slabs}; REDUCE {outputs, length, workspace, splits};
                                // SCAN {lines, chunk length, workspace, chunks}
-  int ocoef = 0;               // SCAN: first of `rank` output strides
+  int ocoef = 0;               // SCAN, MAP: first of `rank` output strides
+  int obase = 0;               // MAP: element offset of the output's first element
   int total = 0;
 };
 

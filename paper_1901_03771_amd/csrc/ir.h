@@ -38,6 +38,8 @@ struct Node {
   int64_t strides[MAXD] = {0};
   int64_t offset = 0;      // elements from `data` to element (0,..,0)
   bool owns_data = false;  // allocated through the context's allocator
+  bool cow_alias = false;  // data lives in another array's storage (result of a direct slice assignment):
+                           // gets its own copy before that storage is written again
   size_t alloc_bytes = 0;
 
   // SCALAR / CONST payload
@@ -147,6 +149,9 @@ struct GroupPlan {
   int result1 = -1;
 
   // output
+  int64_t out_base = 0;                 // MAP: element offset of output element (0,..,0)
+  int64_t out_orig_coef[MAXD] = {0};    // MAP: output strides per original iteration dimension
+  bool out_unit = true;                 // MAP: innermost output stride is 1 (vector stores)
   gr_dtype out_dtype = GR_F32;
   bool out_per_row = false;  // ROWRED: one value per row instead of one per element
 
@@ -182,9 +187,17 @@ struct GroupPlan {
   std::string signature;
 };
 
+// Strided destination of the requested root (slice assignment); NULL = C-contiguous buffer.
+struct OutSpec {
+  int64_t base = 0;
+  int64_t strides[MAXD] = {0};
+};
+
 struct Plan {
   std::vector<std::unique_ptr<GroupPlan>> groups;
   std::vector<Node*> planned_nodes;
+  const OutSpec* out = nullptr;  // in: where the root's elements go
+  bool out_honoured = true;      // out: false if the root's sub-graph can only write a contiguous buffer
 };
 
 }  // namespace gr

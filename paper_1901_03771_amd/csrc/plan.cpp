@@ -404,7 +404,7 @@ void make_signature(GroupPlan* g) {
   for (int64_t v : {(int64_t)g->kind, (int64_t)g->rank, (int64_t)g->out_dtype, (int64_t)g->out_per_row, (int64_t)g->BX, (int64_t)g->BY,
                     (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads, (int64_t)g->xcd_remap, (int64_t)g->red_mode,
                     (int64_t)g->red_kept_rank, (int64_t)g->gemv_mode, (int64_t)g->LPR, (int64_t)g->KV, (int64_t)g->mat_group,
-                    (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode, (int64_t)g->groups.size()})
+                    (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode, (int64_t)g->out_unit, (int64_t)g->groups.size()})
     put(s, v);
   for (const AccessGroup& ag : g->groups) {
     int64_t cls = (int64_t)ag.dtype;
@@ -425,9 +425,28 @@ void make_signature(GroupPlan* g) {
   g->signature.swap(s);
 }
 
+// The output takes part in dimension collapsing as one more access (its strides need not be
+// those of a C-contiguous array when the root is written through a slice assignment).
+void push_output_group(GroupPlan* g, int n) {
+  AccessGroup og;
+  og.leaf = nullptr;
+  og.dtype = g->out_dtype;
+  for (int k = 0; k < MAXD; ++k) og.structural_zero[k] = true;
+  for (int k = 0; k < n; ++k) { og.coef[k] = g->out_orig_coef[k]; og.structural_zero[k] = g->orig_dims[k] == 1; }
+  og.deltas.insert(std::vector<int64_t>(n, 0));
+  g->groups.push_back(og);
+}
+
+void pop_output_group(GroupPlan* g) {
+  for (int k = 0; k < g->rank; ++k) g->out_coef[k] = g->groups.back().coef[k];
+  g->groups.pop_back();
+  g->out_unit = g->out_coef[g->rank - 1] == 1 || g->dims[g->rank - 1] == 1;
+}
+
 struct Planner {
   gr_ctx* c;
   Node* root;
+  const OutSpec* out = nullptr;
   std::vector<Node*> sub;                 // lazy nodes of the visited sub-DAG, ascending id
   std::set<const Node*> cuts;
   std::map<const Node*, const Node*> owner;
@@ -827,10 +846,20 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     b.rank = n; b.dims = g->orig_dims; b.prog = &g->prog1;
     g->result1 = b.eval(r, im);
     if (!b.invalid.empty()) { *invalid = b.invalid; return GR_OK; }
+    // where the elements go: a C-contiguous buffer, or the strided destination of a slice assignment
+    if (r == pl.root && pl.out && r->ndim > 0) {
+      g->out_base = pl.out->base;
+      for (int d = 0; d < r->ndim; ++d) g->out_orig_coef[d] = pl.out->strides[d];
+    } else {
+      int64_t st = 1;
+      for (int d = n - 1; d >= 0; --d) { g->out_orig_coef[d] = st; st *= g->orig_dims[d]; }
+    }
+    push_output_group(g, n);
     std::vector<Instr>* ps[1] = {&g->prog1};
     normalize_deltas(g, ps, 1, n);
     bool barrier[MAXD] = {false};
     collapse_dims(g, barrier, ps, 1);
+    pop_output_group(g);
     choose_map_schedule(c, g);
     g->owned = owned;
   }
@@ -883,12 +912,16 @@ gr_status expand_patch(gr_ctx* c, GroupPlan* g) {
       }
   r->planned = was_planned;
   if (!b.invalid.empty()) return fail(c, GR_ERR_UNSUPPORTED, "map: patch expansion met an unexpected node");
+  tmp.out_dtype = g->out_dtype;
+  for (int k = 0; k < n; ++k) tmp.out_orig_coef[k] = g->out_orig_coef[k];
+  push_output_group(&tmp, n);
   std::vector<Instr>* ps[1] = {&tmp.prog};
   normalize_deltas(&tmp, ps, 1, n);
   bool barrier[MAXD] = {false};
   // the patch shifts touch only dims that are innermost in their runs, so the collapse
   // decision of the single-point program is reproduced
   collapse_dims(&tmp, barrier, ps, 1);
+  pop_output_group(&tmp);
   bool same = tmp.rank == g->rank && tmp.groups.size() == g->groups.size() && tmp.consts.size() == g->consts.size();
   for (size_t i = 0; same && i < tmp.groups.size(); ++i)
     if (tmp.groups[i].ident != g->groups[i].ident || tmp.groups[i].base != g->groups[i].base) same = false;
@@ -941,6 +974,7 @@ gr_status make_plan(gr_ctx* c, Node* root, Plan* plan) {
   Planner pl;
   pl.c = c;
   pl.root = root;
+  pl.out = plan->out;
   pl.collect();
   pl.initial_cuts();
   for (int iter = 0; iter < 10000; ++iter) {
@@ -975,7 +1009,11 @@ gr_status make_plan(gr_ctx* c, Node* root, Plan* plan) {
         plan->planned_nodes.push_back(r);
       }
     }
-    if (!restart) { fuse_gemv_pairs(c, plan); return GR_OK; }
+    if (!restart) {
+      plan->out_honoured = !plan->out || (!plan->groups.empty() && plan->groups.back()->root == root && plan->groups.back()->kind == GroupKind::MAP);
+      fuse_gemv_pairs(c, plan);
+      return GR_OK;
+    }
   }
   clear_planned(plan);
   plan->groups.clear();

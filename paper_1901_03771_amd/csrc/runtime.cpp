@@ -174,6 +174,8 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
   switch (g.kind) {
     case GroupKind::MAP: {
       if (total == 0) return GR_OK;
+      for (int k2 = 0; k2 < g.rank; ++k2) s[L.ocoef + k2] = (uint64_t)g.out_coef[k2];
+      s[L.obase] = (uint64_t)g.out_base;
       int64_t C = g.dims[g.rank - 1], R = g.rank >= 2 ? g.dims[g.rank - 2] : 1, outer = 1;
       for (int k2 = 0; k2 + 2 < g.rank; ++k2) outer *= g.dims[k2];
       int64_t TC = (int64_t)g.BX * 4 * g.UC, TR = (int64_t)g.BY * g.VR;
@@ -274,9 +276,9 @@ static void extent_of(const Node* n, uintptr_t* lo, uintptr_t* hi) {
   *hi = (uintptr_t)n->data + (mx + 1) * itemsize(n->dtype);
 }
 
-gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out) {
+gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool check_alias) {
   if (c->device < 0) return fail(c, GR_ERR_NODEVICE, "context has no device");
-  if (user_out) {
+  if (user_out && check_alias) {
     uintptr_t olo = (uintptr_t)user_out, ohi = olo + root->count() * itemsize(root->dtype);
     for (const auto& g : plan->groups)
       for (const GroupPlan* gp : {g.get(), g->pair.get()}) {
@@ -325,6 +327,13 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out) {
       r->offset = 0;
       int64_t sstride = 1;
       for (int d = r->ndim - 1; d >= 0; --d) { r->strides[d] = sstride; sstride *= r->shape[d]; }
+      if (r == root && plan->out && plan->out_honoured) {
+        // written straight into another array's storage (slice assignment): the node's data
+        // is that region until the storage is written again
+        r->offset = plan->out->base;
+        for (int d = 0; d < r->ndim; ++d) r->strides[d] = plan->out->strides[d];
+        r->cow_alias = true;
+      }
       r->materialized = true;
       r->planned = false;
     }
@@ -414,7 +423,7 @@ gr_status gr_materialize(gr_ctx* ctx, gr_array a) {
   Plan plan;
   gr_status st = make_plan(ctx, x, &plan);
   if (st != GR_OK) return st;
-  st = execute_plan(ctx, &plan, x, nullptr);
+  st = execute_plan(ctx, &plan, x, nullptr, true);
   clear_planned(&plan);
   return st;
 }
@@ -432,10 +441,197 @@ gr_status gr_materialize_into(gr_ctx* ctx, gr_array a, void* dptr, size_t bytes)
   Plan plan;
   gr_status st = make_plan(ctx, x, &plan);
   if (st != GR_OK) return st;
-  st = execute_plan(ctx, &plan, x, dptr);
+  st = execute_plan(ctx, &plan, x, dptr, true);
   clear_planned(&plan);
   return st;
 }
+
+}  // extern "C"
+
+// ---- slice assignment -----------------------------------------------------------
+
+namespace gr {
+
+static bool resolve_view_rt(const Node* n, const Node** base, int64_t* offset, int64_t* strides) {
+  if (n->materialized) {
+    *base = n;
+    *offset = n->offset;
+    for (int d = 0; d < n->ndim; ++d) strides[d] = n->strides[d];
+    return true;
+  }
+  if (!n->is_view()) return false;
+  int64_t st[MAXD];
+  if (!resolve_view_rt(n->in[0], base, offset, st)) return false;
+  if (n->kind == Kind::SLICE) {
+    for (int d = 0; d < n->ndim; ++d) { *offset += n->start[d] * st[d]; strides[d] = st[d] * n->step[d]; }
+  } else {
+    for (int d = 0; d < n->ndim; ++d) strides[d] = st[n->perm[d]];
+  }
+  return true;
+}
+
+static void view_extent(const Node* base, int ndim, const int64_t* shape, int64_t offset, const int64_t* strides, uintptr_t* lo, uintptr_t* hi) {
+  int64_t mn = offset, mx = offset;
+  for (int d = 0; d < ndim; ++d) {
+    if (shape[d] == 0) { *lo = *hi = 0; return; }
+    int64_t span = (shape[d] - 1) * strides[d];
+    if (span < 0) mn += span; else mx += span;
+  }
+  *lo = (uintptr_t)base->data + mn * itemsize(base->dtype);
+  *hi = (uintptr_t)base->data + (mx + 1) * itemsize(base->dtype);
+}
+
+// Does the (unevaluated) array `n` read memory in [lo, hi)?
+static bool reads_range(const Node* n, uintptr_t lo, uintptr_t hi, std::set<const Node*>* seen) {
+  if (!seen->insert(n).second) return false;
+  if (n->materialized) {
+    uintptr_t a, b;
+    extent_of(n, &a, &b);
+    return a < hi && lo < b;
+  }
+  for (const Node* p : n->in) if (reads_range(p, lo, hi, seen)) return true;
+  return false;
+}
+
+}  // namespace gr
+
+extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
+  if (!ctx) return GR_ERR_ARG;
+  Node* d = lookup(ctx, dst);
+  Node* v = lookup(ctx, value);
+  if (!d || !v) return fail(ctx, GR_ERR_HANDLE, "assign: bad handle");
+  if (d->kind == Kind::SCALAR || v->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "assign: bare scalar operand");
+  const Node* base = nullptr;
+  OutSpec spec;
+  if (!resolve_view_rt(d, &base, &spec.base, spec.strides)) return fail(ctx, GR_ERR_UNSUPPORTED, "assign: destination is not (a view of) a materialised array");
+  if (v->dtype != d->dtype) return fail(ctx, GR_ERR_DTYPE, "assign: element types differ");
+  if (v->ndim != d->ndim) return fail(ctx, GR_ERR_SHAPE, "assign: shapes differ");
+  for (int k = 0; k < d->ndim; ++k) {
+    if (v->shape[k] != d->shape[k]) return fail(ctx, GR_ERR_SHAPE, "assign: shapes differ");
+    if (d->shape[k] > 1 && spec.strides[k] == 0) return fail(ctx, GR_ERR_UNSUPPORTED, "assign: destination elements overlap");
+  }
+  if (ctx->device < 0) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
+  if (d->count() == 0) return GR_OK;
+  uintptr_t lo, hi;
+  view_extent(base, d->ndim, d->shape, spec.base, spec.strides, &lo, &hi);
+
+  // 1. Arrays recorded earlier that read this storage keep the values they had when recorded:
+  //    evaluate them now.  Results of earlier direct assignments that still live inside this
+  //    storage get their own copy.
+  std::vector<gr_array> pending, aliases;
+  for (auto& kv : ctx->nodes) {
+    Node* n = kv.second;
+    if (n == v || n->handle_refs <= 0 || n->kind == Kind::SCALAR) continue;
+    if (n->materialized) {
+      if (n->cow_alias) { uintptr_t a, b; extent_of(n, &a, &b); if (a < hi && lo < b) aliases.push_back(n->id); }
+      continue;
+    }
+    if (n->is_view()) { const Node* vb; int64_t o, st[MAXD]; if (resolve_view_rt(n, &vb, &o, st)) continue; }  // aliases see the new contents
+    std::set<const Node*> seen;
+    if (reads_range(n, lo, hi, &seen)) pending.push_back(n->id);
+  }
+  for (gr_array id : pending) {
+    gr_status st = gr_materialize(ctx, id);
+    if (st != GR_OK) return st;
+  }
+  for (gr_array id : aliases) {
+    Node* n = lookup(ctx, id);
+    if (!n || !n->cow_alias) continue;
+    size_t bytes = (size_t)n->count() * itemsize(n->dtype);
+    void* buf = ctx_alloc(ctx, bytes);
+    if (!buf) return fail(ctx, GR_ERR_OOM, "allocator returned NULL");
+    Plan cp;
+    gr_status st = make_plan(ctx, n, &cp);  // a plain strided copy of an array that has data
+    if (st == GR_OK) st = execute_plan(ctx, &cp, n, buf, false);
+    clear_planned(&cp);
+    if (st != GR_OK) { ctx_free(ctx, buf, bytes); return st; }
+    n->data = buf; n->owns_data = true; n->alloc_bytes = bytes; n->offset = 0; n->cow_alias = false;
+    int64_t sstride = 1;
+    for (int k = n->ndim - 1; k >= 0; --k) { n->strides[k] = sstride; sstride *= n->shape[k]; }
+  }
+  v = lookup(ctx, value);
+  if (!v) return fail(ctx, GR_ERR_HANDLE, "assign: value handle vanished");
+
+  // 2. Can one fused kernel write the destination directly?  Only if the value is still
+  //    unevaluated, its last sub-graph is a map, and that sub-graph reads the destination's
+  //    storage at exactly the positions it writes (or not at all).
+  bool direct = false;
+  resolve_view_rt(d, &base, &spec.base, spec.strides);
+  const Node* vb = nullptr; int64_t vo, vst[MAXD];
+  const bool value_has_data = resolve_view_rt(v, &vb, &vo, vst);
+  if (!value_has_data) {
+    Plan plan;
+    plan.out = &spec;
+    gr_status st = make_plan(ctx, v, &plan);
+    if (st != GR_OK) return st;
+    bool safe = plan.out_honoured;
+    if (safe) {
+      const GroupPlan& g = *plan.groups.back();
+      for (const AccessGroup& ag : g.groups) {
+        if (!ag.leaf->materialized) continue;
+        uintptr_t a, b;
+        extent_of(ag.leaf, &a, &b);
+        if (!(a < hi && lo < b)) continue;
+        bool same = ag.leaf->data == base->data && ag.base == g.out_base && ag.deltas.size() == 1;
+        for (int k = 0; same && k < g.rank; ++k) if (ag.coef[k] != g.out_coef[k]) same = false;
+        if (!same) safe = false;
+      }
+      // earlier sub-graphs of the plan finish before the last one starts: no hazard there
+    }
+    if (safe) {
+      st = execute_plan(ctx, &plan, v, base->data, false);
+      clear_planned(&plan);
+      if (st != GR_OK) return st;
+      direct = true;
+    } else {
+      clear_planned(&plan);
+    }
+  }
+  if (direct) return GR_OK;
+
+  // 3. General case (NumPy's own cost model): finish the value in its own buffer, then copy.
+  if (!value_has_data) {
+    gr_status st = gr_materialize(ctx, value);
+    if (st != GR_OK) return st;
+    v = lookup(ctx, value);
+  } else {
+    // the value is an alias of materialised data; if it overlaps the destination it is
+    // copied to a temporary first (overlapping source and destination)
+    uintptr_t a, b;
+    view_extent(vb, v->ndim, v->shape, vo, vst, &a, &b);
+    if (a < hi && lo < b) {
+      size_t bytes = (size_t)v->count() * itemsize(v->dtype);
+      void* buf = ctx_alloc(ctx, bytes);
+      if (!buf) return fail(ctx, GR_ERR_OOM, "allocator returned NULL");
+      Plan cp;
+      gr_status st = make_plan(ctx, v, &cp);
+      if (st == GR_OK) st = execute_plan(ctx, &cp, v, buf, false);
+      clear_planned(&cp);
+      if (st != GR_OK) { ctx_free(ctx, buf, bytes); return st; }
+      // copy tmp -> destination through a temporary leaf node
+      gr_array tmp_h = 0;
+      st = gr_array_from_device(ctx, buf, v->dtype, v->ndim, v->shape, nullptr, &tmp_h);
+      if (st != GR_OK) { ctx_free(ctx, buf, bytes); return st; }
+      Node* t = lookup(ctx, tmp_h);
+      Plan wp;
+      wp.out = &spec;
+      st = make_plan(ctx, t, &wp);
+      if (st == GR_OK) st = execute_plan(ctx, &wp, t, base->data, false);
+      clear_planned(&wp);
+      gr_release(ctx, tmp_h);
+      ctx_free(ctx, buf, bytes);  // stream order: the copy kernel is already queued before any reuse
+      return st;
+    }
+  }
+  Plan wp;
+  wp.out = &spec;
+  gr_status st = make_plan(ctx, v, &wp);
+  if (st == GR_OK) st = execute_plan(ctx, &wp, v, base->data, false);
+  clear_planned(&wp);
+  return st;
+}
+
+extern "C" {
 
 static gr_status copy_out(const std::string& s, char* buf, size_t cap, size_t* needed) {
   if (needed) *needed = s.size() + 1;

@@ -32,7 +32,7 @@ STATUS = {0: "GR_OK", 1: "GR_ERR_HANDLE", 2: "GR_ERR_SHAPE", 3: "GR_ERR_DTYPE", 
 SYMBOLS = [
     "gr_ctx_create", "gr_ctx_destroy", "gr_ctx_set_stream", "gr_ctx_set_allocator", "gr_ctx_set_option", "gr_sync",
     "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose",
-    "gr_reduce", "gr_scan", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_ndim", "gr_shape", "gr_dtype_of",
+    "gr_reduce", "gr_scan", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_assign", "gr_ndim", "gr_shape", "gr_dtype_of",
     "gr_is_materialized", "gr_data_ptr", "gr_retain", "gr_release", "gr_plan_describe", "gr_plan_source",
     "gr_plan_compile", "gr_stats", "gr_profile_reset", "gr_profile_read", "gr_stream_copy", "gr_stream_read",
 ]
@@ -80,7 +80,7 @@ def lib():
         "gr_transpose": [P, U64, PP(I), PP(U64)],
         "gr_reduce": [P, I, U64, PP(I), I, I, PP(U64)], "gr_dot": [P, U64, U64, PP(U64)],
         "gr_scan": [P, I, U64, I, PP(U64)],
-        "gr_materialize": [P, U64], "gr_materialize_into": [P, U64, P, SZ],
+        "gr_materialize": [P, U64], "gr_assign": [P, U64, U64], "gr_materialize_into": [P, U64, P, SZ],
         "gr_ndim": [P, U64, PP(I)], "gr_shape": [P, U64, PP(I64)], "gr_dtype_of": [P, U64, PP(I)],
         "gr_is_materialized": [P, U64, PP(I)], "gr_data_ptr": [P, U64, PP(P), PP(I64)],
         "gr_retain": [P, U64], "gr_release": [P, U64],
@@ -325,6 +325,12 @@ class Array:
 
     def __getitem__(self, key):
         return slice_(self, key)
+
+    def __setitem__(self, key, value):
+        if not isinstance(value, Array):
+            raise GrError(5, "only arrays can be assigned")
+        dst = slice_(self, key)
+        self.ctx.check(lib().gr_assign(self.ctx._p, dst.h, value.h))
 
     @property
     def T(self):

@@ -314,6 +314,67 @@ def test_gemv_pair_matches_two_pass_execution(env):
     ctx2.close()
 
 
+# ------------------------------------------------------------- slice assignment ----
+def test_jacobi_listing6(env):
+    gr, ctx, torch = env
+    for shape, iters in [((12, 9), 4), ((151, 1234), 3), ((64, 4096), 2)]:
+        grid = np.random.default_rng(70).random(shape).astype(f32)
+        t = torch.from_numpy(grid).cuda()
+        out = wl.jacobi(gr, ctx.array(t), iters)
+        ref = wl.jacobi(ora, ora.array(grid), iters).numpy()
+        assert np.array_equal(out.numpy(), ref), f"jacobi {shape}"
+        assert np.array_equal(t.cpu().numpy(), ref), "the caller's tensor is the grid's storage"
+
+
+def test_assign_direct_in_place_and_strided_destinations(env):
+    gr, ctx, torch = env
+    a0 = _rand((40, 60), 71)
+    b0 = _rand((40, 60), 72)
+    ta, tb = torch.from_numpy(a0).cuda(), torch.from_numpy(b0).cuda()
+    A, B = ctx.array(ta), ctx.array(tb)
+    s0 = ctx.stats()["kernel_launches"]
+    A[:] = A * 2.0 + B                      # reads the destination only where it writes: one kernel
+    assert ctx.stats()["kernel_launches"] - s0 == 1
+    want = a0 * f32(2) + b0
+    assert np.array_equal(ta.cpu().numpy(), want)
+    A[::2, 1::3] = B[::2, 1::3] * 3.0        # strided destination
+    want[::2, 1::3] = b0[::2, 1::3] * f32(3)
+    assert np.array_equal(ta.cpu().numpy(), want)
+    A.T[5:9] = gr.sqrt(abs(B.T[5:9]))        # through a transposed view
+    want.T[5:9] = np.sqrt(np.abs(b0.T[5:9]))
+    assert np.array_equal(ta.cpu().numpy(), want)
+    A[3:10] = A[2:9]                         # overlapping source and destination rows
+    want[3:10] = want[2:9].copy()
+    assert np.array_equal(ta.cpu().numpy(), want)
+    A[1:, :] = A[:-1, :] + A[1:, :]          # shifted read of the destination: evaluated first, then copied
+    want[1:, :] = want[:-1, :] + want[1:, :]
+    assert np.array_equal(ta.cpu().numpy(), want)
+    i = ctx.array(torch.arange(10, dtype=torch.int32, device="cuda"))
+    i[1:] = i[:-1]
+    assert i.numpy().tolist() == [0, 0, 1, 2, 3, 4, 5, 6, 7, 8]
+    for bad, code in [(lambda: A.__setitem__(slice(0, 2), B[0:3]), "GR_ERR_SHAPE"), (lambda: A.__setitem__(slice(None), i), "GR_ERR_DTYPE"),
+                      (lambda: (A + 1.0).__setitem__(slice(None), B), "GR_ERR_UNSUPPORTED")]:
+        with pytest.raises(gr.GrError) as ei:
+            bad()
+        assert ei.value.code == code
+
+
+def test_assign_keeps_recorded_values(env):
+    gr, ctx, torch = env
+    a0, b0 = _rand((300,), 73), _rand((300,), 74)
+    ta, tb = torch.from_numpy(a0).cuda(), torch.from_numpy(b0).cuda()
+    A, B = ctx.array(ta), ctx.array(tb)
+    t = A + 1.0                    # recorded, not evaluated, reads A
+    view = A[10:20]                # alias of A
+    v = B * 2.0                    # the value, kept by the caller
+    A[:] = v                       # written directly into A's storage
+    assert np.array_equal(t.numpy(), a0 + f32(1)), "a recorded array keeps the values it had when recorded"
+    assert np.array_equal(view.numpy(), (b0 * f32(2))[10:20]), "a view sees the new contents"
+    A[:] = A * 0.0                 # the storage changes again
+    assert np.array_equal(v.numpy(), b0 * f32(2)), "the assigned value is an array of its own"
+    assert np.all(ta.cpu().numpy() == 0)
+
+
 def test_mnist_listing2(env):
     g = np.random.default_rng(37)
     arrays = dict(W=g.standard_normal((200, 10)).astype(f32), a=g.standard_normal(200).astype(f32), b=g.standard_normal(10).astype(f32))
