@@ -241,6 +241,45 @@ def main():
             extras[label + "_us_per_step"] = round(d_ms / k * 1e3, 2)
             del ow
             torch.cuda.empty_cache()
+        # rows beyond the five configurations: two-stage reduction, map-scan, the full Jacobi loop
+        def timed(fn, iters, warm=3):
+            for _ in range(warm):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / iters
+
+        n = 1 << 27
+        xs = [torch.rand(n, device="cuda") for _ in range(2)]
+        out1 = torch.empty((), device="cuda")
+        k = [0]
+
+        def red():
+            k[0] += 1
+            gr.sum(gr.sqrt(ctx.array(xs[k[0] % 2]))).materialize_into(out1)
+        ms = timed(red, 20)
+        extras["sum_sqrt_n2^27_GBps"] = round(4 * n / (ms * 1e-3) / 1e9, 1)
+        outn = torch.empty(n, device="cuda")
+
+        def scan():
+            k[0] += 1
+            gr.cumsum(ctx.array(xs[k[0] % 2]), 0).materialize_into(outn)
+        ms = timed(scan, 10)
+        extras["cumsum_n2^27_GBps"] = round(8 * n / (ms * 1e-3) / 1e9, 1)
+        del xs, outn
+        torch.cuda.empty_cache()
+        grid = ctx.array(torch.rand(8192, 8192, device="cuda"))
+        sweeps = 10
+        ms = timed(lambda: wl.jacobi(gr, grid, sweeps), 5, warm=1)
+        extras["jacobi_8192_GBps_per_sweep"] = round((4 * 8192 * 8192 + 4 * 8190 * 8190) / (ms / sweeps * 1e-3) / 1e9, 1)
+        extras["jacobi_8192_us_per_sweep"] = round(ms / sweeps * 1e3, 1)
+        del grid
+        torch.cuda.empty_cache()
         result["supplementary"] = extras
 
     result["stats"] = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in ctx.stats().items()}

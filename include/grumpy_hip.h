@@ -112,6 +112,13 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *   "gemv_pair"       1 (default) = a contraction A.v whose epilogue result r
  *                     feeds the contraction A^T.r runs with it in one pass
  *                     over A; 0 = two passes
+ *   "async_compile"   1 (default) = the kernels of all sub-graphs of a request
+ *                     are compiled concurrently on host threads while earlier
+ *                     sub-graphs already run (compilation overlapped with
+ *                     execution, Section 6 of the paper); 0 = one after another
+ *   "disk_cache"      1 (default) = compiled code objects are kept in
+ *                     $GR_CACHE_DIR (default ~/.cache/grumpy_hip) keyed on
+ *                     the sub-graph signature; 0 = in-memory cache only
  *   "profile"         1 = bracket every launch with HIP events (gr_profile_*)
  * Unknown key: GR_ERR_ARG. */
 gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value);
@@ -246,6 +253,7 @@ typedef struct {
   uint64_t cache_misses;      /* = run-time compilations */
   double compile_ms;          /* total time inside the run-time compiler */
   uint64_t bytes_allocated;   /* by the context's allocator, cumulative */
+  uint64_t disk_hits;         /* cache misses served from the on-disk code-object cache */
 } gr_stats_t;
 
 gr_status gr_stats(gr_ctx* ctx, gr_stats_t* out);

@@ -767,6 +767,30 @@ void gen_scan(Em& e) {
     e.o << "  GM " << TA << "* const ws = (GM " << TA << "*)" << e.slot(e.L.extra + 2) << ";\n  (void)ws; (void)CH; (void)po; (void)L;\n";
   };
 
+  // mode 0: the four elements a lane owns in a tile, fetched with one dwordx4 where the tile is
+  // full (the scanned axis is contiguous for every access that follows it)
+  auto tile_loads = [&](const std::string& ind) {
+    for (size_t i = 0; i < g.prog.size(); ++i) {
+      const Instr& in = g.prog[i];
+      if (in.kind != IKind::LOAD) continue;
+      const AccessGroup& ag = g.groups[in.group];
+      std::ostringstream base;
+      base << "p" << in.group;
+      for (int k = 0; k < sd; ++k) if (!ag.structural_zero[k] && in.delta[k]) base << " + " << in.delta[k] << " * " << e.coef(in.group, k);
+      e.o << ind << cty(in.dtype) << " l" << i << "[4];\n";
+      if (ag.structural_zero[sd]) {
+        e.o << ind << "for (int j = 0; j < 4; ++j) l" << i << "[j] = (" << base.str() << ")[0];\n";
+      } else if (in.dtype == GR_I64) {
+        e.o << ind << "for (int j = 0; j < 4; ++j) l" << i << "[j] = (c + j < cend) ? (" << base.str() << ")[c + j + " << in.delta[sd] << "] : 0;\n";
+      } else {
+        e.o << ind << "if (c + 4 <= cend) { const " << vty4(in.dtype) << " w = " << e.ld(in.group, vty4(in.dtype), base.str() + " + c + " + std::to_string(in.delta[sd]))
+            << "; l" << i << "[0] = w[0]; l" << i << "[1] = w[1]; l" << i << "[2] = w[2]; l" << i << "[3] = w[3]; }\n";
+        e.o << ind << "else { for (int j = 0; j < 4; ++j) l" << i << "[j] = (c + j < cend) ? (" << base.str() << ")[c + j + " << in.delta[sd] << "] : " << Em::zero(in.dtype) << "; }\n";
+      }
+    }
+  };
+  auto tile_value = [](const Instr&, int id) { return "l" + std::to_string(id) + "[j]"; };
+
   if (g.scan_mode == 1) {
     kernel_head(e, "gr_scan");
     head(false);
@@ -782,9 +806,11 @@ void gen_scan(Em& e) {
   head(true);
   e.o << "  __shared__ long long gr_sm[4];\n";
   e.o << "  const long long cbeg = chunk * CH, cend = (cbeg + CH < L) ? cbeg + CH : L;\n  " << TA << " acc = " << ident << ";\n";
-  e.o << "  for (long long j = cbeg + threadIdx.x; j < cend; j += 256) {\n";
-  emit_scalar_program(e, g.prog, {ph.value}, load_at("j"), "0.0f", "t", "    ");
-  e.o << "    acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n  }\n";
+  e.o << "  for (long long t0 = cbeg; t0 < cend; t0 += 1024) {\n    const long long c = t0 + threadIdx.x * 4;\n";
+  tile_loads("    ");
+  e.o << "#pragma unroll\n    for (int j = 0; j < 4; ++j) {\n      if (c + j < cend) {\n";
+  emit_scalar_program(e, g.prog, {ph.value}, tile_value, "0.0f", "t", "        ");
+  e.o << "        acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n      }\n    }\n  }\n";
   e.o << "  acc = gr_lanes0(acc);\n  { " << TA << "* sm = (" << TA << "*)gr_sm;\n    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;\n    __syncthreads();\n"
          "    if (threadIdx.x == 0) ws[line * NCHUNK + chunk] = gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])); }\n}\n";
 
@@ -811,15 +837,22 @@ void gen_scan(Em& e) {
   e.o << "  " << TA << " carry = NCHUNK > 1 ? ws[line * NCHUNK + chunk] : " << ident << ";\n";
   e.o << "  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;\n  int buf = 0;\n";
   e.o << "  for (long long t0 = cbeg; t0 < cend; t0 += 1024) {\n    const long long c = t0 + threadIdx.x * 4;\n    " << TA << " v[4];\n";
+  tile_loads("    ");
   e.o << "#pragma unroll\n    for (int j = 0; j < 4; ++j) {\n      v[j] = " << ident << ";\n      if (c + j < cend) {\n";
-  emit_scalar_program(e, g.prog, {ph.value}, load_at("(c + j)"), "0.0f", "t", "        ");
+  emit_scalar_program(e, g.prog, {ph.value}, tile_value, "0.0f", "t", "        ");
   e.o << "        v[j] = " << conv("t" + std::to_string(ph.value)) << ";\n      }\n    }\n";
   e.o << "    v[1] = gr_comb0(v[0], v[1]); v[2] = gr_comb0(v[1], v[2]); v[3] = gr_comb0(v[2], v[3]);\n    " << TA << " x = v[3];\n";
   for (int d = 1; d < 64; d <<= 1) e.o << "    { const " << TA << " y = gr_up(x, " << d << "); if (lane >= " << d << ") x = gr_comb0(y, x); }\n";
   e.o << "    " << TA << "* sm = (" << TA << "*)gr_sm[buf];\n    if (lane == 63) sm[wave] = x;\n    __syncthreads();\n";
   e.o << "    " << TA << " base = carry;\n    for (int q = 0; q < wave; ++q) base = gr_comb0(base, sm[q]);\n";
   e.o << "    { " << TA << " ex = gr_up(x, 1); if (lane != 0) base = gr_comb0(base, ex); }\n";
-  e.o << "    for (int j = 0; j < 4; ++j) if (c + j < cend) po[c + j] = gr_comb0(base, v[j]);\n";
+  if (ph.out_dtype == GR_I64)
+    e.o << "    for (int j = 0; j < 4; ++j) if (c + j < cend) po[c + j] = gr_comb0(base, v[j]);\n";
+  else {
+    const char* vt = ph.out_dtype == GR_F32 ? "f4u" : "i4u";
+    e.o << "    if (c + 4 <= cend) { " << vt << " ov; for (int j = 0; j < 4; ++j) ov[j] = gr_comb0(base, v[j]); *(GM " << vt << "*)(po + c) = ov; }\n"
+           "    else { for (int j = 0; j < 4; ++j) if (c + j < cend) po[c + j] = gr_comb0(base, v[j]); }\n";
+  }
   e.o << "    carry = gr_comb0(carry, gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])));\n    buf ^= 1;\n  }\n}\n";
 }
 

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <chrono>
+#include <future>
 #include <string>
 #include <unordered_map>
 #include <vector>
@@ -29,6 +30,8 @@ struct gr_ctx {
   int64_t opt_rowred_threads = 0;
   int64_t opt_gemv_slabs = 0, opt_gemv_unroll = 0;
   int64_t opt_gemv_pair = 1;
+  int64_t opt_async_compile = 1;
+  int64_t opt_disk_cache = 1;
 
   // allocator
   void* (*alloc_fn)(size_t, void*) = nullptr;
@@ -47,6 +50,16 @@ struct gr_ctx {
     std::string name;
   };
   std::unordered_map<std::string, Kernel> cache;
+
+  // run-time compilations in flight (signature -> job), see runtime.cpp
+  struct CompileJob {
+    std::string src, log, kernel;
+    std::vector<char> code;
+    bool ok = false;
+    double ms = 0.0;
+  };
+  std::unordered_map<std::string, std::pair<std::shared_ptr<CompileJob>, std::future<void>>> pending;
+  std::string cache_dir;       // "" = not resolved yet, "-" = unavailable
 
   // workspace for two-stage kernels
   void* workspace = nullptr;
@@ -86,6 +99,7 @@ std::string generate_source(const GroupPlan& g);
 std::string kernel_name(const GroupPlan& g);
 
 // runtime.cpp
+gr_status prepare_group(gr_ctx* c, GroupPlan& g);
 gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out);
 gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr, void* pair_out_ptr);
 gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool check_alias);

@@ -102,6 +102,8 @@ gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   else if (k == "gemv_slabs") ctx->opt_gemv_slabs = value;
   else if (k == "gemv_unroll") ctx->opt_gemv_unroll = value;
   else if (k == "gemv_pair") ctx->opt_gemv_pair = value;
+  else if (k == "async_compile") ctx->opt_async_compile = value;
+  else if (k == "disk_cache") ctx->opt_disk_cache = value;
   else return fail(ctx, GR_ERR_ARG, "unknown option '" + k + "'");
   return GR_OK;
 }

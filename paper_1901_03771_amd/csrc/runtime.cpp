@@ -12,6 +12,9 @@
 #include <chrono>
 #include <cstdio>
 #include <cstdlib>
+#include <sys/stat.h>
+#include <sys/types.h>
+#include <unistd.h>
 
 #include "codegen.h"
 #include "ctx.h"
@@ -54,42 +57,99 @@ void ctx_free(gr_ctx* c, void* p, size_t bytes) {
   c->pool_free[(bytes + 255) & ~(size_t)255].push_back(p);
 }
 
-gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
-  auto it = c->cache.find(g.signature);
-  if (it != c->cache.end()) {
-    c->stats.cache_hits++;
-    *out = &it->second;
-    return GR_OK;
-  }
-  c->stats.cache_misses++;
+// ---- run-time compilation: in-memory cache, on-disk cache, host threads -----------------
+
+// hipRTC on a worker thread: touches nothing but its job.  No FMA contraction and no fast-math
+// (every recorded op rounds once, as in eager evaluation); packed FP32 instructions disabled.
+static void run_hiprtc(gr_ctx::CompileJob* j) {
   auto t0 = std::chrono::steady_clock::now();
-  gr_status est = expand_patch(c, &g);
-  if (est != GR_OK) return est;
-  std::string src = generate_source(g);
-  if (getenv("GR_LOG")) fprintf(stderr, "---- generated kernel ----\n%s\n", src.c_str());
   hiprtcProgram prog;
-  if (hiprtcCreateProgram(&prog, src.c_str(), "gr_kernel.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
-    return fail(c, GR_ERR_COMPILE, "hiprtcCreateProgram failed");
-  // No FMA contraction and no fast-math: every recorded op rounds once, as in
-  // eager evaluation.  Packed FP32 instructions are disabled.
+  if (hiprtcCreateProgram(&prog, j->src.c_str(), "gr_kernel.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS) {
+    j->log = "hiprtcCreateProgram failed";
+    return;
+  }
   const char* opts[] = {"--offload-arch=gfx950", "-O3", "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
-  int nopts = 7;
-  hiprtcResult r = hiprtcCompileProgram(prog, nopts, opts);
+  hiprtcResult r = hiprtcCompileProgram(prog, 7, opts);
   if (r != HIPRTC_SUCCESS) {
     size_t n = 0;
     hiprtcGetProgramLogSize(prog, &n);
-    std::string log(n, '\0');
-    if (n) hiprtcGetProgramLog(prog, &log[0]);
+    j->log.assign(n, '\0');
+    if (n) hiprtcGetProgramLog(prog, &j->log[0]);
     hiprtcDestroyProgram(&prog);
-    if (getenv("GR_LOG")) fprintf(stderr, "%s\n", src.c_str());
-    return fail(c, GR_ERR_COMPILE, "hipRTC: " + log);
+    return;
   }
   size_t cs = 0;
   hiprtcGetCodeSize(prog, &cs);
-  gr_ctx::Kernel k;
-  k.code.resize(cs);
-  hiprtcGetCode(prog, k.code.data());
+  j->code.resize(cs);
+  hiprtcGetCode(prog, j->code.data());
   hiprtcDestroyProgram(&prog);
+  j->ok = true;
+  j->ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+}
+
+static const char kDiskMagic[8] = {'G', 'R', 'C', 'O', '0', '0', '0', '2'};
+
+static std::string disk_path(gr_ctx* c, const std::string& sig) {
+  if (!c->opt_disk_cache) return "";
+  if (c->cache_dir.empty()) {
+    const char* env = getenv("GR_CACHE_DIR");
+    const char* home = getenv("HOME");
+    std::string dir = env ? env : (home ? std::string(home) + "/.cache/grumpy_hip" : "");
+    c->cache_dir = "-";
+    if (!dir.empty()) {
+      std::string cmd;
+      // create the directory (and parents) with plain mkdir calls
+      for (size_t i = 1; i <= dir.size(); ++i)
+        if (i == dir.size() || dir[i] == '/') ::mkdir(dir.substr(0, i).c_str(), 0755);
+      struct stat st;
+      if (::stat(dir.c_str(), &st) == 0 && S_ISDIR(st.st_mode)) c->cache_dir = dir;
+    }
+  }
+  if (c->cache_dir == "-") return "";
+  uint64_t h = 1469598103934665603ull;  // FNV-1a over a tool tag and the signature
+  const std::string tag = std::string("grumpy-hip-2|") + std::to_string(HIP_VERSION) + "|gfx950|O3|";
+  for (unsigned char ch : tag) { h ^= ch; h *= 1099511628211ull; }
+  for (unsigned char ch : sig) { h ^= ch; h *= 1099511628211ull; }
+  char name[64];
+  snprintf(name, sizeof name, "/%016llx_%zu.co", (unsigned long long)h, sig.size());
+  return c->cache_dir + name;
+}
+
+static bool disk_load(const std::string& path, const std::string& sig, std::vector<char>* code) {
+  if (path.empty()) return false;
+  FILE* f = fopen(path.c_str(), "rb");
+  if (!f) return false;
+  bool ok = false;
+  char magic[8];
+  uint64_t sl = 0, cl = 0;
+  if (fread(magic, 1, 8, f) == 8 && std::memcmp(magic, kDiskMagic, 8) == 0 && fread(&sl, 8, 1, f) == 1 && sl == sig.size()) {
+    std::string stored(sl, '\0');
+    if ((sl == 0 || fread(&stored[0], 1, sl, f) == sl) && stored == sig && fread(&cl, 8, 1, f) == 1 && cl > 0 && cl < (1ull << 30)) {
+      code->resize(cl);
+      ok = fread(code->data(), 1, cl, f) == cl;
+    }
+  }
+  fclose(f);
+  return ok;
+}
+
+static void disk_store(const std::string& path, const std::string& sig, const std::vector<char>& code) {
+  if (path.empty()) return;
+  std::string tmp = path + ".tmp" + std::to_string((long long)getpid());
+  FILE* f = fopen(tmp.c_str(), "wb");
+  if (!f) return;
+  uint64_t sl = sig.size(), cl = code.size();
+  bool ok = fwrite(kDiskMagic, 1, 8, f) == 8 && fwrite(&sl, 8, 1, f) == 1 && fwrite(sig.data(), 1, sl, f) == sl &&
+            fwrite(&cl, 8, 1, f) == 1 && fwrite(code.data(), 1, cl, f) == cl;
+  ok = (fclose(f) == 0) && ok;
+  if (ok) ::rename(tmp.c_str(), path.c_str());  // atomic: readers see a whole file or none
+  else ::remove(tmp.c_str());
+}
+
+// Loads a code object and publishes the kernel in the in-memory cache.
+static gr_status finish_kernel(gr_ctx* c, const GroupPlan& g, std::vector<char>&& code, gr_ctx::Kernel** out) {
+  gr_ctx::Kernel k;
+  k.code = std::move(code);
   k.name = kernel_name(g);
   if (c->device >= 0) {
     GR_HIP(c, hipModuleLoadData(&k.module, k.code.data()));
@@ -101,10 +161,58 @@ gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
       GR_HIP(c, hipModuleGetFunction(&k.fn3, k.module, "gr_scan_offsets"));
     }
   }
-  c->stats.compile_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
   auto ins = c->cache.emplace(g.signature, std::move(k));
-  *out = &ins.first->second;
+  if (out) *out = &ins.first->second;
   return GR_OK;
+}
+
+// Starts whatever a later compile_group() of this sub-graph will need: nothing on a cache
+// hit, a module load on a disk hit, otherwise a hipRTC job on a host thread.  Calling this for
+// every sub-graph of a request before running the first one overlaps compilation with
+// execution (the paper names JIT time as its main bottleneck and pipelining as the remedy).
+gr_status prepare_group(gr_ctx* c, GroupPlan& g) {
+  if (c->cache.count(g.signature) || c->pending.count(g.signature)) return GR_OK;
+  std::vector<char> code;
+  if (disk_load(disk_path(c, g.signature), g.signature, &code)) {
+    c->stats.cache_misses++;
+    c->stats.disk_hits++;
+    return finish_kernel(c, g, std::move(code), nullptr);
+  }
+  gr_status est = expand_patch(c, &g);
+  if (est != GR_OK) return est;
+  auto job = std::make_shared<gr_ctx::CompileJob>();
+  job->src = generate_source(g);
+  if (getenv("GR_LOG")) fprintf(stderr, "---- generated kernel ----\n%s\n", job->src.c_str());
+  gr_ctx::CompileJob* raw = job.get();
+  std::future<void> fut = c->opt_async_compile ? std::async(std::launch::async, run_hiprtc, raw) : std::async(std::launch::deferred, run_hiprtc, raw);
+  c->pending.emplace(g.signature, std::make_pair(job, std::move(fut)));
+  return GR_OK;
+}
+
+gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
+  auto it = c->cache.find(g.signature);
+  if (it != c->cache.end()) {
+    c->stats.cache_hits++;
+    *out = &it->second;
+    return GR_OK;
+  }
+  gr_status st = prepare_group(c, g);
+  if (st != GR_OK) return st;
+  it = c->cache.find(g.signature);
+  if (it != c->cache.end()) { *out = &it->second; return GR_OK; }  // served from disk
+  auto pit = c->pending.find(g.signature);
+  if (pit == c->pending.end()) return fail(c, GR_ERR_COMPILE, "no compilation job for this sub-graph");
+  pit->second.second.get();  // wait for (or, when deferred, run) the job
+  std::shared_ptr<gr_ctx::CompileJob> job = pit->second.first;
+  c->pending.erase(pit);
+  c->stats.cache_misses++;
+  c->stats.compile_ms += job->ms;
+  if (!job->ok) {
+    if (getenv("GR_LOG")) fprintf(stderr, "%s\n", job->src.c_str());
+    return fail(c, GR_ERR_COMPILE, "hipRTC: " + job->log);
+  }
+  disk_store(disk_path(c, g.signature), g.signature, job->code);
+  return finish_kernel(c, g, std::move(job->code), out);
 }
 
 static gr_status launch(gr_ctx* c, hipFunction_t fn, const std::string& name, int64_t grid, std::vector<uint64_t>& args) {
@@ -293,6 +401,10 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
   }
   c->stats.materialize_calls++;
   for (auto& gp : plan->groups) {
+    gr_status pst = prepare_group(c, *gp);
+    if (pst != GR_OK) return pst;
+  }
+  for (auto& gp : plan->groups) {
     GroupPlan& g = *gp;
     gr_ctx::Kernel* k = nullptr;
     gr_status st = compile_group(c, g, &k);
@@ -383,6 +495,8 @@ gr_status gr_sync(gr_ctx* ctx) {
 gr_status gr_ctx_destroy(gr_ctx* ctx) {
   if (!ctx) return GR_ERR_ARG;
   if (ctx->device >= 0) (void)hipStreamSynchronize(ctx->stream);
+  for (auto& kv : ctx->pending) if (kv.second.second.valid()) kv.second.second.wait();
+  ctx->pending.clear();
   std::vector<Node*> all;
   for (auto& kv : ctx->nodes) all.push_back(kv.second);
   for (Node* n : all) {
@@ -678,9 +792,13 @@ gr_status gr_plan_compile(gr_ctx* ctx, gr_array a) {
   gr_status st = make_plan(ctx, x, &plan);
   if (st != GR_OK) return st;
   for (auto& g : plan.groups) {
+    st = prepare_group(ctx, *g);
+    if (st != GR_OK) break;
+  }
+  for (auto& g : plan.groups) {
+    if (st != GR_OK) break;
     gr_ctx::Kernel* k = nullptr;
     st = compile_group(ctx, *g, &k);
-    if (st != GR_OK) break;
   }
   clear_planned(&plan);
   return st;

@@ -8,6 +8,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+# compiled kernels of a test session go to a private directory, not to ~/.cache
+_CACHE = os.path.join(ROOT, ".pytest_cache", "grumpy_hip_kernels")
+os.makedirs(_CACHE, exist_ok=True)
+os.environ.setdefault("GR_CACHE_DIR", _CACHE)
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 

@@ -331,6 +331,56 @@ def test_same_structure_hits_the_kernel_cache(ctx):
     assert s1["cache_misses"] == s0["cache_misses"] and s1["cache_hits"] == s0["cache_hits"] + 1
 
 
+def test_disk_cache_round_trip_and_corruption(tmp_path, monkeypatch):
+    monkeypatch.setenv("GR_CACHE_DIR", str(tmp_path / "kernels"))
+
+    def program(c):
+        x = c.spec((64, 300))
+        return gr.tanh(x * 3.0 + 0.125) - gr.sum(gr.sqrt(abs(x)), axis=0, keepdims=True)
+
+    c1 = gr.Context(device=-1)
+    program(c1).compile()
+    s1 = c1.stats()
+    assert s1["cache_misses"] == 2 and s1["disk_hits"] == 0 and s1["compile_ms"] > 0
+    files = sorted((tmp_path / "kernels").iterdir())
+    assert len(files) == 2 and all(f.suffix == ".co" for f in files)
+    c2 = gr.Context(device=-1)          # a new context (a new process would do the same): served from disk
+    program(c2).compile()
+    s2 = c2.stats()
+    assert s2["disk_hits"] == 2 and s2["compile_ms"] == 0
+    files[0].write_bytes(b"garbage")     # a damaged file is ignored and rewritten
+    c3 = gr.Context(device=-1)
+    program(c3).compile()
+    s3 = c3.stats()
+    assert s3["disk_hits"] == 1 and s3["compile_ms"] > 0
+    assert files[0].stat().st_size > 100
+    c4 = gr.Context(device=-1)
+    c4.set_option("disk_cache", 0)
+    program(c4).compile()
+    assert c4.stats()["disk_hits"] == 0
+    for c in (c1, c2, c3, c4):
+        c.close()
+
+
+def test_async_and_serial_compilation_agree(ctx):
+    ctx.set_option("disk_cache", 0)
+    x = ctx.spec((32, 200))
+    out = gr.exp(gr.cumsum(x, 1)) + gr.sum(x * x, axis=0) * 2.0 + gr.max(x, axis=1, keepdims=True)
+    n = len(out.plan().splitlines())
+    assert n >= 3
+    ctx.set_option("async_compile", 0)
+    out.compile()
+    serial = ctx.stats()["cache_misses"]
+    c2 = gr.Context(device=-1)
+    c2.set_option("disk_cache", 0)
+    x2 = c2.spec((32, 200))
+    out2 = gr.exp(gr.cumsum(x2, 1)) + gr.sum(x2 * x2, axis=0) * 2.0 + gr.max(x2, axis=1, keepdims=True)
+    out2.compile()                        # all kernels of the request compiled concurrently
+    assert c2.stats()["cache_misses"] == serial == n
+    assert [out.source(i) for i in range(n)] == [out2.source(i) for i in range(n)]
+    c2.close()
+
+
 def test_generated_code_has_no_contraction_or_packed_math(ctx):
     src = wl.chain(gr, ctx.spec((4096,)), ctx.spec((4096,))).source(0)
     assert "fmaf" not in src and "__fdividef" not in src and "__expf" not in src
