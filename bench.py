@@ -23,14 +23,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-ARGNAMES = {"chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
+ARGNAMES = {"blackscholes": ("S", "K", "T"), "chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
             "stencil": ("I",), "logreg": ("X", "w", "y")}
 # kernel whose launches dominate each workload, and its algorithmic bytes per launch
-DOMINANT = {"chain": "gr_map", "normalize": "gr_map", "softmax": "gr_rowred", "stencil": "gr_map", "logreg": "gr_gemv_pair"}
+DOMINANT = {"blackscholes": "gr_map", "chain": "gr_map", "normalize": "gr_map", "softmax": "gr_rowred", "stencil": "gr_map", "logreg": "gr_gemv_pair"}
 
 
 def out_shape(name, p):
-    return {"chain": lambda: (p["n"],), "normalize": lambda: (p["rows"], p["cols"]), "softmax": lambda: (p["rows"], p["cols"]),
+    return {"chain": lambda: (p["n"],), "blackscholes": lambda: (p["n"],), "normalize": lambda: (p["rows"], p["cols"]), "softmax": lambda: (p["rows"], p["cols"]),
             "stencil": lambda: (p["rows"] - 4, p["cols"] - 4), "logreg": lambda: (p["cols"],)}[name]()
 
 
@@ -229,14 +229,14 @@ def main():
                 extras[label + "_GBps"] = round(nbytes / (e0.elapsed_time(e1) / 60 * 1e-3) / 1e9, 1)
         del w
         torch.cuda.empty_cache()
-        others = [("chain", None), ("chain", dict(n=1 << 27)), ("softmax", None), ("stencil", None), ("logreg", None), ("normalize", None)]
+        others = [("chain", None), ("chain", dict(n=1 << 27)), ("blackscholes", dict(n=1 << 26)), ("softmax", None), ("stencil", None), ("logreg", None), ("normalize", None)]
         for oname, size in others:
             if oname == name and size is None:
                 continue
             ow = Workload(oname, ctx, 3 if size is None else 2, size)
             k = 1000 if (oname == "chain" and size is None) else 50
             d_ms, _ = time_steps(torch, ow, k, 10)
-            label = oname if size is None else f"{oname}_n2^27"
+            label = oname if size is None else f"{oname}_n2^{size['n'].bit_length() - 1}"
             extras[label + "_GBps"] = round(ow.unique_bytes / (d_ms / k * 1e-3) / 1e9, 1)
             extras[label + "_us_per_step"] = round(d_ms / k * 1e3, 2)
             del ow

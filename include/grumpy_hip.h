@@ -63,7 +63,7 @@ typedef enum { GR_F32 = 0, GR_I32 = 1, GR_I64 = 2 } gr_dtype;
 
 typedef enum {
   /* unary (Section 1 / Section 2: pointwise NumPy operations) */
-  GR_NEG = 0, GR_ABS = 1, GR_EXP = 2, GR_LOG = 3, GR_SQRT = 4, GR_SQUARE = 5, GR_TANH = 6,
+  GR_NEG = 0, GR_ABS = 1, GR_EXP = 2, GR_LOG = 3, GR_SQRT = 4, GR_SQUARE = 5, GR_TANH = 6, GR_ERF = 7,
   /* binary, NumPy broadcasting */
   GR_ADD = 16, GR_SUB = 17, GR_MUL = 18, GR_DIV = 19, GR_MAXIMUM = 20, GR_MINIMUM = 21,
   /* reductions (Section 3.2: associative and commutative binary operator) */

@@ -24,7 +24,7 @@ _SRC = os.path.join(_HERE, "eager.cpp")
 
 _DT = {np.dtype(np.float32): 0, np.dtype(np.int32): 1, np.dtype(np.int64): 2}
 _NP = {0: np.float32, 1: np.int32, 2: np.int64}
-_UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "square": 5, "tanh": 6}
+_UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "square": 5, "tanh": 6, "erf": 7}
 _BINARY = {"add": 0, "sub": 1, "mul": 2, "div": 3, "maximum": 4, "minimum": 5}
 _REDUCE = {"sum": 0, "max": 1, "min": 2}
 
@@ -263,6 +263,7 @@ def log(a): return unary("log", a)
 def sqrt(a): return unary("sqrt", a)
 def square(a): return unary("square", a)
 def tanh(a): return unary("tanh", a)
+def erf(a): return unary("erf", a)
 def sum(a, axis=None, keepdims=False): return reduce("sum", a, axis, keepdims)  # noqa: A001
 def max(a, axis=None, keepdims=False): return reduce("max", a, axis, keepdims)  # noqa: A001
 def min(a, axis=None, keepdims=False): return reduce("min", a, axis, keepdims)  # noqa: A001

@@ -19,7 +19,7 @@
 //   * f32 + - * / neg abs sqrt square maximum minimum: one IEEE-754 binary32
 //     round-to-nearest operation per op (square(x) = x*x).  Build with
 //     -ffp-contract=off and without fast-math.
-//   * f32 exp log tanh: evaluated in binary64 libm, rounded once to binary32.
+//   * f32 exp log tanh erf: evaluated in binary64 libm, rounded once to binary32.
 //   * i32 + - * neg abs square: two's-complement wrap-around.
 //   * maximum/minimum: NaN-propagating, as NumPy's.
 //   * sum of f32 over axes: binary64 accumulator, elements taken in row-major
@@ -49,7 +49,7 @@
 namespace {
 
 enum { DT_F32 = 0, DT_I32 = 1, DT_I64 = 2, DT_WEAK = 3 };
-enum { U_NEG = 0, U_ABS, U_EXP, U_LOG, U_SQRT, U_SQUARE, U_TANH };
+enum { U_NEG = 0, U_ABS, U_EXP, U_LOG, U_SQRT, U_SQUARE, U_TANH, U_ERF };
 enum { B_ADD = 0, B_SUB, B_MUL, B_DIV, B_MAXIMUM, B_MINIMUM };
 enum { R_SUM = 0, R_MAX, R_MIN };
 const int MAXD = 8;
@@ -140,6 +140,7 @@ float f32_unary(int op, float x) {
     case U_SQRT: return std::sqrt(x);
     case U_SQUARE: return x * x;
     case U_TANH: return (float)std::tanh((double)x);
+    case U_ERF: return (float)std::erf((double)x);
   }
   return 0.f;
 }

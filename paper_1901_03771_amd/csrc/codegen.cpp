@@ -131,6 +131,7 @@ struct Em {
       case GR_SQRT: return "sqrtf(" + x + ")";
       case GR_SQUARE: return "(" + x + " * " + x + ")";
       case GR_TANH: return "tanhf(" + x + ")";
+      case GR_ERF: return "erff(" + x + ")";
     }
     switch (op) {  // i32: two's-complement wrap-around through unsigned arithmetic
       case GR_NEG: return "((int)(0u - (unsigned)" + x + "))";

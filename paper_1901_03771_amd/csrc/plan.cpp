@@ -42,7 +42,7 @@ int64_t floormod(int64_t a, int64_t b) { return a - floordiv(a, b) * b; }
 const char* op_name(int op) {
   switch (op) {
     case GR_NEG: return "neg"; case GR_ABS: return "abs"; case GR_EXP: return "exp"; case GR_LOG: return "log";
-    case GR_SQRT: return "sqrt"; case GR_SQUARE: return "square"; case GR_TANH: return "tanh";
+    case GR_SQRT: return "sqrt"; case GR_SQUARE: return "square"; case GR_TANH: return "tanh"; case GR_ERF: return "erf";
     case GR_ADD: return "add"; case GR_SUB: return "sub"; case GR_MUL: return "mul"; case GR_DIV: return "div";
     case GR_MAXIMUM: return "maximum"; case GR_MINIMUM: return "minimum";
     case GR_SUM: return "sum"; case GR_MAX: return "max"; case GR_MIN: return "min";

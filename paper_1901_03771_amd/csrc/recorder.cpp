@@ -76,7 +76,7 @@ static void contiguous_strides(Node* n) {
   }
 }
 
-static bool is_unary(int op) { return op >= GR_NEG && op <= GR_TANH; }
+static bool is_unary(int op) { return op >= GR_NEG && op <= GR_ERF; }
 static bool is_binary(int op) { return op >= GR_ADD && op <= GR_MINIMUM; }
 static bool is_reduce(int op) { return op >= GR_SUM && op <= GR_MIN; }
 

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("GRUMPY_HIP_LIB", os.path.join(_HERE, "libgrumpy_hip.so"))
 
 GR_F32, GR_I32, GR_I64 = 0, 1, 2
-_UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "square": 5, "tanh": 6}
+_UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "square": 5, "tanh": 6, "erf": 7}
 _BINARY = {"add": 16, "sub": 17, "mul": 18, "div": 19, "maximum": 20, "minimum": 21}
 _REDUCE = {"sum": 32, "max": 33, "min": 34}
 STATUS = {0: "GR_OK", 1: "GR_ERR_HANDLE", 2: "GR_ERR_SHAPE", 3: "GR_ERR_DTYPE", 4: "GR_ERR_AXIS",
@@ -472,6 +472,7 @@ def log(a): return unary("log", a)
 def sqrt(a): return unary("sqrt", a)
 def square(a): return unary("square", a)
 def tanh(a): return unary("tanh", a)
+def erf(a): return unary("erf", a)
 def sum(a, axis=None, keepdims=False): return reduce("sum", a, axis, keepdims)  # noqa: A001
 def max(a, axis=None, keepdims=False): return reduce("max", a, axis, keepdims)  # noqa: A001
 def min(a, axis=None, keepdims=False): return reduce("min", a, axis, keepdims)  # noqa: A001

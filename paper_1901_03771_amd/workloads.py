@@ -29,6 +29,7 @@ FULL = {
     "softmax": dict(rows=16384, cols=4096),
     "stencil": dict(rows=8192, cols=8192),
     "logreg": dict(rows=262144, cols=512),
+    "blackscholes": dict(n=1 << 24),
 }
 SMALL = {
     "chain": dict(n=100_003),
@@ -36,8 +37,9 @@ SMALL = {
     "softmax": dict(rows=67, cols=1000),
     "stencil": dict(rows=151, cols=1234),
     "logreg": dict(rows=3001, cols=200),
+    "blackscholes": dict(n=70_001),
 }
-CONFIG_INDEX = {"chain": 0, "normalize": 1, "softmax": 2, "stencil": 3, "logreg": 4}
+CONFIG_INDEX = {"chain": 0, "normalize": 1, "softmax": 2, "stencil": 3, "logreg": 4, "blackscholes": 5}
 
 
 def rng_for(name: str, salt: int = 0) -> np.random.Generator:
@@ -77,6 +79,11 @@ def make_inputs(name: str, salt: int = 0, **size) -> dict:
             w=(np.sqrt(0.05) * g.standard_normal(c)).astype(f32),
             y=(g.random(r) < 0.5).astype(f32),
         )
+    if name == "blackscholes":
+        n = p["n"]
+        # option parameters in the ranges commonly used for synthetic pricing benchmarks
+        return dict(S=g.uniform(5.0, 30.0, n).astype(f32), K=g.uniform(1.0, 100.0, n).astype(f32),
+                    T=g.uniform(0.25, 10.0, n).astype(f32))
     raise KeyError(name)
 
 
@@ -109,7 +116,18 @@ def logreg(xp, X, w, y):
     return w - 0.1 * g
 
 
-PROGRAMS = {"chain": chain, "normalize": normalize, "softmax": softmax, "stencil": stencil, "logreg": logreg}
+def blackscholes(xp, S, K, T, r=0.02, sigma=0.30):
+    """European call price by the Black-Scholes formula: a long pointwise chain with log,
+    sqrt, exp and erf, the shape of the paper's best-case benchmark (Section 4.2)."""
+    sqrt_t = xp.sqrt(T)
+    d1 = (xp.log(S / K) + (r + 0.5 * sigma * sigma) * T) / (sigma * sqrt_t)
+    d2 = d1 - sigma * sqrt_t
+    cdf1 = 0.5 * (1.0 + xp.erf(d1 / 1.4142135623730951))
+    cdf2 = 0.5 * (1.0 + xp.erf(d2 / 1.4142135623730951))
+    return S * cdf1 - K * xp.exp(-r * T) * cdf2
+
+
+PROGRAMS = {"blackscholes": blackscholes, "chain": chain, "normalize": normalize, "softmax": softmax, "stencil": stencil, "logreg": logreg}
 
 
 def unique_bytes(name: str, **size) -> int:
@@ -118,6 +136,8 @@ def unique_bytes(name: str, **size) -> int:
     p.update(size)
     if name == "chain":
         return 12 * p["n"]
+    if name == "blackscholes":
+        return 16 * p["n"]
     if name == "normalize":
         return 8 * p["rows"] * p["cols"] + 16 * p["cols"]
     if name == "softmax":

@@ -112,6 +112,17 @@ def test_logreg_small(env, rows, cols):
     assert_reduction(got, ref, what=f"logreg residual {rows}x{cols}")
 
 
+@pytest.mark.parametrize("n", [1, 1023, 70_001, 1 << 22])
+def test_blackscholes(env, n):
+    arrays = wl.make_inputs("blackscholes", n=n)
+    got, ref = run_both(env, wl.blackscholes, arrays)
+    # the price is a difference of two products of order S and K: floor of 4 ulp of the larger one
+    floor = 4.0 * ulp_of(np.maximum(arrays["S"], arrays["K"]))
+    assert_elementwise(got, ref, floor=floor, what=f"blackscholes n={n}")
+    got, ref = run_both(env, lambda xp, a: xp.erf(a), dict(a=_rand((5000,), 80, 1.5)))
+    assert_elementwise(got, ref, what="erf")
+
+
 # -------------------------------------------- full sizes, sampled against the oracle --
 def _sample_rows(n, k, rng):
     edge = list(range(min(4, n))) + list(range(max(0, n - 4), n))

@@ -178,6 +178,16 @@ def test_five_configurations_partition_as_designed(ctx):
     assert len(far.plan().splitlines()) == 2
 
 
+def test_blackscholes_is_one_fused_kernel(ctx):
+    # Section 4.2: "a lot of point-wise operations which could be completely fused"
+    n = 1 << 20
+    out = wl.blackscholes(gr, ctx.spec((n,)), ctx.spec((n,)), ctx.spec((n,)))
+    g = groups(out)
+    assert len(g) == 1 and g[0][0] == "MAP" and len(g[0][1]) >= 20 and g[0][1].count("erf") == 2
+    assert "loads=3" in out.plan()
+    out.compile()
+
+
 def test_jacobi_slices_fuse_into_one_kernel(ctx):
     # Section 4.2: the stencil is fused into a single kernel even when slicing
     out = wl.jacobi_sweep(gr, ctx.spec((512, 512)))

@@ -175,6 +175,57 @@ def test_exp_is_correctly_rounded_on_exact_rational_series(xv):
     assert got == want
 
 
+def test_erf_against_high_precision_series():
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+
+    def pi_machin():
+        def arctan_inv(n):  # arctan(1/n)
+            x = Decimal(1) / n
+            s_, t, k = Decimal(0), x, 0
+            while abs(t) > Decimal(10) ** -58:
+                s_ += t / (2 * k + 1) if k % 2 == 0 else -t / (2 * k + 1)
+                t *= x * x
+                k += 1
+            return s_
+        return 16 * arctan_inv(5) - 4 * arctan_inv(239)
+
+    def erf_dec(x):
+        x = Decimal(x)
+        s_, term, n = Decimal(0), x, 0
+        while abs(term) > Decimal(10) ** -55:
+            s_ += term / (2 * n + 1)
+            n += 1
+            term = -term * x * x / n
+        return 2 * s_ / pi_machin().sqrt()
+
+    xs = np.array([0.0, 0.125, -0.5, 0.75, 1.0, -1.5, 2.25, 3.0], f32)
+    got = ora.erf(ora.array(xs)).numpy()
+    for x, g_ in zip(xs, got):
+        want = erf_dec(float(x))
+        assert abs(Decimal(float(g_)) - want) <= Decimal(float(np.spacing(f32(abs(float(want)))))) * Decimal("0.51") + Decimal(10) ** -45
+    assert got[0] == 0 and np.array_equal(ora.erf(ora.array(-xs)).numpy(), -got)          # odd
+    big = ora.erf(ora.array(np.array([6.0, -6.0, np.inf], f32))).numpy()
+    assert big.tolist() == [1.0, -1.0, 1.0]
+
+
+def test_blackscholes_limits_and_float64_reference():
+    import math
+    inp = wl.make_inputs("blackscholes", n=2000)
+    got = wl.blackscholes(ora, *(ora.array(inp[k]) for k in ("S", "K", "T"))).numpy()
+    S, K, T = (inp[k].astype(np.float64) for k in ("S", "K", "T"))
+    r, sig = 0.02, 0.30
+    d1 = (np.log(S / K) + (r + 0.5 * sig * sig) * T) / (sig * np.sqrt(T))
+    d2 = d1 - sig * np.sqrt(T)
+    N = np.vectorize(lambda v: 0.5 * (1 + math.erf(v / math.sqrt(2))))
+    want = S * N(d1) - K * np.exp(-r * T) * N(d2)
+    assert np.max(np.abs(got - want)) < 2e-5            # prices of order 10, f32 arithmetic
+    assert np.all(got >= -1e-5) and np.all(got <= inp["S"] + 1e-5)   # 0 <= call <= S
+    # deep in the money: call -> S - K exp(-rT)
+    deep = wl.blackscholes(ora, ora.array(np.array([1000.0], f32)), ora.array(np.array([1.0], f32)), ora.array(np.array([1.0], f32))).numpy()
+    assert abs(float(deep[0]) - (1000.0 - math.exp(-0.02))) < 1e-3
+
+
 def test_log_tanh_special_values_and_inverse():
     x = np.array([0.25, 1.0, 3.0, 10.0], f32)
     lg = ora.log(ora.array(x)).numpy()
