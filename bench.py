@@ -284,6 +284,11 @@ def main():
         extras["cumsum_n2^27_GBps"] = round(8 * n / (ms * 1e-3) / 1e9, 1)
         del xs, outn
         torch.cuda.empty_cache()
+        ga, gb = torch.randn(4096, 4096, device="cuda"), torch.randn(4096, 4096, device="cuda")
+        gc = torch.empty(4096, 4096, device="cuda")
+        ms = timed(lambda: (ctx.array(ga) @ ctx.array(gb)).materialize_into(gc), 10)
+        extras["gemm_4096_f32_TFLOPs"] = round(2 * 4096 ** 3 / (ms * 1e-3) / 1e12, 1)
+        del ga, gb, gc
         grid = ctx.array(torch.rand(8192, 8192, device="cuda"))
         sweeps = 10
         ms = timed(lambda: wl.jacobi(gr, grid, sweeps), 5, warm=1)

@@ -179,9 +179,11 @@ gr_status gr_reduce(gr_ctx* ctx, gr_op op, gr_array a, const int* axes, int naxe
  * scan kernel, its consumers read the stored result. */
 gr_status gr_scan(gr_ctx* ctx, gr_op op, gr_array a, int axis, gr_array* out);
 
-/* np.dot for f32: (M,K).(K,) -> (M,) and (K,).(K,) -> ().  Either operand
- * may be any strided view (a transposed matrix is folded into the kernel,
- * Section 2).  Matrix-matrix products: GR_ERR_UNSUPPORTED. */
+/* np.dot for f32: (M,K).(K,N) -> (M,N), (M,K).(K,) -> (M,) and (K,).(K,) -> ().
+ * Either operand may be any strided view (a transposed matrix is folded into
+ * the kernel, Section 2).  Operands are materialised first; pointwise consumers
+ * of the same shape run as the contraction kernel's epilogue.  The matrix-matrix
+ * product runs on the matrix cores (MFMA, f32 inputs and accumulation). */
 gr_status gr_dot(gr_ctx* ctx, gr_array a, gr_array b, gr_array* out);
 
 /* ---- materialisation (Section 2, Algorithm 1, Section 3) ---------------- */

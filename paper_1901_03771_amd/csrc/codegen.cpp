@@ -43,6 +43,7 @@ bool nontemporal_group(const GroupPlan& g, int group) {
   const AccessGroup& ag = g.groups[group];
   if (g.nt <= 0 || ag.dtype == GR_I64) return false;
   if (g.kind == GroupKind::GEMV) return group == g.mat_group;
+  if (g.kind == GroupKind::GEMM) return false;  // operand tiles are re-read by other workgroups: keep them cacheable
   if (access_class(ag, g.rank - 1) != '1') return false;
   if (g.nt >= 2) return true;
   if (ag.deltas.size() > 1) return false;
@@ -55,7 +56,7 @@ ArgLayout arg_layout(const GroupPlan& g) {
   ArgLayout L;
   int s = 0;
   for (size_t i = 0; i < g.groups.size(); ++i) {
-    bool core = g.kind == GroupKind::GEMV && ((int)i == g.mat_group || (int)i == g.vec_group);
+    bool core = (g.kind == GroupKind::GEMV || g.kind == GroupKind::GEMM) && ((int)i == g.mat_group || (int)i == g.vec_group);
     int nc = core ? 2 : g.rank;
     L.ptr.push_back(s++);
     L.base.push_back(s++);
@@ -84,6 +85,7 @@ std::string kernel_name(const GroupPlan& g) {
     case GroupKind::ROWRED: return "gr_rowred";
     case GroupKind::REDUCE: return "gr_reduce";
     case GroupKind::SCAN: return "gr_scan";
+    case GroupKind::GEMM: return "gr_gemm";
     case GroupKind::GEMV: return g.gemv_mode == 2 ? "gr_gemv_pair" : (g.gemv_mode ? "gr_gemv_colacc" : "gr_gemv_rowdot");
   }
   return "gr_kernel";
@@ -1020,6 +1022,102 @@ void gen_gemv_pair(Em& e, Em& e2) {
   e.o << e2.o.str();
 }
 
+// ---- GEMM (matrix cores) ----------------------------------------------------------
+
+// C = A.B for f32 on MFMA (v_mfma_f32_32x32x2_f32: f32 inputs, f32 accumulation), the one place
+// on this path that is a dense contraction.  A workgroup of four waves owns a 128x128 tile of
+// C; each wave a 64x64 quarter as 2x2 MFMA blocks (64 accumulator VGPRs).  K advances in steps
+// of 16: the next A and B tiles are fetched from global memory into registers (dwordx4 along
+// whichever dimension of the operand is contiguous, so transposed views cost nothing) while the
+// current tiles are consumed from LDS, k-major so that the 32 lanes of an MFMA operand read 32
+// consecutive words.  The pointwise consumers of the dot run on the accumulators (epilogue).
+void gen_gemm(Em& e) {
+  const GroupPlan& g = e.g;
+  const AccessGroup& ag = g.groups[g.mat_group];
+  const AccessGroup& bg = g.groups[g.vec_group];
+  const int a_mode = ag.coef[1] == 1 ? 0 : (ag.coef[0] == 1 ? 1 : 2);  // 0: k contiguous, 1: m contiguous, 2: neither
+  const int b_mode = bg.coef[1] == 1 ? 0 : (bg.coef[0] == 1 ? 1 : 2);  // 0: n contiguous, 1: k contiguous, 2: neither
+  prelude(e);
+  e.o << "typedef float f16v __attribute__((ext_vector_type(16)));\n";
+  kernel_head(e, "gr_gemm");
+  e.o << "  const long long M = " << e.S(e.L.extra) << ", N = " << e.S(e.L.extra + 1) << ", K = " << e.S(e.L.extra + 2) << ";\n";
+  group_pointers(e, "  ");
+  e.o << "  const GM float* const A = q" << g.mat_group << "; const GM float* const B = q" << g.vec_group << ";\n";
+  e.o << "  const long long am = " << e.coef(g.mat_group, 0) << ", ak = " << e.coef(g.mat_group, 1) << ", bk = " << e.coef(g.vec_group, 0)
+      << ", bn = " << e.coef(g.vec_group, 1) << ";\n  (void)am; (void)ak; (void)bk; (void)bn;\n";
+  e.o << "  __shared__ float As[2][16][132];\n  __shared__ float Bs[2][16][132];\n";
+  e.o << "  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;\n";
+  e.o << "  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64, l32 = lane & 31, lh = lane >> 5;\n";
+  e.o << "  const long long tiles_n = (N + 127) / 128;\n";
+  e.o << "  const long long bm0 = (long long)(blockIdx.x / tiles_n) * 128, bn0 = (long long)(blockIdx.x % tiles_n) * 128;\n";
+  e.o << "  f16v acc[2][2];\n  for (int i = 0; i < 2; ++i) for (int j = 0; j < 2; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n";
+  e.o << "  float ra[8], rb[8];\n";
+  // --- global -> registers
+  e.o << "  auto fetch = [&](long long k0) {\n";
+  if (a_mode == 0) {
+    e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long row = bm0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n"
+           "      if (row < M && kk + 4 <= K) { const f4u w = *(const GM f4u*)(A + row * am + kk); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
+           "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (row < M && kk + j < K) ? A[row * am + kk + j] : 0.0f; }\n    }\n";
+  } else if (a_mode == 1) {
+    e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, row = bm0 + (tid % 32) * 4;\n"
+           "      if (kk < K && row + 4 <= M) { const f4u w = *(const GM f4u*)(A + kk * ak + row); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
+           "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (kk < K && row + j < M) ? A[kk * ak + row + j] : 0.0f; }\n    }\n";
+  } else {
+    e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; const long long row = bm0 + el % 128, kk = k0 + el / 128;\n"
+           "      ra[i] = (row < M && kk < K) ? A[row * am + kk * ak] : 0.0f; }\n";
+  }
+  if (b_mode == 0) {
+    e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, col = bn0 + (tid % 32) * 4;\n"
+           "      if (kk < K && col + 4 <= N) { const f4u w = *(const GM f4u*)(B + kk * bk + col); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
+           "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (kk < K && col + j < N) ? B[kk * bk + col + j] : 0.0f; }\n    }\n";
+  } else if (b_mode == 1) {
+    e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long col = bn0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n"
+           "      if (col < N && kk + 4 <= K) { const f4u w = *(const GM f4u*)(B + col * bn + kk); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
+           "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (col < N && kk + j < K) ? B[col * bn + kk + j] : 0.0f; }\n    }\n";
+  } else {
+    e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; const long long col = bn0 + el % 128, kk = k0 + el / 128;\n"
+           "      rb[i] = (col < N && kk < K) ? B[kk * bk + col * bn] : 0.0f; }\n";
+  }
+  e.o << "  };\n";
+  // --- registers -> LDS (k-major tiles)
+  e.o << "  auto stash = [&](int buf) {\n";
+  if (a_mode == 0) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) As[buf][(tid % 4) * 4 + j][tid / 4 + 64 * i] = ra[4*i+j];\n";
+  else if (a_mode == 1) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) As[buf][tid / 32 + 8 * i][(tid % 32) * 4 + j] = ra[4*i+j];\n";
+  else e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; As[buf][el / 128][el % 128] = ra[i]; }\n";
+  if (b_mode == 0) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) Bs[buf][tid / 32 + 8 * i][(tid % 32) * 4 + j] = rb[4*i+j];\n";
+  else if (b_mode == 1) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) Bs[buf][(tid % 4) * 4 + j][tid / 4 + 64 * i] = rb[4*i+j];\n";
+  else e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; Bs[buf][el / 128][el % 128] = rb[i]; }\n";
+  e.o << "  };\n";
+  e.o << "  const long long nkt = (K + 15) / 16;\n  int cur = 0;\n";
+  e.o << "  if (nkt > 0) { fetch(0); stash(0); }\n  __syncthreads();\n";
+  e.o << "  for (long long kt = 0; kt < nkt; ++kt) {\n    if (kt + 1 < nkt) fetch((kt + 1) * 16);\n";
+  e.o << "#pragma unroll\n    for (int ks = 0; ks < 8; ++ks) {\n"
+         "      const float a0 = As[cur][2 * ks + lh][wm + l32], a1 = As[cur][2 * ks + lh][wm + 32 + l32];\n"
+         "      const float b0 = Bs[cur][2 * ks + lh][wn + l32], b1 = Bs[cur][2 * ks + lh][wn + 32 + l32];\n"
+         "      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);\n"
+         "      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);\n"
+         "      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);\n"
+         "      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);\n    }\n";
+  e.o << "    if (kt + 1 < nkt) stash(cur ^ 1);\n    __syncthreads();\n    cur ^= 1;\n  }\n";
+  // --- epilogue on the accumulators: element q of a 32x32 block sits at row 8*(q/4) + 4*(lane/32) + q%4, column lane%32
+  e.o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
+  e.o << "  for (int i = 0; i < 2; ++i) for (int j = 0; j < 2; ++j)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
+         "      const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4), col = bn0 + wn + 32 * j + l32;\n"
+         "      if (row < M && col < N) {\n        const float cacc = acc[i][j][q];\n";
+  emit_scalar_program(e, g.prog, g.results,
+                      [&](const Instr& in, int) {
+                        const AccessGroup& eg = g.groups[in.group];
+                        std::ostringstream s2;
+                        s2 << e.qp << in.group << "[0";
+                        if (!eg.structural_zero[0]) s2 << " + (row + " << in.delta[0] << ") * " << e.coef(in.group, 0);
+                        if (!eg.structural_zero[1]) s2 << " + (col + " << in.delta[1] << ") * " << e.coef(in.group, 1);
+                        s2 << "]";
+                        return s2.str();
+                      },
+                      "cacc", "t", "        ");
+  e.o << "        out[row * N + col] = t" << g.results[0] << ";\n      }\n    }\n}\n";
+}
+
 }  // namespace
 
 std::string generate_source(const GroupPlan& g) {
@@ -1029,6 +1127,7 @@ std::string generate_source(const GroupPlan& g) {
     case GroupKind::ROWRED: gen_rowred(e); break;
     case GroupKind::REDUCE: gen_reduce(e); break;
     case GroupKind::SCAN: gen_scan(e); break;
+    case GroupKind::GEMM: gen_gemm(e); break;
     case GroupKind::GEMV:
       if (g.gemv_mode == 2) {
         Em e2(*g.pair);

@@ -106,7 +106,7 @@ struct AccessGroup {
   std::set<std::vector<int64_t>> deltas;  // all shifts used (length = iteration rank)
 };
 
-enum class GroupKind : uint8_t { MAP, ROWRED, REDUCE, GEMV, SCAN };
+enum class GroupKind : uint8_t { MAP, ROWRED, REDUCE, GEMV, SCAN, GEMM };
 
 struct Phase {
   int op = 0;  // GR_SUM / GR_MAX / GR_MIN
@@ -177,8 +177,8 @@ struct GroupPlan {
   int gemv_mode = 0;  // 0: inner stride 1 along k (row-dot); 1: inner stride 1 along m (column-accumulate);
                       // 2: row-dot fused with the column-accumulate sub-graph in `pair` (one pass over the matrix)
   std::unique_ptr<GroupPlan> pair;
-  int64_t M = 0, K = 0;
-  int mat_group = -1, vec_group = -1;
+  int64_t M = 0, K = 0, N = 0;  // N: GEMM only
+  int mat_group = -1, vec_group = -1;  // GEMM: left (m,k) and right (k,n) operand
   int LPR = 64;       // gemv row-dot: lanes per row
   int KV = 1;         // gemv row-dot: vec4 per lane along k
   int slabs = 1;      // gemv column-accumulate: row slabs (first-stage partial vectors)

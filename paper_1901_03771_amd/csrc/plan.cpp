@@ -227,8 +227,8 @@ struct Builder {
           break;
         }
         case Kind::DOT: {
-          bool ok = g->kind == GroupKind::GEMV && (dot_core == nullptr || dot_core == n);
-          if (ok && n->ndim == 1) ok = is_identity_on(m, 0, 0, n->shape[0]);
+          bool ok = (g->kind == GroupKind::GEMV || g->kind == GroupKind::GEMM) && (dot_core == nullptr || dot_core == n);
+          for (int d = 0; ok && d < n->ndim; ++d) ok = is_identity_on(m, d, d, n->shape[d]);
           if (!ok) { invalid.push_back({n, "dot result not usable as an epilogue input"}); id = constant(GR_F32, 0.0); break; }
           dot_core = n;
           Instr in;
@@ -638,6 +638,48 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     }
     g->red_out = lines;
     g->red_len = L;
+  } else if (dot && dot->ndim == 2) {
+    // ---- matrix-matrix product on the matrix cores, with pointwise epilogue -----------------
+    g->kind = GroupKind::GEMM;
+    b.g->kind = GroupKind::GEMM;
+    const Node* A = dot->in[0];
+    const Node* B = dot->in[1];
+    g->M = A->shape[0]; g->K = A->shape[1]; g->N = B->shape[1];
+    if (r->ndim != 2 || r->shape[0] != g->M || r->shape[1] != g->N) { invalid->push_back({dot, "epilogue changes the shape"}); return GR_OK; }
+    g->orig_rank = 2;
+    g->orig_dims[0] = g->M; g->orig_dims[1] = g->N;
+    b.rank = 2; b.dims = g->orig_dims; b.prog = &g->prog;
+    IndexMap im(2);
+    im[0] = DimMap{0, 1, 0}; im[1] = DimMap{1, 1, 0};
+    int res = b.eval(r, im);
+    if (!b.invalid.empty()) { *invalid = b.invalid; return GR_OK; }
+    g->results.push_back(res);
+    std::vector<Instr>* eps[1] = {&g->prog};
+    normalize_deltas(g, eps, 1, 2);
+    // operands: left in the space (m,k), right in the space (k,n); resolved through views only
+    for (int side = 0; side < 2; ++side) {
+      const Node* X = side == 0 ? A : B;
+      int64_t cd[2] = {side == 0 ? g->M : g->K, side == 0 ? g->K : g->N};
+      Builder cb;
+      std::vector<Instr> scratch;
+      cb.g = g; cb.owned = &owned; cb.rank = 2; cb.dims = cd; cb.prog = &scratch;
+      IndexMap xm(2);
+      xm[0] = DimMap{0, 1, 0}; xm[1] = DimMap{1, 1, 0};
+      cb.canonicalize(X, xm);
+      const Node* leaf; IndexMap lm;
+      if (!resolve_to_leaf(X, xm, &leaf, &lm)) return fail(c, GR_ERR_UNSUPPORTED, "dot: operand is not materialised");
+      // a private group per operand (an epilogue access or the other operand may read the same leaf
+      // with the same map, but their coefficient slots mean different dimensions)
+      size_t before = g->groups.size();
+      cb.load(leaf, lm);
+      if (g->groups.size() == before) g->groups.push_back(g->groups[cb.prog->back().group]);
+      (side == 0 ? g->mat_group : g->vec_group) = (int)g->groups.size() - 1;
+      b.leaves_seen.insert(leaf);
+    }
+    b.members_seen.insert(dot);
+    g->rank = 2;
+    g->dims[0] = g->M; g->dims[1] = g->N;
+    g->collapse_to[0] = 0; g->collapse_to[1] = 1;
   } else if (dot) {
     // ---- contraction with pointwise epilogue ------------------------------
     g->kind = GroupKind::GEMV;
@@ -1030,7 +1072,7 @@ std::string describe_plan(const Plan& plan) {
   int i = 0;
   for (const auto& gp : plan.groups) {
     const GroupPlan& g = *gp;
-    const char* kn = g.kind == GroupKind::MAP ? "MAP" : g.kind == GroupKind::ROWRED ? "ROWRED" : g.kind == GroupKind::REDUCE ? "REDUCE" : g.kind == GroupKind::SCAN ? "SCAN" : "GEMV";
+    const char* kn = g.kind == GroupKind::MAP ? "MAP" : g.kind == GroupKind::ROWRED ? "ROWRED" : g.kind == GroupKind::REDUCE ? "REDUCE" : g.kind == GroupKind::SCAN ? "SCAN" : g.kind == GroupKind::GEMM ? "GEMM" : "GEMV";
     s << '#' << i++ << ' ' << kn << " root=" << g.root->id << " shape=(";
     for (int d = 0; d < g.root->ndim; ++d) s << (d ? "," : "") << g.root->shape[d];
     s << ") iter=(";
@@ -1046,6 +1088,7 @@ std::string describe_plan(const Plan& plan) {
     first = true;
     for (const Node* n : g.leaves) { s << (first ? "" : ",") << n->id; first = false; }
     s << "] loads=" << [&] { int k = 0; for (const Instr& in : (g.kind == GroupKind::MAP ? g.prog1 : g.prog)) if (in.kind == IKind::LOAD) ++k; return k; }();
+    if (g.kind == GroupKind::GEMM) s << " M=" << g.M << " N=" << g.N << " K=" << g.K;
     if (g.kind == GroupKind::GEMV) s << " mode=" << (g.gemv_mode == 2 ? "row-dot+column-accumulate" : (g.gemv_mode ? "column-accumulate" : "row-dot")) << " M=" << g.M << " K=" << g.K;
     if (g.pair) {
       s << " fused-with=[root=" << g.pair->root->id << " members=[";

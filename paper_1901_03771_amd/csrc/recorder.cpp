@@ -352,13 +352,14 @@ gr_status gr_dot(gr_ctx* ctx, gr_array a, gr_array b, gr_array* out) {
   if (!x || !y) return fail(ctx, GR_ERR_HANDLE, "dot: bad handle");
   if (x->kind == Kind::SCALAR || y->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "dot: scalar operand");
   if (x->dtype != GR_F32 || y->dtype != GR_F32) return fail(ctx, GR_ERR_DTYPE, "dot: f32 operands only");
-  if (y->ndim == 2 && (x->ndim == 2 || x->ndim == 1)) return fail(ctx, GR_ERR_UNSUPPORTED, "dot: matrix right operand (matrix-matrix product) is not supported");
-  if (y->ndim != 1 || x->ndim < 1 || x->ndim > 2) return fail(ctx, GR_ERR_UNSUPPORTED, "dot: supported ranks are (M,K).(K,) and (K,).(K,)");
+  if (y->ndim == 2 && x->ndim == 1) return fail(ctx, GR_ERR_UNSUPPORTED, "dot: vector-matrix product is not supported (transpose both sides)");
+  if (y->ndim < 1 || y->ndim > 2 || x->ndim < 1 || x->ndim > 2) return fail(ctx, GR_ERR_UNSUPPORTED, "dot: supported ranks are (M,K).(K,N), (M,K).(K,) and (K,).(K,)");
   if (x->shape[x->ndim - 1] != y->shape[0]) return fail(ctx, GR_ERR_SHAPE, "dot: inner dimensions differ");
   Node* r = new_node(ctx, Kind::DOT);
   r->dtype = GR_F32;
-  r->ndim = x->ndim - 1;
+  r->ndim = x->ndim - 1 + y->ndim - 1;
   if (x->ndim == 2) r->shape[0] = x->shape[0];
+  if (y->ndim == 2) r->shape[r->ndim - 1] = y->shape[1];
   add_input(r, x);
   add_input(r, y);
   *out = r->id;

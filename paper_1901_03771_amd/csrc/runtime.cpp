@@ -331,6 +331,13 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       }
       return launch(c, k->fn, k->name, g.red_out * g.scan_nchunk, s);
     }
+    case GroupKind::GEMM: {
+      if (g.M == 0 || g.N == 0) return GR_OK;
+      s[L.extra] = (uint64_t)g.M;
+      s[L.extra + 1] = (uint64_t)g.N;
+      s[L.extra + 2] = (uint64_t)g.K;
+      return launch(c, k->fn, k->name, ((g.M + 127) / 128) * ((g.N + 127) / 128), s);
+    }
     case GroupKind::GEMV: {
       if (g.M == 0) return GR_OK;
       s[L.extra] = (uint64_t)g.M;

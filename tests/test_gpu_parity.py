@@ -386,6 +386,39 @@ def test_assign_keeps_recorded_values(env):
     assert np.all(ta.cpu().numpy() == 0)
 
 
+GEMM_CASES = [(1, 1, 1), (130, 17, 129), (300, 200, 150), (128, 16, 128), (257, 1000, 64), (1024, 512, 768), (5, 4099, 3)]
+
+
+@pytest.mark.parametrize("M,K,N", GEMM_CASES)
+def test_matrix_product(env, M, K, N):
+    A, B = _rand((M, K), 90), _rand((K, N), 91)
+    At, Bt = np.ascontiguousarray(A.T), np.ascontiguousarray(B.T)
+    bias = _rand((N,), 92)
+    cases = [
+        (lambda xp, A, B, At, Bt, bias: A @ B, "row-major operands"),
+        (lambda xp, A, B, At, Bt, bias: At.T @ B, "left operand transposed view"),
+        (lambda xp, A, B, At, Bt, bias: A @ Bt.T, "right operand transposed view"),
+        (lambda xp, A, B, At, Bt, bias: xp.maximum(A @ B + bias, 0) * 0.5, "bias + relu epilogue"),
+    ]
+    for prog, what in cases:
+        got, ref = run_both(env, prog, dict(A=A, B=B, At=At, Bt=Bt, bias=bias))
+        assert got.shape == ref.shape == (M, N), what
+        assert_reduction(got, ref, what=f"{what} {M}x{K}x{N}")
+
+
+def test_matrix_product_strided_and_chained(env):
+    A, B, C = _rand((90, 140), 93), _rand((70, 200), 94), _rand((67, 33), 95)
+    got, ref = run_both(env, lambda xp, A, B, C: (A[:, ::2] @ B[:, ::3]) @ C, dict(A=A, B=B, C=C))
+    assert got.shape == (90, 33)
+    assert_reduction(got, ref, what="strided operands, product feeding product")
+    # an asymmetric matrix of small integers: exact in f32, catches any mis-indexed accumulator element
+    g = np.random.default_rng(96)
+    X = g.integers(-3, 4, (200, 96)).astype(f32)
+    Y = g.integers(-3, 4, (96, 160)).astype(f32)
+    got, ref = run_both(env, lambda xp, X, Y: X @ Y, dict(X=X, Y=Y))
+    assert np.array_equal(got, ref)
+
+
 def test_mnist_listing2(env):
     g = np.random.default_rng(37)
     arrays = dict(W=g.standard_normal((200, 10)).astype(f32), a=g.standard_normal(200).astype(f32), b=g.standard_normal(10).astype(f32))

@@ -104,9 +104,13 @@ def test_transpose_reduce_dot_shapes_and_errors(ctx):
     with pytest.raises(gr.GrError) as ei:
         m @ ctx.spec((5,))
     assert ei.value.code == "GR_ERR_SHAPE"
+    assert (m @ ctx.spec((7, 2))).shape == (5, 2)
     with pytest.raises(gr.GrError) as ei:
-        m @ ctx.spec((7, 2))
+        v @ ctx.spec((7, 2))
     assert ei.value.code == "GR_ERR_UNSUPPORTED"
+    with pytest.raises(gr.GrError) as ei:
+        m @ ctx.spec((6, 2))
+    assert ei.value.code == "GR_ERR_SHAPE"
 
 
 def test_dtype_rules(ctx):
@@ -322,6 +326,22 @@ def test_scan_is_a_cut_and_checks_its_axis(ctx):
     long_line = gr.cumsum(ctx.spec((1 << 22,)), 0)
     assert "chunks=512" in long_line.plan()
     assert "gr_scan_sums" in long_line.source(0) and "gr_scan_offsets" in long_line.source(0)
+
+
+def test_matrix_product_plans_and_compiles(ctx):
+    A, B, bias = ctx.spec((300, 200)), ctx.spec((200, 150)), ctx.spec((150,))
+    out = gr.tanh(A @ B + bias) * 2.0
+    assert groups(out) == [("GEMM", ["dot", "add", "tanh", "mul"])]      # pointwise consumers run as the epilogue
+    src = out.source(0)
+    assert "__builtin_amdgcn_mfma_f32_32x32x2f32" in src and "__shared__" in src
+    out.compile()
+    (ctx.spec((200, 300)).T @ B).compile()                # left operand contiguous along m
+    (A @ ctx.spec((150, 200)).T).compile()                # right operand contiguous along k
+    (A[::2, ::2] @ B[::2, ::3]).compile()                 # neither: scalar loads
+    chain = (A @ B) @ ctx.spec((150, 64))                 # a product feeding a product: two sub-graphs
+    assert [k for k, _ in groups(chain)] == ["GEMM", "GEMM"]
+    lazy_operand = gr.exp(A) @ B                          # operands are materialised first (Section 2)
+    assert [k for k, _ in groups(lazy_operand)] == ["MAP", "GEMM"]
 
 
 def test_rowred_and_dot_cases_compile(ctx):
