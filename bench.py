@@ -252,6 +252,17 @@ def main():
             extras[label + "_us_per_step"] = round(d_ms / k * 1e3, 2)
             del ow
             torch.cuda.empty_cache()
+        # the same GPU without fusion: one kernel per recorded op, every intermediate through HBM
+        # (the eager model the paper starts from, Section 1)
+        uctx = gr.Context(device=0)
+        uctx.set_option("fusion", 0)
+        for oname in ("normalize", "softmax"):
+            ow = Workload(oname, uctx, 2)
+            d_ms, _ = time_steps(torch, ow, 20, 3)
+            extras[oname + "_unfused_GBps"] = round(ow.unique_bytes / (d_ms / 20 * 1e-3) / 1e9, 1)
+            del ow
+            torch.cuda.empty_cache()
+        uctx.close()
         # rows beyond the five configurations: two-stage reduction, map-scan, the full Jacobi loop
         def timed(fn, iters, warm=3):
             for _ in range(warm):
