@@ -140,6 +140,35 @@ class Context:
         if st:
             raise GrError(st, lib().gr_last_error(self._p).decode())
 
+    def set_allocator(self, alloc, free):
+        """Installs Python callables alloc(nbytes) -> device address or None, free(address) as the
+        context's device allocator (results of gr_materialize, temporaries, workspaces)."""
+        ALLOC = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
+        FREE = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
+
+        def _alloc(n, user):
+            try:
+                return alloc(n)
+            except Exception:
+                return None
+
+        def _free(ptr, user):
+            try:
+                free(ptr)
+            except Exception:
+                pass
+
+        self._allocator = (ALLOC(_alloc), FREE(_free))  # kept alive: the library calls them until close()
+        self.check(lib().gr_ctx_set_allocator(self._p, ctypes.cast(self._allocator[0], ctypes.c_void_p),
+                                              ctypes.cast(self._allocator[1], ctypes.c_void_p), None))
+
+    def use_torch_allocator(self):
+        """Routes the context's allocations through PyTorch's caching allocator."""
+        torch = _torch()
+        dev = self.device
+        self.set_allocator(lambda n: torch.cuda.caching_allocator_alloc(n, dev, torch.cuda.current_stream(dev)),
+                           lambda ptr: torch.cuda.caching_allocator_delete(ptr))
+
     def set_option(self, key: str, value: int):
         self.check(lib().gr_ctx_set_option(self._p, key.encode(), int(value)))
 

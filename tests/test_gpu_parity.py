@@ -497,6 +497,38 @@ def test_unfused_mode_matches_fused(env):
     ctx2.close()
 
 
+def test_allocator_callbacks_and_out_of_memory(env):
+    gr, ctx, torch = env
+    arrays = wl.make_inputs("logreg", rows=3001, cols=200)
+    keep = {k: torch.from_numpy(v).cuda() for k, v in arrays.items()}
+    ref = wl.logreg(ora, **{k: ora.array(v) for k, v in arrays.items()}).numpy()
+    c2 = gr.Context()
+    c2.use_torch_allocator()                       # PyTorch's caching allocator behind the library
+    before = torch.cuda.memory_allocated()
+    out = wl.logreg(gr, **{k: c2.array(t) for k, t in keep.items()}).materialize()
+    assert torch.cuda.memory_allocated() > before  # the result and the workspace came from torch
+    ptr, strides = out.data_ptr()
+    assert ptr != 0 and strides == (1,)
+    assert_reduction(out.numpy(), ref, what="logreg through the torch allocator")
+    del out
+    c2.close()
+    assert torch.cuda.memory_allocated() <= before + 4096
+    # an allocator that fails: the call returns GR_ERR_OOM, nothing is launched, the context stays usable
+    c3 = gr.Context()
+    calls = []
+    c3.set_allocator(lambda n: calls.append(n) or None, lambda p: None)
+    lazy = wl.logreg(gr, **{k: c3.array(t) for k, t in keep.items()})
+    launched = c3.stats()["kernel_launches"]
+    with pytest.raises(gr.GrError) as ei:
+        lazy.materialize()
+    assert ei.value.code == "GR_ERR_OOM" and calls and c3.stats()["kernel_launches"] == launched
+    assert not lazy.is_materialized
+    c3.use_torch_allocator()                       # with a working allocator the same request succeeds
+    assert_reduction(lazy.numpy(), ref, what="retry after an allocation failure")
+    del lazy
+    c3.close()
+
+
 def test_stream_kernels(env):
     gr, ctx, torch = env
     src = torch.arange(1 << 20, dtype=torch.float32, device="cuda")
