@@ -529,6 +529,56 @@ def test_allocator_callbacks_and_out_of_memory(env):
     c3.close()
 
 
+def test_index_space_beyond_32_bits(env):
+    # 2^31 + 4099 elements: every offset computation must be 64-bit (map, two-stage reduction, scan)
+    gr, ctx, torch = env
+    n = (1 << 31) + 4099
+    a = torch.ones(n, dtype=torch.int32, device="cuda")
+    special = [0, 1, 4095, (1 << 31) - 1, 1 << 31, (1 << 31) + 1, n - 2, n - 1]
+    for k, i in enumerate(special):
+        a[i] = 10 + k
+    A = ctx.array(a)
+    out = (A * 3 + 1).torch()
+    assert out.shape[0] == n
+    for k, i in enumerate(special):
+        assert int(out[i]) == (10 + k) * 3 + 1, i
+    idx = torch.randint(2, n - 2, (4096,), device="cuda")
+    idx = idx[(idx != 4095) & (idx != (1 << 31) - 1) & (idx != (1 << 31)) & (idx != (1 << 31) + 1)]
+    assert bool((out[idx] == 4).all())
+    del out
+    total = int(gr.sum(A).numpy())
+    assert total == n - len(special) + sum(10 + k for k in range(len(special)))   # exact in int64
+    tail = gr.cumsum(A, 0).torch()[-1]
+    assert int(tail) == total
+    del a, A, tail
+    torch.cuda.empty_cache()
+
+
+def test_retain_release_and_explicit_stream(env):
+    gr, ctx, torch = env
+    import ctypes
+    st = torch.cuda.Stream()                      # default priority
+    c2 = gr.Context(stream=st.cuda_stream)
+    t = torch.from_numpy(_rand((1000,), 97)).cuda()
+    torch.cuda.synchronize()
+    a = c2.array(t)
+    z = gr.exp(a) * 2.0
+    assert gr.lib().gr_retain(c2._p, ctypes.c_uint64(z.h)) == 0      # a second handle reference
+    h = z.h
+    del z                                                            # drops one; the node lives on
+    z2 = gr.Array(c2, h)
+    out = torch.empty(1000, device="cuda")
+    with torch.cuda.stream(st):
+        z2.materialize_into(out)
+    c2.sync()
+    ref = (ora.exp(ora.array(t.cpu().numpy())) * 2.0).numpy()
+    assert_elementwise(out.cpu().numpy(), ref, what="explicit stream")
+    c2.set_stream(torch.cuda.current_stream().cuda_stream)
+    assert_elementwise((gr.exp(a) * 2.0).numpy(), ref, what="after set_stream")
+    del z2, a
+    c2.close()
+
+
 def test_stream_kernels(env):
     gr, ctx, torch = env
     src = torch.arange(1 << 20, dtype=torch.float32, device="cuda")
