@@ -119,6 +119,11 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *   "disk_cache"      1 (default) = compiled code objects are kept in
  *                     $GR_CACHE_DIR (default ~/.cache/grumpy_hip) keyed on
  *                     the sub-graph signature; 0 = in-memory cache only
+ *   "merge"           1 (default) = a reduction, scan or contraction recorded
+ *                     while a node with the same pending expression is still
+ *                     waiting to be evaluated returns a handle to that node
+ *                     (common subexpressions, Section 5 of the paper); the two
+ *                     handles then share value and storage; 0 = never
  *   "profile"         1 = bracket every launch with HIP events (gr_profile_*)
  * Unknown key: GR_ERR_ARG. */
 gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value);
@@ -256,6 +261,7 @@ typedef struct {
   double compile_ms;          /* total time inside the run-time compiler */
   uint64_t bytes_allocated;   /* by the context's allocator, cumulative */
   uint64_t disk_hits;         /* cache misses served from the on-disk code-object cache */
+  uint64_t nodes_merged;      /* recordings answered with an equal pending node (option "merge") */
 } gr_stats_t;
 
 gr_status gr_stats(gr_ctx* ctx, gr_stats_t* out);

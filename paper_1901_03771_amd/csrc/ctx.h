@@ -19,6 +19,8 @@ struct gr_ctx {
   // nodes
   std::unordered_map<uint64_t, gr::Node*> nodes;
   uint64_t next_id = 1;
+  // pending reductions, scans and contractions by expression hash (merging of equal ones at record time)
+  std::unordered_multimap<uint64_t, uint64_t> pending_expensive;
 
   // options
   int64_t opt_fusion = 1;
@@ -32,6 +34,7 @@ struct gr_ctx {
   int64_t opt_gemv_pair = 1;
   int64_t opt_async_compile = 1;
   int64_t opt_disk_cache = 1;
+  int64_t opt_merge = 1;
 
   // allocator
   void* (*alloc_fn)(size_t, void*) = nullptr;

@@ -30,6 +30,7 @@ struct Node {
   std::vector<Node*> in;  // predecessors (each holds one consumer reference)
   int handle_refs = 0;
   int consumer_refs = 0;
+  uint64_t shash = 0;  // hash of the expression below this node (materialised nodes: of their identity)
 
   // "data" / "is_materialized"
   bool materialized = false;

@@ -40,6 +40,12 @@ static void add_input(Node* n, Node* in) {
   in->consumer_refs++;
 }
 
+static void forget_pending(gr_ctx* c, const Node* n) {
+  auto range = c->pending_expensive.equal_range(n->shash);
+  for (auto it = range.first; it != range.second; ++it)
+    if (it->second == n->id) { c->pending_expensive.erase(it); return; }
+}
+
 // Frees every node that has lost its last reference, iteratively.
 void node_maybe_free(gr_ctx* c, Node* n0) {
   std::vector<Node*> work{n0};
@@ -53,6 +59,7 @@ void node_maybe_free(gr_ctx* c, Node* n0) {
     }
     n->in.clear();
     if (n->owns_data && n->data) ctx_free(c, n->data, n->alloc_bytes);
+    if (n->kind == Kind::REDUCE || n->kind == Kind::DOT || n->kind == Kind::SCAN) forget_pending(c, n);
     c->nodes.erase(n->id);
     c->stats.nodes_alive--;
     delete n;
@@ -74,6 +81,90 @@ static void contiguous_strides(Node* n) {
     n->strides[d] = s;
     s *= n->shape[d];
   }
+}
+
+// ---- merging of equal pending expressions at record time -----------------------
+// The DAG makes common subexpressions visible (Section 5 names their elimination as
+// something the representation enables).  Cheap pointwise duplicates are merged later,
+// inside a sub-graph, by value numbering of the point program: merging them here would
+// hand one node to several sub-graphs and the multiple-use rule of Algorithm 1 would then
+// store it, which costs more than recomputing it.  Reductions, scans and contractions are
+// sub-graph roots anyway and expensive, so an operation of those kinds whose whole pending
+// expression equals that of a node still waiting to be evaluated returns that node.
+// Materialised nodes never match anything but themselves: their storage may have been
+// written (slice assignment, or the caller's own code on a wrapped buffer) since.
+
+static inline uint64_t mix(uint64_t h, uint64_t v) {
+  h ^= v + 0x9e3779b97f4a7c15ull + (h << 6) + (h >> 2);
+  return h * 0xff51afd7ed558ccdull;
+}
+
+static void set_shash(Node* n) {
+  if (n->materialized || n->kind == Kind::LEAF) { n->shash = mix(0x4c454146, n->id); return; }
+  uint64_t h = mix((uint64_t)n->kind, (uint64_t)n->op * 16 + (uint64_t)n->dtype);
+  h = mix(h, (uint64_t)n->ndim);
+  for (int d = 0; d < n->ndim; ++d) h = mix(h, (uint64_t)n->shape[d]);
+  if (n->kind == Kind::CONST || n->kind == Kind::SCALAR) {
+    uint64_t bits;
+    std::memcpy(&bits, &n->value, 8);
+    h = mix(h, bits * 2 + (n->is_int ? 1 : 0));
+  }
+  for (const Node* p : n->in) {
+    h = mix(h, p->shash);
+    if (n->kind == Kind::SLICE) for (int d = 0; d < p->ndim; ++d) h = mix(mix(h, (uint64_t)n->start[d]), (uint64_t)n->step[d]);
+    if (n->kind == Kind::TRANSPOSE) for (int d = 0; d < p->ndim; ++d) h = mix(h, (uint64_t)n->perm[d]);
+    if (n->kind == Kind::REDUCE || n->kind == Kind::SCAN) {
+      for (int d = 0; d < p->ndim; ++d) h = mix(h, n->red_axis[d] ? 2 : 1);
+      h = mix(h, n->keepdims ? 2 : 1);
+    }
+  }
+  n->shash = h;
+}
+
+static bool same_expr(const Node* a, const Node* b, std::set<std::pair<uint64_t, uint64_t>>& assumed) {
+  if (a == b) return true;
+  if (a->materialized || b->materialized || a->kind == Kind::LEAF || b->kind == Kind::LEAF) return false;
+  if (a->shash != b->shash || a->kind != b->kind || a->op != b->op || a->dtype != b->dtype || a->ndim != b->ndim ||
+      a->in.size() != b->in.size())
+    return false;
+  for (int d = 0; d < a->ndim; ++d) if (a->shape[d] != b->shape[d]) return false;
+  if (a->kind == Kind::CONST || a->kind == Kind::SCALAR) return std::memcmp(&a->value, &b->value, 8) == 0 && a->is_int == b->is_int;
+  if (!assumed.insert({a->id, b->id}).second) return true;  // already compared (or being compared) on another path
+  if (!a->in.empty()) {
+    const Node* p = a->in[0];
+    if (a->kind == Kind::SLICE) for (int d = 0; d < p->ndim; ++d) if (a->start[d] != b->start[d] || a->step[d] != b->step[d]) return false;
+    if (a->kind == Kind::TRANSPOSE) for (int d = 0; d < p->ndim; ++d) if (a->perm[d] != b->perm[d]) return false;
+    if (a->kind == Kind::REDUCE || a->kind == Kind::SCAN) {
+      if (a->keepdims != b->keepdims || p->ndim != b->in[0]->ndim) return false;
+      for (int d = 0; d < p->ndim; ++d) if (a->red_axis[d] != b->red_axis[d]) return false;
+    }
+  }
+  for (size_t i = 0; i < a->in.size(); ++i) if (!same_expr(a->in[i], b->in[i], assumed)) return false;
+  return true;
+}
+
+// Finishes the recording of `n`: returns the handle to give out, which is an equal pending
+// node's if there is one (`n` is then dropped again).
+static gr_array finish(gr_ctx* c, Node* n) {
+  set_shash(n);
+  if (!(n->kind == Kind::REDUCE || n->kind == Kind::DOT || n->kind == Kind::SCAN)) return n->id;
+  if (c->opt_merge) {
+    auto range = c->pending_expensive.equal_range(n->shash);
+    for (auto it = range.first; it != range.second; ++it) {
+      auto f = c->nodes.find(it->second);
+      if (f == c->nodes.end() || f->second->materialized || f->second->planned) continue;
+      std::set<std::pair<uint64_t, uint64_t>> assumed;
+      if (!same_expr(f->second, n, assumed)) continue;
+      Node* e = f->second;
+      e->handle_refs++;
+      n->handle_refs = 0;
+      node_maybe_free(c, n);
+      c->stats.nodes_merged++;
+      return e->id;
+    }
+  }
+  c->pending_expensive.emplace(n->shash, n->id);
+  return n->id;
 }
 
 static bool is_unary(int op) { return op >= GR_NEG && op <= GR_ERF; }
@@ -104,6 +195,7 @@ gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   else if (k == "gemv_pair") ctx->opt_gemv_pair = value;
   else if (k == "async_compile") ctx->opt_async_compile = value;
   else if (k == "disk_cache") ctx->opt_disk_cache = value;
+  else if (k == "merge") ctx->opt_merge = value;
   else return fail(ctx, GR_ERR_ARG, "unknown option '" + k + "'");
   return GR_OK;
 }
@@ -138,6 +230,7 @@ gr_status gr_array_from_device(gr_ctx* ctx, void* dptr, gr_dtype dtype, int ndim
   nd->materialized = true;
   nd->data = dptr;
   nd->offset = 0;
+  set_shash(nd);
   *out = nd->id;
   return GR_OK;
 }
@@ -149,6 +242,7 @@ gr_status gr_scalar(gr_ctx* ctx, double value, int is_integer, gr_array* out) {
   nd->value = value;
   nd->is_int = is_integer != 0;
   nd->ndim = 0;
+  set_shash(nd);
   *out = nd->id;
   return GR_OK;
 }
@@ -168,7 +262,7 @@ gr_status gr_unary(gr_ctx* ctx, gr_op op, gr_array a, gr_array* out) {
   n->ndim = x->ndim;
   for (int d = 0; d < x->ndim; ++d) n->shape[d] = x->shape[d];
   add_input(n, x);
-  *out = n->id;
+  *out = finish(ctx, n);
   return GR_OK;
 }
 
@@ -217,11 +311,12 @@ gr_status gr_binary(gr_ctx* ctx, gr_op op, gr_array a, gr_array b, gr_array* out
     k->ndim = 0;
     k->is_int = o->is_int;
     k->value = dt == GR_F32 ? (double)(float)o->value : o->value;
+    set_shash(k);
     return k;
   };
   add_input(r, operand(x));
   add_input(r, operand(y));
-  *out = r->id;
+  *out = finish(ctx, r);
   return GR_OK;
 }
 
@@ -263,7 +358,7 @@ gr_status gr_slice(gr_ctx* ctx, gr_array a, int nspec, const int64_t* start, con
   r->ndim = x->ndim;
   for (int d = 0; d < x->ndim; ++d) { r->shape[d] = len[d]; r->start[d] = lo[d]; r->step[d] = st[d]; }
   add_input(r, x);
-  *out = r->id;
+  *out = finish(ctx, r);
   return GR_OK;
 }
 
@@ -286,7 +381,7 @@ gr_status gr_transpose(gr_ctx* ctx, gr_array a, const int* perm, gr_array* out) 
   r->ndim = x->ndim;
   for (int d = 0; d < x->ndim; ++d) { r->shape[d] = x->shape[p[d]]; r->perm[d] = p[d]; }
   add_input(r, x);
-  *out = r->id;
+  *out = finish(ctx, r);
   return GR_OK;
 }
 
@@ -321,7 +416,7 @@ gr_status gr_reduce(gr_ctx* ctx, gr_op op, gr_array a, const int* axes, int naxe
   }
   r->ndim = nd;
   add_input(r, x);
-  *out = r->id;
+  *out = finish(ctx, r);
   return GR_OK;
 }
 
@@ -341,7 +436,7 @@ gr_status gr_scan(gr_ctx* ctx, gr_op op, gr_array a, int axis, gr_array* out) {
   r->ndim = x->ndim;
   for (int d = 0; d < x->ndim; ++d) { r->shape[d] = x->shape[d]; r->red_axis[d] = d == ax; }
   add_input(r, x);
-  *out = r->id;
+  *out = finish(ctx, r);
   return GR_OK;
 }
 
@@ -362,7 +457,7 @@ gr_status gr_dot(gr_ctx* ctx, gr_array a, gr_array b, gr_array* out) {
   if (y->ndim == 2) r->shape[r->ndim - 1] = y->shape[1];
   add_input(r, x);
   add_input(r, y);
-  *out = r->id;
+  *out = finish(ctx, r);
   return GR_OK;
 }
 

@@ -50,7 +50,8 @@ class Stats(ctypes.Structure):
                 ("materialize_calls", ctypes.c_uint64), ("groups_executed", ctypes.c_uint64),
                 ("kernel_launches", ctypes.c_uint64), ("cache_hits", ctypes.c_uint64),
                 ("cache_misses", ctypes.c_uint64), ("compile_ms", ctypes.c_double),
-                ("bytes_allocated", ctypes.c_uint64), ("disk_hits", ctypes.c_uint64)]
+                ("bytes_allocated", ctypes.c_uint64), ("disk_hits", ctypes.c_uint64),
+                ("nodes_merged", ctypes.c_uint64)]
 
 
 _lib = None

@@ -529,6 +529,35 @@ def test_allocator_callbacks_and_out_of_memory(env):
     c3.close()
 
 
+def test_merged_pending_nodes_never_serve_stale_values(env):
+    gr, ctx, torch = env
+    x = _rand((3000,), 311)
+    t = torch.from_numpy(x.copy()).cuda()
+    a = ctx.array(t)
+    s1 = gr.sum(a * a)
+    s2 = gr.sum(a * a)                      # same pending expression: one node
+    assert s1.h == s2.h
+    v1 = float(s1.numpy())
+    assert float(s2.numpy()) == v1
+    assert_reduction(np.float32(v1), (ora.array(x) * ora.array(x)).sum().numpy(), what="merged sum")
+    t.mul_(2.0)                             # the caller rewrites the wrapped buffer
+    torch.cuda.synchronize()
+    s3 = gr.sum(a * a)                      # s1 is materialised: it must not be handed out again
+    assert s3.h != s1.h
+    assert_reduction(np.float32(s3.numpy()), 4.0 * (ora.array(x) * ora.array(x)).sum().numpy(), what="after rewrite")
+    # slice assignment evaluates pending readers first; a recording after it sees the new contents
+    p1 = gr.cumsum(a, 0)
+    a[0:10] = 1.0
+    p2 = gr.cumsum(a, 0)
+    assert p1.h != p2.h
+    y = 2.0 * x
+    r1 = ora.array(y).cumsum(0).numpy()
+    y[0:10] = 1.0
+    r2 = ora.array(y).cumsum(0).numpy()
+    assert_reduction(p1.numpy(), r1, what="scan recorded before the write")
+    assert_reduction(p2.numpy(), r2, what="scan recorded after the write")
+
+
 def test_index_space_beyond_32_bits(env):
     # 2^31 + 4099 elements: every offset computation must be 64-bit (map, two-stage reduction, scan)
     gr, ctx, torch = env

@@ -234,6 +234,54 @@ def test_multiple_use_across_subgraphs_materialises_once(ctx):
         assert exp_root in re.search(r"leaves=\[(.*?)\]", line).group(1).split(",")
 
 
+def test_equal_pending_reductions_scans_and_dots_are_merged_at_record_time(ctx):
+    # common subexpressions (Section 5): an expensive operation recorded twice on equal pending
+    # expressions is one node; cheap pointwise duplicates stay separate nodes (value numbering inside
+    # the kernel merges them without forcing a store)
+    X = ctx.spec((64, 5000))
+    m1, m2 = gr.max(X, axis=1, keepdims=True), gr.max(X, axis=1, keepdims=True)
+    assert m1.h == m2.h
+    assert gr.max(X, axis=1).h != m1.h and gr.max(X, axis=0, keepdims=True).h != m1.h and gr.min(X, axis=1, keepdims=True).h != m1.h
+    d1, d2 = X - m1, X - m2
+    assert d1.h != d2.h
+    s1, s2 = gr.sum(gr.exp(d1), axis=1, keepdims=True), gr.sum(gr.exp(d2), axis=1, keepdims=True)
+    assert s1.h == s2.h                                   # equal below different pointwise nodes
+    assert gr.sum(gr.exp(d1 * 2.0), axis=1, keepdims=True).h != s1.h
+    assert gr.sum(gr.exp(d1 * 1.0), axis=1, keepdims=True).h != s1.h
+    out = gr.exp(d1) / s1 + gr.exp(d2) / s2
+    kinds = groups(out)
+    assert [k for k, _ in kinds] == ["ROWRED"] and kinds[0][1].count("max") == 1 and kinds[0][1].count("sum") == 1
+    v = ctx.spec((1 << 22,))
+    two = gr.sum(v * v) + gr.sum(v * v)
+    assert [k for k, _ in groups(two)] == ["REDUCE", "MAP"]
+    A, w = ctx.spec((300, 200)), ctx.spec((200,))
+    assert gr.dot(A, w).h == gr.dot(A, w).h and gr.dot(A, w).h != gr.dot(A, w * 2.0).h
+    assert gr.dot(A.T[:, 1:], A[1:, :]).h == gr.dot(A.T[:, 1:], A[1:, :]).h
+    assert gr.dot(A.T[:, 1:], A[1:, :]).h != gr.dot(A.T[:, :-1], A[1:, :]).h
+    assert gr.cumsum(v * 2.0, 0).h == gr.cumsum(v * 2.0, 0).h and gr.cumsum(v, 0).h != gr.cummax(v, 0).h
+    merged = ctx.stats()["nodes_merged"]
+    assert merged >= 6
+    # every handle given out is its own reference: dropping one of two leaves the node alive
+    del m2
+    assert m1.shape == (64, 1) and (X - m1).shape == (64, 5000)
+    ctx.set_option("merge", 0)
+    assert gr.max(X, axis=1, keepdims=True).h != m1.h
+    assert ctx.stats()["nodes_merged"] == merged
+
+
+def test_merged_nodes_do_not_leak(ctx):
+    X = ctx.spec((100, 100))
+    base = ctx.stats()["nodes_alive"]
+    a = gr.sum(X * X)
+    b = gr.sum(X * X)
+    c = gr.sum(X * X) + 1.0
+    assert a.h == b.h
+    del a
+    assert b.shape == ()
+    del b, c
+    assert ctx.stats()["nodes_alive"] == base
+
+
 def test_leaves_and_only_leaves_are_materialised(ctx):
     a = ctx.spec((33, 65))
     out = (a.T @ (a @ ctx.spec((65,)))) * 2.0
