@@ -119,6 +119,14 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *   "disk_cache"      1 (default) = compiled code objects are kept in
  *                     $GR_CACHE_DIR (default ~/.cache/grumpy_hip) keyed on
  *                     the sub-graph signature; 0 = in-memory cache only
+ *   "interp"          1 (default) = a map sub-graph whose kernel is still in the
+ *                     run-time compiler is evaluated by a precompiled byte-code
+ *                     interpreter of the point function instead of waiting
+ *                     (f32 / i32 programs within fixed size limits; everything
+ *                     else waits as with 0); the compilation goes on in the
+ *                     background and later requests use the compiled kernel;
+ *                     0 = always wait for the compiler; 2 = interpret every map
+ *                     sub-graph the interpreter covers (for testing it)
  *   "merge"           1 (default) = a reduction, scan or contraction recorded
  *                     while a node with the same pending expression is still
  *                     waiting to be evaluated returns a handle to that node
@@ -248,6 +256,13 @@ gr_status gr_plan_source(gr_ctx* ctx, gr_array a, int index, char* buf, size_t c
  * gr_last_error on failure. */
 gr_status gr_plan_compile(gr_ctx* ctx, gr_array a);
 
+/* Blocks until every run-time compilation started by earlier requests has
+ * finished, loads the kernels and writes their code objects to the on-disk
+ * cache (Section 6 of the paper: compilation runs beside execution; this is
+ * the point where a caller who wants the compiled kernels from now on waits
+ * for them).  GR_ERR_COMPILE with the first compiler log on failure. */
+gr_status gr_compile_wait(gr_ctx* ctx);
+
 /* ---- statistics and profiling ------------------------------------------- */
 
 typedef struct {
@@ -262,6 +277,7 @@ typedef struct {
   uint64_t bytes_allocated;   /* by the context's allocator, cumulative */
   uint64_t disk_hits;         /* cache misses served from the on-disk code-object cache */
   uint64_t nodes_merged;      /* recordings answered with an equal pending node (option "merge") */
+  uint64_t interp_launches;   /* sub-graphs evaluated by the byte-code interpreter (option "interp") */
 } gr_stats_t;
 
 gr_status gr_stats(gr_ctx* ctx, gr_stats_t* out);

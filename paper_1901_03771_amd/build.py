@@ -7,12 +7,12 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgrumpy_hip.so")
-SOURCES = ["recorder.cpp", "plan.cpp", "codegen.cpp", "runtime.cpp", "stream_kernels.hip"]
+SOURCES = ["recorder.cpp", "plan.cpp", "codegen.cpp", "runtime.cpp", "interp.cpp", "stream_kernels.hip", "interp_kernel.hip"]
 
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-fPIC", "-shared",
+    cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
            "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES] + ["-lhiprtc"]

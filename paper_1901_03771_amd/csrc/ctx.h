@@ -35,6 +35,7 @@ struct gr_ctx {
   int64_t opt_async_compile = 1;
   int64_t opt_disk_cache = 1;
   int64_t opt_merge = 1;
+  int64_t opt_interp = 1;
 
   // allocator
   void* (*alloc_fn)(size_t, void*) = nullptr;
@@ -56,7 +57,8 @@ struct gr_ctx {
 
   // run-time compilations in flight (signature -> job), see runtime.cpp
   struct CompileJob {
-    std::string src, log, kernel;
+    std::string src, log, kernel;  // kernel: name of the entry point
+    bool combine = false, scan = false;  // the code object also holds a combine stage / the scan helpers
     std::vector<char> code;
     bool ok = false;
     double ms = 0.0;
@@ -103,6 +105,7 @@ std::string kernel_name(const GroupPlan& g);
 
 // runtime.cpp
 gr_status prepare_group(gr_ctx* c, GroupPlan& g);
+gr_status collect_all_jobs(gr_ctx* c);
 gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out);
 gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr, void* pair_out_ptr);
 gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool check_alias);

@@ -1,0 +1,148 @@
+// Host side of the point-program interpreter: encodes the single-point program
+// of a map sub-graph as byte code with LDS slots assigned by a linear scan over
+// the values' live ranges, and launches the precompiled kernel.
+#include <algorithm>
+
+#include "ctx.h"
+#include "interp.h"
+
+extern "C" int gr_launch_interp_map(void* stream, const GrInterpArgs* args, unsigned grid);
+
+namespace gr {
+
+static int opcode(const Instr& in) {
+  const bool f = in.dtype == GR_F32;
+  if (in.kind == IKind::UNARY) switch (in.op) {
+    case GR_NEG: return f ? GI_FNEG : GI_INEG;
+    case GR_ABS: return f ? GI_FABS : GI_IABS;
+    case GR_SQUARE: return f ? GI_FSQUARE : GI_ISQUARE;
+    case GR_EXP: return f ? GI_FEXP : -1;
+    case GR_LOG: return f ? GI_FLOG : -1;
+    case GR_SQRT: return f ? GI_FSQRT : -1;
+    case GR_TANH: return f ? GI_FTANH : -1;
+    case GR_ERF: return f ? GI_FERF : -1;
+  }
+  if (in.kind == IKind::BINARY) switch (in.op) {
+    case GR_ADD: return f ? GI_FADD : GI_IADD;
+    case GR_SUB: return f ? GI_FSUB : GI_ISUB;
+    case GR_MUL: return f ? GI_FMUL : GI_IMUL;
+    case GR_DIV: return f ? GI_FDIV : -1;
+    case GR_MAXIMUM: return f ? GI_FMAX : GI_IMAX;
+    case GR_MINIMUM: return f ? GI_FMIN : GI_IMIN;
+  }
+  return -1;
+}
+
+// Fills `A` and `grid` for sub-graph `g` writing to `out_ptr`; false if the sub-graph is outside
+// what the interpreter covers (then the caller waits for the compiler as usual).
+bool interp_encode(const GroupPlan& g, void* out_ptr, GrInterpArgs* A, unsigned* grid) {
+  if (g.kind != GroupKind::MAP || g.rank < 1 || g.rank > GR_INTERP_RANK || g.out_dtype == GR_I64 || g.result1 < 0) return false;
+  if (g.groups.size() > GR_INTERP_GROUPS || g.consts.size() > GR_INTERP_CONSTS) return false;
+  const std::vector<Instr>& p = g.prog1;
+  const int n = (int)p.size();
+  // instructions the result depends on, and the last reader of each value
+  std::vector<int> last(n, -1);
+  std::vector<char> need(n, 0);
+  need[g.result1] = 1;
+  for (int i = n - 1; i >= 0; --i) {
+    if (!need[i]) continue;
+    for (int o : {p[i].a, p[i].b}) {
+      if (o < 0) continue;
+      if (o >= i) return false;  // not in evaluation order
+      need[o] = 1;
+      last[o] = std::max(last[o], i);
+    }
+  }
+  last[g.result1] = n;
+  const int pad = GR_INTERP_RANK - g.rank;
+  std::memset(A, 0, sizeof *A);
+  int64_t total = 1;
+  for (int k = 0; k < GR_INTERP_RANK; ++k) A->dims[k] = 1;
+  for (int k = 0; k < g.rank; ++k) { A->dims[k + pad] = g.dims[k]; total *= g.dims[k]; }
+  if (total <= 0) return false;
+  int64_t blocks = (g.dims[g.rank - 1] + 255) / 256;
+  for (int k = 0; k + 1 < g.rank; ++k) {
+    blocks *= g.dims[k];
+    if (blocks > 0x7fffffffLL) return false;
+  }
+  *grid = (unsigned)blocks;
+  for (size_t gi = 0; gi < g.groups.size(); ++gi) {
+    const AccessGroup& ag = g.groups[gi];
+    if (ag.dtype == GR_I64 || !ag.leaf || !ag.leaf->data) return false;
+    A->gptr[gi] = (unsigned long long)(uintptr_t)ag.leaf->data + 4ull * (unsigned long long)ag.base;
+    for (int k = 0; k < g.rank; ++k) A->gcoef[gi][k + pad] = ag.structural_zero[k] ? 0 : ag.coef[k];
+  }
+  A->out = (unsigned long long)(uintptr_t)out_ptr + 4ull * (unsigned long long)g.out_base;
+  for (int k = 0; k < g.rank; ++k) A->ocoef[k + pad] = g.out_coef[k];
+  if (g.out_unit) A->ocoef[GR_INTERP_RANK - 1] = 1;
+  for (size_t i = 0; i < g.consts.size(); ++i) {
+    const ConstSlot& cs = g.consts[i];
+    if (cs.dtype == GR_F32) { float f = (float)cs.value; std::memcpy(&A->consts[i], &f, 4); }
+    else if (cs.dtype == GR_I32) A->consts[i] = (unsigned)(int32_t)(int64_t)cs.value;
+    else return false;
+  }
+  // linear scan: a value's slot is free again after its last reader
+  std::vector<int> slot(n, -1), free_slots;
+  for (int s = GR_INTERP_SLOTS - 1; s >= 0; --s) free_slots.push_back(s);
+  int ni = 0, nl = 0;
+  for (int i = 0; i < n; ++i) {
+    if (!need[i]) continue;
+    const Instr& in = p[i];
+    if (in.dtype == GR_I64 || ni >= GR_INTERP_INSTR) return false;
+    unsigned op, xa = 0, xb = 0;
+    if (in.kind == IKind::LOAD) {
+      if (nl >= GR_INTERP_LOADS || in.group < 0 || in.group >= (int)g.groups.size()) return false;
+      const AccessGroup& ag = g.groups[in.group];
+      int64_t off = 0;
+      for (int k = 0; k < g.rank; ++k) if (!ag.structural_zero[k]) off += in.delta[k] * ag.coef[k];
+      A->ldoff[nl] = off;
+      op = GI_LOAD; xa = (unsigned)in.group; xb = (unsigned)nl++;
+    } else if (in.kind == IKind::CONST) {
+      if (in.cslot < 0 || in.cslot >= (int)g.consts.size()) return false;
+      op = GI_CONST; xa = (unsigned)in.cslot;
+    } else {
+      int oc = opcode(in);
+      if (oc < 0 || in.a < 0 || slot[in.a] < 0) return false;
+      op = (unsigned)oc;
+      xa = (unsigned)slot[in.a];
+      xb = xa;
+      if (in.kind == IKind::BINARY) {
+        if (in.b < 0 || slot[in.b] < 0) return false;
+        xb = (unsigned)slot[in.b];
+      }
+      // operands are read before the result is written: a dying operand's slot can be reused at once
+      for (int o : {in.a, in.kind == IKind::BINARY ? in.b : -1})
+        if (o >= 0 && last[o] == i && slot[o] >= 0) { free_slots.push_back(slot[o]); slot[o] = -2 - slot[o]; }
+    }
+    if (free_slots.empty()) return false;
+    int dst = free_slots.back();
+    free_slots.pop_back();
+    slot[i] = dst;
+    A->code[ni++] = op | ((unsigned)dst << 8) | (xa << 16) | (xb << 24);
+  }
+  A->n_instr = ni;
+  A->result_slot = slot[g.result1];
+  return A->result_slot >= 0;
+}
+
+gr_status interp_launch(gr_ctx* c, const GrInterpArgs& A, unsigned grid) {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (c->opt_profile) {
+    for (hipEvent_t* ev : {&e0, &e1}) {
+      if (!c->event_pool.empty()) { *ev = c->event_pool.back(); c->event_pool.pop_back(); }
+      else if (hipEventCreate(ev) != hipSuccess) return fail(c, GR_ERR_HIP, "hipEventCreate failed");
+    }
+    (void)hipEventRecord(e0, c->stream);
+  }
+  int e = gr_launch_interp_map(c->stream, &A, grid);
+  if (e != 0) return fail(c, GR_ERR_HIP, std::string("interpreter launch -> ") + hipGetErrorName((hipError_t)e));
+  if (c->opt_profile) {
+    (void)hipEventRecord(e1, c->stream);
+    c->prof.push_back({"gr_interp_map", e0, e1});
+  }
+  c->stats.kernel_launches++;
+  c->stats.interp_launches++;
+  return GR_OK;
+}
+
+}  // namespace gr

@@ -1,0 +1,35 @@
+// Argument block of the point-program interpreter, shared by the host encoder
+// and the device kernel.  A map sub-graph whose kernel is still being compiled
+// runs through this one precompiled kernel instead of waiting (Section 6 of
+// the paper names JIT time as the main bottleneck and overlapping compilation
+// with execution as the remedy): the point function of Section 3.1 is executed
+// as byte code, one iteration point per lane.
+#pragma once
+
+#define GR_INTERP_RANK 6       // iteration dimensions, right-aligned (leading ones pad)
+#define GR_INTERP_GROUPS 12    // operand access patterns
+#define GR_INTERP_LOADS 48
+#define GR_INTERP_CONSTS 32
+#define GR_INTERP_INSTR 192
+#define GR_INTERP_SLOTS 40     // live 32-bit values per lane (kept in LDS, slot-major)
+
+enum {
+  GI_LOAD = 0, GI_CONST,
+  GI_FNEG, GI_FABS, GI_FEXP, GI_FLOG, GI_FSQRT, GI_FSQUARE, GI_FTANH, GI_FERF,
+  GI_FADD, GI_FSUB, GI_FMUL, GI_FDIV, GI_FMAX, GI_FMIN,
+  GI_INEG, GI_IABS, GI_ISQUARE, GI_IADD, GI_ISUB, GI_IMUL, GI_IMAX, GI_IMIN
+};
+
+struct GrInterpArgs {
+  int n_instr;
+  int result_slot;
+  long long dims[GR_INTERP_RANK];
+  unsigned long long gptr[GR_INTERP_GROUPS];               // byte address read at iteration point 0 with no shift
+  long long gcoef[GR_INTERP_GROUPS][GR_INTERP_RANK];       // elements per unit step of each iteration dimension
+  unsigned long long out;                                  // byte address of the output element of point 0
+  long long ocoef[GR_INTERP_RANK];
+  long long ldoff[GR_INTERP_LOADS];                        // element offset of each load's static shift
+  unsigned consts[GR_INTERP_CONSTS];                       // bit patterns
+  unsigned code[GR_INTERP_INSTR];                          // op | dst << 8 | a << 16 | b << 24
+                                                           // LOAD: a = group, b = index into ldoff; CONST: a = index into consts
+};

@@ -1,0 +1,91 @@
+// Point-program interpreter: evaluates a fused map sub-graph from byte code
+// while its generated kernel is still in the run-time compiler.  Same
+// arithmetic as the generated code (one IEEE operation per recorded op, no
+// contraction; the same device math functions), one iteration point per lane.
+//
+// A workgroup covers 256 consecutive positions of the innermost iteration
+// dimension at one index of the outer dimensions, so the outer index is found
+// once per workgroup with 32-bit divisions.  Values live in LDS, slot-major
+// (lane l of slot s at s*256+l: conflict-free, and no private-memory arrays).
+#include <hip/hip_runtime.h>
+
+#include "interp.h"
+
+#define GM __attribute__((address_space(1)))
+
+static __device__ __forceinline__ float gi_maxf(float a, float b) { return (a >= b || a != a) ? a : b; }
+static __device__ __forceinline__ float gi_minf(float a, float b) { return (a <= b || a != a) ? a : b; }
+
+__global__ __launch_bounds__(256) void gr_interp_map_kernel(GrInterpArgs a) {
+  __shared__ unsigned vals[GR_INTERP_SLOTS * 256];
+  constexpr int CD = GR_INTERP_RANK - 1;
+  const long long C = a.dims[CD];
+  const unsigned ntc = (unsigned)((C + 255) / 256);
+  const unsigned ct = blockIdx.x % ntc;
+  unsigned rem = blockIdx.x / ntc;
+  unsigned idx[CD];
+#pragma unroll
+  for (int k = CD - 1; k >= 0; --k) {
+    const unsigned d = (unsigned)a.dims[k];  // the host checked that the grid, hence every outer extent, fits 31 bits
+    idx[k] = rem % d;
+    rem /= d;
+  }
+  const long long c = (long long)ct * 256 + threadIdx.x;
+  if (c >= C) return;  // no barrier below: every lane touches only its own LDS column
+  unsigned* const my = vals + threadIdx.x;
+  const int n = a.n_instr;
+  for (int pc = 0; pc < n; ++pc) {
+    const unsigned w = a.code[pc];
+    const unsigned op = w & 0xffu, dst = (w >> 8) & 0xffu, xa = (w >> 16) & 0xffu, xb = w >> 24;
+    unsigned r;
+    if (op == GI_LOAD) {
+      long long off = a.ldoff[xb] + a.gcoef[xa][CD] * c;
+#pragma unroll
+      for (int k = 0; k < CD; ++k) off += a.gcoef[xa][k] * (long long)idx[k];
+      r = *(const GM unsigned*)(a.gptr[xa] + 4ull * (unsigned long long)off);
+    } else if (op == GI_CONST) {
+      r = a.consts[xa];
+    } else {
+      const unsigned ux = my[xa * 256];
+      const unsigned uy = my[xb * 256];  // unary ops encode b = a
+      const float fx = __uint_as_float(ux), fy = __uint_as_float(uy);
+      const int ix = (int)ux, iy = (int)uy;
+      switch (op) {
+        case GI_FNEG: r = __float_as_uint(-fx); break;
+        case GI_FABS: r = __float_as_uint(__builtin_fabsf(fx)); break;
+        case GI_FEXP: r = __float_as_uint(expf(fx)); break;
+        case GI_FLOG: r = __float_as_uint(logf(fx)); break;
+        case GI_FSQRT: r = __float_as_uint(sqrtf(fx)); break;
+        case GI_FSQUARE: r = __float_as_uint(fx * fx); break;
+        case GI_FTANH: r = __float_as_uint(tanhf(fx)); break;
+        case GI_FERF: r = __float_as_uint(erff(fx)); break;
+        case GI_FADD: r = __float_as_uint(fx + fy); break;
+        case GI_FSUB: r = __float_as_uint(fx - fy); break;
+        case GI_FMUL: r = __float_as_uint(fx * fy); break;
+        case GI_FDIV: r = __float_as_uint(fx / fy); break;
+        case GI_FMAX: r = __float_as_uint(gi_maxf(fx, fy)); break;
+        case GI_FMIN: r = __float_as_uint(gi_minf(fx, fy)); break;
+        // i32: two's-complement wrap-around through unsigned arithmetic
+        case GI_INEG: r = 0u - ux; break;
+        case GI_IABS: r = ix < 0 ? 0u - ux : ux; break;
+        case GI_ISQUARE: r = ux * ux; break;
+        case GI_IADD: r = ux + uy; break;
+        case GI_ISUB: r = ux - uy; break;
+        case GI_IMUL: r = ux * uy; break;
+        case GI_IMAX: r = ix >= iy ? ux : uy; break;
+        case GI_IMIN: r = ix <= iy ? ux : uy; break;
+        default: r = 0u; break;
+      }
+    }
+    my[dst * 256] = r;
+  }
+  long long oo = a.ocoef[CD] * c;
+#pragma unroll
+  for (int k = 0; k < CD; ++k) oo += a.ocoef[k] * (long long)idx[k];
+  *(GM unsigned*)(a.out + 4ull * (unsigned long long)oo) = my[a.result_slot * 256];
+}
+
+extern "C" int gr_launch_interp_map(void* stream, const GrInterpArgs* args, unsigned grid) {
+  hipLaunchKernelGGL(gr_interp_map_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args);
+  return (int)hipGetLastError();
+}

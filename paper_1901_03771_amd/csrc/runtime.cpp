@@ -18,11 +18,15 @@
 
 #include "codegen.h"
 #include "ctx.h"
+#include "interp.h"
 
 extern "C" void gr_launch_stream_copy(void* stream, void* dst, const void* src, size_t n16);
 extern "C" void gr_launch_stream_read(void* stream, const void* src, size_t n16, void* sink);
 
 namespace gr {
+
+bool interp_encode(const GroupPlan& g, void* out_ptr, GrInterpArgs* A, unsigned* grid);
+gr_status interp_launch(gr_ctx* c, const GrInterpArgs& A, unsigned grid);
 
 static std::string hip_err(hipError_t e) { return std::string(hipGetErrorName(e)) + ": " + hipGetErrorString(e); }
 
@@ -146,22 +150,30 @@ static void disk_store(const std::string& path, const std::string& sig, const st
   else ::remove(tmp.c_str());
 }
 
+// What finish_kernel needs to know about a sub-graph: kept with a compilation job so that the
+// job can be collected without the plan that started it.
+static void kernel_entry_points(const GroupPlan& g, std::string* name, bool* combine, bool* scan) {
+  *name = kernel_name(g);
+  *combine = (g.kind == GroupKind::GEMV && g.gemv_mode >= 1) || g.kind == GroupKind::REDUCE;
+  *scan = g.kind == GroupKind::SCAN && g.scan_mode == 0;
+}
+
 // Loads a code object and publishes the kernel in the in-memory cache.
-static gr_status finish_kernel(gr_ctx* c, const GroupPlan& g, std::vector<char>&& code, gr_ctx::Kernel** out) {
+static gr_status finish_kernel(gr_ctx* c, const std::string& sig, const std::string& name, bool combine, bool scan,
+                               std::vector<char>&& code, gr_ctx::Kernel** out) {
   gr_ctx::Kernel k;
   k.code = std::move(code);
-  k.name = kernel_name(g);
+  k.name = name;
   if (c->device >= 0) {
     GR_HIP(c, hipModuleLoadData(&k.module, k.code.data()));
     GR_HIP(c, hipModuleGetFunction(&k.fn, k.module, k.name.c_str()));
-    if ((g.kind == GroupKind::GEMV && g.gemv_mode >= 1) || g.kind == GroupKind::REDUCE)
-      GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, (k.name + "_combine").c_str()));
-    if (g.kind == GroupKind::SCAN && g.scan_mode == 0) {
+    if (combine) GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, (k.name + "_combine").c_str()));
+    if (scan) {
       GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, "gr_scan_sums"));
       GR_HIP(c, hipModuleGetFunction(&k.fn3, k.module, "gr_scan_offsets"));
     }
   }
-  auto ins = c->cache.emplace(g.signature, std::move(k));
+  auto ins = c->cache.emplace(sig, std::move(k));
   if (out) *out = &ins.first->second;
   return GR_OK;
 }
@@ -176,17 +188,59 @@ gr_status prepare_group(gr_ctx* c, GroupPlan& g) {
   if (disk_load(disk_path(c, g.signature), g.signature, &code)) {
     c->stats.cache_misses++;
     c->stats.disk_hits++;
-    return finish_kernel(c, g, std::move(code), nullptr);
+    std::string name;
+    bool combine, scan;
+    kernel_entry_points(g, &name, &combine, &scan);
+    return finish_kernel(c, g.signature, name, combine, scan, std::move(code), nullptr);
   }
   gr_status est = expand_patch(c, &g);
   if (est != GR_OK) return est;
   auto job = std::make_shared<gr_ctx::CompileJob>();
   job->src = generate_source(g);
+  kernel_entry_points(g, &job->kernel, &job->combine, &job->scan);
   if (getenv("GR_LOG")) fprintf(stderr, "---- generated kernel ----\n%s\n", job->src.c_str());
   gr_ctx::CompileJob* raw = job.get();
   std::future<void> fut = c->opt_async_compile ? std::async(std::launch::async, run_hiprtc, raw) : std::async(std::launch::deferred, run_hiprtc, raw);
   c->pending.emplace(g.signature, std::make_pair(job, std::move(fut)));
   return GR_OK;
+}
+
+// Waits for the compilation job of `sig` (or, when deferred, runs it), stores the code object
+// on disk and publishes the kernel.
+static gr_status collect_job(gr_ctx* c, const std::string& sig, gr_ctx::Kernel** out) {
+  auto pit = c->pending.find(sig);
+  if (pit == c->pending.end()) return fail(c, GR_ERR_COMPILE, "no compilation job for this sub-graph");
+  pit->second.second.get();
+  std::shared_ptr<gr_ctx::CompileJob> job = pit->second.first;
+  c->pending.erase(pit);
+  c->stats.cache_misses++;
+  c->stats.compile_ms += job->ms;
+  if (!job->ok) {
+    if (getenv("GR_LOG")) fprintf(stderr, "%s\n", job->src.c_str());
+    return fail(c, GR_ERR_COMPILE, "hipRTC: " + job->log);
+  }
+  disk_store(disk_path(c, sig), sig, job->code);
+  return finish_kernel(c, sig, job->kernel, job->combine, job->scan, std::move(job->code), out);
+}
+
+gr_status collect_all_jobs(gr_ctx* c) {
+  gr_status first = GR_OK;
+  std::string first_err;
+  while (!c->pending.empty()) {
+    std::string sig = c->pending.begin()->first;
+    gr_status st = collect_job(c, sig, nullptr);
+    if (st != GR_OK && first == GR_OK) { first = st; first_err = c->err; }
+  }
+  if (first != GR_OK) c->err = first_err;
+  return first;
+}
+
+// True while the kernel of `g` is neither cached nor ready to be collected without waiting.
+static bool still_compiling(gr_ctx* c, const GroupPlan& g) {
+  if (c->cache.count(g.signature)) return false;
+  auto pit = c->pending.find(g.signature);
+  if (pit == c->pending.end()) return false;
+  return pit->second.second.wait_for(std::chrono::seconds(0)) == std::future_status::timeout;
 }
 
 gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
@@ -200,19 +254,7 @@ gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
   if (st != GR_OK) return st;
   it = c->cache.find(g.signature);
   if (it != c->cache.end()) { *out = &it->second; return GR_OK; }  // served from disk
-  auto pit = c->pending.find(g.signature);
-  if (pit == c->pending.end()) return fail(c, GR_ERR_COMPILE, "no compilation job for this sub-graph");
-  pit->second.second.get();  // wait for (or, when deferred, run) the job
-  std::shared_ptr<gr_ctx::CompileJob> job = pit->second.first;
-  c->pending.erase(pit);
-  c->stats.cache_misses++;
-  c->stats.compile_ms += job->ms;
-  if (!job->ok) {
-    if (getenv("GR_LOG")) fprintf(stderr, "%s\n", job->src.c_str());
-    return fail(c, GR_ERR_COMPILE, "hipRTC: " + job->log);
-  }
-  disk_store(disk_path(c, g.signature), g.signature, job->code);
-  return finish_kernel(c, g, std::move(job->code), out);
+  return collect_job(c, g.signature, out);
 }
 
 static gr_status launch(gr_ctx* c, hipFunction_t fn, const std::string& name, int64_t grid, std::vector<uint64_t>& args) {
@@ -414,7 +456,11 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
   for (auto& gp : plan->groups) {
     GroupPlan& g = *gp;
     gr_ctx::Kernel* k = nullptr;
-    gr_status st = compile_group(c, g, &k);
+    // A map sub-graph whose kernel is still in the compiler runs through the byte-code
+    // interpreter instead of waiting; the job stays pending and a later request collects it.
+    // (option "interp" = 2: every map sub-graph the interpreter covers, compiled or not)
+    const bool try_interp = g.kind == GroupKind::MAP && !g.pair && (c->opt_interp >= 2 || (c->opt_interp == 1 && still_compiling(c, g)));
+    gr_status st = try_interp ? GR_OK : compile_group(c, g, &k);
     if (st != GR_OK) return st;
     // output buffers: the caller's for the requested root, the allocator's otherwise
     Node* roots[2] = {g.root, g.pair ? g.pair->root : nullptr};
@@ -430,7 +476,22 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
         own[q] = true;
       }
     }
-    st = launch_group(c, g, k, outs[0], outs[1]);
+    bool interpreted = false;
+    if (try_interp) {
+      GrInterpArgs ia;
+      unsigned igrid = 0;
+      int64_t total = 1;
+      for (int k2 = 0; k2 < g.rank; ++k2) total *= g.dims[k2];
+      if (total == 0) interpreted = true;  // nothing to compute
+      else if (interp_encode(g, outs[0], &ia, &igrid)) {
+        st = interp_launch(c, ia, igrid);
+        interpreted = true;
+      }
+    }
+    if (!interpreted) {
+      if (!k) st = compile_group(c, g, &k);
+      if (st == GR_OK) st = launch_group(c, g, k, outs[0], outs[1]);
+    }
     if (st != GR_OK) {
       for (int q = 0; q < 2; ++q) if (own[q]) ctx_free(c, outs[q], nbytes[q]);
       return st;
@@ -502,8 +563,7 @@ gr_status gr_sync(gr_ctx* ctx) {
 gr_status gr_ctx_destroy(gr_ctx* ctx) {
   if (!ctx) return GR_ERR_ARG;
   if (ctx->device >= 0) (void)hipStreamSynchronize(ctx->stream);
-  for (auto& kv : ctx->pending) if (kv.second.second.valid()) kv.second.second.wait();
-  ctx->pending.clear();
+  (void)collect_all_jobs(ctx);  // finished code objects go to the on-disk cache
   std::vector<Node*> all;
   for (auto& kv : ctx->nodes) all.push_back(kv.second);
   for (Node* n : all) {
@@ -518,6 +578,11 @@ gr_status gr_ctx_destroy(gr_ctx* ctx) {
   for (void* p : ctx->pool_all) (void)hipFree(p);
   delete ctx;
   return GR_OK;
+}
+
+gr_status gr_compile_wait(gr_ctx* ctx) {
+  if (!ctx) return GR_ERR_ARG;
+  return collect_all_jobs(ctx);
 }
 
 gr_status gr_ctx_set_stream(gr_ctx* ctx, void* hip_stream) {

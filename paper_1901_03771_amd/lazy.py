@@ -34,7 +34,7 @@ SYMBOLS = [
     "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose",
     "gr_reduce", "gr_scan", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_assign", "gr_ndim", "gr_shape", "gr_dtype_of",
     "gr_is_materialized", "gr_data_ptr", "gr_retain", "gr_release", "gr_plan_describe", "gr_plan_source",
-    "gr_plan_compile", "gr_stats", "gr_profile_reset", "gr_profile_read", "gr_stream_copy", "gr_stream_read",
+    "gr_plan_compile", "gr_compile_wait", "gr_stats", "gr_profile_reset", "gr_profile_read", "gr_stream_copy", "gr_stream_read",
 ]
 
 
@@ -51,7 +51,7 @@ class Stats(ctypes.Structure):
                 ("kernel_launches", ctypes.c_uint64), ("cache_hits", ctypes.c_uint64),
                 ("cache_misses", ctypes.c_uint64), ("compile_ms", ctypes.c_double),
                 ("bytes_allocated", ctypes.c_uint64), ("disk_hits", ctypes.c_uint64),
-                ("nodes_merged", ctypes.c_uint64)]
+                ("nodes_merged", ctypes.c_uint64), ("interp_launches", ctypes.c_uint64)]
 
 
 _lib = None
@@ -87,6 +87,7 @@ def lib():
         "gr_retain": [P, U64], "gr_release": [P, U64],
         "gr_plan_describe": [P, U64, ctypes.c_char_p, SZ, PP(SZ)],
         "gr_plan_source": [P, U64, I, ctypes.c_char_p, SZ, PP(SZ)], "gr_plan_compile": [P, U64],
+        "gr_compile_wait": [P],
         "gr_stats": [P, PP(Stats)], "gr_profile_reset": [P],
         "gr_profile_read": [P, ctypes.c_char_p, PP(U64), PP(ctypes.c_double)],
         "gr_stream_copy": [P, P, P, SZ], "gr_stream_read": [P, P, SZ, P],
@@ -179,6 +180,10 @@ class Context:
     def sync(self):
         self.check(lib().gr_sync(self._p))
 
+    def compile_wait(self):
+        """Blocks until every compilation running in the background has finished."""
+        self.check(lib().gr_compile_wait(self._p))
+
     def stats(self) -> dict:
         s = Stats()
         self.check(lib().gr_stats(self._p, ctypes.byref(s)))
@@ -244,6 +249,15 @@ class Context:
                                         ctypes.c_void_p(sink.data_ptr())))
 
 
+class _DeviceExport:
+    """Zero-copy hand-over of a materialised node's storage (CUDA array interface, version 2)."""
+
+    def __init__(self, owner, ptr, shape, byte_strides, typestr):
+        self.owner = owner  # keeps the handle, hence the storage, alive
+        self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": typestr, "data": (ptr, False), "version": 2,
+                                         "strides": byte_strides if len(shape) else None}
+
+
 class Array:
     """Handle of one DAG node."""
 
@@ -306,16 +320,23 @@ class Array:
             self.ctx.check(st)
         return self
 
-    def torch(self):
-        """Evaluates the node into a fresh torch tensor on the context's device."""
+    def torch(self, copy: bool = True):
+        """Evaluates the node (its storage then belongs to the library and lives as long as the node,
+        Section 2) and returns its value as a torch tensor on the context's device: a copy by default,
+        with copy=False a tensor that shares the node's storage (and keeps this handle alive)."""
         torch = _torch()
-        dt = {GR_F32: torch.float32, GR_I32: torch.int32, GR_I64: torch.int64}[self.dtype_code]
-        out = torch.empty(self.shape, dtype=dt, device=f"cuda:{self.ctx.device}")
-        self.materialize_into(out)
-        return out
+        dt = {GR_F32: (torch.float32, "<f4", 4), GR_I32: (torch.int32, "<i4", 4), GR_I64: (torch.int64, "<i8", 8)}[self.dtype_code]
+        shape = self.shape
+        if 0 in shape:
+            return torch.empty(shape, dtype=dt[0], device=f"cuda:{self.ctx.device}")
+        self.materialize()
+        ptr, strides = self.data_ptr()
+        view = torch.as_tensor(_DeviceExport(self, ptr, shape, tuple(s * dt[2] for s in strides), dt[1]),
+                               device=f"cuda:{self.ctx.device}")
+        return view.clone() if copy else view
 
     def numpy(self):
-        return self.torch().cpu().numpy()
+        return self.torch(copy=False).cpu().numpy()
 
     def plan(self) -> str:
         need = ctypes.c_size_t()

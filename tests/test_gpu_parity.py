@@ -27,6 +27,20 @@ def env():
     import torch
     from paper_1901_03771_amd import lazy as gr
     ctx = gr.Context()
+    ctx.set_option("interp", 0)   # these tests are about the generated kernels: always wait for the compiler
+    ora.set_threads(min(16, os.cpu_count() or 1))
+    yield gr, ctx, torch
+    ctx.sync()
+    ctx.close()
+
+
+@pytest.fixture(scope="module")
+def env_interp():
+    """A context that sends every map sub-graph through the byte-code interpreter."""
+    import torch
+    from paper_1901_03771_amd import lazy as gr
+    ctx = gr.Context()
+    ctx.set_option("interp", 2)
     ora.set_threads(min(16, os.cpu_count() or 1))
     yield gr, ctx, torch
     ctx.sync()
@@ -529,6 +543,103 @@ def test_allocator_callbacks_and_out_of_memory(env):
     c3.close()
 
 
+# ---- the byte-code interpreter that stands in while a kernel is being compiled ----------------
+
+@pytest.mark.parametrize("name", sorted(ELEMENTWISE_CASES))
+def test_interpreter_elementwise_cases(env, env_interp, name):
+    prog, mk = ELEMENTWISE_CASES[name]
+    arrays = mk()
+    n0 = env_interp[1].stats()["interp_launches"]
+    got, ref = run_both(env_interp, lambda xp, **kw: prog(xp, **kw), arrays)
+    assert env_interp[1].stats()["interp_launches"] > n0, "the interpreter did not run"
+    floor = 4 * ulp_of(np.full(1, 4.0, f32)) if name == "unary_mix" else None
+    assert_elementwise(got, ref, floor=floor, what=name)
+    compiled, _ = run_both(env, lambda xp, **kw: prog(xp, **kw), arrays)
+    assert np.array_equal(got.view(np.uint32), compiled.view(np.uint32)), "interpreter and generated kernel differ in some bit"
+
+
+@pytest.mark.parametrize("name", ["chain", "normalize", "stencil", "blackscholes", "softmax", "logreg"])
+def test_interpreter_small_configurations(env, env_interp, name):
+    arrays = wl.make_inputs(name, **wl.SMALL[name])
+    n0 = env_interp[1].stats()["interp_launches"]
+    got, ref = run_both(env_interp, wl.PROGRAMS[name], arrays)
+    if name in ("softmax", "logreg"):
+        # no map sub-graph in these: reductions and contractions always wait for their kernels
+        assert env_interp[1].stats()["interp_launches"] == n0
+        assert_reduction(got, ref, what=name)
+        return
+    assert env_interp[1].stats()["interp_launches"] > n0
+    floor = chain_floor(arrays) if name == "chain" else None
+    if name == "blackscholes":
+        floor = 4 * ulp_of(np.maximum(arrays["S"], arrays["K"]))
+    assert_elementwise(got, ref, floor=floor, what=name)
+    compiled, _ = run_both(env, wl.PROGRAMS[name], arrays)
+    assert np.array_equal(got.view(np.uint32), compiled.view(np.uint32))
+
+
+def test_interpreter_int32_and_strided_destinations(env_interp):
+    gr, ctx, torch = env_interp
+    g = np.random.default_rng(23)
+    x = g.integers(-2**31, 2**31 - 1, (10, 20), dtype=np.int64).astype(np.int32)
+    y = g.integers(-2**31, 2**31 - 1, (20,), dtype=np.int64).astype(np.int32)
+    got, ref = run_both(env_interp, wl.listing1, dict(x=x, y=y))
+    assert got.dtype == np.int32 and np.array_equal(got, ref)
+    got, ref = run_both(env_interp, lambda xp, x, y: xp.maximum(abs(x), -y) - xp.minimum(x, y) * 3 + x ** 2, dict(x=x, y=y))
+    assert np.array_equal(got, ref)
+    # slice assignment: the interpreter writes through the destination's strides
+    a0, b0 = _rand((40, 60), 75), _rand((40, 60), 76)
+    ta, tb = torch.from_numpy(a0).cuda(), torch.from_numpy(b0).cuda()
+    A, B = ctx.array(ta), ctx.array(tb)
+    A[::2, 1::3] = B[::2, 1::3] * 3.0
+    want = a0.copy()
+    want[::2, 1::3] = b0[::2, 1::3] * f32(3)
+    assert np.array_equal(ta.cpu().numpy(), want)
+    A.T[5:9] = gr.sqrt(abs(B.T[5:9]))
+    want.T[5:9] = np.sqrt(np.abs(b0.T[5:9]))
+    assert np.array_equal(ta.cpu().numpy(), want)
+    grid = np.random.default_rng(77).random((151, 1234)).astype(f32)
+    t = torch.from_numpy(grid).cuda()
+    out = wl.jacobi(gr, ctx.array(t), 3)
+    assert np.array_equal(out.numpy(), wl.jacobi(ora, ora.array(grid), 3).numpy())
+    # an empty result and a rank-6 iteration space
+    assert (ctx.array(torch.zeros((0, 7), device="cuda")) * 2.0).numpy().shape == (0, 7)
+    z = _rand((3, 4, 5, 2, 6, 7), 78)
+    w = _rand((3, 1, 5, 1, 6, 1), 79)
+    got, ref = run_both(env_interp, lambda xp, z, w: xp.transpose(z, (5, 1, 2, 3, 4, 0)) * 2.0 + xp.transpose(w, (5, 1, 2, 3, 4, 0)), dict(z=z, w=w))
+    assert_elementwise(got, ref, what="rank 6")
+
+
+def test_first_request_runs_while_its_kernel_compiles(tmp_path, monkeypatch):
+    # nothing cached in memory or on disk: the first request of a new structure is answered by the
+    # interpreter and leaves a compilation running; once that has finished the kernel takes over
+    import torch
+    from paper_1901_03771_amd import lazy as gr
+    monkeypatch.setenv("GR_CACHE_DIR", str(tmp_path / "empty_cache"))
+    ctx = gr.Context()
+    arrays = wl.make_inputs("normalize", **wl.SMALL["normalize"])
+    ref = wl.normalize(ora, **{k: ora.array(v) for k, v in arrays.items()}).numpy()
+    dev, keep = to_dev(torch, ctx, arrays)
+    first = wl.normalize(gr, **dev).numpy()
+    st = ctx.stats()
+    assert st["interp_launches"] == 1 and st["cache_misses"] == 0 and st["cache_hits"] == 0
+    assert_elementwise(first, ref, what="interpreted first request")
+    ctx.compile_wait()
+    assert ctx.stats()["cache_misses"] == 1
+    second = wl.normalize(gr, **dev).numpy()
+    st = ctx.stats()
+    assert st["interp_launches"] == 1 and st["cache_hits"] == 1
+    assert np.array_equal(first.view(np.uint32), second.view(np.uint32))
+    ctx.close()
+    # a new context finds the code object the first one left on disk: no interpreter, no compiler
+    ctx2 = gr.Context()
+    dev2, keep2 = to_dev(torch, ctx2, arrays)
+    third = wl.normalize(gr, **dev2).numpy()
+    st = ctx2.stats()
+    assert st["disk_hits"] == 1 and st["interp_launches"] == 0 and st["compile_ms"] == 0.0
+    assert np.array_equal(first.view(np.uint32), third.view(np.uint32))
+    ctx2.close()
+
+
 def test_merged_pending_nodes_never_serve_stale_values(env):
     gr, ctx, torch = env
     x = _rand((3000,), 311)
@@ -547,7 +658,8 @@ def test_merged_pending_nodes_never_serve_stale_values(env):
     assert_reduction(np.float32(s3.numpy()), 4.0 * (ora.array(x) * ora.array(x)).sum().numpy(), what="after rewrite")
     # slice assignment evaluates pending readers first; a recording after it sees the new contents
     p1 = gr.cumsum(a, 0)
-    a[0:10] = 1.0
+    ones = torch.ones(10, device="cuda")
+    a[0:10] = ctx.array(ones)
     p2 = gr.cumsum(a, 0)
     assert p1.h != p2.h
     y = 2.0 * x
@@ -567,7 +679,7 @@ def test_index_space_beyond_32_bits(env):
     for k, i in enumerate(special):
         a[i] = 10 + k
     A = ctx.array(a)
-    out = (A * 3 + 1).torch()
+    out = (A * 3 + 1).torch(copy=False)
     assert out.shape[0] == n
     for k, i in enumerate(special):
         assert int(out[i]) == (10 + k) * 3 + 1, i
@@ -577,7 +689,7 @@ def test_index_space_beyond_32_bits(env):
     del out
     total = int(gr.sum(A).numpy())
     assert total == n - len(special) + sum(10 + k for k in range(len(special)))   # exact in int64
-    tail = gr.cumsum(A, 0).torch()[-1]
+    tail = gr.cumsum(A, 0).torch(copy=False)[-1]
     assert int(tail) == total
     del a, A, tail
     torch.cuda.empty_cache()
