@@ -127,6 +127,12 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     background and later requests use the compiled kernel;
  *                     0 = always wait for the compiler; 2 = interpret every map
  *                     sub-graph the interpreter covers (for testing it)
+ *   "assign_swap"     1 (default) = gr_assign of a value that reads the
+ *                     destination's storage at shifted positions (a stencil
+ *                     sweep), into a unit-step box that covers at least 4/5 of
+ *                     an array whose storage the library owns, writes a second
+ *                     buffer, copies the cells outside the box and swaps the
+ *                     two buffers; 0 = always evaluate, then copy
  *   "merge"           1 (default) = a reduction, scan or contraction recorded
  *                     while a node with the same pending expression is still
  *                     waiting to be evaluated returns a handle to that node
@@ -278,6 +284,7 @@ typedef struct {
   uint64_t disk_hits;         /* cache misses served from the on-disk code-object cache */
   uint64_t nodes_merged;      /* recordings answered with an equal pending node (option "merge") */
   uint64_t interp_launches;   /* sub-graphs evaluated by the byte-code interpreter (option "interp") */
+  uint64_t assign_swaps;      /* slice assignments done by writing a second buffer and swapping (option "assign_swap") */
 } gr_stats_t;
 
 gr_status gr_stats(gr_ctx* ctx, gr_stats_t* out);

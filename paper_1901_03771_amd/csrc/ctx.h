@@ -36,6 +36,7 @@ struct gr_ctx {
   int64_t opt_disk_cache = 1;
   int64_t opt_merge = 1;
   int64_t opt_interp = 1;
+  int64_t opt_assign_swap = 1;
 
   // allocator
   void* (*alloc_fn)(size_t, void*) = nullptr;

@@ -679,6 +679,63 @@ static bool reads_range(const Node* n, uintptr_t lo, uintptr_t hi, std::set<cons
   return false;
 }
 
+// Gives a node whose data lives inside another array's storage (the result of a direct slice
+// assignment) a buffer of its own.
+static gr_status unshare(gr_ctx* ctx, gr_array id) {
+  Node* n = lookup(ctx, id);
+  if (!n || !n->cow_alias) return GR_OK;
+  size_t bytes = (size_t)n->count() * itemsize(n->dtype);
+  void* buf = ctx_alloc(ctx, bytes);
+  if (!buf) return fail(ctx, GR_ERR_OOM, "allocator returned NULL");
+  Plan cp;
+  gr_status st = make_plan(ctx, n, &cp);  // a plain strided copy of an array that has data
+  if (st == GR_OK) st = execute_plan(ctx, &cp, n, buf, false);
+  clear_planned(&cp);
+  if (st != GR_OK) { ctx_free(ctx, buf, bytes); return st; }
+  n->data = buf; n->owns_data = true; n->alloc_bytes = bytes; n->offset = 0; n->cow_alias = false;
+  int64_t sstride = 1;
+  for (int k = n->ndim - 1; k >= 0; --k) { n->strides[k] = sstride; sstride *= n->shape[k]; }
+  return GR_OK;
+}
+
+// Copies the box `shape` at element offset `off` (strides `strides`) from `src` to the same
+// place in `dst`.
+static gr_status copy_box(gr_ctx* ctx, gr_dtype dt, int nd, const int64_t* shape, const int64_t* strides, int64_t off, void* src, void* dst) {
+  gr_array h = 0;
+  gr_status st = gr_array_from_device(ctx, (char*)src + off * (int64_t)itemsize(dt), dt, nd, shape, strides, &h);
+  if (st != GR_OK) return st;
+  Node* t = lookup(ctx, h);
+  OutSpec os;
+  os.base = off;
+  for (int k = 0; k < nd; ++k) os.strides[k] = strides[k];
+  Plan wp;
+  wp.out = &os;
+  st = make_plan(ctx, t, &wp);
+  if (st == GR_OK) st = execute_plan(ctx, &wp, t, dst, false);
+  clear_planned(&wp);
+  gr_release(ctx, h);
+  return st;
+}
+
+// Is the destination a unit-step box of a C-contiguous array whose storage the library owns,
+// and is the rest of that array small next to the box?  Then a value that reads the destination's
+// storage at shifted positions (a stencil sweep) can be written into a second buffer, the rest
+// copied over, and the two buffers swapped: half the traffic of "evaluate, then copy".
+static bool swap_candidate(const Node* base, const Node* d, const OutSpec& spec, int64_t* start) {
+  if (!base->owns_data || base->cow_alias || base->offset != 0 || d->ndim != base->ndim) return false;
+  int64_t s = 1, rest = spec.base;
+  for (int k = base->ndim - 1; k >= 0; --k) { if (base->strides[k] != s) return false; s *= base->shape[k]; }
+  for (int k = 0; k < base->ndim; ++k) {
+    if (spec.strides[k] != base->strides[k]) return false;
+    start[k] = rest / base->strides[k];
+    rest -= start[k] * base->strides[k];
+    if (start[k] < 0 || start[k] + d->shape[k] > base->shape[k]) return false;
+  }
+  if (rest != 0) return false;
+  const int64_t box = d->count(), all = base->count();
+  return box > 0 && (all - box) * 4 <= box;
+}
+
 }  // namespace gr
 
 extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
@@ -721,19 +778,8 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
     if (st != GR_OK) return st;
   }
   for (gr_array id : aliases) {
-    Node* n = lookup(ctx, id);
-    if (!n || !n->cow_alias) continue;
-    size_t bytes = (size_t)n->count() * itemsize(n->dtype);
-    void* buf = ctx_alloc(ctx, bytes);
-    if (!buf) return fail(ctx, GR_ERR_OOM, "allocator returned NULL");
-    Plan cp;
-    gr_status st = make_plan(ctx, n, &cp);  // a plain strided copy of an array that has data
-    if (st == GR_OK) st = execute_plan(ctx, &cp, n, buf, false);
-    clear_planned(&cp);
-    if (st != GR_OK) { ctx_free(ctx, buf, bytes); return st; }
-    n->data = buf; n->owns_data = true; n->alloc_bytes = bytes; n->offset = 0; n->cow_alias = false;
-    int64_t sstride = 1;
-    for (int k = n->ndim - 1; k >= 0; --k) { n->strides[k] = sstride; sstride *= n->shape[k]; }
+    gr_status st = unshare(ctx, id);
+    if (st != GR_OK) return st;
   }
   v = lookup(ctx, value);
   if (!v) return fail(ctx, GR_ERR_HANDLE, "assign: value handle vanished");
@@ -764,10 +810,61 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
       }
       // earlier sub-graphs of the plan finish before the last one starts: no hazard there
     }
+    int64_t start[MAXD];
     if (safe) {
       st = execute_plan(ctx, &plan, v, base->data, false);
       clear_planned(&plan);
       if (st != GR_OK) return st;
+      direct = true;
+    } else if (ctx->opt_assign_swap && plan.out_honoured && swap_candidate(base, d, spec, start)) {
+      // 2b. The value reads the destination's storage where it does not write it (a stencil sweep).
+      //     Write it into a second buffer, copy the cells outside the destination, swap the buffers:
+      //     views resolve through the owning node, so they all see the new storage.
+      clear_planned(&plan);
+      Node* b = const_cast<Node*>(base);
+      std::vector<gr_array> inside;
+      for (auto& kv : ctx->nodes)
+        if (kv.second->materialized && kv.second->cow_alias && kv.second->data == b->data) inside.push_back(kv.first);
+      for (gr_array id : inside) {
+        st = unshare(ctx, id);
+        if (st != GR_OK) return st;
+      }
+      v = lookup(ctx, value);
+      if (!v) return fail(ctx, GR_ERR_HANDLE, "assign: value handle vanished");
+      const size_t bytes = (size_t)b->count() * itemsize(b->dtype);
+      void* fresh = ctx_alloc(ctx, bytes);
+      if (!fresh) return fail(ctx, GR_ERR_OOM, "allocator returned NULL");
+      Plan p2;
+      p2.out = &spec;
+      st = make_plan(ctx, v, &p2);
+      if (st == GR_OK && !p2.out_honoured) st = fail(ctx, GR_ERR_UNSUPPORTED, "assign: plan changed between two passes");
+      if (st == GR_OK) st = execute_plan(ctx, &p2, v, fresh, false);
+      clear_planned(&p2);
+      // the cells around the box: per dimension a slab below and a slab above it
+      int64_t shp[MAXD], off = 0;
+      for (int k = 0; k < b->ndim; ++k) shp[k] = b->shape[k];
+      for (int k = 0; st == GR_OK && k < b->ndim; ++k) {
+        const int64_t lo_n = start[k], hi_n = b->shape[k] - (start[k] + d->shape[k]);
+        if (lo_n > 0) { shp[k] = lo_n; st = copy_box(ctx, b->dtype, b->ndim, shp, b->strides, off, b->data, fresh); }
+        if (st == GR_OK && hi_n > 0) {
+          shp[k] = hi_n;
+          st = copy_box(ctx, b->dtype, b->ndim, shp, b->strides, off + (start[k] + d->shape[k]) * b->strides[k], b->data, fresh);
+        }
+        shp[k] = d->shape[k];
+        off += start[k] * b->strides[k];
+      }
+      if (st != GR_OK) {
+        // the value may already be bound to the abandoned buffer: give it a buffer of its own first
+        v = lookup(ctx, value);
+        if (v && v->materialized && v->cow_alias && v->data == fresh) (void)unshare(ctx, value);
+        ctx_free(ctx, fresh, bytes);
+        return st;
+      }
+      void* old = b->data;
+      b->data = fresh;
+      ctx_free(ctx, old, b->alloc_bytes);  // stream order: every reader of the old buffer is already queued
+      b->alloc_bytes = bytes;
+      ctx->stats.assign_swaps++;
       direct = true;
     } else {
       clear_planned(&plan);

@@ -51,7 +51,8 @@ class Stats(ctypes.Structure):
                 ("kernel_launches", ctypes.c_uint64), ("cache_hits", ctypes.c_uint64),
                 ("cache_misses", ctypes.c_uint64), ("compile_ms", ctypes.c_double),
                 ("bytes_allocated", ctypes.c_uint64), ("disk_hits", ctypes.c_uint64),
-                ("nodes_merged", ctypes.c_uint64), ("interp_launches", ctypes.c_uint64)]
+                ("nodes_merged", ctypes.c_uint64), ("interp_launches", ctypes.c_uint64),
+                ("assign_swaps", ctypes.c_uint64)]
 
 
 _lib = None
@@ -308,6 +309,11 @@ class Array:
         st = (ctypes.c_int64 * 8)()
         self.ctx.check(lib().gr_data_ptr(self.ctx._p, self.h, ctypes.byref(p), st))
         return p.value or 0, tuple(int(st[i]) for i in range(self.ndim))
+
+    def copy(self) -> "Array":
+        """An evaluated array with storage of its own (allocated and owned by the library) holding
+        this array's values; multiplying by one is exact for every value."""
+        return (self * 1).materialize()
 
     # -- materialisation --------------------------------------------------------
     def materialize(self) -> "Array":

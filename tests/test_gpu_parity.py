@@ -351,6 +351,54 @@ def test_jacobi_listing6(env):
         assert np.array_equal(t.cpu().numpy(), ref), "the caller's tensor is the grid's storage"
 
 
+def test_jacobi_on_library_owned_storage_swaps_buffers(env):
+    # a sweep reads the destination's storage at shifted positions; when the library owns the grid it
+    # writes a second buffer, copies the border and swaps, instead of evaluating and copying back
+    gr, ctx, torch = env
+    # (shape, sweeps, does the destination cover enough of the grid for the swap to pay)
+    for shape, iters, swaps in [((12, 9), 4, False), ((151, 1234), 3, True), ((40, 50, 60), 2, True)]:
+        g0 = np.random.default_rng(170).random(shape).astype(f32)
+        t = torch.from_numpy(g0).cuda()
+        if len(shape) == 2:
+            prog = wl.jacobi
+        else:
+            def prog(xp, grid, iterations):
+                c = grid[1:-1, 1:-1, 2:-1]
+                for _ in range(iterations):
+                    c[:] = (grid[:-2, 1:-1, 2:-1] + grid[2:, 1:-1, 2:-1] + grid[1:-1, :-2, 2:-1] + grid[1:-1, 2:, 2:-1]
+                            + grid[1:-1, 1:-1, 1:-2] + grid[1:-1, 1:-1, 3:]) / 6.0
+                return grid
+        ref = prog(ora, ora.array(g0), iters).numpy()
+        grid = ctx.array(t).copy()
+        before = ctx.stats()["assign_swaps"]
+        view = grid[1:-1]                         # a view taken before the sweeps follows the swaps
+        out = prog(gr, grid, iters)
+        swapped = ctx.stats()["assign_swaps"] - before
+        assert swapped == (iters if swaps else 0), (shape, swapped)
+        assert np.array_equal(out.numpy(), ref), f"jacobi on owned storage {shape}"
+        assert np.array_equal(view.numpy(), ref[1:-1])
+        assert np.array_equal(t.cpu().numpy(), g0), "the caller's tensor was copied, not adopted"
+        # the same through evaluate-then-copy
+        ctx.set_option("assign_swap", 0)
+        grid2 = ctx.array(t).copy()
+        assert np.array_equal(prog(gr, grid2, iters).numpy(), ref)
+        ctx.set_option("assign_swap", 1)
+    # the value of a sweep, kept by the caller, survives the next swap as an array of its own
+    g0 = np.random.default_rng(171).random((64, 256)).astype(f32)
+    grid = ctx.array(torch.from_numpy(g0).cuda()).copy()
+    c = grid[1:-1, 1:-1]
+    v1 = 0.2 * (c + grid[:-2, 1:-1] + grid[2:, 1:-1] + grid[1:-1, :-2] + grid[1:-1, 2:])
+    c[:] = v1
+    c[:] = 0.2 * (c + grid[:-2, 1:-1] + grid[2:, 1:-1] + grid[1:-1, :-2] + grid[1:-1, 2:])
+    og = ora.array(g0)
+    oc = og[1:-1, 1:-1]
+    ov1 = 0.2 * (oc + og[:-2, 1:-1] + og[2:, 1:-1] + og[1:-1, :-2] + og[1:-1, 2:])
+    oc[:] = ov1
+    oc[:] = 0.2 * (oc + og[:-2, 1:-1] + og[2:, 1:-1] + og[1:-1, :-2] + og[1:-1, 2:])
+    assert np.array_equal(v1.numpy(), ov1.numpy())
+    assert np.array_equal(grid.numpy(), og.numpy())
+
+
 def test_assign_direct_in_place_and_strided_destinations(env):
     gr, ctx, torch = env
     a0 = _rand((40, 60), 71)
