@@ -264,6 +264,7 @@ def main():
         # (the eager model the paper starts from, Section 1)
         uctx = gr.Context(device=0)
         uctx.set_option("fusion", 0)
+        uctx.set_option("interp", 0)
         for oname in ("normalize", "softmax"):
             ow = Workload(oname, uctx, 2)
             d_ms, _ = time_steps(torch, ow, 20, 3)
