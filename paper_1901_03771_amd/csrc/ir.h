@@ -42,6 +42,11 @@ struct Node {
   bool cow_alias = false;  // data lives in another array's storage (result of a direct slice assignment):
                            // gets its own copy before that storage is written again
   size_t alloc_bytes = 0;
+  // Second buffer of an array that stencil sweeps are assigned into (see gr_assign): same size as
+  // `data`; outside the box [shadow_start, shadow_start + shadow_len) it holds the same cells.
+  void* shadow = nullptr;
+  int64_t shadow_start[MAXD] = {0};
+  int64_t shadow_len[MAXD] = {0};
 
   // SCALAR / CONST payload
   double value = 0.0;

@@ -59,6 +59,7 @@ void node_maybe_free(gr_ctx* c, Node* n0) {
     }
     n->in.clear();
     if (n->owns_data && n->data) ctx_free(c, n->data, n->alloc_bytes);
+    if (n->shadow) ctx_free(c, n->shadow, n->alloc_bytes);
     if (n->kind == Kind::REDUCE || n->kind == Kind::DOT || n->kind == Kind::SCAN) forget_pending(c, n);
     c->nodes.erase(n->id);
     c->stats.nodes_alive--;

@@ -568,6 +568,7 @@ gr_status gr_ctx_destroy(gr_ctx* ctx) {
   for (auto& kv : ctx->nodes) all.push_back(kv.second);
   for (Node* n : all) {
     if (n->owns_data && n->data) ctx_free(ctx, n->data, n->alloc_bytes);
+    if (n->shadow) ctx_free(ctx, n->shadow, n->alloc_bytes);
     delete n;
   }
   ctx->nodes.clear();
@@ -717,6 +718,13 @@ static gr_status copy_box(gr_ctx* ctx, gr_dtype dt, int nd, const int64_t* shape
   return st;
 }
 
+// The second buffer of `b` stops mirroring it as soon as `b` is written in any other way.
+static void drop_shadow(gr_ctx* ctx, Node* b) {
+  if (!b->shadow) return;
+  ctx_free(ctx, b->shadow, b->alloc_bytes);
+  b->shadow = nullptr;
+}
+
 // Is the destination a unit-step box of a C-contiguous array whose storage the library owns,
 // and is the rest of that array small next to the box?  Then a value that reads the destination's
 // storage at shifted positions (a stencil sweep) can be written into a second buffer, the rest
@@ -812,6 +820,7 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
     }
     int64_t start[MAXD];
     if (safe) {
+      drop_shadow(ctx, const_cast<Node*>(base));
       st = execute_plan(ctx, &plan, v, base->data, false);
       clear_planned(&plan);
       if (st != GR_OK) return st;
@@ -832,8 +841,14 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
       v = lookup(ctx, value);
       if (!v) return fail(ctx, GR_ERR_HANDLE, "assign: value handle vanished");
       const size_t bytes = (size_t)b->count() * itemsize(b->dtype);
-      void* fresh = ctx_alloc(ctx, bytes);
+      // the buffer this array was swapped out of by the last sweep over the same box already holds
+      // the cells outside the box: nothing to copy
+      bool mirrored = b->shadow != nullptr && bytes == b->alloc_bytes;
+      for (int k = 0; mirrored && k < b->ndim; ++k) mirrored = b->shadow_start[k] == start[k] && b->shadow_len[k] == d->shape[k];
+      if (!mirrored) drop_shadow(ctx, b);
+      void* fresh = mirrored ? b->shadow : ctx_alloc(ctx, bytes);
       if (!fresh) return fail(ctx, GR_ERR_OOM, "allocator returned NULL");
+      b->shadow = nullptr;
       Plan p2;
       p2.out = &spec;
       st = make_plan(ctx, v, &p2);
@@ -843,7 +858,7 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
       // the cells around the box: per dimension a slab below and a slab above it
       int64_t shp[MAXD], off = 0;
       for (int k = 0; k < b->ndim; ++k) shp[k] = b->shape[k];
-      for (int k = 0; st == GR_OK && k < b->ndim; ++k) {
+      for (int k = 0; st == GR_OK && !mirrored && k < b->ndim; ++k) {
         const int64_t lo_n = start[k], hi_n = b->shape[k] - (start[k] + d->shape[k]);
         if (lo_n > 0) { shp[k] = lo_n; st = copy_box(ctx, b->dtype, b->ndim, shp, b->strides, off, b->data, fresh); }
         if (st == GR_OK && hi_n > 0) {
@@ -860,10 +875,10 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
         ctx_free(ctx, fresh, bytes);
         return st;
       }
-      void* old = b->data;
+      // the old buffer becomes the mirror: outside the box it equals the new one
+      b->shadow = b->data;
       b->data = fresh;
-      ctx_free(ctx, old, b->alloc_bytes);  // stream order: every reader of the old buffer is already queued
-      b->alloc_bytes = bytes;
+      for (int k = 0; k < b->ndim; ++k) { b->shadow_start[k] = start[k]; b->shadow_len[k] = d->shape[k]; }
       ctx->stats.assign_swaps++;
       direct = true;
     } else {
@@ -873,6 +888,7 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
   if (direct) return GR_OK;
 
   // 3. General case (NumPy's own cost model): finish the value in its own buffer, then copy.
+  drop_shadow(ctx, const_cast<Node*>(base));
   if (!value_has_data) {
     gr_status st = gr_materialize(ctx, value);
     if (st != GR_OK) return st;

@@ -397,6 +397,17 @@ def test_jacobi_on_library_owned_storage_swaps_buffers(env):
     oc[:] = 0.2 * (oc + og[:-2, 1:-1] + og[2:, 1:-1] + og[1:-1, :-2] + og[1:-1, 2:])
     assert np.array_equal(v1.numpy(), ov1.numpy())
     assert np.array_equal(grid.numpy(), og.numpy())
+    # the buffer swapped out by one sweep is reused by the next without copying the border again;
+    # any other write to the grid in between (here: a new top row) must not be lost
+    top = _rand((1, 256), 172)
+    sweep = lambda xp, g_: 0.2 * (g_[1:-1, 1:-1] + g_[:-2, 1:-1] + g_[2:, 1:-1] + g_[1:-1, :-2] + g_[1:-1, 2:])
+    for step in range(4):
+        if step == 2:
+            grid[0:1] = ctx.array(torch.from_numpy(top).cuda())
+            og[0:1] = ora.array(top)
+        grid[1:-1, 1:-1] = sweep(gr, grid)
+        og[1:-1, 1:-1] = sweep(ora, og)
+        assert np.array_equal(grid.numpy(), og.numpy()), f"sweep {step}"
 
 
 def test_assign_direct_in_place_and_strided_destinations(env):
