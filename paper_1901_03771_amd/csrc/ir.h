@@ -71,6 +71,13 @@ struct Node {
   bool has_data() const { return materialized || planned; }
 };
 
+// Node containers are ordered by node id (recording order), never by address: plans must not
+// depend on where the allocator happened to put a node.
+struct NodeIdLess {
+  bool operator()(const Node* a, const Node* b) const { return a->id < b->id; }
+};
+using NodeSet = std::set<const Node*, NodeIdLess>;
+
 inline size_t itemsize(gr_dtype dt) { return dt == GR_I64 ? 8 : 4; }
 
 // ---- plan --------------------------------------------------------------------
@@ -150,7 +157,7 @@ struct GroupPlan {
 
   // MAP: single-point program (boundary tiles, cache key); `prog` holds the per-lane patch
   // program and is only built when a kernel has to be generated
-  std::set<const Node*> owned;
+  NodeSet owned;
   std::vector<Instr> prog1;
   int result1 = -1;
 

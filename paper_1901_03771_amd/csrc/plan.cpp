@@ -72,7 +72,7 @@ struct Invalid {
 // Builds the SSA program of one sub-graph.
 struct Builder {
   GroupPlan* g;
-  const std::set<const Node*>* owned;  // lazy nodes this sub-graph computes
+  const NodeSet* owned;  // lazy nodes this sub-graph computes
   int rank = 0;                        // iteration rank (original dims)
   const int64_t* dims = nullptr;
   std::vector<Instr>* prog = nullptr;
@@ -80,10 +80,10 @@ struct Builder {
   std::map<std::pair<uint64_t, std::vector<int64_t>>, int> memo;
   std::map<std::vector<int64_t>, int> load_ids;   // (group, delta...) -> instr
   std::map<std::vector<int64_t>, int> value_ids;  // (kind, op, dtype, a, b) -> instr
-  std::map<const Node*, int> phase_of;
+  std::map<const Node*, int, NodeIdLess> phase_of;
   const Node* dot_core = nullptr;
   std::vector<Invalid> invalid;
-  std::set<const Node*> leaves_seen, members_seen;
+  NodeSet leaves_seen, members_seen;
 
   static std::vector<int64_t> flatten(const IndexMap& m) {
     std::vector<int64_t> v;
@@ -448,8 +448,8 @@ struct Planner {
   Node* root;
   const OutSpec* out = nullptr;
   std::vector<Node*> sub;                 // lazy nodes of the visited sub-DAG, ascending id
-  std::set<const Node*> cuts;
-  std::map<const Node*, const Node*> owner;
+  NodeSet cuts;
+  std::map<const Node*, const Node*, NodeIdLess> owner;
 
   void collect() {
     std::set<Node*> seen;
@@ -493,7 +493,7 @@ struct Planner {
     for (Node* r : sub) {
       if (!cuts.count(r)) continue;
       std::vector<const Node*> work;
-      std::set<const Node*> seen;
+      NodeSet seen;
       for (Node* p : r->in) work.push_back(p);
       owner[r] = r;
       while (!work.empty()) {
@@ -512,8 +512,8 @@ struct Planner {
     return true;
   }
 
-  std::set<const Node*> owned_by(const Node* r) const {
-    std::set<const Node*> s;
+  NodeSet owned_by(const Node* r) const {
+    NodeSet s;
     for (const auto& kv : owner) if (kv.second == r) s.insert(kv.first);
     return s;
   }
@@ -551,7 +551,7 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
 // ---------------------------------------------------------------------------
 
 static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std::vector<Invalid>* invalid) {
-  std::set<const Node*> owned = pl.owned_by(r);
+  NodeSet owned = pl.owned_by(r);
   g->root = r;
   g->out_dtype = r->dtype;
   g->nt = (int)c->opt_nontemporal;
@@ -821,7 +821,9 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     } else {
       // ---- row-resident reductions fused with producers and consumers -----
       g->kind = GroupKind::ROWRED;
-      const Node* x = reds[0]->in[0];
+      // the reduction recorded last (nearest to the root, possibly the root itself) fixes the row
+      // space; reductions over any other space become sub-graphs of their own
+      const Node* x = reds.back()->in[0];
       for (const Node* n : reds) {
         const Node* xo = n->in[0];
         bool same = xo->ndim == x->ndim;

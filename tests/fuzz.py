@@ -1,0 +1,240 @@
+"""Seeded random array programs for differential tests.
+
+A recipe is a list of steps over a pool of arrays: exactly rounded pointwise
+ops (+ - * / neg abs square sqrt maximum minimum) with NumPy broadcasting and
+Python scalars, slices with steps, transpositions, max/min reductions over
+random axes, running max/min, and - for int32 programs - wrap-around sums and
+prefix sums.  Every op in a recipe rounds once (or not at all), so any two
+correct evaluators agree bit for bit, whatever they fuse: the GPU library is
+compared with the CPU evaluator exactly, and the CPU evaluator with NumPy.
+
+Shapes are tracked here by hand-written NumPy rules (no array library is
+called while a recipe is built); `apply` runs a recipe on any array module
+with NumPy's names.
+"""
+from __future__ import annotations
+
+import random
+
+import numpy as np
+
+DIMS = [1, 1, 2, 3, 5, 7, 16, 33, 64, 130]
+
+
+def _broadcast(a, b):
+    n = max(len(a), len(b))
+    a2, b2 = (1,) * (n - len(a)) + tuple(a), (1,) * (n - len(b)) + tuple(b)
+    out = []
+    for x, y in zip(a2, b2):
+        if x != y and x != 1 and y != 1:
+            return None
+        out.append(max(x, y))
+    return tuple(out)
+
+
+def make_recipe(seed: int, max_steps: int = 10):
+    """Returns (dtype, leaf_shapes, steps, result_index); steps are tuples whose first entry names the op."""
+    r = random.Random(seed)
+    dtype = "i32" if r.random() < 0.3 else "f32"
+    nleaf = r.randint(1, 3)
+    rank = r.randint(1, 4)
+    base = [r.choice(DIMS) for _ in range(rank)]
+    while int(np.prod(base)) > 60000:
+        base[r.randrange(rank)] = r.choice(DIMS[:6])
+    leaf_shapes = [tuple(base)]
+    for _ in range(nleaf - 1):
+        # a broadcast-compatible partner: trailing dims of the base, some replaced by 1
+        k = r.randint(0, rank)
+        s = [d if r.random() < 0.7 else 1 for d in base[rank - k:]] if k else []
+        leaf_shapes.append(tuple(s) if s else (1,))
+    shapes = list(leaf_shapes)      # pool shapes
+    final = [False] * len(shapes)   # i64 results cannot feed further ops
+    steps = []
+
+    def pick(pred=lambda i: True):
+        c = [i for i in range(len(shapes)) if not final[i] and pred(i)]
+        return r.choice(c) if c else None
+
+    nsteps = r.randint(3, max_steps)
+    for _ in range(nsteps):
+        kind = r.choices(["unary", "binary", "scalar", "slice", "transpose", "reduce", "scan", "materialize"],
+                         weights=[3, 6, 3, 3, 2, 2, 1, 1])[0]
+        a = pick()
+        if a is None:
+            break
+        sa = shapes[a]
+        if len(sa) == 0 and kind in ("slice", "transpose", "reduce", "scan"):
+            kind = "unary"
+        if kind == "unary":
+            op = r.choice(["neg", "abs", "square"] + (["sqrtabs"] if dtype == "f32" else []))
+            steps.append(("unary", op, a))
+            shapes.append(sa)
+        elif kind == "binary":
+            b = pick(lambda i: _broadcast(shapes[i], sa) is not None)
+            op = r.choice(["add", "sub", "mul", "maximum", "minimum"] + (["divsafe"] if dtype == "f32" else []))
+            steps.append(("binary", op, a, b))
+            shapes.append(_broadcast(sa, shapes[b]))
+        elif kind == "scalar":
+            op = r.choice(["add", "sub", "mul", "maximum", "minimum"])
+            v = r.choice([-3, -1, 0, 2, 7]) if dtype == "i32" or r.random() < 0.3 else r.choice([-1.5, 0.25, 0.1, 3.0])
+            steps.append(("scalar", op, a, v, r.random() < 0.5))
+            shapes.append(sa)
+        elif kind == "slice":
+            key, out = [], []
+            for d in sa:
+                if d == 1 or r.random() < 0.3:
+                    key.append((None, None, None))
+                    out.append(d)
+                    continue
+                lo = r.randint(0, d - 1)
+                hi = r.randint(lo + 1, d)
+                st = r.choice([1, 1, 2, 3])
+                neg = r.random() < 0.3                      # negative indices address from the end
+                key.append((lo - d if neg else lo, hi - d if (neg and hi < d) else hi, st))
+                out.append((hi - lo + st - 1) // st)
+            steps.append(("slice", a, tuple(key)))
+            shapes.append(tuple(out))
+        elif kind == "transpose":
+            perm = list(range(len(sa)))
+            r.shuffle(perm)
+            steps.append(("transpose", a, tuple(perm)))
+            shapes.append(tuple(sa[p] for p in perm))
+        elif kind == "reduce":
+            ops = ["max", "min"] + (["sum"] if dtype == "i32" else [])
+            op = r.choice(ops)
+            naxes = r.randint(0, len(sa))                  # 0: all axes (axis=None)
+            axes = tuple(sorted(r.sample(range(len(sa)), naxes))) if naxes else None
+            keep = r.random() < 0.5
+            red = set(range(len(sa))) if axes is None else set(axes)
+            out = tuple((1 if i in red else d) for i, d in enumerate(sa) if keep or i not in red)
+            steps.append(("reduce", op, a, axes, keep))
+            shapes.append(out)
+            if op == "sum":
+                final.append(True)
+                continue
+        elif kind == "scan":
+            op = r.choice(["cummax", "cummin"] + (["cumsum"] if dtype == "i32" else []))
+            steps.append(("scan", op, a, r.randrange(len(sa))))
+            shapes.append(sa)
+            if op == "cumsum":
+                final.append(True)
+                continue
+        else:
+            steps.append(("materialize", a))
+            continue
+        final.append(False)
+    if not steps or steps[-1][0] == "materialize":
+        steps.append(("unary", "neg", 0))
+        shapes.append(shapes[0])
+        final.append(False)
+    return dtype, leaf_shapes, steps, len(shapes) - 1
+
+
+def make_leaves(seed: int, dtype: str, leaf_shapes):
+    g = np.random.default_rng(1000003 * seed + 17)
+    out = []
+    for s in leaf_shapes:
+        if dtype == "i32":
+            # mostly small values (products stay meaningful), a few extreme ones (wrap-around)
+            x = g.integers(-50, 50, s).astype(np.int32)
+            m = g.random(s) < 0.02
+            x[m] = g.integers(-2**31, 2**31 - 1, s, dtype=np.int64).astype(np.int32)[m]
+        else:
+            x = g.uniform(-2.0, 2.0, s).astype(np.float32)
+            x[g.random(s) < 0.02] = 0.0
+        out.append(x)
+    return out
+
+
+def apply(xp, steps, leaves):
+    """Runs the recipe on arrays of module `xp` (NumPy's names); returns the pool."""
+    pool = list(leaves)
+    for st in steps:
+        k = st[0]
+        if k == "unary":
+            x = pool[st[2]]
+            pool.append({"neg": lambda: -x, "abs": lambda: abs(x), "square": lambda: xp.square(x),
+                         "sqrtabs": lambda: xp.sqrt(abs(x))}[st[1]]())
+        elif k == "binary":
+            x, y = pool[st[2]], pool[st[3]]
+            pool.append({"add": lambda: x + y, "sub": lambda: x - y, "mul": lambda: x * y,
+                         "maximum": lambda: xp.maximum(x, y), "minimum": lambda: xp.minimum(x, y),
+                         "divsafe": lambda: x / (abs(y) + 1.0)}[st[1]]())
+        elif k == "scalar":
+            x, v, left = pool[st[2]], st[3], st[4]
+            if st[1] in ("maximum", "minimum"):
+                f = getattr(xp, st[1])
+                pool.append(f(v, x) if left else f(x, v))
+            else:
+                pool.append({"add": (lambda: v + x) if left else (lambda: x + v), "sub": (lambda: v - x) if left else (lambda: x - v),
+                             "mul": (lambda: v * x) if left else (lambda: x * v)}[st[1]]())
+        elif k == "slice":
+            pool.append(pool[st[1]][tuple(slice(*t) for t in st[2])])
+        elif k == "transpose":
+            pool.append(xp.transpose(pool[st[1]], st[2]))
+        elif k == "reduce":
+            pool.append(getattr(xp, st[1])(pool[st[2]], axis=st[3], keepdims=st[4]))
+        elif k == "scan":
+            pool.append(getattr(xp, st[1])(pool[st[2]], st[3]))
+        elif k == "materialize":
+            if hasattr(pool[st[1]], "materialize"):
+                pool[st[1]].materialize()
+    return pool
+
+
+class NumpyModule:
+    """NumPy under the names the recipes use; scalars keep the array's element type (the rule of
+    both evaluators: a Python scalar never promotes an array)."""
+    square = staticmethod(np.square)
+    sqrt = staticmethod(np.sqrt)
+    transpose = staticmethod(np.transpose)
+
+    @staticmethod
+    def maximum(a, b):
+        a, b = NumpyModule._pair(a, b)
+        return np.maximum(a, b)
+
+    @staticmethod
+    def minimum(a, b):
+        a, b = NumpyModule._pair(a, b)
+        return np.minimum(a, b)
+
+    @staticmethod
+    def _pair(a, b):
+        if isinstance(a, (int, float)):
+            a = b.dtype.type(a)
+        if isinstance(b, (int, float)):
+            b = a.dtype.type(b)
+        return a, b
+
+    @staticmethod
+    def max(a, axis=None, keepdims=False): return np.max(a, axis=axis, keepdims=keepdims)
+    @staticmethod
+    def min(a, axis=None, keepdims=False): return np.min(a, axis=axis, keepdims=keepdims)
+    @staticmethod
+    def sum(a, axis=None, keepdims=False): return np.sum(a, axis=axis, keepdims=keepdims, dtype=np.int64)
+    @staticmethod
+    def cummax(a, axis): return np.maximum.accumulate(a, axis=axis)
+    @staticmethod
+    def cummin(a, axis): return np.minimum.accumulate(a, axis=axis)
+    @staticmethod
+    def cumsum(a, axis): return np.cumsum(a, axis=axis, dtype=np.int64)
+
+
+def same_bits(got: np.ndarray, ref: np.ndarray, zero_signs: bool = True) -> bool:
+    """Equal shape, element type and bit patterns; NaNs compare equal whatever their payload.
+    zero_signs=False also lets +0 and -0 compare equal (which of two equal operands a maximum or
+    minimum returns is not fixed by NumPy's documentation; none of the recipe's ops turns a
+    difference in the sign of a zero into anything but a difference in the sign of a zero)."""
+    got, ref = np.asarray(got), np.asarray(ref)
+    if got.shape != ref.shape or got.dtype != ref.dtype:
+        return False
+    if got.dtype == np.float32:
+        nan = np.isnan(ref)
+        if not np.array_equal(np.isnan(got), nan):
+            return False
+        g, r = got.view(np.uint32)[~nan], ref.view(np.uint32)[~nan]
+        if not zero_signs:
+            g, r = np.where(g == 0x80000000, 0, g), np.where(r == 0x80000000, 0, r)
+        return bool(np.array_equal(g, r))
+    return bool(np.array_equal(got, ref))

@@ -602,6 +602,32 @@ def test_allocator_callbacks_and_out_of_memory(env):
     c3.close()
 
 
+# ---- random programs: bit-exact against the oracle --------------------------------------------
+
+def _run_fuzz_seed(envx, seed):
+    import fuzz
+    gr, ctx, torch = envx
+    dtype, shapes, steps, res = fuzz.make_recipe(seed)
+    leaves = fuzz.make_leaves(seed, dtype, shapes)
+    ref = fuzz.apply(ora, steps, [ora.array(x) for x in leaves])[res].numpy()
+    keep = [torch.from_numpy(x).cuda() for x in leaves]
+    got = fuzz.apply(gr, steps, [ctx.array(t) for t in keep])[res].numpy()
+    assert fuzz.same_bits(got, ref), f"seed {seed}: {dtype} {shapes} {steps}"
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_programs_bit_exact_generated_kernels(env, block):
+    # exactly rounded ops only, so fusion must not change a single bit (tests/fuzz.py)
+    for seed in range(10 * block, 10 * block + 10):
+        _run_fuzz_seed(env, seed)
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_programs_bit_exact_interpreter(env_interp, block):
+    for seed in range(1000 + 40 * block, 1000 + 40 * block + 40):
+        _run_fuzz_seed(env_interp, seed)
+
+
 # ---- the byte-code interpreter that stands in while a kernel is being compiled ----------------
 
 @pytest.mark.parametrize("name", sorted(ELEMENTWISE_CASES))

@@ -282,6 +282,34 @@ def test_merged_nodes_do_not_leak(ctx):
     assert ctx.stats()["nodes_alive"] == base
 
 
+def test_random_programs_partition_into_valid_subgraph_lists(ctx):
+    # 400 seeded random programs (tests/fuzz.py): each partitions, every recorded node that the result
+    # needs is computed by exactly one sub-graph, and sub-graphs only read leaves or earlier roots
+    import fuzz
+    kinds = set()
+    for seed in range(400):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed)
+        leaves = [ctx.spec(s_, gr.GR_I32 if dtype == "i32" else gr.GR_F32) for s_ in shapes]
+        pool = fuzz.apply(gr, [st for st in steps if st[0] != "materialize"], leaves)
+        lines = pool[res].plan().strip().splitlines()
+        assert lines, seed
+        seen_members, roots = set(), set()
+        leaf_ids = {x.h for x in leaves}
+        for line in lines:
+            kinds.add(line.split()[1])
+            members = [int(m.split(":")[0]) for m in re.search(r"members=\[(.*?)\]", line).group(1).split(",") if m]
+            reads = [int(m) for m in re.search(r"leaves=\[(.*?)\]", line).group(1).split(",") if m]
+            root = int(re.search(r"root=(\d+)", line).group(1))
+            assert not (set(members) & seen_members), (seed, "a node is computed twice")
+            assert all(x in leaf_ids or x in roots for x in reads), (seed, "reads something that is neither a leaf nor an earlier root")
+            seen_members |= set(members)
+            roots.add(root)
+        assert pool[res].h in roots or pool[res].h in leaf_ids or not seen_members
+        for a in pool:
+            del a
+    assert {"MAP", "REDUCE", "ROWRED", "SCAN"} <= kinds
+
+
 def test_leaves_and_only_leaves_are_materialised(ctx):
     a = ctx.spec((33, 65))
     out = (a.T @ (a @ ctx.spec((65,)))) * 2.0

@@ -661,3 +661,25 @@ def test_threads_do_not_change_results():
     finally:
         ora.set_threads(1)
     assert np.array_equal(one, four)
+
+
+# ---- random programs against NumPy ---------------------------------------------------------
+
+def test_random_programs_match_numpy_bit_for_bit():
+    # every op of a recipe rounds once, so the evaluator and NumPy (a library routine per op, the
+    # special case the evaluator reduces to) must agree in every bit of every intermediate;
+    # only the sign of a zero returned by maximum/minimum on equal operands is left open
+    import warnings
+    import fuzz
+    checked = 0
+    with warnings.catch_warnings():
+        warnings.simplefilter("ignore")          # NumPy warns about float overflow; inf is the expected value
+        for seed in range(400):
+            dtype, shapes, steps, res = fuzz.make_recipe(seed)
+            leaves = fuzz.make_leaves(seed, dtype, shapes)
+            ref = fuzz.apply(fuzz.NumpyModule, steps, leaves)
+            got = fuzz.apply(ora, steps, [ora.array(x) for x in leaves])
+            for i, (g, r) in enumerate(zip(got, ref)):
+                assert fuzz.same_bits(g.numpy(), r, zero_signs=False), (seed, i, steps)
+                checked += 1
+    assert checked > 2000
