@@ -214,7 +214,9 @@ gr_status gr_materialize(gr_ctx* ctx, gr_array a);
 /* Computes `a` into the caller's C-contiguous device buffer of `bytes` bytes
  * (must equal count * itemsize).  The buffer must not overlap any leaf the
  * request reads (GR_ERR_ALIAS) and stays owned by the caller, who keeps it
- * alive while the node or anything recorded on top of it is in use. */
+ * alive while the node or anything recorded on top of it is in use.  An array
+ * that already has data, or a view of one, is copied: it keeps its own storage
+ * (a view stays a view of its base) and no reference to `dptr` is kept. */
 gr_status gr_materialize_into(gr_ctx* ctx, gr_array a, void* dptr, size_t bytes);
 
 /* Slice assignment dst[...] = value with NumPy semantics (Listing 6 of the

@@ -433,6 +433,15 @@ static void extent_of(const Node* n, uintptr_t* lo, uintptr_t* hi) {
   *hi = (uintptr_t)n->data + (mx + 1) * itemsize(n->dtype);
 }
 
+// Materialised, or a chain of views that ends at a materialised array.
+static bool has_storage(const Node* n) {
+  while (!n->materialized) {
+    if (!n->is_view()) return false;
+    n = n->in[0];
+  }
+  return true;
+}
+
 gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool check_alias) {
   if (c->device < 0) return fail(c, GR_ERR_NODEVICE, "context has no device");
   if (user_out && check_alias) {
@@ -499,7 +508,9 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
     c->stats.groups_executed += g.pair ? 2 : 1;
     for (int q = 0; q < 2 && roots[q]; ++q) {
       Node* r = roots[q];
-      if (r->materialized) continue;  // a plain copy of an array that already had data
+      // a plain copy of an array that already had data (or of a view of one: a view stays a view
+      // of its base, it is never bound to the buffer its elements were copied to)
+      if (has_storage(r)) continue;
       // the node now has data and stays materialised (Section 2)
       r->data = outs[q];
       r->owns_data = own[q];
@@ -522,7 +533,7 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
   // (topological) order: dropping a root's inputs can only free nodes upstream of it, which
   // includes earlier roots that nothing else refers to, never a root still to be visited.
   for (auto& gp : plan->groups) {
-    drop_inputs(c, gp->root);
+    if (gp->root->materialized) drop_inputs(c, gp->root);  // (a view keeps its base)
     if (gp->pair) drop_inputs(c, gp->pair->root);
   }
   return GR_OK;

@@ -32,8 +32,10 @@ def _broadcast(a, b):
     return tuple(out)
 
 
-def make_recipe(seed: int, max_steps: int = 10):
-    """Returns (dtype, leaf_shapes, steps, result_index); steps are tuples whose first entry names the op."""
+def make_recipe(seed: int, max_steps: int = 10, assign: bool = False):
+    """Returns (dtype, leaf_shapes, steps, result_index); steps are tuples whose first entry names the op.
+    assign=True adds slice assignments into leaves and views of leaves (values: an array of the same
+    shape, an expression of the destination itself, or a shifted and possibly overlapping view)."""
     r = random.Random(seed)
     dtype = "i32" if r.random() < 0.3 else "f32"
     nleaf = r.randint(1, 3)
@@ -49,6 +51,7 @@ def make_recipe(seed: int, max_steps: int = 10):
         leaf_shapes.append(tuple(s) if s else (1,))
     shapes = list(leaf_shapes)      # pool shapes
     final = [False] * len(shapes)   # i64 results cannot feed further ops
+    storage = [True] * len(shapes)  # leaves and views of leaves: valid destinations of an assignment
     steps = []
 
     def pick(pred=lambda i: True):
@@ -57,8 +60,25 @@ def make_recipe(seed: int, max_steps: int = 10):
 
     nsteps = r.randint(3, max_steps)
     for _ in range(nsteps):
-        kind = r.choices(["unary", "binary", "scalar", "slice", "transpose", "reduce", "scan", "materialize"],
-                         weights=[3, 6, 3, 3, 2, 2, 1, 1])[0]
+        kind = r.choices(["unary", "binary", "scalar", "slice", "transpose", "reduce", "scan", "materialize", "assign"],
+                         weights=[3, 6, 3, 3, 2, 2, 1, 1, 3 if assign else 0])[0]
+        if kind == "assign":
+            t = r.choice([i for i in range(len(shapes)) if storage[i]])
+            st_ = shapes[t]
+            key, key2, out = [], [], []
+            for d in st_:
+                n = r.randint(1, d)                       # extent of the destination along this dimension
+                step = r.choice([1, 1, 2]) if (n - 1) * 2 < d else 1
+                span = (n - 1) * step + 1
+                lo = r.randint(0, d - span)
+                lo2 = r.randint(0, d - span)
+                key.append((lo, lo + span, step))
+                key2.append((lo2, lo2 + span, step))
+                out.append(n)
+            same = [i for i in range(len(shapes)) if not final[i] and shapes[i] == tuple(out)]
+            mode = r.choice(["self", "shift", "shiftexpr"] + (["pool"] * 2 if same else []))
+            steps.append(("assign", t, tuple(key), mode, r.choice(same) if mode == "pool" else tuple(key2)))
+            continue
         a = pick()
         if a is None:
             break
@@ -111,6 +131,7 @@ def make_recipe(seed: int, max_steps: int = 10):
             shapes.append(out)
             if op == "sum":
                 final.append(True)
+                storage.append(False)
                 continue
         elif kind == "scan":
             op = r.choice(["cummax", "cummin"] + (["cumsum"] if dtype == "i32" else []))
@@ -118,11 +139,14 @@ def make_recipe(seed: int, max_steps: int = 10):
             shapes.append(sa)
             if op == "cumsum":
                 final.append(True)
+                storage.append(False)
                 continue
         else:
             steps.append(("materialize", a))
             continue
         final.append(False)
+        while len(storage) < len(shapes):
+            storage.append(kind in ("slice", "transpose") and storage[a])
     if not steps or steps[-1][0] == "materialize":
         steps.append(("unary", "neg", 0))
         shapes.append(shapes[0])
@@ -179,6 +203,18 @@ def apply(xp, steps, leaves):
         elif k == "materialize":
             if hasattr(pool[st[1]], "materialize"):
                 pool[st[1]].materialize()
+        elif k == "assign":
+            key = tuple(slice(*t) for t in st[2])
+            dst = pool[st[1]]
+            if st[3] == "pool":
+                val = pool[st[4]]
+            elif st[3] == "self":
+                val = dst[key] * 2 - 1
+            else:
+                val = dst[tuple(slice(*t) for t in st[4])]
+                if st[3] == "shiftexpr":
+                    val = val + 1
+            dst[key] = val
     return pool
 
 
