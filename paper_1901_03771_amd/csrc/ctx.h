@@ -106,7 +106,7 @@ std::string kernel_name(const GroupPlan& g);
 
 // runtime.cpp
 gr_status prepare_group(gr_ctx* c, GroupPlan& g);
-gr_status collect_all_jobs(gr_ctx* c);
+gr_status collect_all_jobs(gr_ctx* c, bool load);
 gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out);
 gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr, void* pair_out_ptr);
 gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool check_alias);

@@ -182,6 +182,8 @@ static gr_status finish_kernel(gr_ctx* c, const std::string& sig, const std::str
 // hit, a module load on a disk hit, otherwise a hipRTC job on a host thread.  Calling this for
 // every sub-graph of a request before running the first one overlaps compilation with
 // execution (the paper names JIT time as its main bottleneck and pipelining as the remedy).
+static void bound_pending(gr_ctx* c);
+
 gr_status prepare_group(gr_ctx* c, GroupPlan& g) {
   if (c->cache.count(g.signature) || c->pending.count(g.signature)) return GR_OK;
   std::vector<char> code;
@@ -195,6 +197,7 @@ gr_status prepare_group(gr_ctx* c, GroupPlan& g) {
   }
   gr_status est = expand_patch(c, &g);
   if (est != GR_OK) return est;
+  bound_pending(c);
   auto job = std::make_shared<gr_ctx::CompileJob>();
   job->src = generate_source(g);
   kernel_entry_points(g, &job->kernel, &job->combine, &job->scan);
@@ -206,8 +209,8 @@ gr_status prepare_group(gr_ctx* c, GroupPlan& g) {
 }
 
 // Waits for the compilation job of `sig` (or, when deferred, runs it), stores the code object
-// on disk and publishes the kernel.
-static gr_status collect_job(gr_ctx* c, const std::string& sig, gr_ctx::Kernel** out) {
+// on disk and, unless `load` is false (context teardown), publishes the kernel.
+static gr_status collect_job(gr_ctx* c, const std::string& sig, gr_ctx::Kernel** out, bool load = true) {
   auto pit = c->pending.find(sig);
   if (pit == c->pending.end()) return fail(c, GR_ERR_COMPILE, "no compilation job for this sub-graph");
   pit->second.second.get();
@@ -220,19 +223,35 @@ static gr_status collect_job(gr_ctx* c, const std::string& sig, gr_ctx::Kernel**
     return fail(c, GR_ERR_COMPILE, "hipRTC: " + job->log);
   }
   disk_store(disk_path(c, sig), sig, job->code);
+  if (!load) return GR_OK;
   return finish_kernel(c, sig, job->kernel, job->combine, job->scan, std::move(job->code), out);
 }
 
-gr_status collect_all_jobs(gr_ctx* c) {
+gr_status collect_all_jobs(gr_ctx* c, bool load) {
   gr_status first = GR_OK;
   std::string first_err;
   while (!c->pending.empty()) {
     std::string sig = c->pending.begin()->first;
-    gr_status st = collect_job(c, sig, nullptr);
+    gr_status st = collect_job(c, sig, nullptr, load);
     if (st != GR_OK && first == GR_OK) { first = st; first_err = c->err; }
   }
   if (first != GR_OK) c->err = first_err;
   return first;
+}
+
+// Keeps the number of compilations in flight bounded: finished ones are collected, and beyond
+// the bound the caller waits for one of them (each job occupies a host thread).
+static void bound_pending(gr_ctx* c) {
+  const size_t limit = 16;
+  if (c->pending.size() < limit) return;
+  std::vector<std::string> ready;
+  for (auto& kv : c->pending)
+    if (kv.second.second.wait_for(std::chrono::seconds(0)) != std::future_status::timeout) ready.push_back(kv.first);
+  for (const std::string& sig : ready) (void)collect_job(c, sig, nullptr);
+  while (c->pending.size() >= limit) {
+    std::string sig = c->pending.begin()->first;
+    (void)collect_job(c, sig, nullptr);
+  }
 }
 
 // True while the kernel of `g` is neither cached nor ready to be collected without waiting.
@@ -459,6 +478,7 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
   }
   c->stats.materialize_calls++;
   for (auto& gp : plan->groups) {
+    if (c->opt_interp >= 2 && gp->kind == GroupKind::MAP) continue;  // interpreted whenever possible: no kernel wanted
     gr_status pst = prepare_group(c, *gp);
     if (pst != GR_OK) return pst;
   }
@@ -574,7 +594,7 @@ gr_status gr_sync(gr_ctx* ctx) {
 gr_status gr_ctx_destroy(gr_ctx* ctx) {
   if (!ctx) return GR_ERR_ARG;
   if (ctx->device >= 0) (void)hipStreamSynchronize(ctx->stream);
-  (void)collect_all_jobs(ctx);  // finished code objects go to the on-disk cache
+  (void)collect_all_jobs(ctx, false);  // finished code objects go to the on-disk cache; nothing is loaded any more
   std::vector<Node*> all;
   for (auto& kv : ctx->nodes) all.push_back(kv.second);
   for (Node* n : all) {
@@ -594,7 +614,7 @@ gr_status gr_ctx_destroy(gr_ctx* ctx) {
 
 gr_status gr_compile_wait(gr_ctx* ctx) {
   if (!ctx) return GR_ERR_ARG;
-  return collect_all_jobs(ctx);
+  return collect_all_jobs(ctx, true);
 }
 
 gr_status gr_ctx_set_stream(gr_ctx* ctx, void* hip_stream) {

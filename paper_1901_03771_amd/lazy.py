@@ -13,7 +13,9 @@ unchanged with this module passed in its place.
 from __future__ import annotations
 
 import builtins
+import atexit
 import ctypes
+import weakref
 import os
 from typing import Optional, Sequence
 
@@ -108,6 +110,20 @@ def _torch():
     return torch
 
 
+# Contexts still open when the interpreter exits are closed while the HIP runtime is still up
+# (a context may have compilations running on host threads).
+_LIVE = weakref.WeakSet()
+
+
+@atexit.register
+def _close_live_contexts():
+    for c in list(_LIVE):
+        try:
+            c.close()
+        except Exception:
+            pass
+
+
 class Context:
     """One gr_ctx.  device=-1 records, plans and generates code without a GPU."""
 
@@ -127,11 +143,13 @@ class Context:
         if st:
             raise GrError(st, L.gr_last_error(None).decode())
         self.device = int(device)
+        _LIVE.add(self)
 
     def close(self):
         if self._p:
             lib().gr_ctx_destroy(self._p)
             self._p = ctypes.c_void_p()
+        _LIVE.discard(self)
 
     def __del__(self):
         try:
