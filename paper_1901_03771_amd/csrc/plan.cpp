@@ -550,6 +550,26 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
 
 // ---------------------------------------------------------------------------
 
+// Operand of a contraction as an access group of its own.  The contraction kernels address it as
+// base + i * coef[0] + j * coef[1]; the static shift that `load` keeps apart (a slice that starts
+// at or beyond its step) is folded into the base here, and the group is never shared with another
+// access: the other operand or an epilogue load may read the same array with the same map, but
+// with coefficient slots that mean other dimensions or with another shift.
+static int add_core_group(GroupPlan* g, const Builder& like, const Node* leaf, const IndexMap& lm) {
+  GroupPlan tmp;
+  std::vector<Instr> prog;
+  Builder cb;
+  cb.g = &tmp; cb.owned = like.owned; cb.rank = 2; cb.dims = like.dims; cb.prog = &prog;
+  cb.load(leaf, lm);
+  AccessGroup ag = tmp.groups[0];
+  const Instr& ld = prog.back();
+  for (int k = 0; k < 2; ++k) if (!ag.structural_zero[k]) ag.base += ag.coef[k] * ld.delta[k];
+  ag.deltas.clear();
+  ag.deltas.insert(std::vector<int64_t>(2, 0));
+  g->groups.push_back(ag);
+  return (int)g->groups.size() - 1;
+}
+
 static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std::vector<Invalid>* invalid) {
   NodeSet owned = pl.owned_by(r);
   g->root = r;
@@ -670,10 +690,7 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       if (!resolve_to_leaf(X, xm, &leaf, &lm)) return fail(c, GR_ERR_UNSUPPORTED, "dot: operand is not materialised");
       // a private group per operand (an epilogue access or the other operand may read the same leaf
       // with the same map, but their coefficient slots mean different dimensions)
-      size_t before = g->groups.size();
-      cb.load(leaf, lm);
-      if (g->groups.size() == before) g->groups.push_back(g->groups[cb.prog->back().group]);
-      (side == 0 ? g->mat_group : g->vec_group) = (int)g->groups.size() - 1;
+      (side == 0 ? g->mat_group : g->vec_group) = add_core_group(g, cb, leaf, lm);
       b.leaves_seen.insert(leaf);
     }
     b.members_seen.insert(dot);
@@ -710,25 +727,14 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     cb.canonicalize(A, am);
     if (!resolve_to_leaf(A, am, &leaf, &lm)) return fail(c, GR_ERR_UNSUPPORTED, "dot: matrix operand is not materialised");
     // the epilogue's groups use 1-D coefficients; core groups are appended with (m,k) coefficients
-    size_t before = g->groups.size();
-    cb.load(leaf, lm);
-    g->mat_group = (int)g->groups.size() - 1;
-    if (g->groups.size() == before) {  // identical ident as an epilogue group cannot happen (rank differs), keep defensive
-      return fail(c, GR_ERR_UNSUPPORTED, "dot: internal access clash");
-    }
+    g->mat_group = add_core_group(g, cb, leaf, lm);
+    b.leaves_seen.insert(leaf);
     IndexMap vm(1);
     vm[0] = DimMap{1, 1, 0};
     cb.canonicalize(v, vm);
     if (!resolve_to_leaf(v, vm, &leaf, &lm)) return fail(c, GR_ERR_UNSUPPORTED, "dot: vector operand is not materialised");
-    before = g->groups.size();
-    cb.load(leaf, lm);
-    g->vec_group = (int)g->groups.size() - 1;
-    if (g->groups.size() == before) {
-      // same leaf, same map as the matrix (a.a for 1-D a): duplicate the group
-      g->groups.push_back(g->groups[g->mat_group]);
-      g->vec_group = (int)g->groups.size() - 1;
-    }
-    for (const Node* l : cb.leaves_seen) b.leaves_seen.insert(l);
+    g->vec_group = add_core_group(g, cb, leaf, lm);
+    b.leaves_seen.insert(leaf);
     b.members_seen.insert(dot);
     g->rank = 1;
     g->dims[0] = g->M;

@@ -55,6 +55,12 @@ DOT_CASES = [
     (lambda xp, A, v, u: xp.tanh(A @ (v * 2.0 + 1.0)) + u, "lazy vector operand + epilogue"),
     (lambda xp, A, v, u: (A @ v) * (A @ v) + u, "dot used twice"),
     (lambda xp, A, v, u: A.T @ (A @ v), "dot feeding dot"),
+    # slices that start at or beyond their step (the shift is not absorbed by the stride pattern)
+    (lambda xp, A, v, u: A[3:, 5:] @ v[5:], "offset matrix and vector"),
+    (lambda xp, A, v, u: A.T[7:, 2:] @ u[2:], "offset transposed matrix"),
+    (lambda xp, A, v, u: A[1::2, 48:51:2] @ v[100:104:2], "offset and step"),
+    (lambda xp, A, v, u: xp.dot(v[5:], v[:-5]), "inner product of two windows of one array"),
+    (lambda xp, A, v, u: A[10:20, 5:] @ xp.transpose(A[30:31, 5:], (1, 0)), "matrix times a column taken from itself"),
 ]
 
 # (shape, axis): inclusive scans along the contiguous axis, along outer axes, over long lines

@@ -154,6 +154,38 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False):
     return dtype, leaf_shapes, steps, len(shapes) - 1
 
 
+def make_tail(seed: int, dtype: str, shape):
+    """One more step for a float recipe whose result is only reproducible up to rounding: a
+    transcendental function, a float sum, or a contraction.  Returns (step, kind of comparison)."""
+    r = random.Random(seed * 7919 + 1)
+    if dtype != "f32":
+        return None, None
+    c = ["exp", "tanh", "erf", "log"] + (["sum"] * 3 if len(shape) >= 1 else []) + (["dot"] * 3 if len(shape) in (1, 2) else [])
+    k = r.choice(c)
+    if k == "sum":
+        naxes = r.randint(0, len(shape))
+        axes = tuple(sorted(r.sample(range(len(shape)), naxes))) if naxes else None
+        return ("tail", "sum", axes, r.random() < 0.5), "reduction"
+    if k == "dot":
+        return ("tail", "dot", r.choice(["self_t", "column"]) if len(shape) == 2 else "inner"), "reduction"
+    return ("tail", k), "elementwise"
+
+
+def apply_tail(xp, step, x):
+    if step[1] == "sum":
+        return xp.sum(x, axis=step[2], keepdims=step[3])
+    if step[1] == "dot":
+        if step[2] == "inner":
+            return xp.dot(x, x)
+        if step[2] == "self_t":
+            return xp.dot(x, xp.transpose(x, (1, 0)))
+        return xp.dot(x, xp.transpose(x[0:1], (1, 0)))
+    x = xp.minimum(xp.maximum(x, -30.0), 30.0)       # keep exp finite and the functions' arguments tame
+    if step[1] == "log":
+        return xp.log(abs(x) + 0.5)
+    return getattr(xp, step[1])(x)
+
+
 def make_leaves(seed: int, dtype: str, leaf_shapes):
     g = np.random.default_rng(1000003 * seed + 17)
     out = []

@@ -490,6 +490,13 @@ def test_matrix_product_strided_and_chained(env):
     Y = g.integers(-3, 4, (96, 160)).astype(f32)
     got, ref = run_both(env, lambda xp, X, Y: X @ Y, dict(X=X, Y=Y))
     assert np.array_equal(got, ref)
+    # operands that are windows of larger arrays (offsets at or beyond the step), and two windows of one array
+    got, ref = run_both(env, lambda xp, X, Y: X[7:, 5:] @ Y[5:, 9::3], dict(X=X, Y=Y))
+    assert got.shape == (193, 51) and np.array_equal(got, ref)
+    got, ref = run_both(env, lambda xp, X, Y: X[-2:-1, 48:51:2] @ xp.transpose(X[-2:-1, 48:51:2], (1, 0)), dict(X=X, Y=Y))
+    assert got.shape == (1, 1) and np.array_equal(got, ref)
+    got, ref = run_both(env, lambda xp, X, Y: X[3:50, 4:] @ xp.transpose(X[100:180, :-4], (1, 0)), dict(X=X, Y=Y))
+    assert got.shape == (47, 80) and np.array_equal(got, ref)
 
 
 def test_mnist_listing2(env):
@@ -626,6 +633,38 @@ def test_random_programs_bit_exact_generated_kernels(env, block):
 def test_random_programs_bit_exact_interpreter(env_interp, block):
     for seed in range(1000 + 40 * block, 1000 + 40 * block + 40):
         _run_fuzz_seed(env_interp, seed)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_programs_ending_in_a_rounding_op(env, block):
+    # an exactly rounded random program followed by one op whose result depends on the evaluation
+    # order or the function library (float sum, contraction, exp/log/tanh/erf): compared within the
+    # stated tolerances
+    import fuzz
+    gr, ctx, torch = env
+    done = 0
+    for seed in range(7000 + 25 * block, 7000 + 25 * block + 25):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed)
+        if dtype != "f32":
+            continue
+        leaves = fuzz.make_leaves(seed, dtype, shapes)
+        opool = fuzz.apply(ora, steps, [ora.array(x) for x in leaves])
+        if opool[res].numpy().dtype != np.float32:
+            continue
+        tail, how = fuzz.make_tail(seed, dtype, opool[res].shape)
+        base = opool[res].numpy()
+        if not np.isfinite(base).all() or np.abs(base).max() > 1e15:
+            continue                                     # sums and products of these would overflow
+        ref = fuzz.apply_tail(ora, tail, opool[res]).numpy()
+        keep = [torch.from_numpy(x).cuda() for x in leaves]
+        got = fuzz.apply_tail(gr, tail, fuzz.apply(gr, steps, [ctx.array(t) for t in keep])[res]).numpy()
+        assert got.shape == ref.shape and got.dtype == ref.dtype, (seed, tail)
+        if how == "reduction":
+            assert_reduction(got, ref, what=f"seed {seed} {tail} after {steps}")
+        else:
+            assert_elementwise(got, ref, what=f"seed {seed} {tail} after {steps}")
+        done += 1
+    assert done >= 8
 
 
 @pytest.mark.parametrize("owned", [False, True])
