@@ -19,6 +19,7 @@ import random
 import numpy as np
 
 DIMS = [1, 1, 2, 3, 5, 7, 16, 33, 64, 130]
+BIG_DIMS = [1, 2, 3, 5, 17, 130, 257, 1030, 2051, 4100]   # several tiles of every kernel, ragged tails
 
 
 def _broadcast(a, b):
@@ -32,7 +33,7 @@ def _broadcast(a, b):
     return tuple(out)
 
 
-def make_recipe(seed: int, max_steps: int = 10, assign: bool = False):
+def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool = False):
     """Returns (dtype, leaf_shapes, steps, result_index); steps are tuples whose first entry names the op.
     assign=True adds slice assignments into leaves and views of leaves (values: an array of the same
     shape, an expression of the destination itself, or a shifted and possibly overlapping view)."""
@@ -40,9 +41,10 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False):
     dtype = "i32" if r.random() < 0.3 else "f32"
     nleaf = r.randint(1, 3)
     rank = r.randint(1, 4)
-    base = [r.choice(DIMS) for _ in range(rank)]
-    while int(np.prod(base)) > 60000:
-        base[r.randrange(rank)] = r.choice(DIMS[:6])
+    dims, limit = (BIG_DIMS, 3_000_000) if big else (DIMS, 60000)
+    base = [r.choice(dims) for _ in range(rank)]
+    while int(np.prod(base)) > limit:
+        base[r.randrange(rank)] = r.choice(dims[:6])
     leaf_shapes = [tuple(base)]
     for _ in range(nleaf - 1):
         # a broadcast-compatible partner: trailing dims of the base, some replaced by 1

@@ -629,6 +629,19 @@ def test_random_programs_bit_exact_generated_kernels(env, block):
         _run_fuzz_seed(env, seed)
 
 
+def test_random_programs_bit_exact_on_large_shapes(env):
+    # the same with extents up to 4100 (up to 3 million elements): several tiles and ragged tails
+    import fuzz
+    gr, ctx, torch = env
+    for seed in range(9000, 9016):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed, big=True)
+        leaves = fuzz.make_leaves(seed, dtype, shapes)
+        ref = fuzz.apply(ora, steps, [ora.array(x) for x in leaves])[res].numpy()
+        keep = [torch.from_numpy(x).cuda() for x in leaves]
+        got = fuzz.apply(gr, steps, [ctx.array(t) for t in keep])[res].numpy()
+        assert fuzz.same_bits(got, ref), f"seed {seed}: {dtype} {shapes} {steps}"
+
+
 @pytest.mark.parametrize("block", range(6))
 def test_random_programs_bit_exact_interpreter(env_interp, block):
     for seed in range(1000 + 40 * block, 1000 + 40 * block + 40):
