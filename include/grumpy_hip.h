@@ -133,6 +133,13 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     an array whose storage the library owns, writes a second
  *                     buffer, copies the cells outside the box and swaps the
  *                     two buffers; 0 = always evaluate, then copy
+ *   "dry_run"         on a device-less context only: 1 = materialise and assign
+ *                     calls run everything except the kernel launches
+ *                     (partitioning, code generation, compilation, buffer and
+ *                     node bookkeeping; buffers get addresses that are never
+ *                     dereferenced), so the host logic can be exercised
+ *                     without a GPU; 2 = the same without compiling; 0
+ *                     (default) = such calls return GR_ERR_NODEVICE
  *   "merge"           1 (default) = a reduction, scan or contraction recorded
  *                     while a node with the same pending expression is still
  *                     waiting to be evaluated returns a handle to that node

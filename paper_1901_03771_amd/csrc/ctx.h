@@ -37,6 +37,8 @@ struct gr_ctx {
   int64_t opt_merge = 1;
   int64_t opt_interp = 1;
   int64_t opt_assign_swap = 1;
+  int64_t opt_dry_run = 0;
+  uintptr_t dry_next = 0x100000;  // fake device addresses handed out by a dry run
 
   // allocator
   void* (*alloc_fn)(size_t, void*) = nullptr;

@@ -576,6 +576,10 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
   g->out_dtype = r->dtype;
   g->nt = (int)c->opt_nontemporal;
 
+  // A root that already has data (the plain copy of an array into another buffer or through a
+  // strided destination) is a map that loads it, whatever operation once produced it.
+  if (r->materialized) owned.clear();
+
   // classify
   const Node* dot = nullptr;
   std::vector<const Node*> reds;
@@ -589,7 +593,7 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
   b.g = g;
   b.owned = &owned;
 
-  if (r->kind == Kind::SCAN) {
+  if (r->kind == Kind::SCAN && !r->materialized) {
     // ---- map-scan: the operand expression is the map, the scan runs along one axis --------
     g->kind = GroupKind::SCAN;
     b.g->kind = GroupKind::SCAN;

@@ -40,6 +40,12 @@ void* ctx_alloc(gr_ctx* c, size_t bytes) {
   if (bytes == 0) bytes = 256;
   c->stats.bytes_allocated += bytes;
   if (c->alloc_fn) return c->alloc_fn(bytes, c->alloc_user);
+  if (c->device < 0) {
+    // dry run on a device-less context: distinct addresses that nothing ever dereferences
+    void* p = (void*)c->dry_next;
+    c->dry_next += (bytes + 255) & ~(uintptr_t)255;
+    return p;
+  }
   size_t rounded = (bytes + 255) & ~(size_t)255;
   auto& fl = c->pool_free[rounded];
   if (!fl.empty()) {
@@ -57,6 +63,7 @@ void ctx_free(gr_ctx* c, void* p, size_t bytes) {
   if (!p) return;
   if (bytes == 0) bytes = 256;
   if (c->free_fn) { c->free_fn(p, c->alloc_user); return; }
+  if (c->device < 0) return;
   // stream order makes reuse safe: every kernel of this context runs on one stream
   c->pool_free[(bytes + 255) & ~(size_t)255].push_back(p);
 }
@@ -279,6 +286,7 @@ gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
 static gr_status launch(gr_ctx* c, hipFunction_t fn, const std::string& name, int64_t grid, std::vector<uint64_t>& args) {
   if (grid <= 0) return GR_OK;
   if (grid > 0x7fffffffLL) return fail(c, GR_ERR_UNSUPPORTED, "launch: grid too large");
+  if (c->device < 0) { c->stats.kernel_launches++; return GR_OK; }  // dry run: everything but the launch itself
   size_t sz = args.size() * sizeof(uint64_t);
   void* extra[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, args.data(), HIP_LAUNCH_PARAM_BUFFER_SIZE, &sz, HIP_LAUNCH_PARAM_END};
   hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -462,7 +470,7 @@ static bool has_storage(const Node* n) {
 }
 
 gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool check_alias) {
-  if (c->device < 0) return fail(c, GR_ERR_NODEVICE, "context has no device");
+  if (c->device < 0 && !c->opt_dry_run) return fail(c, GR_ERR_NODEVICE, "context has no device");
   if (user_out && check_alias) {
     uintptr_t olo = (uintptr_t)user_out, ohi = olo + root->count() * itemsize(root->dtype);
     for (const auto& g : plan->groups)
@@ -477,8 +485,10 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
       }
   }
   c->stats.materialize_calls++;
+  static gr_ctx::Kernel dry_kernel;  // stands for any kernel in a dry run that does not compile
+  const bool no_compile = c->device < 0 && c->opt_dry_run >= 2;
   for (auto& gp : plan->groups) {
-    if (c->opt_interp >= 2 && gp->kind == GroupKind::MAP) continue;  // interpreted whenever possible: no kernel wanted
+    if (no_compile || (c->opt_interp >= 2 && gp->kind == GroupKind::MAP)) continue;  // no kernel wanted
     gr_status pst = prepare_group(c, *gp);
     if (pst != GR_OK) return pst;
   }
@@ -489,7 +499,8 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
     // interpreter instead of waiting; the job stays pending and a later request collects it.
     // (option "interp" = 2: every map sub-graph the interpreter covers, compiled or not)
     const bool try_interp = g.kind == GroupKind::MAP && !g.pair && (c->opt_interp >= 2 || (c->opt_interp == 1 && still_compiling(c, g)));
-    gr_status st = try_interp ? GR_OK : compile_group(c, g, &k);
+    if (no_compile) k = &dry_kernel;
+    gr_status st = (try_interp || no_compile) ? GR_OK : compile_group(c, g, &k);
     if (st != GR_OK) return st;
     // output buffers: the caller's for the requested root, the allocator's otherwise
     Node* roots[2] = {g.root, g.pair ? g.pair->root : nullptr};
@@ -549,6 +560,9 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
       r->planned = false;
     }
   }
+  // The plan's marks are cleared while every node it names is still alive: releasing the
+  // predecessors below may free intermediate roots that nothing else refers to.
+  clear_planned(plan);
   // Predecessors of materialised nodes are no longer needed.  Roots are visited in execution
   // (topological) order: dropping a root's inputs can only free nodes upstream of it, which
   // includes earlier roots that nothing else refers to, never a root still to be visited.
@@ -637,7 +651,7 @@ gr_status gr_materialize(gr_ctx* ctx, gr_array a) {
   if (!x) return fail(ctx, GR_ERR_HANDLE, "materialize: bad handle");
   if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "materialize: a bare scalar has no array value");
   if (resolves_to_data(x)) return GR_OK;
-  if (ctx->device < 0) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
+  if (ctx->device < 0 && !ctx->opt_dry_run) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
   Plan plan;
   gr_status st = make_plan(ctx, x, &plan);
   if (st != GR_OK) return st;
@@ -655,7 +669,7 @@ gr_status gr_materialize_into(gr_ctx* ctx, gr_array a, void* dptr, size_t bytes)
   if (bytes != need) return fail(ctx, GR_ERR_ARG, "materialize_into: buffer size does not match the array");
   if (need > 0 && !dptr) return fail(ctx, GR_ERR_ARG, "materialize_into: NULL buffer");
   if (((uintptr_t)dptr) % itemsize(x->dtype)) return fail(ctx, GR_ERR_ARG, "materialize_into: buffer not aligned to the element size");
-  if (ctx->device < 0) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
+  if (ctx->device < 0 && !ctx->opt_dry_run) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
   Plan plan;
   gr_status st = make_plan(ctx, x, &plan);
   if (st != GR_OK) return st;
@@ -792,7 +806,7 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
     if (v->shape[k] != d->shape[k]) return fail(ctx, GR_ERR_SHAPE, "assign: shapes differ");
     if (d->shape[k] > 1 && spec.strides[k] == 0) return fail(ctx, GR_ERR_UNSUPPORTED, "assign: destination elements overlap");
   }
-  if (ctx->device < 0) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
+  if (ctx->device < 0 && !ctx->opt_dry_run) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
   if (d->count() == 0) return GR_OK;
   uintptr_t lo, hi;
   view_extent(base, d->ndim, d->shape, spec.base, spec.strides, &lo, &hi);

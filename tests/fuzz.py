@@ -92,7 +92,8 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool 
             steps.append(("unary", op, a))
             shapes.append(sa)
         elif kind == "binary":
-            b = pick(lambda i: _broadcast(shapes[i], sa) is not None)
+            # broadcasting two transposed operands can multiply extents: keep results within bounds
+            b = pick(lambda i: _broadcast(shapes[i], sa) is not None and int(np.prod(_broadcast(shapes[i], sa))) <= 2 * limit)
             op = r.choice(["add", "sub", "mul", "maximum", "minimum"] + (["divsafe"] if dtype == "f32" else []))
             steps.append(("binary", op, a, b))
             shapes.append(_broadcast(sa, shapes[b]))

@@ -443,6 +443,26 @@ def test_assign_direct_in_place_and_strided_destinations(env):
         assert ei.value.code == code
 
 
+def test_assign_of_evaluated_scans_reductions_and_products(env):
+    # a value that already has data is copied, whatever operation produced it
+    gr, ctx, torch = env
+    a0, b0 = _rand((6, 40), 171), _rand((6, 40), 172)
+    A, B = ctx.array(torch.from_numpy(a0).cuda()), ctx.array(torch.from_numpy(b0.copy()).cuda())
+    oa, ob = ora.array(a0), ora.array(b0.copy())
+    c, oc = gr.cummax(A, 1).materialize(), ora.cummax(oa, 1)
+    m, om = gr.max(A, axis=1, keepdims=True).materialize(), ora.max(oa, axis=1, keepdims=True)
+    d, od = gr.dot(A, gr.transpose(A)).materialize(), ora.dot(oa, ora.transpose(oa))
+    B[:] = c
+    ob[:] = oc
+    B[:, 3:4] = m
+    ob[:, 3:4] = om
+    B[:, 10:16] = d
+    ob[:, 10:16] = od
+    got, ref = B.numpy(), ob.numpy()
+    assert np.array_equal(got[:, :10], ref[:, :10]) and np.array_equal(got[:, 16:], ref[:, 16:])
+    assert_reduction(got[:, 10:16], ref[:, 10:16], what="assigned product")
+
+
 def test_assign_keeps_recorded_values(env):
     gr, ctx, torch = env
     a0, b0 = _rand((300,), 73), _rand((300,), 74)

@@ -310,6 +310,62 @@ def test_random_programs_partition_into_valid_subgraph_lists(ctx):
     assert {"MAP", "REDUCE", "ROWRED", "SCAN"} <= kinds
 
 
+def test_dry_run_exercises_materialise_and_assign_without_a_device(ctx):
+    # option dry_run: everything but the launches.  Random programs with slice assignments and
+    # intermediate materialisations run through partitioning, buffer and node bookkeeping on the CPU.
+    import fuzz
+    x = ctx.spec((100, 50))
+    with pytest.raises(gr.GrError) as ei:
+        (x + 1.0).materialize()
+    assert ei.value.code == "GR_ERR_NODEVICE"
+    ctx.set_option("dry_run", 2)      # 2: no compilation either
+    del x, ei
+    import gc
+    gc.collect()
+    base = ctx.stats()["nodes_alive"]
+    launches = 0
+    for seed in range(5000, 5250):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed, assign=True)
+        leaves = [ctx.spec(s_, gr.GR_I32 if dtype == "i32" else gr.GR_F32) for s_ in shapes]
+        pool = fuzz.apply(gr, steps, leaves)
+        for a in pool:
+            a.materialize()
+            assert a.is_materialized and a.shape is not None
+        del pool, leaves, a
+        assert ctx.stats()["nodes_alive"] == base, seed      # nothing leaks
+    st = ctx.stats()
+    assert st["kernel_launches"] > 500 and st["compile_ms"] == 0.0
+    # one kernel per op: intermediate results without a handle are freed while the plan finishes
+    ctx.set_option("fusion", 0)
+    for seed in range(6000, 6100):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed, assign=True)
+        leaves = [ctx.spec(s_, gr.GR_I32 if dtype == "i32" else gr.GR_F32) for s_ in shapes]
+        for a in fuzz.apply(gr, steps, leaves):
+            a.materialize()
+        del leaves, a
+        assert ctx.stats()["nodes_alive"] == base, seed
+    ctx.set_option("fusion", 1)
+    # an evaluated scan / reduction / contraction assigned somewhere else is a plain copy
+    t = ctx.spec((6, 40))
+    for v in (gr.cummax(t, 1), gr.max(t, axis=1, keepdims=True) + t * 0.0, gr.dot(t, gr.transpose(t))[:, :]):
+        v.materialize()
+    c1, m1, d1 = gr.cummax(t, 1).materialize(), gr.max(t, axis=0).materialize(), gr.dot(t, gr.transpose(t)).materialize()
+    dst = ctx.spec((6, 40))
+    dst[:] = c1
+    dst[:, 0:6] = d1
+    row = ctx.spec((40,))
+    row[:] = m1
+    del row
+    del t, v, c1, m1, d1, dst
+    # with dry_run = 1 the kernels are generated and compiled as well
+    ctx.set_option("dry_run", 1)
+    y = ctx.spec((64, 4096))
+    s = gr.exp(y - gr.max(y, axis=1, keepdims=True))
+    (s / gr.sum(s, axis=1, keepdims=True)).materialize()
+    st = ctx.stats()
+    assert st["cache_misses"] == 1 and (st["compile_ms"] > 0 or st["disk_hits"] == 1)
+
+
 def test_leaves_and_only_leaves_are_materialised(ctx):
     a = ctx.spec((33, 65))
     out = (a.T @ (a @ ctx.spec((65,)))) * 2.0
