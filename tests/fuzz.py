@@ -309,3 +309,78 @@ def same_bits(got: np.ndarray, ref: np.ndarray, zero_signs: bool = True) -> bool
             g, r = np.where(g == 0x80000000, 0, g), np.where(r == 0x80000000, 0, r)
         return bool(np.array_equal(g, r))
     return bool(np.array_equal(got, ref))
+
+
+# ---- contractions on integer-valued floats: exact whatever the summation order ---------------
+
+def make_dot_case(seed: int):
+    """A random contraction whose operands are windows (offset, step, optional transposition in
+    memory) of float arrays holding integers in [-3, 3]: every partial sum is an integer below
+    2**24, so any correct kernel returns the same bits.  Returns (arrays, program(xp, **arrays))."""
+    r = random.Random(seed * 104729 + 7)
+    g = np.random.default_rng(seed + 424242)
+    dims = [1, 2, 3, 5, 16, 33, 64, 130, 257, 600]
+    kind = r.choice(["gemm", "gemm", "rowdot", "colacc", "inner", "pair"])
+    M, K, N = r.choice(dims), r.choice(dims), r.choice(dims)
+    if kind == "pair":
+        M, K = r.choice([5, 64, 257, 600, 3000]), r.choice([3, 16, 64, 130, 512])
+
+    def window(rows, cols):
+        """An integer-valued array and the slicing that cuts a (rows, cols) window out of it,
+        possibly stored transposed."""
+        sr, sc = r.choice([1, 1, 2, 3]), r.choice([1, 1, 2])
+        o_r, o_c = r.randint(0, 7), r.randint(0, 9)
+        tr = r.random() < 0.4
+        full = (o_r + (rows - 1) * sr + 1 + r.randint(0, 3), o_c + (cols - 1) * sc + 1 + r.randint(0, 3))
+        arr = g.integers(-3, 4, full[::-1] if tr else full).astype(np.float32)
+        key = (slice(o_r, o_r + (rows - 1) * sr + 1, sr), slice(o_c, o_c + (cols - 1) * sc + 1, sc))
+        return arr, (lambda xp, a: (xp.transpose(a, (1, 0)) if tr else a)[key])
+
+    def vector(n):
+        st, off = r.choice([1, 1, 2, 5]), r.randint(0, 11)
+        arr = g.integers(-3, 4, (off + (n - 1) * st + 1 + r.randint(0, 3),)).astype(np.float32)
+        return arr, (lambda xp, a: a[off:off + (n - 1) * st + 1:st])
+
+    arrays, epi = {}, r.choice(["none", "bias", "relu", "scale"])
+    if kind == "gemm":
+        arrays["A"], fa = window(M, K)
+        arrays["B"], fb = window(K, N)
+        arrays["c"] = g.integers(-3, 4, (N,)).astype(np.float32)
+        core = lambda xp, A, B, c: xp.dot(fa(xp, A), fb(xp, B))
+    elif kind == "rowdot":
+        arrays["A"], fa = window(M, K)
+        arrays["B"], fb = vector(K)
+        arrays["c"] = g.integers(-3, 4, (M,)).astype(np.float32)
+        core = lambda xp, A, B, c: xp.dot(fa(xp, A), fb(xp, B))
+    elif kind == "colacc":
+        arrays["A"], fa = window(K, M)                       # (K, M) window used transposed: (M, K) . (K,)
+        arrays["B"], fb = vector(K)
+        arrays["c"] = g.integers(-3, 4, (M,)).astype(np.float32)
+        core = lambda xp, A, B, c: xp.dot(xp.transpose(fa(xp, A), (1, 0)), fb(xp, B))
+    elif kind == "inner":
+        arrays["A"], fa = vector(K)
+        arrays["B"], fb = vector(K)
+        arrays["c"] = g.integers(-3, 4, (1,)).astype(np.float32)
+        core = lambda xp, A, B, c: xp.dot(fa(xp, A), fb(xp, B))
+        epi = "none"
+    else:
+        # the logistic-regression pattern with exact arithmetic: r = relu(X.w) - y, g = X^T.r
+        arrays["A"], fa = window(M, K)
+        arrays["B"], fb = vector(K)
+        arrays["c"] = g.integers(0, 2, (M,)).astype(np.float32)
+        def core(xp, A, B, c):
+            X = fa(xp, A)
+            rres = xp.maximum(xp.dot(X, fb(xp, B)), 0) - c
+            return xp.dot(xp.transpose(X, (1, 0)), rres)
+        epi = "none"
+
+    def program(xp, A, B, c):
+        out = core(xp, A, B, c)
+        if epi == "bias":
+            return out + c
+        if epi == "relu":
+            return xp.maximum(out + c, 0)
+        if epi == "scale":
+            return (out - c) * 0.5
+        return out
+    return kind, arrays, program

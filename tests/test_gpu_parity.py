@@ -669,6 +669,20 @@ def test_random_programs_bit_exact_interpreter(env_interp, block):
 
 
 @pytest.mark.parametrize("block", range(4))
+def test_random_contractions_on_integer_valued_floats_are_exact(env, block):
+    # windows with offsets, steps and transposed storage, all contraction kernels (matrix cores,
+    # row-dot, column-accumulate, inner product, the fused pair), exact epilogues
+    import fuzz
+    kinds = set()
+    for seed in range(20 * block, 20 * block + 20):
+        kind, arrays, program = fuzz.make_dot_case(seed)
+        kinds.add(kind)
+        got, ref = run_both(env, program, arrays)
+        assert fuzz.same_bits(got, ref), f"seed {seed} {kind} " + str({k: v.shape for k, v in arrays.items()})
+    assert len(kinds) >= 3
+
+
+@pytest.mark.parametrize("block", range(4))
 def test_random_programs_ending_in_a_rounding_op(env, block):
     # an exactly rounded random program followed by one op whose result depends on the evaluation
     # order or the function library (float sum, contraction, exp/log/tanh/erf): compared within the
