@@ -33,7 +33,7 @@ def _broadcast(a, b):
     return tuple(out)
 
 
-def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool = False):
+def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool = False, empty: bool = False):
     """Returns (dtype, leaf_shapes, steps, result_index); steps are tuples whose first entry names the op.
     assign=True adds slice assignments into leaves and views of leaves (values: an array of the same
     shape, an expression of the destination itself, or a shifted and possibly overlapping view)."""
@@ -87,6 +87,8 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool 
         sa = shapes[a]
         if len(sa) == 0 and kind in ("slice", "transpose", "reduce", "scan"):
             kind = "unary"
+        if 0 in sa and kind == "reduce" and dtype != "i32":
+            kind = "unary"                                  # max/min of nothing is an error; an empty i32 sum is 0
         if kind == "unary":
             op = r.choice(["neg", "abs", "square"] + (["sqrtabs"] if dtype == "f32" else []))
             steps.append(("unary", op, a))
@@ -105,13 +107,15 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool 
         elif kind == "slice":
             key, out = [], []
             for d in sa:
-                if d == 1 or r.random() < 0.3:
+                if d <= 1 or r.random() < 0.3:
                     key.append((None, None, None))
                     out.append(d)
                     continue
                 lo = r.randint(0, d - 1)
                 hi = r.randint(lo + 1, d)
                 st = r.choice([1, 1, 2, 3])
+                if empty and r.random() < 0.15:
+                    hi = lo                                 # an empty window: every later op sees extent 0
                 neg = r.random() < 0.3                      # negative indices address from the end
                 key.append((lo - d if neg else lo, hi - d if (neg and hi < d) else hi, st))
                 out.append((hi - lo + st - 1) // st)
@@ -124,7 +128,7 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool 
             shapes.append(tuple(sa[p] for p in perm))
         elif kind == "reduce":
             ops = ["max", "min"] + (["sum"] if dtype == "i32" else [])
-            op = r.choice(ops)
+            op = "sum" if 0 in sa else r.choice(ops)
             naxes = r.randint(0, len(sa))                  # 0: all axes (axis=None)
             axes = tuple(sorted(r.sample(range(len(sa)), naxes))) if naxes else None
             keep = r.random() < 0.5

@@ -649,6 +649,24 @@ def test_random_programs_bit_exact_generated_kernels(env, block):
         _run_fuzz_seed(env, seed)
 
 
+def test_random_programs_with_empty_windows(env):
+    # slices that select nothing: every later op sees an extent of 0 (no launch, right shapes, i32 sums of nothing are 0)
+    import fuzz
+    gr, ctx, torch = env
+    empties = 0
+    for seed in range(200000, 200060):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed, empty=True)
+        leaves = fuzz.make_leaves(seed, dtype, shapes)
+        ref = fuzz.apply(ora, steps, [ora.array(x) for x in leaves])
+        keep = [torch.from_numpy(x).cuda() for x in leaves]
+        got = fuzz.apply(gr, steps, [ctx.array(t) for t in keep])
+        for i, (g_, r_) in enumerate(zip(got, ref)):
+            r_ = r_.numpy()
+            empties += 0 in r_.shape
+            assert fuzz.same_bits(g_.numpy(), r_), f"seed {seed} value {i}: {dtype} {shapes} {steps}"
+    assert empties >= 5
+
+
 def test_random_programs_bit_exact_on_large_shapes(env):
     # the same with extents up to 4100 (up to 3 million elements): several tiles and ragged tails
     import fuzz
