@@ -1052,33 +1052,43 @@ void gen_gemm(Em& e) {
   e.o << "  const long long bm0 = (long long)(blockIdx.x / tiles_n) * 128, bn0 = (long long)(blockIdx.x % tiles_n) * 128;\n";
   e.o << "  f16v acc[2][2];\n  for (int i = 0; i < 2; ++i) for (int j = 0; j < 2; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n";
   e.o << "  float ra[8], rb[8];\n";
-  // --- global -> registers
-  e.o << "  auto fetch = [&](long long k0) {\n";
-  if (a_mode == 0) {
-    e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long row = bm0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n"
-           "      if (row < M && kk + 4 <= K) { const f4u w = *(const GM f4u*)(A + row * am + kk); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
-           "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (row < M && kk + j < K) ? A[row * am + kk + j] : 0.0f; }\n    }\n";
-  } else if (a_mode == 1) {
-    e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, row = bm0 + (tid % 32) * 4;\n"
-           "      if (kk < K && row + 4 <= M) { const f4u w = *(const GM f4u*)(A + kk * ak + row); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
-           "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (kk < K && row + j < M) ? A[kk * ak + row + j] : 0.0f; }\n    }\n";
-  } else {
-    e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; const long long row = bm0 + el % 128, kk = k0 + el / 128;\n"
-           "      ra[i] = (row < M && kk < K) ? A[row * am + kk * ak] : 0.0f; }\n";
+  // --- global -> registers: a guarded version for edge tiles and the K tail, and an unguarded one
+  // for tiles that lie completely inside both operands (straight-line loads the compiler can keep
+  // in flight under the matrix instructions of the previous step)
+  for (int guarded = 1; guarded >= 0; --guarded) {
+    e.o << "  auto fetch" << (guarded ? "_g" : "_u") << " = [&](long long k0) {\n";
+    if (a_mode == 0) {
+      e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long row = bm0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n";
+      if (guarded) e.o << "      if (row < M && kk + 4 <= K) { const f4u w = *(const GM f4u*)(A + row * am + kk); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
+                          "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (row < M && kk + j < K) ? A[row * am + kk + j] : 0.0f; }\n    }\n";
+      else e.o << "      const f4u w = *(const GM f4u*)(A + row * am + kk); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3];\n    }\n";
+    } else if (a_mode == 1) {
+      e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, row = bm0 + (tid % 32) * 4;\n";
+      if (guarded) e.o << "      if (kk < K && row + 4 <= M) { const f4u w = *(const GM f4u*)(A + kk * ak + row); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
+                          "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (kk < K && row + j < M) ? A[kk * ak + row + j] : 0.0f; }\n    }\n";
+      else e.o << "      const f4u w = *(const GM f4u*)(A + kk * ak + row); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3];\n    }\n";
+    } else {
+      e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; const long long row = bm0 + el % 128, kk = k0 + el / 128;\n";
+      if (guarded) e.o << "      ra[i] = (row < M && kk < K) ? A[row * am + kk * ak] : 0.0f; }\n";
+      else e.o << "      ra[i] = A[row * am + kk * ak]; }\n";
+    }
+    if (b_mode == 0) {
+      e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, col = bn0 + (tid % 32) * 4;\n";
+      if (guarded) e.o << "      if (kk < K && col + 4 <= N) { const f4u w = *(const GM f4u*)(B + kk * bk + col); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
+                          "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (kk < K && col + j < N) ? B[kk * bk + col + j] : 0.0f; }\n    }\n";
+      else e.o << "      const f4u w = *(const GM f4u*)(B + kk * bk + col); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3];\n    }\n";
+    } else if (b_mode == 1) {
+      e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long col = bn0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n";
+      if (guarded) e.o << "      if (col < N && kk + 4 <= K) { const f4u w = *(const GM f4u*)(B + col * bn + kk); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
+                          "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (col < N && kk + j < K) ? B[col * bn + kk + j] : 0.0f; }\n    }\n";
+      else e.o << "      const f4u w = *(const GM f4u*)(B + col * bn + kk); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3];\n    }\n";
+    } else {
+      e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; const long long col = bn0 + el % 128, kk = k0 + el / 128;\n";
+      if (guarded) e.o << "      rb[i] = (col < N && kk < K) ? B[kk * bk + col * bn] : 0.0f; }\n";
+      else e.o << "      rb[i] = B[kk * bk + col * bn]; }\n";
+    }
+    e.o << "  };\n";
   }
-  if (b_mode == 0) {
-    e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, col = bn0 + (tid % 32) * 4;\n"
-           "      if (kk < K && col + 4 <= N) { const f4u w = *(const GM f4u*)(B + kk * bk + col); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
-           "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (kk < K && col + j < N) ? B[kk * bk + col + j] : 0.0f; }\n    }\n";
-  } else if (b_mode == 1) {
-    e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long col = bn0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n"
-           "      if (col < N && kk + 4 <= K) { const f4u w = *(const GM f4u*)(B + col * bn + kk); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
-           "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (col < N && kk + j < K) ? B[col * bn + kk + j] : 0.0f; }\n    }\n";
-  } else {
-    e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; const long long col = bn0 + el % 128, kk = k0 + el / 128;\n"
-           "      rb[i] = (col < N && kk < K) ? B[kk * bk + col * bn] : 0.0f; }\n";
-  }
-  e.o << "  };\n";
   // --- registers -> LDS (k-major tiles)
   e.o << "  auto stash = [&](int buf) {\n";
   if (a_mode == 0) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) As[buf][(tid % 4) * 4 + j][tid / 4 + 64 * i] = ra[4*i+j];\n";
@@ -1088,17 +1098,25 @@ void gen_gemm(Em& e) {
   else if (b_mode == 1) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) Bs[buf][(tid % 4) * 4 + j][tid / 4 + 64 * i] = rb[4*i+j];\n";
   else e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; Bs[buf][el / 128][el % 128] = rb[i]; }\n";
   e.o << "  };\n";
-  e.o << "  const long long nkt = (K + 15) / 16;\n  int cur = 0;\n";
-  e.o << "  if (nkt > 0) { fetch(0); stash(0); }\n  __syncthreads();\n";
-  e.o << "  for (long long kt = 0; kt < nkt; ++kt) {\n    if (kt + 1 < nkt) fetch((kt + 1) * 16);\n";
-  e.o << "#pragma unroll\n    for (int ks = 0; ks < 8; ++ks) {\n"
+  e.o << "  auto step = [&](int cur) {\n"
+         "#pragma unroll\n    for (int ks = 0; ks < 8; ++ks) {\n"
          "      const float a0 = As[cur][2 * ks + lh][wm + l32], a1 = As[cur][2 * ks + lh][wm + 32 + l32];\n"
          "      const float b0 = Bs[cur][2 * ks + lh][wn + l32], b1 = Bs[cur][2 * ks + lh][wn + 32 + l32];\n"
          "      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);\n"
          "      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);\n"
          "      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);\n"
-         "      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);\n    }\n";
-  e.o << "    if (kt + 1 < nkt) stash(cur ^ 1);\n    __syncthreads();\n    cur ^= 1;\n  }\n";
+         "      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);\n    }\n  };\n";
+  e.o << "  const long long nkt = (K + 15) / 16;\n  int cur = 0;\n";
+  // the workgroup-uniform choice between the two loops
+  e.o << "  if (bm0 + 128 <= M && bn0 + 128 <= N && K % 16 == 0) {\n"
+         "    if (nkt > 0) { fetch_u(0); stash(0); }\n    __syncthreads();\n"
+         "    for (long long kt = 0; kt < nkt; ++kt) {\n      if (kt + 1 < nkt) fetch_u((kt + 1) * 16);\n      step(cur);\n"
+         "      if (kt + 1 < nkt) stash(cur ^ 1);\n      __syncthreads();\n      cur ^= 1;\n    }\n"
+         "  } else {\n"
+         "    if (nkt > 0) { fetch_g(0); stash(0); }\n    __syncthreads();\n"
+         "    for (long long kt = 0; kt < nkt; ++kt) {\n      if (kt + 1 < nkt) fetch_g((kt + 1) * 16);\n      step(cur);\n"
+         "      if (kt + 1 < nkt) stash(cur ^ 1);\n      __syncthreads();\n      cur ^= 1;\n    }\n"
+         "  }\n";
   // --- epilogue on the accumulators: element q of a 32x32 block sits at row 8*(q/4) + 4*(lane/32) + q%4, column lane%32
   e.o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
   e.o << "  for (int i = 0; i < 2; ++i) for (int j = 0; j < 2; ++j)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
