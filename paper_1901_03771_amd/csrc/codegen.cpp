@@ -655,7 +655,42 @@ void gen_reduce(Em& e) {
     e.o << ";\n";
   }
   e.o << "  " << T << " acc = " << Em::identity(ph) << ";\n";
-  if (g.red_mode == 0) e.o << "#pragma unroll 4\n  for (long long j = jbeg; j < jend; ++j) {\n";
+  // mode 1 over one contiguous reduced dimension: lanes take four consecutive elements with one
+  // dwordx4 per array and keep four partial results; the ragged end goes through the scalar loop
+  bool vec = g.red_mode == 1 && rank == kr + 1;
+  for (size_t i = 0; vec && i < g.prog.size(); ++i) {
+    const Instr& in = g.prog[i];
+    if (in.dtype == GR_I64) vec = false;
+    if (in.kind == IKind::LOAD && !g.groups[in.group].structural_zero[kr] && access_class(g.groups[in.group], kr) != '1') vec = false;
+  }
+  if (vec) {
+    e.o << "  long long j = jbeg + 4 * (long long)threadIdx.x;\n  {\n    " << T << " acc1 = acc, acc2 = acc, acc3 = acc;\n";
+    e.o << "#pragma unroll 2\n    for (; j + 4 <= jend; j += 1024) {\n";
+    for (size_t i = 0; i < g.prog.size(); ++i) {
+      const Instr& in = g.prog[i];
+      if (in.kind != IKind::LOAD) continue;
+      const AccessGroup& ag = g.groups[in.group];
+      std::ostringstream base;
+      base << "p" << in.group;
+      for (int k = 0; k < kr; ++k) if (!ag.structural_zero[k] && in.delta[k]) base << " + " << in.delta[k] << " * " << e.coef(in.group, k);
+      if (ag.structural_zero[kr]) e.o << "      const " << cty(in.dtype) << " u" << i << " = (" << base.str() << ")[0];\n";
+      else e.o << "      const " << vty4(in.dtype) << " w" << i << " = " << e.ld(in.group, vty4(in.dtype), base.str() + " + j + " + std::to_string(in.delta[kr])) << ";\n";
+    }
+    for (int c4 = 0; c4 < 4; ++c4) {
+      const std::string pre = "v" + std::to_string(c4) + "_";
+      emit_scalar_program(e, g.prog, {ph.value},
+                          [&](const Instr& in, int id) {
+                            const AccessGroup& ag = g.groups[in.group];
+                            if (ag.structural_zero[kr]) return "u" + std::to_string(id);
+                            return "w" + std::to_string(id) + "[" + std::to_string(c4) + "]";
+                          },
+                          "0.0f", pre, "      ");
+      const std::string a = c4 == 0 ? "acc" : "acc" + std::to_string(c4);
+      e.o << "      " << a << " = " << Em::combine(ph, a, pre + std::to_string(ph.value)) << ";\n";
+    }
+    e.o << "    }\n    acc = gr_comb0(gr_comb0(acc, acc1), gr_comb0(acc2, acc3));\n  }\n";
+    e.o << "  for (; j < jend; ++j) {\n";   // at most one lane still has (fewer than four) elements
+  } else if (g.red_mode == 0) e.o << "#pragma unroll 4\n  for (long long j = jbeg; j < jend; ++j) {\n";
   else e.o << "#pragma unroll 4\n  for (long long j = jbeg + threadIdx.x; j < jend; j += 256) {\n";
   if (rank > kr) {
     e.o << "    long long jrem = j;\n";
@@ -754,7 +789,8 @@ void gen_scan(Em& e) {
     e.o << "  const long long LINES = " << e.S(e.L.extra) << ", CH = " << e.S(e.L.extra + 1) << ", NCHUNK = " << e.S(e.L.extra + 3) << ";\n";
     e.o << "  const long long L = " << e.dim(sd) << ";\n";
     if (per_block_line) e.o << "  const long long line = blockIdx.x / NCHUNK, chunk = blockIdx.x % NCHUNK;\n";
-    else e.o << "  const long long line = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (line >= LINES) return;\n";
+    else e.o << "  const long long gt = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (gt >= LINES * NCHUNK) return;\n"
+                "  const long long line = gt % LINES, chunk = gt / LINES;\n  (void)chunk;\n";  // neighbouring threads: neighbouring lines
     e.o << "  long long lrem = line;\n";
     for (int k = sd - 1; k >= 0; --k) e.o << "  const long long i" << k << " = lrem % " << e.dim(k) << "; lrem /= " << e.dim(k) << ";\n";
     group_pointers(e, "  ");
@@ -794,11 +830,38 @@ void gen_scan(Em& e) {
   };
   auto tile_value = [](const Instr&, int id) { return "l" + std::to_string(id) + "[j]"; };
 
+  // ---- kernel 2 of 3 (both modes): exclusive scan of each line's chunk totals, in place (at most 4096 chunks)
+  auto offsets_kernel = [&]() {
+    kernel_head(e, "gr_scan_offsets");
+    e.o << "  const long long NCHUNK = " << e.S(e.L.extra + 3) << ";\n";
+    e.o << "  GM " << TA << "* const w = (GM " << TA << "*)" << e.slot(e.L.extra + 2) << " + (long long)blockIdx.x * NCHUNK;\n";
+    e.o << "  __shared__ long long gr_sm[4];\n";
+    e.o << "  const int per = (int)((NCHUNK + 255) / 256);\n  const long long c0 = (long long)threadIdx.x * per;\n";
+    e.o << "  " << TA << " v[16];\n  " << TA << " tot = " << ident << ";\n";
+    e.o << "  for (int u = 0; u < 16; ++u) { v[u] = (u < per && c0 + u < NCHUNK) ? w[c0 + u] : " << ident << "; tot = gr_comb0(tot, v[u]); }\n";
+    e.o << "  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;\n  " << TA << " x = tot;\n";
+    for (int d = 1; d < 64; d <<= 1) e.o << "  { const " << TA << " y = gr_up(x, " << d << "); if (lane >= " << d << ") x = gr_comb0(y, x); }\n";
+    e.o << "  " << TA << "* sm = (" << TA << "*)gr_sm;\n  if (lane == 63) sm[wave] = x;\n  __syncthreads();\n";
+    e.o << "  " << TA << " off = " << ident << ";\n  for (int q = 0; q < wave; ++q) off = gr_comb0(off, sm[q]);\n";
+    e.o << "  " << TA << " ex = gr_up(x, 1);\n  if (lane == 0) ex = " << ident << ";\n  off = gr_comb0(off, ex);\n";
+    e.o << "  for (int u = 0; u < 16; ++u) if (u < per && c0 + u < NCHUNK) { w[c0 + u] = off; off = gr_comb0(off, v[u]); }\n}\n";
+  };
+
   if (g.scan_mode == 1) {
+    // a thread per (line, chunk), sequential along the axis; with several chunks per line the same
+    // three steps as in mode 0: chunk totals, exclusive scan of the totals, chunks with offsets
+    kernel_head(e, "gr_scan_sums");
+    head(false);
+    e.o << "  const long long cbeg = chunk * CH, cend = (cbeg + CH < L) ? cbeg + CH : L;\n  " << TA << " acc = " << ident << ";\n";
+    e.o << "#pragma unroll 4\n  for (long long j = cbeg; j < cend; ++j) {\n";
+    emit_scalar_program(e, g.prog, {ph.value}, load_at("j"), "0.0f", "t", "    ");
+    e.o << "    acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n  }\n  ws[line * NCHUNK + chunk] = acc;\n}\n";
+    offsets_kernel();
     kernel_head(e, "gr_scan");
     head(false);
-    e.o << "  const long long ostep = " << e.S(e.L.ocoef + sd) << ";\n  " << TA << " acc = " << ident << ";\n";
-    e.o << "  for (long long j = 0; j < L; ++j) {\n";
+    e.o << "  const long long cbeg = chunk * CH, cend = (cbeg + CH < L) ? cbeg + CH : L;\n";
+    e.o << "  const long long ostep = " << e.S(e.L.ocoef + sd) << ";\n  " << TA << " acc = NCHUNK > 1 ? ws[line * NCHUNK + chunk] : " << ident << ";\n";
+    e.o << "#pragma unroll 4\n  for (long long j = cbeg; j < cend; ++j) {\n";
     emit_scalar_program(e, g.prog, {ph.value}, load_at("j"), "0.0f", "t", "    ");
     e.o << "    acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n    po[j * ostep] = acc;\n  }\n}\n";
     return;
@@ -817,20 +880,7 @@ void gen_scan(Em& e) {
   e.o << "  acc = gr_lanes0(acc);\n  { " << TA << "* sm = (" << TA << "*)gr_sm;\n    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;\n    __syncthreads();\n"
          "    if (threadIdx.x == 0) ws[line * NCHUNK + chunk] = gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])); }\n}\n";
 
-  // ---- kernel 2 of 3: exclusive scan of each line's chunk totals, in place (at most 4096 chunks)
-  kernel_head(e, "gr_scan_offsets");
-  e.o << "  const long long NCHUNK = " << e.S(e.L.extra + 3) << ";\n";
-  e.o << "  GM " << TA << "* const w = (GM " << TA << "*)" << e.slot(e.L.extra + 2) << " + (long long)blockIdx.x * NCHUNK;\n";
-  e.o << "  __shared__ long long gr_sm[4];\n";
-  e.o << "  const int per = (int)((NCHUNK + 255) / 256);\n  const long long c0 = (long long)threadIdx.x * per;\n";
-  e.o << "  " << TA << " v[16];\n  " << TA << " tot = " << ident << ";\n";
-  e.o << "  for (int u = 0; u < 16; ++u) { v[u] = (u < per && c0 + u < NCHUNK) ? w[c0 + u] : " << ident << "; tot = gr_comb0(tot, v[u]); }\n";
-  e.o << "  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;\n  " << TA << " x = tot;\n";
-  for (int d = 1; d < 64; d <<= 1) e.o << "  { const " << TA << " y = gr_up(x, " << d << "); if (lane >= " << d << ") x = gr_comb0(y, x); }\n";
-  e.o << "  " << TA << "* sm = (" << TA << "*)gr_sm;\n  if (lane == 63) sm[wave] = x;\n  __syncthreads();\n";
-  e.o << "  " << TA << " off = " << ident << ";\n  for (int q = 0; q < wave; ++q) off = gr_comb0(off, sm[q]);\n";
-  e.o << "  " << TA << " ex = gr_up(x, 1);\n  if (lane == 0) ex = " << ident << ";\n  off = gr_comb0(off, ex);\n";
-  e.o << "  for (int u = 0; u < 16; ++u) if (u < per && c0 + u < NCHUNK) { w[c0 + u] = off; off = gr_comb0(off, v[u]); }\n}\n";
+  offsets_kernel();
 
   // ---- kernel 3 of 3 (the only one for single-chunk lines): scan of a chunk with its offset
   kernel_head(e, "gr_scan");

@@ -660,6 +660,16 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       g->scan_chunk = chunk;
       g->scan_nchunk = (int)nch;
     }
+    if (g->scan_mode == 1 && lines < 65536 && L >= 128) {
+      // few lines, each walked by one thread: cut the lines into chunks so that about 2^17 threads
+      // run (chunk totals, scan of the totals, chunks with offsets, as above)
+      int64_t want = std::max<int64_t>(1, 131072 / std::max<int64_t>(lines, 1));
+      int64_t chunk = std::max<int64_t>(32, (L + want - 1) / want);
+      int64_t nch = (L + chunk - 1) / chunk;
+      if (nch > 4096) { chunk = (L + 4095) / 4096; nch = (L + chunk - 1) / chunk; }
+      g->scan_chunk = chunk;
+      g->scan_nchunk = (int)nch;
+    }
     g->red_out = lines;
     g->red_len = L;
   } else if (dot && dot->ndim == 2) {

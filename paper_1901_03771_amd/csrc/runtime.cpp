@@ -162,7 +162,7 @@ static void disk_store(const std::string& path, const std::string& sig, const st
 static void kernel_entry_points(const GroupPlan& g, std::string* name, bool* combine, bool* scan) {
   *name = kernel_name(g);
   *combine = (g.kind == GroupKind::GEMV && g.gemv_mode >= 1) || g.kind == GroupKind::REDUCE;
-  *scan = g.kind == GroupKind::SCAN && g.scan_mode == 0;
+  *scan = g.kind == GroupKind::SCAN;
 }
 
 // Loads a code object and publishes the kernel in the in-memory cache.
@@ -388,7 +388,20 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       s[L.extra] = (uint64_t)g.red_out;
       s[L.extra + 1] = (uint64_t)g.scan_chunk;
       s[L.extra + 3] = (uint64_t)g.scan_nchunk;
-      if (g.scan_mode == 1) return launch(c, k->fn, k->name, (g.red_out + 255) / 256, s);
+      if (g.scan_mode == 1) {
+        // a thread per (line, chunk)
+        const int64_t blocks = (g.red_out * g.scan_nchunk + 255) / 256;
+        if (g.scan_nchunk > 1) {
+          gr_status wst = ensure_workspace(c, (size_t)g.red_out * (size_t)g.scan_nchunk * itemsize(g.out_dtype));
+          if (wst != GR_OK) return wst;
+          s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+          gr_status st = launch(c, k->fn2, "gr_scan_sums", blocks, s);
+          if (st != GR_OK) return st;
+          st = launch(c, k->fn3, "gr_scan_offsets", g.red_out, s);
+          if (st != GR_OK) return st;
+        }
+        return launch(c, k->fn, k->name, blocks, s);
+      }
       if (g.scan_nchunk > 1) {
         gr_status wst = ensure_workspace(c, (size_t)g.red_out * (size_t)g.scan_nchunk * itemsize(g.out_dtype));
         if (wst != GR_OK) return wst;

@@ -65,4 +65,6 @@ DOT_CASES = [
 
 # (shape, axis): inclusive scans along the contiguous axis, along outer axes, over long lines
 SCAN_CASES = [((1000,), 0), ((37, 211), 1), ((37, 211), 0), ((4, 5, 6), 1), ((4, 5, 6), 0), ((4, 5, 6), -1), ((3, 100000), 1),
-              ((1 << 21,), 0), ((5, 1), 1), ((1, 7), 0), ((1,), 0), ((600, 1030), 1), ((2, 5000), 0)]
+              ((1 << 21,), 0), ((5, 1), 1), ((1, 7), 0), ((1,), 0), ((600, 1030), 1), ((2, 5000), 0),
+              # long lines along an axis that is not contiguous: a thread per (line, chunk)
+              ((1000, 300), 0), ((4100, 7), 0), ((3, 2000, 5), 1), ((129, 1), 0), ((70000, 2), 0)]
