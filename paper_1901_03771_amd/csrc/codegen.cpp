@@ -637,7 +637,11 @@ void gen_reduce(Em& e) {
   // cut into NSPLIT chunks; a thread (mode 0) or a workgroup (mode 1) combines one chunk.
   kernel_head(e, kernel_name(g));
   e.o << "  const long long NOUT = " << e.S(e.L.extra) << ", LEN = " << e.S(e.L.extra + 1) << ", NSPLIT = " << e.S(e.L.extra + 3) << ";\n";
-  if (g.red_mode == 0) {
+  if (g.red_mode == 0 && g.red_vec) {
+    e.o << "  const long long blocks_o = (NOUT / 4 + 255) / 256;\n"
+           "  const long long o = 4 * ((long long)(blockIdx.x % blocks_o) * 256 + threadIdx.x), split = blockIdx.x / blocks_o;\n"
+           "  if (o >= NOUT) return;\n";
+  } else if (g.red_mode == 0) {
     e.o << "  const long long blocks_o = (NOUT + 255) / 256;\n"
            "  const long long o = (long long)(blockIdx.x % blocks_o) * 256 + threadIdx.x, split = blockIdx.x / blocks_o;\n"
            "  if (o >= NOUT) return;\n";
@@ -663,6 +667,47 @@ void gen_reduce(Em& e) {
     if (in.dtype == GR_I64) vec = false;
     if (in.kind == IKind::LOAD && !g.groups[in.group].structural_zero[kr] && access_class(g.groups[in.group], kr) != '1') vec = false;
   }
+  if (g.red_mode == 0 && g.red_vec) {
+    // four consecutive outputs per thread: one dwordx4 per array and reduced element
+    const int kd = kr - 1;
+    e.o << "  " << T << " acc1 = acc, acc2 = acc, acc3 = acc;\n#pragma unroll 4\n  for (long long j = jbeg; j < jend; ++j) {\n";
+    if (rank > kr) {
+      e.o << "    long long jrem = j;\n";
+      for (int k = rank - 1; k >= kr; --k) {
+        if (k == kr) e.o << "    const long long i" << k << " = jrem;\n";
+        else e.o << "    const long long i" << k << " = jrem % " << e.dim(k) << "; jrem /= " << e.dim(k) << ";\n";
+      }
+    }
+    for (size_t i = 0; i < g.prog.size(); ++i) {
+      const Instr& in = g.prog[i];
+      if (in.kind != IKind::LOAD) continue;
+      const AccessGroup& ag = g.groups[in.group];
+      std::ostringstream at;
+      at << "p" << in.group << " + 0";
+      for (int k = 0; k < rank; ++k) {
+        if (ag.structural_zero[k]) continue;
+        if (k >= kr) at << " + (i" << k << " + " << in.delta[k] << ") * " << e.coef(in.group, k);
+        else if (in.delta[k]) at << " + " << in.delta[k] << (k == kd ? std::string("") : " * " + e.coef(in.group, k));
+      }
+      if (ag.structural_zero[kd]) e.o << "    const " << cty(in.dtype) << " u" << i << " = (" << at.str() << ")[0];\n";
+      else e.o << "    const " << vty4(in.dtype) << " w" << i << " = " << e.ld(in.group, vty4(in.dtype), at.str()) << ";\n";
+    }
+    for (int c4 = 0; c4 < 4; ++c4) {
+      const std::string pre = "v" + std::to_string(c4) + "_";
+      emit_scalar_program(e, g.prog, {ph.value},
+                          [&](const Instr& in, int id) {
+                            const AccessGroup& ag = g.groups[in.group];
+                            if (ag.structural_zero[kd]) return "u" + std::to_string(id);
+                            return "w" + std::to_string(id) + "[" + std::to_string(c4) + "]";
+                          },
+                          "0.0f", pre, "    ");
+      const std::string a = c4 == 0 ? "acc" : "acc" + std::to_string(c4);
+      e.o << "    " << a << " = " << Em::combine(ph, a, pre + std::to_string(ph.value)) << ";\n";
+    }
+    e.o << "  }\n";
+    e.o << "  GM " << T << "* const dst = NSPLIT > 1 ? (GM " << T << "*)" << e.slot(e.L.extra + 2) << " + split * NOUT : (GM " << T << "*)" << e.slot(e.L.out) << ";\n";
+    e.o << "  dst[o] = acc; dst[o + 1] = acc1; dst[o + 2] = acc2; dst[o + 3] = acc3;\n}\n";
+  } else {
   if (vec) {
     e.o << "  long long j = jbeg + 4 * (long long)threadIdx.x;\n  {\n    " << T << " acc1 = acc, acc2 = acc, acc3 = acc;\n";
     e.o << "#pragma unroll 2\n    for (; j + 4 <= jend; j += 1024) {\n";
@@ -726,6 +771,7 @@ void gen_reduce(Em& e) {
     e.o << "  dst[o] = acc;\n";
   }
   e.o << "}\n";
+  }
   // Stage 2 (Section 3.2: "a separate kernel ... only uses the binary operation"): combines the
   // NSPLIT partial results of every output in a fixed order.
   kernel_head(e, kernel_name(g) + "_combine");
@@ -736,7 +782,13 @@ void gen_reduce(Em& e) {
   e.o << "  if (NOUT >= 1024) {\n"
          "    const long long o = (long long)blockIdx.x * 256 + threadIdx.x;\n"
          "    if (o < NOUT) {\n      " << T << " acc = ws[o];\n"
-         "      for (long long s = 1; s < NSPLIT; ++s) acc = gr_comb0(acc, ws[s * NOUT + o]);\n"
+         "      long long s = 1;\n"
+         "      for (; s + 8 <= NSPLIT; s += 8) {\n"   // eight independent loads in flight, combined in the fixed order
+         "        const " << T << " v0 = ws[s * NOUT + o], v1 = ws[(s + 1) * NOUT + o], v2 = ws[(s + 2) * NOUT + o], v3 = ws[(s + 3) * NOUT + o];\n"
+         "        const " << T << " v4 = ws[(s + 4) * NOUT + o], v5 = ws[(s + 5) * NOUT + o], v6 = ws[(s + 6) * NOUT + o], v7 = ws[(s + 7) * NOUT + o];\n"
+         "        acc = gr_comb0(gr_comb0(gr_comb0(gr_comb0(gr_comb0(gr_comb0(gr_comb0(gr_comb0(acc, v0), v1), v2), v3), v4), v5), v6), v7);\n"
+         "      }\n"
+         "      for (; s < NSPLIT; ++s) acc = gr_comb0(acc, ws[s * NOUT + o]);\n"
          "      out[o] = acc;\n    }\n"
          "  } else {\n"
          "    const long long o = blockIdx.x;\n    " << T << " acc = " << Em::identity(ph) << ";\n"

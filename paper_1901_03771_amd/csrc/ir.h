@@ -175,6 +175,7 @@ struct GroupPlan {
   bool xcd_remap = false;
   int nt = 0;                            // non-temporal load hint: 0 none, 1 arrays read once, 2 all vector loads
   int red_mode = 0;                      // REDUCE: 0 thread-per-output, 1 block-per-output
+  int red_vec = 0;                       // REDUCE mode 0: a thread owns four consecutive outputs (dwordx4 loads)
   int64_t red_out = 0, red_len = 0;      // REDUCE: outputs, reduced elements per output
   int red_kept_rank = 0;
 

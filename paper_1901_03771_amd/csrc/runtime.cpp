@@ -377,7 +377,7 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
         if (wst != GR_OK) return wst;
         s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
       }
-      int64_t units = g.red_mode == 0 ? (g.red_out + 255) / 256 : g.red_out;
+      int64_t units = g.red_mode == 0 ? ((g.red_vec ? g.red_out / 4 : g.red_out) + 255) / 256 : g.red_out;
       gr_status st = launch(c, k->fn, k->name, units * g.slabs, s);
       if (st != GR_OK || g.slabs <= 1) return st;
       return launch(c, k->fn2, k->name + "_combine", g.red_out >= 1024 ? (g.red_out + 255) / 256 : g.red_out, s);
