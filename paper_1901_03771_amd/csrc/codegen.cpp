@@ -841,6 +841,8 @@ void gen_scan(Em& e) {
     e.o << "  const long long LINES = " << e.S(e.L.extra) << ", CH = " << e.S(e.L.extra + 1) << ", NCHUNK = " << e.S(e.L.extra + 3) << ";\n";
     e.o << "  const long long L = " << e.dim(sd) << ";\n";
     if (per_block_line) e.o << "  const long long line = blockIdx.x / NCHUNK, chunk = blockIdx.x % NCHUNK;\n";
+    else if (g.scan_vec) e.o << "  const long long gt = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (gt >= (LINES / 4) * NCHUNK) return;\n"
+                "  const long long line = 4 * (gt % (LINES / 4)), chunk = gt / (LINES / 4);\n  (void)chunk;\n";  // four lines per thread
     else e.o << "  const long long gt = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (gt >= LINES * NCHUNK) return;\n"
                 "  const long long line = gt % LINES, chunk = gt / LINES;\n  (void)chunk;\n";  // neighbouring threads: neighbouring lines
     e.o << "  long long lrem = line;\n";
@@ -899,6 +901,58 @@ void gen_scan(Em& e) {
     e.o << "  for (int u = 0; u < 16; ++u) if (u < per && c0 + u < NCHUNK) { w[c0 + u] = off; off = gr_comb0(off, v[u]); }\n}\n";
   };
 
+  if (g.scan_mode == 1 && g.scan_vec) {
+    // as below with four neighbouring lines per thread: one dwordx4 per array and step
+    const int ld = sd - 1;
+    auto body = [&](bool store) {
+      for (size_t i = 0; i < g.prog.size(); ++i) {
+        const Instr& in = g.prog[i];
+        if (in.kind != IKind::LOAD) continue;
+        const AccessGroup& ag = g.groups[in.group];
+        std::ostringstream at;
+        at << "p" << in.group << " + 0";
+        for (int k = 0; k < sd; ++k) if (!ag.structural_zero[k] && in.delta[k]) at << " + " << in.delta[k] << (k == ld ? std::string("") : " * " + e.coef(in.group, k));
+        if (!ag.structural_zero[sd]) at << " + (j + " << in.delta[sd] << ") * " << e.coef(in.group, sd);
+        if (ag.structural_zero[ld]) e.o << "    const " << cty(in.dtype) << " u" << i << " = (" << at.str() << ")[0];\n";
+        else e.o << "    const " << vty4(in.dtype) << " w" << i << " = " << e.ld(in.group, vty4(in.dtype), at.str()) << ";\n";
+      }
+      for (int c4 = 0; c4 < 4; ++c4) {
+        const std::string pre = "v" + std::to_string(c4) + "_";
+        emit_scalar_program(e, g.prog, {ph.value},
+                            [&](const Instr& in, int id) {
+                              const AccessGroup& ag = g.groups[in.group];
+                              if (ag.structural_zero[ld]) return "u" + std::to_string(id);
+                              return "w" + std::to_string(id) + "[" + std::to_string(c4) + "]";
+                            },
+                            "0.0f", pre, "    ");
+        e.o << "    acc" << c4 << " = " << Em::combine(ph, "acc" + std::to_string(c4), pre + std::to_string(ph.value)) << ";\n";
+      }
+      if (store) {
+        if (ph.out_dtype == GR_I64) e.o << "    po[j * ostep] = acc0; po[j * ostep + 1] = acc1; po[j * ostep + 2] = acc2; po[j * ostep + 3] = acc3;\n";
+        else {
+          const char* vt = ph.out_dtype == GR_F32 ? "f4u" : "i4u";
+          e.o << "    { " << vt << " ov; ov[0] = acc0; ov[1] = acc1; ov[2] = acc2; ov[3] = acc3; *(GM " << vt << "*)(po + j * ostep) = ov; }\n";
+        }
+      }
+    };
+    kernel_head(e, "gr_scan_sums");
+    head(false);
+    e.o << "  const long long cbeg = chunk * CH, cend = (cbeg + CH < L) ? cbeg + CH : L;\n  " << TA << " acc0 = " << ident << ", acc1 = acc0, acc2 = acc0, acc3 = acc0;\n";
+    e.o << "#pragma unroll 4\n  for (long long j = cbeg; j < cend; ++j) {\n";
+    body(false);
+    e.o << "  }\n  ws[line * NCHUNK + chunk] = acc0; ws[(line + 1) * NCHUNK + chunk] = acc1; ws[(line + 2) * NCHUNK + chunk] = acc2; ws[(line + 3) * NCHUNK + chunk] = acc3;\n}\n";
+    offsets_kernel();
+    kernel_head(e, "gr_scan");
+    head(false);
+    e.o << "  const long long cbeg = chunk * CH, cend = (cbeg + CH < L) ? cbeg + CH : L;\n";
+    e.o << "  const long long ostep = " << e.S(e.L.ocoef + sd) << ";\n";
+    e.o << "  " << TA << " acc0 = " << ident << ", acc1 = acc0, acc2 = acc0, acc3 = acc0;\n";
+    e.o << "  if (NCHUNK > 1) { acc0 = ws[line * NCHUNK + chunk]; acc1 = ws[(line + 1) * NCHUNK + chunk]; acc2 = ws[(line + 2) * NCHUNK + chunk]; acc3 = ws[(line + 3) * NCHUNK + chunk]; }\n";
+    e.o << "#pragma unroll 4\n  for (long long j = cbeg; j < cend; ++j) {\n";
+    body(true);
+    e.o << "  }\n}\n";
+    return;
+  }
   if (g.scan_mode == 1) {
     // a thread per (line, chunk), sequential along the axis; with several chunks per line the same
     // three steps as in mode 0: chunk totals, exclusive scan of the totals, chunks with offsets

@@ -184,6 +184,7 @@ struct GroupPlan {
   // axis (it is contiguous), 1 = a thread per line; chunking of long lines
   int64_t out_coef[MAXD] = {0};
   int scan_mode = 0;
+  int scan_vec = 0;   // mode 1: a thread walks four neighbouring lines (dwordx4 per step)
   int64_t scan_chunk = 0;
   int scan_nchunk = 1;
 

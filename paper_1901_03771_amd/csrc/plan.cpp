@@ -404,7 +404,7 @@ void make_signature(GroupPlan* g) {
   for (int64_t v : {(int64_t)g->kind, (int64_t)g->rank, (int64_t)g->out_dtype, (int64_t)g->out_per_row, (int64_t)g->BX, (int64_t)g->BY,
                     (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads, (int64_t)g->xcd_remap, (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
                     (int64_t)g->red_kept_rank, (int64_t)g->gemv_mode, (int64_t)g->LPR, (int64_t)g->KV, (int64_t)g->mat_group,
-                    (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode, (int64_t)g->out_unit, (int64_t)g->groups.size()})
+                    (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode + 16 * (int64_t)g->scan_vec, (int64_t)g->out_unit, (int64_t)g->groups.size()})
     put(s, v);
   for (const AccessGroup& ag : g->groups) {
     int64_t cls = (int64_t)ag.dtype;
@@ -660,6 +660,17 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       g->scan_chunk = chunk;
       g->scan_nchunk = (int)nch;
     }
+    // four neighbouring lines per thread where the innermost line dimension is contiguous in every
+    // array read and in the output, holds a multiple of four, and all values are 32 bits wide
+    g->scan_vec = 0;
+    if (g->scan_mode == 1 && sd >= 1 && g->dims[sd - 1] % 4 == 0 && g->out_coef[sd - 1] == 1 && p.in_dtype != GR_I64) {
+      bool ok = true;
+      for (const AccessGroup& ag : g->groups)
+        if (ag.dtype == GR_I64 || (!ag.structural_zero[sd - 1] && ag.coef[sd - 1] != 1)) ok = false;
+      for (const Instr& in : g->prog) if (in.dtype == GR_I64) ok = false;
+      g->scan_vec = ok ? 1 : 0;
+    }
+    if (g->scan_vec) lines /= 4;   // threads per chunk
     if (g->scan_mode == 1 && lines < 65536 && L >= 128) {
       // few lines, each walked by one thread: cut the lines into chunks so that about 2^17 threads
       // run (chunk totals, scan of the totals, chunks with offsets, as above)
@@ -670,7 +681,7 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       g->scan_chunk = chunk;
       g->scan_nchunk = (int)nch;
     }
-    g->red_out = lines;
+    g->red_out = g->scan_vec ? lines * 4 : lines;
     g->red_len = L;
   } else if (dot && dot->ndim == 2) {
     // ---- matrix-matrix product on the matrix cores, with pointwise epilogue -----------------

@@ -390,7 +390,7 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       s[L.extra + 3] = (uint64_t)g.scan_nchunk;
       if (g.scan_mode == 1) {
         // a thread per (line, chunk)
-        const int64_t blocks = (g.red_out * g.scan_nchunk + 255) / 256;
+        const int64_t blocks = ((g.scan_vec ? g.red_out / 4 : g.red_out) * g.scan_nchunk + 255) / 256;
         if (g.scan_nchunk > 1) {
           gr_status wst = ensure_workspace(c, (size_t)g.red_out * (size_t)g.scan_nchunk * itemsize(g.out_dtype));
           if (wst != GR_OK) return wst;
