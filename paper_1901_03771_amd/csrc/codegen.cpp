@@ -1060,7 +1060,19 @@ void gen_gemv_rowdot(Em& e) {
   else
     e.o << "        for (int j = 0; j < 4; ++j) xv[q][j] = (k0 + j < K) ? Ar[(k0 + j) * ak] : 0.0f;\n";
   e.o << "      }\n#pragma unroll\n      for (int q = 0; q < " << KV << "; ++q)\n#pragma unroll\n        for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(xv[q][j], wv[q][j], acc);\n";
-  e.o << "    } else {\n      for (long long kb = 0; kb < K; kb += " << CH << ") {\n        const long long k0 = kb + lane * 4;\n";
+  e.o << "    } else {\n      long long kb = 0;\n";
+  if (mat_unit && vec_unit) {
+    // long rows: four chunks per step, one dwordx4 of the row and of the vector per chunk and lane
+    // (the vector comes from cache), four independent partial sums
+    e.o << "      float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;\n";
+    e.o << "      for (; kb + " << 4 * CH << " <= K; kb += " << 4 * CH << ") {\n        const long long k0 = kb + lane * 4;\n";
+    for (int q = 0; q < 4; ++q)
+      e.o << "        const f4u x" << q << " = " << e.ld(g.mat_group, "f4u", "Ar + k0 + " + std::to_string(q * CH)) << "; const f4u v" << q << " = *(const GM f4u*)(V + k0 + " << q * CH << ");\n";
+    for (int q = 0; q < 4; ++q)
+      e.o << "        for (int j = 0; j < 4; ++j) a" << q << " = __builtin_fmaf(x" << q << "[j], v" << q << "[j], a" << q << ");\n";
+    e.o << "      }\n      acc = (a0 + a1) + (a2 + a3);\n";
+  }
+  e.o << "      for (; kb < K; kb += " << CH << ") {\n        const long long k0 = kb + lane * 4;\n";
   e.o << "        for (int j = 0; j < 4; ++j) if (k0 + j < K) acc = __builtin_fmaf(Ar[(k0 + j) * ak], V[(k0 + j) * vk], acc);\n      }\n    }\n";
   for (int m = LPR / 2; m > 0; m >>= 1) e.o << "    acc += gr_xor(acc, " << m << ");\n";
   e.o << "    if (lane == 0) {\n";

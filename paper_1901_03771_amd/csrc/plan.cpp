@@ -539,7 +539,10 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
     for (int uc : {4, 2}) if (tiles(1, uc) >= 2048) { g->UC = uc; break; }
   } else {
     int want = 4;  // measured on MI355X: 4 rows per lane is the best patch for broadcast and stencil programs alike
-    for (int vr = want; vr >= 2; vr >>= 1) if (tiles(vr, 1) >= 1024 || (shifted_rows && tiles(vr, 1) >= 256)) { g->VR = vr; break; }
+    // (lanes whose patch sticks out of the array take the guarded point-by-point path: with few
+    // rows the patch height has to divide them)
+    for (int vr = want; vr >= 2; vr >>= 1)
+      if ((R % vr == 0 || R >= 16 * vr) && (tiles(vr, 1) >= 1024 || (shifted_rows && tiles(vr, 1) >= 256))) { g->VR = vr; break; }
   }
   if (c->opt_map_rows > 0 && g->rank >= 2) g->VR = (int)std::min<int64_t>(c->opt_map_rows, 16);
   if (c->opt_map_chunks > 0) g->UC = (int)std::min<int64_t>(c->opt_map_chunks, 8);
@@ -671,10 +674,11 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       g->scan_vec = ok ? 1 : 0;
     }
     if (g->scan_vec) lines /= 4;   // threads per chunk
-    if (g->scan_mode == 1 && lines < 65536 && L >= 128) {
-      // few lines, each walked by one thread: cut the lines into chunks so that about 2^17 threads
-      // run (chunk totals, scan of the totals, chunks with offsets, as above)
-      int64_t want = std::max<int64_t>(1, 131072 / std::max<int64_t>(lines, 1));
+    if (g->scan_mode == 1 && lines < 262144 && L >= 128) {
+      // few lines, each walked by one thread: cut the lines into chunks so that about 2^19 threads
+      // run (chunk totals, scan of the totals, chunks with offsets, as above); a thread has only a
+      // few loads in flight, so it takes this many to keep HBM busy
+      int64_t want = std::max<int64_t>(1, 524288 / std::max<int64_t>(lines, 1));
       int64_t chunk = std::max<int64_t>(32, (L + want - 1) / want);
       int64_t nch = (L + chunk - 1) / chunk;
       if (nch > 4096) { chunk = (L + 4095) / 4096; nch = (L + chunk - 1) / chunk; }
