@@ -73,6 +73,7 @@ ArgLayout arg_layout(const GroupPlan& g) {
   s += 4;
   L.ocoef = s;
   if (g.kind == GroupKind::SCAN || g.kind == GroupKind::MAP) s += g.rank;
+  if (g.kind == GroupKind::GEMM) s += 2;  // split-K: workspace pointer, k extent of one split
   L.obase = s;
   if (g.kind == GroupKind::MAP) s += 1;
   L.total = s;
@@ -1216,8 +1217,14 @@ void gen_gemm(Em& e) {
   e.o << "  __shared__ float As[2][16][132];\n  __shared__ float Bs[2][16][132];\n";
   e.o << "  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;\n";
   e.o << "  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64, l32 = lane & 31, lh = lane >> 5;\n";
-  e.o << "  const long long tiles_n = (N + 127) / 128;\n";
-  e.o << "  const long long bm0 = (long long)(blockIdx.x / tiles_n) * 128, bn0 = (long long)(blockIdx.x % tiles_n) * 128;\n";
+  // split-K for products with few output tiles: workgroup (tile, split) accumulates k in
+  // [kbeg, KE) and leaves its partial tile in a workspace; gr_gemm_combine adds the partial tiles
+  // in a fixed order and applies the epilogue (the two-kernel reduction of Section 3.2)
+  e.o << "  const long long NSPLIT = " << e.S(e.L.extra + 3) << ", KCH = " << e.S(e.L.ocoef + 1) << ";\n";
+  e.o << "  const long long tiles_n = (N + 127) / 128, tiles = tiles_n * ((M + 127) / 128);\n";
+  e.o << "  const long long tile = blockIdx.x % tiles, split = blockIdx.x / tiles;\n";
+  e.o << "  const long long bm0 = (tile / tiles_n) * 128, bn0 = (tile % tiles_n) * 128;\n";
+  e.o << "  const long long kbeg = split * KCH, KE = (kbeg + KCH < K) ? kbeg + KCH : K;\n";
   e.o << "  f16v acc[2][2];\n  for (int i = 0; i < 2; ++i) for (int j = 0; j < 2; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n";
   e.o << "  float ra[8], rb[8];\n";
   // --- global -> registers: a guarded version for edge tiles and the K tail, and an unguarded one
@@ -1227,32 +1234,32 @@ void gen_gemm(Em& e) {
     e.o << "  auto fetch" << (guarded ? "_g" : "_u") << " = [&](long long k0) {\n";
     if (a_mode == 0) {
       e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long row = bm0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n";
-      if (guarded) e.o << "      if (row < M && kk + 4 <= K) { const f4u w = *(const GM f4u*)(A + row * am + kk); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
-                          "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (row < M && kk + j < K) ? A[row * am + kk + j] : 0.0f; }\n    }\n";
+      if (guarded) e.o << "      if (row < M && kk + 4 <= KE) { const f4u w = *(const GM f4u*)(A + row * am + kk); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
+                          "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (row < M && kk + j < KE) ? A[row * am + kk + j] : 0.0f; }\n    }\n";
       else e.o << "      const f4u w = *(const GM f4u*)(A + row * am + kk); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3];\n    }\n";
     } else if (a_mode == 1) {
       e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, row = bm0 + (tid % 32) * 4;\n";
-      if (guarded) e.o << "      if (kk < K && row + 4 <= M) { const f4u w = *(const GM f4u*)(A + kk * ak + row); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
-                          "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (kk < K && row + j < M) ? A[kk * ak + row + j] : 0.0f; }\n    }\n";
+      if (guarded) e.o << "      if (kk < KE && row + 4 <= M) { const f4u w = *(const GM f4u*)(A + kk * ak + row); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
+                          "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (kk < KE && row + j < M) ? A[kk * ak + row + j] : 0.0f; }\n    }\n";
       else e.o << "      const f4u w = *(const GM f4u*)(A + kk * ak + row); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3];\n    }\n";
     } else {
       e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; const long long row = bm0 + el % 128, kk = k0 + el / 128;\n";
-      if (guarded) e.o << "      ra[i] = (row < M && kk < K) ? A[row * am + kk * ak] : 0.0f; }\n";
+      if (guarded) e.o << "      ra[i] = (row < M && kk < KE) ? A[row * am + kk * ak] : 0.0f; }\n";
       else e.o << "      ra[i] = A[row * am + kk * ak]; }\n";
     }
     if (b_mode == 0) {
       e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, col = bn0 + (tid % 32) * 4;\n";
-      if (guarded) e.o << "      if (kk < K && col + 4 <= N) { const f4u w = *(const GM f4u*)(B + kk * bk + col); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
-                          "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (kk < K && col + j < N) ? B[kk * bk + col + j] : 0.0f; }\n    }\n";
+      if (guarded) e.o << "      if (kk < KE && col + 4 <= N) { const f4u w = *(const GM f4u*)(B + kk * bk + col); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
+                          "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (kk < KE && col + j < N) ? B[kk * bk + col + j] : 0.0f; }\n    }\n";
       else e.o << "      const f4u w = *(const GM f4u*)(B + kk * bk + col); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3];\n    }\n";
     } else if (b_mode == 1) {
       e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long col = bn0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n";
-      if (guarded) e.o << "      if (col < N && kk + 4 <= K) { const f4u w = *(const GM f4u*)(B + col * bn + kk); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
-                          "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (col < N && kk + j < K) ? B[col * bn + kk + j] : 0.0f; }\n    }\n";
+      if (guarded) e.o << "      if (col < N && kk + 4 <= KE) { const f4u w = *(const GM f4u*)(B + col * bn + kk); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
+                          "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (col < N && kk + j < KE) ? B[col * bn + kk + j] : 0.0f; }\n    }\n";
       else e.o << "      const f4u w = *(const GM f4u*)(B + col * bn + kk); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3];\n    }\n";
     } else {
       e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; const long long col = bn0 + el % 128, kk = k0 + el / 128;\n";
-      if (guarded) e.o << "      rb[i] = (col < N && kk < K) ? B[kk * bk + col * bn] : 0.0f; }\n";
+      if (guarded) e.o << "      rb[i] = (col < N && kk < KE) ? B[kk * bk + col * bn] : 0.0f; }\n";
       else e.o << "      rb[i] = B[kk * bk + col * bn]; }\n";
     }
     e.o << "  };\n";
@@ -1274,19 +1281,23 @@ void gen_gemm(Em& e) {
          "      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);\n"
          "      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);\n"
          "      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);\n    }\n  };\n";
-  e.o << "  const long long nkt = (K + 15) / 16;\n  int cur = 0;\n";
+  e.o << "  const long long nkt = KE > kbeg ? (KE - kbeg + 15) / 16 : 0;\n  int cur = 0;\n";
   // the workgroup-uniform choice between the two loops
-  e.o << "  if (bm0 + 128 <= M && bn0 + 128 <= N && K % 16 == 0) {\n"
-         "    if (nkt > 0) { fetch_u(0); stash(0); }\n    __syncthreads();\n"
-         "    for (long long kt = 0; kt < nkt; ++kt) {\n      if (kt + 1 < nkt) fetch_u((kt + 1) * 16);\n      step(cur);\n"
+  e.o << "  if (bm0 + 128 <= M && bn0 + 128 <= N && (KE - kbeg) % 16 == 0) {\n"
+         "    if (nkt > 0) { fetch_u(kbeg); stash(0); }\n    __syncthreads();\n"
+         "    for (long long kt = 0; kt < nkt; ++kt) {\n      if (kt + 1 < nkt) fetch_u(kbeg + (kt + 1) * 16);\n      step(cur);\n"
          "      if (kt + 1 < nkt) stash(cur ^ 1);\n      __syncthreads();\n      cur ^= 1;\n    }\n"
          "  } else {\n"
-         "    if (nkt > 0) { fetch_g(0); stash(0); }\n    __syncthreads();\n"
-         "    for (long long kt = 0; kt < nkt; ++kt) {\n      if (kt + 1 < nkt) fetch_g((kt + 1) * 16);\n      step(cur);\n"
+         "    if (nkt > 0) { fetch_g(kbeg); stash(0); }\n    __syncthreads();\n"
+         "    for (long long kt = 0; kt < nkt; ++kt) {\n      if (kt + 1 < nkt) fetch_g(kbeg + (kt + 1) * 16);\n      step(cur);\n"
          "      if (kt + 1 < nkt) stash(cur ^ 1);\n      __syncthreads();\n      cur ^= 1;\n    }\n"
          "  }\n";
   // --- epilogue on the accumulators: element q of a 32x32 block sits at row 8*(q/4) + 4*(lane/32) + q%4, column lane%32
   e.o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
+  e.o << "  if (NSPLIT > 1) {\n    GM float* const ws = (GM float*)" << e.slot(e.L.ocoef) << " + split * M * N;\n"
+         "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 2; ++j)\n#pragma unroll\n      for (int q = 0; q < 16; ++q) {\n"
+         "        const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4), col = bn0 + wn + 32 * j + l32;\n"
+         "        if (row < M && col < N) ws[row * N + col] = acc[i][j][q];\n      }\n    return;\n  }\n";
   e.o << "  for (int i = 0; i < 2; ++i) for (int j = 0; j < 2; ++j)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
          "      const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4), col = bn0 + wn + 32 * j + l32;\n"
          "      if (row < M && col < N) {\n        const float cacc = acc[i][j][q];\n";
@@ -1302,6 +1313,31 @@ void gen_gemm(Em& e) {
                       },
                       "cacc", "t", "        ");
   e.o << "        out[row * N + col] = t" << g.results[0] << ";\n      }\n    }\n}\n";
+  // second stage of a split product: partial tiles added in split order, then the epilogue
+  kernel_head(e, "gr_gemm_combine");
+  e.o << "  const long long M = " << e.S(e.L.extra) << ", N = " << e.S(e.L.extra + 1) << ", NSPLIT = " << e.S(e.L.extra + 3) << ";\n";
+  e.o << "  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (idx >= M * N) return;\n";
+  e.o << "  const long long row = idx / N, col = idx % N;\n";
+  e.o << "  const GM float* const ws = (const GM float*)" << e.slot(e.L.ocoef) << ";\n";
+  e.o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
+  group_pointers(e, "  ", {g.mat_group, g.vec_group});
+  e.o << "  float cacc = ws[idx];\n  long long s = 1;\n"
+         "  for (; s + 4 <= NSPLIT; s += 4) {\n"
+         "    const float v0 = ws[s * M * N + idx], v1 = ws[(s + 1) * M * N + idx], v2 = ws[(s + 2) * M * N + idx], v3 = ws[(s + 3) * M * N + idx];\n"
+         "    cacc = (((cacc + v0) + v1) + v2) + v3;\n  }\n"
+         "  for (; s < NSPLIT; ++s) cacc += ws[s * M * N + idx];\n";
+  emit_scalar_program(e, g.prog, g.results,
+                      [&](const Instr& in, int) {
+                        const AccessGroup& eg = g.groups[in.group];
+                        std::ostringstream s2;
+                        s2 << e.qp << in.group << "[0";
+                        if (!eg.structural_zero[0]) s2 << " + (row + " << in.delta[0] << ") * " << e.coef(in.group, 0);
+                        if (!eg.structural_zero[1]) s2 << " + (col + " << in.delta[1] << ") * " << e.coef(in.group, 1);
+                        s2 << "]";
+                        return s2.str();
+                      },
+                      "cacc", "t", "  ");
+  e.o << "  out[idx] = t" << g.results[0] << ";\n}\n";
 }
 
 }  // namespace

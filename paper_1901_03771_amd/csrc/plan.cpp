@@ -726,6 +726,16 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     g->rank = 2;
     g->dims[0] = g->M; g->dims[1] = g->N;
     g->collapse_to[0] = 0; g->collapse_to[1] = 1;
+    // few output tiles and a long contraction: split K over workgroups (about 512 of them, at
+    // least 128 k per split); the partial tiles are combined by a second kernel
+    g->slabs = 1;
+    {
+      const int64_t tiles = ((g->M + 127) / 128) * ((g->N + 127) / 128);
+      if (tiles > 0 && tiles < 192 && g->K >= 256) {
+        int64_t ks = std::min<int64_t>(512 / tiles, g->K / 128);
+        if (ks >= 2) g->slabs = (int)std::min<int64_t>(ks, 256);
+      }
+    }
   } else if (dot) {
     // ---- contraction with pointwise epilogue ------------------------------
     g->kind = GroupKind::GEMV;
@@ -916,7 +926,9 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       int64_t C = g->dims[g->rank - 1];
       // few vec4 positions per lane keep the register count low and the occupancy high
       // (measured on MI355X for 4096-float rows: 256 lanes 93 us, 128 lanes 96 us, 64 lanes 104 us)
-      g->row_threads = C <= 256 ? 16 : (C <= 1024 ? 64 : (C <= 2048 ? 128 : 256));
+      // lanes per row: enough for one to four dwordx4 positions per lane; very short rows share a
+      // wave between many rows instead of leaving most of 16 lanes idle
+      g->row_threads = C <= 4 ? 1 : (C <= 8 ? 2 : (C <= 16 ? 4 : (C <= 32 ? 8 : (C <= 256 ? 16 : (C <= 1024 ? 64 : (C <= 2048 ? 128 : 256))))));
       if (c->opt_rowred_threads == 16 || c->opt_rowred_threads == 64 || c->opt_rowred_threads == 128 || c->opt_rowred_threads == 256)
         if (C <= c->opt_rowred_threads * 64) g->row_threads = (int)c->opt_rowred_threads;  // at most 16 positions per lane
       g->NP = (int)std::max<int64_t>(1, (C + (int64_t)g->row_threads * 4 - 1) / ((int64_t)g->row_threads * 4));

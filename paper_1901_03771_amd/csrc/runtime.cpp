@@ -161,7 +161,7 @@ static void disk_store(const std::string& path, const std::string& sig, const st
 // job can be collected without the plan that started it.
 static void kernel_entry_points(const GroupPlan& g, std::string* name, bool* combine, bool* scan) {
   *name = kernel_name(g);
-  *combine = (g.kind == GroupKind::GEMV && g.gemv_mode >= 1) || g.kind == GroupKind::REDUCE;
+  *combine = (g.kind == GroupKind::GEMV && g.gemv_mode >= 1) || g.kind == GroupKind::REDUCE || g.kind == GroupKind::GEMM;
   *scan = g.kind == GroupKind::SCAN;
 }
 
@@ -418,7 +418,20 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       s[L.extra] = (uint64_t)g.M;
       s[L.extra + 1] = (uint64_t)g.N;
       s[L.extra + 2] = (uint64_t)g.K;
-      return launch(c, k->fn, k->name, ((g.M + 127) / 128) * ((g.N + 127) / 128), s);
+      const int64_t tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128);
+      const int64_t nsplit = std::max(1, g.slabs);
+      // k extent of one split: a multiple of 16 that covers K in nsplit pieces
+      const int64_t kch = nsplit > 1 ? (((g.K + nsplit - 1) / nsplit + 15) / 16) * 16 : g.K;
+      s[L.extra + 3] = (uint64_t)nsplit;
+      s[L.ocoef + 1] = (uint64_t)std::max<int64_t>(kch, 1);
+      if (nsplit > 1) {
+        gr_status wst = ensure_workspace(c, (size_t)nsplit * (size_t)g.M * (size_t)g.N * sizeof(float));
+        if (wst != GR_OK) return wst;
+        s[L.ocoef] = (uint64_t)(uintptr_t)c->workspace;
+      }
+      gr_status st = launch(c, k->fn, k->name, tiles * nsplit, s);
+      if (st != GR_OK || nsplit <= 1) return st;
+      return launch(c, k->fn2, k->name + "_combine", (g.M * g.N + 255) / 256, s);
     }
     case GroupKind::GEMV: {
       if (g.M == 0) return GR_OK;
