@@ -1206,6 +1206,12 @@ void gen_gemm(Em& e) {
   const AccessGroup& bg = g.groups[g.vec_group];
   const int a_mode = ag.coef[1] == 1 ? 0 : (ag.coef[0] == 1 ? 1 : 2);  // 0: k contiguous, 1: m contiguous, 2: neither
   const int b_mode = bg.coef[1] == 1 ? 0 : (bg.coef[0] == 1 ? 1 : 2);  // 0: n contiguous, 1: k contiguous, 2: neither
+  // Tile of C per workgroup: 128 x 128 (four waves, each a 64 x 64 quarter as 2 x 2 matrix-core
+  // blocks), or 128 x 32 for products with at most 32 columns (each wave one 32 x 32 block of its
+  // own 32 rows): a 128-wide tile would spend the matrix cores on columns that do not exist.
+  const int BN = g.BX == 32 ? 32 : 128;
+  const int IB = BN == 128 ? 2 : 1, JB = IB;   // 32 x 32 blocks per wave along m and n
+  const int BP = BN + 4;                        // padded LDS row of the B tile
   prelude(e);
   e.o << "typedef float f16v __attribute__((ext_vector_type(16)));\n";
   kernel_head(e, "gr_gemm");
@@ -1214,24 +1220,25 @@ void gen_gemm(Em& e) {
   e.o << "  const GM float* const A = q" << g.mat_group << "; const GM float* const B = q" << g.vec_group << ";\n";
   e.o << "  const long long am = " << e.coef(g.mat_group, 0) << ", ak = " << e.coef(g.mat_group, 1) << ", bk = " << e.coef(g.vec_group, 0)
       << ", bn = " << e.coef(g.vec_group, 1) << ";\n  (void)am; (void)ak; (void)bk; (void)bn;\n";
-  e.o << "  __shared__ float As[2][16][132];\n  __shared__ float Bs[2][16][132];\n";
+  e.o << "  __shared__ float As[2][16][132];\n  __shared__ float Bs[2][16][" << BP << "];\n";
   e.o << "  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;\n";
-  e.o << "  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64, l32 = lane & 31, lh = lane >> 5;\n";
+  if (BN == 128) e.o << "  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64, l32 = lane & 31, lh = lane >> 5;\n";
+  else e.o << "  const int wm = wave * 32, wn = 0, l32 = lane & 31, lh = lane >> 5;\n";
   // split-K for products with few output tiles: workgroup (tile, split) accumulates k in
   // [kbeg, KE) and leaves its partial tile in a workspace; gr_gemm_combine adds the partial tiles
   // in a fixed order and applies the epilogue (the two-kernel reduction of Section 3.2)
   e.o << "  const long long NSPLIT = " << e.S(e.L.extra + 3) << ", KCH = " << e.S(e.L.ocoef + 1) << ";\n";
-  e.o << "  const long long tiles_n = (N + 127) / 128, tiles = tiles_n * ((M + 127) / 128);\n";
+  e.o << "  const long long tiles_n = (N + " << BN - 1 << ") / " << BN << ", tiles = tiles_n * ((M + 127) / 128);\n";
   e.o << "  const long long tile = blockIdx.x % tiles, split = blockIdx.x / tiles;\n";
-  e.o << "  const long long bm0 = (tile / tiles_n) * 128, bn0 = (tile % tiles_n) * 128;\n";
+  e.o << "  const long long bm0 = (tile / tiles_n) * 128, bn0 = (tile % tiles_n) * " << BN << ";\n";
   e.o << "  const long long kbeg = split * KCH, KE = (kbeg + KCH < K) ? kbeg + KCH : K;\n";
-  e.o << "  f16v acc[2][2];\n  for (int i = 0; i < 2; ++i) for (int j = 0; j < 2; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n";
-  e.o << "  float ra[8], rb[8];\n";
-  // --- global -> registers: a guarded version for edge tiles and the K tail, and an unguarded one
-  // for tiles that lie completely inside both operands (straight-line loads the compiler can keep
-  // in flight under the matrix instructions of the previous step)
+  e.o << "  f16v acc[" << IB << "][" << JB << "];\n  for (int i = 0; i < " << IB << "; ++i) for (int j = 0; j < " << JB << "; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n";
+  e.o << "  float ra[8], rb[8];\n  (void)rb;\n";
+  // --- global -> registers, per operand a guarded version (edge tiles, K tail) and an unguarded
+  // one for tiles that lie inside the operand: straight-line loads that the compiler keeps in
+  // flight under the matrix instructions of the previous step
   for (int guarded = 1; guarded >= 0; --guarded) {
-    e.o << "  auto fetch" << (guarded ? "_g" : "_u") << " = [&](long long k0) {\n";
+    e.o << "  auto fetchA" << (guarded ? "_g" : "_u") << " = [&](long long k0) {\n";
     if (a_mode == 0) {
       e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long row = bm0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n";
       if (guarded) e.o << "      if (row < M && kk + 4 <= KE) { const f4u w = *(const GM f4u*)(A + row * am + kk); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
@@ -1247,7 +1254,13 @@ void gen_gemm(Em& e) {
       if (guarded) e.o << "      ra[i] = (row < M && kk < KE) ? A[row * am + kk * ak] : 0.0f; }\n";
       else e.o << "      ra[i] = A[row * am + kk * ak]; }\n";
     }
-    if (b_mode == 0) {
+    e.o << "  };\n";
+    e.o << "  auto fetchB" << (guarded ? "_g" : "_u") << " = [&](long long k0) {\n";
+    if (BN == 32) {
+      // 16 x 32 tile: two elements per thread, always guarded (the operand is small)
+      e.o << "    for (int i = 0; i < 2; ++i) { const int el = tid + 256 * i; const long long col = bn0 + el % 32, kk = k0 + el / 32;\n"
+             "      rb[i] = (col < N && kk < KE) ? B[kk * bk + col * bn] : 0.0f; }\n";
+    } else if (b_mode == 0) {
       e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, col = bn0 + (tid % 32) * 4;\n";
       if (guarded) e.o << "      if (kk < KE && col + 4 <= N) { const f4u w = *(const GM f4u*)(B + kk * bk + col); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
                           "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (kk < KE && col + j < N) ? B[kk * bk + col + j] : 0.0f; }\n    }\n";
@@ -1269,49 +1282,61 @@ void gen_gemm(Em& e) {
   if (a_mode == 0) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) As[buf][(tid % 4) * 4 + j][tid / 4 + 64 * i] = ra[4*i+j];\n";
   else if (a_mode == 1) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) As[buf][tid / 32 + 8 * i][(tid % 32) * 4 + j] = ra[4*i+j];\n";
   else e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; As[buf][el / 128][el % 128] = ra[i]; }\n";
-  if (b_mode == 0) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) Bs[buf][tid / 32 + 8 * i][(tid % 32) * 4 + j] = rb[4*i+j];\n";
+  if (BN == 32) e.o << "    for (int i = 0; i < 2; ++i) { const int el = tid + 256 * i; Bs[buf][el / 32][el % 32] = rb[i]; }\n";
+  else if (b_mode == 0) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) Bs[buf][tid / 32 + 8 * i][(tid % 32) * 4 + j] = rb[4*i+j];\n";
   else if (b_mode == 1) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) Bs[buf][(tid % 4) * 4 + j][tid / 4 + 64 * i] = rb[4*i+j];\n";
   else e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; Bs[buf][el / 128][el % 128] = rb[i]; }\n";
   e.o << "  };\n";
-  e.o << "  auto step = [&](int cur) {\n"
-         "#pragma unroll\n    for (int ks = 0; ks < 8; ++ks) {\n"
-         "      const float a0 = As[cur][2 * ks + lh][wm + l32], a1 = As[cur][2 * ks + lh][wm + 32 + l32];\n"
-         "      const float b0 = Bs[cur][2 * ks + lh][wn + l32], b1 = Bs[cur][2 * ks + lh][wn + 32 + l32];\n"
-         "      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);\n"
-         "      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);\n"
-         "      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);\n"
-         "      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);\n    }\n  };\n";
+  e.o << "  auto step = [&](int cur) {\n#pragma unroll\n    for (int ks = 0; ks < 8; ++ks) {\n";
+  if (BN == 128)
+    e.o << "      const float a0 = As[cur][2 * ks + lh][wm + l32], a1 = As[cur][2 * ks + lh][wm + 32 + l32];\n"
+           "      const float b0 = Bs[cur][2 * ks + lh][wn + l32], b1 = Bs[cur][2 * ks + lh][wn + 32 + l32];\n"
+           "      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);\n"
+           "      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);\n"
+           "      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);\n"
+           "      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);\n    }\n  };\n";
+  else
+    e.o << "      const float a0 = As[cur][2 * ks + lh][wm + l32];\n"
+           "      const float b0 = Bs[cur][2 * ks + lh][l32];\n"
+           "      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);\n    }\n  };\n";
   e.o << "  const long long nkt = KE > kbeg ? (KE - kbeg + 15) / 16 : 0;\n  int cur = 0;\n";
-  // the workgroup-uniform choice between the two loops
-  e.o << "  if (bm0 + 128 <= M && bn0 + 128 <= N && (KE - kbeg) % 16 == 0) {\n"
-         "    if (nkt > 0) { fetch_u(kbeg); stash(0); }\n    __syncthreads();\n"
-         "    for (long long kt = 0; kt < nkt; ++kt) {\n      if (kt + 1 < nkt) fetch_u(kbeg + (kt + 1) * 16);\n      step(cur);\n"
-         "      if (kt + 1 < nkt) stash(cur ^ 1);\n      __syncthreads();\n      cur ^= 1;\n    }\n"
-         "  } else {\n"
-         "    if (nkt > 0) { fetch_g(kbeg); stash(0); }\n    __syncthreads();\n"
-         "    for (long long kt = 0; kt < nkt; ++kt) {\n      if (kt + 1 < nkt) fetch_g(kbeg + (kt + 1) * 16);\n      step(cur);\n"
-         "      if (kt + 1 < nkt) stash(cur ^ 1);\n      __syncthreads();\n      cur ^= 1;\n    }\n"
-         "  }\n";
+  // workgroup-uniform choice between four loops: each operand unguarded where its tile is interior
+  e.o << "  const bool kfull = (KE - kbeg) % 16 == 0, a_in = kfull && bm0 + 128 <= M, b_in = kfull && bn0 + " << BN << " <= N;\n";
+  auto loop = [&](const char* fa, const char* fb, const char* ind) {
+    e.o << ind << "if (nkt > 0) { " << fa << "(kbeg); " << fb << "(kbeg); stash(0); }\n" << ind << "__syncthreads();\n"
+        << ind << "for (long long kt = 0; kt < nkt; ++kt) {\n"
+        << ind << "  if (kt + 1 < nkt) { " << fa << "(kbeg + (kt + 1) * 16); " << fb << "(kbeg + (kt + 1) * 16); }\n"
+        << ind << "  step(cur);\n"
+        << ind << "  if (kt + 1 < nkt) stash(cur ^ 1);\n" << ind << "  __syncthreads();\n" << ind << "  cur ^= 1;\n" << ind << "}\n";
+  };
+  e.o << "  if (a_in && b_in) {\n";
+  loop("fetchA_u", "fetchB_u", "    ");
+  e.o << "  } else if (a_in) {\n";
+  loop("fetchA_u", "fetchB_g", "    ");
+  e.o << "  } else if (b_in) {\n";
+  loop("fetchA_g", "fetchB_u", "    ");
+  e.o << "  } else {\n";
+  loop("fetchA_g", "fetchB_g", "    ");
+  e.o << "  }\n";
   // --- epilogue on the accumulators: element q of a 32x32 block sits at row 8*(q/4) + 4*(lane/32) + q%4, column lane%32
   e.o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
   e.o << "  if (NSPLIT > 1) {\n    GM float* const ws = (GM float*)" << e.slot(e.L.ocoef) << " + split * M * N;\n"
-         "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 2; ++j)\n#pragma unroll\n      for (int q = 0; q < 16; ++q) {\n"
+         "    for (int i = 0; i < " << IB << "; ++i) for (int j = 0; j < " << JB << "; ++j)\n#pragma unroll\n      for (int q = 0; q < 16; ++q) {\n"
          "        const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4), col = bn0 + wn + 32 * j + l32;\n"
          "        if (row < M && col < N) ws[row * N + col] = acc[i][j][q];\n      }\n    return;\n  }\n";
-  e.o << "  for (int i = 0; i < 2; ++i) for (int j = 0; j < 2; ++j)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
+  e.o << "  for (int i = 0; i < " << IB << "; ++i) for (int j = 0; j < " << JB << "; ++j)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
          "      const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4), col = bn0 + wn + 32 * j + l32;\n"
          "      if (row < M && col < N) {\n        const float cacc = acc[i][j][q];\n";
-  emit_scalar_program(e, g.prog, g.results,
-                      [&](const Instr& in, int) {
-                        const AccessGroup& eg = g.groups[in.group];
-                        std::ostringstream s2;
-                        s2 << e.qp << in.group << "[0";
-                        if (!eg.structural_zero[0]) s2 << " + (row + " << in.delta[0] << ") * " << e.coef(in.group, 0);
-                        if (!eg.structural_zero[1]) s2 << " + (col + " << in.delta[1] << ") * " << e.coef(in.group, 1);
-                        s2 << "]";
-                        return s2.str();
-                      },
-                      "cacc", "t", "        ");
+  auto epi_load = [&](const Instr& in, int) {
+    const AccessGroup& eg = g.groups[in.group];
+    std::ostringstream s2;
+    s2 << e.qp << in.group << "[0";
+    if (!eg.structural_zero[0]) s2 << " + (row + " << in.delta[0] << ") * " << e.coef(in.group, 0);
+    if (!eg.structural_zero[1]) s2 << " + (col + " << in.delta[1] << ") * " << e.coef(in.group, 1);
+    s2 << "]";
+    return s2.str();
+  };
+  emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
   e.o << "        out[row * N + col] = t" << g.results[0] << ";\n      }\n    }\n}\n";
   // second stage of a split product: partial tiles added in split order, then the epilogue
   kernel_head(e, "gr_gemm_combine");
@@ -1326,17 +1351,7 @@ void gen_gemm(Em& e) {
          "    const float v0 = ws[s * M * N + idx], v1 = ws[(s + 1) * M * N + idx], v2 = ws[(s + 2) * M * N + idx], v3 = ws[(s + 3) * M * N + idx];\n"
          "    cacc = (((cacc + v0) + v1) + v2) + v3;\n  }\n"
          "  for (; s < NSPLIT; ++s) cacc += ws[s * M * N + idx];\n";
-  emit_scalar_program(e, g.prog, g.results,
-                      [&](const Instr& in, int) {
-                        const AccessGroup& eg = g.groups[in.group];
-                        std::ostringstream s2;
-                        s2 << e.qp << in.group << "[0";
-                        if (!eg.structural_zero[0]) s2 << " + (row + " << in.delta[0] << ") * " << e.coef(in.group, 0);
-                        if (!eg.structural_zero[1]) s2 << " + (col + " << in.delta[1] << ") * " << e.coef(in.group, 1);
-                        s2 << "]";
-                        return s2.str();
-                      },
-                      "cacc", "t", "  ");
+  emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "  ");
   e.o << "  out[idx] = t" << g.results[0] << ";\n}\n";
 }
 

@@ -729,8 +729,9 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     // few output tiles and a long contraction: split K over workgroups (about 512 of them, at
     // least 128 k per split); the partial tiles are combined by a second kernel
     g->slabs = 1;
+    g->BX = g->N <= 32 ? 32 : 128;  // columns of the output tile of one workgroup
     {
-      const int64_t tiles = ((g->M + 127) / 128) * ((g->N + 127) / 128);
+      const int64_t tiles = ((g->M + 127) / 128) * ((g->N + g->BX - 1) / g->BX);
       if (tiles > 0 && tiles < 192 && g->K >= 256) {
         int64_t ks = std::min<int64_t>(512 / tiles, g->K / 128);
         if (ks >= 2) g->slabs = (int)std::min<int64_t>(ks, 256);
