@@ -662,12 +662,16 @@ void gen_reduce(Em& e) {
   e.o << "  " << T << " acc = " << Em::identity(ph) << ";\n";
   // mode 1 over one contiguous reduced dimension: lanes take four consecutive elements with one
   // dwordx4 per array and keep four partial results; the ragged end goes through the scalar loop
-  bool vec = g.red_mode == 1 && rank == kr + 1;
+  // (several reduced dimensions: the same when the innermost one holds a multiple of four, so that
+  // four consecutive elements never straddle it; chunks are then cut at multiples of four)
+  const int rd = rank - 1;
+  bool vec = g.red_mode == 1 && rank > kr && (rank == kr + 1 || g.red_vec);
   for (size_t i = 0; vec && i < g.prog.size(); ++i) {
     const Instr& in = g.prog[i];
     if (in.dtype == GR_I64) vec = false;
-    if (in.kind == IKind::LOAD && !g.groups[in.group].structural_zero[kr] && access_class(g.groups[in.group], kr) != '1') vec = false;
+    if (in.kind == IKind::LOAD && !g.groups[in.group].structural_zero[rd] && access_class(g.groups[in.group], rd) != '1') vec = false;
   }
+  if (vec && rank > kr + 1) e.o << "  const long long chunk4 = (chunk + 3) / 4 * 4, jbeg4 = split * chunk4, jend4 = (jbeg4 + chunk4 < LEN) ? jbeg4 + chunk4 : LEN;\n";
   if (g.red_mode == 0 && g.red_vec) {
     // four consecutive outputs per thread: one dwordx4 per array and reduced element
     const int kd = kr - 1;
@@ -710,24 +714,39 @@ void gen_reduce(Em& e) {
     e.o << "  dst[o] = acc; dst[o + 1] = acc1; dst[o + 2] = acc2; dst[o + 3] = acc3;\n}\n";
   } else {
   if (vec) {
-    e.o << "  long long j = jbeg + 4 * (long long)threadIdx.x;\n  {\n    " << T << " acc1 = acc, acc2 = acc, acc3 = acc;\n";
-    e.o << "#pragma unroll 2\n    for (; j + 4 <= jend; j += 1024) {\n";
+    const bool multi = rank > kr + 1;
+    const char* jb = multi ? "jbeg4" : "jbeg";
+    const char* je = multi ? "jend4" : "jend";
+    e.o << "  long long j = " << jb << " + 4 * (long long)threadIdx.x;\n  {\n    " << T << " acc1 = acc, acc2 = acc, acc3 = acc;\n";
+    e.o << "#pragma unroll 2\n    for (; j + 4 <= " << je << "; j += 1024) {\n";
+    if (multi) {
+      e.o << "      long long jrem = j;\n";
+      for (int k = rank - 1; k >= kr; --k) {
+        if (k == kr) e.o << "      const long long i" << k << " = jrem;\n";
+        else e.o << "      const long long i" << k << " = jrem % " << e.dim(k) << "; jrem /= " << e.dim(k) << ";\n";
+      }
+    } else e.o << "      const long long i" << kr << " = j;\n";
     for (size_t i = 0; i < g.prog.size(); ++i) {
       const Instr& in = g.prog[i];
       if (in.kind != IKind::LOAD) continue;
       const AccessGroup& ag = g.groups[in.group];
       std::ostringstream base;
-      base << "p" << in.group;
+      base << "p" << in.group << " + 0";
       for (int k = 0; k < kr; ++k) if (!ag.structural_zero[k] && in.delta[k]) base << " + " << in.delta[k] << " * " << e.coef(in.group, k);
-      if (ag.structural_zero[kr]) e.o << "      const " << cty(in.dtype) << " u" << i << " = (" << base.str() << ")[0];\n";
-      else e.o << "      const " << vty4(in.dtype) << " w" << i << " = " << e.ld(in.group, vty4(in.dtype), base.str() + " + j + " + std::to_string(in.delta[kr])) << ";\n";
+      for (int k = kr; k < rank; ++k) {
+        if (ag.structural_zero[k]) continue;
+        if (k == rd) base << " + i" << k << " + " << in.delta[k];
+        else base << " + (i" << k << " + " << in.delta[k] << ") * " << e.coef(in.group, k);
+      }
+      if (ag.structural_zero[rd]) e.o << "      const " << cty(in.dtype) << " u" << i << " = (" << base.str() << ")[0];\n";
+      else e.o << "      const " << vty4(in.dtype) << " w" << i << " = " << e.ld(in.group, vty4(in.dtype), base.str()) << ";\n";
     }
     for (int c4 = 0; c4 < 4; ++c4) {
       const std::string pre = "v" + std::to_string(c4) + "_";
       emit_scalar_program(e, g.prog, {ph.value},
                           [&](const Instr& in, int id) {
                             const AccessGroup& ag = g.groups[in.group];
-                            if (ag.structural_zero[kr]) return "u" + std::to_string(id);
+                            if (ag.structural_zero[rd]) return "u" + std::to_string(id);
                             return "w" + std::to_string(id) + "[" + std::to_string(c4) + "]";
                           },
                           "0.0f", pre, "      ");
@@ -735,7 +754,7 @@ void gen_reduce(Em& e) {
       e.o << "      " << a << " = " << Em::combine(ph, a, pre + std::to_string(ph.value)) << ";\n";
     }
     e.o << "    }\n    acc = gr_comb0(gr_comb0(acc, acc1), gr_comb0(acc2, acc3));\n  }\n";
-    e.o << "  for (; j < jend; ++j) {\n";   // at most one lane still has (fewer than four) elements
+    e.o << "  for (; j < " << je << "; ++j) {\n";   // at most one lane still has (fewer than four) elements
   } else if (g.red_mode == 0) e.o << "#pragma unroll 4\n  for (long long j = jbeg; j < jend; ++j) {\n";
   else e.o << "#pragma unroll 4\n  for (long long j = jbeg + threadIdx.x; j < jend; j += 256) {\n";
   if (rank > kr) {

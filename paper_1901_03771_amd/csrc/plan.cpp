@@ -870,6 +870,9 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
         for (const Instr& in : g->prog) if (in.dtype == GR_I64) ok = false;
         g->red_vec = ok ? 1 : 0;
       }
+      // mode 1 over several reduced dimensions: four consecutive elements per lane as long as they
+      // cannot straddle the innermost one
+      if (g->red_mode == 1 && g->rank > kept_rank + 1 && g->dims[g->rank - 1] % 4 == 0) g->red_vec = 1;
       int64_t units = g->red_mode == 0 ? ((g->red_vec ? g->red_out / 4 : g->red_out) + 255) / 256 : g->red_out;
       // measured on MI355X (column sums of 8192^2): fewer, longer chunks win once a thread streams
       // dwordx4 rows (32 splits: 53 us, 128 splits: 61 us, 512 splits: 72 us)
