@@ -133,6 +133,10 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     an array whose storage the library owns, writes a second
  *                     buffer, copies the cells outside the box and swaps the
  *                     two buffers; 0 = always evaluate, then copy
+ *   "stage_transposed" 1 (default) = a map sub-graph reads operands whose contiguous
+ *                     dimension is the row dimension of the iteration space
+ *                     (transposed views) through 64 x 64 tiles transposed in LDS;
+ *                     0 = strided loads
  *   "dry_run"         on a device-less context only: 1 = materialise and assign
  *                     calls run everything except the kernel launches
  *                     (partitioning, code generation, compilation, buffer and

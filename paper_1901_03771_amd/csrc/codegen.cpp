@@ -333,6 +333,27 @@ void gen_map(Em& e) {
     return s.str();
   };
 
+  // ---- transposed operands: the workgroup's 64 x 64 tile goes through LDS, loaded along the
+  // operand's own contiguous dimension (the rows of the iteration space) ----
+  if (g.stage_mask) {
+    for (size_t gi = 0; gi < g.groups.size(); ++gi) {
+      if (!(g.stage_mask >> gi & 1)) continue;
+      const AccessGroup& ag = g.groups[gi];
+      const char* T = cty(ag.dtype);
+      const char* V4 = vty4(ag.dtype);
+      e.o << "  __shared__ " << T << " tg" << gi << "[64][65];\n";
+      e.o << "  { const GM " << T << "* const pt = q" << gi;
+      for (int k = 0; k + 2 < rank; ++k) if (!ag.structural_zero[k]) e.o << " + i" << k << " * " << e.coef((int)gi, k);
+      e.o << " + (long long)by * 64 + (long long)bx * 64 * " << e.coef((int)gi, cd) << ";\n";
+      e.o << "    for (int i = 0; i < 4; ++i) {\n      const int cc = threadIdx.x / 16 + 16 * i, r4 = (threadIdx.x % 16) * 4;\n"
+             "      const long long gc = (long long)bx * 64 + cc, gr = (long long)by * 64 + r4;\n"
+             "      if (gc < C && gr + 4 <= R) { const " << V4 << " w = *(const GM " << V4 << "*)(pt + cc * " << e.coef((int)gi, cd) << " + r4);"
+             " tg" << gi << "[cc][r4] = w[0]; tg" << gi << "[cc][r4 + 1] = w[1]; tg" << gi << "[cc][r4 + 2] = w[2]; tg" << gi << "[cc][r4 + 3] = w[3]; }\n"
+             "      else if (gc < C) { for (int j = 0; j < 4; ++j) if (gr + j < R) tg" << gi << "[cc][r4 + j] = pt[cc * " << e.coef((int)gi, cd) << " + r4 + j]; }\n"
+             "    }\n  }\n";
+    }
+    e.o << "  __syncthreads();\n";
+  }
   // ---- lanes whose whole patch lies inside the array: straight-line ----
   e.o << "  if (r0 + " << g.VR << " <= R && c0 + " << (g.UC - 1) * g.BX * 4 + 4 << " <= C) {\n";
   // group the contiguous loads of the patch program into vector loads
@@ -357,6 +378,11 @@ void gen_map(Em& e) {
       const Instr& in = g.prog[i];
       if (in.kind != IKind::LOAD || !used[i]) continue;
       const AccessGroup& ag = g.groups[in.group];
+      if (g.stage_mask >> in.group & 1) {
+        // element (row r0 + dr, column c0 + dc) of the iteration space sits at [column][row] of the tile
+        load_name[(int)i] = "tg" + std::to_string(in.group) + "[tx * 4 + " + std::to_string(in.delta[cd]) + "][ty * " + std::to_string(g.VR) + " + " + std::to_string(in.delta[rd]) + "]";
+        continue;
+      }
       if (access_class(ag, cd) != '1') {
         load_name[(int)i] = "p" + std::to_string(in.group) + "[" + shift_expr(in, true) + "]";
         continue;

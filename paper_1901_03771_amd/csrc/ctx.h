@@ -38,6 +38,7 @@ struct gr_ctx {
   int64_t opt_interp = 1;
   int64_t opt_assign_swap = 1;
   int64_t opt_dry_run = 0;
+  int64_t opt_stage = 1;
   uintptr_t dry_next = 0x100000;  // fake device addresses handed out by a dry run
 
   // allocator

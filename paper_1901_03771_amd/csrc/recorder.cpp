@@ -200,6 +200,7 @@ gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   else if (k == "interp") ctx->opt_interp = value;
   else if (k == "assign_swap") ctx->opt_assign_swap = value;
   else if (k == "dry_run") ctx->opt_dry_run = value;
+  else if (k == "stage_transposed") ctx->opt_stage = value;
   else return fail(ctx, GR_ERR_ARG, "unknown option '" + k + "'");
   return GR_OK;
 }

@@ -649,6 +649,37 @@ def test_random_programs_bit_exact_generated_kernels(env, block):
         _run_fuzz_seed(env, seed)
 
 
+def test_transposed_operands_through_lds_tiles(env):
+    # operands whose contiguous dimension is the row dimension of the iteration space are read through
+    # transposing 64 x 64 LDS tiles: ragged edges, outer dimensions, two staged operands, int32, slices
+    gr, ctx, torch = env
+    a, b = _rand((257, 130), 181), _rand((130, 257), 182)
+    got, ref = run_both(env, lambda xp, a, b: a - xp.transpose(b, (1, 0)) * 2.0, dict(a=a, b=b))
+    assert np.array_equal(got, ref)
+    got, ref = run_both(env, lambda xp, a, b: xp.transpose(a, (1, 0)) + b, dict(a=a, b=b))
+    assert np.array_equal(got, ref)
+    c = _rand((70, 300), 183)
+    d = _rand((70, 300), 184)
+    got, ref = run_both(env, lambda xp, c, d: xp.transpose(c, (1, 0)) * xp.transpose(d, (1, 0)), dict(c=c, d=d))   # both operands staged
+    assert got.shape == (300, 70) and np.array_equal(got, ref)
+    got, ref = run_both(env, lambda xp, c, d: xp.transpose(c[3:, 5:200:2], (1, 0)) - 1.0, dict(c=c, d=d))          # a window, stepped
+    assert np.array_equal(got, ref)
+    t3 = _rand((5, 66, 129), 185)
+    got, ref = run_both(env, lambda xp, t: xp.transpose(t, (0, 2, 1)) * 3.0, dict(t=t3))
+    assert got.shape == (5, 129, 66) and np.array_equal(got, ref)
+    got, ref = run_both(env, lambda xp, t: xp.transpose(t, (2, 0, 1)) + 1.0, dict(t=t3))
+    assert got.shape == (129, 5, 66) and np.array_equal(got, ref)
+    i = np.random.default_rng(186).integers(-1000, 1000, (200, 64)).astype(np.int32)
+    got, ref = run_both(env, lambda xp, i: xp.transpose(i, (1, 0)) * 7 - 3, dict(i=i))
+    assert got.dtype == np.int32 and np.array_equal(got, ref)
+    plan = (ctx.array(torch.zeros(128, 128, device="cuda")).T * 1.0).plan()
+    assert "tile=64x64" in plan
+    ctx.set_option("stage_transposed", 0)
+    got2, _ = run_both(env, lambda xp, a, b: a - xp.transpose(b, (1, 0)) * 2.0, dict(a=a, b=b))
+    ctx.set_option("stage_transposed", 1)
+    assert np.array_equal(got2, a - b.T * f32(2))
+
+
 def test_random_programs_with_empty_windows(env):
     # slices that select nothing: every later op sees an extent of 0 (no launch, right shapes, i32 sums of nothing are 0)
     import fuzz
