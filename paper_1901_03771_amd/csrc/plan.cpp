@@ -305,6 +305,37 @@ bool resolve_to_leaf(const Node* n, IndexMap m, const Node** leaf, IndexMap* lm)
   return true;
 }
 
+// A contraction with one output row or very few, over a long k: too little parallelism for the
+// row-per-lane-group kernel.  It is planned as the map-reduce it is (Listing 5 of the paper writes
+// the inner product exactly so): value a[m,k] * v[k], reduced over k in two stages.
+// Element strides an array will have when it is read: those of its storage if it has one, of a
+// C-contiguous result if it is still to be computed, transformed by the views in between.
+static void strides_when_read(const Node* n, int64_t* st) {
+  if (n->materialized) { for (int d = 0; d < n->ndim; ++d) st[d] = n->strides[d]; return; }
+  if (!n->is_view()) {
+    int64_t s = 1;
+    for (int d = n->ndim - 1; d >= 0; --d) { st[d] = s; s *= n->shape[d]; }
+    return;
+  }
+  int64_t in[MAXD];
+  strides_when_read(n->in[0], in);
+  if (n->kind == Kind::SLICE) for (int d = 0; d < n->ndim; ++d) st[d] = in[d] * n->step[d];
+  else for (int d = 0; d < n->ndim; ++d) st[d] = in[n->perm[d]];
+}
+
+bool dot_as_reduce(const Node* n) {
+  if (n->kind != Kind::DOT) return false;
+  const Node* A = n->in[0];
+  const Node* v = n->in[1];
+  if (v->ndim != 1) return false;
+  const int64_t K = v->shape[0], M = A->ndim == 2 ? A->shape[0] : 1;
+  if (!(K >= 8192 && M * 64 <= K && M <= 2048)) return false;
+  // rows that are contiguous along k only: a transposed matrix has the column-accumulate kernel
+  int64_t st[MAXD];
+  strides_when_read(A, st);
+  return st[A->ndim - 1] == 1 || st[A->ndim - 1] == 2 || A->ndim == 1;
+}
+
 const Node* strip_views(const Node* n) {
   while (n->is_view() && !n->has_data()) n = n->in[0];
   return n;
@@ -477,6 +508,7 @@ struct Planner {
           if (!b->materialized) cuts.insert(b);
         }
       }
+      if (dot_as_reduce(n)) cuts.insert(n);       // evaluated as a two-stage reduction: consumers read its result
       if (n->kind == Kind::SCAN) cuts.insert(n);  // a scan is materialised (materialize_node, Section 2)
       if (n->kind == Kind::REDUCE) {
         const Node* x = n->in[0];
@@ -751,7 +783,7 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
         if (ks >= 2) g->slabs = (int)std::min<int64_t>(ks, 256);
       }
     }
-  } else if (dot) {
+  } else if (dot && !(dot == r && dot_as_reduce(dot) && c->opt_fusion)) {
     // ---- contraction with pointwise epilogue ------------------------------
     g->kind = GroupKind::GEMV;
     const Node* A = dot->in[0];
@@ -817,9 +849,9 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     std::vector<Instr>* ps[1] = {&g->prog};
     // epilogue groups only: core groups carry no deltas
     normalize_deltas(g, ps, 1, 1);
-  } else if (!reds.empty()) {
+  } else if (!reds.empty() || dot) {
     // Decide between row-resident and generic reduction.
-    bool generic = false;
+    bool generic = dot != nullptr;   // (a contraction planned as a reduction, see dot_as_reduce)
     if (r->kind == Kind::REDUCE) {
       const Node* x = r->in[0];
       bool last_only = x->ndim >= 1;
@@ -834,6 +866,31 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       const Node* x = r->in[0];
       int pos[MAXD];
       int nk = 0;
+      int v = -1;
+      if (dot) {
+        // iteration space (m, k) or (k): value A[m,k] * v[k], summed over k
+        const Node* A = dot->in[0];
+        const Node* vec = dot->in[1];
+        if (A->ndim == 2) g->orig_dims[nk++] = A->shape[0];
+        g->red_kept_rank = nk;
+        g->orig_dims[nk] = vec->shape[0];
+        g->orig_rank = nk + 1;
+        b.rank = g->orig_rank; b.dims = g->orig_dims; b.prog = &g->prog;
+        b.g->kind = GroupKind::REDUCE;
+        int ids[2];
+        for (int side = 0; side < 2; ++side) {
+          const Node* X = side == 0 ? A : vec;
+          IndexMap xm(X->ndim);
+          if (X->ndim == 2) { xm[0] = DimMap{0, 1, 0}; xm[1] = DimMap{1, 1, 0}; } else xm[0] = DimMap{nk, 1, 0};
+          b.canonicalize(X, xm);
+          const Node* leaf; IndexMap lm;
+          if (!resolve_to_leaf(X, xm, &leaf, &lm)) return fail(c, GR_ERR_UNSUPPORTED, "dot: operand is not materialised");
+          ids[side] = b.load(leaf, lm);
+        }
+        Instr mul;
+        mul.kind = IKind::BINARY; mul.op = GR_MUL; mul.dtype = GR_F32; mul.a = ids[0]; mul.b = ids[1];
+        v = b.value_number(mul);
+      } else {
       for (int d = 0; d < x->ndim; ++d) if (!r->red_axis[d]) { pos[d] = nk; g->orig_dims[nk++] = x->shape[d]; }
       g->red_kept_rank = nk;
       int nr = nk;
@@ -844,11 +901,12 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       IndexMap xm(x->ndim);
       for (int d = 0; d < x->ndim; ++d) xm[d] = DimMap{pos[d], 1, 0};
       b.g->kind = GroupKind::REDUCE;
-      int v = b.eval(x, xm);
+      v = b.eval(x, xm);
+      }
       if (!b.invalid.empty()) { *invalid = b.invalid; return GR_OK; }
       b.members_seen.insert(r);
       Phase p;
-      p.op = r->op; p.in_dtype = x->dtype; p.out_dtype = r->dtype; p.value = v; p.node = r;
+      p.op = dot ? (int)GR_SUM : r->op; p.in_dtype = x->dtype; p.out_dtype = r->dtype; p.value = v; p.node = r;
       g->phases.push_back(p);
       std::vector<Instr>* ps[1] = {&g->prog};
       normalize_deltas(g, ps, 1, g->orig_rank);

@@ -63,6 +63,14 @@ DOT_CASES = [
     (lambda xp, A, v, u: A[10:20, 5:] @ xp.transpose(A[30:31, 5:], (1, 0)), "matrix times a column taken from itself"),
 ]
 
+# long contractions with few rows (planned as two-stage reductions): (name, shapes of A and v, program)
+LONG_DOT_CASES = [
+    ("inner product of 300001", (300001,), (300001,), lambda xp, A, v: xp.sqrt(abs(xp.dot(A, v))) + 1.0),
+    ("three rows of 100003", (3, 100003), (100003,), lambda xp, A, v: xp.dot(A, v) * 2.0 - 1.0),
+    ("windows of long rows", (5, 70000), (70000,), lambda xp, A, v: xp.dot(A[1:4, 7::2], v[7::2])),
+    ("inner product of two windows of one array", (200000,), (200000,), lambda xp, A, v: xp.dot(A[5:], A[:-5])),
+]
+
 # (shape, axis): inclusive scans along the contiguous axis, along outer axes, over long lines
 SCAN_CASES = [((1000,), 0), ((37, 211), 1), ((37, 211), 0), ((4, 5, 6), 1), ((4, 5, 6), 0), ((4, 5, 6), -1), ((3, 100000), 1),
               ((1 << 21,), 0), ((5, 1), 1), ((1, 7), 0), ((1,), 0), ((600, 1030), 1), ((2, 5000), 0),

@@ -14,7 +14,7 @@ import numpy as np
 import pytest
 
 import oracle as ora
-from cases import DOT_CASES, ELEMENTWISE_CASES, REDUCTION_CASES, ROWRED_PROGRAMS, SCAN_CASES, _rand
+from cases import DOT_CASES, ELEMENTWISE_CASES, LONG_DOT_CASES, REDUCTION_CASES, ROWRED_PROGRAMS, SCAN_CASES, _rand
 from helpers import elementwise_close, reduction_close, ulp_of
 from paper_1901_03771_amd import workloads as wl
 
@@ -309,6 +309,18 @@ def test_dot_variants(env):
         got, ref = run_both(env, prog, dict(A=A, v=v, u=u))
         assert got.shape == ref.shape, what
         assert_reduction(got, ref, what=what)
+
+
+@pytest.mark.parametrize("case", LONG_DOT_CASES, ids=[c[0] for c in LONG_DOT_CASES])
+def test_long_contractions_with_few_rows(env, case):
+    name, sa, sv, prog = case
+    gr, ctx, torch = env
+    A, v = _rand(sa, 191), _rand(sv, 192)
+    got, ref = run_both(env, prog, dict(A=A, v=v))
+    assert got.shape == ref.shape
+    assert_reduction(got, ref, what=name)
+    plan = prog(gr, ctx.array(torch.from_numpy(A).cuda()), ctx.array(torch.from_numpy(v).cuda())).plan()
+    assert " REDUCE " in plan.splitlines()[0] and "dot" in plan.splitlines()[0]
 
 
 def test_gemv_pair_matches_two_pass_execution(env):
