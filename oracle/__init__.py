@@ -69,6 +69,8 @@ def lib():
         L.ora_slice.argtypes = [P, I, P, P, P, P, P]
         L.ora_transpose.restype = P
         L.ora_transpose.argtypes = [P, P]
+        L.ora_reshape.restype = P
+        L.ora_reshape.argtypes = [P, I, P]
         L.ora_reduce.restype = P
         L.ora_reduce.argtypes = [I, P, P, I, I]
         L.ora_dot.restype = P
@@ -161,6 +163,9 @@ class Array:
     def T(self):
         return transpose(self)
 
+    def reshape(self, *shape):
+        return reshape(self, shape[0] if len(shape) == 1 and not isinstance(shape[0], int) else shape)
+
     def sum(self, axis=None, keepdims=False): return reduce("sum", self, axis, keepdims)
     def max(self, axis=None, keepdims=False): return reduce("max", self, axis, keepdims)
     def min(self, axis=None, keepdims=False): return reduce("min", self, axis, keepdims)
@@ -221,6 +226,13 @@ def slice_(a: Array, key) -> Array:
 def transpose(a: Array, perm: Optional[Sequence[int]] = None) -> Array:
     p = None if perm is None else (ctypes.c_int * len(perm))(*perm)
     return Array(lib().ora_transpose(a._p, p))
+
+
+def reshape(a: Array, shape) -> Array:
+    """Row-major reshape; always a copy (Section 2 of the paper lists reshape among the operations)."""
+    shape = [int(shape)] if isinstance(shape, int) else [int(v) for v in shape]
+    arr = (ctypes.c_int64 * builtins.max(len(shape), 1))(*shape)
+    return Array(_check(lib().ora_reshape(a._p, len(shape), arr)))
 
 
 def reduce(name: str, a: Array, axis=None, keepdims=False) -> Array:

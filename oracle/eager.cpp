@@ -34,6 +34,10 @@
 //     every view of the same buffer sees the new contents, as in NumPy.
 //   * slice / transpose: views (offset + strides), no data touched
 //     (Section 3.1: index translation for slicing and transpose (i,j)->(j,i)).
+//   * reshape (Section 2 lists it with the n-D transpose): a fresh C-contiguous
+//     array holding the operand's elements in row-major order under the new
+//     shape; always a copy (NumPy returns a view where it can; the values
+//     are the same, only writes through the result differ).
 //   * a "weak" scalar (a Python number) takes the array operand's dtype:
 //     rounded to binary32 first when it meets an f32 array.
 #include <cmath>
@@ -339,6 +343,35 @@ Arr* ora_transpose(const Arr* a, const int* perm) {
     seen[p] = true;
     r->shape[d] = a->shape[p];
     r->strides[d] = a->strides[p];
+  }
+  return r;
+}
+
+// Elements of `a` in row-major order, laid out under `shape` (same count; one
+// extent may be -1 and is then inferred).  Always a copy.
+Arr* ora_reshape(const Arr* a, int ndim, const int64_t* shape) {
+  if (a->dtype == DT_WEAK || ndim < 0 || ndim > MAXD) { g_err = "reshape: bad operand or rank"; return nullptr; }
+  int64_t want[MAXD], known = 1, n = count(a);
+  int infer = -1;
+  for (int d = 0; d < ndim; ++d) {
+    want[d] = shape[d];
+    if (shape[d] == -1) { if (infer >= 0) { g_err = "reshape: more than one inferred extent"; return nullptr; } infer = d; }
+    else if (shape[d] < 0) { g_err = "reshape: negative extent"; return nullptr; }
+    else known *= shape[d];
+  }
+  if (infer >= 0) {
+    if (known == 0 || n % known) { g_err = "reshape: cannot infer the extent"; return nullptr; }
+    want[infer] = n / known;
+    known *= want[infer];
+  }
+  if (known != n) { g_err = "reshape: element counts differ"; return nullptr; }
+  Arr* r = fresh(a->dtype, ndim, want);
+  const int64_t isz = itemsize(a->dtype);
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[MAXD], off = a->offset;
+    unravel(lin, a->ndim, a->shape, idx);
+    for (int d = 0; d < a->ndim; ++d) off += idx[d] * a->strides[d];
+    std::memcpy(r->buf->data() + lin * isz, a->buf->data() + off * isz, (size_t)isz);
   }
   return r;
 }

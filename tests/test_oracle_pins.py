@@ -663,6 +663,37 @@ def test_threads_do_not_change_results():
     assert np.array_equal(one, four)
 
 
+# ---- reshape ---------------------------------------------------------------------------------
+
+def test_reshape_is_row_major_relabelling():
+    # brute force: element number `lin` in row-major order keeps its number under the new shape
+    g = np.random.default_rng(77)
+    x = g.standard_normal((4, 6, 5)).astype(f32)
+    for shape in [(120,), (6, 20), (2, 3, 4, 5), (5, -1), (-1,), (1, 120, 1)]:
+        got = ora.array(x).reshape(*shape).numpy()
+        want = tuple(120 // 5 if v == -1 and len(shape) == 2 else (120 if v == -1 else v) for v in shape)
+        assert got.shape == want
+        flat_src = [x[i, j, k] for i in range(4) for j in range(6) for k in range(5)]
+        assert got.ravel().tolist() == flat_src
+    # a transposed, stepped view is read in ITS row-major order
+    v = ora.array(x).T[::2, 1:, :]
+    src = x.T[::2, 1:, :]
+    got = v.reshape(-1).numpy()
+    assert got.tolist() == [src[i, j, k] for i in range(src.shape[0]) for j in range(src.shape[1]) for k in range(src.shape[2])]
+    assert np.array_equal(ora.array(x).T.reshape(10, 12).numpy(), x.T.reshape(10, 12))       # NumPy as third opinion
+    i = np.arange(24, dtype=np.int32).reshape(2, 12)
+    assert np.array_equal(ora.array(i).reshape(4, 6).numpy(), i.reshape(4, 6))
+    # a copy: writing through the result leaves the operand alone
+    a = ora.array(x)
+    r = a.reshape(6, 20)
+    r[0:1] = ora.array(np.zeros((1, 20), f32))
+    assert np.array_equal(a.numpy(), x)
+    for bad in [(7, 17), (-1, -1), (0, -1), (-2, 60)]:
+        with pytest.raises(Exception):
+            ora.array(x).reshape(*bad)
+    assert ora.array(np.zeros((0, 4), f32)).reshape(4, 0).numpy().shape == (4, 0)
+
+
 # ---- random programs against NumPy ---------------------------------------------------------
 
 def test_random_programs_match_numpy_bit_for_bit():
