@@ -197,6 +197,15 @@ gr_status gr_slice(gr_ctx* ctx, gr_array a, int nspec, const int64_t* start, con
  * (i,j) of the result is element (j,i) of a 2-D operand (Section 3.1). */
 gr_status gr_transpose(gr_ctx* ctx, gr_array a, const int* perm, gr_array* out);
 
+/* Reshape (Section 2 lists it with the n-D transpose among the recorded
+ * operations): the elements of `a` in row-major order under the new shape
+ * (host array of `ndim` extents with the same product; one extent may be -1 and
+ * is then inferred).  The result is an array of its own: evaluating it copies
+ * (fused with whatever pointwise expression `a` still is), so writes through it
+ * never reach `a` (NumPy returns a view where it can; values are the same).
+ * Consumers read the stored result.  GR_ERR_SHAPE if the counts differ. */
+gr_status gr_reshape(gr_ctx* ctx, gr_array a, int ndim, const int64_t* shape, gr_array* out);
+
 /* GR_SUM / GR_MAX / GR_MIN over `axes` (naxes = 0: all axes).  Negative axes
  * count from the end.  i32 sums give i64.  max/min over an empty range:
  * GR_ERR_SHAPE. */

@@ -18,7 +18,7 @@ namespace gr {
 
 constexpr int MAXD = GR_MAX_NDIM;
 
-enum class Kind : uint8_t { LEAF, SCALAR, CONST, UNARY, BINARY, SLICE, TRANSPOSE, REDUCE, DOT, SCAN };
+enum class Kind : uint8_t { LEAF, SCALAR, CONST, UNARY, BINARY, SLICE, TRANSPOSE, REDUCE, DOT, SCAN, RESHAPE };
 
 struct Node {
   uint64_t id = 0;
@@ -67,7 +67,7 @@ struct Node {
     return n;
   }
   bool is_view() const { return kind == Kind::SLICE || kind == Kind::TRANSPOSE; }
-  bool is_compute() const { return kind == Kind::UNARY || kind == Kind::BINARY || kind == Kind::REDUCE || kind == Kind::DOT || kind == Kind::SCAN; }
+  bool is_compute() const { return kind == Kind::UNARY || kind == Kind::BINARY || kind == Kind::REDUCE || kind == Kind::DOT || kind == Kind::SCAN || kind == Kind::RESHAPE; }
   bool has_data() const { return materialized || planned; }
 };
 

@@ -58,6 +58,7 @@ std::string node_label(const Node* n) {
     case Kind::UNARY: case Kind::BINARY: case Kind::REDUCE: return op_name(n->op);
     case Kind::SLICE: return "slice";
     case Kind::TRANSPOSE: return "transpose";
+    case Kind::RESHAPE: return "reshape";
     case Kind::DOT: return "dot";
     case Kind::SCAN: return std::string("cum") + op_name(n->op);
   }
@@ -336,6 +337,12 @@ bool dot_as_reduce(const Node* n) {
   return st[A->ndim - 1] == 1 || st[A->ndim - 1] == 2 || A->ndim == 1;
 }
 
+// The node whose index space a map sub-graph rooted at `r` iterates over: the operand of a reshape
+// that is still to be evaluated, `r` itself otherwise.
+const Node* map_source(const Node* r) {
+  return (r->kind == Kind::RESHAPE && !r->materialized && !r->in.empty()) ? r->in[0] : r;
+}
+
 const Node* strip_views(const Node* n) {
   while (n->is_view() && !n->has_data()) n = n->in[0];
   return n;
@@ -510,6 +517,7 @@ struct Planner {
       }
       if (dot_as_reduce(n)) cuts.insert(n);       // evaluated as a two-stage reduction: consumers read its result
       if (n->kind == Kind::SCAN) cuts.insert(n);  // a scan is materialised (materialize_node, Section 2)
+      if (n->kind == Kind::RESHAPE) cuts.insert(n);  // a reshape is a stored copy: its consumers index it under the new shape
       if (n->kind == Kind::REDUCE) {
         const Node* x = n->in[0];
         bool last_only = x->ndim >= 1;
@@ -1014,20 +1022,25 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     g->kind = GroupKind::MAP;
     for (const Node* n : reds) invalid->push_back({n, "reduction inside a map sub-graph"});
     if (!invalid->empty()) return GR_OK;
-    int n = std::max(r->ndim, 1);
+    // A reshape root is the row-major copy of its operand: the sub-graph iterates over the operand's
+    // index space and writes a C-contiguous buffer, which is the result under either shape.
+    const Node* src = map_source(r);
+    int n = std::max(src->ndim, 1);
     g->orig_rank = n;
-    if (r->ndim == 0) g->orig_dims[0] = 1;
-    for (int d = 0; d < r->ndim; ++d) g->orig_dims[d] = r->shape[d];
-    IndexMap im(r->ndim);
-    for (int d = 0; d < r->ndim; ++d) im[d] = DimMap{d, 1, 0};
+    if (src->ndim == 0) g->orig_dims[0] = 1;
+    for (int d = 0; d < src->ndim; ++d) g->orig_dims[d] = src->shape[d];
+    IndexMap im(src->ndim);
+    for (int d = 0; d < src->ndim; ++d) im[d] = DimMap{d, 1, 0};
     // Single-point program: enough to learn the accesses, fix the schedule and key the
     // kernel cache.  The per-lane patch program is a function of exactly these and is only
     // built when the cache misses (expand_patch).
     b.rank = n; b.dims = g->orig_dims; b.prog = &g->prog1;
-    g->result1 = b.eval(r, im);
+    g->result1 = b.eval(src, im);
+    if (src != r) b.members_seen.insert(r);
     if (!b.invalid.empty()) { *invalid = b.invalid; return GR_OK; }
     // where the elements go: a C-contiguous buffer, or the strided destination of a slice assignment
-    if (r == pl.root && pl.out && r->ndim > 0) {
+    // (whose strides are given in the root's own shape: not for a reshape root)
+    if (r == pl.root && pl.out && r->ndim > 0 && src == r) {
       g->out_base = pl.out->base;
       for (int d = 0; d < r->ndim; ++d) g->out_orig_coef[d] = pl.out->strides[d];
     } else {
@@ -1074,21 +1087,22 @@ gr_status expand_patch(gr_ctx* c, GroupPlan* g) {
   tmp.consts = g->consts;
   Builder b;
   b.g = &tmp; b.owned = &g->owned; b.rank = n; b.dims = tmp.orig_dims; b.prog = &tmp.prog;
-  IndexMap im(r->ndim);
-  for (int d = 0; d < r->ndim; ++d) im[d] = DimMap{d, 1, 0};
+  const Node* src = map_source(r);
+  IndexMap im(src->ndim);
+  for (int d = 0; d < src->ndim; ++d) im[d] = DimMap{d, 1, 0};
   const bool was_planned = r->planned;  // the root is computed here, not read
   r->planned = false;
   for (int v = 0; v < g->VR; ++v)
     for (int u = 0; u < g->UC; ++u)
       for (int j = 0; j < 4; ++j) {
         IndexMap pm = im;
-        for (int d = 0; d < r->ndim; ++d) {
+        for (int d = 0; d < src->ndim; ++d) {
           if (d == col_dim) pm[d].off += (int64_t)u * g->BX * 4 + j;
           if (d == row_dim) pm[d].off += v;
         }
         // shifted points are evaluated as if the root were larger; the root's own extent-1
         // dims stay canonicalised to index 0, which is right: such dims carry no shift
-        tmp.results.push_back(b.eval(r, pm));
+        tmp.results.push_back(b.eval(src, pm));
       }
   r->planned = was_planned;
   if (!b.invalid.empty()) return fail(c, GR_ERR_UNSUPPORTED, "map: patch expansion met an unexpected node");
@@ -1190,7 +1204,8 @@ gr_status make_plan(gr_ctx* c, Node* root, Plan* plan) {
       }
     }
     if (!restart) {
-      plan->out_honoured = !plan->out || (!plan->groups.empty() && plan->groups.back()->root == root && plan->groups.back()->kind == GroupKind::MAP);
+      plan->out_honoured = !plan->out || (!plan->groups.empty() && plan->groups.back()->root == root && plan->groups.back()->kind == GroupKind::MAP &&
+                                          map_source(root) == root);
       fuse_gemv_pairs(c, plan);
       return GR_OK;
     }

@@ -390,6 +390,36 @@ gr_status gr_transpose(gr_ctx* ctx, gr_array a, const int* perm, gr_array* out) 
   return GR_OK;
 }
 
+gr_status gr_reshape(gr_ctx* ctx, gr_array a, int ndim, const int64_t* shape, gr_array* out) {
+  if (!ctx || !out) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "reshape: bad handle");
+  if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "reshape: operand is a bare scalar");
+  if (ndim < 0 || ndim > MAXD || (ndim > 0 && !shape)) return fail(ctx, GR_ERR_ARG, "reshape: bad rank or NULL shape");
+  int64_t want[MAXD], known = 1;
+  const int64_t n = x->count();
+  int infer = -1;
+  for (int d = 0; d < ndim; ++d) {
+    want[d] = shape[d];
+    if (shape[d] == -1) { if (infer >= 0) return fail(ctx, GR_ERR_SHAPE, "reshape: more than one inferred extent"); infer = d; }
+    else if (shape[d] < 0) return fail(ctx, GR_ERR_SHAPE, "reshape: negative extent");
+    else known *= shape[d];
+  }
+  if (infer >= 0) {
+    if (known == 0 || n % known) return fail(ctx, GR_ERR_SHAPE, "reshape: cannot infer the extent");
+    want[infer] = n / known;
+    known *= want[infer];
+  }
+  if (known != n) return fail(ctx, GR_ERR_SHAPE, "reshape: element counts differ");
+  Node* r = new_node(ctx, Kind::RESHAPE);
+  r->dtype = x->dtype;
+  r->ndim = ndim;
+  for (int d = 0; d < ndim; ++d) r->shape[d] = want[d];
+  add_input(r, x);
+  *out = finish(ctx, r);
+  return GR_OK;
+}
+
 gr_status gr_reduce(gr_ctx* ctx, gr_op op, gr_array a, const int* axes, int naxes, int keepdims, gr_array* out) {
   if (!ctx || !out) return GR_ERR_ARG;
   if (!is_reduce(op)) return fail(ctx, GR_ERR_ARG, "reduce: not a reduction op");

@@ -33,7 +33,7 @@ STATUS = {0: "GR_OK", 1: "GR_ERR_HANDLE", 2: "GR_ERR_SHAPE", 3: "GR_ERR_DTYPE", 
 # every symbol include/grumpy_hip.h declares
 SYMBOLS = [
     "gr_ctx_create", "gr_ctx_destroy", "gr_ctx_set_stream", "gr_ctx_set_allocator", "gr_ctx_set_option", "gr_sync",
-    "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose",
+    "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose", "gr_reshape",
     "gr_reduce", "gr_scan", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_assign", "gr_ndim", "gr_shape", "gr_dtype_of",
     "gr_is_materialized", "gr_data_ptr", "gr_retain", "gr_release", "gr_plan_describe", "gr_plan_source",
     "gr_plan_compile", "gr_compile_wait", "gr_stats", "gr_profile_reset", "gr_profile_read", "gr_stream_copy", "gr_stream_read",
@@ -82,6 +82,7 @@ def lib():
         "gr_binary_scalar": [P, I, U64, ctypes.c_double, I, I, PP(U64)],
         "gr_slice": [P, U64, I, PP(I64), PP(I64), PP(I64), PP(ctypes.c_uint8), PP(ctypes.c_uint8), PP(U64)],
         "gr_transpose": [P, U64, PP(I), PP(U64)],
+        "gr_reshape": [P, U64, I, PP(I64), PP(U64)],
         "gr_reduce": [P, I, U64, PP(I), I, I, PP(U64)], "gr_dot": [P, U64, U64, PP(U64)],
         "gr_scan": [P, I, U64, I, PP(U64)],
         "gr_materialize": [P, U64], "gr_assign": [P, U64, U64], "gr_materialize_into": [P, U64, P, SZ],
@@ -417,6 +418,9 @@ class Array:
     def dot(self, o): return dot(self, o)
     def cumsum(self, axis): return scan("sum", self, axis)
 
+    def reshape(self, *shape):
+        return reshape(self, shape[0] if len(shape) == 1 and not isinstance(shape[0], int) else shape)
+
 
 def _ctx_of(*xs) -> Context:
     for x in xs:
@@ -498,6 +502,15 @@ def transpose(a: Array, axes: Optional[Sequence[int]] = None) -> Array:
     p = None if axes is None else (ctypes.c_int * len(axes))(*axes)
     h = ctypes.c_uint64()
     a.ctx.check(lib().gr_transpose(a.ctx._p, a.h, p, ctypes.byref(h)))
+    return Array(a.ctx, h.value)
+
+
+def reshape(a: Array, shape) -> Array:
+    """Row-major reshape; the result is an array of its own (a fused copy when it is evaluated)."""
+    shape = [int(shape)] if isinstance(shape, int) else [int(v) for v in shape]
+    arr = (ctypes.c_int64 * builtins.max(len(shape), 1))(*shape)
+    h = ctypes.c_uint64()
+    a.ctx.check(lib().gr_reshape(a.ctx._p, a.h, len(shape), arr, ctypes.byref(h)))
     return Array(a.ctx, h.value)
 
 

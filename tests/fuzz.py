@@ -33,7 +33,8 @@ def _broadcast(a, b):
     return tuple(out)
 
 
-def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool = False, empty: bool = False):
+def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool = False, empty: bool = False,
+                reshape: bool = False):
     """Returns (dtype, leaf_shapes, steps, result_index); steps are tuples whose first entry names the op.
     assign=True adds slice assignments into leaves and views of leaves (values: an array of the same
     shape, an expression of the destination itself, or a shifted and possibly overlapping view)."""
@@ -62,8 +63,8 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool 
 
     nsteps = r.randint(3, max_steps)
     for _ in range(nsteps):
-        kind = r.choices(["unary", "binary", "scalar", "slice", "transpose", "reduce", "scan", "materialize", "assign"],
-                         weights=[3, 6, 3, 3, 2, 2, 1, 1, 3 if assign else 0])[0]
+        kind = r.choices(["unary", "binary", "scalar", "slice", "transpose", "reduce", "scan", "materialize", "assign", "reshape"],
+                         weights=[3, 6, 3, 3, 2, 2, 1, 1, 3 if assign else 0, 3 if reshape else 0])[0]
         if kind == "assign":
             t = r.choice([i for i in range(len(shapes)) if storage[i]])
             st_ = shapes[t]
@@ -89,7 +90,27 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool 
             kind = "unary"
         if 0 in sa and kind == "reduce" and dtype != "i32":
             kind = "unary"                                  # max/min of nothing is an error; an empty i32 sum is 0
-        if kind == "unary":
+        if kind == "reshape":
+            # flatten, merge two neighbouring dimensions, or split one by a divisor
+            new = list(sa)
+            how = r.choice(["flat", "merge", "split"])
+            if how == "merge" and len(sa) >= 2:
+                i = r.randrange(len(sa) - 1)
+                new = list(sa[:i]) + [sa[i] * sa[i + 1]] + list(sa[i + 2:])
+            elif how == "split" and len(sa) >= 1 and len(sa) < 5:
+                i = r.randrange(len(sa))
+                divs = [f for f in (2, 3, 4, 5, 7, 8, 10, 13, 16) if sa[i] % f == 0 and sa[i] > 0]
+                if divs:
+                    f = r.choice(divs)
+                    new = list(sa[:i]) + ([f, sa[i] // f] if r.random() < 0.5 else [sa[i] // f, f]) + list(sa[i + 1:])
+            else:
+                new = [int(np.prod(sa))] if len(sa) else [1]
+            given = list(new)
+            if given and int(np.prod(sa)) > 0 and r.random() < 0.3:
+                given[r.randrange(len(given))] = -1          # one extent left to be inferred
+            steps.append(("reshape", a, tuple(given)))
+            shapes.append(tuple(new))
+        elif kind == "unary":
             op = r.choice(["neg", "abs", "square"] + (["sqrtabs"] if dtype == "f32" else []))
             steps.append(("unary", op, a))
             shapes.append(sa)
@@ -235,6 +256,8 @@ def apply(xp, steps, leaves):
             pool.append(pool[st[1]][tuple(slice(*t) for t in st[2])])
         elif k == "transpose":
             pool.append(xp.transpose(pool[st[1]], st[2]))
+        elif k == "reshape":
+            pool.append(xp.reshape(pool[st[1]], st[2]))
         elif k == "reduce":
             pool.append(getattr(xp, st[1])(pool[st[2]], axis=st[3], keepdims=st[4]))
         elif k == "scan":
@@ -263,6 +286,10 @@ class NumpyModule:
     square = staticmethod(np.square)
     sqrt = staticmethod(np.sqrt)
     transpose = staticmethod(np.transpose)
+
+    @staticmethod
+    def reshape(a, shape):
+        return np.reshape(a, shape).copy()        # the evaluators' reshape is an array of its own
 
     @staticmethod
     def maximum(a, b):

@@ -692,6 +692,44 @@ def test_transposed_operands_through_lds_tiles(env):
     assert np.array_equal(got2, a - b.T * f32(2))
 
 
+def test_reshape(env):
+    gr, ctx, torch = env
+    x, y = _rand((4, 6, 5), 201), _rand((5,), 202)
+    got, ref = run_both(env, lambda xp, x, y: xp.reshape(x * 2.0 + y, (6, 20)), dict(x=x, y=y))
+    assert got.shape == (6, 20) and np.array_equal(got, ref)
+    got, ref = run_both(env, lambda xp, x, y: xp.sum(xp.reshape(xp.transpose(x, (2, 0, 1)), (10, -1)), axis=1) + 1.0, dict(x=x, y=y))
+    assert_reduction(got, ref, what="reshape of a transposed view feeding a reduction")
+    big = _rand((130, 257), 203)
+    got, ref = run_both(env, lambda xp, b: xp.exp(xp.reshape(b[1:, ::2], (-1,))[5::3]), dict(b=big))
+    assert_elementwise(got, ref, what="slice of a reshape of a slice")
+    got, ref = run_both(env, lambda xp, b: xp.reshape(xp.reshape(b, (257, 130)), (2, 5, 13, 257)) - 1.0, dict(b=big))
+    assert np.array_equal(got, ref)
+    # an array of its own: writes to the operand afterwards do not reach it, and the other way round
+    t = torch.from_numpy(x.copy()).cuda()
+    a = ctx.array(t)
+    r = a.reshape(24, 5)
+    a[0:1] = ctx.array(torch.zeros(1, 6, 5, device="cuda"))
+    assert np.array_equal(r.numpy(), x.reshape(24, 5))
+    r[0:2] = ctx.array(torch.ones(2, 5, device="cuda"))
+    want = x.copy(); want[0:1] = 0
+    assert np.array_equal(t.cpu().numpy(), want)
+    assert (ctx.array(torch.zeros(0, 4, device="cuda")).reshape(4, 0) + 1.0).numpy().shape == (4, 0)
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_random_programs_with_reshapes(env, block):
+    import fuzz
+    gr, ctx, torch = env
+    for seed in range(400000 + 20 * block, 400000 + 20 * block + 20):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed, reshape=True, assign=(seed % 2 == 0))
+        leaves = fuzz.make_leaves(seed, dtype, shapes)
+        ref = fuzz.apply(ora, steps, [ora.array(x.copy()) for x in leaves])
+        keep = [torch.from_numpy(x.copy()).cuda() for x in leaves]
+        got = fuzz.apply(gr, steps, [ctx.array(t) for t in keep])
+        for i, (g_, r_) in enumerate(zip(got, ref)):
+            assert fuzz.same_bits(g_.numpy(), r_.numpy()), f"seed {seed} value {i}: {dtype} {shapes} {steps}"
+
+
 def test_random_programs_with_empty_windows(env):
     # slices that select nothing: every later op sees an extent of 0 (no launch, right shapes, i32 sums of nothing are 0)
     import fuzz

@@ -366,6 +366,34 @@ def test_dry_run_exercises_materialise_and_assign_without_a_device(ctx):
     assert st["cache_misses"] == 1 and (st["compile_ms"] > 0 or st["disk_hits"] == 1)
 
 
+def test_reshape_records_shapes_and_is_a_fused_copy(ctx):
+    x, y = ctx.spec((4, 6, 5)), ctx.spec((5,))
+    assert x.reshape(6, 20).shape == (6, 20) and x.reshape(-1).shape == (120,) and x.reshape((2, -1, 5)).shape == (2, 12, 5)
+    assert gr.reshape(x, (1, 120, 1)).shape == (1, 120, 1) and x.T.reshape(10, 12).shape == (10, 12)
+    for bad in [(7, 17), (-1, -1), (-2, 60)]:
+        with pytest.raises(gr.GrError) as ei:
+            x.reshape(*bad)
+        assert ei.value.code == "GR_ERR_SHAPE"
+    r = (x * 2.0 + y).reshape(6, 20)
+    kinds = groups(r)
+    assert kinds == [("MAP", ["mul", "add", "reshape"])]             # producers fuse into the copy
+    z = gr.sum(r, axis=1) + 1.0
+    assert [k for k, _ in groups(z)] == ["MAP", "ROWRED"]             # consumers read the stored result
+    z.compile()
+    x.T.reshape(-1).compile()
+    assert ctx.spec((0, 4)).reshape(4, 0).shape == (4, 0)
+
+
+def test_random_programs_with_reshapes_dry_run(ctx):
+    import fuzz
+    ctx.set_option("dry_run", 2)
+    for seed in range(400000, 400150):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed, reshape=True, assign=(seed % 2 == 0))
+        leaves = [ctx.spec(s_, gr.GR_I32 if dtype == "i32" else gr.GR_F32) for s_ in shapes]
+        for a in fuzz.apply(gr, steps, leaves):
+            a.materialize()
+
+
 def test_leaves_and_only_leaves_are_materialised(ctx):
     a = ctx.spec((33, 65))
     out = (a.T @ (a @ ctx.spec((65,)))) * 2.0

@@ -716,6 +716,23 @@ def test_random_programs_match_numpy_bit_for_bit():
     assert checked > 2000
 
 
+def test_random_programs_with_reshapes_match_numpy():
+    import warnings
+    import fuzz
+    n = 0
+    with warnings.catch_warnings():
+        warnings.simplefilter("ignore")
+        for seed in range(400000, 400300):
+            dtype, shapes, steps, res = fuzz.make_recipe(seed, reshape=True, assign=(seed % 2 == 0))
+            n += sum(1 for st in steps if st[0] == "reshape")
+            leaves = fuzz.make_leaves(seed, dtype, shapes)
+            ref = fuzz.apply(fuzz.NumpyModule, steps, [x.copy() for x in leaves])
+            got = fuzz.apply(ora, steps, [ora.array(x.copy()) for x in leaves])
+            for i, (g, r) in enumerate(zip(got, ref)):
+                assert fuzz.same_bits(g.numpy(), r, zero_signs=False), (seed, i, steps)
+    assert n > 100
+
+
 def test_random_programs_with_slice_assignments_match_numpy():
     # the same with writes through views: overlapping sources, values that were computed before a
     # write, views that must show it (NumPy's eager semantics are the definition)
