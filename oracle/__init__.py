@@ -170,7 +170,7 @@ class Array:
     def max(self, axis=None, keepdims=False): return reduce("max", self, axis, keepdims)
     def min(self, axis=None, keepdims=False): return reduce("min", self, axis, keepdims)
     def dot(self, o): return dot(self, o)
-    def cumsum(self, axis): return scan("sum", self, axis)
+    def cumsum(self, axis=None): return cumsum(self, axis)
 
 
 def array(x) -> Array:
@@ -252,9 +252,14 @@ def scan(name: str, a: Array, axis: int) -> Array:
     return Array(lib().ora_scan(_REDUCE[name], a._p, int(axis)))
 
 
-def cumsum(a, axis): return scan("sum", a, axis)
-def cummax(a, axis): return scan("max", a, axis)
-def cummin(a, axis): return scan("min", a, axis)
+def _scan_axis(name, a, axis):
+    # axis=None: NumPy's scan over the flattened array
+    return scan(name, reshape(a, (-1,)), 0) if axis is None else scan(name, a, axis)
+
+
+def cumsum(a, axis=None): return _scan_axis("sum", a, axis)
+def cummax(a, axis=None): return _scan_axis("max", a, axis)
+def cummin(a, axis=None): return _scan_axis("min", a, axis)
 
 
 def dot(a: Array, b: Array) -> Array:

@@ -19,6 +19,7 @@ struct gr_ctx {
   // nodes
   std::unordered_map<uint64_t, gr::Node*> nodes;
   uint64_t next_id = 1;
+  bool any_storage_alias = false;  // some node's data has lived inside another node's buffer (direct slice assignment)
   // pending reductions, scans and contractions by expression hash (merging of equal ones at record time)
   std::unordered_multimap<uint64_t, uint64_t> pending_expensive;
 

@@ -58,7 +58,18 @@ void node_maybe_free(gr_ctx* c, Node* n0) {
       if (--p->consumer_refs == 0 && p->handle_refs == 0) work.push_back(p);
     }
     n->in.clear();
-    if (n->owns_data && n->data) ctx_free(c, n->data, n->alloc_bytes);
+    if (n->owns_data && n->data) {
+      // a value that was assigned directly into this array's storage may outlive the array: the
+      // buffer then passes to it instead of being freed
+      Node* heir = nullptr;
+      if (c->any_storage_alias)
+        for (auto& kv : c->nodes) {
+          Node* m = kv.second;
+          if (m != n && m->materialized && m->cow_alias && m->data == n->data) { heir = m; break; }
+        }
+      if (heir) { heir->owns_data = true; heir->alloc_bytes = n->alloc_bytes; heir->cow_alias = false; }
+      else ctx_free(c, n->data, n->alloc_bytes);
+    }
     if (n->shadow) ctx_free(c, n->shadow, n->alloc_bytes);
     if (n->kind == Kind::REDUCE || n->kind == Kind::DOT || n->kind == Kind::SCAN) forget_pending(c, n);
     c->nodes.erase(n->id);

@@ -582,6 +582,7 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
         r->offset = plan->out->base;
         for (int d = 0; d < r->ndim; ++d) r->strides[d] = plan->out->strides[d];
         r->cow_alias = true;
+        c->any_storage_alias = true;
       }
       r->materialized = true;
       r->planned = false;

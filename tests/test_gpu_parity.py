@@ -475,6 +475,25 @@ def test_assign_of_evaluated_scans_reductions_and_products(env):
     assert_reduction(got[:, 10:16], ref[:, 10:16], what="assigned product")
 
 
+def test_assigned_value_outlives_the_array_it_was_written_into(env):
+    # the value of a direct slice assignment lives inside the destination's buffer; when a
+    # library-owned destination dies first, the buffer passes to the value instead of being reused
+    gr, ctx, torch = env
+    a0, b0 = _rand((256, 300), 211), _rand((256, 300), 212)
+    A = ctx.array(torch.from_numpy(a0).cuda()).copy()
+    B = ctx.array(torch.from_numpy(b0).cuda())
+    v = B * 2.0
+    w = B[:100] * 3.0
+    A[:] = v                       # written straight into A's storage
+    A[100:200] = w                 # v gets a copy of its own first, w now lives in rows 100..199
+    del A
+    junk = [(B * float(k)).materialize() for k in range(4)]     # same-sized allocations that would reuse a freed buffer
+    assert np.array_equal(v.numpy(), b0 * f32(2))
+    assert np.array_equal(w.numpy(), b0[:100] * f32(3))
+    del junk, v
+    assert np.array_equal(w.numpy(), b0[:100] * f32(3))
+
+
 def test_assign_keeps_recorded_values(env):
     gr, ctx, torch = env
     a0, b0 = _rand((300,), 73), _rand((300,), 74)
@@ -714,6 +733,9 @@ def test_reshape(env):
     want = x.copy(); want[0:1] = 0
     assert np.array_equal(t.cpu().numpy(), want)
     assert (ctx.array(torch.zeros(0, 4, device="cuda")).reshape(4, 0) + 1.0).numpy().shape == (4, 0)
+    # a scan over all elements (NumPy's axis=None) is a scan of the flattened array
+    got, ref = run_both(env, lambda xp, b: xp.cummax(xp.transpose(b, (1, 0)) * 0.5), dict(b=big))
+    assert got.shape == (130 * 257,) and np.array_equal(got, ref) and np.array_equal(got, np.maximum.accumulate((big.T * f32(0.5)).ravel()))
 
 
 @pytest.mark.parametrize("block", range(3))
