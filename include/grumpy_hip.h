@@ -84,7 +84,9 @@ gr_status gr_ctx_create(gr_ctx** out, int device, void* hip_stream);
  * the context owns.  Borrowed leaf buffers are not freed. */
 gr_status gr_ctx_destroy(gr_ctx* ctx);
 
-/* Replaces the stream later launches go to (borrowed). */
+/* Replaces the stream later launches go to (borrowed).  Waits for the work
+ * already queued on the old stream: the context reuses its buffers in stream
+ * order. */
 gr_status gr_ctx_set_stream(gr_ctx* ctx, void* hip_stream);
 
 /* Installs the device allocator used for materialised results and

@@ -661,6 +661,9 @@ gr_status gr_compile_wait(gr_ctx* ctx) {
 
 gr_status gr_ctx_set_stream(gr_ctx* ctx, void* hip_stream) {
   if (!ctx) return GR_ERR_ARG;
+  // buffers of the pool are reused in stream order: work queued on the old stream has to be
+  // finished before another stream may touch them
+  if (ctx->device >= 0 && (hipStream_t)hip_stream != ctx->stream) GR_HIP(ctx, hipStreamSynchronize(ctx->stream));
   ctx->stream = (hipStream_t)hip_stream;
   return GR_OK;
 }
