@@ -163,12 +163,16 @@ gr_status gr_sync(gr_ctx* ctx);
  * text of the last failed gr_ctx_create. */
 const char* gr_last_error(gr_ctx* ctx);
 
-/* ---- leaves (Section 2: "only the input nodes have the data field non-empty") */
+/* ---- leaves (Section 2: when recording starts, inputs are the only nodes that hold values) */
 
 /* Wraps an existing device buffer as a materialised leaf.  `dptr` points at
  * element (0,..,0); strides_elems = NULL means C-contiguous.  BORROWED: the
  * caller keeps the memory alive and unmodified until every array that
- * depends on this leaf has been materialised or released. */
+ * depends on this leaf has been materialised or released.
+ * Limits (GR_ERR_ARG): the product of the non-zero extents, and the largest
+ * element offset the strides reach, stay at or below 2^40; `dptr` is aligned
+ * to the element size.  Results that would exceed 2^40 elements (a broadcast,
+ * an outer-product-like dot, a reshape) are refused with GR_ERR_SHAPE. */
 gr_status gr_array_from_device(gr_ctx* ctx, void* dptr, gr_dtype dtype, int ndim, const int64_t* shape,
                                const int64_t* strides_elems, gr_array* out);
 

@@ -348,7 +348,7 @@ const Node* strip_views(const Node* n) {
   return n;
 }
 
-int next_pow2(int64_t v) { int p = 1; while (p < v) p <<= 1; return p; }
+int next_pow2(int64_t v) { int p = 1; while (p < v && p < (1 << 30)) p <<= 1; return p; }  // saturates at 2^30
 
 void normalize_deltas(GroupPlan* g, std::vector<Instr>* progs[], int nprogs, int rank) {
   for (size_t gi = 0; gi < g->groups.size(); ++gi) {
@@ -844,7 +844,7 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     } else {
       g->BX = std::min(256, std::max(16, next_pow2((g->M + 3) / 4)));  // lanes across the output index
       g->BY = 256 / g->BX;
-      int64_t colblocks = (g->M + (int64_t)g->BX * 4 - 1) / ((int64_t)g->BX * 4);
+      int64_t colblocks = std::max<int64_t>(1, (g->M + (int64_t)g->BX * 4 - 1) / ((int64_t)g->BX * 4));
       // about one workgroup per CU measured best on MI355X (256 slabs: 78 us for 512 MiB, 1024: 85 us),
       // and fewer partial vectors make the second stage cheaper
       int64_t rows_per_slab = std::max<int64_t>((int64_t)g->BY * 8, (g->K + 255) / 256);

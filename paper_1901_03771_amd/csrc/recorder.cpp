@@ -24,6 +24,21 @@ Node* lookup(gr_ctx* c, gr_array a) {
   return it->second;
 }
 
+// Element counts and element offsets stay below 2^40 so that byte offsets and every product of two
+// extents the planner forms fit int64 with room to spare (288 GB of HBM holds 2^36 f32 elements).
+// Zero extents count as one: reducing an empty axis away leaves the other extents as the result.
+constexpr int64_t MAX_COUNT = int64_t(1) << 40;
+
+bool count_fits(const int64_t* shape, int ndim) {
+  int64_t n = 1;
+  for (int d = 0; d < ndim; ++d) {
+    if (shape[d] <= 0) continue;
+    if (shape[d] > MAX_COUNT || n > MAX_COUNT / shape[d]) return false;
+    n *= shape[d];
+  }
+  return true;
+}
+
 Node* new_node(gr_ctx* c, Kind kind) {
   Node* n = new Node();
   n->id = c->next_id++;
@@ -231,9 +246,21 @@ gr_status gr_array_from_device(gr_ctx* ctx, void* dptr, gr_dtype dtype, int ndim
   if (ndim < 0 || ndim > MAXD || (ndim > 0 && !shape)) return fail(ctx, GR_ERR_ARG, "from_device: bad rank or NULL shape");
   if (dtype != GR_F32 && dtype != GR_I32 && dtype != GR_I64) return fail(ctx, GR_ERR_ARG, "from_device: bad dtype");
   int64_t n = 1;
-  for (int d = 0; d < ndim; ++d) {
+  for (int d = 0; d < ndim; ++d)
     if (shape[d] < 0) return fail(ctx, GR_ERR_ARG, "from_device: negative extent");
-    n *= shape[d];
+  if (!count_fits(shape, ndim)) return fail(ctx, GR_ERR_ARG, "from_device: more than 2^40 elements");
+  for (int d = 0; d < ndim; ++d) n *= shape[d];
+  if (strides_elems) {
+    int64_t span = 0;  // largest |element offset| any index reaches
+    for (int d = 0; d < ndim; ++d) {
+      if (shape[d] <= 1) continue;
+      if (strides_elems[d] < -MAX_COUNT || strides_elems[d] > MAX_COUNT)
+        return fail(ctx, GR_ERR_ARG, "from_device: strides reach beyond 2^40 elements");
+      int64_t st = strides_elems[d] < 0 ? -strides_elems[d] : strides_elems[d];
+      if (st > (MAX_COUNT - span) / (shape[d] - 1))
+        return fail(ctx, GR_ERR_ARG, "from_device: strides reach beyond 2^40 elements");
+      span += st * (shape[d] - 1);
+    }
   }
   if (n > 0 && !dptr) return fail(ctx, GR_ERR_ARG, "from_device: NULL device pointer");
   if (((uintptr_t)dptr) % itemsize(dtype)) return fail(ctx, GR_ERR_ARG, "from_device: pointer not aligned to the element size");
@@ -314,6 +341,7 @@ gr_status gr_binary(gr_ctx* ctx, gr_op op, gr_array a, gr_array b, gr_array* out
     else if (sy == 1) shape[d] = sx;
     else return fail(ctx, GR_ERR_SHAPE, "binary: shapes do not broadcast");
   }
+  if (!count_fits(shape, n)) return fail(ctx, GR_ERR_SHAPE, "binary: the broadcast result has more than 2^40 elements");
   Node* r = new_node(ctx, Kind::BINARY);
   r->op = op;
   r->dtype = dt;
@@ -407,6 +435,7 @@ gr_status gr_reshape(gr_ctx* ctx, gr_array a, int ndim, const int64_t* shape, gr
   if (!x) return fail(ctx, GR_ERR_HANDLE, "reshape: bad handle");
   if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "reshape: operand is a bare scalar");
   if (ndim < 0 || ndim > MAXD || (ndim > 0 && !shape)) return fail(ctx, GR_ERR_ARG, "reshape: bad rank or NULL shape");
+  if (!count_fits(shape, ndim)) return fail(ctx, GR_ERR_SHAPE, "reshape: element counts differ");
   int64_t want[MAXD], known = 1;
   const int64_t n = x->count();
   int infer = -1;
@@ -496,6 +525,10 @@ gr_status gr_dot(gr_ctx* ctx, gr_array a, gr_array b, gr_array* out) {
   if (y->ndim == 2 && x->ndim == 1) return fail(ctx, GR_ERR_UNSUPPORTED, "dot: vector-matrix product is not supported (transpose both sides)");
   if (y->ndim < 1 || y->ndim > 2 || x->ndim < 1 || x->ndim > 2) return fail(ctx, GR_ERR_UNSUPPORTED, "dot: supported ranks are (M,K).(K,N), (M,K).(K,) and (K,).(K,)");
   if (x->shape[x->ndim - 1] != y->shape[0]) return fail(ctx, GR_ERR_SHAPE, "dot: inner dimensions differ");
+  {
+    const int64_t mn[2] = {x->ndim == 2 ? x->shape[0] : 1, y->ndim == 2 ? y->shape[1] : 1};
+    if (!count_fits(mn, 2)) return fail(ctx, GR_ERR_SHAPE, "dot: the result has more than 2^40 elements");
+  }
   Node* r = new_node(ctx, Kind::DOT);
   r->dtype = GR_F32;
   r->ndim = x->ndim - 1 + y->ndim - 1;

@@ -480,7 +480,7 @@ static void extent_of(const Node* n, uintptr_t* lo, uintptr_t* hi) {
   int64_t mn = n->offset, mx = n->offset;
   for (int d = 0; d < n->ndim; ++d) {
     if (n->shape[d] == 0) { *lo = *hi = 0; return; }
-    int64_t span = (n->shape[d] - 1) * n->strides[d];
+    int64_t span = (n->shape[d] - 1) * n->strides[d];  // both factors are bounded when the node is recorded
     if (span < 0) mn += span; else mx += span;
   }
   *lo = (uintptr_t)n->data + mn * itemsize(n->dtype);

@@ -574,3 +574,84 @@ def test_async_and_serial_compilation_agree(ctx):
 def test_generated_code_has_no_contraction_or_packed_math(ctx):
     src = wl.chain(gr, ctx.spec((4096,)), ctx.spec((4096,))).source(0)
     assert "fmaf" not in src and "__fdividef" not in src and "__expf" not in src
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_api_arguments_are_answered_with_statuses(seed):
+    """Arbitrary arguments (stale handles, absurd ranks, extents of 2^40, empty axes, misaligned pointers) end in
+    a status code, never in a crash, a hang or an arithmetic overflow: planning runs on a device-less context
+    that skips launches, so everything short of the kernels themselves is exercised."""
+    import ctypes
+    import random
+
+    L = gr.lib()
+    ctx = gr.Context(device=-1)
+    ctx.set_option("dry_run", 2)
+    P = ctx._p
+    r = random.Random(seed)
+    handles = [0, 1, 2, 999999, 2**63]
+    I64 = ctypes.c_int64
+    out = ctypes.c_uint64()
+
+    def h():
+        return ctypes.c_uint64(r.choice(handles))
+
+    def extents(n):
+        n = max(n, 1)
+        return (I64 * n)(*[r.choice([-5, -1, 0, 1, 2, 3, 7, 64, 2**40]) for _ in range(n)])
+
+    made = 0
+    for _ in range(6000):
+        k = r.randrange(15)
+        st = None
+        if k == 0:
+            nd = r.choice([-1, 0, 1, 2, 3, 8, 9, 100])
+            m = min(max(nd, 0), 12)
+            st = L.gr_array_from_device(P, ctypes.c_void_p(r.choice([0, 0x1000, 0x1003])), r.choice([0, 1, 2, 3, -1]), nd,
+                                        extents(m) if r.random() < 0.9 else None, extents(m) if r.random() < 0.3 else None,
+                                        ctypes.byref(out))
+        elif k == 1:
+            st = L.gr_unary(P, r.choice([0, 1, 2, 3, 4, 5, 6, 7, 8, 16, -1, 99]), h(), ctypes.byref(out))
+        elif k == 2:
+            st = L.gr_binary(P, r.choice([16, 17, 18, 19, 20, 21, 0, 22, -3]), h(), h(), ctypes.byref(out))
+        elif k == 3:
+            st = L.gr_binary_scalar(P, r.choice([16, 17, 18, 19, 20, 21, 5]), h(), r.choice([0.0, 1.5, -2.0, float("nan"), 1e40, 3.0]),
+                                    r.choice([0, 1]), r.choice([0, 1]), ctypes.byref(out))
+        elif k == 4:
+            n = r.choice([0, 1, 2, 3, 9, -1])
+            m = max(n, 1)
+            U8 = ctypes.c_uint8 * m
+            st = L.gr_slice(P, h(), n, extents(m), extents(m), (I64 * m)(*[r.choice([1, 2, 3, 0, -1]) for _ in range(m)]),
+                            U8(*[r.choice([0, 1]) for _ in range(m)]), U8(*[r.choice([0, 1]) for _ in range(m)]), ctypes.byref(out))
+        elif k == 5:
+            perm = (ctypes.c_int * 8)(*[r.choice([0, 1, 2, 3, -1, 7, 9]) for _ in range(8)])
+            st = L.gr_transpose(P, h(), perm if r.random() < 0.8 else None, ctypes.byref(out))
+        elif k == 6:
+            axes = (ctypes.c_int * 8)(*[r.choice([0, 1, 2, -1, -2, 5, 9]) for _ in range(8)])
+            st = L.gr_reduce(P, r.choice([32, 33, 34, 0, 35]), h(), axes, r.choice([0, 1, 2, 3, 9, -1]), r.choice([0, 1]), ctypes.byref(out))
+        elif k == 7:
+            st = L.gr_scan(P, r.choice([32, 33, 34, 1]), h(), r.choice([0, 1, -1, 5, -9]), ctypes.byref(out))
+        elif k == 8:
+            st = L.gr_dot(P, h(), h(), ctypes.byref(out))
+        elif k == 9:
+            nd = r.choice([0, 1, 2, 3, 9, -1])
+            st = L.gr_reshape(P, h(), nd, extents(nd), ctypes.byref(out))
+        elif k == 10:
+            st = L.gr_materialize(P, h())
+        elif k == 11:
+            st = L.gr_assign(P, h(), h())
+        elif k == 12 and r.random() < 0.2:
+            st = L.gr_release(P, h())
+        elif k == 13:
+            need = ctypes.c_size_t()
+            st = L.gr_plan_describe(P, h(), None, 0, ctypes.byref(need))
+        elif k == 14:
+            st = L.gr_materialize_into(P, h(), ctypes.c_void_p(r.choice([0, 0x2000, 0x2002])), r.choice([0, 4, 16, 4096]))
+        assert st is None or 0 <= st <= 11
+        if st == 0 and k <= 9:
+            made += 1
+            handles.append(out.value)
+            if len(handles) > 60:
+                handles.pop(r.randrange(5, len(handles)))
+    assert made > 200
+    ctx.close()
