@@ -139,6 +139,16 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     dimension is the row dimension of the iteration space
  *                     (transposed views) through 64 x 64 tiles transposed in LDS;
  *                     0 = strided loads
+ *   "plan_cache"      1 (default) = a request whose sub-DAG has the structure of an
+ *                     earlier one (node kinds, shapes, strides of stored arrays,
+ *                     slice bounds, scalar values, sharing of operands, recording
+ *                     order) reuses that request's partition and index maps
+ *                     instead of planning again (iterative programs record the
+ *                     same expression every sweep); 0 = plan every request;
+ *                     2 = reuse, but also plan afresh and fail the request
+ *                     (GR_ERR_UNSUPPORTED) if the two plans differ (self-check);
+ *                     the environment variable GR_PLAN_CACHE gives the value a
+ *                     new context starts with
  *   "dry_run"         on a device-less context only: 1 = materialise and assign
  *                     calls run everything except the kernel launches
  *                     (partitioning, code generation, compilation, buffer and
@@ -313,6 +323,7 @@ typedef struct {
   uint64_t nodes_merged;      /* recordings answered with an equal pending node (option "merge") */
   uint64_t interp_launches;   /* sub-graphs evaluated by the byte-code interpreter (option "interp") */
   uint64_t assign_swaps;      /* slice assignments done by writing a second buffer and swapping (option "assign_swap") */
+  uint64_t plan_hits;         /* requests answered with a remembered plan (option "plan_cache") */
 } gr_stats_t;
 
 gr_status gr_stats(gr_ctx* ctx, gr_stats_t* out);

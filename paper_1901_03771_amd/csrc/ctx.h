@@ -40,6 +40,8 @@ struct gr_ctx {
   int64_t opt_assign_swap = 1;
   int64_t opt_dry_run = 0;
   int64_t opt_stage = 1;
+  int64_t opt_plan_cache = 1;
+  uint64_t options_epoch = 0;  // bumped by every gr_ctx_set_option: part of a request's fingerprint
   uintptr_t dry_next = 0x100000;  // fake device addresses handed out by a dry run
 
   // allocator
@@ -71,6 +73,10 @@ struct gr_ctx {
   std::unordered_map<std::string, std::pair<std::shared_ptr<CompileJob>, std::future<void>>> pending;
   std::string cache_dir;       // "" = not resolved yet, "-" = unavailable
 
+  // plan cache: fingerprint hash -> remembered requests
+  std::unordered_multimap<uint64_t, std::unique_ptr<gr::PlanEntry>> plan_cache;
+  uint64_t walk_epoch = 0, plan_clock = 0;
+
   // workspace for two-stage kernels
   void* workspace = nullptr;
   size_t workspace_bytes = 0;
@@ -99,7 +105,8 @@ void* ctx_alloc(gr_ctx* c, size_t bytes);
 void ctx_free(gr_ctx* c, void* p, size_t bytes);
 
 // plan.cpp
-gr_status make_plan(gr_ctx* c, Node* root, Plan* plan);
+gr_status make_plan(gr_ctx* c, Node* root, Plan* plan);           // plancache.cpp: remembered or planned afresh
+gr_status make_plan_uncached(gr_ctx* c, Node* root, Plan* plan);  // plan.cpp
 void clear_planned(Plan* plan);
 gr_status expand_patch(gr_ctx* c, GroupPlan* g);
 std::string describe_plan(const Plan& plan);

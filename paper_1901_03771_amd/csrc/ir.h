@@ -31,6 +31,8 @@ struct Node {
   int handle_refs = 0;
   int consumer_refs = 0;
   uint64_t shash = 0;  // hash of the expression below this node (materialised nodes: of their identity)
+  uint64_t walk_epoch = 0;  // numbering of the request being fingerprinted (plan cache)
+  int walk_idx = -1;
 
   // "data" / "is_materialized"
   bool materialized = false;
@@ -209,11 +211,32 @@ struct OutSpec {
   int64_t strides[MAXD] = {0};
 };
 
+struct PlanEntry;
+
 struct Plan {
   std::vector<std::unique_ptr<GroupPlan>> groups;
   std::vector<Node*> planned_nodes;
   const OutSpec* out = nullptr;  // in: where the root's elements go
   bool out_honoured = true;      // out: false if the root's sub-graph can only write a contiguous buffer
+  PlanEntry* entry = nullptr;    // plan cache entry the sub-graphs are on loan from (handed back on destruction)
+  Plan() = default;
+  Plan(const Plan&) = delete;
+  Plan& operator=(const Plan&) = delete;
+  ~Plan();
+};
+
+// One remembered request (see plancache.cpp): the fingerprint of the sub-DAG it was planned for,
+// the sub-graph list, and for every node pointer inside that list the position of the node in
+// the fingerprint's numbering, so that the list can be pointed at the nodes of a later request
+// with the same fingerprint.
+struct PlanEntry {
+  std::vector<int64_t> key;
+  std::vector<std::unique_ptr<GroupPlan>> groups;
+  bool out_honoured = true;
+  std::vector<int> slots;    // numbering position per pointer slot, in the order of the slot walk
+  std::vector<int> planned;  // roots marked as planned, in order
+  bool on_loan = false;
+  uint64_t last_use = 0;
 };
 
 }  // namespace gr

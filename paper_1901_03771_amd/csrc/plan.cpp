@@ -1163,7 +1163,7 @@ static void fuse_gemv_pairs(gr_ctx* c, Plan* plan) {
   }
 }
 
-gr_status make_plan(gr_ctx* c, Node* root, Plan* plan) {
+gr_status make_plan_uncached(gr_ctx* c, Node* root, Plan* plan) {
   if (root->kind == Kind::SCALAR) return fail(c, GR_ERR_UNSUPPORTED, "a bare scalar cannot be materialised");
   Planner pl;
   pl.c = c;

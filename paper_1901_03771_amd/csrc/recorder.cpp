@@ -209,6 +209,7 @@ const char* gr_last_error(gr_ctx* ctx) { return ctx ? ctx->err.c_str() : g_creat
 gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   if (!ctx || !key) return GR_ERR_ARG;
   std::string k(key);
+  ctx->options_epoch++;
   if (k == "fusion") ctx->opt_fusion = value;
   else if (k == "rowred_max_cols") ctx->opt_rowred_max_cols = value;
   else if (k == "map_rows") ctx->opt_map_rows = value;
@@ -227,6 +228,7 @@ gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   else if (k == "assign_swap") ctx->opt_assign_swap = value;
   else if (k == "dry_run") ctx->opt_dry_run = value;
   else if (k == "stage_transposed") ctx->opt_stage = value;
+  else if (k == "plan_cache") ctx->opt_plan_cache = value;
   else return fail(ctx, GR_ERR_ARG, "unknown option '" + k + "'");
   return GR_OK;
 }

@@ -612,6 +612,7 @@ gr_status gr_ctx_create(gr_ctx** out, int device, void* hip_stream) {
   gr_ctx* c = new gr_ctx();
   c->device = device;
   c->stream = (hipStream_t)hip_stream;
+  if (const char* pc = getenv("GR_PLAN_CACHE")) c->opt_plan_cache = atoi(pc);  // initial value of option "plan_cache"
   if (device >= 0) {
     int n = 0;
     hipError_t e = hipGetDeviceCount(&n);

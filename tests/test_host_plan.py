@@ -655,3 +655,57 @@ def test_random_api_arguments_are_answered_with_statuses(seed):
                 handles.pop(r.randrange(5, len(handles)))
     assert made > 200
     ctx.close()
+
+
+def test_repeated_requests_reuse_the_remembered_plan(ctx):
+    # An iterative program records the same expression again over new nodes: from the second sweep on the
+    # partition comes from the plan cache.  With "plan_cache" = 2 every hit is also planned afresh and the
+    # request fails if the two plans differ, so this doubles as the check of the cache's fingerprint.
+    import fuzz
+    ctx.set_option("dry_run", 2)
+    ctx.set_option("plan_cache", 2)
+    from paper_1901_03771_amd import workloads as W
+    grid = ctx.spec((130, 258))
+    for _ in range(4):
+        grid[1:-1, 1:-1] = W.jacobi_sweep(gr, grid)
+    X, w, y = ctx.spec((3001, 200)), ctx.spec((200,)), ctx.spec((3001,))
+    for _ in range(3):
+        w = W.logreg(gr, X, w, y).materialize()
+    h0 = ctx.stats()["plan_hits"]
+    assert h0 >= 4
+    # the same structure over different constants, shapes, strides, sharing or recording order is a different request
+    a, b = ctx.spec((64, 32)), ctx.spec((64, 32))
+    def hits_after(f):
+        before = ctx.stats()["plan_hits"]
+        f().materialize()
+        return ctx.stats()["plan_hits"] - before
+    assert hits_after(lambda: a * 2.0 + b) == 0
+    assert hits_after(lambda: a * 2.0 + b) == 1
+    assert hits_after(lambda: a * 3.0 + b) == 0                       # another constant
+    assert hits_after(lambda: a * 2.0 + a) == 0                       # operands shared
+    assert hits_after(lambda: ctx.spec((64, 33)) * 2.0 + ctx.spec((64, 33))) == 0
+    assert hits_after(lambda: ctx.spec((64, 32), strides=(1, 64)) * 2.0 + b) == 0
+    assert hits_after(lambda: a[:, 1:] * 2.0 + b[:, :-1]) == 0
+    assert hits_after(lambda: a[:, 1:] * 2.0 + b[:, :-1]) == 1
+    assert hits_after(lambda: a[:, 2:] * 2.0 + b[:, :-2]) == 0
+    def other_order():
+        t = b + 0.0
+        return a * 2.0 + t
+    def this_order():
+        t = a * 2.0
+        return t + (b + 0.0)
+    assert hits_after(this_order) == 0 and hits_after(this_order) == 1 and hits_after(other_order) == 0
+    ctx.set_option("fusion", 0)                                       # options are part of the fingerprint
+    assert hits_after(lambda: a * 2.0 + b) == 0
+    ctx.set_option("fusion", 1)
+    # random programs, each run three times in a row on the same context
+    before = ctx.stats()["plan_hits"]
+    for seed in list(range(7000, 7150)) + list(range(400000, 400060)):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed, assign=(seed % 2 == 0), reshape=seed >= 400000)
+        for rep in range(3):
+            leaves = [ctx.spec(s_, gr.GR_I32 if dtype == "i32" else gr.GR_F32) for s_ in shapes]
+            for x in fuzz.apply(gr, steps, leaves):
+                x.materialize()
+    assert ctx.stats()["plan_hits"] - before > 300
+    ctx.set_option("plan_cache", 0)
+    assert hits_after(lambda: a * 2.0 + b) == 0
