@@ -1,8 +1,10 @@
-"""Builds the C-ABI library libgrumpy_hip.so in-tree with hipcc for gfx950."""
+"""Builds, in-tree, the C-ABI library libgrumpy_hip.so (hipcc, gfx950) and the CPython type with the
+binding's recording fast paths (_fastbind, host C)."""
 from __future__ import annotations
 
 import os
 import subprocess
+import sysconfig
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -25,7 +27,22 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+    build_fastbind(verbose)
     return LIB
+
+
+def build_fastbind(verbose: bool = False) -> str:
+    out = os.path.join(HERE, "_fastbind" + (sysconfig.get_config_var("EXT_SUFFIX") or ".so"))
+    cmd = [os.environ.get("CC", "gcc"), "-O2", "-fPIC", "-shared", "-Wall", "-I" + sysconfig.get_paths()["include"],
+           os.path.join(CSRC, "fastbind.c"), "-o", out]
+    if verbose:
+        print(" ".join(cmd))
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building _fastbind failed:\n" + r.stdout)
+    if verbose and r.stdout.strip():
+        print(r.stdout)
+    return out
 
 
 if __name__ == "__main__":

@@ -23,6 +23,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("GRUMPY_HIP_LIB", os.path.join(_HERE, "libgrumpy_hip.so"))
 
 GR_F32, GR_I32, GR_I64 = 0, 1, 2
+GR_NEG, GR_ABS, GR_EXP, GR_LOG, GR_SQRT, GR_SQUARE, GR_TANH, GR_ERF = range(8)
+GR_ADD, GR_SUB, GR_MUL, GR_DIV, GR_MAXIMUM, GR_MINIMUM = range(16, 22)
 _UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "square": 5, "tanh": 6, "erf": 7}
 _BINARY = {"add": 16, "sub": 17, "mul": 18, "div": 19, "maximum": 20, "minimum": 21}
 _REDUCE = {"sum": 32, "max": 33, "min": 34}
@@ -103,6 +105,7 @@ def lib():
     L.gr_last_error.argtypes = [P]
     L.gr_last_error.restype = ctypes.c_char_p
     _lib = L
+    _bind_fast_paths(L)
     return L
 
 
@@ -143,10 +146,12 @@ class Context:
         st = L.gr_ctx_create(ctypes.byref(self._p), int(device), ctypes.c_void_p(stream or 0))
         if st:
             raise GrError(st, L.gr_last_error(None).decode())
+        self._addr = self._p.value or 0  # what the C fast paths read; 0 once closed
         self.device = int(device)
         _LIVE.add(self)
 
     def close(self):
+        self._addr = 0
         if self._p:
             lib().gr_ctx_destroy(self._p)
             self._p = ctypes.c_void_p()
@@ -278,16 +283,15 @@ class _DeviceExport:
                                          "strides": byte_strides if len(shape) else None}
 
 
-class Array:
-    """Handle of one DAG node."""
-
-    __array_priority__ = 1000
+class _PyArrayBase:
+    """The recording calls through ctypes alone (GRUMPY_NO_FASTBIND=1): what _fastbind.ArrayBase does in C."""
 
     __slots__ = ("ctx", "h", "_owner")
 
     def __init__(self, ctx: Context, handle: int):
         self.ctx = ctx
         self.h = handle
+        self._owner = None
 
     def __del__(self):
         try:
@@ -296,6 +300,35 @@ class Array:
                 _lib.gr_release(p, self.h)
         except Exception:
             pass
+
+    def materialize(self):
+        self.ctx.check(lib().gr_materialize(self.ctx._p, self.h))
+        return self
+
+    def __add__(self, o): return _binary_slow(GR_ADD, self, o)
+    def __radd__(self, o): return _binary_slow(GR_ADD, o, self)
+    def __sub__(self, o): return _binary_slow(GR_SUB, self, o)
+    def __rsub__(self, o): return _binary_slow(GR_SUB, o, self)
+    def __mul__(self, o): return _binary_slow(GR_MUL, self, o)
+    def __rmul__(self, o): return _binary_slow(GR_MUL, o, self)
+    def __truediv__(self, o): return _binary_slow(GR_DIV, self, o)
+    def __rtruediv__(self, o): return _binary_slow(GR_DIV, o, self)
+    def __neg__(self): return _unary_slow(GR_NEG, self)
+    def __abs__(self): return _unary_slow(GR_ABS, self)
+    def __matmul__(self, o): return dot(self, o)
+    def __pow__(self, e): return _pow_slow(self, e)
+    def __getitem__(self, key): return slice_(self, key)
+    def __setitem__(self, key, value): _setitem_slow(self, key, value)
+
+    @property
+    def T(self):
+        return transpose(self)
+
+
+class _ArrayMethods:
+    """Everything of an Array that is not on the recording fast path."""
+
+    __slots__ = ()
 
     # -- inspection -----------------------------------------------------------
     @property
@@ -335,10 +368,6 @@ class Array:
         return (self * 1).materialize()
 
     # -- materialisation --------------------------------------------------------
-    def materialize(self) -> "Array":
-        self.ctx.check(lib().gr_materialize(self.ctx._p, self.h))
-        return self
-
     def materialize_into(self, t) -> "Array":
         st = _lib.gr_materialize_into(self.ctx._p, self.h, t.data_ptr(), t.numel() * t.element_size())
         if st:
@@ -381,37 +410,7 @@ class Array:
         self.ctx.check(lib().gr_plan_compile(self.ctx._p, self.h))
         return self
 
-    # -- operators ----------------------------------------------------------------
-    def __add__(self, o): return binary("add", self, o)
-    def __radd__(self, o): return binary("add", o, self)
-    def __sub__(self, o): return binary("sub", self, o)
-    def __rsub__(self, o): return binary("sub", o, self)
-    def __mul__(self, o): return binary("mul", self, o)
-    def __rmul__(self, o): return binary("mul", o, self)
-    def __truediv__(self, o): return binary("div", self, o)
-    def __rtruediv__(self, o): return binary("div", o, self)
-    def __neg__(self): return unary("neg", self)
-    def __abs__(self): return unary("abs", self)
-    def __matmul__(self, o): return dot(self, o)
-
-    def __pow__(self, e):
-        if isinstance(e, int) and e == 2:
-            return unary("square", self)  # NumPy evaluates x**2 as square(x)
-        raise GrError(5, "only **2 is supported")
-
-    def __getitem__(self, key):
-        return slice_(self, key)
-
-    def __setitem__(self, key, value):
-        if not isinstance(value, Array):
-            raise GrError(5, "only arrays can be assigned")
-        dst = slice_(self, key)
-        self.ctx.check(lib().gr_assign(self.ctx._p, dst.h, value.h))
-
-    @property
-    def T(self):
-        return transpose(self)
-
+    # -- NumPy-named methods --------------------------------------------------------
     def sum(self, axis=None, keepdims=False): return reduce("sum", self, axis, keepdims)
     def max(self, axis=None, keepdims=False): return reduce("max", self, axis, keepdims)
     def min(self, axis=None, keepdims=False): return reduce("min", self, axis, keepdims)
@@ -420,6 +419,38 @@ class Array:
 
     def reshape(self, *shape):
         return reshape(self, shape[0] if len(shape) == 1 and not isinstance(shape[0], int) else shape)
+
+
+def _load_fastbind():
+    """The C type with the recording fast paths (built in-tree by build.py).  GRUMPY_NO_FASTBIND=1
+    selects the ctypes-only route instead; a missing module is an error, not a silent fallback."""
+    if os.environ.get("GRUMPY_NO_FASTBIND") == "1":
+        return None
+    try:
+        from . import _fastbind
+    except ImportError as e:
+        raise ImportError(f"{e}: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or set GRUMPY_NO_FASTBIND=1 for the ctypes-only binding)") from None
+    return _fastbind
+
+
+_fastbind = _load_fastbind()
+
+
+class Array(_PyArrayBase if _fastbind is None else _fastbind.ArrayBase, _ArrayMethods):
+    """Handle of one DAG node."""
+
+    __slots__ = ()
+    __array_priority__ = 1000
+
+
+def _bind_fast_paths(L):
+    if _fastbind is None:
+        return
+    names = ["gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose", "gr_dot", "gr_assign",
+             "gr_materialize", "gr_release", "gr_reduce", "gr_ndim", "gr_shape"]
+    _fastbind.bind({n: ctypes.cast(getattr(L, n), ctypes.c_void_p).value for n in names})
+    _fastbind.set_hooks(_binary_slow, slice_, _setitem_slow, _pow_slow, _reduce_slow)
 
 
 def _ctx_of(*xs) -> Context:
@@ -437,17 +468,16 @@ def _operand(ctx: Context, x) -> Array:
     return ctx.scalar(x)
 
 
-def unary(name: str, a) -> Array:
+def _unary_slow(op: int, a) -> Array:
     ctx = _ctx_of(a)
     h = ctypes.c_uint64()
-    st = _lib.gr_unary(ctx._p, _UNARY[name], a.h, ctypes.byref(h))
+    st = _lib.gr_unary(ctx._p, op, a.h, ctypes.byref(h))
     if st:
         ctx.check(st)
     return Array(ctx, h.value)
 
 
-def binary(name: str, a, b) -> Array:
-    op = _BINARY[name]
+def _binary_slow(op: int, a, b) -> Array:
     h = ctypes.c_uint64()
     if isinstance(a, Array):
         ctx = a.ctx
@@ -465,6 +495,31 @@ def binary(name: str, a, b) -> Array:
     if st:
         ctx.check(st)
     return Array(ctx, h.value)
+
+
+def _pow_slow(a, e) -> Array:
+    if isinstance(a, Array) and isinstance(e, int) and not isinstance(e, bool) and e == 2:
+        return _unary(GR_SQUARE, a)  # NumPy evaluates x**2 as square(x)
+    raise GrError(5, "only **2 is supported")
+
+
+def _setitem_slow(a, key, value):
+    if not isinstance(value, Array):
+        raise GrError(5, "only arrays can be assigned")
+    dst = slice_(a, key)
+    a.ctx.check(lib().gr_assign(a.ctx._p, dst.h, value.h))
+
+
+_unary = _unary_slow if _fastbind is None else _fastbind.unary
+_binary = _binary_slow if _fastbind is None else _fastbind.binary
+
+
+def unary(name: str, a) -> Array:
+    return _unary(_UNARY[name], a)
+
+
+def binary(name: str, a, b) -> Array:
+    return _binary(_BINARY[name], a, b)
 
 
 def _number(v):
@@ -515,6 +570,10 @@ def reshape(a: Array, shape) -> Array:
 
 
 def reduce(name: str, a: Array, axis=None, keepdims=False) -> Array:
+    return _reduce(_REDUCE[name], a, axis, keepdims)
+
+
+def _reduce_slow(op: int, a: Array, axis=None, keepdims=False) -> Array:
     if axis is None:
         axes = []
     elif isinstance(axis, int):
@@ -525,8 +584,11 @@ def reduce(name: str, a: Array, axis=None, keepdims=False) -> Array:
             raise GrError(4, "empty axis tuple")
     arr = (ctypes.c_int * builtins.max(len(axes), 1))(*axes)
     h = ctypes.c_uint64()
-    a.ctx.check(lib().gr_reduce(a.ctx._p, _REDUCE[name], a.h, arr, len(axes), int(bool(keepdims)), ctypes.byref(h)))
+    a.ctx.check(lib().gr_reduce(a.ctx._p, op, a.h, arr, len(axes), int(bool(keepdims)), ctypes.byref(h)))
     return Array(a.ctx, h.value)
+
+
+_reduce = _reduce_slow if _fastbind is None else _fastbind.reduce
 
 
 def scan(name: str, a: Array, axis: int) -> Array:
@@ -546,26 +608,28 @@ def cummin(a, axis=None): return _scan_axis("min", a, axis)
 
 
 def dot(a: Array, b: Array) -> Array:
+    if not isinstance(a, Array) or not isinstance(b, Array):
+        raise TypeError("dot: both operands must be arrays")
     h = ctypes.c_uint64()
     a.ctx.check(lib().gr_dot(a.ctx._p, a.h, b.h, ctypes.byref(h)))
     return Array(a.ctx, h.value)
 
 
 # NumPy-named functions
-def add(a, b): return binary("add", a, b)
-def subtract(a, b): return binary("sub", a, b)
-def multiply(a, b): return binary("mul", a, b)
-def divide(a, b): return binary("div", a, b)
-def maximum(a, b): return binary("maximum", a, b)
-def minimum(a, b): return binary("minimum", a, b)
-def negative(a): return unary("neg", a)
-def absolute(a): return unary("abs", a)
-def exp(a): return unary("exp", a)
-def log(a): return unary("log", a)
-def sqrt(a): return unary("sqrt", a)
-def square(a): return unary("square", a)
-def tanh(a): return unary("tanh", a)
-def erf(a): return unary("erf", a)
-def sum(a, axis=None, keepdims=False): return reduce("sum", a, axis, keepdims)  # noqa: A001
-def max(a, axis=None, keepdims=False): return reduce("max", a, axis, keepdims)  # noqa: A001
-def min(a, axis=None, keepdims=False): return reduce("min", a, axis, keepdims)  # noqa: A001
+def add(a, b): return _binary(GR_ADD, a, b)
+def subtract(a, b): return _binary(GR_SUB, a, b)
+def multiply(a, b): return _binary(GR_MUL, a, b)
+def divide(a, b): return _binary(GR_DIV, a, b)
+def maximum(a, b): return _binary(GR_MAXIMUM, a, b)
+def minimum(a, b): return _binary(GR_MINIMUM, a, b)
+def negative(a): return _unary(GR_NEG, a)
+def absolute(a): return _unary(GR_ABS, a)
+def exp(a): return _unary(GR_EXP, a)
+def log(a): return _unary(GR_LOG, a)
+def sqrt(a): return _unary(GR_SQRT, a)
+def square(a): return _unary(GR_SQUARE, a)
+def tanh(a): return _unary(GR_TANH, a)
+def erf(a): return _unary(GR_ERF, a)
+def sum(a, axis=None, keepdims=False): return _reduce(32, a, axis, keepdims)  # noqa: A001
+def max(a, axis=None, keepdims=False): return _reduce(33, a, axis, keepdims)  # noqa: A001
+def min(a, axis=None, keepdims=False): return _reduce(34, a, axis, keepdims)  # noqa: A001

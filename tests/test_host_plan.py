@@ -709,3 +709,77 @@ def test_repeated_requests_reuse_the_remembered_plan(ctx):
     assert ctx.stats()["plan_hits"] - before > 300
     ctx.set_option("plan_cache", 0)
     assert hits_after(lambda: a * 2.0 + b) == 0
+
+
+_BINDING_PROBE = r"""
+import sys, json
+import numpy as np
+from paper_1901_03771_amd import lazy as gr, workloads as W
+ctx = gr.Context(device=-1)
+out = {"fast": gr._fastbind is not None}
+a, b = ctx.spec((6, 40)), ctx.spec((6, 40))
+i = ctx.spec((6, 40), gr.GR_I32)
+progs = {
+    "ops": lambda: gr.maximum(abs(-a) * 2 + 1.5 - b / 3.0, 0.25) ** 2 @ b.T,
+    "rops": lambda: 2 * a + (1.0 - b) + 3 / (a * a) - np.float32(0.5) * b,
+    "int": lambda: (i * 3 - i) + 7,
+    "slices": lambda: a[1:-1, ::2] + b[:-2, 1::2] + a[..., 0:20][1:5] if False else a[1:-1, ::2] + b[:-2, 1::2],
+    "reduce": lambda: gr.sum(gr.exp(a - gr.max(a, axis=1, keepdims=True)), axis=(0, 1)) + a.sum(axis=-1).max(),
+    "softmax": lambda: W.softmax(gr, a),
+    "stencil": lambda: W.stencil(gr, ctx.spec((40, 50))),
+}
+for k, f in progs.items():
+    r = f()
+    out[k] = [list(r.shape), r.ndim, r.plan().count("\n")]
+def code_of(f):
+    try:
+        f()
+    except gr.GrError as e:
+        return e.code
+    except Exception as e:
+        return type(e).__name__
+    return "no error"
+out["errors"] = [code_of(lambda: a + True), code_of(lambda: a + "x"), code_of(lambda: a[0]), code_of(lambda: a ** 3),
+                 code_of(lambda: a + ctx.spec((7, 40))), code_of(lambda: i * 0.5), code_of(lambda: i + 2**40),
+                 code_of(lambda: a.__setitem__((slice(None), slice(None)), 1.0)), code_of(lambda: gr.sum(a, axis=())),
+                 code_of(lambda: gr.sum(a, axis=5)), code_of(lambda: a @ 3), code_of(lambda: a + gr.Context(device=-1).spec((6, 40)))]
+ctx.set_option("dry_run", 2)
+del r
+import gc
+gc.collect()
+g = ctx.spec((34, 66))
+base = ctx.stats()["nodes_alive"]
+for _ in range(3):
+    g[1:-1, 1:-1] = W.jacobi_sweep(gr, g)
+tmp = a * 2.0 + g[0:6, 0:40]
+del tmp
+out["alive_after_jacobi"] = ctx.stats()["nodes_alive"] - base
+ctx2 = gr.Context(device=-1)
+z = ctx2.spec((3,)) + 1.0
+ctx2.close()
+out["closed"] = code_of(lambda: z + 1.0)
+del z
+print(json.dumps(out))
+"""
+
+
+def test_c_fast_paths_and_ctypes_route_of_the_binding_agree():
+    # The Array type's operators run in C (_fastbind); GRUMPY_NO_FASTBIND=1 selects the ctypes-only
+    # implementation of the same calls.  Both record the same DAGs, raise the same errors and release
+    # every handle.
+    import json
+    import subprocess
+    import sys
+    outs = []
+    for no_fast in ("0", "1"):
+        env = dict(os.environ, GRUMPY_NO_FASTBIND=no_fast)
+        r = subprocess.run([sys.executable, "-c", _BINDING_PROBE], env=env, capture_output=True, text=True, timeout=300,
+                           cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+        assert r.returncode == 0, r.stderr[-2000:]
+        outs.append(json.loads(r.stdout.strip().splitlines()[-1]))
+    assert outs[0].pop("fast") is True and outs[1].pop("fast") is False
+    assert outs[0].pop("closed") in ("RuntimeError", "GR_ERR_ARG") and outs[1].pop("closed") in ("RuntimeError", "GR_ERR_ARG")
+    assert outs[0] == outs[1]
+    assert outs[0]["alive_after_jacobi"] == 0
+    assert outs[0]["errors"] == ["GR_ERR_UNSUPPORTED", "TypeError", "GR_ERR_UNSUPPORTED", "GR_ERR_UNSUPPORTED", "GR_ERR_SHAPE", "GR_ERR_DTYPE",
+                                 "GR_ERR_DTYPE", "GR_ERR_UNSUPPORTED", "GR_ERR_AXIS", "GR_ERR_AXIS", "TypeError", "ValueError"]
