@@ -120,7 +120,9 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     execution, Section 6 of the paper); 0 = one after another
  *   "disk_cache"      1 (default) = compiled code objects are kept in
  *                     $GR_CACHE_DIR (default ~/.cache/grumpy_hip) keyed on
- *                     the sub-graph signature; 0 = in-memory cache only
+ *                     the generated kernel source (and compiler version and
+ *                     flags), so another build of the library never reads
+ *                     them by mistake; 0 = in-memory cache only
  *   "interp"          1 (default) = a map sub-graph whose kernel is still in the
  *                     run-time compiler is evaluated by a precompiled byte-code
  *                     interpreter of the point function instead of waiting
@@ -139,6 +141,14 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     dimension is the row dimension of the iteration space
  *                     (transposed views) through 64 x 64 tiles transposed in LDS;
  *                     0 = strided loads
+ *   "scan_min_threads", "scan_threads"
+ *                     a scan along a non-contiguous axis gives each thread one
+ *                     line (four neighbouring lines with dwordx4 loads); with
+ *                     fewer threads than scan_min_threads the lines are cut into
+ *                     chunks so that about scan_threads threads run, at the
+ *                     price of a second read of the input; 0 (default) =
+ *                     16384 / 65536 with dwordx4 loads, 32768 / 131072 with
+ *                     scalar loads
  *   "plan_cache"      1 (default) = a request whose sub-DAG has the structure of an
  *                     earlier one (node kinds, shapes, strides of stored arrays,
  *                     slice bounds, scalar values, sharing of operands, recording

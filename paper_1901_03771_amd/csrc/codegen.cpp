@@ -47,9 +47,10 @@ bool nontemporal_group(const GroupPlan& g, int group) {
   if (access_class(ag, g.rank - 1) != '1') return false;
   if (g.nt >= 2) return true;
   if (ag.deltas.size() > 1) return false;
-  bool varies_outside_columns = g.rank < 2;
-  for (int k = 0; k + 1 < g.rank; ++k) if (!ag.structural_zero[k]) varies_outside_columns = true;
-  return varies_outside_columns;
+  // read once = the operand follows every outer iteration dimension; one that is broadcast along
+  // any of them is read again by other rows or planes and stays cacheable
+  for (int k = 0; k + 1 < g.rank; ++k) if (ag.structural_zero[k]) return false;
+  return true;
 }
 
 ArgLayout arg_layout(const GroupPlan& g) {
@@ -947,10 +948,16 @@ void gen_scan(Em& e) {
     e.o << "  for (int u = 0; u < 16; ++u) if (u < per && c0 + u < NCHUNK) { w[c0 + u] = off; off = gr_comb0(off, v[u]); }\n}\n";
   };
 
+  // Mode 1 walks a line sequentially; the running value makes every step depend on the one before,
+  // and in the scan kernel the store of a step may alias the next load as far as the compiler
+  // knows, so left alone each step waits for its own load.  The steps are therefore taken U at a
+  // time: all loads of a batch first, then the U combines (and stores); a scalar loop finishes
+  // the chunk.
+  const int U = g.prog.size() <= 16 ? 8 : (g.prog.size() <= 48 ? 4 : 2);
   if (g.scan_mode == 1 && g.scan_vec) {
-    // as below with four neighbouring lines per thread: one dwordx4 per array and step
+    // four neighbouring lines per thread: one dwordx4 per array and step
     const int ld = sd - 1;
-    auto body = [&](bool store) {
+    auto loads = [&](const std::string& jx, const std::string& sfx, const std::string& ind) {
       for (size_t i = 0; i < g.prog.size(); ++i) {
         const Instr& in = g.prog[i];
         if (in.kind != IKind::LOAD) continue;
@@ -958,35 +965,46 @@ void gen_scan(Em& e) {
         std::ostringstream at;
         at << "p" << in.group << " + 0";
         for (int k = 0; k < sd; ++k) if (!ag.structural_zero[k] && in.delta[k]) at << " + " << in.delta[k] << (k == ld ? std::string("") : " * " + e.coef(in.group, k));
-        if (!ag.structural_zero[sd]) at << " + (j + " << in.delta[sd] << ") * " << e.coef(in.group, sd);
-        if (ag.structural_zero[ld]) e.o << "    const " << cty(in.dtype) << " u" << i << " = (" << at.str() << ")[0];\n";
-        else e.o << "    const " << vty4(in.dtype) << " w" << i << " = " << e.ld(in.group, vty4(in.dtype), at.str()) << ";\n";
+        if (!ag.structural_zero[sd]) at << " + (" << jx << " + " << in.delta[sd] << ") * " << e.coef(in.group, sd);
+        if (ag.structural_zero[ld]) e.o << ind << "const " << cty(in.dtype) << " u" << i << sfx << " = (" << at.str() << ")[0];\n";
+        else e.o << ind << "const " << vty4(in.dtype) << " w" << i << sfx << " = " << e.ld(in.group, vty4(in.dtype), at.str()) << ";\n";
       }
+    };
+    auto step = [&](const std::string& jx, const std::string& sfx, const std::string& ind, bool store) {
       for (int c4 = 0; c4 < 4; ++c4) {
-        const std::string pre = "v" + std::to_string(c4) + "_";
+        const std::string pre = "v" + std::to_string(c4) + sfx + "_";
         emit_scalar_program(e, g.prog, {ph.value},
                             [&](const Instr& in, int id) {
                               const AccessGroup& ag = g.groups[in.group];
-                              if (ag.structural_zero[ld]) return "u" + std::to_string(id);
-                              return "w" + std::to_string(id) + "[" + std::to_string(c4) + "]";
+                              if (ag.structural_zero[ld]) return "u" + std::to_string(id) + sfx;
+                              return "w" + std::to_string(id) + sfx + "[" + std::to_string(c4) + "]";
                             },
-                            "0.0f", pre, "    ");
-        e.o << "    acc" << c4 << " = " << Em::combine(ph, "acc" + std::to_string(c4), pre + std::to_string(ph.value)) << ";\n";
+                            "0.0f", pre, ind);
+        e.o << ind << "acc" << c4 << " = " << Em::combine(ph, "acc" + std::to_string(c4), pre + std::to_string(ph.value)) << ";\n";
       }
       if (store) {
-        if (ph.out_dtype == GR_I64) e.o << "    po[j * ostep] = acc0; po[j * ostep + 1] = acc1; po[j * ostep + 2] = acc2; po[j * ostep + 3] = acc3;\n";
+        if (ph.out_dtype == GR_I64)
+          e.o << ind << "po[(" << jx << ") * ostep] = acc0; po[(" << jx << ") * ostep + 1] = acc1; po[(" << jx << ") * ostep + 2] = acc2; po[(" << jx << ") * ostep + 3] = acc3;\n";
         else {
           const char* vt = ph.out_dtype == GR_F32 ? "f4u" : "i4u";
-          e.o << "    { " << vt << " ov; ov[0] = acc0; ov[1] = acc1; ov[2] = acc2; ov[3] = acc3; *(GM " << vt << "*)(po + j * ostep) = ov; }\n";
+          e.o << ind << "{ " << vt << " ov; ov[0] = acc0; ov[1] = acc1; ov[2] = acc2; ov[3] = acc3; *(GM " << vt << "*)(po + (" << jx << ") * ostep) = ov; }\n";
         }
       }
+    };
+    auto walk = [&](bool store) {
+      e.o << "  long long j = cbeg;\n  for (; j + " << U << " <= cend; j += " << U << ") {\n";
+      for (int u = 0; u < U; ++u) loads("j + " + std::to_string(u), "_" + std::to_string(u), "    ");
+      for (int u = 0; u < U; ++u) { e.o << "    {\n"; step("j + " + std::to_string(u), "_" + std::to_string(u), "      ", store); e.o << "    }\n"; }
+      e.o << "  }\n  for (; j < cend; ++j) {\n";
+      loads("j", "", "    ");
+      step("j", "", "    ", store);
+      e.o << "  }\n";
     };
     kernel_head(e, "gr_scan_sums");
     head(false);
     e.o << "  const long long cbeg = chunk * CH, cend = (cbeg + CH < L) ? cbeg + CH : L;\n  " << TA << " acc0 = " << ident << ", acc1 = acc0, acc2 = acc0, acc3 = acc0;\n";
-    e.o << "#pragma unroll 4\n  for (long long j = cbeg; j < cend; ++j) {\n";
-    body(false);
-    e.o << "  }\n  ws[line * NCHUNK + chunk] = acc0; ws[(line + 1) * NCHUNK + chunk] = acc1; ws[(line + 2) * NCHUNK + chunk] = acc2; ws[(line + 3) * NCHUNK + chunk] = acc3;\n}\n";
+    walk(false);
+    e.o << "  ws[line * NCHUNK + chunk] = acc0; ws[(line + 1) * NCHUNK + chunk] = acc1; ws[(line + 2) * NCHUNK + chunk] = acc2; ws[(line + 3) * NCHUNK + chunk] = acc3;\n}\n";
     offsets_kernel();
     kernel_head(e, "gr_scan");
     head(false);
@@ -994,28 +1012,51 @@ void gen_scan(Em& e) {
     e.o << "  const long long ostep = " << e.S(e.L.ocoef + sd) << ";\n";
     e.o << "  " << TA << " acc0 = " << ident << ", acc1 = acc0, acc2 = acc0, acc3 = acc0;\n";
     e.o << "  if (NCHUNK > 1) { acc0 = ws[line * NCHUNK + chunk]; acc1 = ws[(line + 1) * NCHUNK + chunk]; acc2 = ws[(line + 2) * NCHUNK + chunk]; acc3 = ws[(line + 3) * NCHUNK + chunk]; }\n";
-    e.o << "#pragma unroll 4\n  for (long long j = cbeg; j < cend; ++j) {\n";
-    body(true);
-    e.o << "  }\n}\n";
+    walk(true);
+    e.o << "}\n";
     return;
   }
   if (g.scan_mode == 1) {
     // a thread per (line, chunk), sequential along the axis; with several chunks per line the same
     // three steps as in mode 0: chunk totals, exclusive scan of the totals, chunks with offsets
+    auto walk = [&](bool store) {
+      e.o << "  long long j = cbeg;\n  for (; j + " << U << " <= cend; j += " << U << ") {\n";
+      // the loads of the whole batch first (a load's value is named <prefix><id>)
+      for (int u = 0; u < U; ++u) {
+        const std::string pre = "t" + std::to_string(u) + "_";
+        for (size_t i = 0; i < g.prog.size(); ++i) {
+          if (g.prog[i].kind != IKind::LOAD) continue;
+          e.o << "    const " << cty(g.prog[i].dtype) << ' ' << pre << i << " = " << load_at("(j + " + std::to_string(u) + ")")(g.prog[i], (int)i) << ";\n";
+        }
+      }
+      for (int u = 0; u < U; ++u) {
+        const std::string pre = "t" + std::to_string(u) + "_";
+        std::vector<char> have(g.prog.size(), 0);
+        for (size_t i = 0; i < g.prog.size(); ++i) if (g.prog[i].kind == IKind::LOAD) have[i] = 1;
+        e.o << "    {\n";
+        emit_scalar_program(e, g.prog, {ph.value}, load_at("j"), "0.0f", pre, "      ", &have);
+        e.o << "      acc = " << Em::combine(ph, "acc", pre + std::to_string(ph.value)) << ";\n";
+        if (store) e.o << "      po[(j + " << u << ") * ostep] = acc;\n";
+        e.o << "    }\n";
+      }
+      e.o << "  }\n  for (; j < cend; ++j) {\n";
+      emit_scalar_program(e, g.prog, {ph.value}, load_at("j"), "0.0f", "t", "    ");
+      e.o << "    acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n";
+      if (store) e.o << "    po[j * ostep] = acc;\n";
+      e.o << "  }\n";
+    };
     kernel_head(e, "gr_scan_sums");
     head(false);
     e.o << "  const long long cbeg = chunk * CH, cend = (cbeg + CH < L) ? cbeg + CH : L;\n  " << TA << " acc = " << ident << ";\n";
-    e.o << "#pragma unroll 4\n  for (long long j = cbeg; j < cend; ++j) {\n";
-    emit_scalar_program(e, g.prog, {ph.value}, load_at("j"), "0.0f", "t", "    ");
-    e.o << "    acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n  }\n  ws[line * NCHUNK + chunk] = acc;\n}\n";
+    walk(false);
+    e.o << "  ws[line * NCHUNK + chunk] = acc;\n}\n";
     offsets_kernel();
     kernel_head(e, "gr_scan");
     head(false);
     e.o << "  const long long cbeg = chunk * CH, cend = (cbeg + CH < L) ? cbeg + CH : L;\n";
     e.o << "  const long long ostep = " << e.S(e.L.ocoef + sd) << ";\n  " << TA << " acc = NCHUNK > 1 ? ws[line * NCHUNK + chunk] : " << ident << ";\n";
-    e.o << "#pragma unroll 4\n  for (long long j = cbeg; j < cend; ++j) {\n";
-    emit_scalar_program(e, g.prog, {ph.value}, load_at("j"), "0.0f", "t", "    ");
-    e.o << "    acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n    po[j * ostep] = acc;\n  }\n}\n";
+    walk(true);
+    e.o << "}\n";
     return;
   }
 

@@ -728,11 +728,16 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       g->scan_vec = ok ? 1 : 0;
     }
     if (g->scan_vec) lines /= 4;   // threads per chunk
-    if (g->scan_mode == 1 && lines < 262144 && L >= 128) {
-      // few lines, each walked by one thread: cut the lines into chunks so that about 2^19 threads
-      // run (chunk totals, scan of the totals, chunks with offsets, as above); a thread has only a
-      // few loads in flight, so it takes this many to keep HBM busy
-      int64_t want = std::max<int64_t>(1, 524288 / std::max<int64_t>(lines, 1));
+    // A thread walks its line eight steps at a time (eight loads in flight).  One pass over the
+    // lines reads the input once and is kept down to scan_min threads (measured: 2^14 threads with
+    // dwordx4 loads still beat the chunked form); below that the lines are cut into chunks so that
+    // about scan_threads threads run.
+    const int64_t scan_threads = c->opt_scan_threads > 0 ? c->opt_scan_threads : (g->scan_vec ? 65536 : 131072);
+    const int64_t scan_min = c->opt_scan_min_threads > 0 ? c->opt_scan_min_threads : (g->scan_vec ? 16384 : 32768);
+    if (g->scan_mode == 1 && lines < scan_min && L >= 128) {
+      // fewer lines than that: cut the lines into chunks (chunk totals, scan of the totals, chunks
+      // with offsets, as above), which costs a second read of the input
+      int64_t want = std::max<int64_t>(1, scan_threads / std::max<int64_t>(lines, 1));
       int64_t chunk = std::max<int64_t>(32, (L + want - 1) / want);
       int64_t nch = (L + chunk - 1) / chunk;
       if (nch > 4096) { chunk = (L + 4095) / 4096; nch = (L + chunk - 1) / chunk; }

@@ -229,6 +229,8 @@ gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   else if (k == "dry_run") ctx->opt_dry_run = value;
   else if (k == "stage_transposed") ctx->opt_stage = value;
   else if (k == "plan_cache") ctx->opt_plan_cache = value;
+  else if (k == "scan_threads") ctx->opt_scan_threads = value;
+  else if (k == "scan_min_threads") ctx->opt_scan_min_threads = value;
   else return fail(ctx, GR_ERR_ARG, "unknown option '" + k + "'");
   return GR_OK;
 }

@@ -98,9 +98,9 @@ static void run_hiprtc(gr_ctx::CompileJob* j) {
   j->ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
 }
 
-static const char kDiskMagic[8] = {'G', 'R', 'C', 'O', '0', '0', '0', '2'};
+static const char kDiskMagic[8] = {'G', 'R', 'C', 'O', '0', '0', '0', '3'};
 
-static std::string disk_path(gr_ctx* c, const std::string& sig) {
+static std::string disk_path(gr_ctx* c, const std::string& key) {
   if (!c->opt_disk_cache) return "";
   if (c->cache_dir.empty()) {
     const char* env = getenv("GR_CACHE_DIR");
@@ -117,25 +117,25 @@ static std::string disk_path(gr_ctx* c, const std::string& sig) {
     }
   }
   if (c->cache_dir == "-") return "";
-  uint64_t h = 1469598103934665603ull;  // FNV-1a over a tool tag and the signature
-  const std::string tag = std::string("grumpy-hip-2|") + std::to_string(HIP_VERSION) + "|gfx950|O3|";
+  uint64_t h = 1469598103934665603ull;  // FNV-1a over a tool tag and the key (the kernel's source text)
+  const std::string tag = std::string("grumpy-hip-3|") + std::to_string(HIP_VERSION) + "|gfx950|O3|";
   for (unsigned char ch : tag) { h ^= ch; h *= 1099511628211ull; }
-  for (unsigned char ch : sig) { h ^= ch; h *= 1099511628211ull; }
+  for (unsigned char ch : key) { h ^= ch; h *= 1099511628211ull; }
   char name[64];
-  snprintf(name, sizeof name, "/%016llx_%zu.co", (unsigned long long)h, sig.size());
+  snprintf(name, sizeof name, "/%016llx_%zu.co", (unsigned long long)h, key.size());
   return c->cache_dir + name;
 }
 
-static bool disk_load(const std::string& path, const std::string& sig, std::vector<char>* code) {
+static bool disk_load(const std::string& path, const std::string& key, std::vector<char>* code) {
   if (path.empty()) return false;
   FILE* f = fopen(path.c_str(), "rb");
   if (!f) return false;
   bool ok = false;
   char magic[8];
   uint64_t sl = 0, cl = 0;
-  if (fread(magic, 1, 8, f) == 8 && std::memcmp(magic, kDiskMagic, 8) == 0 && fread(&sl, 8, 1, f) == 1 && sl == sig.size()) {
+  if (fread(magic, 1, 8, f) == 8 && std::memcmp(magic, kDiskMagic, 8) == 0 && fread(&sl, 8, 1, f) == 1 && sl == key.size()) {
     std::string stored(sl, '\0');
-    if ((sl == 0 || fread(&stored[0], 1, sl, f) == sl) && stored == sig && fread(&cl, 8, 1, f) == 1 && cl > 0 && cl < (1ull << 30)) {
+    if ((sl == 0 || fread(&stored[0], 1, sl, f) == sl) && stored == key && fread(&cl, 8, 1, f) == 1 && cl > 0 && cl < (1ull << 30)) {
       code->resize(cl);
       ok = fread(code->data(), 1, cl, f) == cl;
     }
@@ -144,13 +144,13 @@ static bool disk_load(const std::string& path, const std::string& sig, std::vect
   return ok;
 }
 
-static void disk_store(const std::string& path, const std::string& sig, const std::vector<char>& code) {
+static void disk_store(const std::string& path, const std::string& key, const std::vector<char>& code) {
   if (path.empty()) return;
   std::string tmp = path + ".tmp" + std::to_string((long long)getpid());
   FILE* f = fopen(tmp.c_str(), "wb");
   if (!f) return;
-  uint64_t sl = sig.size(), cl = code.size();
-  bool ok = fwrite(kDiskMagic, 1, 8, f) == 8 && fwrite(&sl, 8, 1, f) == 1 && fwrite(sig.data(), 1, sl, f) == sl &&
+  uint64_t sl = key.size(), cl = code.size();
+  bool ok = fwrite(kDiskMagic, 1, 8, f) == 8 && fwrite(&sl, 8, 1, f) == 1 && fwrite(key.data(), 1, sl, f) == sl &&
             fwrite(&cl, 8, 1, f) == 1 && fwrite(code.data(), 1, cl, f) == cl;
   ok = (fclose(f) == 0) && ok;
   if (ok) ::rename(tmp.c_str(), path.c_str());  // atomic: readers see a whole file or none
@@ -193,8 +193,14 @@ static void bound_pending(gr_ctx* c);
 
 gr_status prepare_group(gr_ctx* c, GroupPlan& g) {
   if (c->cache.count(g.signature) || c->pending.count(g.signature)) return GR_OK;
+  gr_status est = expand_patch(c, &g);
+  if (est != GR_OK) return est;
+  // The on-disk cache is keyed by the generated source text itself (plus compiler version and
+  // flags), not by the signature: a library whose generator emits other code for the same
+  // structure never picks up a code object written by another build.
+  std::string src = generate_source(g);
   std::vector<char> code;
-  if (disk_load(disk_path(c, g.signature), g.signature, &code)) {
+  if (disk_load(disk_path(c, src), src, &code)) {
     c->stats.cache_misses++;
     c->stats.disk_hits++;
     std::string name;
@@ -202,11 +208,9 @@ gr_status prepare_group(gr_ctx* c, GroupPlan& g) {
     kernel_entry_points(g, &name, &combine, &scan);
     return finish_kernel(c, g.signature, name, combine, scan, std::move(code), nullptr);
   }
-  gr_status est = expand_patch(c, &g);
-  if (est != GR_OK) return est;
   bound_pending(c);
   auto job = std::make_shared<gr_ctx::CompileJob>();
-  job->src = generate_source(g);
+  job->src = std::move(src);
   kernel_entry_points(g, &job->kernel, &job->combine, &job->scan);
   if (getenv("GR_LOG")) fprintf(stderr, "---- generated kernel ----\n%s\n", job->src.c_str());
   gr_ctx::CompileJob* raw = job.get();
@@ -229,7 +233,7 @@ static gr_status collect_job(gr_ctx* c, const std::string& sig, gr_ctx::Kernel**
     if (getenv("GR_LOG")) fprintf(stderr, "%s\n", job->src.c_str());
     return fail(c, GR_ERR_COMPILE, "hipRTC: " + job->log);
   }
-  disk_store(disk_path(c, sig), sig, job->code);
+  disk_store(disk_path(c, job->src), job->src, job->code);
   if (!load) return GR_OK;
   return finish_kernel(c, sig, job->kernel, job->combine, job->scan, std::move(job->code), out);
 }

@@ -75,4 +75,7 @@ LONG_DOT_CASES = [
 SCAN_CASES = [((1000,), 0), ((37, 211), 1), ((37, 211), 0), ((4, 5, 6), 1), ((4, 5, 6), 0), ((4, 5, 6), -1), ((3, 100000), 1),
               ((1 << 21,), 0), ((5, 1), 1), ((1, 7), 0), ((1,), 0), ((600, 1030), 1), ((2, 5000), 0),
               # long lines along an axis that is not contiguous: a thread per (line, chunk)
-              ((1000, 300), 0), ((4100, 7), 0), ((3, 2000, 5), 1), ((129, 1), 0), ((70000, 2), 0)]
+              ((1000, 300), 0), ((4100, 7), 0), ((3, 2000, 5), 1), ((129, 1), 0), ((70000, 2), 0),
+              # batches of eight steps with a ragged tail: chunked (four lines per thread, one line per thread)
+              # and in one pass over the lines (enough lines for that: 2^14 threads of four lines, 2^15 of one)
+              ((1003, 300), 0), ((1003, 301), 0), ((139, 65540), 0), ((131, 33001), 0), ((5, 143, 13108), 1)]
