@@ -859,6 +859,27 @@ def test_random_programs_with_slice_assignments(env, block, owned):
             assert fuzz.same_bits(g_.numpy(), r_.numpy()), f"seed {seed} value {i}: {dtype} {shapes} {steps}"
 
 
+@pytest.mark.parametrize("block", range(3))
+def test_random_programs_run_again_on_new_data_reuse_plans(env, block):
+    # The same recipe recorded a second and third time over other input values: the requests are answered
+    # from the plan cache (and the kernel cache) and must still match the oracle on the new data; every
+    # array of the program is compared.  Recipes with slice assignments and reshapes take part.
+    import fuzz
+    gr, ctx, torch = env
+    before = ctx.stats()["plan_hits"]
+    for seed in range(9000 + 10 * block, 9000 + 10 * block + 10):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed, assign=(seed % 2 == 0), reshape=(seed % 3 == 0))
+        for rep in range(3):
+            leaves = fuzz.make_leaves(seed + 7919 * rep, dtype, shapes)
+            ref = fuzz.apply(ora, steps, [ora.array(x.copy()) for x in leaves])
+            keep = [torch.from_numpy(x.copy()).cuda() for x in leaves]
+            got = fuzz.apply(gr, steps, [ctx.array(t) for t in keep])
+            for i, (g_, r_) in enumerate(zip(got, ref)):
+                assert fuzz.same_bits(g_.numpy(), r_.numpy()), f"seed {seed} run {rep} value {i}: {dtype} {shapes} {steps}"
+            del got
+    assert ctx.stats()["plan_hits"] - before >= 10
+
+
 # ---- the byte-code interpreter that stands in while a kernel is being compiled ----------------
 
 @pytest.mark.parametrize("name", sorted(ELEMENTWISE_CASES))
