@@ -242,7 +242,7 @@ struct Builder {
           id = constant(n->dtype, 0.0);
           break;
         default:
-          invalid.push_back({n, "unexpected lazy node kind"});
+          invalid.push_back({n, "unexpected lazy node kind (" + node_label(n) + " #" + std::to_string(n->id) + ")"});
           id = constant(GR_F32, 0.0);
       }
     }
@@ -645,6 +645,13 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     if (n->kind == Kind::REDUCE) reds.push_back(n);
   }
   if (dot && !reds.empty()) { invalid->push_back({dot, "dot mixed with a reduction"}); return GR_OK; }
+  if (r->kind == Kind::RESHAPE && !r->materialized && (dot || !reds.empty())) {
+    // a reshape is a row-major copy fused with pointwise producers only: reductions and contractions
+    // below it are evaluated first and read as stored arrays
+    if (dot) invalid->push_back({dot, "dot under a reshape"});
+    for (const Node* n : reds) invalid->push_back({n, "reduction under a reshape"});
+    return GR_OK;
+  }
 
   Builder b;
   b.g = g;

@@ -738,6 +738,23 @@ def test_reshape(env):
     assert got.shape == (130 * 257,) and np.array_equal(got, ref) and np.array_equal(got, np.maximum.accumulate((big.T * f32(0.5)).ravel()))
 
 
+
+def test_reshape_of_reductions_and_contractions(env):
+    # what feeds a reshape through a reduction or a contraction is evaluated first; row-resident
+    # reductions included
+    x, w, B = _rand((67, 100), 611), _rand((100,), 612), _rand((100, 12), 613)
+    got, ref = run_both(env, lambda xp, x: xp.reshape(x - xp.max(x, axis=1, keepdims=True), (100, 67)), dict(x=x))
+    assert got.shape == (100, 67) and np.array_equal(got, ref)
+    got, ref = run_both(env, lambda xp, x: xp.reshape(xp.min(x), (1, 1)) * 2.0, dict(x=x))
+    assert got.shape == (1, 1) and np.array_equal(got, ref)
+    got, ref = run_both(env, lambda xp, x: xp.reshape(xp.sum(x, axis=0), (10, 10)), dict(x=x))
+    assert_reduction(got, ref, what="reshape of column sums")
+    got, ref = run_both(env, lambda xp, x, w: xp.reshape(xp.dot(x[:64], w) + 1.0, (8, 8)), dict(x=x, w=w))
+    assert_reduction(got, ref, what="reshape of a matrix-vector product")
+    got, ref = run_both(env, lambda xp, x, B: xp.reshape(xp.dot(x, B), (-1,)), dict(x=x, B=B))
+    assert got.shape == (67 * 12,)
+    assert_reduction(got, ref, what="reshape of a matrix product")
+
 @pytest.mark.parametrize("block", range(3))
 def test_random_programs_with_reshapes(env, block):
     import fuzz

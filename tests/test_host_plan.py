@@ -382,6 +382,14 @@ def test_reshape_records_shapes_and_is_a_fused_copy(ctx):
     z.compile()
     x.T.reshape(-1).compile()
     assert ctx.spec((0, 4)).reshape(4, 0).shape == (4, 0)
+    # reductions and contractions below a reshape are evaluated first (also the row-resident ones that
+    # would otherwise stay fused with their consumers), the pointwise rest fuses into the copy
+    m = ctx.spec((64, 100))
+    assert groups((m - gr.max(m, axis=1, keepdims=True)).reshape(100, 64)) == [("ROWRED", ["max"]), ("MAP", ["sub", "reshape"])]
+    assert [k for k, _ in groups(gr.min(ctx.spec((1,))).reshape(1))] == ["ROWRED", "MAP"]
+    assert [k for k, _ in groups((m @ ctx.spec((100,))).reshape(8, 8))] == ["GEMV", "MAP"]
+    assert [k for k, _ in groups((m @ ctx.spec((100, 32)) + 1.0).reshape(-1))] == ["GEMM", "MAP"]
+    (m - gr.max(m, axis=1, keepdims=True)).reshape(100, 64).compile()
 
 
 def test_random_programs_with_reshapes_dry_run(ctx):
