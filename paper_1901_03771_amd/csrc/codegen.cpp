@@ -435,6 +435,21 @@ void gen_map(Em& e) {
         ri += 4;
       }
   }
+  // ---- narrow arrays: the lanes of the last, incomplete group of four columns (all rows of
+  // their patch inside): the same patch program restricted to the columns that exist, scalar
+  // loads and stores, no guards ----
+  if (g.tail > 0) {
+    e.o << "  } else if (r0 + " << g.VR << " <= R && c0 + " << g.tail << " == C) {\n";
+    std::vector<int> want;
+    for (int v = 0; v < g.VR; ++v)
+      for (int j = 0; j < g.tail; ++j) want.push_back(g.results[(size_t)v * 4 + j]);
+    emit_scalar_program(e, g.prog, want,
+                        [&](const Instr& in, int) { return "p" + std::to_string(in.group) + "[" + shift_expr(in, true) + "]"; },
+                        "0.0f", "w", "    ");
+    for (int v = 0; v < g.VR; ++v)
+      for (int j = 0; j < g.tail; ++j)
+        e.o << "    po[" << v << " * orow + " << j << " * oc] = w" << g.results[(size_t)v * 4 + j] << ";\n";
+  }
   // ---- lanes on the array's edge: one guarded point at a time ----
   e.o << "  } else {\n"
          "    for (int v = 0; v < " << g.VR << "; ++v)\n"

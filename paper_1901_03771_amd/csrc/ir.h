@@ -176,6 +176,7 @@ struct GroupPlan {
   int row_threads = 64;                  // ROWRED: lanes cooperating on one row (64 or 256)
   bool xcd_remap = false;
   int stage_mask = 0;                    // MAP: access groups (bit per group) read through a transposing LDS tile
+  int tail = 0;                          // MAP: columns mod 4 of a narrow array (1..3): its last lanes get straight-line code too
   int nt = 0;                            // non-temporal load hint: 0 none, 1 arrays read once, 2 all vector loads
   int red_mode = 0;                      // REDUCE: 0 thread-per-output, 1 block-per-output
   int red_vec = 0;                       // REDUCE mode 0: a thread owns four consecutive outputs (dwordx4 loads)

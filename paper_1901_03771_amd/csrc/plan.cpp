@@ -70,6 +70,13 @@ struct Invalid {
   std::string why;
 };
 
+// A contraction over at most eight terms (points times a 3 x 3 matrix, a handful of weights) is
+// written out as products and sums inside the point function: it fuses with producers and
+// consumers like any pointwise op instead of becoming a library-style kernel of its own.
+bool small_dot(const Node* n) {
+  return n->kind == Kind::DOT && n->ndim >= 1 && n->in[1]->shape[0] <= 8;
+}
+
 // Builds the SSA program of one sub-graph.
 struct Builder {
   GroupPlan* g;
@@ -228,6 +235,31 @@ struct Builder {
           break;
         }
         case Kind::DOT: {
+          if (small_dot(n)) {
+            const Node* A = n->in[0];
+            const Node* B = n->in[1];
+            const int64_t K = B->shape[0];
+            // the sum starts from +0 like the accumulator of a contraction kernel (and of the eager
+            // evaluation): products that are all -0 add up to +0
+            id = constant(n->dtype, 0.0);
+            for (int64_t k = 0; k < K; ++k) {
+              IndexMap am(A->ndim), bm(B->ndim);
+              if (A->ndim == 2) am[0] = m[0];
+              am[A->ndim - 1] = DimMap{-1, 0, k};
+              bm[0] = DimMap{-1, 0, k};
+              if (B->ndim == 2) bm[1] = m[n->ndim - 1];
+              Instr mul;
+              mul.kind = IKind::BINARY; mul.op = GR_MUL; mul.dtype = n->dtype;
+              mul.a = eval(A, am); mul.b = eval(B, bm);
+              mul.uniform = (*prog)[mul.a].uniform && (*prog)[mul.b].uniform;
+              int p = value_number(mul);
+              Instr add;
+              add.kind = IKind::BINARY; add.op = GR_ADD; add.dtype = n->dtype; add.a = id; add.b = p;
+              add.uniform = (*prog)[id].uniform && (*prog)[p].uniform;
+              id = value_number(add);
+            }
+            break;  // (an empty contraction is the constant 0)
+          }
           bool ok = (g->kind == GroupKind::GEMV || g->kind == GroupKind::GEMM) && (dot_core == nullptr || dot_core == n);
           for (int d = 0; ok && d < n->ndim; ++d) ok = is_identity_on(m, d, d, n->shape[d]);
           if (!ok) { invalid.push_back({n, "dot result not usable as an epilogue input"}); id = constant(GR_F32, 0.0); break; }
@@ -440,7 +472,7 @@ void make_signature(GroupPlan* g) {
   std::string s;
   s.reserve(256 + 32 * (g->prog.size() + g->prog1.size()));
   for (int64_t v : {(int64_t)g->kind, (int64_t)g->rank, (int64_t)g->out_dtype, (int64_t)g->out_per_row, (int64_t)g->BX, (int64_t)g->BY,
-                    (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask, (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
+                    (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask + (((int64_t)g->tail) << 40), (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
                     (int64_t)g->red_kept_rank, (int64_t)g->gemv_mode, (int64_t)g->LPR, (int64_t)g->KV, (int64_t)g->mat_group,
                     (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode + 16 * (int64_t)g->scan_vec, (int64_t)g->out_unit, (int64_t)g->groups.size()})
     put(s, v);
@@ -507,7 +539,7 @@ struct Planner {
     cuts.insert(root);
     for (Node* n : sub) {
       if (!c->opt_fusion && n->is_compute()) cuts.insert(n);
-      if (n->kind == Kind::DOT) {
+      if (n->kind == Kind::DOT && !small_dot(n)) {
         // operands of a contraction are materialised first; views (a transposed
         // matrix in particular) are folded into the contraction kernel instead
         for (Node* o : n->in) {
@@ -601,6 +633,10 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
   if (c->opt_map_rows > 0 && g->rank >= 2) g->VR = (int)std::min<int64_t>(c->opt_map_rows, 16);
   if (c->opt_map_chunks > 0) g->UC = (int)std::min<int64_t>(c->opt_map_chunks, 8);
   g->xcd_remap = shifted_rows;
+  // Narrow arrays (points, pixels: a few columns): the lanes that own the last, incomplete group
+  // of four columns are a large share of all lanes (all of them below four columns).  The kernel
+  // is specialised on columns mod 4 and gives those lanes straight-line code as well.
+  g->tail = (g->rank >= 2 && C < 64 && (C & 3) && g->UC == 1 && !g->stage_mask) ? (int)(C & 3) : 0;
 }
 
 }  // namespace
@@ -641,7 +677,7 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
   const Node* dot = nullptr;
   std::vector<const Node*> reds;
   for (const Node* n : owned) {
-    if (n->kind == Kind::DOT) { if (dot) { invalid->push_back({n, "second dot in one sub-graph"}); return GR_OK; } dot = n; }
+    if (n->kind == Kind::DOT && !small_dot(n)) { if (dot) { invalid->push_back({n, "second dot in one sub-graph"}); return GR_OK; } dot = n; }
     if (n->kind == Kind::REDUCE) reds.push_back(n);
   }
   if (dot && !reds.empty()) { invalid->push_back({dot, "dot mixed with a reduction"}); return GR_OK; }
@@ -661,7 +697,7 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     // ---- map-scan: the operand expression is the map, the scan runs along one axis --------
     g->kind = GroupKind::SCAN;
     b.g->kind = GroupKind::SCAN;
-    for (const Node* n : owned) if (n != r && (n->kind == Kind::REDUCE || n->kind == Kind::DOT || n->kind == Kind::SCAN))
+    for (const Node* n : owned) if (n != r && (n->kind == Kind::REDUCE || (n->kind == Kind::DOT && !small_dot(n)) || n->kind == Kind::SCAN))
       invalid->push_back({n, "reduction, scan or dot under a scan"});
     if (!invalid->empty()) return GR_OK;
     const Node* x = r->in[0];

@@ -71,6 +71,30 @@ LONG_DOT_CASES = [
     ("inner product of two windows of one array", (200000,), (200000,), lambda xp, A, v: xp.dot(A[5:], A[:-5])),
 ]
 
+# arrays with a few columns (points, pixels) and contractions over a few terms (written out inside the
+# point function): (name, {array name: shape}, program)
+NARROW_CASES = [
+    ("points minus centroid", dict(x=(5003, 3), c=(3,)), lambda xp, x, c: x - c),
+    ("points scaled per row", dict(x=(5003, 3), c=(5003, 1)), lambda xp, x, c: x * c + 1.0),
+    ("two columns", dict(x=(4099, 2), c=(2,)), lambda xp, x, c: xp.maximum(x, c) * 2.0),
+    ("one column", dict(x=(4099, 1), c=(1,)), lambda xp, x, c: x + c),
+    ("seven columns", dict(x=(3001, 7), c=(7,)), lambda xp, x, c: x * c - 1.0),
+    ("five columns, stencil along rows", dict(x=(3001, 5), c=(5,)), lambda xp, x, c: x[2:] - x[:-2] + c),
+    ("three columns, shifted columns", dict(x=(3001, 5), c=(3,)), lambda xp, x, c: x[:, 2:] + x[:, :-2] * c),
+    ("61 columns", dict(x=(1001, 61), c=(61,)), lambda xp, x, c: x / (abs(c) + 1.0)),
+    ("3-d, three channels last", dict(x=(37, 41, 3), c=(3,)), lambda xp, x, c: x * c + x),
+    ("rotate points", dict(x=(5003, 3), c=(3, 3)), lambda xp, x, c: xp.dot(x, c)),
+    ("rotate and shift", dict(x=(5003, 3), c=(3, 3), d=(3,)), lambda xp, x, c, d: xp.dot(x * 2.0, c) + d),
+    ("weights of three", dict(x=(5003, 3), c=(3,)), lambda xp, x, c: xp.tanh(xp.dot(x, c))),
+    ("transposed operand", dict(x=(3, 5003), c=(3,)), lambda xp, x, c: xp.dot(xp.transpose(x, (1, 0)), c) - 1.0),
+    ("eight terms, wide result", dict(x=(301, 8), c=(8, 1030)), lambda xp, x, c: xp.dot(x, c)),
+    ("one term (outer product)", dict(x=(301, 1), c=(1, 130)), lambda xp, x, c: xp.dot(x, c) + 1.0),
+    ("softmax of a small product", dict(x=(2003, 4), c=(4, 6)),
+     lambda xp, x, c: xp.exp(xp.dot(x, c) - xp.max(xp.dot(x, c), axis=1, keepdims=True)) / xp.sum(xp.exp(xp.dot(x, c) - xp.max(xp.dot(x, c), axis=1, keepdims=True)), axis=1, keepdims=True)),
+    ("small product feeding a large one", dict(x=(257, 3), c=(3, 12), d=(12, 40)), lambda xp, x, c, d: xp.dot(xp.dot(x, c), d[:, :33])),
+    ("scan of a small product", dict(x=(1003, 3), c=(3, 3)), lambda xp, x, c: xp.cumsum(xp.dot(x, c), 0)),
+]
+
 # (shape, axis): inclusive scans along the contiguous axis, along outer axes, over long lines
 SCAN_CASES = [((1000,), 0), ((37, 211), 1), ((37, 211), 0), ((4, 5, 6), 1), ((4, 5, 6), 0), ((4, 5, 6), -1), ((3, 100000), 1),
               ((1 << 21,), 0), ((5, 1), 1), ((1, 7), 0), ((1,), 0), ((600, 1030), 1), ((2, 5000), 0),

@@ -11,7 +11,7 @@ import re
 import numpy as np
 import pytest
 
-from cases import DOT_CASES, ELEMENTWISE_CASES, REDUCTION_CASES, ROWRED_PROGRAMS, SCAN_CASES
+from cases import DOT_CASES, ELEMENTWISE_CASES, NARROW_CASES, REDUCTION_CASES, ROWRED_PROGRAMS, SCAN_CASES
 from paper_1901_03771_amd import lazy as gr, workloads as wl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -791,3 +791,24 @@ def test_c_fast_paths_and_ctypes_route_of_the_binding_agree():
     assert outs[0]["alive_after_jacobi"] == 0
     assert outs[0]["errors"] == ["GR_ERR_UNSUPPORTED", "TypeError", "GR_ERR_UNSUPPORTED", "GR_ERR_UNSUPPORTED", "GR_ERR_SHAPE", "GR_ERR_DTYPE",
                                  "GR_ERR_DTYPE", "GR_ERR_UNSUPPORTED", "GR_ERR_AXIS", "GR_ERR_AXIS", "TypeError", "ValueError"]
+
+
+
+@pytest.mark.parametrize("case", NARROW_CASES, ids=[c[0] for c in NARROW_CASES])
+def test_narrow_arrays_and_small_contractions_plan_and_compile(ctx, case):
+    name, shapes, prog = case
+    out = prog(gr, **{k: ctx.spec(s_) for k, s_ in shapes.items()})
+    kinds = [k for k, _ in groups(out)]
+    # a contraction over at most eight terms is part of the point function: no contraction kernel
+    assert ("GEMV" in kinds or "GEMM" in kinds) == (name == "small product feeding a large one"), kinds
+    out.compile()
+
+
+def test_small_contractions_fuse_with_their_neighbours(ctx):
+    x, m, v = ctx.spec((1000, 3)), ctx.spec((3, 3)), ctx.spec((3,))
+    assert groups(gr.tanh((x * 2.0) @ m + v)) == [("MAP", ["mul", "dot", "add", "tanh"])]
+    assert [k for k, _ in groups(x @ v)] == ["MAP"]
+    assert [k for k, _ in groups(ctx.spec((100, 9)) @ ctx.spec((9,)))] == ["GEMV"]        # nine terms: a contraction kernel
+    src = (x - v).source(0)
+    assert "c0 + 3 == C" in src                                                           # narrow arrays: straight-line code for the last columns
+    assert "c0 + 3 == C" not in (ctx.spec((1000, 67)) - ctx.spec((67,))).source(0)        # wide ones keep the generic edge path
