@@ -193,6 +193,11 @@ void prelude(Em& e) {
          "typedef int i2 __attribute__((ext_vector_type(2)));\n"
          "typedef i2 i2u __attribute__((aligned(4)));\n"
          "struct Args { unsigned long long s[" << e.total_slots << "]; };\n"
+         // linear index -> coordinates: rem % d with rem /= d, in 32-bit arithmetic whenever both fit
+         // (a 64-bit division is a long instruction sequence, paid per row or per element)
+         "static __device__ __forceinline__ long long gr_peel(long long& rem, long long d) {\n"
+         "  if ((((unsigned long long)rem) | ((unsigned long long)d)) >> 32) { const long long i = rem % d; rem /= d; return i; }\n"
+         "  const unsigned r = (unsigned)rem, dd = (unsigned)d, q = r / dd;\n  rem = q;\n  return r - q * dd;\n}\n"
          "static __device__ __forceinline__ float gr_maxf(float a, float b) { return (a >= b || a != a) ? a : b; }\n"
          "static __device__ __forceinline__ float gr_minf(float a, float b) { return (a <= b || a != a) ? a : b; }\n"
          "static __device__ __forceinline__ float gr_xor(float v, int m) { return __shfl_xor(v, m, 64); }\n"
@@ -522,7 +527,10 @@ void gen_rowred(Em& e) {
   e.o << "  (void)row_ok;\n";
   if (cd >= 1) {
     e.o << "  long long rrem = row;\n";
-    for (int k = cd - 1; k >= 0; --k) e.o << "  const long long i" << k << " = rrem % " << e.dim(k) << "; rrem /= " << e.dim(k) << ";\n";
+    for (int k = cd - 1; k >= 0; --k) {
+      if (k == 0) e.o << "  const long long i0 = rrem;\n";  // what is left is below the outermost extent
+      else e.o << "  const long long i" << k << " = gr_peel(rrem, " << e.dim(k) << ");\n";
+    }
   }
   group_pointers(e, "  ");
   for (size_t gi = 0; gi < g.groups.size(); ++gi) {
@@ -693,7 +701,10 @@ void gen_reduce(Em& e) {
   }
   e.o << "  const long long chunk = (LEN + NSPLIT - 1) / NSPLIT, jbeg = split * chunk, jend = (jbeg + chunk < LEN) ? jbeg + chunk : LEN;\n";
   e.o << "  long long orem = o;\n";
-  for (int k = kr - 1; k >= 0; --k) e.o << "  const long long i" << k << " = orem % " << e.dim(k) << "; orem /= " << e.dim(k) << ";\n";
+  for (int k = kr - 1; k >= 0; --k) {
+    if (k == 0) e.o << "  const long long i0 = orem;\n";
+    else e.o << "  const long long i" << k << " = gr_peel(orem, " << e.dim(k) << ");\n";
+  }
   group_pointers(e, "  ");
   for (size_t gi = 0; gi < g.groups.size(); ++gi) {
     const AccessGroup& ag = g.groups[gi];
@@ -722,7 +733,7 @@ void gen_reduce(Em& e) {
       e.o << "    long long jrem = j;\n";
       for (int k = rank - 1; k >= kr; --k) {
         if (k == kr) e.o << "    const long long i" << k << " = jrem;\n";
-        else e.o << "    const long long i" << k << " = jrem % " << e.dim(k) << "; jrem /= " << e.dim(k) << ";\n";
+        else e.o << "    const long long i" << k << " = gr_peel(jrem, " << e.dim(k) << ");\n";
       }
     }
     for (size_t i = 0; i < g.prog.size(); ++i) {
@@ -765,7 +776,7 @@ void gen_reduce(Em& e) {
       e.o << "      long long jrem = j;\n";
       for (int k = rank - 1; k >= kr; --k) {
         if (k == kr) e.o << "      const long long i" << k << " = jrem;\n";
-        else e.o << "      const long long i" << k << " = jrem % " << e.dim(k) << "; jrem /= " << e.dim(k) << ";\n";
+        else e.o << "      const long long i" << k << " = gr_peel(jrem, " << e.dim(k) << ");\n";
       }
     } else e.o << "      const long long i" << kr << " = j;\n";
     for (size_t i = 0; i < g.prog.size(); ++i) {
@@ -803,7 +814,7 @@ void gen_reduce(Em& e) {
     e.o << "    long long jrem = j;\n";
     for (int k = rank - 1; k >= kr; --k) {
       if (k == kr) e.o << "    const long long i" << k << " = jrem;\n";
-      else e.o << "    const long long i" << k << " = jrem % " << e.dim(k) << "; jrem /= " << e.dim(k) << ";\n";
+      else e.o << "    const long long i" << k << " = gr_peel(jrem, " << e.dim(k) << ");\n";
     }
   }
   emit_scalar_program(e, g.prog, {ph.value},
@@ -908,7 +919,10 @@ void gen_scan(Em& e) {
     else e.o << "  const long long gt = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (gt >= LINES * NCHUNK) return;\n"
                 "  const long long line = gt % LINES, chunk = gt / LINES;\n  (void)chunk;\n";  // neighbouring threads: neighbouring lines
     e.o << "  long long lrem = line;\n";
-    for (int k = sd - 1; k >= 0; --k) e.o << "  const long long i" << k << " = lrem % " << e.dim(k) << "; lrem /= " << e.dim(k) << ";\n";
+    for (int k = sd - 1; k >= 0; --k) {
+      if (k == 0) e.o << "  const long long i0 = lrem;\n";
+      else e.o << "  const long long i" << k << " = gr_peel(lrem, " << e.dim(k) << ");\n";
+    }
     group_pointers(e, "  ");
     for (size_t gi = 0; gi < g.groups.size(); ++gi) {
       const AccessGroup& ag = g.groups[gi];

@@ -987,6 +987,9 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
         if (g->rank > kept_rank && ag.coef[g->rank - 1] == 1) red_unit = true;
       }
       g->red_mode = (kept_unit && !red_unit) ? 0 : ((red_unit && !kept_unit) ? 1 : (g->red_out >= 4096 ? 0 : 1));
+      // a handful of outputs (column sums of an array of points): a thread per output would leave
+      // most lanes idle, so the lanes go along the reduced range even though it is strided
+      if (g->red_mode == 0 && g->red_out < 64 && g->red_len >= 4096) g->red_mode = 1;
       // split the reduced range so that about 2048 workgroups run (two-stage reduction, Section 3.2)
       // mode 0 with four consecutive outputs per thread: the innermost kept dimension is contiguous
       // (or absent) in every array read, holds a multiple of four, and all values are 32 bits wide
