@@ -513,7 +513,14 @@ void gen_rowred(Em& e) {
   e.o << "  const long long C = " << e.dim(cd) << ";\n  long long ROWS = 1;\n";
   for (int k = 0; k < cd; ++k) e.o << "  ROWS *= " << e.dim(k) << ";\n";
   e.o << "  const int lane = threadIdx.x % " << RT << ";\n";
-  if (RT <= 64) {
+  // several rows per lane group (short rows, one value per row): the per-row code below is written
+  // once into `body` and placed in two loops, see the end of this function
+  const int RPT = (g.row_iters > 1 && RT <= 64 && g.out_per_row) ? g.row_iters : 1;
+  // exact: the row is exactly as wide as the lanes' positions, no column guards anywhere
+  auto emit_body = [&](bool exact) {
+  if (RPT > 1) {
+    e.o << "      const long long row = ((long long)blockIdx.x * " << RPT << " + rr) * " << RB << " + threadIdx.x / " << RT << ";\n      const bool row_ok = true;\n";
+  } else if (RT <= 64) {
     // no workgroup barrier in this variant: lanes of rows past the end simply leave
     e.o << "  const long long row = (long long)blockIdx.x * " << RB << " + threadIdx.x / " << RT << ";\n";
     e.o << "  if (row >= ROWS) return;\n  const bool row_ok = true;\n";
@@ -539,6 +546,7 @@ void gen_rowred(Em& e) {
     for (int k = 0; k < cd; ++k) if (!ag.structural_zero[k]) e.o << " + i" << k << " * " << e.coef((int)gi, k);
     e.o << ";\n";
   }
+  if (RPT > 1) e.o << "//@@SPLIT\n";  // up to here: from the row number to the row's pointers
   // kept per-element values live in registers across stages
   for (size_t i = 0; i < g.prog.size(); ++i)
     if (keep[i] && !g.prog[i].uniform) e.o << "  " << cty(g.prog[i].dtype) << " k" << i << "[" << NP << "][4];\n";
@@ -574,8 +582,6 @@ void gen_rowred(Em& e) {
     }
   };
 
-  const bool exact = false;  // the last position is always emitted in guarded form
-  (void)exact;
   for (int s = 0; s < nstage; ++s) {
     const bool final_stage = s == nph;
     if (final_stage && g.results.empty()) break;
@@ -590,7 +596,8 @@ void gen_rowred(Em& e) {
       e.o << ";\n";
     }
     if (final_stage && g.out_per_row) {
-      e.o << "  if (lane == 0 && row_ok) ((GM " << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << ")[row] = " << name(g.results[0], false) << ";\n";
+      if (RPT > 1) e.o << "  GR_ROW_RESULT(" << name(g.results[0], false) << ");\n";
+      else e.o << "  if (lane == 0 && row_ok) ((GM " << cty(g.out_dtype) << "*)" << e.slot(e.L.out) << ")[row] = " << name(g.results[0], false) << ";\n";
       break;
     }
     const Phase* ph = final_stage ? nullptr : &g.phases[s];
@@ -608,8 +615,10 @@ void gen_rowred(Em& e) {
     // two bodies: unguarded positions 0..NP-2, guarded last position
     for (int pass = 0; pass < 2; ++pass) {
       const bool guarded = pass == 1;
-      if (!guarded && NP == 1) continue;
-      if (!guarded) e.o << "#pragma unroll\n  for (int p = 0; p < " << NP - 1 << "; ++p) {\n";
+      if (exact && guarded) continue;
+      const int np_unguarded = exact ? NP : NP - 1;
+      if (!guarded && np_unguarded == 0) continue;
+      if (!guarded) e.o << "#pragma unroll\n  for (int p = 0; p < " << np_unguarded << "; ++p) {\n";
       else e.o << "  { const int p = " << NP - 1 << ";\n";
       e.o << "    const long long c = (long long)p * " << RT * 4 << " + lane * 4;\n";
       // loads of this stage
@@ -671,6 +680,43 @@ void gen_rowred(Em& e) {
       }
       e.o << "  red" << s << " = acc" << s << ";\n";
     }
+  }
+  };  // emit_body
+  if (RPT == 1) emit_body(false);
+  else {
+    // the per-row code as text: without column guards for the workgroups whose rows all exist when
+    // the rows are exactly as wide as the lanes' positions, with guards for everything else
+    std::string body_exact, body_guarded;
+    for (int v = 0; v < 2; ++v) {
+      std::ostringstream tmp;
+      e.o.swap(tmp);
+      emit_body(v == 0);
+      e.o.swap(tmp);
+      (v == 0 ? body_exact : body_guarded) = tmp.str();
+    }
+    const std::string T = cty(g.out_dtype);
+    const std::string out = "((GM " + T + "*)" + e.slot(e.L.out) + ")";
+    const std::string mark = "//@@SPLIT\n";
+    const std::string setup = body_exact.substr(0, body_exact.find(mark)), stages = body_exact.substr(body_exact.find(mark) + mark.size());
+    body_guarded.erase(body_guarded.find(mark), mark.size());
+    e.o << "  if (((long long)blockIdx.x * " << RPT << " + " << RPT << ") * " << RB << " <= ROWS && C == " << RT * 4 * NP << ") {\n"
+           "    // all rows of the workgroup exist and are exactly as wide as the lanes' positions: no guards;\n"
+           "    // the rows' pointers first (index arithmetic with branches), then straight-line code in which\n"
+           "    // the loads of the " << RPT << " rows overlap; the results are stored at the end\n"
+           "    " << T << " outv[" << RPT << "];\n";
+    for (size_t gi = 0; gi < g.groups.size(); ++gi) e.o << "    const GM " << cty(g.groups[gi].dtype) << "* P" << gi << "[" << RPT << "];\n";
+    e.o << "#pragma unroll\n    for (int rr = 0; rr < " << RPT << "; ++rr) {\n" << setup;
+    for (size_t gi = 0; gi < g.groups.size(); ++gi) e.o << "      P" << gi << "[rr] = p" << gi << ";\n";
+    e.o << "    }\n#define GR_ROW_RESULT(v) outv[rr] = (v)\n#pragma unroll\n    for (int rr = 0; rr < " << RPT << "; ++rr) {\n      const bool row_ok = true;\n      (void)row_ok;\n";
+    for (size_t gi = 0; gi < g.groups.size(); ++gi) e.o << "      const GM " << cty(g.groups[gi].dtype) << "* const p" << gi << " = P" << gi << "[rr];\n";
+    e.o << stages << "    }\n#undef GR_ROW_RESULT\n"
+           "    if (lane == 0) {\n";
+    for (int rr = 0; rr < RPT; ++rr)
+      e.o << "      " << out << "[((long long)blockIdx.x * " << RPT << " + " << rr << ") * " << RB << " + threadIdx.x / " << RT << "] = outv[" << rr << "];\n";
+    e.o << "    }\n  } else {\n"
+           "#define GR_ROW_RESULT(v) do { if (lane == 0) " << out << "[row] = (v); } while (0)\n"
+           "    for (int rr = 0; rr < " << RPT << "; ++rr) {\n      if (((long long)blockIdx.x * " << RPT << " + rr) * " << RB << " + threadIdx.x / " << RT << " >= ROWS) break;\n"
+        << body_guarded << "    }\n#undef GR_ROW_RESULT\n  }\n";
   }
   e.o << "}\n";
 }

@@ -174,6 +174,7 @@ struct GroupPlan {
   int BX = 64, BY = 4, VR = 1, UC = 1;  // MAP
   int NP = 1;                            // ROWRED: vec4 positions per lane
   int row_threads = 64;                  // ROWRED: lanes cooperating on one row (64 or 256)
+  int row_iters = 1;                     // ROWRED: rows a lane group takes in one launch (short rows, one value per row)
   bool xcd_remap = false;
   int stage_mask = 0;                    // MAP: access groups (bit per group) read through a transposing LDS tile
   int tail = 0;                          // MAP: columns mod 4 of a narrow array (1..3): its last lanes get straight-line code too

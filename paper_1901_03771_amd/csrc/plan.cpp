@@ -472,7 +472,7 @@ void make_signature(GroupPlan* g) {
   std::string s;
   s.reserve(256 + 32 * (g->prog.size() + g->prog1.size()));
   for (int64_t v : {(int64_t)g->kind, (int64_t)g->rank, (int64_t)g->out_dtype, (int64_t)g->out_per_row, (int64_t)g->BX, (int64_t)g->BY,
-                    (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask + (((int64_t)g->tail) << 40), (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
+                    (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads + 1024 * (int64_t)g->row_iters, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask + (((int64_t)g->tail) << 40), (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
                     (int64_t)g->red_kept_rank, (int64_t)g->gemv_mode, (int64_t)g->LPR, (int64_t)g->KV, (int64_t)g->mat_group,
                     (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode + 16 * (int64_t)g->scan_vec, (int64_t)g->out_unit, (int64_t)g->groups.size()})
     put(s, v);
@@ -1067,6 +1067,13 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       if (c->opt_rowred_threads == 16 || c->opt_rowred_threads == 64 || c->opt_rowred_threads == 128 || c->opt_rowred_threads == 256)
         if (C <= c->opt_rowred_threads * 64) g->row_threads = (int)c->opt_rowred_threads;  // at most 16 positions per lane
       g->NP = (int)std::max<int64_t>(1, (C + (int64_t)g->row_threads * 4 - 1) / ((int64_t)g->row_threads * 4));
+      // Short rows reduced to one value each: a wave that owns only 8 to 64 rows lives about as long as
+      // its loads take, and the waves a SIMD can hold then bound the rate.  Each lane group takes four
+      // rows, the loads of all four in flight together, the four results stored at the end.
+      int64_t rows = 1;
+      for (int k = 0; k + 1 < g->rank; ++k) rows *= g->dims[k];
+      g->row_iters = (g->out_per_row && g->row_threads <= 8 && rows >= (int64_t)1 << 18 && c->opt_rowred_rows != 1) ? 4 : 1;
+      if (c->opt_rowred_rows > 1 && g->out_per_row && g->row_threads <= 64) g->row_iters = (int)std::min<int64_t>(c->opt_rowred_rows, 8);
     }
   } else {
     // ---- map ----------------------------------------------------------------
@@ -1300,7 +1307,7 @@ std::string describe_plan(const Plan& plan) {
       for (const Node* n : g.pair->members) { if (n->is_view()) continue; s << (f2 ? "" : ",") << n->id << ':' << node_label(n); f2 = false; }
       s << "]]";
     }
-    if (g.kind == GroupKind::ROWRED) s << " phases=" << g.phases.size() << " row_threads=" << g.row_threads << " NP=" << g.NP;
+    if (g.kind == GroupKind::ROWRED) s << " phases=" << g.phases.size() << " row_threads=" << g.row_threads << " NP=" << g.NP << (g.row_iters > 1 ? " rows_per_group=" + std::to_string(g.row_iters) : std::string());
     if (g.kind == GroupKind::SCAN) s << " mode=" << (g.scan_mode ? "thread-per-line" : "lanes-along-axis") << " lines=" << g.red_out << " length=" << g.red_len << " chunks=" << g.scan_nchunk;
     if (g.kind == GroupKind::MAP) s << " tile=" << g.BY * g.VR << "x" << g.BX * 4 * g.UC << " patch=" << g.VR << "x" << g.UC * 4;
     s << '\n';

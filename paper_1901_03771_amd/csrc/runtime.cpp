@@ -368,7 +368,7 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       int64_t rows = 1;
       for (int k2 = 0; k2 + 1 < g.rank; ++k2) rows *= g.dims[k2];
       if (rows == 0) return GR_OK;
-      int rb = 256 / g.row_threads;
+      int rb = 256 / g.row_threads * g.row_iters;
       return launch(c, k->fn, k->name, (rows + rb - 1) / rb, s);
     }
     case GroupKind::REDUCE: {

@@ -914,6 +914,40 @@ def test_narrow_arrays_and_small_contractions(env, env_interp, case):
             assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), name     # exactly rounded ops only
 
 
+@pytest.mark.parametrize("rows_opt", [0, 4, 8])
+def test_short_rows_reduced_to_one_value_take_several_rows_per_lane_group(env, rows_opt):
+    # rows of at most 32 elements that reduce to one value each: a lane group takes four (or the given
+    # number of) rows per launch, with unguarded code where the row width is exactly the lanes' positions
+    # (4, 8, 16, 32) and every row of the workgroup exists, guarded code otherwise
+    gr, ctx, torch = env
+    c2 = gr.Context()
+    c2.set_option("interp", 0)
+    c2.set_option("rowred_rows", rows_opt)
+    e2 = (gr, c2, torch)
+    big = 1 << 18 if rows_opt == 0 else 3000          # the default takes several rows from 2^18 rows on
+    for shape, prog, exact in [
+        ((big + 77, 16), lambda xp, x: xp.sum(x * x, axis=1), False),
+        ((big + 64, 8), lambda xp, x: xp.max(x, axis=1) * 2.0, True),
+        ((big + 5, 13), lambda xp, x: xp.min(abs(x), axis=1), True),
+        ((big + 1, 4), lambda xp, x: xp.sqrt(xp.sum(x * x, axis=1)), False),
+        ((big // 8 + 3, 8, 32), lambda xp, x: xp.sum(x, axis=2) + 1.0, False),
+        ((big + 9, 3), lambda xp, x: xp.sum(x, axis=1, keepdims=True), False),
+    ]:
+        x = _rand(shape, 811)
+        got, ref = run_both(e2, lambda xp, x: prog(xp, x), dict(x=x))
+        assert got.shape == ref.shape
+        if exact:
+            assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), shape
+        else:
+            assert_reduction(got, ref, what=f"short rows {shape}")
+    # pairwise squared distances: a broadcast difference reduced over a short innermost axis
+    pts, cen = _rand((big // 16 + 11, 1, 16), 812), _rand((1, 32, 16), 813)
+    got, ref = run_both(e2, lambda xp, p, c: xp.sum((p - c) * (p - c), axis=2), dict(p=pts, c=cen))
+    assert got.shape == (big // 16 + 11, 32)
+    assert_reduction(got, ref, what="pairwise squared distances")
+    c2.close()
+
+
 # ---- the byte-code interpreter that stands in while a kernel is being compiled ----------------
 
 @pytest.mark.parametrize("name", sorted(ELEMENTWISE_CASES))
