@@ -142,7 +142,7 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     (transposed views) through 64 x 64 tiles transposed in LDS;
  *                     0 = strided loads
  *   "rowred_rows"     rows a lane group of a row-resident reduction takes per
- *                     launch when rows are short (at most 32 elements) and reduce
+ *                     launch when rows are short (at most 64 elements) and reduce
  *                     to one value each: 0 (default) = 4 for 2^18 rows or more,
  *                     1 = always one, 2..8 = that many
  *   "scan_min_threads", "scan_threads"

@@ -1067,12 +1067,12 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       if (c->opt_rowred_threads == 16 || c->opt_rowred_threads == 64 || c->opt_rowred_threads == 128 || c->opt_rowred_threads == 256)
         if (C <= c->opt_rowred_threads * 64) g->row_threads = (int)c->opt_rowred_threads;  // at most 16 positions per lane
       g->NP = (int)std::max<int64_t>(1, (C + (int64_t)g->row_threads * 4 - 1) / ((int64_t)g->row_threads * 4));
-      // Short rows reduced to one value each: a wave that owns only 8 to 64 rows lives about as long as
+      // Short rows (up to 64 elements) reduced to one value each: a wave that owns only 4 to 64 rows lives about as long as
       // its loads take, and the waves a SIMD can hold then bound the rate.  Each lane group takes four
       // rows, the loads of all four in flight together, the four results stored at the end.
       int64_t rows = 1;
       for (int k = 0; k + 1 < g->rank; ++k) rows *= g->dims[k];
-      g->row_iters = (g->out_per_row && g->row_threads <= 8 && rows >= (int64_t)1 << 18 && c->opt_rowred_rows != 1) ? 4 : 1;
+      g->row_iters = (g->out_per_row && C <= 64 && rows >= (int64_t)1 << 18 && c->opt_rowred_rows != 1) ? 4 : 1;  // (measured: 2 and 8 rows are no better, 256-element rows lose)
       if (c->opt_rowred_rows > 1 && g->out_per_row && g->row_threads <= 64) g->row_iters = (int)std::min<int64_t>(c->opt_rowred_rows, 8);
     }
   } else {

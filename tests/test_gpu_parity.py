@@ -932,6 +932,8 @@ def test_short_rows_reduced_to_one_value_take_several_rows_per_lane_group(env, r
         ((big + 1, 4), lambda xp, x: xp.sqrt(xp.sum(x * x, axis=1)), False),
         ((big // 8 + 3, 8, 32), lambda xp, x: xp.sum(x, axis=2) + 1.0, False),
         ((big + 9, 3), lambda xp, x: xp.sum(x, axis=1, keepdims=True), False),
+        ((big // 2 + 3, 64), lambda xp, x: xp.sum(x, axis=1) * 0.5, False),
+        ((big // 2 + 3, 50), lambda xp, x: xp.max(x + 1.0, axis=1), True),
     ]:
         x = _rand(shape, 811)
         got, ref = run_both(e2, lambda xp, x: prog(xp, x), dict(x=x))
