@@ -764,7 +764,8 @@ static bool reads_range(const Node* n, uintptr_t lo, uintptr_t hi, std::set<cons
 // Gives a node whose data lives inside another array's storage (the result of a direct slice
 // assignment) a buffer of its own.
 static gr_status unshare(gr_ctx* ctx, gr_array id) {
-  Node* n = lookup(ctx, id);
+  auto it = ctx->nodes.find(id);  // (not lookup(): the node may be held by views only, without a handle)
+  Node* n = it == ctx->nodes.end() ? nullptr : it->second;
   if (!n || !n->cow_alias) return GR_OK;
   size_t bytes = (size_t)n->count() * itemsize(n->dtype);
   void* buf = ctx_alloc(ctx, bytes);
@@ -853,11 +854,13 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
   std::vector<gr_array> pending, aliases;
   for (auto& kv : ctx->nodes) {
     Node* n = kv.second;
-    if (n == v || n->handle_refs <= 0 || n->kind == Kind::SCALAR) continue;
+    if (n == v || n->kind == Kind::SCALAR) continue;
     if (n->materialized) {
+      // (also one that only views refer to: the destination itself may be a view of it)
       if (n->cow_alias) { uintptr_t a, b; extent_of(n, &a, &b); if (a < hi && lo < b) aliases.push_back(n->id); }
       continue;
     }
+    if (n->handle_refs <= 0) continue;
     if (n->is_view()) { const Node* vb; int64_t o, st[MAXD]; if (resolve_view_rt(n, &vb, &o, st)) continue; }  // aliases see the new contents
     std::set<const Node*> seen;
     if (reads_range(n, lo, hi, &seen)) pending.push_back(n->id);
@@ -877,7 +880,9 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
   //    unevaluated, its last sub-graph is a map, and that sub-graph reads the destination's
   //    storage at exactly the positions it writes (or not at all).
   bool direct = false;
+  // (the destination's own base may just have moved to a buffer of its own)
   resolve_view_rt(d, &base, &spec.base, spec.strides);
+  view_extent(base, d->ndim, d->shape, spec.base, spec.strides, &lo, &hi);
   const Node* vb = nullptr; int64_t vo, vst[MAXD];
   const bool value_has_data = resolve_view_rt(v, &vb, &vo, vst);
   if (!value_has_data) {

@@ -34,7 +34,7 @@ def _broadcast(a, b):
 
 
 def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool = False, empty: bool = False,
-                reshape: bool = False):
+                reshape: bool = False, assign_values: bool = False):
     """Returns (dtype, leaf_shapes, steps, result_index); steps are tuples whose first entry names the op.
     assign=True adds slice assignments into leaves and views of leaves (values: an array of the same
     shape, an expression of the destination itself, or a shifted and possibly overlapping view)."""
@@ -55,6 +55,7 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool 
     shapes = list(leaf_shapes)      # pool shapes
     final = [False] * len(shapes)   # i64 results cannot feed further ops
     storage = [True] * len(shapes)  # leaves and views of leaves: valid destinations of an assignment
+    computed = [False] * len(shapes)  # results of operations (not leaves, not views)
     steps = []
 
     def pick(pred=lambda i: True):
@@ -160,6 +161,7 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool 
             if op == "sum":
                 final.append(True)
                 storage.append(False)
+                computed.append(True)
                 continue
         elif kind == "scan":
             op = r.choice(["cummax", "cummin"] + (["cumsum"] if dtype == "i32" else []))
@@ -168,17 +170,25 @@ def make_recipe(seed: int, max_steps: int = 10, assign: bool = False, big: bool 
             if op == "cumsum":
                 final.append(True)
                 storage.append(False)
+                computed.append(True)
                 continue
         else:
             steps.append(("materialize", a))
+            # assign_values: an evaluated result is an array like any other and may be assigned into
+            # (also one that an earlier assignment wrote straight into another array's storage)
+            if assign_values and computed[a] and len(sa) >= 1 and all(d >= 1 for d in sa):
+                storage[a] = True
             continue
         final.append(False)
         while len(storage) < len(shapes):
             storage.append(kind in ("slice", "transpose") and storage[a])
+        while len(computed) < len(shapes):
+            computed.append(kind not in ("slice", "transpose"))
     if not steps or steps[-1][0] == "materialize":
         steps.append(("unary", "neg", 0))
         shapes.append(shapes[0])
         final.append(False)
+        computed.append(True)
     return dtype, leaf_shapes, steps, len(shapes) - 1
 
 

@@ -495,6 +495,37 @@ def test_assigned_value_outlives_the_array_it_was_written_into(env):
     assert np.array_equal(w.numpy(), b0[:100] * f32(3))
 
 
+@pytest.mark.parametrize("owned", [False, True])
+def test_writing_into_a_value_that_lives_in_another_arrays_storage(env, owned):
+    # the value of a direct slice assignment lives inside the destination's buffer until either is written
+    # again; writing into the value itself (through its handle, or through views after its handle is gone)
+    # first gives it a buffer of its own, and a shifted read of itself then needs the temporary
+    gr, ctx, torch = env
+    d0, x0 = _rand((40,), 221), _rand((20,), 222)
+    for through_views in (False, True):
+        D = ctx.array(torch.from_numpy(d0.copy()).cuda())
+        if owned:
+            D = D.copy()
+        X = ctx.array(torch.from_numpy(x0).cuda())
+        val = X * 2.0
+        D[10:30] = val                                   # written straight into D: val lives in D[10:30]
+        ref_val = x0 * f32(2)
+        ref_d = d0.copy()
+        ref_d[10:30] = ref_val
+        new_val = ref_val.copy()
+        new_val[1:] = ref_val[:-1] + f32(1)
+        if through_views:
+            w, u, whole = val[1:], val[:-1], val[:]
+            del val
+            w[:] = u + 1.0
+            got_val = whole.numpy()
+        else:
+            val[1:] = val[:-1] + 1.0
+            got_val = val.numpy()
+        assert np.array_equal(got_val, new_val), ("through views" if through_views else "through the handle")
+        assert np.array_equal(D.numpy(), ref_d), "the array the value was first written into keeps its contents"
+
+
 def test_assign_keeps_recorded_values(env):
     gr, ctx, torch = env
     a0, b0 = _rand((300,), 73), _rand((300,), 74)
@@ -948,6 +979,23 @@ def test_short_rows_reduced_to_one_value_take_several_rows_per_lane_group(env, r
     assert got.shape == (big // 16 + 11, 32)
     assert_reduction(got, ref, what="pairwise squared distances")
     c2.close()
+
+
+@pytest.mark.parametrize("owned", [False, True])
+def test_random_programs_assigning_into_evaluated_values(env, owned):
+    # assignments into results of earlier operations, among them values that an earlier direct assignment
+    # left inside another array's storage: every array of the program is compared
+    import fuzz
+    gr, ctx, torch = env
+    for seed in range(800000, 800030):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed, max_steps=14, assign=True, assign_values=True, reshape=(seed % 3 == 0))
+        leaves = fuzz.make_leaves(seed, dtype, shapes)
+        ref = fuzz.apply(ora, steps, [ora.array(x.copy()) for x in leaves])
+        keep = [torch.from_numpy(x.copy()).cuda() for x in leaves]
+        dev = [ctx.array(t).copy() if owned else ctx.array(t) for t in keep]
+        got = fuzz.apply(gr, steps, dev)
+        for i, (g_, r_) in enumerate(zip(got, ref)):
+            assert fuzz.same_bits(g_.numpy(), r_.numpy()), f"seed {seed} value {i}: {dtype} {shapes} {steps}"
 
 
 # ---- the byte-code interpreter that stands in while a kernel is being compiled ----------------

@@ -333,6 +333,15 @@ def test_dry_run_exercises_materialise_and_assign_without_a_device(ctx):
             assert a.is_materialized and a.shape is not None
         del pool, leaves, a
         assert ctx.stats()["nodes_alive"] == base, seed      # nothing leaks
+    # assignments into evaluated results as well (values living in another array's storage among them)
+    for seed in range(800000, 800150):
+        dtype, shapes, steps, res = fuzz.make_recipe(seed, max_steps=14, assign=True, assign_values=True, reshape=(seed % 3 == 0))
+        leaves = [ctx.spec(s_, gr.GR_I32 if dtype == "i32" else gr.GR_F32) for s_ in shapes]
+        pool = fuzz.apply(gr, steps, leaves)
+        for a in pool:
+            a.materialize()
+        del pool, leaves, a
+        assert ctx.stats()["nodes_alive"] == base, seed
     st = ctx.stats()
     assert st["kernel_launches"] > 500 and st["compile_ms"] == 0.0
     # one kernel per op: intermediate results without a handle are freed while the plan finishes

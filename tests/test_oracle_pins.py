@@ -750,3 +750,22 @@ def test_random_programs_with_slice_assignments_match_numpy():
             for i, (g, r) in enumerate(zip(got, ref)):
                 assert fuzz.same_bits(g.numpy(), r, zero_signs=False), (seed, i, steps)
     assert assigns > 200
+
+
+def test_random_programs_assigning_into_evaluated_values_match_numpy():
+    # writes into arrays that are results of earlier operations (evaluated first), among them values that an
+    # earlier assignment stored into another array: each is an array of its own, as in NumPy
+    import warnings
+    import fuzz
+    into_values = 0
+    with warnings.catch_warnings():
+        warnings.simplefilter("ignore")
+        for seed in range(800000, 800400):
+            dtype, shapes, steps, res = fuzz.make_recipe(seed, max_steps=14, assign=True, assign_values=True, reshape=(seed % 3 == 0))
+            into_values += sum(1 for st in steps if st[0] == "assign" and st[1] >= len(shapes))
+            leaves = fuzz.make_leaves(seed, dtype, shapes)
+            ref = fuzz.apply(fuzz.NumpyModule, steps, [x.copy() for x in leaves])
+            got = fuzz.apply(ora, steps, [ora.array(x.copy()) for x in leaves])
+            for i, (g, r) in enumerate(zip(got, ref)):
+                assert fuzz.same_bits(g.numpy(), r, zero_signs=False), (seed, i, steps)
+    assert into_values > 50
