@@ -89,6 +89,7 @@ NARROW_CASES = [
     ("transposed operand", dict(x=(3, 5003), c=(3,)), lambda xp, x, c: xp.dot(xp.transpose(x, (1, 0)), c) - 1.0),
     ("eight terms, wide result", dict(x=(301, 8), c=(8, 1030)), lambda xp, x, c: xp.dot(x, c)),
     ("one term (outer product)", dict(x=(301, 1), c=(1, 130)), lambda xp, x, c: xp.dot(x, c) + 1.0),
+    ("no term (empty contraction)", dict(x=(5, 0), c=(0, 7)), lambda xp, x, c: xp.dot(x, c) + 1.0),
     ("softmax of a small product", dict(x=(2003, 4), c=(4, 6)),
      lambda xp, x, c: xp.exp(xp.dot(x, c) - xp.max(xp.dot(x, c), axis=1, keepdims=True)) / xp.sum(xp.exp(xp.dot(x, c) - xp.max(xp.dot(x, c), axis=1, keepdims=True)), axis=1, keepdims=True)),
     ("small product feeding a large one", dict(x=(257, 3), c=(3, 12), d=(12, 40)), lambda xp, x, c, d: xp.dot(xp.dot(x, c), d[:, :33])),
