@@ -145,6 +145,9 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     launch when rows are short (at most 64 elements) and reduce
  *                     to one value each: 0 (default) = 4 for 2^18 rows or more,
  *                     1 = always one, 2..8 = that many
+ *   "gemm_bn"         width of the output tile of the matrix-product kernel: 32 or
+ *                     128; 0 (default) = 32 for results of at most 96 columns and
+ *                     where the last 128-wide tile would be more than half empty
  *   "scan_min_threads", "scan_threads"
  *                     a scan along a non-contiguous axis gives each thread one
  *                     line (four neighbouring lines with dwordx4 loads); with

@@ -1482,10 +1482,12 @@ void gen_gemm(Em& e) {
   // --- epilogue on the accumulators: element q of a 32x32 block sits at row 8*(q/4) + 4*(lane/32) + q%4, column lane%32
   e.o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
   e.o << "  if (NSPLIT > 1) {\n    GM float* const ws = (GM float*)" << e.slot(e.L.ocoef) << " + split * M * N;\n"
-         "    for (int i = 0; i < " << IB << "; ++i) for (int j = 0; j < " << JB << "; ++j)\n#pragma unroll\n      for (int q = 0; q < 16; ++q) {\n"
+         "#pragma unroll\n    for (int i = 0; i < " << IB << "; ++i)\n#pragma unroll\n    for (int j = 0; j < " << JB << "; ++j)\n#pragma unroll\n      for (int q = 0; q < 16; ++q) {\n"
          "        const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4), col = bn0 + wn + 32 * j + l32;\n"
          "        if (row < M && col < N) ws[row * N + col] = acc[i][j][q];\n      }\n    return;\n  }\n";
-  e.o << "  for (int i = 0; i < " << IB << "; ++i) for (int j = 0; j < " << JB << "; ++j)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
+  // (all three loops unrolled: an index of acc that is not a constant would move the accumulators
+  // to scratch memory, which a large epilogue such as tanh otherwise provokes)
+  e.o << "#pragma unroll\n  for (int i = 0; i < " << IB << "; ++i)\n#pragma unroll\n  for (int j = 0; j < " << JB << "; ++j)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
          "      const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4), col = bn0 + wn + 32 * j + l32;\n"
          "      if (row < M && col < N) {\n        const float cacc = acc[i][j][q];\n";
   auto epi_load = [&](const Instr& in, int) {

@@ -32,6 +32,7 @@ struct gr_ctx {
   int64_t opt_map_bx = 0;
   int64_t opt_rowred_threads = 0;
   int64_t opt_rowred_rows = 0;
+  int64_t opt_gemm_bn = 0;
   int64_t opt_gemv_slabs = 0, opt_gemv_unroll = 0;
   int64_t opt_gemv_pair = 1;
   int64_t opt_async_compile = 1;

@@ -542,7 +542,9 @@ def test_assign_keeps_recorded_values(env):
     assert np.all(ta.cpu().numpy() == 0)
 
 
-GEMM_CASES = [(1, 1, 1), (130, 17, 129), (300, 200, 150), (128, 16, 128), (257, 1000, 64), (1024, 512, 768), (5, 4099, 3)]
+GEMM_CASES = [(1, 1, 1), (130, 17, 129), (300, 200, 150), (128, 16, 128), (257, 1000, 64), (1024, 512, 768), (5, 4099, 3),
+              # result widths around the choice between 32- and 128-column tiles
+              (300, 64, 96), (300, 64, 97), (200, 40, 160), (130, 33, 520), (64, 300, 192)]
 
 
 @pytest.mark.parametrize("M,K,N", GEMM_CASES)
@@ -555,6 +557,7 @@ def test_matrix_product(env, M, K, N):
         (lambda xp, A, B, At, Bt, bias: At.T @ B, "left operand transposed view"),
         (lambda xp, A, B, At, Bt, bias: A @ Bt.T, "right operand transposed view"),
         (lambda xp, A, B, At, Bt, bias: xp.maximum(A @ B + bias, 0) * 0.5, "bias + relu epilogue"),
+        (lambda xp, A, B, At, Bt, bias: xp.tanh(A @ B * 0.1 + bias) + xp.erf(bias), "large epilogue (tanh, erf)"),
     ]
     for prog, what in cases:
         got, ref = run_both(env, prog, dict(A=A, B=B, At=At, Bt=Bt, bias=bias))
