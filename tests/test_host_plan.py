@@ -593,6 +593,40 @@ def test_generated_code_has_no_contraction_or_packed_math(ctx):
     assert "fmaf" not in src and "__fdividef" not in src and "__expf" not in src
 
 
+def test_generated_kernels_keep_their_values_in_registers(ctx, tmp_path):
+    # Large point functions (tanh, erf, exp, log in an epilogue) must not push accumulators or patch values
+    # into scratch memory: the kernels are compiled to gfx950 assembly offline and searched for scratch
+    # accesses and a private segment.  (A matrix-product epilogue with tanh once did exactly that.)
+    import re
+    import shutil
+    import subprocess
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not found")
+
+    def heavy(x):
+        return gr.erf(gr.tanh(x) * 0.5) + gr.exp(-abs(x)) * gr.log(abs(x) + 1.0)
+
+    X, V, M2 = ctx.spec((4096, 1024)), ctx.spec((1024,)), ctx.spec((1024, 512))
+    progs = {
+        "gemm": heavy(X @ M2) + ctx.spec((512,)),
+        "gemm narrow": heavy(X @ ctx.spec((1024, 32))),
+        "gemv": heavy(X @ V),
+        "rowred": heavy(X - gr.max(X, axis=1, keepdims=True)) / gr.sum(heavy(X), axis=1, keepdims=True),
+        "map": heavy(wl.stencil(gr, X)),
+        "scan": gr.cumsum(heavy(X), 0),
+    }
+    for name, out in progs.items():
+        src = tmp_path / "k.hip"
+        src.write_text("#include <hip/hip_runtime.h>\n" + out.source(0))
+        asm = tmp_path / "k.s"
+        subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                        "-S", "--cuda-device-only", "-o", str(asm), str(src)], check=True, capture_output=True, timeout=600)
+        text = asm.read_text()
+        assert "scratch_" not in text, name
+        assert all(int(v) == 0 for v in re.findall(r"\.private_segment_fixed_size:\s+(\d+)", text)), name
+
+
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_random_api_arguments_are_answered_with_statuses(seed):
     """Arbitrary arguments (stale handles, absurd ranks, extents of 2^40, empty axes, misaligned pointers) end in
