@@ -663,7 +663,7 @@ static int add_core_group(GroupPlan* g, const Builder& like, const Node* leaf, c
   return (int)g->groups.size() - 1;
 }
 
-static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std::vector<Invalid>* invalid) {
+static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std::vector<Invalid>* invalid, bool force_generic = false) {
   NodeSet owned = pl.owned_by(r);
   g->root = r;
   g->out_dtype = r->dtype;
@@ -911,7 +911,7 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     normalize_deltas(g, ps, 1, 1);
   } else if (!reds.empty() || dot) {
     // Decide between row-resident and generic reduction.
-    bool generic = dot != nullptr;   // (a contraction planned as a reduction, see dot_as_reduce)
+    bool generic = dot != nullptr || force_generic;   // (a contraction planned as a reduction, see dot_as_reduce)
     if (r->kind == Kind::REDUCE) {
       const Node* x = r->in[0];
       bool last_only = x->ndim >= 1;
@@ -1071,6 +1071,26 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       if (c->opt_rowred_threads == 16 || c->opt_rowred_threads == 64 || c->opt_rowred_threads == 128 || c->opt_rowred_threads == 256)
         if (C <= c->opt_rowred_threads * 64) g->row_threads = (int)c->opt_rowred_threads;  // at most 16 positions per lane
       g->NP = (int)std::max<int64_t>(1, (C + (int64_t)g->row_threads * 4 - 1) / ((int64_t)g->row_threads * 4));
+      // Rows that run along a strided axis of every array read while another axis is the contiguous
+      // one (an array stored transposed): lanes along such a row would each touch another cache
+      // line.  The reductions are evaluated by the generic kernel instead, which gives a thread
+      // to each output and walks the lanes along the contiguous axis.
+      if (g->row_threads > 1) {
+        const int cd = g->rank - 1;
+        bool inner_unit = false, outer_unit = false;
+        for (const AccessGroup& ag : g->groups) {
+          if (!ag.structural_zero[cd] && ag.coef[cd] == 1) inner_unit = true;
+          for (int k = 0; k < cd; ++k) if (!ag.structural_zero[k] && ag.coef[k] == 1 && g->dims[k] > 1) outer_unit = true;
+        }
+        if (!inner_unit && outer_unit) {
+          if (reds.size() == 1 && reds[0] == r) {
+            *g = GroupPlan();
+            return build_group(c, pl, r, g, invalid, true);
+          }
+          for (const Node* n : reds) if (n != r) invalid->push_back({n, "reduction along a strided axis"});
+          if (!invalid->empty()) return GR_OK;
+        }
+      }
       // Short rows (up to 64 elements) reduced to one value each: a wave that owns only 4 to 64 rows lives about as long as
       // its loads take, and the waves a SIMD can hold then bound the rate.  Each lane group takes four
       // rows, the loads of all four in flight together, the four results stored at the end.

@@ -1001,6 +1001,27 @@ def test_random_programs_assigning_into_evaluated_values(env, owned):
             assert fuzz.same_bits(g_.numpy(), r_.numpy()), f"seed {seed} value {i}: {dtype} {shapes} {steps}"
 
 
+def test_reductions_along_the_strided_axis_of_an_array_stored_transposed(env):
+    # a leaf whose memory is the transpose of its shape (strides (1, rows)): reducing along the strided axis
+    # goes through the generic reduction kernel (a thread per output, lanes along the contiguous axis), alone,
+    # with pointwise producers, and with consumers that read the stored result
+    gr, ctx, torch = env
+    for rows, cols in [(300, 1000), (4099, 70), (64, 5000)]:
+        a = _rand((cols, rows), 931)                          # memory layout
+        t = torch.from_numpy(a).cuda()
+        x = ctx.array(t.t())                                  # shape (rows, cols), strides (1, rows)
+        assert x.shape == (rows, cols)
+        xo = ora.array(np.ascontiguousarray(a.T))
+        kinds = [ln.split()[1] for ln in gr.sum(x, axis=1).plan().strip().splitlines()]
+        assert kinds == ["REDUCE"], kinds
+        assert_reduction(gr.sum(x, axis=1).numpy(), ora.sum(xo, axis=1).numpy(), what="sum along the strided axis")
+        assert np.array_equal(gr.max(x * 2.0, axis=1, keepdims=True).numpy(), ora.max(xo * 2.0, axis=1, keepdims=True).numpy())
+        got = (gr.exp(x - gr.max(x, axis=1, keepdims=True)) / gr.sum(gr.exp(x - gr.max(x, axis=1, keepdims=True)), axis=1, keepdims=True)).numpy()
+        ref = (ora.exp(xo - ora.max(xo, axis=1, keepdims=True)) / ora.sum(ora.exp(xo - ora.max(xo, axis=1, keepdims=True)), axis=1, keepdims=True)).numpy()
+        assert_reduction(got, ref, what="softmax along the strided axis")
+        assert_reduction(gr.sum(x, axis=0).numpy(), ora.sum(xo, axis=0).numpy(), what="sum along the contiguous axis")
+
+
 # ---- the byte-code interpreter that stands in while a kernel is being compiled ----------------
 
 @pytest.mark.parametrize("name", sorted(ELEMENTWISE_CASES))
