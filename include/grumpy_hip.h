@@ -148,6 +148,10 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *   "gemm_bn"         width of the output tile of the matrix-product kernel: 32 or
  *                     128; 0 (default) = 32 for results of at most 96 columns and
  *                     where the last 128-wide tile would be more than half empty
+ *   "pool_limit"      bytes the default pool may hold before a request for a size
+ *                     it has no free block of makes it return its free blocks of
+ *                     other sizes to the device first; 0 (default) = no limit
+ *                     (the same happens whenever the device runs out of memory)
  *   "scan_min_threads", "scan_threads"
  *                     a scan along a non-contiguous axis gives each thread one
  *                     line (four neighbouring lines with dwordx4 loads); with
@@ -341,6 +345,7 @@ typedef struct {
   uint64_t interp_launches;   /* sub-graphs evaluated by the byte-code interpreter (option "interp") */
   uint64_t assign_swaps;      /* slice assignments done by writing a second buffer and swapping (option "assign_swap") */
   uint64_t plan_hits;         /* requests answered with a remembered plan (option "plan_cache") */
+  uint64_t pool_bytes;        /* device memory the default pool holds right now (in use or free for reuse) */
 } gr_stats_t;
 
 gr_status gr_stats(gr_ctx* ctx, gr_stats_t* out);

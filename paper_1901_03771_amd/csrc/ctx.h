@@ -33,6 +33,7 @@ struct gr_ctx {
   int64_t opt_rowred_threads = 0;
   int64_t opt_rowred_rows = 0;
   int64_t opt_gemm_bn = 0;
+  int64_t opt_pool_limit = 0;
   int64_t opt_gemv_slabs = 0, opt_gemv_unroll = 0;
   int64_t opt_gemv_pair = 1;
   int64_t opt_async_compile = 1;
@@ -52,7 +53,8 @@ struct gr_ctx {
   void (*free_fn)(void*, void*) = nullptr;
   void* alloc_user = nullptr;
   std::unordered_map<size_t, std::vector<void*>> pool_free;  // default pool: size -> free blocks
-  std::vector<void*> pool_all;
+  std::unordered_map<void*, size_t> pool_all;  // every block the pool got from hipMalloc -> its size
+  size_t pool_bytes = 0;                       // their sum
 
   // kernel cache: signature -> compiled kernel
   struct Kernel {

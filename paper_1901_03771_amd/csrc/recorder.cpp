@@ -220,6 +220,7 @@ gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   else if (k == "rowred_threads") ctx->opt_rowred_threads = value;
   else if (k == "rowred_rows") ctx->opt_rowred_rows = value;
   else if (k == "gemm_bn") ctx->opt_gemm_bn = value;
+  else if (k == "pool_limit") ctx->opt_pool_limit = value;
   else if (k == "gemv_slabs") ctx->opt_gemv_slabs = value;
   else if (k == "gemv_unroll") ctx->opt_gemv_unroll = value;
   else if (k == "gemv_pair") ctx->opt_gemv_pair = value;
@@ -631,6 +632,7 @@ gr_status gr_release(gr_ctx* ctx, gr_array a) {
 gr_status gr_stats(gr_ctx* ctx, gr_stats_t* out) {
   if (!ctx || !out) return GR_ERR_ARG;
   *out = ctx->stats;
+  out->pool_bytes = ctx->pool_bytes;
   return GR_OK;
 }
 

@@ -36,6 +36,22 @@ static std::string hip_err(hipError_t e) { return std::string(hipGetErrorName(e)
     if (e_ != hipSuccess) return fail((c), GR_ERR_HIP, std::string(#call) + " -> " + hip_err(e_)); \
   } while (0)
 
+// Returns every free block of the default pool to the device.  hipFree waits for the device, so
+// a block that a queued kernel still reads (freed in host order, reused in stream order) is safe.
+static void pool_trim(gr_ctx* c) {
+  for (auto& kv : c->pool_free) {
+    for (void* p : kv.second) {
+      auto it = c->pool_all.find(p);
+      if (it == c->pool_all.end()) continue;
+      c->pool_bytes -= it->second;
+      c->pool_all.erase(it);
+      (void)hipFree(p);
+    }
+    kv.second.clear();
+  }
+  c->pool_free.clear();
+}
+
 void* ctx_alloc(gr_ctx* c, size_t bytes) {
   if (bytes == 0) bytes = 256;
   c->stats.bytes_allocated += bytes;
@@ -53,9 +69,17 @@ void* ctx_alloc(gr_ctx* c, size_t bytes) {
     fl.pop_back();
     return p;
   }
+  // nothing of this size is free: before the pool grows past its limit (option "pool_limit"), and
+  // when the device has no memory left, the free blocks of other sizes go back to the device
+  if (c->opt_pool_limit > 0 && c->pool_bytes + rounded > (size_t)c->opt_pool_limit) pool_trim(c);
   void* p = nullptr;
-  if (hipMalloc(&p, rounded) != hipSuccess) return nullptr;
-  c->pool_all.push_back(p);
+  if (hipMalloc(&p, rounded) != hipSuccess) {
+    (void)hipGetLastError();
+    pool_trim(c);
+    if (hipMalloc(&p, rounded) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  }
+  c->pool_all.emplace(p, rounded);
+  c->pool_bytes += rounded;
   return p;
 }
 
@@ -654,7 +678,7 @@ gr_status gr_ctx_destroy(gr_ctx* ctx) {
   for (auto& kv : ctx->cache) if (kv.second.module) (void)hipModuleUnload(kv.second.module);
   for (auto& p : ctx->prof) { (void)hipEventDestroy(p.e0); (void)hipEventDestroy(p.e1); }
   for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
-  for (void* p : ctx->pool_all) (void)hipFree(p);
+  for (auto& kv : ctx->pool_all) (void)hipFree(kv.first);
   delete ctx;
   return GR_OK;
 }

@@ -56,7 +56,7 @@ class Stats(ctypes.Structure):
                 ("cache_misses", ctypes.c_uint64), ("compile_ms", ctypes.c_double),
                 ("bytes_allocated", ctypes.c_uint64), ("disk_hits", ctypes.c_uint64),
                 ("nodes_merged", ctypes.c_uint64), ("interp_launches", ctypes.c_uint64),
-                ("assign_swaps", ctypes.c_uint64), ("plan_hits", ctypes.c_uint64)]
+                ("assign_swaps", ctypes.c_uint64), ("plan_hits", ctypes.c_uint64), ("pool_bytes", ctypes.c_uint64)]
 
 
 _lib = None

@@ -1022,6 +1022,34 @@ def test_reductions_along_the_strided_axis_of_an_array_stored_transposed(env):
         assert_reduction(gr.sum(x, axis=0).numpy(), ora.sum(xo, axis=0).numpy(), what="sum along the contiguous axis")
 
 
+def test_pool_returns_free_blocks_of_other_sizes_at_its_limit(env):
+    # the default pool keeps freed blocks by size; with a limit it gives the free ones back to the device
+    # before growing past it, also while earlier kernels that read them are still queued
+    gr, ctx, torch = env
+    c2 = gr.Context()
+    c2.set_option("interp", 0)
+    c2.set_option("pool_limit", 24 << 20)
+    peak = 0
+    for i in range(40):
+        n = (1 << 20) + 4099 * i                                  # 4 MiB and a bit, another size every time
+        a = np.full(n, f32(i), f32)
+        x = c2.array(torch.from_numpy(a).cuda())
+        y = (x * 2.0 + 1.0).materialize()
+        z = (y - x).materialize()                                 # two live results of this size, one temporary freed
+        assert np.array_equal(z.numpy()[::4097], (a * f32(2) + f32(1) - a)[::4097])
+        del y, z
+        peak = max(peak, c2.stats()["pool_bytes"])
+    assert peak <= (24 << 20) + 3 * ((n * 4 + 255) // 256 * 256), peak    # the limit plus what one step needs at once
+    c3 = gr.Context()
+    c3.set_option("interp", 0)
+    for i in range(10):
+        x = c3.array(torch.from_numpy(np.ones((1 << 20) + 4099 * i, f32)).cuda())
+        (x * 2.0).materialize()
+    assert c3.stats()["pool_bytes"] > 36 << 20                     # without a limit every size stays
+    c2.close()
+    c3.close()
+
+
 # ---- the byte-code interpreter that stands in while a kernel is being compiled ----------------
 
 @pytest.mark.parametrize("name", sorted(ELEMENTWISE_CASES))
