@@ -35,7 +35,7 @@ def out_shape(name, p):
 
 
 def algorithmic_bytes_per_launch(name, p):
-    """Bytes one launch of the dominant kernel has to move ('Kernels')."""
+    """Bytes one launch of the dominant kernel has to move: every distinct input element once plus the output."""
     from paper_1901_03771_amd import workloads as wl
     if name == "logreg":  # one pass over X for both contractions; the residual r is written once on the way
         return wl.unique_bytes(name, **p) + 4 * p["rows"]
@@ -154,7 +154,7 @@ def main():
     ap.add_argument("--no-launch-events", action="store_true", help="skip the instrumented cross-check pass (one HIP event pair per launch)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards by rows; see DESIGN.md); use --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path would shard by rows, one context per GPU); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
