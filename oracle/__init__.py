@@ -166,6 +166,7 @@ class Array:
     def reshape(self, *shape):
         return reshape(self, shape[0] if len(shape) == 1 and not isinstance(shape[0], int) else shape)
 
+    def mean(self, axis=None, keepdims=False): return mean(self, axis, keepdims)
     def sum(self, axis=None, keepdims=False): return reduce("sum", self, axis, keepdims)
     def max(self, axis=None, keepdims=False): return reduce("max", self, axis, keepdims)
     def min(self, axis=None, keepdims=False): return reduce("min", self, axis, keepdims)
@@ -282,5 +283,16 @@ def square(a): return unary("square", a)
 def tanh(a): return unary("tanh", a)
 def erf(a): return unary("erf", a)
 def sum(a, axis=None, keepdims=False): return reduce("sum", a, axis, keepdims)  # noqa: A001
+
+
+def mean(a, axis=None, keepdims=False):
+    """Arithmetic mean over the given axes of a float32 array: the sum (accumulated in binary64 and
+    rounded once, as `sum` is) divided by the number of terms in one binary32 division."""
+    shape = a.shape
+    dims = range(len(shape)) if axis is None else ([axis] if isinstance(axis, int) else list(axis))
+    terms = 1
+    for d in dims:
+        terms *= shape[d]
+    return reduce("sum", a, axis, keepdims) / float(terms)
 def max(a, axis=None, keepdims=False): return reduce("max", a, axis, keepdims)  # noqa: A001
 def min(a, axis=None, keepdims=False): return reduce("min", a, axis, keepdims)  # noqa: A001

@@ -769,3 +769,23 @@ def test_random_programs_assigning_into_evaluated_values_match_numpy():
             for i, (g, r) in enumerate(zip(got, ref)):
                 assert fuzz.same_bits(g.numpy(), r, zero_signs=False), (seed, i, steps)
     assert into_values > 50
+
+
+def test_mean_is_the_sum_divided_by_the_number_of_terms():
+    # closed forms (exact: every partial sum is a small integer or a dyadic fraction), NumPy in binary64
+    # as the third opinion, and the decomposition over two axes
+    f32 = np.float32
+    for n in (1, 2, 7, 1000, 4097):
+        assert ora.mean(ora.array(np.arange(n, dtype=f32))).numpy() == f32((n - 1) / 2)
+    c = np.full((64, 32), 0.375, f32)
+    assert np.array_equal(ora.mean(ora.array(c), axis=0).numpy(), np.full(32, 0.375, f32))
+    assert np.array_equal(ora.mean(ora.array(c), axis=1, keepdims=True).numpy(), np.full((64, 1), 0.375, f32))
+    x = np.random.default_rng(11).standard_normal((37, 50, 6)).astype(f32)
+    for axis, keep in [(None, False), (0, True), (1, False), (-1, False), ((0, 2), True), ((0, 1, 2), False)]:
+        got = ora.mean(ora.array(x), axis=axis, keepdims=keep).numpy()
+        ref = np.mean(x.astype(np.float64), axis=axis, keepdims=keep)
+        assert got.shape == ref.shape and got.dtype == f32
+        assert np.all(np.abs(got - ref) <= 1e-6 * np.abs(ref) + 1e-7), axis
+    rows = ora.mean(ora.array(x[:, :, 0]), axis=1).numpy()
+    assert abs(float(ora.mean(ora.array(rows)).numpy()) - float(ora.mean(ora.array(x[:, :, 0])).numpy())) < 1e-6
+    assert ora.array(x).mean(axis=1).shape == (37, 6)
