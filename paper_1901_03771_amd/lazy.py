@@ -411,6 +411,7 @@ class _ArrayMethods:
         return self
 
     # -- NumPy-named methods --------------------------------------------------------
+    def mean(self, axis=None, keepdims=False): return mean(self, axis, keepdims)
     def sum(self, axis=None, keepdims=False): return reduce("sum", self, axis, keepdims)
     def max(self, axis=None, keepdims=False): return reduce("max", self, axis, keepdims)
     def min(self, axis=None, keepdims=False): return reduce("min", self, axis, keepdims)
@@ -632,4 +633,13 @@ def tanh(a): return _unary(GR_TANH, a)
 def erf(a): return _unary(GR_ERF, a)
 def sum(a, axis=None, keepdims=False): return _reduce(32, a, axis, keepdims)  # noqa: A001
 def max(a, axis=None, keepdims=False): return _reduce(33, a, axis, keepdims)  # noqa: A001
+
+
+def mean(a, axis=None, keepdims=False):
+    """NumPy's mean of a float32 array, recorded as the sum over the axes divided by their element count."""
+    extents = a.shape
+    count = 1
+    for d in (range(len(extents)) if axis is None else ((axis,) if isinstance(axis, int) else tuple(axis))):
+        count *= extents[d]
+    return _reduce(32, a, axis, keepdims) / float(count)
 def min(a, axis=None, keepdims=False): return _reduce(34, a, axis, keepdims)  # noqa: A001

@@ -1050,6 +1050,22 @@ def test_pool_returns_free_blocks_of_other_sizes_at_its_limit(env):
     c3.close()
 
 
+def test_mean_and_layer_normalisation(env):
+    x = _rand((203, 1501), 941)
+    for axis, keep in [(None, False), (0, True), (1, False), ((0, 1), True)]:
+        got, ref = run_both(env, lambda xp, x: xp.mean(x, axis=axis, keepdims=keep), dict(x=x))
+        assert got.shape == ref.shape
+        assert_reduction(got, ref, what=f"mean over {axis}")
+
+    def layer_norm(xp, x):
+        d = x - xp.mean(x, axis=1, keepdims=True)
+        return d / xp.sqrt(xp.mean(d * d, axis=1, keepdims=True) + 1e-5)
+
+    got, ref = run_both(env, layer_norm, dict(x=x))
+    assert np.all(np.abs(got - ref) <= 2e-5 * np.maximum(np.abs(ref), 1.0))
+    assert np.all(np.abs(got.mean(axis=1)) < 1e-5) and np.all(np.abs(got.var(axis=1) - 1.0) < 1e-3)
+
+
 # ---- the byte-code interpreter that stands in while a kernel is being compiled ----------------
 
 @pytest.mark.parametrize("name", sorted(ELEMENTWISE_CASES))

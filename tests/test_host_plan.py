@@ -855,3 +855,13 @@ def test_small_contractions_fuse_with_their_neighbours(ctx):
     src = (x - v).source(0)
     assert "c0 + 3 == C" in src                                                           # narrow arrays: straight-line code for the last columns
     assert "c0 + 3 == C" not in (ctx.spec((1000, 67)) - ctx.spec((67,))).source(0)        # wide ones keep the generic edge path
+
+
+
+def test_mean_records_a_sum_and_a_division(ctx):
+    x = ctx.spec((64, 1000))
+    assert gr.mean(x, axis=1).shape == (64,) and gr.mean(x).shape == () and x.mean(axis=0, keepdims=True).shape == (1, 1000)
+    d = x - gr.mean(x, axis=1, keepdims=True)
+    ln = d / gr.sqrt(gr.mean(d * d, axis=1, keepdims=True) + 1e-5)
+    assert groups(ln) == [("ROWRED", ["sum", "div", "sub", "mul", "sum", "div", "add", "sqrt", "div"])]   # layer norm: one kernel
+    ln.compile()
