@@ -23,8 +23,10 @@
  *     arguments are host pointers and are copied before the call returns.
  *   - Strides and offsets count ELEMENTS, not bytes.
  *   - Recording calls never touch the device.  Kernels are launched
- *     asynchronously on the context's stream by gr_materialize*; the library
- *     only waits inside gr_sync and gr_ctx_destroy.
+ *     asynchronously on the context's stream by gr_materialize* and
+ *     gr_assign; the library only waits inside gr_sync, gr_ctx_set_stream
+ *     and gr_ctx_destroy (and where its default pool hands memory back to
+ *     the device, see option "pool_limit").
  *   - A context is not thread-safe.
  *   - Supported element types: f32 and i32 for computation; i64 only as the
  *     result of an i32 sum (NumPy's default on Linux).  Mixed i32/f32
