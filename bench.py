@@ -275,13 +275,30 @@ def main():
         # the byte-code interpreter that answers a request while its kernel is still being compiled
         ictx = gr.Context(device=0)
         ictx.set_option("interp", 2)
-        for oname in ("normalize", "stencil"):
+        for oname in ("normalize", "stencil", "softmax"):
             ow = Workload(oname, ictx, 2)
             d_ms, _ = time_steps(torch, ow, 10, 2)
             extras[oname + "_interpreted_GBps"] = round(ow.unique_bytes / (d_ms / 10 * 1e-3) / 1e9, 1)
             del ow
             torch.cuda.empty_cache()
         ictx.close()
+        # first request for a row-resident reduction in a context that has never seen it (and may not read
+        # the on-disk cache): the interpreter's row kernel answers while hipRTC compiles
+        cctx = gr.Context(device=0)
+        cctx.set_option("disk_cache", 0)
+        ow = Workload("softmax", cctx, 2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ow.step()
+        torch.cuda.synchronize()
+        extras["softmax_cold_first_call_ms"] = round((time.perf_counter() - t0) * 1e3, 2)
+        extras["softmax_cold_first_call_interpreted"] = cctx.stats()["interp_launches"] > 0
+        t0 = time.perf_counter()
+        cctx.compile_wait()
+        extras["softmax_compile_wait_after_first_call_ms"] = round((time.perf_counter() - t0) * 1e3, 2)
+        del ow
+        torch.cuda.empty_cache()
+        cctx.close()
         # rows beyond the five configurations: two-stage reduction, map-scan, the full Jacobi loop
         def timed(fn, iters, warm=3):
             for _ in range(warm):

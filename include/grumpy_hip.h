@@ -125,14 +125,15 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     the generated kernel source (and compiler version and
  *                     flags), so another build of the library never reads
  *                     them by mistake; 0 = in-memory cache only
- *   "interp"          1 (default) = a map sub-graph whose kernel is still in the
- *                     run-time compiler is evaluated by a precompiled byte-code
- *                     interpreter of the point function instead of waiting
- *                     (f32 / i32 programs within fixed size limits; everything
- *                     else waits as with 0); the compilation goes on in the
- *                     background and later requests use the compiled kernel;
- *                     0 = always wait for the compiler; 2 = interpret every map
- *                     sub-graph the interpreter covers (for testing it)
+ *   "interp"          1 (default) = a map sub-graph or a row-resident reduction
+ *                     sub-graph whose kernel is still in the run-time compiler is
+ *                     evaluated by a precompiled byte-code interpreter of the
+ *                     point function instead of waiting (f32 / i32 programs
+ *                     within fixed size limits; everything else waits as with
+ *                     0); the compilation goes on in the background and later
+ *                     requests use the compiled kernel; 0 = always wait for the
+ *                     compiler; 2 = interpret every sub-graph the interpreter
+ *                     covers (for testing it)
  *   "assign_swap"     1 (default) = gr_assign of a value that reads the
  *                     destination's storage at shifted positions (a stencil
  *                     sweep), into a unit-step box that covers at least 4/5 of

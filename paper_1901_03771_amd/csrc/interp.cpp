@@ -1,12 +1,14 @@
 // Host side of the point-program interpreter: encodes the single-point program
-// of a map sub-graph as byte code with LDS slots assigned by a linear scan over
-// the values' live ranges, and launches the precompiled kernel.
+// of a map sub-graph, or the phases and the final map of a row-resident
+// reduction sub-graph, as byte code with LDS slots assigned by a linear scan
+// over the values' live ranges, and launches the precompiled kernels.
 #include <algorithm>
 
 #include "ctx.h"
 #include "interp.h"
 
 extern "C" int gr_launch_interp_map(void* stream, const GrInterpArgs* args, unsigned grid);
+extern "C" int gr_launch_interp_rowred(void* stream, const GrInterpRowArgs* args, unsigned grid);
 
 namespace gr {
 
@@ -123,6 +125,144 @@ bool interp_encode(const GroupPlan& g, void* out_ptr, GrInterpArgs* A, unsigned*
   A->n_instr = ni;
   A->result_slot = slot[g.result1];
   return A->result_slot >= 0;
+}
+
+// Operand patterns, constants and extents of a sub-graph: what map and row-resident sub-graphs share.
+static bool encode_operands(const GroupPlan& g, GrInterpArgs* A) {
+  if (g.rank < 1 || g.rank > GR_INTERP_RANK || g.groups.size() > GR_INTERP_GROUPS || g.consts.size() > GR_INTERP_CONSTS) return false;
+  const int pad = GR_INTERP_RANK - g.rank;
+  for (int k = 0; k < GR_INTERP_RANK; ++k) A->dims[k] = 1;
+  for (int k = 0; k < g.rank; ++k) A->dims[k + pad] = g.dims[k];
+  for (size_t gi = 0; gi < g.groups.size(); ++gi) {
+    const AccessGroup& ag = g.groups[gi];
+    if (ag.dtype == GR_I64 || !ag.leaf || !ag.leaf->data) return false;
+    A->gptr[gi] = (unsigned long long)(uintptr_t)ag.leaf->data + 4ull * (unsigned long long)ag.base;
+    for (int k = 0; k < g.rank; ++k) A->gcoef[gi][k + pad] = ag.structural_zero[k] ? 0 : ag.coef[k];
+  }
+  for (size_t i = 0; i < g.consts.size(); ++i) {
+    const ConstSlot& cs = g.consts[i];
+    if (cs.dtype == GR_F32) { float f = (float)cs.value; std::memcpy(&A->consts[i], &f, 4); }
+    else if (cs.dtype == GR_I32) A->consts[i] = (unsigned)(int32_t)(int64_t)cs.value;
+    else return false;
+  }
+  return true;
+}
+
+// Appends to A->code the instructions of `p` that `want` depends on (slots by a linear scan of the
+// live ranges); returns the slot of `want`, -1 if the program is outside what the interpreter covers.
+static int encode_segment(const GroupPlan& g, const std::vector<Instr>& p, int want, GrInterpArgs* A, int* ni, int* nl) {
+  const int n = (int)p.size();
+  if (want < 0 || want >= n) return -1;
+  std::vector<int> last(n, -1);
+  std::vector<char> need(n, 0);
+  need[want] = 1;
+  for (int i = n - 1; i >= 0; --i) {
+    if (!need[i]) continue;
+    for (int o : {p[i].a, p[i].b}) {
+      if (o < 0) continue;
+      if (o >= i) return -1;
+      need[o] = 1;
+      last[o] = std::max(last[o], i);
+    }
+  }
+  last[want] = n;
+  std::vector<int> slot(n, -1), free_slots;
+  for (int s = GR_INTERP_SLOTS - 1; s >= 0; --s) free_slots.push_back(s);
+  for (int i = 0; i < n; ++i) {
+    if (!need[i]) continue;
+    const Instr& in = p[i];
+    if (in.dtype == GR_I64 || *ni >= GR_INTERP_INSTR) return -1;
+    unsigned op, xa = 0, xb = 0;
+    if (in.kind == IKind::LOAD) {
+      if (*nl >= GR_INTERP_LOADS || in.group < 0 || in.group >= (int)g.groups.size()) return -1;
+      const AccessGroup& ag = g.groups[in.group];
+      int64_t off = 0;
+      for (int k = 0; k < g.rank; ++k) if (!ag.structural_zero[k]) off += in.delta[k] * ag.coef[k];
+      A->ldoff[*nl] = off;
+      op = GI_LOAD; xa = (unsigned)in.group; xb = (unsigned)(*nl)++;
+    } else if (in.kind == IKind::CONST) {
+      if (in.cslot < 0 || in.cslot >= (int)g.consts.size()) return -1;
+      op = GI_CONST; xa = (unsigned)in.cslot;
+    } else if (in.kind == IKind::RED) {
+      if (in.phase < 0 || in.phase >= GR_INTERP_PHASES) return -1;
+      op = GI_RED; xa = (unsigned)in.phase;
+    } else if (in.kind == IKind::UNARY || in.kind == IKind::BINARY) {
+      int oc = opcode(in);
+      if (oc < 0 || in.a < 0 || slot[in.a] < 0) return -1;
+      op = (unsigned)oc;
+      xa = (unsigned)slot[in.a];
+      xb = xa;
+      if (in.kind == IKind::BINARY) {
+        if (in.b < 0 || slot[in.b] < 0) return -1;
+        xb = (unsigned)slot[in.b];
+      }
+      for (int o : {in.a, in.kind == IKind::BINARY ? in.b : -1})
+        if (o >= 0 && last[o] == i && slot[o] >= 0) { free_slots.push_back(slot[o]); slot[o] = -2 - slot[o]; }
+    } else return -1;
+    if (free_slots.empty()) return -1;
+    int dst = free_slots.back();
+    free_slots.pop_back();
+    slot[i] = dst;
+    A->code[(*ni)++] = op | ((unsigned)dst << 8) | (xa << 16) | (xb << 24);
+  }
+  return slot[want];
+}
+
+// A row-resident reduction sub-graph (reduction phases over the innermost dimension, then a final
+// map or one value per row) as interpreter segments.  Only rows in number and length that keep the
+// interpreter's run well below a compilation are taken.
+bool interp_encode_rowred(const GroupPlan& g, void* out_ptr, GrInterpRowArgs* R, unsigned* grid) {
+  if (g.kind != GroupKind::ROWRED || g.pair || g.out_dtype == GR_I64 || g.results.empty()) return false;
+  if (g.phases.empty() || g.phases.size() > GR_INTERP_PHASES) return false;
+  std::memset(R, 0, sizeof *R);
+  if (!encode_operands(g, &R->m)) return false;
+  const int64_t C = g.dims[g.rank - 1];
+  int64_t rows = 1;
+  for (int k = 0; k + 1 < g.rank; ++k) rows *= g.dims[k];
+  if (C < 1 || rows < 1 || rows > (int64_t)1 << 22 || rows * C > (int64_t)1 << 28) return false;
+  R->lanes = C <= 512 ? 64 : 256;
+  R->per_row = g.out_per_row ? 1 : 0;
+  R->n_phase = (int)g.phases.size();
+  int ni = 0, nl = 0;
+  for (int s = 0; s <= R->n_phase; ++s) {
+    const bool final = s == R->n_phase;
+    if (!final) {
+      const Phase& ph = g.phases[s];
+      if (ph.in_dtype == GR_I64 || ph.out_dtype == GR_I64) return false;
+      R->phase_op[s] = ph.op == GR_SUM ? 0 : (ph.op == GR_MAX ? 1 : 2);
+      R->phase_int[s] = ph.in_dtype == GR_I32;
+    }
+    R->seg_begin[s] = ni;
+    R->seg_slot[s] = encode_segment(g, g.prog, final ? g.results[0] : g.phases[s].value, &R->m, &ni, &nl);
+    R->seg_end[s] = ni;
+    if (R->seg_slot[s] < 0) return false;
+  }
+  R->m.n_instr = ni;
+  R->m.out = (unsigned long long)(uintptr_t)out_ptr;
+  const int rb = 256 / R->lanes;
+  *grid = (unsigned)((rows + rb - 1) / rb);
+  return true;
+}
+
+gr_status interp_launch_rowred(gr_ctx* c, const GrInterpRowArgs& R, unsigned grid) {
+  if (c->device < 0) { c->stats.kernel_launches++; c->stats.interp_launches++; return GR_OK; }  // dry run
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (c->opt_profile) {
+    for (hipEvent_t* ev : {&e0, &e1}) {
+      if (!c->event_pool.empty()) { *ev = c->event_pool.back(); c->event_pool.pop_back(); }
+      else if (hipEventCreate(ev) != hipSuccess) return fail(c, GR_ERR_HIP, "hipEventCreate failed");
+    }
+    (void)hipEventRecord(e0, c->stream);
+  }
+  int e = gr_launch_interp_rowred(c->stream, &R, grid);
+  if (e != 0) return fail(c, GR_ERR_HIP, std::string("interpreter launch -> ") + hipGetErrorName((hipError_t)e));
+  if (c->opt_profile) {
+    (void)hipEventRecord(e1, c->stream);
+    c->prof.push_back({"gr_interp_rowred", e0, e1});
+  }
+  c->stats.kernel_launches++;
+  c->stats.interp_launches++;
+  return GR_OK;
 }
 
 gr_status interp_launch(gr_ctx* c, const GrInterpArgs& A, unsigned grid) {

@@ -17,7 +17,8 @@ enum {
   GI_LOAD = 0, GI_CONST,
   GI_FNEG, GI_FABS, GI_FEXP, GI_FLOG, GI_FSQRT, GI_FSQUARE, GI_FTANH, GI_FERF,
   GI_FADD, GI_FSUB, GI_FMUL, GI_FDIV, GI_FMAX, GI_FMIN,
-  GI_INEG, GI_IABS, GI_ISQUARE, GI_IADD, GI_ISUB, GI_IMUL, GI_IMAX, GI_IMIN
+  GI_INEG, GI_IABS, GI_ISQUARE, GI_IADD, GI_ISUB, GI_IMUL, GI_IMAX, GI_IMIN,
+  GI_RED   // row-resident reductions: the value of an earlier reduction phase of this row (a = phase)
 };
 
 struct GrInterpArgs {
@@ -32,4 +33,21 @@ struct GrInterpArgs {
   unsigned consts[GR_INTERP_CONSTS];                       // bit patterns
   unsigned code[GR_INTERP_INSTR];                          // op | dst << 8 | a << 16 | b << 24
                                                            // LOAD: a = group, b = index into ldoff; CONST: a = index into consts
+};
+
+// Row-resident reductions (a softmax: row maximum, sum of exponentials, final map) through the
+// interpreter: the code holds one segment per reduction phase and one for the final map; a row
+// is walked once per segment by 64 or 256 lanes.
+#define GR_INTERP_PHASES 4
+
+struct GrInterpRowArgs {
+  GrInterpArgs m;                            // dims (last: row length), operands, constants, all segments' code; out = first output element
+  int n_phase;                               // reduction phases before the final segment
+  int seg_begin[GR_INTERP_PHASES + 1];       // code range and value slot of each segment (phases, then the final one)
+  int seg_end[GR_INTERP_PHASES + 1];
+  int seg_slot[GR_INTERP_PHASES + 1];
+  int phase_op[GR_INTERP_PHASES];            // 0 sum, 1 max, 2 min
+  int phase_int[GR_INTERP_PHASES];           // the phase combines i32 values (else f32)
+  int per_row;                               // one output value per row (else one per element)
+  int lanes;                                 // lanes per row: 64 or 256
 };

@@ -85,6 +85,127 @@ __global__ __launch_bounds__(256) void gr_interp_map_kernel(GrInterpArgs a) {
   *(GM unsigned*)(a.out + 4ull * (unsigned long long)oo) = my[a.result_slot * 256];
 }
 
+// One segment of byte code at element `c` of the row whose outer indices are `idx`.
+static __device__ __forceinline__ void gi_run(const GrInterpArgs& a, int pc, const int end, const long long c, const unsigned* idx,
+                                              unsigned* const my, const unsigned* red) {
+  constexpr int CD = GR_INTERP_RANK - 1;
+  for (; pc < end; ++pc) {
+    const unsigned w = a.code[pc];
+    const unsigned op = w & 0xffu, dst = (w >> 8) & 0xffu, xa = (w >> 16) & 0xffu, xb = w >> 24;
+    unsigned r;
+    if (op == GI_LOAD) {
+      long long off = a.ldoff[xb] + a.gcoef[xa][CD] * c;
+#pragma unroll
+      for (int k = 0; k < CD; ++k) off += a.gcoef[xa][k] * (long long)idx[k];
+      r = *(const GM unsigned*)(a.gptr[xa] + 4ull * (unsigned long long)off);
+    } else if (op == GI_CONST) {
+      r = a.consts[xa];
+    } else if (op == GI_RED) {
+      r = red[xa];
+    } else {
+      const unsigned ux = my[xa * 256];
+      const unsigned uy = my[xb * 256];
+      const float fx = __uint_as_float(ux), fy = __uint_as_float(uy);
+      const int ix = (int)ux, iy = (int)uy;
+      switch (op) {
+        case GI_FNEG: r = __float_as_uint(-fx); break;
+        case GI_FABS: r = __float_as_uint(__builtin_fabsf(fx)); break;
+        case GI_FEXP: r = __float_as_uint(expf(fx)); break;
+        case GI_FLOG: r = __float_as_uint(logf(fx)); break;
+        case GI_FSQRT: r = __float_as_uint(sqrtf(fx)); break;
+        case GI_FSQUARE: r = __float_as_uint(fx * fx); break;
+        case GI_FTANH: r = __float_as_uint(tanhf(fx)); break;
+        case GI_FERF: r = __float_as_uint(erff(fx)); break;
+        case GI_FADD: r = __float_as_uint(fx + fy); break;
+        case GI_FSUB: r = __float_as_uint(fx - fy); break;
+        case GI_FMUL: r = __float_as_uint(fx * fy); break;
+        case GI_FDIV: r = __float_as_uint(fx / fy); break;
+        case GI_FMAX: r = __float_as_uint(gi_maxf(fx, fy)); break;
+        case GI_FMIN: r = __float_as_uint(gi_minf(fx, fy)); break;
+        case GI_INEG: r = 0u - ux; break;
+        case GI_IABS: r = ix < 0 ? 0u - ux : ux; break;
+        case GI_ISQUARE: r = ux * ux; break;
+        case GI_IADD: r = ux + uy; break;
+        case GI_ISUB: r = ux - uy; break;
+        case GI_IMUL: r = ux * uy; break;
+        case GI_IMAX: r = ix >= iy ? ux : uy; break;
+        case GI_IMIN: r = ix <= iy ? ux : uy; break;
+        default: r = 0u; break;
+      }
+    }
+    my[dst * 256] = r;
+  }
+}
+
+static __device__ __forceinline__ unsigned gi_combine(int op, int is_int, unsigned x, unsigned y) {
+  if (is_int) {
+    const int ix = (int)x, iy = (int)y;
+    return op == 0 ? x + y : (op == 1 ? (ix >= iy ? x : y) : (ix <= iy ? x : y));
+  }
+  const float fx = __uint_as_float(x), fy = __uint_as_float(y);
+  return __float_as_uint(op == 0 ? fx + fy : (op == 1 ? gi_maxf(fx, fy) : gi_minf(fx, fy)));
+}
+
+// Row-resident reductions: 256 / lanes rows per workgroup; every segment walks the row once.  All
+// lanes reach every barrier: rows past the end repeat the last row and skip the stores.
+__global__ __launch_bounds__(256) void gr_interp_rowred_kernel(GrInterpRowArgs A) {
+  __shared__ unsigned vals[GR_INTERP_SLOTS * 256];
+  __shared__ unsigned red[4][GR_INTERP_PHASES];
+  __shared__ unsigned part[4];
+  constexpr int CD = GR_INTERP_RANK - 1;
+  const GrInterpArgs& a = A.m;
+  const int RT = A.lanes, lane = threadIdx.x % RT, rslot = threadIdx.x / RT;
+  const long long C = a.dims[CD];
+  unsigned long long rows = 1;
+#pragma unroll
+  for (int k = 0; k < CD; ++k) rows *= (unsigned long long)a.dims[k];
+  const unsigned long long row_raw = (unsigned long long)blockIdx.x * (256 / RT) + rslot;
+  const bool row_ok = row_raw < rows;
+  const unsigned row = (unsigned)(row_ok ? row_raw : rows - 1);   // the host checked that rows fit 31 bits
+  unsigned idx[CD];
+  {
+    unsigned rem = row;
+#pragma unroll
+    for (int k = CD - 1; k >= 0; --k) {
+      const unsigned d = (unsigned)a.dims[k];
+      idx[k] = rem % d;
+      rem /= d;
+    }
+  }
+  unsigned* const my = vals + threadIdx.x;
+  for (int s = 0; s <= A.n_phase; ++s) {
+    const bool final = s == A.n_phase;
+    if (final) {
+      const long long n = A.per_row ? 1 : C;
+      for (long long c = lane; c < n; c += RT) {
+        gi_run(a, A.seg_begin[s], A.seg_end[s], c, idx, my, red[rslot]);
+        if (row_ok) *(GM unsigned*)(a.out + 4ull * (A.per_row ? (unsigned long long)row : (unsigned long long)row * (unsigned long long)C + (unsigned long long)c)) = my[A.seg_slot[s] * 256];
+      }
+      break;
+    }
+    const int op = A.phase_op[s], is_int = A.phase_int[s];
+    unsigned acc = is_int ? (op == 0 ? 0u : (op == 1 ? 0x80000000u : 0x7fffffffu))
+                          : (op == 0 ? 0u : (op == 1 ? 0xff800000u : 0x7f800000u));   // 0, -inf / INT_MIN, +inf / INT_MAX
+    for (long long c = lane; c < C; c += RT) {
+      gi_run(a, A.seg_begin[s], A.seg_end[s], c, idx, my, red[rslot]);
+      acc = gi_combine(op, is_int, acc, my[A.seg_slot[s] * 256]);
+    }
+    for (int d = 32; d >= 1; d >>= 1) acc = gi_combine(op, is_int, acc, (unsigned)__shfl_xor((int)acc, d, 64));
+    if (RT == 256) {
+      if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+      __syncthreads();
+      acc = gi_combine(op, is_int, gi_combine(op, is_int, part[0], part[1]), gi_combine(op, is_int, part[2], part[3]));
+    }
+    if (lane == 0) red[rslot][s] = acc;
+    __syncthreads();
+  }
+}
+
+extern "C" int gr_launch_interp_rowred(void* stream, const GrInterpRowArgs* args, unsigned grid) {
+  hipLaunchKernelGGL(gr_interp_rowred_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args);
+  return (int)hipGetLastError();
+}
+
 extern "C" int gr_launch_interp_map(void* stream, const GrInterpArgs* args, unsigned grid) {
   hipLaunchKernelGGL(gr_interp_map_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args);
   return (int)hipGetLastError();

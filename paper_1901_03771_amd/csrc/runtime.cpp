@@ -27,6 +27,8 @@ namespace gr {
 
 bool interp_encode(const GroupPlan& g, void* out_ptr, GrInterpArgs* A, unsigned* grid);
 gr_status interp_launch(gr_ctx* c, const GrInterpArgs& A, unsigned grid);
+bool interp_encode_rowred(const GroupPlan& g, void* out_ptr, GrInterpRowArgs* R, unsigned* grid);
+gr_status interp_launch_rowred(gr_ctx* c, const GrInterpRowArgs& R, unsigned grid);
 
 static std::string hip_err(hipError_t e) { return std::string(hipGetErrorName(e)) + ": " + hipGetErrorString(e); }
 
@@ -543,7 +545,7 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
   static gr_ctx::Kernel dry_kernel;  // stands for any kernel in a dry run that does not compile
   const bool no_compile = c->device < 0 && c->opt_dry_run >= 2;
   for (auto& gp : plan->groups) {
-    if (no_compile || (c->opt_interp >= 2 && gp->kind == GroupKind::MAP)) continue;  // no kernel wanted
+    if (no_compile || (c->opt_interp >= 2 && (gp->kind == GroupKind::MAP || gp->kind == GroupKind::ROWRED))) continue;  // no kernel wanted (yet)
     gr_status pst = prepare_group(c, *gp);
     if (pst != GR_OK) return pst;
   }
@@ -553,7 +555,8 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
     // A map sub-graph whose kernel is still in the compiler runs through the byte-code
     // interpreter instead of waiting; the job stays pending and a later request collects it.
     // (option "interp" = 2: every map sub-graph the interpreter covers, compiled or not)
-    const bool try_interp = g.kind == GroupKind::MAP && !g.pair && (c->opt_interp >= 2 || (c->opt_interp == 1 && still_compiling(c, g)));
+    const bool try_interp = (g.kind == GroupKind::MAP || g.kind == GroupKind::ROWRED) && !g.pair &&
+                            (c->opt_interp >= 2 || (c->opt_interp == 1 && still_compiling(c, g)));
     if (no_compile) k = &dry_kernel;
     gr_status st = (try_interp || no_compile) ? GR_OK : compile_group(c, g, &k);
     if (st != GR_OK) return st;
@@ -577,10 +580,16 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
       unsigned igrid = 0;
       int64_t total = 1;
       for (int k2 = 0; k2 < g.rank; ++k2) total *= g.dims[k2];
-      if (total == 0) interpreted = true;  // nothing to compute
-      else if (interp_encode(g, outs[0], &ia, &igrid)) {
+      if (total == 0 && g.kind == GroupKind::MAP) interpreted = true;  // nothing to compute
+      else if (g.kind == GroupKind::MAP && interp_encode(g, outs[0], &ia, &igrid)) {
         st = interp_launch(c, ia, igrid);
         interpreted = true;
+      } else if (g.kind == GroupKind::ROWRED) {
+        GrInterpRowArgs ra;
+        if (interp_encode_rowred(g, outs[0], &ra, &igrid)) {
+          st = interp_launch_rowred(c, ra, igrid);
+          interpreted = true;
+        }
       }
     }
     if (!interpreted) {

@@ -1086,9 +1086,14 @@ def test_interpreter_small_configurations(env, env_interp, name):
     arrays = wl.make_inputs(name, **wl.SMALL[name])
     n0 = env_interp[1].stats()["interp_launches"]
     got, ref = run_both(env_interp, wl.PROGRAMS[name], arrays)
-    if name in ("softmax", "logreg"):
-        # no map sub-graph in these: reductions and contractions always wait for their kernels
+    if name == "logreg":
+        # no map or row-resident sub-graph here: contractions always wait for their kernels
         assert env_interp[1].stats()["interp_launches"] == n0
+        assert_reduction(got, ref, what=name)
+        return
+    if name == "softmax":
+        # row maximum, sum of exponentials and the final division as three interpreter segments
+        assert env_interp[1].stats()["interp_launches"] == n0 + 1
         assert_reduction(got, ref, what=name)
         return
     assert env_interp[1].stats()["interp_launches"] > n0
@@ -1098,6 +1103,35 @@ def test_interpreter_small_configurations(env, env_interp, name):
     assert_elementwise(got, ref, floor=floor, what=name)
     compiled, _ = run_both(env, wl.PROGRAMS[name], arrays)
     assert np.array_equal(got.view(np.uint32), compiled.view(np.uint32))
+
+
+@pytest.mark.parametrize("shape", [(67, 1000), (5, 33), (300, 513), (41, 7, 130), (1, 4096), (9, 1)])
+def test_interpreter_row_resident_reductions(env, env_interp, shape):
+    # reductions over the innermost axis fused with producers and consumers, evaluated as byte code: rows
+    # walked by 64 lanes (up to 512 elements) or 256, several phases, values per row and per element, int32
+    a = _rand(shape, 951)
+    last = len(shape) - 1
+    progs = [
+        lambda xp, a: xp.exp(a - xp.max(a, axis=last, keepdims=True)) / xp.sum(xp.exp(a - xp.max(a, axis=last, keepdims=True)), axis=last, keepdims=True),
+        lambda xp, a: xp.sum(a * a, axis=last),
+        lambda xp, a: xp.max(abs(a), axis=last, keepdims=True) - xp.min(a, axis=last, keepdims=True) + a * 0.5,
+        lambda xp, a: (a - xp.sum(a, axis=last, keepdims=True) / float(shape[last])) * 2.0,
+    ]
+    for i, prog in enumerate(progs):
+        n0 = env_interp[1].stats()["interp_launches"]
+        got, ref = run_both(env_interp, prog, dict(a=a))
+        assert env_interp[1].stats()["interp_launches"] > n0, "the interpreter did not run"
+        assert got.shape == ref.shape
+        assert_reduction(got, ref, what=f"program {i} on {shape}")
+        compiled, _ = run_both(env, prog, dict(a=a))
+        assert_reduction(got, compiled.astype(np.float64), what=f"interpreter against generated kernel, program {i}")
+    x = np.random.default_rng(952).integers(-1000, 1000, shape).astype(np.int32)
+    got, ref = run_both(env_interp, lambda xp, x: xp.max(x, axis=last, keepdims=True) - x + xp.min(x, axis=last, keepdims=True), dict(x=x))
+    assert np.array_equal(got, ref)
+    nan_row = a.copy()
+    nan_row.reshape(-1, shape[last])[0, shape[last] // 2] = np.nan
+    got, ref = run_both(env_interp, lambda xp, a: xp.max(a, axis=last), dict(a=nan_row))
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(got[~np.isnan(got)], ref[~np.isnan(ref)])
 
 
 def test_interpreter_int32_and_strided_destinations(env_interp):
