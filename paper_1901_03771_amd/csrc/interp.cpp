@@ -220,7 +220,11 @@ bool interp_encode_rowred(const GroupPlan& g, void* out_ptr, GrInterpRowArgs* R,
   int64_t rows = 1;
   for (int k = 0; k + 1 < g.rank; ++k) rows *= g.dims[k];
   if (C < 1 || rows < 1 || rows > (int64_t)1 << 22 || rows * C > (int64_t)1 << 28) return false;
-  R->lanes = C <= 512 ? 64 : 256;
+  // the generated kernel's assignment of elements to lanes, so that both combine in the same order
+  R->lanes = g.row_threads;
+  R->positions = g.NP;
+  if (!(R->lanes == 1 || R->lanes == 2 || R->lanes == 4 || R->lanes == 8 || R->lanes == 16 || R->lanes == 64 || R->lanes == 128 || R->lanes == 256)) return false;
+  if ((int64_t)R->lanes * 4 * R->positions < C) return false;
   R->per_row = g.out_per_row ? 1 : 0;
   R->n_phase = (int)g.phases.size();
   int ni = 0, nl = 0;

@@ -37,7 +37,7 @@ struct GrInterpArgs {
 
 // Row-resident reductions (a softmax: row maximum, sum of exponentials, final map) through the
 // interpreter: the code holds one segment per reduction phase and one for the final map; a row
-// is walked once per segment by 64 or 256 lanes.
+// is walked once per segment by the lanes the generated kernel would give it.
 #define GR_INTERP_PHASES 4
 
 struct GrInterpRowArgs {
@@ -49,5 +49,6 @@ struct GrInterpRowArgs {
   int phase_op[GR_INTERP_PHASES];            // 0 sum, 1 max, 2 min
   int phase_int[GR_INTERP_PHASES];           // the phase combines i32 values (else f32)
   int per_row;                               // one output value per row (else one per element)
-  int lanes;                                 // lanes per row: 64 or 256
+  int lanes;                                 // lanes per row and vec4 positions per lane: those of the generated kernel
+  int positions;                             // (1, 2, 4, 8, 16, 64, 128 or 256 lanes)
 };

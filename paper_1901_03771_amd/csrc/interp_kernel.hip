@@ -146,15 +146,19 @@ static __device__ __forceinline__ unsigned gi_combine(int op, int is_int, unsign
   return __float_as_uint(op == 0 ? fx + fy : (op == 1 ? gi_maxf(fx, fy) : gi_minf(fx, fy)));
 }
 
-// Row-resident reductions: 256 / lanes rows per workgroup; every segment walks the row once.  All
-// lanes reach every barrier: rows past the end repeat the last row and skip the stores.
+// Row-resident reductions: 256 / lanes rows per workgroup; every segment walks the row once.  The
+// elements of a row go to the lanes, and the partial results are combined, exactly as in the
+// generated kernel of the same sub-graph (lane l takes the elements 4 * (p * lanes + l) + j for
+// p = 0, 1, ... in that order; butterfly over the lanes of a wave from the widest distance down;
+// then the waves of a row in pairs), so both give the same bits, sums included.  All lanes reach
+// every barrier: rows past the end repeat the last row and skip the stores.
 __global__ __launch_bounds__(256) void gr_interp_rowred_kernel(GrInterpRowArgs A) {
   __shared__ unsigned vals[GR_INTERP_SLOTS * 256];
-  __shared__ unsigned red[4][GR_INTERP_PHASES];
+  __shared__ unsigned red[256][GR_INTERP_PHASES];
   __shared__ unsigned part[4];
   constexpr int CD = GR_INTERP_RANK - 1;
   const GrInterpArgs& a = A.m;
-  const int RT = A.lanes, lane = threadIdx.x % RT, rslot = threadIdx.x / RT;
+  const int RT = A.lanes, NP = A.positions, lane = threadIdx.x % RT, rslot = threadIdx.x / RT;
   const long long C = a.dims[CD];
   unsigned long long rows = 1;
 #pragma unroll
@@ -176,25 +180,38 @@ __global__ __launch_bounds__(256) void gr_interp_rowred_kernel(GrInterpRowArgs A
   for (int s = 0; s <= A.n_phase; ++s) {
     const bool final = s == A.n_phase;
     if (final) {
-      const long long n = A.per_row ? 1 : C;
-      for (long long c = lane; c < n; c += RT) {
-        gi_run(a, A.seg_begin[s], A.seg_end[s], c, idx, my, red[rslot]);
-        if (row_ok) *(GM unsigned*)(a.out + 4ull * (A.per_row ? (unsigned long long)row : (unsigned long long)row * (unsigned long long)C + (unsigned long long)c)) = my[A.seg_slot[s] * 256];
+      if (A.per_row) {
+        if (lane == 0) {
+          gi_run(a, A.seg_begin[s], A.seg_end[s], 0, idx, my, red[rslot]);
+          if (row_ok) *(GM unsigned*)(a.out + 4ull * (unsigned long long)row) = my[A.seg_slot[s] * 256];
+        }
+        break;
       }
+      for (int p = 0; p < NP; ++p)
+        for (int j = 0; j < 4; ++j) {
+          const long long c = ((long long)p * RT + lane) * 4 + j;
+          if (c >= C) continue;
+          gi_run(a, A.seg_begin[s], A.seg_end[s], c, idx, my, red[rslot]);
+          if (row_ok) *(GM unsigned*)(a.out + 4ull * ((unsigned long long)row * (unsigned long long)C + (unsigned long long)c)) = my[A.seg_slot[s] * 256];
+        }
       break;
     }
     const int op = A.phase_op[s], is_int = A.phase_int[s];
     unsigned acc = is_int ? (op == 0 ? 0u : (op == 1 ? 0x80000000u : 0x7fffffffu))
                           : (op == 0 ? 0u : (op == 1 ? 0xff800000u : 0x7f800000u));   // 0, -inf / INT_MIN, +inf / INT_MAX
-    for (long long c = lane; c < C; c += RT) {
-      gi_run(a, A.seg_begin[s], A.seg_end[s], c, idx, my, red[rslot]);
-      acc = gi_combine(op, is_int, acc, my[A.seg_slot[s] * 256]);
-    }
-    for (int d = 32; d >= 1; d >>= 1) acc = gi_combine(op, is_int, acc, (unsigned)__shfl_xor((int)acc, d, 64));
-    if (RT == 256) {
+    for (int p = 0; p < NP; ++p)
+      for (int j = 0; j < 4; ++j) {
+        const long long c = ((long long)p * RT + lane) * 4 + j;
+        if (c >= C) continue;
+        gi_run(a, A.seg_begin[s], A.seg_end[s], c, idx, my, red[rslot]);
+        acc = gi_combine(op, is_int, acc, my[A.seg_slot[s] * 256]);
+      }
+    for (int m = (RT < 64 ? RT : 64) / 2; m > 0; m >>= 1) acc = gi_combine(op, is_int, acc, (unsigned)__shfl_xor((int)acc, m, 64));
+    if (RT > 64) {
       if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
       __syncthreads();
-      acc = gi_combine(op, is_int, gi_combine(op, is_int, part[0], part[1]), gi_combine(op, is_int, part[2], part[3]));
+      if (RT == 256) acc = gi_combine(op, is_int, gi_combine(op, is_int, part[0], part[1]), gi_combine(op, is_int, part[2], part[3]));
+      else { const int w0 = (threadIdx.x >> 7) * 2; acc = gi_combine(op, is_int, part[w0], part[w0 + 1]); }
     }
     if (lane == 0) red[rslot][s] = acc;
     __syncthreads();
