@@ -294,5 +294,22 @@ def mean(a, axis=None, keepdims=False):
     for d in dims:
         terms *= shape[d]
     return reduce("sum", a, axis, keepdims) / float(terms)
+
+
+def var(a, axis=None, keepdims=False):
+    """Population variance (NumPy's default, ddof = 0): the mean of the squared deviations from the
+    mean, in two passes as NumPy computes it."""
+    d = a - mean(a, axis, True)
+    return mean(d * d, axis, keepdims)
+
+
+def std(a, axis=None, keepdims=False):
+    """Square root of the population variance."""
+    return sqrt(var(a, axis, keepdims))
+
+
+def clip(a, lo, hi):
+    """NumPy's clip with two bounds: minimum(maximum(a, lo), hi)."""
+    return minimum(maximum(a, lo), hi)
 def max(a, axis=None, keepdims=False): return reduce("max", a, axis, keepdims)  # noqa: A001
 def min(a, axis=None, keepdims=False): return reduce("min", a, axis, keepdims)  # noqa: A001

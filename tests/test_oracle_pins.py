@@ -789,3 +789,24 @@ def test_mean_is_the_sum_divided_by_the_number_of_terms():
     rows = ora.mean(ora.array(x[:, :, 0]), axis=1).numpy()
     assert abs(float(ora.mean(ora.array(rows)).numpy()) - float(ora.mean(ora.array(x[:, :, 0])).numpy())) < 1e-6
     assert ora.array(x).mean(axis=1).shape == (37, 6)
+
+
+def test_var_std_and_clip_follow_their_definitions():
+    # variance: closed form for 0..n-1 ((n^2 - 1) / 12, every intermediate exact for small n), shift invariance,
+    # NumPy in binary64; clip: bounds reached exactly, order of the two bounds as NumPy applies them
+    f32 = np.float32
+    for n in (2, 5, 9, 33):
+        got = float(ora.var(ora.array(np.arange(n, dtype=f32))).numpy())
+        assert abs(got - (n * n - 1) / 12.0) <= 1e-6 * (n * n) / 12.0
+    x = np.random.default_rng(12).standard_normal((41, 30)).astype(f32)
+    for axis, keep in [(None, False), (0, True), (1, False), ((0, 1), False)]:
+        for name in ("var", "std"):
+            got = getattr(ora, name)(ora.array(x), axis=axis, keepdims=keep).numpy()
+            ref = getattr(np, name)(x.astype(np.float64), axis=axis, keepdims=keep)
+            assert got.shape == ref.shape and np.all(np.abs(got - ref) <= 2e-6 * np.abs(ref)), (name, axis)
+    shifted = ora.var(ora.array(x + f32(8)), axis=1).numpy()
+    assert np.all(np.abs(shifted - ora.var(ora.array(x), axis=1).numpy()) <= 1e-4)
+    assert float(ora.var(ora.array(np.full(17, 3.5, f32))).numpy()) == 0.0
+    c = ora.clip(ora.array(x), -0.5, 0.25).numpy()
+    assert np.array_equal(c, np.clip(x, f32(-0.5), f32(0.25))) and c.max() == f32(0.25) and c.min() == f32(-0.5)
+    assert np.array_equal(ora.clip(ora.array(x), 1.0, -1.0).numpy(), np.clip(x, f32(1.0), f32(-1.0)))   # lo > hi: everything becomes hi
