@@ -412,6 +412,9 @@ class _ArrayMethods:
 
     # -- NumPy-named methods --------------------------------------------------------
     def mean(self, axis=None, keepdims=False): return mean(self, axis, keepdims)
+    def var(self, axis=None, keepdims=False): return var(self, axis, keepdims)
+    def std(self, axis=None, keepdims=False): return std(self, axis, keepdims)
+    def clip(self, lo, hi): return clip(self, lo, hi)
     def sum(self, axis=None, keepdims=False): return reduce("sum", self, axis, keepdims)
     def max(self, axis=None, keepdims=False): return reduce("max", self, axis, keepdims)
     def min(self, axis=None, keepdims=False): return reduce("min", self, axis, keepdims)
@@ -642,4 +645,19 @@ def mean(a, axis=None, keepdims=False):
     for d in (range(len(extents)) if axis is None else ((axis,) if isinstance(axis, int) else tuple(axis))):
         count *= extents[d]
     return _reduce(32, a, axis, keepdims) / float(count)
+
+
+def var(a, axis=None, keepdims=False):
+    """NumPy's var (ddof = 0): the mean of the squared deviations from the mean."""
+    d = a - mean(a, axis, True)
+    return mean(d * d, axis, keepdims)
+
+
+def std(a, axis=None, keepdims=False):
+    return sqrt(var(a, axis, keepdims))
+
+
+def clip(a, lo, hi):
+    """NumPy's clip with two bounds."""
+    return minimum(maximum(a, lo), hi)
 def min(a, axis=None, keepdims=False): return _reduce(34, a, axis, keepdims)  # noqa: A001

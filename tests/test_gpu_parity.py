@@ -1061,6 +1061,12 @@ def test_mean_and_layer_normalisation(env):
         d = x - xp.mean(x, axis=1, keepdims=True)
         return d / xp.sqrt(xp.mean(d * d, axis=1, keepdims=True) + 1e-5)
 
+    for axis, keep in [(None, False), (0, False), (1, True)]:
+        for fn in ("var", "std"):
+            got, ref = run_both(env, lambda xp, x: getattr(xp, fn)(x, axis=axis, keepdims=keep), dict(x=x))
+            assert got.shape == ref.shape and np.all(np.abs(got - ref) <= 2e-5 * np.abs(ref)), (fn, axis)
+    got, ref = run_both(env, lambda xp, x: xp.clip(x * 2.0, -0.5, 1.25), dict(x=x))
+    assert np.array_equal(got, ref)
     got, ref = run_both(env, layer_norm, dict(x=x))
     assert np.all(np.abs(got - ref) <= 2e-5 * np.maximum(np.abs(ref), 1.0))
     assert np.all(np.abs(got.mean(axis=1)) < 1e-5) and np.all(np.abs(got.var(axis=1) - 1.0) < 1e-3)

@@ -865,3 +865,12 @@ def test_mean_records_a_sum_and_a_division(ctx):
     ln = d / gr.sqrt(gr.mean(d * d, axis=1, keepdims=True) + 1e-5)
     assert groups(ln) == [("ROWRED", ["sum", "div", "sub", "mul", "sum", "div", "add", "sqrt", "div"])]   # layer norm: one kernel
     ln.compile()
+
+
+def test_var_std_clip_are_recorded_from_existing_ops(ctx):
+    x = ctx.spec((64, 1000))
+    assert gr.var(x, axis=1).shape == (64,) and x.std(axis=0, keepdims=True).shape == (1, 1000) and gr.clip(x, -1.0, 1.0).shape == (64, 1000)
+    z = (x - gr.mean(x, axis=1, keepdims=True)) / (gr.std(x, axis=1, keepdims=True) + 1e-6)
+    assert [k for k, _ in groups(z)] == ["ROWRED"]            # standardising rows: one row-resident kernel
+    assert groups(gr.clip(x * 2.0, 0.0, 6.0)) == [("MAP", ["mul", "maximum", "minimum"])]
+    z.compile()
