@@ -142,8 +142,14 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     two buffers; 0 = always evaluate, then copy
  *   "stage_transposed" 1 (default) = a map sub-graph reads operands whose contiguous
  *                     dimension is the row dimension of the iteration space
- *                     (transposed views) through 64 x 64 tiles transposed in LDS;
+ *                     (transposed views) through tiles transposed in LDS;
  *                     0 = strided loads
+ *   "stage_rows"      rows of such a tile (it has 64 columns): 0 (default) = 128
+ *                     where the iteration space has 128 rows or more, else 64;
+ *                     64 = always 64
+ *   "stage_diag"      1 (default) = kernels with such tiles take row blocks
+ *                     diagonally and give each XCD a contiguous range of column
+ *                     blocks; 0 = row-major tile order
  *   "rowred_rows"     rows a lane group of a row-resident reduction takes per
  *                     launch when rows are short (at most 64 elements) and reduce
  *                     to one value each: 0 (default) = 4 for 2^18 rows or more,

@@ -24,6 +24,7 @@
 #include <algorithm>
 #include <functional>
 #include <map>
+#include <set>
 #include <sstream>
 
 #include "ctx.h"
@@ -297,7 +298,19 @@ void gen_map(Em& e) {
            "    tile = (blockIdx.x % 8) * per + blockIdx.x / 8;\n"
            "    if (tile >= ntiles) return; }\n";
   }
-  e.o << "  const unsigned bx = tile % nbx, t2 = tile / nbx, by = t2 % nby, olin = t2 / nby;\n";
+  if (g.diag)
+    // A transposed operand of a matrix whose rows are a power of two long: the tiles of one row
+    // block lie megabytes apart in it, on few memory channels.  Workgroups in flight together
+    // take different row blocks as well as different column blocks.  Column blocks next to each
+    // other share cache lines of the output when its rows are not a multiple of 128 bytes long:
+    // they go to the same XCD (workgroups are dealt round-robin over the 8 XCDs), whose L2 then
+    // merges the two halves of such a line into one write.
+    e.o << "  const unsigned slab = nbx * nby, olin = tile / slab, sl = tile % slab;\n"
+           "  unsigned bx, by;\n"
+           "  if ((nbx & 7) == 0) { const unsigned nq = nbx >> 3, l = sl >> 3; bx = (sl & 7) * nq + l % nq; by = (l / nq + bx) % nby; }\n"
+           "  else { bx = sl % nbx; by = (sl / nbx + bx) % nby; }\n";
+  else
+    e.o << "  const unsigned bx = tile % nbx, t2 = tile / nbx, by = t2 % nby, olin = t2 / nby;\n";
   if (rank > 2) {
     e.o << "  unsigned orem = olin;\n";
     for (int k = rank - 3; k >= 0; --k) e.o << "  const long long i" << k << " = orem % (unsigned)" << e.dim(k) << "; orem /= (unsigned)" << e.dim(k) << ";\n";
@@ -347,15 +360,30 @@ void gen_map(Em& e) {
       const AccessGroup& ag = g.groups[gi];
       const char* T = cty(ag.dtype);
       const char* V4 = vty4(ag.dtype);
-      e.o << "  __shared__ " << T << " tg" << gi << "[64][65];\n";
+      // tile: 64 columns by STR = BY * VR rows of the iteration space, i.e. 64 runs of STR
+      // contiguous elements of the operand
+      const int STR = g.BY * g.VR, TPR = STR / 4, RPP = 256 / TPR, NPASS = 64 / RPP;
+      // Row cc of the tile is rotated by 4 * (cc / 4) elements: a lane's four-element writes
+      // (along the operand's contiguous dimension) and its four-element reads (rows of its patch,
+      // one column) both touch every LDS bank once per eight lanes.
+      const char* V4A = ag.dtype == GR_F32 ? "f4" : "i4";
+      e.o << "  __shared__ __attribute__((aligned(16))) " << T << " tg" << gi << "[64][" << STR << "];\n";
       e.o << "  { const GM " << T << "* const pt = q" << gi;
       for (int k = 0; k + 2 < rank; ++k) if (!ag.structural_zero[k]) e.o << " + i" << k << " * " << e.coef((int)gi, k);
-      e.o << " + (long long)by * 64 + (long long)bx * 64 * " << e.coef((int)gi, cd) << ";\n";
-      e.o << "    for (int i = 0; i < 4; ++i) {\n      const int cc = threadIdx.x / 16 + 16 * i, r4 = (threadIdx.x % 16) * 4;\n"
-             "      const long long gc = (long long)bx * 64 + cc, gr = (long long)by * 64 + r4;\n"
+      e.o << " + (long long)by * " << STR << " + (long long)bx * 64 * " << e.coef((int)gi, cd) << ";\n";
+      e.o << "    const int c1 = threadIdx.x / " << TPR << ", r4 = (threadIdx.x % " << TPR << ") * 4;\n";
+      // interior tiles: every load is issued before the first LDS store
+      e.o << "    if ((long long)bx * 64 + 64 <= C && (long long)by * " << STR << " + " << STR << " <= R) {\n"
+             "      " << V4 << " w[" << NPASS << "];\n"
+             "      _Pragma(\"unroll\") for (int i = 0; i < " << NPASS << "; ++i) w[i] = *(const GM " << V4 << "*)(pt + (c1 + " << RPP << " * i) * " << e.coef((int)gi, cd) << " + r4);\n"
+             "      _Pragma(\"unroll\") for (int i = 0; i < " << NPASS << "; ++i) { const int cc = c1 + " << RPP << " * i;"
+             " *(" << V4A << "*)&tg" << gi << "[cc][(r4 + 4 * (cc >> 2)) & " << STR - 1 << "] = w[i]; }\n"
+             "    } else\n";
+      e.o << "    for (int i = 0; i < " << NPASS << "; ++i) {\n      const int cc = c1 + " << RPP << " * i;\n"
+             "      const long long gc = (long long)bx * 64 + cc, gr = (long long)by * " << STR << " + r4;\n"
              "      if (gc < C && gr + 4 <= R) { const " << V4 << " w = *(const GM " << V4 << "*)(pt + cc * " << e.coef((int)gi, cd) << " + r4);"
-             " tg" << gi << "[cc][r4] = w[0]; tg" << gi << "[cc][r4 + 1] = w[1]; tg" << gi << "[cc][r4 + 2] = w[2]; tg" << gi << "[cc][r4 + 3] = w[3]; }\n"
-             "      else if (gc < C) { for (int j = 0; j < 4; ++j) if (gr + j < R) tg" << gi << "[cc][r4 + j] = pt[cc * " << e.coef((int)gi, cd) << " + r4 + j]; }\n"
+             " *(" << V4A << "*)&tg" << gi << "[cc][(r4 + 4 * (cc >> 2)) & " << STR - 1 << "] = w; }\n"
+             "      else if (gc < C) { for (int j = 0; j < 4; ++j) if (gr + j < R) tg" << gi << "[cc][(r4 + j + 4 * (cc >> 2)) & " << STR - 1 << "] = pt[cc * " << e.coef((int)gi, cd) << " + r4 + j]; }\n"
              "    }\n  }\n";
     }
     e.o << "  __syncthreads();\n";
@@ -380,13 +408,20 @@ void gen_map(Em& e) {
       }
     }
     int nl = 0;
+    std::set<std::string> staged_done;
     for (size_t i = 0; i < g.prog.size(); ++i) {
       const Instr& in = g.prog[i];
       if (in.kind != IKind::LOAD || !used[i]) continue;
       const AccessGroup& ag = g.groups[in.group];
       if (g.stage_mask >> in.group & 1) {
-        // element (row r0 + dr, column c0 + dc) of the iteration space sits at [column][row] of the tile
-        load_name[(int)i] = "tg" + std::to_string(in.group) + "[tx * 4 + " + std::to_string(in.delta[cd]) + "][ty * " + std::to_string(g.VR) + " + " + std::to_string(in.delta[rd]) + "]";
+        // element (row r0 + dr, column c0 + dc) of the iteration space sits at [column][row] of the
+        // tile (rotated): four rows of one column are one 16-byte LDS read
+        const int dc = (int)in.delta[cd], dr = (int)in.delta[rd];
+        const std::string nm = "S" + std::to_string(in.group) + "_" + std::to_string(dc) + "_" + std::to_string(dr / 4);
+        if (staged_done.insert(nm).second)
+          e.o << "    const " << (ag.dtype == GR_F32 ? "f4" : "i4") << ' ' << nm << " = *(const " << (ag.dtype == GR_F32 ? "f4" : "i4") << "*)&tg" << in.group
+              << "[tx * 4 + " << dc << "][(ty * " << g.VR << " + " << dr / 4 * 4 << " + 4 * tx) & " << g.BY * g.VR - 1 << "];\n";
+        load_name[(int)i] = nm + "[" + std::to_string(dr % 4) + "]";
         continue;
       }
       if (access_class(ag, cd) != '1') {

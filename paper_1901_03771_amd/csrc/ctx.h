@@ -34,6 +34,8 @@ struct gr_ctx {
   int64_t opt_rowred_rows = 0;
   int64_t opt_gemm_bn = 0;
   int64_t opt_pool_limit = 0;
+  int64_t opt_stage_rows = 0;
+  int64_t opt_stage_diag = 1;
   int64_t opt_gemv_slabs = 0, opt_gemv_unroll = 0;
   int64_t opt_gemv_pair = 1;
   int64_t opt_async_compile = 1;

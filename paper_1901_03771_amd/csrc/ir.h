@@ -177,6 +177,7 @@ struct GroupPlan {
   int row_iters = 1;                     // ROWRED: rows a lane group takes in one launch (short rows, one value per row)
   bool xcd_remap = false;
   int stage_mask = 0;                    // MAP: access groups (bit per group) read through a transposing LDS tile
+  int diag = 0;                          // MAP with staged operands: tile rows are taken diagonally (row block + column block)
   int tail = 0;                          // MAP: columns mod 4 of a narrow array (1..3): its last lanes get straight-line code too
   int nt = 0;                            // non-temporal load hint: 0 none, 1 arrays read once, 2 all vector loads
   int red_mode = 0;                      // REDUCE: 0 thread-per-output, 1 block-per-output

@@ -472,7 +472,7 @@ void make_signature(GroupPlan* g) {
   std::string s;
   s.reserve(256 + 32 * (g->prog.size() + g->prog1.size()));
   for (int64_t v : {(int64_t)g->kind, (int64_t)g->rank, (int64_t)g->out_dtype, (int64_t)g->out_per_row, (int64_t)g->BX, (int64_t)g->BY,
-                    (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads + 1024 * (int64_t)g->row_iters, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask + (((int64_t)g->tail) << 40), (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
+                    (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads + 1024 * (int64_t)g->row_iters, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask + (((int64_t)g->tail) << 40) + (((int64_t)g->diag) << 44), (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
                     (int64_t)g->red_kept_rank, (int64_t)g->gemv_mode, (int64_t)g->LPR, (int64_t)g->KV, (int64_t)g->mat_group,
                     (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode + 16 * (int64_t)g->scan_vec, (int64_t)g->out_unit, (int64_t)g->groups.size()})
     put(s, v);
@@ -620,6 +620,7 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
   // views): lanes along the columns would read them with a stride.  A 64 x 64 tile of such an
   // operand is loaded along its own contiguous dimension into LDS and read from there transposed.
   g->stage_mask = 0;
+  g->diag = 0;
   if (g->rank >= 2 && R >= 64 && C >= 64 && c->opt_map_rows == 0 && c->opt_map_chunks == 0 && c->opt_map_bx == 0 && c->opt_stage) {
     int staged = 0;
     for (size_t gi = 0; gi < g->groups.size() && gi < 24; ++gi) {
@@ -628,7 +629,8 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
       if (ag.structural_zero[g->rank - 1] || ag.structural_zero[g->rank - 2]) continue;
       if (ag.coef[g->rank - 1] != 1 && ag.coef[g->rank - 2] == 1 && staged < 2) { g->stage_mask |= 1 << gi; ++staged; }
     }
-    if (g->stage_mask) { g->BX = 16; g->BY = 16; g->VR = 4; g->UC = 1; }
+    // (64 columns by 64 or 128 rows: the taller tile reads 512-byte runs of the operand)
+    if (g->stage_mask) { g->BX = 16; g->BY = 16; g->VR = (R >= 128 && c->opt_stage_rows != 64) ? 8 : 4; g->UC = 1; g->diag = c->opt_stage_diag != 0; }
   }
   if (c->opt_map_rows > 0 && g->rank >= 2) g->VR = (int)std::min<int64_t>(c->opt_map_rows, 16);
   if (c->opt_map_chunks > 0) g->UC = (int)std::min<int64_t>(c->opt_map_chunks, 8);

@@ -715,9 +715,18 @@ def test_random_programs_bit_exact_generated_kernels(env, block):
         _run_fuzz_seed(env, seed)
 
 
-def test_transposed_operands_through_lds_tiles(env):
+@pytest.mark.parametrize("stage_rows", [0, 64])
+def test_transposed_operands_through_lds_tiles(env, stage_rows):
+    env[1].set_option("stage_rows", stage_rows)
+    try:
+        _transposed_tile_cases(env, stage_rows)
+    finally:
+        env[1].set_option("stage_rows", 0)
+
+
+def _transposed_tile_cases(env, stage_rows):
     # operands whose contiguous dimension is the row dimension of the iteration space are read through
-    # transposing 64 x 64 LDS tiles: ragged edges, outer dimensions, two staged operands, int32, slices
+    # transposing 64 x 64 (or 128 x 64) LDS tiles: ragged edges, outer dimensions, two staged operands, int32, slices
     gr, ctx, torch = env
     a, b = _rand((257, 130), 181), _rand((130, 257), 182)
     got, ref = run_both(env, lambda xp, a, b: a - xp.transpose(b, (1, 0)) * 2.0, dict(a=a, b=b))
@@ -739,7 +748,7 @@ def test_transposed_operands_through_lds_tiles(env):
     got, ref = run_both(env, lambda xp, i: xp.transpose(i, (1, 0)) * 7 - 3, dict(i=i))
     assert got.dtype == np.int32 and np.array_equal(got, ref)
     plan = (ctx.array(torch.zeros(128, 128, device="cuda")).T * 1.0).plan()
-    assert "tile=64x64" in plan
+    assert ("tile=64x64" if stage_rows == 64 else "tile=128x64") in plan
     ctx.set_option("stage_transposed", 0)
     got2, _ = run_both(env, lambda xp, a, b: a - xp.transpose(b, (1, 0)) * 2.0, dict(a=a, b=b))
     ctx.set_option("stage_transposed", 1)
