@@ -112,7 +112,10 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     slabs (first-stage partial vectors) and rows in flight
  *                     per lane, 8 or 16 (0 = auto)
  *   "nontemporal"     1 (default) = loads of arrays that are read once carry
- *                     the non-temporal hint; 0 = none; 2 = every vector load
+ *                     the non-temporal hint, and so do the vector stores of an
+ *                     output of 2^23 elements or more; 0 = none; 2 = every
+ *                     vector load; 8 = vector stores only; 9 = the loads of 1
+ *                     and every vector store
  *   "gemv_pair"       1 (default) = a contraction A.v whose epilogue result r
  *                     feeds the contraction A^T.r runs with it in one pass
  *                     over A; 0 = two passes

@@ -42,11 +42,11 @@ char access_class(const AccessGroup& ag, int dim) {
 // share stay cacheable.
 bool nontemporal_group(const GroupPlan& g, int group) {
   const AccessGroup& ag = g.groups[group];
-  if (g.nt <= 0 || ag.dtype == GR_I64) return false;
+  if ((g.nt & 7) == 0 || ag.dtype == GR_I64) return false;
   if (g.kind == GroupKind::GEMV) return group == g.mat_group;
   if (g.kind == GroupKind::GEMM) return false;  // operand tiles are re-read by other workgroups: keep them cacheable
   if (access_class(ag, g.rank - 1) != '1') return false;
-  if (g.nt >= 2) return true;
+  if ((g.nt & 7) >= 2) return true;
   if (ag.deltas.size() > 1) return false;
   // read once = the operand follows every outer iteration dimension; one that is broadcast along
   // any of them is read again by other rows or planes and stays cacheable
@@ -470,7 +470,7 @@ void gen_map(Em& e) {
         } else {
           const char* vt = g.out_dtype == GR_F32 ? "f4u" : "i4u";
           e.o << "    { " << vt << " ov; ov[0] = t" << g.results[ri] << "; ov[1] = t" << g.results[ri + 1] << "; ov[2] = t" << g.results[ri + 2]
-              << "; ov[3] = t" << g.results[ri + 3] << "; *(GM " << vt << "*)(po + " << off << ") = ov; }\n";
+              << "; ov[3] = t" << g.results[ri + 3] << "; " << ((g.nt & 8) ? "__builtin_nontemporal_store(ov, (GM " + std::string(vt) + "*)(po + " + off + "))" : "*(GM " + std::string(vt) + "*)(po + " + off + ") = ov") << "; }\n";
         }
         ri += 4;
       }
@@ -698,8 +698,9 @@ void gen_rowred(Em& e) {
       e.o << "    }\n";
       if (final_stage && g.out_dtype != GR_I64) {
         const char* vt = g.out_dtype == GR_F32 ? "f4u" : "i4u";
-        if (guarded) e.o << "    if (row_ok) { if (c + 4 <= C) *(GM " << vt << "*)(po + c) = ov; else { for (int j = 0; j < 4; ++j) if (c + j < C) po[c + j] = ov[j]; } }\n";
-        else e.o << "    if (row_ok) *(GM " << vt << "*)(po + c) = ov;\n";
+        const std::string st = (g.nt & 8) ? "__builtin_nontemporal_store(ov, (GM " + std::string(vt) + "*)(po + c))" : "*(GM " + std::string(vt) + "*)(po + c) = ov";
+        if (guarded) e.o << "    if (row_ok) { if (c + 4 <= C) " << st << "; else { for (int j = 0; j < 4; ++j) if (c + j < C) po[c + j] = ov[j]; } }\n";
+        else e.o << "    if (row_ok) " << st << ";\n";
       }
       e.o << "  }\n";
     }
@@ -1206,7 +1207,8 @@ void gen_scan(Em& e) {
     e.o << "    for (int j = 0; j < 4; ++j) if (c + j < cend) po[c + j] = gr_comb0(base, v[j]);\n";
   else {
     const char* vt = ph.out_dtype == GR_F32 ? "f4u" : "i4u";
-    e.o << "    if (c + 4 <= cend) { " << vt << " ov; for (int j = 0; j < 4; ++j) ov[j] = gr_comb0(base, v[j]); *(GM " << vt << "*)(po + c) = ov; }\n"
+    e.o << "    if (c + 4 <= cend) { " << vt << " ov; for (int j = 0; j < 4; ++j) ov[j] = gr_comb0(base, v[j]); "
+        << ((g.nt & 8) ? "__builtin_nontemporal_store(ov, (GM " + std::string(vt) + "*)(po + c))" : "*(GM " + std::string(vt) + "*)(po + c) = ov") << "; }\n"
            "    else { for (int j = 0; j < 4; ++j) if (c + j < cend) po[c + j] = gr_comb0(base, v[j]); }\n";
   }
   e.o << "    carry = gr_comb0(carry, gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])));\n    buf ^= 1;\n  }\n}\n";
