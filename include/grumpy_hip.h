@@ -127,7 +127,12 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     $GR_CACHE_DIR (default ~/.cache/grumpy_hip) keyed on
  *                     the generated kernel source (and compiler version and
  *                     flags), so another build of the library never reads
- *                     them by mistake; 0 = in-memory cache only
+ *                     them by mistake.  A miss there is looked up in the
+ *                     kernel pack next: the directory "kernel_pack" beside
+ *                     the shared library (or $GR_KERNEL_PACK; empty = none),
+ *                     same file format, written at build time for common
+ *                     sub-graphs, never written at run time.
+ *                     0 = in-memory cache only, no pack
  *   "interp"          1 (default) = a map sub-graph or a row-resident reduction
  *                     sub-graph whose kernel is still in the run-time compiler is
  *                     evaluated by a precompiled byte-code interpreter of the

@@ -5,6 +5,7 @@
 // strides and constants), argument marshalling and launches on the caller's
 // stream, and the materialise entry points (Section 2: the computed node gets
 // its data and is_materialized = true).
+#include <dlfcn.h>
 #include <hip/hip_runtime_api.h>
 #include <hip/hiprtc.h>
 
@@ -126,6 +127,16 @@ static void run_hiprtc(gr_ctx::CompileJob* j) {
 
 static const char kDiskMagic[8] = {'G', 'R', 'C', 'O', '0', '0', '0', '3'};
 
+static std::string cache_file_name(const std::string& key) {
+  uint64_t h = 1469598103934665603ull;  // FNV-1a over a tool tag and the key (the kernel's source text)
+  const std::string tag = std::string("grumpy-hip-3|") + std::to_string(HIP_VERSION) + "|gfx950|O3|";
+  for (unsigned char ch : tag) { h ^= ch; h *= 1099511628211ull; }
+  for (unsigned char ch : key) { h ^= ch; h *= 1099511628211ull; }
+  char name[64];
+  snprintf(name, sizeof name, "/%016llx_%zu.co", (unsigned long long)h, key.size());
+  return name;
+}
+
 static std::string disk_path(gr_ctx* c, const std::string& key) {
   if (!c->opt_disk_cache) return "";
   if (c->cache_dir.empty()) {
@@ -143,13 +154,27 @@ static std::string disk_path(gr_ctx* c, const std::string& key) {
     }
   }
   if (c->cache_dir == "-") return "";
-  uint64_t h = 1469598103934665603ull;  // FNV-1a over a tool tag and the key (the kernel's source text)
-  const std::string tag = std::string("grumpy-hip-3|") + std::to_string(HIP_VERSION) + "|gfx950|O3|";
-  for (unsigned char ch : tag) { h ^= ch; h *= 1099511628211ull; }
-  for (unsigned char ch : key) { h ^= ch; h *= 1099511628211ull; }
-  char name[64];
-  snprintf(name, sizeof name, "/%016llx_%zu.co", (unsigned long long)h, key.size());
-  return c->cache_dir + name;
+  return c->cache_dir + cache_file_name(key);
+}
+
+// The kernel pack: code objects of common sub-graphs (the benchmark programs, plain pointwise
+// operations, reductions, scans and contractions) that the build step compiles ahead of time
+// into the directory `kernel_pack` beside this library (or $GR_KERNEL_PACK).  Same file format
+// and naming as the user's cache, read-only, consulted after it; the stored source text is
+// compared in full, so a pack written by another version of the generator never matches.
+static std::string pack_path(gr_ctx* c, const std::string& key) {
+  if (!c->opt_disk_cache) return "";
+  if (const char* env = getenv("GR_KERNEL_PACK")) return *env ? env + cache_file_name(key) : std::string();
+  static const std::string dir = [] {
+    Dl_info info;
+    if (dladdr((const void*)&cache_file_name, &info) && info.dli_fname) {
+      std::string p = info.dli_fname;
+      size_t slash = p.rfind('/');
+      if (slash != std::string::npos) return p.substr(0, slash) + "/kernel_pack";
+    }
+    return std::string();
+  }();
+  return dir.empty() ? "" : dir + cache_file_name(key);
 }
 
 static bool disk_load(const std::string& path, const std::string& key, std::vector<char>* code) {
@@ -226,7 +251,7 @@ gr_status prepare_group(gr_ctx* c, GroupPlan& g) {
   // structure never picks up a code object written by another build.
   std::string src = generate_source(g);
   std::vector<char> code;
-  if (disk_load(disk_path(c, src), src, &code)) {
+  if (disk_load(disk_path(c, src), src, &code) || disk_load(pack_path(c, src), src, &code)) {
     c->stats.cache_misses++;
     c->stats.disk_hits++;
     std::string name;

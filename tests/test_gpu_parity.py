@@ -1191,6 +1191,7 @@ def test_first_request_runs_while_its_kernel_compiles(tmp_path, monkeypatch):
     import torch
     from paper_1901_03771_amd import lazy as gr
     monkeypatch.setenv("GR_CACHE_DIR", str(tmp_path / "empty_cache"))
+    monkeypatch.setenv("GR_KERNEL_PACK", "")   # and no ahead-of-time pack
     ctx = gr.Context()
     arrays = wl.make_inputs("normalize", **wl.SMALL["normalize"])
     ref = wl.normalize(ora, **{k: ora.array(v) for k, v in arrays.items()}).numpy()

@@ -540,6 +540,7 @@ def test_same_structure_hits_the_kernel_cache(ctx):
 
 def test_disk_cache_round_trip_and_corruption(tmp_path, monkeypatch):
     monkeypatch.setenv("GR_CACHE_DIR", str(tmp_path / "kernels"))
+    monkeypatch.setenv("GR_KERNEL_PACK", "")   # no ahead-of-time pack in this test
 
     def program(c):
         x = c.spec((64, 300))
@@ -567,6 +568,55 @@ def test_disk_cache_round_trip_and_corruption(tmp_path, monkeypatch):
     assert c4.stats()["disk_hits"] == 0
     for c in (c1, c2, c3, c4):
         c.close()
+
+
+def test_kernel_pack_is_read_after_the_user_cache_and_never_written(tmp_path, monkeypatch):
+    # a directory of code objects written by one context serves as the read-only pack of another
+    pack, user = tmp_path / "pack", tmp_path / "user"
+
+    def program(c):
+        x = c.spec((300, 70))
+        return gr.tanh(x) * 3.0 + gr.sum(x, axis=1, keepdims=True)
+
+    monkeypatch.setenv("GR_KERNEL_PACK", "")
+    monkeypatch.setenv("GR_CACHE_DIR", str(pack))
+    c1 = gr.Context(device=-1)
+    program(c1).compile()
+    s1 = c1.stats()
+    assert s1["disk_hits"] == 0 and s1["cache_misses"] >= 1 and s1["compile_ms"] > 0
+    packed = sorted(f.name for f in pack.iterdir())
+    assert len(packed) == s1["cache_misses"]
+    monkeypatch.setenv("GR_KERNEL_PACK", str(pack))
+    monkeypatch.setenv("GR_CACHE_DIR", str(user))
+    c2 = gr.Context(device=-1)
+    program(c2).compile()
+    s2 = c2.stats()
+    assert s2["disk_hits"] == s1["cache_misses"] and s2["compile_ms"] == 0
+    assert not list(user.iterdir()) and sorted(f.name for f in pack.iterdir()) == packed
+    (c2.spec((300, 70)) * 2.0 - 1.0).compile()            # not in the pack: compiled, stored in the user's cache only
+    assert c2.stats()["compile_ms"] > 0 and len(list(user.iterdir())) == 1 and sorted(f.name for f in pack.iterdir()) == packed
+    c3 = gr.Context(device=-1)
+    c3.set_option("disk_cache", 0)                          # switches the pack off as well
+    program(c3).compile()
+    assert c3.stats()["disk_hits"] == 0
+    for c in (c1, c2, c3):
+        c.close()
+
+
+def test_built_kernel_pack_covers_the_benchmark_programs(monkeypatch, tmp_path):
+    from paper_1901_03771_amd import kernel_pack
+    if not os.path.isdir(kernel_pack.PACK_DIR) or not any(f.endswith(".co") for f in os.listdir(kernel_pack.PACK_DIR)):
+        pytest.skip("the kernel pack has not been built")
+    monkeypatch.delenv("GR_KERNEL_PACK", raising=False)
+    monkeypatch.setenv("GR_CACHE_DIR", str(tmp_path / "user"))
+    c = gr.Context(device=-1)
+    X = c.spec((8192, 8192))
+    wl.normalize(gr, X, c.spec((1, 8192)), c.spec((1, 8192)), c.spec((8192,)), c.spec((8192,))).compile()
+    wl.softmax(gr, c.spec((16384, 4096))).compile()
+    gr.sum(c.spec((1 << 24,))).compile()
+    st = c.stats()
+    assert st["compile_ms"] == 0 and st["disk_hits"] == st["cache_misses"] >= 3
+    c.close()
 
 
 def test_async_and_serial_compilation_agree(ctx):
