@@ -715,13 +715,15 @@ def test_random_programs_bit_exact_generated_kernels(env, block):
         _run_fuzz_seed(env, seed)
 
 
-@pytest.mark.parametrize("stage_rows", [0, 64])
-def test_transposed_operands_through_lds_tiles(env, stage_rows):
+@pytest.mark.parametrize("stage_rows,stage_diag", [(0, 1), (64, 1), (0, 0)])
+def test_transposed_operands_through_lds_tiles(env, stage_rows, stage_diag):
     env[1].set_option("stage_rows", stage_rows)
+    env[1].set_option("stage_diag", stage_diag)
     try:
         _transposed_tile_cases(env, stage_rows)
     finally:
         env[1].set_option("stage_rows", 0)
+        env[1].set_option("stage_diag", 1)
 
 
 def _transposed_tile_cases(env, stage_rows):
@@ -747,6 +749,12 @@ def _transposed_tile_cases(env, stage_rows):
     i = np.random.default_rng(186).integers(-1000, 1000, (200, 64)).astype(np.int32)
     got, ref = run_both(env, lambda xp, i: xp.transpose(i, (1, 0)) * 7 - 3, dict(i=i))
     assert got.dtype == np.int32 and np.array_equal(got, ref)
+    # eight and sixteen column blocks (each XCD takes a contiguous range of them), ragged rows
+    for k, shp in enumerate([(512, 300), (1024, 131), (3, 520, 129)]):
+        w = _rand(shp, 187 + k)
+        perm = (1, 0) if len(shp) == 2 else (0, 2, 1)
+        got, ref = run_both(env, lambda xp, w: xp.transpose(w, perm) * 0.5 + 2.0, dict(w=w))
+        assert got.shape == tuple(shp[a] for a in perm) and np.array_equal(got, ref)
     plan = (ctx.array(torch.zeros(128, 128, device="cuda")).T * 1.0).plan()
     assert ("tile=64x64" if stage_rows == 64 else "tile=128x64") in plan
     ctx.set_option("stage_transposed", 0)
