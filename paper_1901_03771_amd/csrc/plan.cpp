@@ -670,12 +670,12 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
   g->root = r;
   g->out_dtype = r->dtype;
   g->nt = (int)c->opt_nontemporal;
-  // An output at least as large as the memory-side cache (256 MiB) is streamed out: its vector
+  // An output of at least three quarters of the memory-side cache (256 MiB) is streamed out: its vector
   // stores carry the non-temporal hint as well (measured on MI355X: normalize 8192^2 93.9 ->
   // 86.7 us).  Smaller outputs stay cacheable for the sub-graph that reads them next (a 64 MiB
   // result that is consumed, or whose buffer is reused, within a few launches is 7-15 % slower
   // with hinted stores).
-  if (g->nt == 1 && r->count() * (r->dtype == GR_I64 ? 8 : 4) >= (256ll << 20)) g->nt |= 8;
+  if (g->nt == 1 && r->count() * (r->dtype == GR_I64 ? 8 : 4) >= (192ll << 20)) g->nt |= 8;
 
   // A root that already has data (the plain copy of an array into another buffer or through a
   // strided destination) is a map that loads it, whatever operation once produced it.
