@@ -352,7 +352,7 @@ void gen_map(Em& e) {
     return s.str();
   };
 
-  // ---- transposed operands: the workgroup's 64 x 64 tile goes through LDS, loaded along the
+  // ---- transposed operands: the workgroup's tile (64 columns by 64 or 128 rows) goes through LDS, loaded along the
   // operand's own contiguous dimension (the rows of the iteration space) ----
   if (g.stage_mask) {
     for (size_t gi = 0; gi < g.groups.size(); ++gi) {

@@ -617,7 +617,7 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
       if ((R % vr == 0 || R >= 16 * vr) && (tiles(vr, 1) >= 1024 || (shifted_rows && tiles(vr, 1) >= 256))) { g->VR = vr; break; }
   }
   // Operands whose contiguous dimension is the row dimension of the iteration space (transposed
-  // views): lanes along the columns would read them with a stride.  A 64 x 64 tile of such an
+  // views): lanes along the columns would read them with a stride.  A tile (64 columns by 64 or 128 rows) of such an
   // operand is loaded along its own contiguous dimension into LDS and read from there transposed.
   g->stage_mask = 0;
   g->diag = 0;
