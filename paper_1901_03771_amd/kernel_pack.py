@@ -60,6 +60,27 @@ def _programs(gr, wl, ctx):
         yield f"matvec {m}x{k}", (lambda m=m, k=k: ctx.spec((m, k)) @ ctx.spec((k,)))
         yield f"vecmat {m}x{k}", (lambda m=m, k=k: ctx.spec((m, k)).T @ ctx.spec((m,)))
     yield "inner product", (lambda: wl.inner_product(gr, ctx.spec((1 << 20,)), ctx.spec((1 << 20,))))
+    # row-resident reductions at common row lengths (lanes per row and positions per lane depend on it)
+    for cols in (64, 256, 1000, 1024, 2048, 4096, 8192):
+        rows = max(64, (1 << 24) // cols)
+        yield f"softmax rows of {cols}", (lambda rows=rows, cols=cols: wl.softmax(gr, ctx.spec((rows, cols))))
+
+        def layernorm(rows=rows, cols=cols):
+            x = ctx.spec((rows, cols))
+            return (x - gr.mean(x, axis=1, keepdims=True)) / gr.sqrt(gr.var(x, axis=1, keepdims=True) + 1e-5)
+        yield f"layernorm rows of {cols}", layernorm
+
+        def l2norm(rows=rows, cols=cols):
+            x = ctx.spec((rows, cols))
+            return x / gr.sqrt(gr.sum(x * x, axis=1, keepdims=True))
+        yield f"l2-normalised rows of {cols}", l2norm
+    # a dense layer: matrix product with bias and activation in the epilogue
+    for m, k, n in ((8192, 512, 512), (65536, 64, 64)):
+        for act in (None, gr.tanh, lambda y: gr.maximum(y, 0)):
+            def dense(m=m, k=k, n=n, act=act):
+                y = ctx.spec((m, k)) @ ctx.spec((k, n)) + ctx.spec((n,))
+                return act(y) if act else y
+            yield f"dense {m}x{k}x{n}", dense
 
 
 def build_pack(verbose: bool = False) -> int:
@@ -98,3 +119,7 @@ def build_pack(verbose: bool = False) -> int:
     if verbose:
         print(f"kernel pack: {n} code objects in {time.time() - t0:.1f} s -> {PACK_DIR}")
     return n
+
+
+if __name__ == "__main__":
+    build_pack(verbose=True)
