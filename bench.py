@@ -144,7 +144,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=100)   # ~10 ms: the GPU idles while the inputs are drawn on the host, then takes a while to run at full speed
     ap.add_argument("--workload", default="normalize", choices=sorted(ARGNAMES))
     ap.add_argument("--sets", type=int, default=3)
     ap.add_argument("--no-extras", action="store_true", help="skip the supplementary configurations and ceilings")
@@ -254,7 +254,9 @@ def main():
                 continue
             ow = Workload(oname, ctx, 3 if size is None else 2, size)
             k = 1000 if (oname == "chain" and size is None) else 50
-            d_ms, _ = time_steps(torch, ow, k, 10)
+            # (60 untimed steps: building the inputs on the host leaves the GPU idle for about a second, and
+            # the first hundred or so launches after that run up to 10 % slower)
+            d_ms, _ = time_steps(torch, ow, k, 60)
             label = oname if size is None else f"{oname}_n2^{size['n'].bit_length() - 1}"
             extras[label + "_GBps"] = round(ow.unique_bytes / (d_ms / k * 1e-3) / 1e9, 1)
             extras[label + "_us_per_step"] = round(d_ms / k * 1e3, 2)
