@@ -24,7 +24,8 @@ __global__ __launch_bounds__(256) void gr_stream_read_kernel(const f4* __restric
   size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
   f4 acc = {0.f, 0.f, 0.f, 0.f};
   if (i + 768 < n16) {
-    f4 a = src[i], b = src[i + 256], c = src[i + 512], d = src[i + 768];
+    f4 a = __builtin_nontemporal_load(&src[i]), b = __builtin_nontemporal_load(&src[i + 256]);
+    f4 c = __builtin_nontemporal_load(&src[i + 512]), d = __builtin_nontemporal_load(&src[i + 768]);
     acc = (a + b) + (c + d);
   } else {
     for (int u = 0; u < 4; ++u) if (i + 256 * u < n16) acc += src[i + 256 * u];
