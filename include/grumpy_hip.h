@@ -113,7 +113,8 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     per lane, 8 or 16 (0 = auto)
  *   "nontemporal"     1 (default) = loads of arrays that are read once carry
  *                     the non-temporal hint, and so do the vector stores of an
- *                     output of 192 MiB or more (except in kernels that read a
+ *                     requested value of 192 MiB or more (not of intermediate
+ *                     results of the request; except in kernels that read a
  *                     transposed operand through LDS tiles when output rows
  *                     are not 64-byte aligned); 0 = none; 2 = every
  *                     vector load; 8 = vector stores only; 9 = the loads of 1

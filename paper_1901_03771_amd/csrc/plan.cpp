@@ -679,7 +679,9 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
   // 86.7 us).  Smaller outputs stay cacheable for the sub-graph that reads them next (a 64 MiB
   // result that is consumed, or whose buffer is reused, within a few launches is 7-15 % slower
   // with hinted stores).
-  if (g->nt == 1 && r->count() * (r->dtype == GR_I64 ? 8 : 4) >= (192ll << 20)) g->nt |= 8;
+  // Only the value the request asked for: an intermediate result is read by the next sub-graph
+  // of the same request at once.
+  if (g->nt == 1 && r == pl.root && r->count() * (r->dtype == GR_I64 ? 8 : 4) >= (192ll << 20)) g->nt |= 8;
 
   // A root that already has data (the plain copy of an array into another buffer or through a
   // strided destination) is a map that loads it, whatever operation once produced it.
