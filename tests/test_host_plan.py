@@ -530,6 +530,23 @@ def test_rowred_and_dot_cases_compile(ctx):
     wl.listing1(gr, ctx.spec((10, 20), gr.GR_I32), ctx.spec((20,), gr.GR_I32)).compile()
 
 
+def test_streaming_store_hint_rule(ctx):
+    hint = "__builtin_nontemporal_store"
+    big, small = ctx.spec((8192, 8192)), ctx.spec((1024, 1024))
+    assert hint in (big * 2.0).source(0) and hint not in (small * 2.0).source(0)
+    assert hint in wl.softmax(gr, ctx.spec((16384, 4096))).source(0)
+    # an intermediate result of the same request keeps plain stores; the requested value is streamed
+    out = gr.cumsum(big, 1) * 2.0
+    assert hint not in out.source(0) and hint in out.source(1)
+    # a transposed operand read through LDS tiles: only where output rows start on 64-byte boundaries
+    assert hint in (big.T * 1.0).source(0) and hint not in (ctx.spec((8191, 8191)).T * 1.0).source(0)
+    ctx.set_option("nontemporal", 0)
+    assert hint not in (big * 3.0).source(0) and "__builtin_nontemporal_load" not in (big * 3.0).source(0)
+    ctx.set_option("nontemporal", 9)
+    assert hint in (small * 3.0).source(0)
+    ctx.set_option("nontemporal", 1)
+
+
 def test_same_structure_hits_the_kernel_cache(ctx):
     (ctx.spec((64, 300)) * 2.0 + 1.0).compile()
     s0 = ctx.stats()
