@@ -30,6 +30,20 @@ def _programs(gr, wl, ctx):
             def thunk(prog=prog, sh=shapes[name](sizes)):
                 return prog(gr, **{k: ctx.spec(s) for k, s in sh.items()})
             yield f"{name}/{tag}", thunk
+    # the streamed sizes of the two pointwise chains, the paper's small listings
+    yield "chain 2^27", (lambda: wl.chain(gr, ctx.spec((1 << 27,)), ctx.spec((1 << 27,))))
+    yield "blackscholes 2^26", (lambda: wl.blackscholes(gr, ctx.spec((1 << 26,)), ctx.spec((1 << 26,)), ctx.spec((1 << 26,))))
+    for n in (1 << 26, 1 << 16):
+        yield f"listing 1 {n}", (lambda n=n: wl.listing1(gr, ctx.spec((n,), gr.GR_I32), ctx.spec((n,), gr.GR_I32)))
+    yield "listing 2", (lambda: wl.mnist(gr, ctx.spec((200, 10)), ctx.spec((200,)), ctx.spec((10,))))
+    for n in (8192, 1024):
+        yield f"jacobi sweep {n}", (lambda n=n: wl.jacobi_sweep(gr, ctx.spec((n, n))))
+    # 32-bit integers: pointwise, reductions (sums widen to 64 bits), scans
+    for shp in ((1 << 26,), (1 << 16,), (4096, 4096)):
+        yield f"i32 a*3+b {shp}", (lambda shp=shp: ctx.spec(shp, gr.GR_I32) * 3 + ctx.spec(shp, gr.GR_I32))
+        for op in ("sum", "max", "min"):
+            yield f"i32 {op} {shp}", (lambda op=op, shp=shp: gr.reduce(op, ctx.spec(shp, gr.GR_I32), None, False))
+        yield f"i32 cumsum {shp}", (lambda shp=shp: gr.cumsum(ctx.spec(shp, gr.GR_I32), len(shp) - 1))
     # plain pointwise operations, large (streamed stores) and small, one and two dimensions
     unary = dict(neg=lambda x: -x, abs=abs, exp=gr.exp, log=gr.log, sqrt=gr.sqrt, tanh=gr.tanh, square=lambda x: x * x)
     binary = dict(add=lambda x, y: x + y, sub=lambda x, y: x - y, mul=lambda x, y: x * y, div=lambda x, y: x / y,
