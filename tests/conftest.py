@@ -31,3 +31,21 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    # how many elements of each reduction comparison passed the strict per-element bar and how many
+    # only the bar against the caller's cancellation scale (sum|terms|)
+    try:
+        from helpers import SCALE_REPORT
+    except Exception:
+        return
+    if not SCALE_REPORT:
+        return
+    total = sum(n for _, n, _ in SCALE_REPORT)
+    needed = sum(k for _, _, k in SCALE_REPORT)
+    terminalreporter.write_line(f"reduction comparisons: {len(SCALE_REPORT)} arrays, {total} elements, "
+                                f"{total - needed} within 1e-5 of the oracle per element, {needed} only within 1e-5 of sum|terms|")
+    for what, n, k in SCALE_REPORT:
+        if k:
+            terminalreporter.write_line(f"  {what}: {k} of {n} needed the cancellation scale")
