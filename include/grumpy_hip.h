@@ -296,6 +296,35 @@ gr_status gr_materialize(gr_ctx* ctx, gr_array a);
  * (a view stays a view of its base) and no reference to `dptr` is kept. */
 gr_status gr_materialize_into(gr_ctx* ctx, gr_array a, void* dptr, size_t bytes);
 
+/* gr_materialize_into for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result and
+ * errors as gr_materialize_into, and the same kernels; the call itself allocates and frees no
+ * device memory and calls no allocating library routine (the context's allocator callbacks are
+ * not called for anything the request needs).
+ *   - Everything the request needs beyond its leaves and `dptr` -- the stored results of
+ *     earlier sub-graphs of the request, the first-stage partial results of two-stage kernels
+ *     (reductions split over workgroups, chunked scans, column-accumulate and one-pass
+ *     contractions, split-K matrix products) -- lives in one static device array of
+ *     gr_static_scratch_bytes() = 16 MiB inside the library (every GPU the library runs on
+ *     holds its own copy until the process ends).  A request that needs more is refused with
+ *     GR_ERR_OOM before anything is launched; the message names both sizes.
+ *   - Every kernel of the request must already be loaded on this context (loading a code
+ *     object allocates): call gr_plan_compile(ctx, a), or evaluate a request of the same
+ *     structure with gr_materialize / gr_materialize_into, once beforehand.  Otherwise
+ *     GR_ERR_UNSUPPORTED, nothing launched.  Option "profile" is ignored by this call.
+ *   - Results of earlier sub-graphs exist only while the request runs: after the call those
+ *     arrays are unevaluated again (and can be evaluated later); only `a` keeps its value, in
+ *     `dptr`, as with gr_materialize_into.  Arrays that lose their last reference during the
+ *     call are released as usual (the default pool keeps their blocks; an installed free
+ *     callback is called for them).
+ *   - All calls on one GPU share that GPU's array, which keeps the previous call's contents;
+ *     nothing in it needs to start at zero (every partial result is written before it is
+ *     read).  Calls that overlap on one GPU -- two contexts, or two streams -- race. */
+gr_status gr_materialize_into_static(gr_ctx* ctx, gr_array a, void* dptr, size_t bytes);
+
+/* Size in bytes of the static device array behind gr_materialize_into_static. */
+gr_status gr_static_scratch_bytes(size_t* bytes);
+
 /* Slice assignment dst[...] = value with NumPy semantics (Listing 6 of the
  * paper: center[:] = 0.2*(center+north+east+west+south)).  `dst` must be a
  * materialised array or a slice/transpose view of one (the storage is

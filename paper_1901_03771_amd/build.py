@@ -11,7 +11,7 @@ import sysconfig
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgrumpy_hip.so")
-SOURCES = ["recorder.cpp", "plan.cpp", "codegen.cpp", "runtime.cpp", "interp.cpp", "plancache.cpp", "stream_kernels.hip", "interp_kernel.hip"]
+SOURCES = ["recorder.cpp", "plan.cpp", "codegen.cpp", "runtime.cpp", "interp.cpp", "plancache.cpp", "stream_kernels.hip", "interp_kernel.hip", "static_scratch.hip"]
 
 
 def build(verbose: bool = False, pack: bool = True) -> str:

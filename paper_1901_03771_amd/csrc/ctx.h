@@ -88,6 +88,12 @@ struct gr_ctx {
   void* workspace = nullptr;
   size_t workspace_bytes = 0;
 
+  // gr_materialize_into_static: this device's copy of the library's static device array, and the
+  // part of it the running request has taken (static_mode is set for the duration of such a call)
+  unsigned char* static_base = nullptr;
+  size_t static_cap = 0, static_used = 0;
+  bool static_mode = false;
+
   // profiling
   struct ProfRec {
     std::string name;
@@ -128,5 +134,8 @@ gr_status collect_all_jobs(gr_ctx* c, bool load);
 gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out);
 gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr, void* pair_out_ptr);
 gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool check_alias);
+
+// static_scratch.hip
+gr_status static_scratch_attach(gr_ctx* c);
 
 }  // namespace gr

@@ -55,8 +55,21 @@ static void pool_trim(gr_ctx* c) {
   c->pool_free.clear();
 }
 
+// Inside the static device array of gr_materialize_into_static?
+static inline bool in_static(const gr_ctx* c, const void* p) {
+  return c->static_base && (const unsigned char*)p >= c->static_base && (const unsigned char*)p < c->static_base + c->static_cap;
+}
+
 void* ctx_alloc(gr_ctx* c, size_t bytes) {
   if (bytes == 0) bytes = 256;
+  if (c->static_mode) {
+    // a request that must not allocate: pieces of the static array, handed out once per call
+    size_t rounded = (bytes + 255) & ~(size_t)255;
+    if (rounded > c->static_cap - c->static_used) return nullptr;
+    void* p = c->static_base + c->static_used;
+    c->static_used += rounded;
+    return p;
+  }
   c->stats.bytes_allocated += bytes;
   if (c->alloc_fn) return c->alloc_fn(bytes, c->alloc_user);
   if (c->device < 0) {
@@ -87,7 +100,7 @@ void* ctx_alloc(gr_ctx* c, size_t bytes) {
 }
 
 void ctx_free(gr_ctx* c, void* p, size_t bytes) {
-  if (!p) return;
+  if (!p || in_static(c, p)) return;
   if (bytes == 0) bytes = 256;
   if (c->free_fn) { c->free_fn(p, c->alloc_user); return; }
   if (c->device < 0) return;
@@ -345,7 +358,8 @@ static gr_status launch(gr_ctx* c, hipFunction_t fn, const std::string& name, in
   size_t sz = args.size() * sizeof(uint64_t);
   void* extra[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, args.data(), HIP_LAUNCH_PARAM_BUFFER_SIZE, &sz, HIP_LAUNCH_PARAM_END};
   hipEvent_t e0 = nullptr, e1 = nullptr;
-  if (c->opt_profile) {
+  const bool profile = c->opt_profile && !c->static_mode;  // (creating an event allocates)
+  if (profile) {
     for (hipEvent_t* ev : {&e0, &e1}) {
       if (!c->event_pool.empty()) { *ev = c->event_pool.back(); c->event_pool.pop_back(); }
       else GR_HIP(c, hipEventCreate(ev));
@@ -353,7 +367,7 @@ static gr_status launch(gr_ctx* c, hipFunction_t fn, const std::string& name, in
     GR_HIP(c, hipEventRecord(e0, c->stream));
   }
   GR_HIP(c, hipModuleLaunchKernel(fn, (unsigned)grid, 1, 1, 256, 1, 1, 0, c->stream, nullptr, extra));
-  if (c->opt_profile) {
+  if (profile) {
     GR_HIP(c, hipEventRecord(e1, c->stream));
     c->prof.push_back({name, e0, e1});
   }
@@ -385,12 +399,43 @@ static gr_status fill_args(gr_ctx* c, const GroupPlan& g, const ArgLayout& L, vo
   return GR_OK;
 }
 
-static gr_status ensure_workspace(gr_ctx* c, size_t need) {
-  if (need <= c->workspace_bytes) return GR_OK;
-  if (c->workspace) ctx_free(c, c->workspace, c->workspace_bytes);
-  c->workspace = ctx_alloc(c, need);
-  c->workspace_bytes = c->workspace ? need : 0;
-  if (!c->workspace) return fail(c, GR_ERR_OOM, "workspace allocation failed");
+// Device memory a sub-graph's kernels need beyond inputs and output: the first-stage partial
+// results of two-stage kernels.
+static size_t workspace_need(const GroupPlan& g) {
+  switch (g.kind) {
+    case GroupKind::REDUCE: return g.slabs > 1 && g.red_out > 0 ? (size_t)g.slabs * (size_t)g.red_out * itemsize(g.out_dtype) : 0;
+    case GroupKind::SCAN: {
+      int64_t total = 1;
+      for (int k2 = 0; k2 < g.rank; ++k2) total *= g.dims[k2];
+      return g.scan_nchunk > 1 && total > 0 ? (size_t)g.red_out * (size_t)g.scan_nchunk * itemsize(g.out_dtype) : 0;
+    }
+    case GroupKind::GEMM: return g.slabs > 1 && g.M > 0 && g.N > 0 ? (size_t)g.slabs * (size_t)g.M * (size_t)g.N * sizeof(float) : 0;
+    case GroupKind::GEMV:
+      if (g.M == 0) return 0;
+      if (g.gemv_mode == 2) return (size_t)g.slabs * (size_t)g.K * sizeof(float);
+      if (g.gemv_mode == 1) return (size_t)g.slabs * (size_t)g.M * sizeof(float);
+      return 0;
+    default: return 0;
+  }
+}
+
+// Returns the workspace of `g` (NULL if it needs none): the context's own, grown on demand, or,
+// for a request that must not allocate, a piece of the static array.
+static gr_status get_workspace(gr_ctx* c, const GroupPlan& g, void** ws) {
+  *ws = nullptr;
+  const size_t need = workspace_need(g);
+  if (need == 0) return GR_OK;
+  if (c->static_mode) {
+    *ws = ctx_alloc(c, need);
+    return *ws ? GR_OK : fail(c, GR_ERR_OOM, "the static scratch array is too small for this request's partial results");
+  }
+  if (need > c->workspace_bytes) {
+    if (c->workspace) ctx_free(c, c->workspace, c->workspace_bytes);
+    c->workspace = ctx_alloc(c, need);
+    c->workspace_bytes = c->workspace ? need : 0;
+    if (!c->workspace) return fail(c, GR_ERR_OOM, "workspace allocation failed");
+  }
+  *ws = c->workspace;
   return GR_OK;
 }
 
@@ -401,6 +446,7 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
   std::vector<uint64_t> s(L.total + (g.pair ? L2.total : 0), 0);
   gr_status fst = fill_args(c, g, L, out_ptr, s.data());
   if (fst != GR_OK) return fst;
+  void* ws = nullptr;
   int64_t total = 1;
   for (int k2 = 0; k2 < g.rank; ++k2) total *= g.dims[k2];
   switch (g.kind) {
@@ -428,9 +474,9 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       s[L.extra + 1] = (uint64_t)g.red_len;
       s[L.extra + 3] = (uint64_t)g.slabs;
       if (g.slabs > 1) {
-        gr_status wst = ensure_workspace(c, (size_t)g.slabs * (size_t)g.red_out * itemsize(g.out_dtype));
+        gr_status wst = get_workspace(c, g, &ws);
         if (wst != GR_OK) return wst;
-        s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+        s[L.extra + 2] = (uint64_t)(uintptr_t)ws;
       }
       int64_t units = g.red_mode == 0 ? ((g.red_vec ? g.red_out / 4 : g.red_out) + 255) / 256 : g.red_out;
       gr_status st = launch(c, k->fn, k->name, units * g.slabs, s);
@@ -447,9 +493,9 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
         // a thread per (line, chunk)
         const int64_t blocks = ((g.scan_vec ? g.red_out / 4 : g.red_out) * g.scan_nchunk + 255) / 256;
         if (g.scan_nchunk > 1) {
-          gr_status wst = ensure_workspace(c, (size_t)g.red_out * (size_t)g.scan_nchunk * itemsize(g.out_dtype));
+          gr_status wst = get_workspace(c, g, &ws);
           if (wst != GR_OK) return wst;
-          s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+          s[L.extra + 2] = (uint64_t)(uintptr_t)ws;
           gr_status st = launch(c, k->fn2, "gr_scan_sums", blocks, s);
           if (st != GR_OK) return st;
           st = launch(c, k->fn3, "gr_scan_offsets", g.red_out, s);
@@ -458,9 +504,9 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
         return launch(c, k->fn, k->name, blocks, s);
       }
       if (g.scan_nchunk > 1) {
-        gr_status wst = ensure_workspace(c, (size_t)g.red_out * (size_t)g.scan_nchunk * itemsize(g.out_dtype));
+        gr_status wst = get_workspace(c, g, &ws);
         if (wst != GR_OK) return wst;
-        s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+        s[L.extra + 2] = (uint64_t)(uintptr_t)ws;
         gr_status st = launch(c, k->fn2, "gr_scan_sums", g.red_out * g.scan_nchunk, s);
         if (st != GR_OK) return st;
         st = launch(c, k->fn3, "gr_scan_offsets", g.red_out, s);
@@ -481,9 +527,9 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       s[L.extra + 3] = (uint64_t)nsplit;
       s[L.ocoef + 1] = (uint64_t)std::max<int64_t>(kch, 1);
       if (nsplit > 1) {
-        gr_status wst = ensure_workspace(c, (size_t)nsplit * (size_t)g.M * (size_t)g.N * sizeof(float));
+        gr_status wst = get_workspace(c, g, &ws);
         if (wst != GR_OK) return wst;
-        s[L.ocoef] = (uint64_t)(uintptr_t)c->workspace;
+        s[L.ocoef] = (uint64_t)(uintptr_t)ws;
       }
       gr_status st = launch(c, k->fn, k->name, tiles * nsplit, s);
       if (st != GR_OK || nsplit <= 1) return st;
@@ -499,14 +545,14 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
         const GroupPlan& p = *g.pair;
         fst = fill_args(c, p, L2, pair_out_ptr, s.data() + L.total, g.root, out_ptr);
         if (fst != GR_OK) return fst;
-        gr_status wst = ensure_workspace(c, (size_t)g.slabs * (size_t)g.K * sizeof(float));
+        gr_status wst = get_workspace(c, g, &ws);
         if (wst != GR_OK) return wst;
-        s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+        s[L.extra + 2] = (uint64_t)(uintptr_t)ws;
         s[L.extra + 3] = (uint64_t)g.slabs;
         uint64_t* s2 = s.data() + L.total;
         s2[L2.extra] = (uint64_t)p.M;
         s2[L2.extra + 1] = (uint64_t)p.K;
-        s2[L2.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+        s2[L2.extra + 2] = (uint64_t)(uintptr_t)ws;
         s2[L2.extra + 3] = (uint64_t)g.slabs;
         gr_status st = launch(c, k->fn, k->name, g.slabs, s);
         if (st != GR_OK) return st;
@@ -517,9 +563,9 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
         int64_t grid = std::min<int64_t>((g.M + rpb - 1) / rpb, 256 * 16);
         return launch(c, k->fn, k->name, grid, s);
       }
-      gr_status wst = ensure_workspace(c, (size_t)g.slabs * (size_t)g.M * sizeof(float));
+      gr_status wst = get_workspace(c, g, &ws);
       if (wst != GR_OK) return wst;
-      s[L.extra + 2] = (uint64_t)(uintptr_t)c->workspace;
+      s[L.extra + 2] = (uint64_t)(uintptr_t)ws;
       s[L.extra + 3] = (uint64_t)g.slabs;
       int64_t ncb = (g.M + (int64_t)g.BX * 4 - 1) / ((int64_t)g.BX * 4);
       gr_status st = launch(c, k->fn, k->name, ncb * g.slabs, s);
@@ -551,6 +597,21 @@ static bool has_storage(const Node* n) {
   return true;
 }
 
+// Results of earlier sub-graphs that a non-allocating request stored in the static array exist
+// only for the duration of that request (the next call overwrites them): their nodes go back to
+// being unevaluated, with their inputs, and can be evaluated again later.
+static void static_unbind(gr_ctx* c, Plan* plan) {
+  if (!c->static_mode) return;
+  for (auto& gp : plan->groups)
+    for (Node* r : {gp->root, gp->pair ? gp->pair->root : (Node*)nullptr}) {
+      if (!r || !r->materialized || !in_static(c, r->data)) continue;
+      r->data = nullptr;
+      r->owns_data = false;
+      r->alloc_bytes = 0;
+      if (r->count() > 0) r->materialized = false;  // (an empty array needs no storage)
+    }
+}
+
 gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool check_alias) {
   if (c->device < 0 && !c->opt_dry_run) return fail(c, GR_ERR_NODEVICE, "context has no device");
   if (user_out && check_alias) {
@@ -566,10 +627,32 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
         }
       }
   }
-  c->stats.materialize_calls++;
   static gr_ctx::Kernel dry_kernel;  // stands for any kernel in a dry run that does not compile
   const bool no_compile = c->device < 0 && c->opt_dry_run >= 2;
+  if (c->static_mode) {
+    // A request that must not allocate: checked in full before the first launch.  Every kernel
+    // has to be loaded already (loading a code object allocates device memory), and the stored
+    // results of earlier sub-graphs plus the partial results of two-stage kernels have to fit
+    // the static array.
+    size_t need = 0;
+    for (auto& gp : plan->groups) {
+      if (!no_compile && !c->cache.count(gp->signature))
+        return fail(c, GR_ERR_UNSUPPORTED, "materialize_into_static: a kernel of this request is not loaded yet; call gr_plan_compile "
+                                           "(or evaluate a request of the same structure with gr_materialize_into) once first");
+      for (const Node* r : {(const Node*)gp->root, gp->pair ? (const Node*)gp->pair->root : nullptr}) {
+        if (!r || (r == root && user_out)) continue;
+        size_t nb = (size_t)r->count() * itemsize(r->dtype);
+        need += ((nb ? nb : 256) + 255) & ~(size_t)255;
+      }
+      need += (workspace_need(*gp) + 255) & ~(size_t)255;
+    }
+    if (need > c->static_cap)
+      return fail(c, GR_ERR_OOM, "materialize_into_static: the request needs " + std::to_string(need) + " bytes for intermediate and partial results; "
+                                 "the static scratch array holds " + std::to_string(c->static_cap));
+  }
+  c->stats.materialize_calls++;
   for (auto& gp : plan->groups) {
+    if (c->static_mode) break;
     if (no_compile || (c->opt_interp >= 2 && (gp->kind == GroupKind::MAP || gp->kind == GroupKind::ROWRED))) continue;  // no kernel wanted (yet)
     gr_status pst = prepare_group(c, *gp);
     if (pst != GR_OK) return pst;
@@ -580,11 +663,11 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
     // A map sub-graph whose kernel is still in the compiler runs through the byte-code
     // interpreter instead of waiting; the job stays pending and a later request collects it.
     // (option "interp" = 2: every map sub-graph the interpreter covers, compiled or not)
-    const bool try_interp = (g.kind == GroupKind::MAP || g.kind == GroupKind::ROWRED) && !g.pair &&
+    const bool try_interp = (g.kind == GroupKind::MAP || g.kind == GroupKind::ROWRED) && !g.pair && !c->static_mode &&
                             (c->opt_interp >= 2 || (c->opt_interp == 1 && still_compiling(c, g)));
     if (no_compile) k = &dry_kernel;
     gr_status st = (try_interp || no_compile) ? GR_OK : compile_group(c, g, &k);
-    if (st != GR_OK) return st;
+    if (st != GR_OK) { static_unbind(c, plan); return st; }
     // output buffers: the caller's for the requested root, the allocator's otherwise
     Node* roots[2] = {g.root, g.pair ? g.pair->root : nullptr};
     void* outs[2] = {nullptr, nullptr};
@@ -595,7 +678,7 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
       if (roots[q] == root && user_out) outs[q] = user_out;
       else {
         outs[q] = ctx_alloc(c, nbytes[q]);
-        if (!outs[q]) { if (q == 1 && own[0]) ctx_free(c, outs[0], nbytes[0]); return fail(c, GR_ERR_OOM, "allocator returned NULL"); }
+        if (!outs[q]) { if (q == 1 && own[0]) ctx_free(c, outs[0], nbytes[0]); static_unbind(c, plan); return fail(c, GR_ERR_OOM, "allocator returned NULL"); }
         own[q] = true;
       }
     }
@@ -623,6 +706,7 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
     }
     if (st != GR_OK) {
       for (int q = 0; q < 2; ++q) if (own[q]) ctx_free(c, outs[q], nbytes[q]);
+      static_unbind(c, plan);
       return st;
     }
     c->stats.groups_executed += g.pair ? 2 : 1;
@@ -653,12 +737,13 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
   // The plan's marks are cleared while every node it names is still alive: releasing the
   // predecessors below may free intermediate roots that nothing else refers to.
   clear_planned(plan);
+  static_unbind(c, plan);
   // Predecessors of materialised nodes are no longer needed.  Roots are visited in execution
   // (topological) order: dropping a root's inputs can only free nodes upstream of it, which
   // includes earlier roots that nothing else refers to, never a root still to be visited.
   for (auto& gp : plan->groups) {
     if (gp->root->materialized) drop_inputs(c, gp->root);  // (a view keeps its base)
-    if (gp->pair) drop_inputs(c, gp->pair->root);
+    if (gp->pair && gp->pair->root->materialized) drop_inputs(c, gp->pair->root);
   }
   return GR_OK;
 }
@@ -684,6 +769,8 @@ gr_status gr_ctx_create(gr_ctx** out, int device, void* hip_stream) {
     }
     e = hipSetDevice(device);
     if (e != hipSuccess) { delete c; return fail(nullptr, GR_ERR_HIP, "hipSetDevice: " + hip_err(e)); }
+    gr_status sst = static_scratch_attach(c);  // this device's copy of the static array (gr_materialize_into_static)
+    if (sst != GR_OK) { delete c; return sst; }
   }
   *out = c;
   return GR_OK;

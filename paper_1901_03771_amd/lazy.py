@@ -36,7 +36,7 @@ STATUS = {0: "GR_OK", 1: "GR_ERR_HANDLE", 2: "GR_ERR_SHAPE", 3: "GR_ERR_DTYPE", 
 SYMBOLS = [
     "gr_ctx_create", "gr_ctx_destroy", "gr_ctx_set_stream", "gr_ctx_set_allocator", "gr_ctx_set_option", "gr_sync",
     "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose", "gr_reshape",
-    "gr_reduce", "gr_scan", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_assign", "gr_ndim", "gr_shape", "gr_dtype_of",
+    "gr_reduce", "gr_scan", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_materialize_into_static", "gr_static_scratch_bytes", "gr_assign", "gr_ndim", "gr_shape", "gr_dtype_of",
     "gr_is_materialized", "gr_data_ptr", "gr_retain", "gr_release", "gr_plan_describe", "gr_plan_source",
     "gr_plan_compile", "gr_compile_wait", "gr_stats", "gr_profile_reset", "gr_profile_read", "gr_stream_copy", "gr_stream_read",
 ]
@@ -88,6 +88,7 @@ def lib():
         "gr_reduce": [P, I, U64, PP(I), I, I, PP(U64)], "gr_dot": [P, U64, U64, PP(U64)],
         "gr_scan": [P, I, U64, I, PP(U64)],
         "gr_materialize": [P, U64], "gr_assign": [P, U64, U64], "gr_materialize_into": [P, U64, P, SZ],
+        "gr_materialize_into_static": [P, U64, P, SZ], "gr_static_scratch_bytes": [PP(SZ)],
         "gr_ndim": [P, U64, PP(I)], "gr_shape": [P, U64, PP(I64)], "gr_dtype_of": [P, U64, PP(I)],
         "gr_is_materialized": [P, U64, PP(I)], "gr_data_ptr": [P, U64, PP(P), PP(I64)],
         "gr_retain": [P, U64], "gr_release": [P, U64],
@@ -166,6 +167,9 @@ class Context:
     def check(self, st: int):
         if st:
             raise GrError(st, lib().gr_last_error(self._p).decode())
+
+    def last_error(self) -> str:
+        return lib().gr_last_error(self._p).decode()
 
     def set_allocator(self, alloc, free):
         """Installs Python callables alloc(nbytes) -> device address or None, free(address) as the
@@ -370,6 +374,13 @@ class _ArrayMethods:
     # -- materialisation --------------------------------------------------------
     def materialize_into(self, t) -> "Array":
         st = _lib.gr_materialize_into(self.ctx._p, self.h, t.data_ptr(), t.numel() * t.element_size())
+        if st:
+            self.ctx.check(st)
+        return self
+
+    def materialize_into_static(self, t) -> "Array":
+        """materialize_into for callers that must not allocate device memory (gr_materialize_into_static)."""
+        st = _lib.gr_materialize_into_static(self.ctx._p, self.h, t.data_ptr(), t.numel() * t.element_size())
         if st:
             self.ctx.check(st)
         return self
