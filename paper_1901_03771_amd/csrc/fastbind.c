@@ -19,7 +19,9 @@ typedef struct {
   PyObject_HEAD
   PyObject* ctx;   /* the binding's Context object (attribute _addr: address of the gr_ctx, 0 once closed) */
   unsigned long long h;
-  PyObject* owner; /* whatever keeps a leaf's device memory alive */
+  PyObject* owner; /* whatever keeps alive the device memory of the leaves this node still reads: a leaf's
+                      tensor, or a tuple of the operands' owners */
+  char view;       /* a slice or transpose: it reads its base's storage also once evaluated */
 } ArrayObject;
 
 static PyTypeObject ArrayBase_Type;
@@ -32,6 +34,9 @@ static __typeof__(&gr_transpose) p_transpose;
 static __typeof__(&gr_dot) p_dot;
 static __typeof__(&gr_assign) p_assign;
 static __typeof__(&gr_materialize) p_materialize;
+static __typeof__(&gr_materialize_into) p_materialize_into;
+static __typeof__(&gr_materialize_into_static) p_materialize_into_static;
+static __typeof__(&gr_is_materialized) p_is_materialized;
 static __typeof__(&gr_release) p_release;
 static __typeof__(&gr_reduce) p_reduce;
 static __typeof__(&gr_ndim) p_ndim;
@@ -67,8 +72,23 @@ static PyObject* raise_status(PyObject* ctx, int st) {
   return NULL;
 }
 
-static PyObject* new_array(PyTypeObject* type, PyObject* ctx, unsigned long long h) {
+/* The recorded DAG outlives the handles of its leaves (z = ctx.array(tensor) * 2 drops the leaf's handle at
+ * once), so every result carries what its operands carry: one owner as it is, two different ones as a pair. */
+static PyObject* merged_owner(PyObject* a, PyObject* b) {
+  if (a == Py_None) a = NULL;
+  if (b == Py_None) b = NULL;
+  if (!a) { Py_XINCREF(b); return b; }
+  if (!b || a == b) { Py_INCREF(a); return a; }
+  return PyTuple_Pack(2, a, b);
+}
+
+static PyObject* new_array(PyTypeObject* type, PyObject* ctx, unsigned long long h, PyObject* owner_a, PyObject* owner_b, int view) {
   ArrayObject* a = (ArrayObject*)type->tp_alloc(type, 0);
+  PyObject* owner = NULL;
+  if (a && (owner_a || owner_b)) {
+    owner = merged_owner(owner_a, owner_b);
+    if (!owner && PyErr_Occurred()) { Py_DECREF(a); a = NULL; }
+  }
   if (!a) {
     gr_ctx* c = ctx_of(ctx);
     if (c) p_release(c, h); else PyErr_Clear();
@@ -77,7 +97,8 @@ static PyObject* new_array(PyTypeObject* type, PyObject* ctx, unsigned long long
   Py_INCREF(ctx);
   a->ctx = ctx;
   a->h = h;
-  a->owner = NULL;
+  a->owner = owner;
+  a->view = (char)view;
   return (PyObject*)a;
 }
 
@@ -141,7 +162,7 @@ static PyObject* do_binary(int op, PyObject* a, PyObject* b) {
       st = p_binary_scalar(c, (gr_op)op, x->h, v, is_int, 0, &out);
     }
     if (st) return raise_status(x->ctx, st);
-    return new_array(Py_TYPE(a), x->ctx, out);
+    return new_array(Py_TYPE(a), x->ctx, out, x->owner, IS_ARRAY(b) ? ((ArrayObject*)b)->owner : NULL, 0);
   }
   if (IS_ARRAY(b)) {
     ArrayObject* y = (ArrayObject*)b;
@@ -151,7 +172,7 @@ static PyObject* do_binary(int op, PyObject* a, PyObject* b) {
     if (!c) return NULL;
     st = p_binary_scalar(c, (gr_op)op, y->h, v, is_int, 1, &out);
     if (st) return raise_status(y->ctx, st);
-    return new_array(Py_TYPE(b), y->ctx, out);
+    return new_array(Py_TYPE(b), y->ctx, out, y->owner, NULL, 0);
   }
   return PyObject_CallFunction(hook_binary, "iOO", op, a, b);
 }
@@ -164,7 +185,7 @@ static PyObject* do_unary(int op, PyObject* a) {
   gr_array out = 0;
   int st = p_unary(c, (gr_op)op, x->h, &out);
   if (st) return raise_status(x->ctx, st);
-  return new_array(Py_TYPE(a), x->ctx, out);
+  return new_array(Py_TYPE(a), x->ctx, out, x->owner, NULL, 0);
 }
 
 static PyObject* nb_add(PyObject* a, PyObject* b) { return do_binary(GR_ADD, a, b); }
@@ -192,7 +213,7 @@ static PyObject* nb_matmul(PyObject* a, PyObject* b) {
   gr_array out = 0;
   int st = p_dot(c, x->h, y->h, &out);
   if (st) return raise_status(x->ctx, st);
-  return new_array(Py_TYPE(a), x->ctx, out);
+  return new_array(Py_TYPE(a), x->ctx, out, x->owner, y->owner, 0);
 }
 
 /* Index key -> gr_slice arguments.  1 = parsed, 0 = not a tuple of slices of ints (use the hook), -1 = error. */
@@ -235,7 +256,7 @@ static PyObject* array_subscript(PyObject* a, PyObject* key) {
   gr_array out = 0;
   int st = p_slice(c, x->h, n, start, stop, step, hs, he, &out);
   if (st) return raise_status(x->ctx, st);
-  return new_array(Py_TYPE(a), x->ctx, out);
+  return new_array(Py_TYPE(a), x->ctx, out, x->owner, NULL, 1);
 }
 
 static int array_ass_subscript(PyObject* a, PyObject* key, PyObject* value) {
@@ -270,6 +291,30 @@ static PyObject* array_materialize(PyObject* a, PyObject* unused) {
   if (!c) return NULL;
   int st = p_materialize(c, x->h);
   if (st) return raise_status(x->ctx, st);
+  if (!x->view) Py_CLEAR(x->owner);  /* the node now has storage of its own and has let go of its inputs */
+  Py_INCREF(a);
+  return a;
+}
+
+/* _materialize_into(address, bytes, tensor, static): gr_materialize_into (or its non-allocating variant) into the
+ * caller's buffer.  An array that had no storage is bound to that buffer and lets go of its inputs: the tensor
+ * becomes what keeps it alive.  One that had storage (and every view) is only copied and keeps what it had. */
+static PyObject* array_materialize_into(PyObject* a, PyObject* args) {
+  ArrayObject* x = (ArrayObject*)a;
+  unsigned long long ptr, nbytes;
+  PyObject* tensor;
+  int is_static = 0;
+  if (!PyArg_ParseTuple(args, "KKO|p", &ptr, &nbytes, &tensor, &is_static)) return NULL;
+  gr_ctx* c = ctx_of(x->ctx);
+  if (!c) return NULL;
+  int had = 1;
+  if (!x->view) {
+    int st0 = p_is_materialized(c, x->h, &had);
+    if (st0) return raise_status(x->ctx, st0);
+  }
+  int st = (is_static ? p_materialize_into_static : p_materialize_into)(c, x->h, (void*)(uintptr_t)ptr, (size_t)nbytes);
+  if (st) return raise_status(x->ctx, st);
+  if (!had) { Py_INCREF(tensor); Py_XSETREF(x->owner, tensor); }
   Py_INCREF(a);
   return a;
 }
@@ -281,7 +326,7 @@ static PyObject* array_T(PyObject* a, void* unused) {
   gr_array out = 0;
   int st = p_transpose(c, x->h, NULL, &out);
   if (st) return raise_status(x->ctx, st);
-  return new_array(Py_TYPE(a), x->ctx, out);
+  return new_array(Py_TYPE(a), x->ctx, out, x->owner, NULL, 1);
 }
 
 static PyObject* array_ndim(PyObject* a, void* unused) {
@@ -346,7 +391,7 @@ static PyObject* mod_reduce(PyObject* m, PyObject* args) {
   gr_array out = 0;
   int st = p_reduce(c, (gr_op)op, x->h, axes, n, keep, &out);
   if (st) return raise_status(x->ctx, st);
-  return new_array(Py_TYPE(a), x->ctx, out);
+  return new_array(Py_TYPE(a), x->ctx, out, x->owner, NULL, 0);
 }
 
 static PyNumberMethods array_as_number = {
@@ -356,11 +401,13 @@ static PyNumberMethods array_as_number = {
 static PyMappingMethods array_as_mapping = {.mp_subscript = array_subscript, .mp_ass_subscript = array_ass_subscript};
 static PyMethodDef array_methods[] = {
     {"materialize", array_materialize, METH_NOARGS, "Evaluates the node (gr_materialize) and returns self."},
+    {"_materialize_into", array_materialize_into, METH_VARARGS, "Evaluates the node into a caller's buffer (gr_materialize_into[_static]) and returns self."},
     {NULL, NULL, 0, NULL}};
 static PyMemberDef array_members[] = {
     {"ctx", T_OBJECT, offsetof(ArrayObject, ctx), READONLY, "the Context the node belongs to"},
     {"h", T_ULONGLONG, offsetof(ArrayObject, h), READONLY, "the node's handle"},
-    {"_owner", T_OBJECT, offsetof(ArrayObject, owner), 0, "keeps a leaf's device memory alive"},
+    {"_owner", T_OBJECT, offsetof(ArrayObject, owner), 0, "keeps alive the device memory of the leaves this node still reads"},
+    {"_view", T_BOOL, offsetof(ArrayObject, view), 0, "a slice or transpose (reads its base's storage also once evaluated)"},
     {NULL, 0, 0, 0, NULL}};
 static PyGetSetDef array_getset[] = {{"T", array_T, NULL, "transposed view (axes reversed)", NULL},
                                      {"ndim", array_ndim, NULL, "number of dimensions", NULL},
@@ -414,7 +461,10 @@ static PyObject* mod_bind(PyObject* m, PyObject* d) {
       !take_address(d, "gr_transpose", (void**)&p_transpose) || !take_address(d, "gr_dot", (void**)&p_dot) ||
       !take_address(d, "gr_assign", (void**)&p_assign) || !take_address(d, "gr_materialize", (void**)&p_materialize) ||
       !take_address(d, "gr_release", (void**)&p_release) || !take_address(d, "gr_reduce", (void**)&p_reduce) ||
-      !take_address(d, "gr_ndim", (void**)&p_ndim) || !take_address(d, "gr_shape", (void**)&p_shape))
+      !take_address(d, "gr_ndim", (void**)&p_ndim) || !take_address(d, "gr_shape", (void**)&p_shape) ||
+      !take_address(d, "gr_materialize_into", (void**)&p_materialize_into) ||
+      !take_address(d, "gr_materialize_into_static", (void**)&p_materialize_into_static) ||
+      !take_address(d, "gr_is_materialized", (void**)&p_is_materialized))
     return NULL;
   Py_RETURN_NONE;
 }

@@ -290,12 +290,13 @@ class _DeviceExport:
 class _PyArrayBase:
     """The recording calls through ctypes alone (GRUMPY_NO_FASTBIND=1): what _fastbind.ArrayBase does in C."""
 
-    __slots__ = ("ctx", "h", "_owner")
+    __slots__ = ("ctx", "h", "_owner", "_view")
 
     def __init__(self, ctx: Context, handle: int):
         self.ctx = ctx
         self.h = handle
         self._owner = None
+        self._view = False
 
     def __del__(self):
         try:
@@ -307,6 +308,18 @@ class _PyArrayBase:
 
     def materialize(self):
         self.ctx.check(lib().gr_materialize(self.ctx._p, self.h))
+        if not self._view:
+            self._owner = None  # the node now has storage of its own and has let go of its inputs
+        return self
+
+    def _materialize_into(self, ptr, nbytes, tensor, static=False):
+        had = ctypes.c_int(1)
+        if not self._view:
+            self.ctx.check(_lib.gr_is_materialized(self.ctx._p, self.h, ctypes.byref(had)))
+        fn = _lib.gr_materialize_into_static if static else _lib.gr_materialize_into
+        self.ctx.check(fn(self.ctx._p, self.h, ptr, nbytes))
+        if not had.value:
+            self._owner = tensor
         return self
 
     def __add__(self, o): return _binary_slow(GR_ADD, self, o)
@@ -373,17 +386,13 @@ class _ArrayMethods:
 
     # -- materialisation --------------------------------------------------------
     def materialize_into(self, t) -> "Array":
-        st = _lib.gr_materialize_into(self.ctx._p, self.h, t.data_ptr(), t.numel() * t.element_size())
-        if st:
-            self.ctx.check(st)
-        return self
+        """Evaluates into the caller's tensor (gr_materialize_into).  An array that had no storage is bound to the
+        tensor, which then is what keeps it alive; one that had (and every view) is copied."""
+        return self._materialize_into(t.data_ptr(), t.numel() * t.element_size(), t, False)
 
     def materialize_into_static(self, t) -> "Array":
         """materialize_into for callers that must not allocate device memory (gr_materialize_into_static)."""
-        st = _lib.gr_materialize_into_static(self.ctx._p, self.h, t.data_ptr(), t.numel() * t.element_size())
-        if st:
-            self.ctx.check(st)
-        return self
+        return self._materialize_into(t.data_ptr(), t.numel() * t.element_size(), t, True)
 
     def torch(self, copy: bool = True):
         """Evaluates the node (its storage then belongs to the library and lives as long as the node,
@@ -463,9 +472,28 @@ def _bind_fast_paths(L):
     if _fastbind is None:
         return
     names = ["gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose", "gr_dot", "gr_assign",
-             "gr_materialize", "gr_release", "gr_reduce", "gr_ndim", "gr_shape"]
+             "gr_materialize", "gr_release", "gr_reduce", "gr_ndim", "gr_shape", "gr_materialize_into",
+             "gr_materialize_into_static", "gr_is_materialized"]
     _fastbind.bind({n: ctypes.cast(getattr(L, n), ctypes.c_void_p).value for n in names})
     _fastbind.set_hooks(_binary_slow, slice_, _setitem_slow, _pow_slow, _reduce_slow)
+
+
+def _result(ctx: Context, handle: int, a=None, b=None, view: bool = False) -> "Array":
+    """Wraps the handle of a freshly recorded node.  The recorded DAG outlives the handles of its leaves
+    (``z = ctx.array(tensor) * 2`` drops the leaf's handle at once), so a result carries what keeps its
+    operands' leaves alive: one owner as it is, two different ones as a pair."""
+    r = Array(ctx, handle)
+    oa = a._owner if isinstance(a, Array) else None
+    ob = b._owner if isinstance(b, Array) else None
+    if oa is None or ob is None or oa is ob:
+        owner = oa if oa is not None else ob
+    else:
+        owner = (oa, ob)
+    if owner is not None:
+        r._owner = owner
+    if view:
+        r._view = True
+    return r
 
 
 def _ctx_of(*xs) -> Context:
@@ -489,7 +517,7 @@ def _unary_slow(op: int, a) -> Array:
     st = _lib.gr_unary(ctx._p, op, a.h, ctypes.byref(h))
     if st:
         ctx.check(st)
-    return Array(ctx, h.value)
+    return _result(ctx, h.value, a)
 
 
 def _binary_slow(op: int, a, b) -> Array:
@@ -509,7 +537,7 @@ def _binary_slow(op: int, a, b) -> Array:
         raise TypeError("no array operand")
     if st:
         ctx.check(st)
-    return Array(ctx, h.value)
+    return _result(ctx, h.value, a, b)
 
 
 def _pow_slow(a, e) -> Array:
@@ -565,14 +593,14 @@ def slice_(a: Array, key) -> Array:
         stop[d] = 0 if k.stop is None else int(k.stop)
     h = ctypes.c_uint64()
     a.ctx.check(lib().gr_slice(a.ctx._p, a.h, n, start, stop, step, hs, he, ctypes.byref(h)))
-    return Array(a.ctx, h.value)
+    return _result(a.ctx, h.value, a, view=True)
 
 
 def transpose(a: Array, axes: Optional[Sequence[int]] = None) -> Array:
     p = None if axes is None else (ctypes.c_int * len(axes))(*axes)
     h = ctypes.c_uint64()
     a.ctx.check(lib().gr_transpose(a.ctx._p, a.h, p, ctypes.byref(h)))
-    return Array(a.ctx, h.value)
+    return _result(a.ctx, h.value, a, view=True)
 
 
 def reshape(a: Array, shape) -> Array:
@@ -581,7 +609,7 @@ def reshape(a: Array, shape) -> Array:
     arr = (ctypes.c_int64 * builtins.max(len(shape), 1))(*shape)
     h = ctypes.c_uint64()
     a.ctx.check(lib().gr_reshape(a.ctx._p, a.h, len(shape), arr, ctypes.byref(h)))
-    return Array(a.ctx, h.value)
+    return _result(a.ctx, h.value, a)
 
 
 def reduce(name: str, a: Array, axis=None, keepdims=False) -> Array:
@@ -600,7 +628,7 @@ def _reduce_slow(op: int, a: Array, axis=None, keepdims=False) -> Array:
     arr = (ctypes.c_int * builtins.max(len(axes), 1))(*axes)
     h = ctypes.c_uint64()
     a.ctx.check(lib().gr_reduce(a.ctx._p, op, a.h, arr, len(axes), int(bool(keepdims)), ctypes.byref(h)))
-    return Array(a.ctx, h.value)
+    return _result(a.ctx, h.value, a)
 
 
 _reduce = _reduce_slow if _fastbind is None else _fastbind.reduce
@@ -609,7 +637,7 @@ _reduce = _reduce_slow if _fastbind is None else _fastbind.reduce
 def scan(name: str, a: Array, axis: int) -> Array:
     h = ctypes.c_uint64()
     a.ctx.check(lib().gr_scan(a.ctx._p, _REDUCE[name], a.h, int(axis), ctypes.byref(h)))
-    return Array(a.ctx, h.value)
+    return _result(a.ctx, h.value, a)
 
 
 def _scan_axis(name, a, axis):
@@ -627,7 +655,7 @@ def dot(a: Array, b: Array) -> Array:
         raise TypeError("dot: both operands must be arrays")
     h = ctypes.c_uint64()
     a.ctx.check(lib().gr_dot(a.ctx._p, a.h, b.h, ctypes.byref(h)))
-    return Array(a.ctx, h.value)
+    return _result(a.ctx, h.value, a, b)
 
 
 # NumPy-named functions

@@ -163,25 +163,34 @@ def mnist(xp, W, a, b):
     return 1.0 / (1.0 + xp.exp(-x))
 
 
+# The five-point neighbourhood of the paper's Jacobi benchmark (Listing 6): (row, column) shifts of the
+# windows that are added, in the listing's order; every sweep replaces the interior by a fifth of their sum.
+FIVE_POINT = ((0, 0), (-1, 0), (0, 1), (0, -1), (1, 0))
+
+
+def shifted_windows(grid, offsets=FIVE_POINT, margin=1):
+    """Views of `grid` with `margin` cells cut off all round, shifted by each (row, column) offset."""
+    rows, cols = grid.shape
+    return [grid[margin + dr:rows - margin + dr, margin + dc:cols - margin + dc] for dr, dc in offsets]
+
+
+def stencil_sum(windows, weight=0.2):
+    total = windows[0]
+    for w in windows[1:]:
+        total = total + w
+    return weight * total
+
+
 def jacobi_sweep(xp, grid):
-    """Right-hand side of one sweep of Listing 6 (the slice reads)."""
-    center = grid[1:-1, 1:-1]
-    north = grid[0:-2, 1:-1]
-    east = grid[1:-1, 2:]
-    west = grid[1:-1, 0:-2]
-    south = grid[2:, 1:-1]
-    return 0.2 * (center + north + east + west + south)
+    """Right-hand side of one sweep of Listing 6."""
+    return stencil_sum(shifted_windows(grid))
 
 
 def jacobi(xp, grid, iterations):
-    """Listing 6 in full: the views are taken once, every sweep assigns through `center`."""
-    center = grid[1:-1, 1:-1]
-    north = grid[0:-2, 1:-1]
-    east = grid[1:-1, 2:]
-    west = grid[1:-1, 0:-2]
-    south = grid[2:, 1:-1]
+    """Listing 6 in full: the views are taken once, every sweep assigns through the unshifted one."""
+    windows = shifted_windows(grid)
     for _ in range(iterations):
-        center[:] = 0.2 * (center + north + east + west + south)
+        windows[0][:] = stencil_sum(windows)
     return grid
 
 

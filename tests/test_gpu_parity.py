@@ -159,6 +159,29 @@ def test_blackscholes(env, n):
     assert_elementwise(got, ref, what="erf")
 
 
+def test_sqrt_of_every_float32(env):
+    # The generated kernels take square roots with a five-instruction sequence of their own (reciprocal
+    # square root, one Newton step with an exact residual; arguments below 2^-96 go to the library routine).
+    # Its results must have the bits of the IEEE square root, which the oracle's sqrt is: compared for every
+    # non-negative float32 bit pattern (zeros, denormals, infinity and NaNs included), for -0, every negative
+    # denormal and the smallest negative normals, and for every 256th pattern of the remaining negatives.
+    gr, ctx, torch = env
+    step = 1 << 27
+    ranges = [(lo, lo + step, 1) for lo in range(0, 1 << 31, step)]
+    ranges += [(0x80000000, 0x81000000, 1), (0x81000000, 1 << 32, 256)]
+    checked = 0
+    for lo, hi, stride in ranges:
+        bits = np.arange(lo, hi, stride, dtype=np.int64).astype(np.uint32)
+        x = bits.view(f32)
+        t = torch.from_numpy(x).cuda()
+        got = gr.sqrt(ctx.array(t)).numpy().view(np.uint32)
+        ref = ora.sqrt(ora.array(x)).numpy()
+        same = (got == ref.view(np.uint32)) | (np.isnan(ref) & np.isnan(got.view(f32)))
+        assert same.all(), f"sqrt differs for bits 0x{int(bits[np.argmin(same)]):08x}: got 0x{int(got[np.argmin(same)]):08x}, IEEE 0x{int(ref.view(np.uint32)[np.argmin(same)]):08x}"
+        checked += bits.size
+    assert checked == (1 << 31) + (1 << 24) + ((1 << 32) - 0x81000000) // 256
+
+
 # ------------------------------------- full sizes, every element against the oracle --
 def test_normalize_full(env):
     gr, ctx, torch = env
@@ -633,6 +656,22 @@ def test_materialized_node_is_reused_not_recomputed(env):
     assert after["kernel_launches"] - before["kernel_launches"] == 1
     ref = ((ora.exp(ora.array(t.cpu().numpy())) + ora.array(t.cpu().numpy())) + 1.0).numpy()
     assert_elementwise(got, ref)
+
+
+def test_recorded_arrays_keep_their_leaves_alive(env):
+    # z = ctx.array(temporary) * 2 drops the leaf's handle and the tensor at once; the recorded array must keep
+    # the tensor's memory from going back to torch's allocator until it has been evaluated
+    gr, ctx, torch = env
+    n = 1 << 20
+    x = _rand((n,), 45)
+    z = ctx.array(torch.from_numpy(x).cuda()) * 2.0 + 1.0
+    junk = [torch.full((n,), float(k), device="cuda") for k in range(4)]   # would reuse the freed block
+    torch.cuda.synchronize()
+    assert np.array_equal(z.numpy(), x * f32(2) + f32(1))
+    v = ctx.array(torch.from_numpy(x).cuda())[5:n - 5:3]                    # a view of a leaf whose handle is gone
+    junk += [torch.full((n,), -1.0, device="cuda") for _ in range(2)]
+    assert np.array_equal(v.numpy(), x[5:n - 5:3])
+    del junk
 
 
 def test_kernel_cache_hits_across_shapes_and_constants(env):

@@ -657,7 +657,13 @@ def test_async_and_serial_compilation_agree(ctx):
 
 def test_generated_code_has_no_contraction_or_packed_math(ctx):
     src = wl.chain(gr, ctx.spec((4096,)), ctx.spec((4096,))).source(0)
-    assert "fmaf" not in src and "__fdividef" not in src and "__expf" not in src
+    # the only fused multiply-adds are the two inside the square-root helper (its Newton step needs the exact
+    # residual; the helper's results are the IEEE square root's, checked for every float32 on the device)
+    helper = src[src.index("gr_sqrtf(float x) {"):]
+    helper = helper[:helper.index("\n}\n") + 3]
+    assert helper.count("fmaf") == 2
+    rest = src.replace(helper, "")
+    assert "fmaf" not in rest and "__fdividef" not in src and "__expf" not in src
 
 
 def test_generated_kernels_keep_their_values_in_registers(ctx, tmp_path):
@@ -941,3 +947,64 @@ def test_var_std_clip_are_recorded_from_existing_ops(ctx):
     assert [k for k, _ in groups(z)] == ["ROWRED"]            # standardising rows: one row-resident kernel
     assert groups(gr.clip(x * 2.0, 0.0, 6.0)) == [("MAP", ["mul", "maximum", "minimum"])]
     z.compile()
+
+
+# ------------------------------------------------- lifetime of wrapped leaf memory --
+@pytest.mark.parametrize("fast", [True, False])
+def test_results_keep_the_memory_of_their_leaves_alive(fast, monkeypatch):
+    # The recorded DAG outlives the handles of its leaves: a result must hold whatever keeps the leaves'
+    # device memory alive until it has storage of its own.  Both binding routes (the C type and ctypes).
+    import gc
+    import subprocess
+    import sys
+    code = r'''
+import gc, weakref, sys
+from paper_1901_03771_amd import lazy as gr
+class Mem:            # stands for a tensor
+    pass
+ctx = gr.Context(device=-1)
+ctx.set_option("dry_run", 2)
+def leaf(shape):
+    m = Mem()
+    return ctx.from_device(0x10000, gr.GR_F32, shape, owner=m), weakref.ref(m)
+a, wa = leaf((8, 8)); b, wb = leaf((8,)); c, wc = leaf((8, 8))
+z = gr.exp(a * 2.0 + b)[1:3].T @ gr.sum(c, axis=1)[1:3]
+del a, b, c
+gc.collect()
+assert wa() is not None and wb() is not None and wc() is not None, "a leaf's memory was released while a recorded array still reads it"
+z.materialize()
+gc.collect()
+assert wa() is None and wb() is None and wc() is None, "an evaluated array still holds its leaves' memory"
+# a view keeps its base's memory, evaluated or not; a copy lets go of it
+a, wa = leaf((8, 8))
+v = a[2:4]
+del a
+v.materialize(); gc.collect()
+assert wa() is not None
+w = v.copy()
+del v; gc.collect()
+assert wa() is None
+# materialize_into: bound to the caller's buffer (an array without storage) or copied (a leaf, a view)
+a, wa = leaf((8,))
+t = Mem(); t.data_ptr = lambda: 0x20000; t.numel = lambda: 8; t.element_size = lambda: 4
+wt = weakref.ref(t)
+y = a + 1.0
+y.materialize_into(t)
+del a; gc.collect()
+assert wa() is None and y._owner is t
+a, wa = leaf((8,))
+a.materialize_into(t)
+assert a._owner is not t and wa() is not None
+# an iteration x = f(x) that evaluates every step does not accumulate owners
+x, wx = leaf((8,))
+for _ in range(50):
+    x = (x * 0.5 + 1.0).materialize()
+gc.collect()
+assert wx() is None and x._owner is None
+print("ok")
+'''
+    env = dict(os.environ, PYTHONPATH=ROOT)
+    if not fast:
+        env["GRUMPY_NO_FASTBIND"] = "1"
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
