@@ -11,6 +11,12 @@ in HBM before the timed region and three buffer sets are rotated so that the
 256 MB Infinity Cache cannot serve repeats.  Prints ONE JSON line.
 
 Metric: effective GB/s = (unique input bytes + output bytes) / time.
+
+Timing: HIP events on the stream the kernels are launched on (the context uses
+torch's current stream).  The K timed steps of a region run back to back; events
+recorded inside the region at (up to) ten block boundaries give a per-step median
+and minimum over blocks beside the average of the whole region, without
+lengthening it.
 """
 import argparse
 import json
@@ -23,9 +29,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+FP32_MFMA_PEAK_TFLOPS = 157.3
 ARGNAMES = {"blackscholes": ("S", "K", "T"), "chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
             "stencil": ("I",), "logreg": ("X", "w", "y")}
-# kernel whose launches dominate each workload, and its algorithmic bytes per launch
+# kernel whose launches dominate each workload
 DOMINANT = {"blackscholes": "gr_map", "chain": "gr_map", "normalize": "gr_map", "softmax": "gr_rowred", "stencil": "gr_map", "logreg": "gr_gemv_pair"}
 
 
@@ -60,6 +67,7 @@ class Workload:
             self.sets.append((dev, out))
         self.i = 0
         self.unique_bytes = wl.unique_bytes(name, **self.p)
+        self.program = None
 
     def step(self):
         dev, out = self.sets[self.i % len(self.sets)]
@@ -68,59 +76,113 @@ class Workload:
         self.wl.PROGRAMS[self.name](self.gr, **leaves).materialize_into(out)
         return out
 
+    def record(self):
+        """Records the request once for replay (gr_program_create) with every input rebindable."""
+        dev, _ = self.sets[0]
+        leaves = {k: self.ctx.array(t) for k, t in dev.items()}
+        self.program = self.ctx.program(self.wl.PROGRAMS[self.name](self.gr, **leaves), [leaves[k] for k in ARGNAMES[self.name]])
+        self.order = [[dev_[k] for k in ARGNAMES[self.name]] for dev_, _ in self.sets]
 
-def time_steps(torch, w, steps, warmup):
+    def replay(self):
+        k = self.i % len(self.sets)
+        self.i += 1
+        self.program.run(self.order[k], self.sets[k][1])
+
+
+def time_region(torch, step, steps, warmup, blocks=10):
+    """`warmup` untimed steps, then exactly `steps` steps back to back between two events; events at block
+    boundaries inside the region give per-step times per block.  Returns (region ms, wall ms, [us per step per block])."""
     for _ in range(warmup):
-        w.step()
+        step()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    w.ctx.profile_reset()
+    nb = max(1, min(blocks, steps))
+    bounds = [steps * b // nb for b in range(nb + 1)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(nb + 1)]
     t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
-        w.step()
-    e1.record()
+    ev[0].record()
+    for b in range(nb):
+        for _ in range(bounds[b + 1] - bounds[b]):
+            step()
+        ev[b + 1].record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    dev_ms = e0.elapsed_time(e1)
-    return max(dev_ms, 0.0), wall_ms
+    per_block = [ev[b].elapsed_time(ev[b + 1]) / (bounds[b + 1] - bounds[b]) * 1e3 for b in range(nb)]
+    return max(ev[0].elapsed_time(ev[nb]), 0.0), wall_ms, per_block
+
+
+def spin_up(torch, step, min_ms=40.0, min_steps=20):
+    """Untimed steps for at least `min_ms` of device time: drawing a configuration's inputs on the host leaves the GPU
+    idle for about a second, and for some 25 ms after that launches run up to 10 % slower than in steady state."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    done, n = 0.0, min_steps
+    while done < min_ms:
+        e0.record()
+        for _ in range(n):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        done += ms
+        n = max(min_steps, min(4000, int(n * (min_ms - done) / max(ms, 1e-3)) + 1))
+
+
+def median(xs):
+    s = sorted(xs)
+    return s[len(s) // 2] if len(s) % 2 else 0.5 * (s[len(s) // 2 - 1] + s[len(s) // 2])
+
+
+def hbm_roofline(kernel, alg_bytes, avg_us, per_block_us, launches, **more):
+    achieved = alg_bytes / (avg_us * 1e-6) / 1e9
+    r = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(achieved / HBM_PEAK_GBS, 4), "launches": launches, "avg_launch_us": round(avg_us, 2),
+         "median_us": round(median(per_block_us), 2), "min_us": round(min(per_block_us), 2),
+         "algorithmic_bytes_per_launch": alg_bytes}
+    r.update(more)
+    return r
 
 
 def cpu_baseline(name, target_cpu_s=20.0):
-    """The oracle as it stands, timed on the host cores on a bounded sample of the workload
-    (about `target_cpu_s` core-seconds in total), plus eager NumPy on the same sample as context
-    (the paper's own denominator, Section 4.2)."""
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload: on every core the
+    process may use (`value`, `cores`) and on one thread (`single_thread`), about `target_cpu_s` core-seconds in
+    all; eager NumPy on the same sample as context (the paper's own denominator, Section 4.2)."""
     import numpy as np
     import oracle as ora
     from paper_1901_03771_amd import workloads as wl
-    cores = min(16, len(os.sched_getaffinity(0)))
-    ora.set_threads(cores)
+    cores = len(os.sched_getaffinity(0))
     full = wl.FULL[name]
-    if name in ("chain", "blackscholes"):
-        size = dict(n=full["n"])
-    else:
-        size = dict(rows=64 if name != "logreg" else 4096, cols=full["cols"])
 
-    def run(sz):
+    def run(sz, threads):
+        ora.set_threads(threads)
         arrays = wl.make_inputs(name, **sz)
         t0 = time.perf_counter()
         wl.PROGRAMS[name](ora, **{k: ora.array(v) for k, v in arrays.items()}).numpy()
         return time.perf_counter() - t0, arrays
 
-    t, arrays = run(size)
-    if "rows" in size:  # scale the row count towards the target, capped at the full workload
-        rows = int(min(full["rows"], max(size["rows"], size["rows"] * (target_cpu_s / cores / 3) / max(t, 1e-3))))
-        size = dict(rows=rows, cols=full["cols"])
-    times = []
-    while not times or (sum(times) * cores < target_cpu_s and len(times) < 20):
-        t, arrays = run(size)
-        times.append(t)
-    t = sorted(times)[len(times) // 2]
-    nbytes = wl.unique_bytes(name, **size)
-    out = {"value": round(nbytes / t / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
-           "sample": f"{name} program on " + ", ".join(f"{k}={v}" for k, v in size.items()) +
-                     f" (same recipe, seed and column count as the timed workload), median of {len(times)} runs, "
-                     f"{t:.2f} s wall each on {cores} OpenMP threads, {sum(times) * cores:.0f} core-seconds in all"}
+    def leg(threads, budget_core_s):
+        if name in ("chain", "blackscholes"):
+            size = dict(n=full["n"])
+        else:
+            size = dict(rows=64 if name != "logreg" else 4096, cols=full["cols"])
+        t, arrays = run(size, threads)
+        if "rows" in size:  # scale the row count towards the budget, capped at the full workload
+            rows = int(min(full["rows"], max(size["rows"], size["rows"] * (budget_core_s / threads / 3) / max(t, 1e-3))))
+            size = dict(rows=rows, cols=full["cols"])
+        times = []
+        while not times or (sum(times) * threads < budget_core_s and len(times) < 20):
+            t, arrays = run(size, threads)
+            times.append(t)
+        t = median(times)
+        nbytes = wl.unique_bytes(name, **size)
+        return {"value": round(nbytes / t / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+                "sample": f"{name} program on " + ", ".join(f"{k}={v}" for k, v in size.items()) +
+                          f" (same recipe, seed and column count as the timed workload), median of {len(times)} runs, "
+                          f"{t:.2f} s wall each on {threads} OpenMP thread{'s' if threads > 1 else ''}, {sum(times) * threads:.0f} core-seconds in all"}, arrays, nbytes
+
+    out, arrays, nbytes = leg(cores, 0.7 * target_cpu_s)
+    out["host_cores_available"] = cores
+    if cores > 1:
+        single, _, _ = leg(1, 0.3 * target_cpu_s)
+        out["single_thread"] = single
     if name != "blackscholes":  # NumPy has no erf
         t0 = time.perf_counter()
         wl.PROGRAMS[name](np, **arrays)
@@ -129,15 +191,16 @@ def cpu_baseline(name, target_cpu_s=20.0):
 
 
 def traffic_from_profiles(name):
-    """HBM bytes per launch measured with rocprofv3 --pmc, if a summary is committed."""
-    path = os.path.join(ROOT, "profiles", f"{DOMINANT[name]}_{name}_pmc.txt")
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and workload (not measured in
+    this run: counters need a profiler pass of their own)."""
+    rel = os.path.join("profiles", f"{DOMINANT[name]}_{name}_pmc.txt")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                return float(line.split(":")[1]), rel
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def main():
@@ -179,9 +242,8 @@ def main():
     compile_wait_ms = (time.perf_counter() - t0) * 1e3
     ctx.set_option("interp", 0)  # everything timed below runs the generated kernels
 
-    # Timed region: K steps back to back, bracketed by HIP events on the stream the kernels run on
-    # (the context launches on torch's current stream).  No per-launch instrumentation here.
-    dev_ms, wall_ms = time_steps(torch, w, args.steps, args.warmup)
+    # Timed region: exactly K steps back to back after W untimed ones.  No per-launch instrumentation here.
+    dev_ms, wall_ms, per_block = time_region(torch, w.step, args.steps, args.warmup)
     ms_per_step = dev_ms / args.steps
     value = w.unique_bytes / (ms_per_step * 1e-3) / 1e9
 
@@ -189,17 +251,13 @@ def main():
     # region time / launches (kernels run back to back, so this includes the launch gaps and is
     # an upper bound); a second, instrumented pass brackets every launch with its own event
     # pair as a cross-check against the rocprofv3 kernel trace.
-    launches_per_step = 1  # (logreg: the 6 us second-stage combine kernel rides in the same figure)
-    alg = algorithmic_bytes_per_launch(name, w.p)
-    per_launch_ms = ms_per_step / launches_per_step
-    achieved = alg / (per_launch_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": DOMINANT[name], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_from_profiles(name),
-                "launches": args.steps * launches_per_step, "avg_launch_us": round(per_launch_ms * 1e3, 2),
-                "algorithmic_bytes_per_launch": alg}
+    traffic, traffic_src = traffic_from_profiles(name)
+    roofline = hbm_roofline(DOMINANT[name], algorithmic_bytes_per_launch(name, w.p), ms_per_step * 1e3, per_block, args.steps,
+                            traffic=traffic, traffic_source=(traffic_src + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by the plain copy kernel; committed summary, not measured in this run)") if traffic_src else None)
     if not args.no_launch_events:
         ctx.set_option("profile", 1)
-        time_steps(torch, w, min(args.steps, 100), 5)
+        ctx.profile_reset()
+        time_region(torch, w.step, min(args.steps, 100), 5)
         n, total_ms = ctx.profile_read(DOMINANT[name])
         ctx.set_option("profile", 0)
         roofline["per_launch_event_us"] = round(total_ms / max(n, 1) * 1e3, 2)
@@ -212,6 +270,7 @@ def main():
         "config": {"workload": f"{name}: " + ", ".join(f"{k}={v}" for k, v in w.p.items()), "buffer_sets": args.sets,
                    "unique_bytes_per_step": w.unique_bytes},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "us_per_step_median_of_blocks": round(median(per_block), 2), "us_per_step_min_of_blocks": round(min(per_block), 2),
         "host_wall_ms_per_step": round(wall_ms / args.steps, 5),
         "cold_first_call_ms": round(cold_ms, 2), "cold_first_call_interpreted": cold_interpreted,
         "compile_wait_after_first_call_ms": round(compile_wait_ms, 2),
@@ -225,7 +284,7 @@ def main():
         torch.cuda.synchronize()
 
     if not args.no_extras:
-        extras = {}
+        extras, rooflines = {}, {}
         # practical ceiling of the box: plain copy and read-only kernels, rotating over the same
         # buffer sets as the workload so that the Infinity Cache cannot serve the reads
         first = ARGNAMES[name][0]
@@ -234,32 +293,52 @@ def main():
         if nel >= (1 << 22):
             pairs = [(a[:nel], b[:nel]) for a, b in pairs]
             sink = torch.zeros(4096, device="cuda")
-            for label, fn, nbytes in (("stream_copy", lambda i: ctx.stream_copy(pairs[i % len(pairs)][1], pairs[i % len(pairs)][0]), 8 * nel),
-                                      ("stream_read", lambda i: ctx.stream_read(pairs[i % len(pairs)][0], sink), 4 * nel)):
-                for i in range(5):
-                    fn(i)
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for i in range(60):
-                    fn(i)
-                e1.record()
-                torch.cuda.synchronize()
-                extras[label + "_GBps"] = round(nbytes / (e0.elapsed_time(e1) / 60 * 1e-3) / 1e9, 1)
+            k = [0]
+
+            def copy_step():
+                k[0] += 1
+                ctx.stream_copy(pairs[k[0] % len(pairs)][1], pairs[k[0] % len(pairs)][0])
+
+            def read_step():
+                k[0] += 1
+                ctx.stream_read(pairs[k[0] % len(pairs)][0], sink)
+            for label, fn, nbytes in (("stream_copy", copy_step, 8 * nel), ("stream_read", read_step, 4 * nel)):
+                d_ms, _, blocks = time_region(torch, fn, 100, 20)
+                extras[label + "_GBps"] = round(nbytes / (d_ms / 100 * 1e-3) / 1e9, 1)
+                rooflines[label] = hbm_roofline("gr_" + label + "_kernel", nbytes, d_ms / 100 * 1e3, blocks, 100)
         del w
         torch.cuda.empty_cache()
+
+        # the other configurations (and two scaled pointwise chains): each spun up to steady state first
         others = [("chain", None), ("chain", dict(n=1 << 27)), ("blackscholes", dict(n=1 << 26)), ("softmax", None), ("stencil", None), ("logreg", None), ("normalize", None)]
         for oname, size in others:
             if oname == name and size is None:
                 continue
             ow = Workload(oname, ctx, 3 if size is None else 2, size)
-            k = 1000 if (oname == "chain" and size is None) else 50
-            # (60 untimed steps: building the inputs on the host leaves the GPU idle for about a second, and
-            # the first hundred or so launches after that run up to 10 % slower)
-            d_ms, _ = time_steps(torch, ow, k, 60)
+            small = oname == "chain" and size is None
+            k = 2000 if small else 100
+            spin_up(torch, ow.step)
+            d_ms, o_wall, blocks = time_region(torch, ow.step, k, 0)
             label = oname if size is None else f"{oname}_n2^{size['n'].bit_length() - 1}"
-            extras[label + "_GBps"] = round(ow.unique_bytes / (d_ms / k * 1e-3) / 1e9, 1)
-            extras[label + "_us_per_step"] = round(d_ms / k * 1e3, 2)
+            us = d_ms / k * 1e3
+            extras[label + "_GBps"] = round(ow.unique_bytes / (us * 1e-6) / 1e9, 1)
+            extras[label + "_us_per_step"] = round(us, 2)
+            rooflines[label] = hbm_roofline(DOMINANT[oname], algorithmic_bytes_per_launch(oname, ow.p), us, blocks, k,
+                                            **({"note": "12 MiB working set: resident in L2 / Infinity Cache, bound by launch rate and host work per step, not by HBM"} if small else {}),
+                                            **({"note": "ALU-bound: log, exp, sqrt, two erf and four IEEE divisions per element"} if oname == "blackscholes" else {}))
+            if small:
+                # the same request recorded once and replayed (gr_program_run): launches only
+                extras[label + "_host_wall_us_per_step"] = round(o_wall / k * 1e3, 2)
+                ow.record()
+                spin_up(torch, ow.replay)
+                d_ms, o_wall, blocks = time_region(torch, ow.replay, k, 0)
+                us = d_ms / k * 1e3
+                extras[label + "_replay_GBps"] = round(ow.unique_bytes / (us * 1e-6) / 1e9, 1)
+                extras[label + "_replay_us_per_step"] = round(us, 2)
+                extras[label + "_replay_host_wall_us_per_step"] = round(o_wall / k * 1e3, 2)
+                rooflines[label + "_replay"] = hbm_roofline("gr_map", algorithmic_bytes_per_launch(oname, ow.p), us, blocks, k,
+                                                            note="recorded once, replayed: launches only; 12 MiB working set, cache-resident")
+                ow.program.close()
             del ow
             torch.cuda.empty_cache()
         # the same GPU without fusion: one kernel per recorded op, every intermediate through HBM
@@ -269,7 +348,7 @@ def main():
         uctx.set_option("interp", 0)
         for oname in ("normalize", "softmax"):
             ow = Workload(oname, uctx, 2)
-            d_ms, _ = time_steps(torch, ow, 20, 3)
+            d_ms, _, _ = time_region(torch, ow.step, 20, 3)
             extras[oname + "_unfused_GBps"] = round(ow.unique_bytes / (d_ms / 20 * 1e-3) / 1e9, 1)
             del ow
             torch.cuda.empty_cache()
@@ -279,7 +358,7 @@ def main():
         ictx.set_option("interp", 2)
         for oname in ("normalize", "stencil", "softmax"):
             ow = Workload(oname, ictx, 2)
-            d_ms, _ = time_steps(torch, ow, 10, 2)
+            d_ms, _, _ = time_region(torch, ow.step, 10, 2)
             extras[oname + "_interpreted_GBps"] = round(ow.unique_bytes / (d_ms / 10 * 1e-3) / 1e9, 1)
             del ow
             torch.cuda.empty_cache()
@@ -301,18 +380,12 @@ def main():
         del ow
         torch.cuda.empty_cache()
         cctx.close()
-        # rows beyond the five configurations: two-stage reduction, map-scan, the full Jacobi loop
-        def timed(fn, iters, warm=3):
-            for _ in range(warm):
-                fn()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(iters):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / iters
+
+        # rows beyond the five configurations: two-stage reduction, map-scan, matrix product, the full Jacobi loop
+        def timed(fn, iters, spin_ms=40.0):
+            spin_up(torch, fn, min_ms=spin_ms, min_steps=2)
+            d_ms, _, blocks = time_region(torch, fn, iters, 0)
+            return d_ms / iters, blocks
 
         n = 1 << 27
         xs = [torch.rand(n, device="cuda") for _ in range(2)]
@@ -322,37 +395,57 @@ def main():
         def red():
             k[0] += 1
             gr.sum(gr.sqrt(ctx.array(xs[k[0] % 2]))).materialize_into(out1)
-        ms = timed(red, 20)
+        ms, blocks = timed(red, 40)
         extras["sum_sqrt_n2^27_GBps"] = round(4 * n / (ms * 1e-3) / 1e9, 1)
+        rooflines["sum_sqrt_n2^27"] = hbm_roofline("gr_reduce", 4 * n, ms * 1e3, blocks, 40)
         outn = torch.empty(n, device="cuda")
 
         def scan():
             k[0] += 1
             gr.cumsum(ctx.array(xs[k[0] % 2]), 0).materialize_into(outn)
-        ms = timed(scan, 10)
+        ms, blocks = timed(scan, 20)
         extras["cumsum_n2^27_GBps"] = round(8 * n / (ms * 1e-3) / 1e9, 1)
+        extras["cumsum_n2^27_us"] = round(ms * 1e3, 1)
+        rooflines["cumsum_n2^27"] = hbm_roofline("gr_scan", 8 * n, ms * 1e3, blocks, 20)
         del xs, outn
+        torch.cuda.empty_cache()
+        m2 = [torch.rand(8192, 8192, device="cuda") for _ in range(2)]
+        outm = torch.empty(8192, 8192, device="cuda")
+
+        def colscan():
+            k[0] += 1
+            gr.cumsum(ctx.array(m2[k[0] % 2]), 0).materialize_into(outm)
+        ms, blocks = timed(colscan, 20)
+        extras["cumsum_axis0_8192_GBps"] = round(8 * 8192 * 8192 / (ms * 1e-3) / 1e9, 1)
+        extras["cumsum_axis0_8192_us"] = round(ms * 1e3, 1)
+        rooflines["cumsum_axis0_8192"] = hbm_roofline("gr_scan", 8 * 8192 * 8192, ms * 1e3, blocks, 20)
+        del m2, outm
         torch.cuda.empty_cache()
         ga, gb = torch.randn(4096, 4096, device="cuda"), torch.randn(4096, 4096, device="cuda")
         gc = torch.empty(4096, 4096, device="cuda")
-        ms = timed(lambda: (ctx.array(ga) @ ctx.array(gb)).materialize_into(gc), 10)
-        extras["gemm_4096_f32_TFLOPs"] = round(2 * 4096 ** 3 / (ms * 1e-3) / 1e12, 1)
+        ms, blocks = timed(lambda: (ctx.array(ga) @ ctx.array(gb)).materialize_into(gc), 40, spin_ms=60.0)
+        tf = 2 * 4096 ** 3 / (ms * 1e-3) / 1e12
+        extras["gemm_4096_f32_TFLOPs"] = round(tf, 1)
+        rooflines["gemm_4096_f32"] = {"bound": "mfma", "kernel": "gr_gemm", "achieved": round(tf, 1), "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                      "frac": round(tf / FP32_MFMA_PEAK_TFLOPS, 4), "launches": 40, "avg_launch_us": round(ms * 1e3, 1),
+                                      "median_us": round(median(blocks), 1), "min_us": round(min(blocks), 1), "algorithmic_flops_per_launch": 2 * 4096 ** 3}
         del ga, gb, gc
-        grid = ctx.array(torch.rand(8192, 8192, device="cuda"))
+        jac_bytes = 4 * 8192 * 8192 + 4 * 8190 * 8190
         sweeps = 10
-        ms = timed(lambda: wl.jacobi(gr, grid, sweeps), 5, warm=1)
-        extras["jacobi_8192_GBps_per_sweep"] = round((4 * 8192 * 8192 + 4 * 8190 * 8190) / (ms / sweeps * 1e-3) / 1e9, 1)
-        extras["jacobi_8192_us_per_sweep"] = round(ms / sweeps * 1e3, 1)
-        del grid
-        # the same loop on a grid whose storage the library owns: each sweep writes a second buffer,
-        # copies the border and swaps, instead of evaluating into a temporary and copying back
-        grid = ctx.array(torch.rand(8192, 8192, device="cuda")).copy()
-        ms = timed(lambda: wl.jacobi(gr, grid, sweeps), 5, warm=1)
-        extras["jacobi_owned_8192_GBps_per_sweep"] = round((4 * 8192 * 8192 + 4 * 8190 * 8190) / (ms / sweeps * 1e-3) / 1e9, 1)
-        extras["jacobi_owned_8192_us_per_sweep"] = round(ms / sweeps * 1e3, 1)
-        del grid
-        torch.cuda.empty_cache()
+        for label, owned in (("jacobi_8192", False), ("jacobi_owned_8192", True)):
+            # wrapped: the caller's tensor is the grid's storage; owned: the library's own copy (each sweep writes a
+            # second buffer, copies the border and swaps)
+            grid = ctx.array(torch.rand(8192, 8192, device="cuda"))
+            if owned:
+                grid = grid.copy()
+            ms, blocks = timed(lambda: wl.jacobi(gr, grid, sweeps), 10)
+            extras[label + "_GBps_per_sweep"] = round(jac_bytes / (ms / sweeps * 1e-3) / 1e9, 1)
+            extras[label + "_us_per_sweep"] = round(ms / sweeps * 1e3, 1)
+            rooflines[label] = hbm_roofline("gr_map", jac_bytes, ms / sweeps * 1e3, [b / sweeps for b in blocks], 10 * sweeps)
+            del grid
+            torch.cuda.empty_cache()
         result["supplementary"] = extras
+        result["supplementary_rooflines"] = rooflines
 
     result["stats"] = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in ctx.stats().items()}
     if not args.no_cpu:

@@ -325,6 +325,32 @@ gr_status gr_materialize_into_static(gr_ctx* ctx, gr_array a, void* dptr, size_t
 /* Size in bytes of the static device array behind gr_materialize_into_static. */
 gr_status gr_static_scratch_bytes(size_t* bytes);
 
+/* ---- record once, run many times (Section 4.2, Section 6: at small array sizes the time goes into
+ * everything around the kernels -- recording, partitioning, code generation -- not into the kernels) */
+
+typedef struct gr_program gr_program;
+
+/* Prepares the evaluation of `root` for replay.  The DAG below `root` is partitioned as for
+ * gr_materialize_into (Algorithm 1), its kernels are compiled and loaded, buffers for the stored
+ * results of earlier sub-graphs and for partial results are allocated (the program owns them),
+ * and the launches are written down with their arguments; nothing runs and no node changes.
+ * `leaves` (host array of `nleaves` handles made by gr_array_from_device, each at most once) are
+ * the inputs a run may rebind; every other stored array the request reads stays bound to the
+ * address it has now and must stay alive while the program is used.  The program belongs to the
+ * context and dies with it at the latest. */
+gr_status gr_program_create(gr_ctx* ctx, gr_array root, const gr_array* leaves, int nleaves, gr_program** out);
+
+/* Evaluates the recorded request on new data: leaf_ptrs (host array, one device pointer per
+ * rebindable leaf, in the order given to gr_program_create) point at arrays of the same element
+ * type, shape and strides as the leaves the program was made from; the result is written to the
+ * C-contiguous device buffer out_ptr (GR_ERR_ALIAS if it overlaps an input).  Launches only:
+ * asynchronous on the context's stream, no planning, no allocation, no node is touched.  Runs
+ * of one program are ordered by the stream; its internal buffers make concurrent runs on
+ * different streams unsafe. */
+gr_status gr_program_run(gr_program* prog, void* const* leaf_ptrs, void* out_ptr);
+
+gr_status gr_program_destroy(gr_program* prog);
+
 /* Slice assignment dst[...] = value with NumPy semantics (Listing 6 of the
  * paper: center[:] = 0.2*(center+north+east+west+south)).  `dst` must be a
  * materialised array or a slice/transpose view of one (the storage is

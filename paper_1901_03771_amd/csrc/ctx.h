@@ -11,6 +11,26 @@
 
 #include "ir.h"
 
+// A request recorded once for replay (gr_program_*): the kernel launches of its sub-graph list with
+// their argument blocks, and where in those blocks the addresses of the rebindable leaves and of
+// the output go.
+struct gr_program {
+  gr_ctx* ctx = nullptr;
+  struct Launch {
+    hipFunction_t fn = nullptr;
+    std::string name;
+    unsigned grid = 0;
+    std::vector<uint64_t> args;
+    std::vector<std::pair<int, int>> patch;  // (argument slot, source): source k >= 0 = leaf k, -1 = the output
+  };
+  std::vector<Launch> launches;
+  std::vector<std::pair<void*, size_t>> buffers;  // stored results of earlier sub-graphs and workspaces: owned
+  std::vector<const gr::Node*> leaf_nodes;        // (only while recording)
+  std::vector<size_t> leaf_bytes;                 // extent of each rebindable leaf from its address, for the overlap check
+  size_t out_bytes = 0;
+  std::vector<std::pair<int, int>> cur_patch;     // provenance of the argument block being filled (while recording)
+};
+
 struct gr_ctx {
   int device = -1;
   hipStream_t stream = nullptr;
@@ -93,6 +113,10 @@ struct gr_ctx {
   unsigned char* static_base = nullptr;
   size_t static_cap = 0, static_used = 0;
   bool static_mode = false;
+
+  // gr_program_create: the request being recorded instead of executed, and the programs alive
+  gr_program* capture = nullptr;
+  std::vector<gr_program*> programs;
 
   // profiling
   struct ProfRec {

@@ -37,6 +37,7 @@ static __typeof__(&gr_materialize) p_materialize;
 static __typeof__(&gr_materialize_into) p_materialize_into;
 static __typeof__(&gr_materialize_into_static) p_materialize_into_static;
 static __typeof__(&gr_is_materialized) p_is_materialized;
+static __typeof__(&gr_program_run) p_program_run;
 static __typeof__(&gr_release) p_release;
 static __typeof__(&gr_reduce) p_reduce;
 static __typeof__(&gr_ndim) p_ndim;
@@ -394,6 +395,22 @@ static PyObject* mod_reduce(PyObject* m, PyObject* args) {
   return new_array(Py_TYPE(a), x->ctx, out, x->owner, NULL, 0);
 }
 
+/* program_run(program address, tuple of input addresses, output address) -> status: gr_program_run without
+ * ctypes in between (a replayed request of a small array costs less than marshalling its arguments twice) */
+static PyObject* mod_program_run(PyObject* m, PyObject* args) {
+  unsigned long long prog, out;
+  PyObject* ptrs;
+  if (!PyArg_ParseTuple(args, "KO!K", &prog, &PyTuple_Type, &ptrs, &out)) return NULL;
+  void* v[64];
+  Py_ssize_t n = PyTuple_GET_SIZE(ptrs);
+  if (n > 64) { PyErr_SetString(PyExc_ValueError, "more than 64 inputs"); return NULL; }
+  for (Py_ssize_t i = 0; i < n; ++i) {
+    v[i] = PyLong_AsVoidPtr(PyTuple_GET_ITEM(ptrs, i));
+    if (!v[i] && PyErr_Occurred()) return NULL;
+  }
+  return PyLong_FromLong(p_program_run((gr_program*)(uintptr_t)prog, v, (void*)(uintptr_t)out));
+}
+
 static PyNumberMethods array_as_number = {
     .nb_add = nb_add, .nb_subtract = nb_sub, .nb_multiply = nb_mul, .nb_true_divide = nb_div,
     .nb_negative = nb_neg, .nb_absolute = nb_abs, .nb_power = nb_pow, .nb_matrix_multiply = nb_matmul,
@@ -464,7 +481,8 @@ static PyObject* mod_bind(PyObject* m, PyObject* d) {
       !take_address(d, "gr_ndim", (void**)&p_ndim) || !take_address(d, "gr_shape", (void**)&p_shape) ||
       !take_address(d, "gr_materialize_into", (void**)&p_materialize_into) ||
       !take_address(d, "gr_materialize_into_static", (void**)&p_materialize_into_static) ||
-      !take_address(d, "gr_is_materialized", (void**)&p_is_materialized))
+      !take_address(d, "gr_is_materialized", (void**)&p_is_materialized) ||
+      !take_address(d, "gr_program_run", (void**)&p_program_run))
     return NULL;
   Py_RETURN_NONE;
 }
@@ -484,6 +502,7 @@ static PyMethodDef module_methods[] = {
     {"unary", mod_unary, METH_VARARGS, "unary(op, a): gr_unary"},
     {"binary", mod_binary, METH_VARARGS, "binary(op, a, b): gr_binary / gr_binary_scalar"},
     {"reduce", mod_reduce, METH_VARARGS, "reduce(op, a, axis, keepdims): gr_reduce"},
+    {"program_run", mod_program_run, METH_VARARGS, "program_run(program, input addresses, output address) -> status: gr_program_run"},
     {"bind", mod_bind, METH_O, "bind({name: address}): entry points of the loaded library"},
     {"set_hooks", mod_set_hooks, METH_VARARGS, "set_hooks(binary, getitem, setitem, pow, reduce): Python fallbacks"},
     {NULL, NULL, 0, NULL}};

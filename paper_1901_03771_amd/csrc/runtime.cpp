@@ -354,6 +354,17 @@ gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
 static gr_status launch(gr_ctx* c, hipFunction_t fn, const std::string& name, int64_t grid, std::vector<uint64_t>& args) {
   if (grid <= 0) return GR_OK;
   if (grid > 0x7fffffffLL) return fail(c, GR_ERR_UNSUPPORTED, "launch: grid too large");
+  if (c->capture) {
+    // recorded for replay instead of launched
+    gr_program::Launch l;
+    l.fn = fn;
+    l.name = name;
+    l.grid = (unsigned)grid;
+    l.args = args;
+    l.patch = c->capture->cur_patch;
+    c->capture->launches.push_back(std::move(l));
+    return GR_OK;
+  }
   if (c->device < 0) { c->stats.kernel_launches++; return GR_OK; }  // dry run: everything but the launch itself
   size_t sz = args.size() * sizeof(uint64_t);
   void* extra[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, args.data(), HIP_LAUNCH_PARAM_BUFFER_SIZE, &sz, HIP_LAUNCH_PARAM_END};
@@ -378,17 +389,28 @@ static gr_status launch(gr_ctx* c, hipFunction_t fn, const std::string& name, in
 // Fills one sub-graph's block of the kernel argument array.
 // `fresh` / `fresh_ptr`: a node whose buffer is being written by this very launch (the first
 // sub-graph's result inside a fused pair) and therefore has no data pointer yet.
+// Stands for "the caller's output buffer" while a request is recorded for replay.
+static void* const kReplayOut = (void*)(uintptr_t)0x10;
+
+// `slot0`: position of this block inside the launch's whole argument array (a fused pair has two blocks).
 static gr_status fill_args(gr_ctx* c, const GroupPlan& g, const ArgLayout& L, void* out_ptr, uint64_t* s,
-                           const Node* fresh = nullptr, void* fresh_ptr = nullptr) {
+                           const Node* fresh = nullptr, void* fresh_ptr = nullptr, int slot0 = 0) {
   for (size_t gi = 0; gi < g.groups.size(); ++gi) {
     const AccessGroup& ag = g.groups[gi];
     void* data = ag.leaf == fresh ? fresh_ptr : ag.leaf->data;
     if (!data && ag.leaf->count() > 0) return fail(c, GR_ERR_HIP, "launch: a leaf has no data");
     s[L.ptr[gi]] = (uint64_t)(uintptr_t)data;
+    if (c->capture) {
+      if (data == kReplayOut) c->capture->cur_patch.push_back({slot0 + L.ptr[gi], -1});
+      else
+        for (size_t k = 0; k < c->capture->leaf_nodes.size(); ++k)
+          if (c->capture->leaf_nodes[k] == ag.leaf) { c->capture->cur_patch.push_back({slot0 + L.ptr[gi], (int)k}); break; }
+    }
     s[L.base[gi]] = (uint64_t)ag.base;
     for (int k2 = 0; k2 < L.ncoef[gi]; ++k2) s[L.coef[gi] + k2] = (uint64_t)ag.coef[k2];
   }
   s[L.out] = (uint64_t)(uintptr_t)out_ptr;
+  if (c->capture && out_ptr == kReplayOut) c->capture->cur_patch.push_back({slot0 + L.out, -1});
   for (int k2 = 0; k2 < g.rank; ++k2) s[L.dims + k2] = (uint64_t)g.dims[k2];
   for (size_t i = 0; i < g.consts.size(); ++i) {
     const ConstSlot& cs = g.consts[i];
@@ -429,6 +451,14 @@ static gr_status get_workspace(gr_ctx* c, const GroupPlan& g, void** ws) {
     *ws = ctx_alloc(c, need);
     return *ws ? GR_OK : fail(c, GR_ERR_OOM, "the static scratch array is too small for this request's partial results");
   }
+  if (c->capture) {
+    // a recorded request keeps workspaces of its own: replays must not depend on what the context's
+    // shared workspace is used for in between
+    *ws = ctx_alloc(c, need);
+    if (!*ws) return fail(c, GR_ERR_OOM, "workspace allocation failed");
+    c->capture->buffers.push_back({*ws, need});
+    return GR_OK;
+  }
   if (need > c->workspace_bytes) {
     if (c->workspace) ctx_free(c, c->workspace, c->workspace_bytes);
     c->workspace = ctx_alloc(c, need);
@@ -444,6 +474,7 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
   ArgLayout L2;
   if (g.pair) L2 = arg_layout(*g.pair);
   std::vector<uint64_t> s(L.total + (g.pair ? L2.total : 0), 0);
+  if (c->capture) c->capture->cur_patch.clear();
   gr_status fst = fill_args(c, g, L, out_ptr, s.data());
   if (fst != GR_OK) return fst;
   void* ws = nullptr;
@@ -543,7 +574,7 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
         // one pass over the matrix for both contractions; the second block of arguments is the
         // column-accumulate sub-graph's (read by the combine kernel)
         const GroupPlan& p = *g.pair;
-        fst = fill_args(c, p, L2, pair_out_ptr, s.data() + L.total, g.root, out_ptr);
+        fst = fill_args(c, p, L2, pair_out_ptr, s.data() + L.total, g.root, out_ptr, L.total);
         if (fst != GR_OK) return fst;
         gr_status wst = get_workspace(c, g, &ws);
         if (wst != GR_OK) return wst;
@@ -748,11 +779,130 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
   return GR_OK;
 }
 
+// Runs the planner's sub-graph list of `root` with recording switched on (c->capture): kernels are
+// compiled and loaded, stored results of earlier sub-graphs and workspaces are allocated for the
+// program to keep, every launch is written down instead of issued, and the nodes are left as
+// they were (nothing becomes materialised, no input is released).
+static gr_status record_plan(gr_ctx* c, Plan* plan, Node* root) {
+  gr_program* P = c->capture;
+  for (auto& gp : plan->groups) {
+    gr_status pst = prepare_group(c, *gp);  // all compilations of the request start together
+    if (pst != GR_OK) return pst;
+  }
+  std::vector<Node*> bound;
+  gr_status st = GR_OK;
+  for (auto& gp : plan->groups) {
+    GroupPlan& g = *gp;
+    gr_ctx::Kernel* k = nullptr;
+    st = compile_group(c, g, &k);
+    if (st != GR_OK) break;
+    Node* roots[2] = {g.root, g.pair ? g.pair->root : nullptr};
+    void* outs[2] = {nullptr, nullptr};
+    for (int q = 0; q < 2 && roots[q] && st == GR_OK; ++q) {
+      if (roots[q] == root) { outs[q] = kReplayOut; continue; }
+      const size_t nb = (size_t)roots[q]->count() * itemsize(roots[q]->dtype);
+      outs[q] = ctx_alloc(c, nb);
+      if (!outs[q]) st = fail(c, GR_ERR_OOM, "allocator returned NULL");
+      else P->buffers.push_back({outs[q], nb});
+    }
+    if (st != GR_OK) break;
+    st = launch_group(c, g, k, outs[0], outs[1]);
+    if (st != GR_OK) break;
+    for (int q = 0; q < 2 && roots[q]; ++q) {
+      Node* r = roots[q];
+      if (has_storage(r)) continue;
+      // visible to the later sub-graphs of this recording only
+      r->data = outs[q];
+      r->owns_data = false;
+      r->alloc_bytes = 0;
+      r->offset = 0;
+      int64_t sstride = 1;
+      for (int d = r->ndim - 1; d >= 0; --d) { r->strides[d] = sstride; sstride *= r->shape[d]; }
+      r->materialized = true;
+      r->planned = false;
+      bound.push_back(r);
+    }
+  }
+  clear_planned(plan);
+  for (Node* r : bound) { r->data = nullptr; r->materialized = false; }
+  return st;
+}
+
+static void program_free(gr_ctx* c, gr_program* P) {
+  for (auto& b : P->buffers) ctx_free(c, b.first, b.second);
+  for (size_t i = 0; i < c->programs.size(); ++i)
+    if (c->programs[i] == P) { c->programs.erase(c->programs.begin() + i); break; }
+  delete P;
+}
+
 }  // namespace gr
 
 using namespace gr;
 
 extern "C" {
+
+gr_status gr_program_create(gr_ctx* ctx, gr_array root, const gr_array* leaves, int nleaves, gr_program** out) {
+  if (!ctx || !out || nleaves < 0 || (nleaves > 0 && !leaves)) return GR_ERR_ARG;
+  Node* x = lookup(ctx, root);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "program_create: bad handle");
+  if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "program_create: a bare scalar has no array value");
+  if (ctx->device < 0 && !ctx->opt_dry_run) return fail(ctx, GR_ERR_NODEVICE, "context has no device");
+  std::unique_ptr<gr_program> P(new gr_program());
+  P->ctx = ctx;
+  for (int i = 0; i < nleaves; ++i) {
+    const Node* l = lookup(ctx, leaves[i]);
+    if (!l) return fail(ctx, GR_ERR_HANDLE, "program_create: bad leaf handle");
+    if (l->kind != Kind::LEAF || !l->data) return fail(ctx, GR_ERR_ARG, "program_create: a rebindable input must be an array made by gr_array_from_device");
+    for (const Node* m : P->leaf_nodes) if (m == l) return fail(ctx, GR_ERR_ARG, "program_create: the same leaf is listed twice");
+    uintptr_t lo, hi;
+    extent_of(l, &lo, &hi);
+    if (lo < (uintptr_t)l->data) return fail(ctx, GR_ERR_UNSUPPORTED, "program_create: a rebindable input reaches below its address (negative strides)");
+    P->leaf_nodes.push_back(l);
+    P->leaf_bytes.push_back(hi > (uintptr_t)l->data ? (size_t)(hi - (uintptr_t)l->data) : 0);
+  }
+  P->out_bytes = (size_t)x->count() * itemsize(x->dtype);
+  Plan plan;
+  gr_status st = make_plan(ctx, x, &plan);
+  if (st != GR_OK) return st;
+  ctx->capture = P.get();
+  st = record_plan(ctx, &plan, x);
+  ctx->capture = nullptr;
+  clear_planned(&plan);
+  P->leaf_nodes.clear();
+  P->cur_patch.clear();
+  if (st != GR_OK) {
+    for (auto& b : P->buffers) ctx_free(ctx, b.first, b.second);
+    return st;
+  }
+  ctx->programs.push_back(P.get());
+  *out = P.release();
+  return GR_OK;
+}
+
+gr_status gr_program_run(gr_program* prog, void* const* leaf_ptrs, void* out_ptr) {
+  if (!prog) return GR_ERR_ARG;
+  gr_ctx* c = prog->ctx;
+  const size_t nl = prog->leaf_bytes.size();
+  if ((nl > 0 && !leaf_ptrs) || (prog->out_bytes > 0 && !out_ptr)) return fail(c, GR_ERR_ARG, "program_run: NULL pointer");
+  const uintptr_t olo = (uintptr_t)out_ptr, ohi = olo + prog->out_bytes;
+  for (size_t k = 0; k < nl; ++k) {
+    if (!leaf_ptrs[k] && prog->leaf_bytes[k]) return fail(c, GR_ERR_ARG, "program_run: NULL input");
+    const uintptr_t lo = (uintptr_t)leaf_ptrs[k], hi = lo + prog->leaf_bytes[k];
+    if (lo < ohi && olo < hi) return fail(c, GR_ERR_ALIAS, "output buffer overlaps an input of the request");
+  }
+  for (gr_program::Launch& l : prog->launches) {
+    for (const auto& pt : l.patch) l.args[pt.first] = (uint64_t)(uintptr_t)(pt.second < 0 ? out_ptr : leaf_ptrs[pt.second]);
+    gr_status st = launch(c, l.fn, l.name, l.grid, l.args);
+    if (st != GR_OK) return st;
+  }
+  return GR_OK;
+}
+
+gr_status gr_program_destroy(gr_program* prog) {
+  if (!prog) return GR_ERR_ARG;
+  program_free(prog->ctx, prog);
+  return GR_OK;
+}
 
 gr_status gr_ctx_create(gr_ctx** out, int device, void* hip_stream) {
   if (!out) return GR_ERR_ARG;
@@ -795,6 +945,7 @@ gr_status gr_ctx_destroy(gr_ctx* ctx) {
     delete n;
   }
   ctx->nodes.clear();
+  while (!ctx->programs.empty()) program_free(ctx, ctx->programs.back());
   if (ctx->workspace) ctx_free(ctx, ctx->workspace, ctx->workspace_bytes);
   for (auto& kv : ctx->cache) if (kv.second.module) (void)hipModuleUnload(kv.second.module);
   for (auto& p : ctx->prof) { (void)hipEventDestroy(p.e0); (void)hipEventDestroy(p.e1); }

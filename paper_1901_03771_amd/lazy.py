@@ -36,7 +36,7 @@ STATUS = {0: "GR_OK", 1: "GR_ERR_HANDLE", 2: "GR_ERR_SHAPE", 3: "GR_ERR_DTYPE", 
 SYMBOLS = [
     "gr_ctx_create", "gr_ctx_destroy", "gr_ctx_set_stream", "gr_ctx_set_allocator", "gr_ctx_set_option", "gr_sync",
     "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose", "gr_reshape",
-    "gr_reduce", "gr_scan", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_materialize_into_static", "gr_static_scratch_bytes", "gr_assign", "gr_ndim", "gr_shape", "gr_dtype_of",
+    "gr_reduce", "gr_scan", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_materialize_into_static", "gr_static_scratch_bytes", "gr_program_create", "gr_program_run", "gr_program_destroy", "gr_assign", "gr_ndim", "gr_shape", "gr_dtype_of",
     "gr_is_materialized", "gr_data_ptr", "gr_retain", "gr_release", "gr_plan_describe", "gr_plan_source",
     "gr_plan_compile", "gr_compile_wait", "gr_stats", "gr_profile_reset", "gr_profile_read", "gr_stream_copy", "gr_stream_read",
 ]
@@ -89,6 +89,7 @@ def lib():
         "gr_scan": [P, I, U64, I, PP(U64)],
         "gr_materialize": [P, U64], "gr_assign": [P, U64, U64], "gr_materialize_into": [P, U64, P, SZ],
         "gr_materialize_into_static": [P, U64, P, SZ], "gr_static_scratch_bytes": [PP(SZ)],
+        "gr_program_create": [P, U64, PP(U64), I, PP(P)], "gr_program_run": [P, PP(P), P], "gr_program_destroy": [P],
         "gr_ndim": [P, U64, PP(I)], "gr_shape": [P, U64, PP(I64)], "gr_dtype_of": [P, U64, PP(I)],
         "gr_is_materialized": [P, U64, PP(I)], "gr_data_ptr": [P, U64, PP(P), PP(I64)],
         "gr_retain": [P, U64], "gr_release": [P, U64],
@@ -149,10 +150,17 @@ class Context:
             raise GrError(st, L.gr_last_error(None).decode())
         self._addr = self._p.value or 0  # what the C fast paths read; 0 once closed
         self.device = int(device)
+        self._programs = set()  # recorded requests (Program): they die with the context
         _LIVE.add(self)
+
+    def program(self, root: "Array", leaves: Sequence["Array"]) -> "Program":
+        """Records the evaluation of ``root`` for replay on new data in place of ``leaves`` (gr_program_create)."""
+        return Program(root, leaves)
 
     def close(self):
         self._addr = 0
+        for prog in list(getattr(self, "_programs", ())):
+            prog._p = None              # the library frees a context's programs with it
         if self._p:
             lib().gr_ctx_destroy(self._p)
             self._p = ctypes.c_void_p()
@@ -285,6 +293,41 @@ class _DeviceExport:
         self.owner = owner  # keeps the handle, hence the storage, alive
         self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": typestr, "data": (ptr, False), "version": 2,
                                          "strides": byte_strides if len(shape) else None}
+
+
+class Program:
+    """A request recorded once and run many times on new data (gr_program_*): ``root`` is evaluated with the
+    tensors given to ``run`` in place of ``leaves`` (same element type, shape and strides), launches only."""
+
+    def __init__(self, root: "Array", leaves: Sequence["Array"]):
+        self.ctx = root.ctx
+        n = len(leaves)
+        arr = (ctypes.c_uint64 * builtins.max(n, 1))(*[l.h for l in leaves])
+        p = ctypes.c_void_p()
+        self.ctx.check(lib().gr_program_create(self.ctx._p, root.h, arr, n, ctypes.byref(p)))
+        self._p = p.value
+        self._n = n
+        self._keep = root._owner        # inputs that are not rebound stay bound to their memory
+        self.ctx._programs.add(self)
+
+    def run(self, tensors, out):
+        """Launches the recorded kernels on ``tensors`` (one per rebindable leaf, in order) into ``out``."""
+        if len(tensors) != self._n:
+            raise ValueError(f"expected {self._n} inputs")
+        ptrs = tuple(t.data_ptr() for t in tensors)
+        if _fastbind is not None:
+            st = _fastbind.program_run(self._p, ptrs, out.data_ptr())
+        else:
+            st = _lib.gr_program_run(self._p, (ctypes.c_void_p * builtins.max(self._n, 1))(*ptrs), out.data_ptr())
+        if st:
+            self.ctx.check(st)
+        return out
+
+    def close(self):
+        if self._p and self.ctx._p:
+            lib().gr_program_destroy(self._p)
+        self._p = None
+        self.ctx._programs.discard(self)
 
 
 class _PyArrayBase:
@@ -473,7 +516,7 @@ def _bind_fast_paths(L):
         return
     names = ["gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose", "gr_dot", "gr_assign",
              "gr_materialize", "gr_release", "gr_reduce", "gr_ndim", "gr_shape", "gr_materialize_into",
-             "gr_materialize_into_static", "gr_is_materialized"]
+             "gr_materialize_into_static", "gr_is_materialized", "gr_program_run"]
     _fastbind.bind({n: ctypes.cast(getattr(L, n), ctypes.c_void_p).value for n in names})
     _fastbind.set_hooks(_binary_slow, slice_, _setitem_slow, _pow_slow, _reduce_slow)
 

@@ -658,6 +658,62 @@ def test_materialized_node_is_reused_not_recomputed(env):
     assert_elementwise(got, ref)
 
 
+def test_recorded_programs_replay_on_new_data(env):
+    # record once (partition, compile, allocate), then only launch: every replay is compared with the oracle
+    # run on that replay's inputs
+    gr, ctx, torch = env
+    cases = [
+        ("chain", wl.chain, lambda s: wl.make_inputs("chain", salt=s, n=100_003), ("a", "b"), "elementwise"),
+        ("logreg (one-pass pair, stored residual, partial vectors)", wl.logreg, lambda s: wl.make_inputs("logreg", salt=s, rows=3001, cols=200), ("X", "w", "y"), "reduction"),
+        ("softmax of a product (two sub-graphs)", lambda xp, a, b: wl.softmax(xp, a @ b), lambda s: dict(a=_rand((300, 70), 500 + s), b=_rand((70, 130), 600 + s)), ("a", "b"), "reduction"),
+        ("two-stage sum", lambda xp, a: xp.sum(xp.sqrt(abs(a))), lambda s: dict(a=_rand((1 << 21,), 700 + s)), ("a",), "reduction"),
+        ("chunked prefix sum", lambda xp, a: xp.cumsum(abs(a), 0), lambda s: dict(a=_rand((300_001,), 800 + s)), ("a",), "reduction"),
+        ("stencil", wl.stencil, lambda s: wl.make_inputs("stencil", salt=s, rows=151, cols=1234), ("I",), "exact"),
+    ]
+    for name, prog, make, order, bar in cases:
+        first = make(0)
+        keep = {k: torch.from_numpy(v).cuda() for k, v in first.items()}
+        leaves = {k: ctx.array(t) for k, t in keep.items()}
+        lazy = prog(gr, **leaves)
+        program = ctx.program(lazy, [leaves[k] for k in order])
+        assert not lazy.is_materialized, "recording a program evaluates nothing"
+        out = torch.empty(lazy.shape, dtype=torch.float32, device="cuda")
+        launches = ctx.stats()["kernel_launches"]
+        for s in (1, 2, 0):
+            arrays = make(s)
+            dev = [torch.from_numpy(arrays[k]).cuda() for k in order]
+            out.fill_(float("nan"))
+            before = ctx.stats()
+            program.run(dev, out)
+            after = ctx.stats()
+            assert after["nodes_recorded"] == before["nodes_recorded"] and after["bytes_allocated"] == before["bytes_allocated"]
+            got = out.cpu().numpy()
+            ref = prog(ora, **{k: ora.array(v) for k, v in arrays.items()}).numpy()
+            if bar == "exact":
+                assert np.array_equal(got, ref), name
+            elif bar == "elementwise":
+                assert_elementwise(got, ref, floor=chain_floor(arrays), what=f"replayed {name}")
+            else:
+                assert_reduction(got, ref, what=f"replayed {name}", scale=track.of(prog, arrays)[1])
+        assert ctx.stats()["kernel_launches"] > launches
+        program.close()
+    # an input that is not rebound stays bound to its memory; the output may not overlap an input
+    arrays = wl.make_inputs("normalize", rows=64, cols=500)
+    keep = {k: torch.from_numpy(v).cuda() for k, v in arrays.items()}
+    leaves = {k: ctx.array(t) for k, t in keep.items()}
+    program = ctx.program(wl.normalize(gr, **leaves), [leaves["X"]])
+    x2 = wl.make_inputs("normalize", salt=3, rows=64, cols=500)["X"]
+    t2 = torch.from_numpy(x2).cuda()
+    out = torch.empty(64, 500, device="cuda")
+    program.run([t2], out)
+    ref = wl.normalize(ora, **{k: ora.array(v) for k, v in dict(arrays, X=x2).items()}).numpy()
+    assert np.array_equal(out.cpu().numpy(), ref)
+    with pytest.raises(gr.GrError) as ei:
+        program.run([t2], t2)
+    assert ei.value.code == "GR_ERR_ALIAS"
+    program.close()
+
+
 def test_recorded_arrays_keep_their_leaves_alive(env):
     # z = ctx.array(temporary) * 2 drops the leaf's handle and the tensor at once; the recorded array must keep
     # the tensor's memory from going back to torch's allocator until it has been evaluated
