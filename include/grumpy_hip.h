@@ -68,6 +68,7 @@ typedef enum {
   GR_NEG = 0, GR_ABS = 1, GR_EXP = 2, GR_LOG = 3, GR_SQRT = 4, GR_SQUARE = 5, GR_TANH = 6, GR_ERF = 7,
   /* binary, NumPy broadcasting */
   GR_ADD = 16, GR_SUB = 17, GR_MUL = 18, GR_DIV = 19, GR_MAXIMUM = 20, GR_MINIMUM = 21,
+  GR_POW_INT = 22, /* array ** integer scalar: only the exponent 2 (recorded as GR_SQUARE, as NumPy evaluates x**2); anything else GR_ERR_UNSUPPORTED */
   /* reductions (Section 3.2: associative and commutative binary operator) */
   GR_SUM = 32, GR_MAX = 33, GR_MIN = 34
 } gr_op;
@@ -99,26 +100,14 @@ gr_status gr_ctx_set_stream(gr_ctx* ctx, void* hip_stream);
 gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* user),
                                void (*free_)(void* ptr, void* user), void* user);
 
-/* Integer options (host string key):
+/* Integer options (host string key).  The keys below change WHAT the library does; keys that only
+ * tune HOW a kernel is scheduled (patch sizes, lanes per row, slab counts, tile shapes, thresholds)
+ * are listed in grumpy_hip_tuning.h and go through the same call.
  *   "fusion"          1 (default) fuse per Algorithm 1 as relaxed below; 0 =
  *                     one kernel per recorded op, every intermediate stored
  *                     (the eager execution model the paper starts from)
  *   "rowred_max_cols" longest row (elements) a reduction may keep resident
  *                     in registers and still fuse with its consumers
- *   "map_rows", "map_chunks"   per-lane patch of the map skeleton (0 = auto)
- *   "map_bx"          lanes of a workgroup along the columns (power of two <= 256; 0 = auto)
- *   "rowred_threads"  lanes that hold one row: 16, 64, 128 or 256 (0 = auto)
- *   "gemv_slabs", "gemv_unroll"  column-accumulate contraction: number of row
- *                     slabs (first-stage partial vectors) and rows in flight
- *                     per lane, 8 or 16 (0 = auto)
- *   "nontemporal"     1 (default) = loads of arrays that are read once carry
- *                     the non-temporal hint, and so do the vector stores of an
- *                     requested value of 192 MiB or more (not of intermediate
- *                     results of the request; except in kernels that read a
- *                     transposed operand through LDS tiles when output rows
- *                     are not 64-byte aligned); 0 = none; 2 = every
- *                     vector load; 8 = vector stores only; 9 = the loads of 1
- *                     and every vector store
  *   "gemv_pair"       1 (default) = a contraction A.v whose epilogue result r
  *                     feeds the contraction A^T.r runs with it in one pass
  *                     over A; 0 = two passes
@@ -151,35 +140,10 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     an array whose storage the library owns, writes a second
  *                     buffer, copies the cells outside the box and swaps the
  *                     two buffers; 0 = always evaluate, then copy
- *   "stage_transposed" 1 (default) = a map sub-graph reads operands whose contiguous
- *                     dimension is the row dimension of the iteration space
- *                     (transposed views) through tiles transposed in LDS;
- *                     0 = strided loads
- *   "stage_rows"      rows of such a tile (it has 64 columns): 0 (default) = 128
- *                     where the iteration space has 128 rows or more, else 64;
- *                     64 = always 64
- *   "stage_diag"      1 (default) = kernels with such tiles take row blocks
- *                     diagonally and give each XCD a contiguous range of column
- *                     blocks; 0 = row-major tile order
- *   "rowred_rows"     rows a lane group of a row-resident reduction takes per
- *                     launch when rows are short (at most 64 elements) and reduce
- *                     to one value each: 0 (default) = 4 for 2^18 rows or more,
- *                     1 = always one, 2..8 = that many
- *   "gemm_bn"         width of the output tile of the matrix-product kernel: 32 or
- *                     128; 0 (default) = 32 for results of at most 96 columns and
- *                     where the last 128-wide tile would be more than half empty
  *   "pool_limit"      bytes the default pool may hold before a request for a size
  *                     it has no free block of makes it return its free blocks of
  *                     other sizes to the device first; 0 (default) = no limit
  *                     (the same happens whenever the device runs out of memory)
- *   "scan_min_threads", "scan_threads"
- *                     a scan along a non-contiguous axis gives each thread one
- *                     line (four neighbouring lines with dwordx4 loads); with
- *                     fewer threads than scan_min_threads the lines are cut into
- *                     chunks so that about scan_threads threads run, at the
- *                     price of a second read of the input; 0 (default) =
- *                     16384 / 65536 with dwordx4 loads, 32768 / 131072 with
- *                     scalar loads
  *   "plan_cache"      1 (default) = a request whose sub-DAG has the structure of an
  *                     earlier one (node kinds, shapes, strides of stored arrays,
  *                     slice bounds, scalar values, sharing of operands, recording
@@ -432,15 +396,6 @@ gr_status gr_stats(gr_ctx* ctx, gr_stats_t* out);
  * gr_profile_reset. */
 gr_status gr_profile_reset(gr_ctx* ctx);
 gr_status gr_profile_read(gr_ctx* ctx, const char* prefix, uint64_t* launches, double* total_ms);
-
-/* ---- plain streaming kernels (practical HBM ceiling of the box) --------- */
-
-/* dst[i] = src[i] for `bytes` bytes (multiple of 16; both device pointers,
- * 16-byte aligned, not overlapping), launched on the context's stream. */
-gr_status gr_stream_copy(gr_ctx* ctx, void* dst, const void* src, size_t bytes);
-/* Reads `bytes` bytes (multiple of 16) and writes one 4-byte word per
- * workgroup to `sink` (device pointer, at least 16 KiB). */
-gr_status gr_stream_read(gr_ctx* ctx, const void* src, size_t bytes, void* sink);
 
 #ifdef __cplusplus
 }

@@ -1184,6 +1184,122 @@ void gen_scan(Em& e) {
     return;
   }
 
+
+  if (g.scan_mode == 2) {
+    // ---- mode 2: long contiguous lines in ONE pass over the input.  A workgroup owns a tile of TU x 1024
+    // consecutive elements of a line, keeps it in registers, scans it, publishes the tile's total and
+    // needs, before it may store, the combination of everything before its tile.  Tiles form groups
+    // of 128; the last tile of a group also publishes the group's total.  A tile's offset is
+    //     fold(totals of the earlier groups) (+) fold(totals of the earlier tiles of its own group),
+    // each fold taken lane by lane in a fixed pattern, so the association -- and with it every float
+    // result -- does not depend on timing.  A published cell is one 8-byte word (valid bit, value)
+    // written and read with relaxed agent-scope atomics.  Waiting is bounded: a workgroup that runs
+    // out of polls computes its offset from the input itself, so every wave terminates whatever order
+    // the tiles are dispatched in (in dispatch order, which is what happens, everything a tile waits
+    // for is already running).  A small kernel clears the cells before every launch.
+    const int TU = (int)(g.scan_chunk / 1024);  // blocks of 1024 elements per tile
+    const std::string bits = ph.out_dtype == GR_F32 ? "__float_as_uint" : "(unsigned)";
+    const std::string unbits = ph.out_dtype == GR_F32 ? "__uint_as_float" : "(int)";
+    kernel_head(e, "gr_scan_clear");
+    e.o << "  const long long LINES = " << e.S(e.L.extra) << ", NCHUNK = " << e.S(e.L.extra + 3) << ";\n"
+           "  const long long n = LINES * NCHUNK + LINES * ((NCHUNK + 127) / 128);\n"   // one cell per tile and per group
+           "  GM unsigned long long* const w = (GM unsigned long long*)" << e.slot(e.L.extra + 2) << ";\n"
+           "  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (i < n) w[i] = 0ull;\n}\n";
+    // wave-wide inclusive scan with row shifts inside rows of 16 lanes and two row broadcasts; lanes without a source take the identity
+    e.o << "#define GR_DPP(idn, v, ctrl, rmask) " << unbits << "((unsigned)__builtin_amdgcn_update_dpp((int)" << bits << "(idn), (int)" << bits << "(v), ctrl, rmask, 0xf, false))\n";
+    e.o << "static __device__ __forceinline__ " << TA << " gr_wscan(" << TA << " x) {\n  const " << TA << " idn = " << ident << ";\n"
+           "  x = gr_comb0(GR_DPP(idn, x, 0x111, 0xf), x);\n  x = gr_comb0(GR_DPP(idn, x, 0x112, 0xf), x);\n"
+           "  x = gr_comb0(GR_DPP(idn, x, 0x114, 0xf), x);\n  x = gr_comb0(GR_DPP(idn, x, 0x118, 0xf), x);\n"
+           "  x = gr_comb0(GR_DPP(idn, x, 0x142, 0xa), x);\n  x = gr_comb0(GR_DPP(idn, x, 0x143, 0xc), x);\n  return x;\n}\n";
+    e.o << "static __device__ __forceinline__ unsigned long long gr_poll(GM unsigned long long* p, unsigned& polls) {\n"
+           "  unsigned long long w = __hip_atomic_load((unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
+           "  while (!(w >> 32) && polls) { __builtin_amdgcn_s_sleep(8); --polls; w = __hip_atomic_load((unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }\n"
+           "  return w;\n}\n";
+    e.o << "static __device__ __forceinline__ " << TA << " gr_fold(" << TA << " x, " << TA << "* f) {\n"
+           "  x = gr_lanes0(x);\n  if ((threadIdx.x & 63) == 0) f[threadIdx.x >> 6] = x;\n  __syncthreads();\n"
+           "  return gr_comb0(gr_comb0(f[0], f[1]), gr_comb0(f[2], f[3]));\n}\n";
+    kernel_head(e, "gr_scan");
+    head(true);
+    e.o << "  __shared__ " << TA << " gr_wt[" << TU << "][4];\n  __shared__ " << TA << " gr_fs[4][4];\n";
+    e.o << "  const long long cbeg = chunk * CH;\n  const int clen = (int)((cbeg + CH < L) ? CH : L - cbeg);\n";
+    e.o << "  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;\n";
+    e.o << "  " << TA << " v[" << TU << "][4];\n";
+    // positions inside the tile are 32-bit offsets from the tile's first element (one 64-bit base per array)
+    for (size_t gi = 0; gi < g.groups.size(); ++gi)
+      e.o << "  const GM " << cty(g.groups[gi].dtype) << "* const tp" << gi << " = p" << gi << (g.groups[gi].structural_zero[sd] ? "" : " + cbeg") << ";\n";
+    e.o << "  GM " << TA << "* const tpo = po + cbeg;\n";
+    // the whole tile first: TU vector loads per array in flight per lane
+    // (a full tile -- every tile of a line but the last -- takes straight-line code without bounds checks)
+    e.o << "  const bool whole = clen == " << TU * 1024 << ";\n";
+    e.o << "  if (whole) {\n    const int cend = " << TU * 1024 << ";\n";
+    for (size_t gi = 0; gi < g.groups.size(); ++gi) e.o << "    const GM " << cty(g.groups[gi].dtype) << "* const p" << gi << " = tp" << gi << ";\n";
+    e.o << "#pragma unroll\n    for (int u = 0; u < " << TU << "; ++u) {\n      const int c = u * 1024 + threadIdx.x * 4;\n";
+    tile_loads("      ");
+    e.o << "#pragma unroll\n      for (int j = 0; j < 4; ++j) {\n";
+    emit_scalar_program(e, g.prog, {ph.value}, tile_value, "0.0f", "t", "        ");
+    e.o << "        v[u][j] = " << conv("t" + std::to_string(ph.value)) << ";\n      }\n    }\n  } else {\n    const int cend = clen;\n";
+    for (size_t gi = 0; gi < g.groups.size(); ++gi) e.o << "    const GM " << cty(g.groups[gi].dtype) << "* const p" << gi << " = tp" << gi << ";\n";
+    e.o << "#pragma unroll\n    for (int u = 0; u < " << TU << "; ++u) {\n      const int c = u * 1024 + threadIdx.x * 4;\n";
+    tile_loads("      ");
+    e.o << "#pragma unroll\n      for (int j = 0; j < 4; ++j) {\n        v[u][j] = " << ident << ";\n        if (c + j < cend) {\n";
+    emit_scalar_program(e, g.prog, {ph.value}, tile_value, "0.0f", "t", "          ");
+    e.o << "          v[u][j] = " << conv("t" + std::to_string(ph.value)) << ";\n        }\n      }\n    }\n  }\n";
+    // scan inside the tile: four elements of a lane, the lanes of a wave, then waves and blocks through LDS
+    e.o << "  " << TA << " xs[" << TU << "];\n";
+    e.o << "#pragma unroll\n  for (int u = 0; u < " << TU << "; ++u) {\n"
+           "    v[u][1] = gr_comb0(v[u][0], v[u][1]); v[u][2] = gr_comb0(v[u][1], v[u][2]); v[u][3] = gr_comb0(v[u][2], v[u][3]);\n"
+           "    xs[u] = gr_wscan(v[u][3]);\n    if (lane == 63) gr_wt[u][wave] = xs[u];\n  }\n  __syncthreads();\n";
+    e.o << "  " << TA << " carry = " << ident << ";\n";
+    e.o << "#pragma unroll\n  for (int u = 0; u < " << TU << "; ++u) {\n    " << TA << " b = carry;\n"
+           "    for (int q = 0; q < wave; ++q) b = gr_comb0(b, gr_wt[u][q]);\n"
+           "    { const " << TA << " ex = GR_DPP(" << ident << ", xs[u], 0x138, 0xf); if (lane != 0) b = gr_comb0(b, ex); }\n"
+           "#pragma unroll\n    for (int j = 0; j < 4; ++j) v[u][j] = gr_comb0(b, v[u][j]);\n"
+           "    carry = gr_comb0(carry, gr_comb0(gr_comb0(gr_wt[u][0], gr_wt[u][1]), gr_comb0(gr_wt[u][2], gr_wt[u][3])));\n  }\n";
+    // publish, then collect the offset
+    e.o << "  const long long NGROUP = (NCHUNK + 127) / 128, grp = chunk / 128, gfirst = grp * 128;\n"
+           "  GM unsigned long long* const wq = (GM unsigned long long*)" << e.slot(e.L.extra + 2) << ";\n"
+           "  GM unsigned long long* const wa = wq + line * NCHUNK;\n"
+           "  GM unsigned long long* const wg = wq + LINES * NCHUNK + line * NGROUP;\n"
+           "  if (threadIdx.x == 0) __hip_atomic_store((unsigned long long*)(wa + chunk), (1ull << 32) | " << bits << "(carry), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
+           "  unsigned polls = 1u << 20;\n  int lost = 0;\n"
+           "  if (chunk == gfirst + 127) {\n"
+           "    // last tile of a full group: the group's total, for every later group\n"
+           "    " << TA << " acc = " << ident << ";\n"
+           "    if (threadIdx.x < 128) { const unsigned long long w = gr_poll(wa + gfirst + threadIdx.x, polls); if (w >> 32) acc = " << unbits << "((unsigned)w); else lost = 1; }\n"
+           "    const " << TA << " tot = gr_fold(acc, gr_fs[0]);\n"
+           "    if (!__syncthreads_or(lost) && threadIdx.x == 0) __hip_atomic_store((unsigned long long*)(wg + grp), (1ull << 32) | " << bits << "(tot), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
+           "  }\n"
+           "  " << TA << " p1 = " << ident << ", p2 = " << ident << ";\n"
+           "  // (first the earlier groups, then the earlier tiles of this group: measured faster than waiting for both at once)\n"
+           "  for (long long q = threadIdx.x; q < grp; q += 256) { const unsigned long long w = gr_poll(wg + q, polls); if (w >> 32) p1 = gr_comb0(p1, " << unbits << "((unsigned)w)); else lost = 1; }\n"
+           "  for (long long q = gfirst + threadIdx.x; q < chunk; q += 256) { const unsigned long long w = gr_poll(wa + q, polls); if (w >> 32) p2 = gr_comb0(p2, " << unbits << "((unsigned)w)); else lost = 1; }\n"
+           "  p1 = gr_fold(p1, gr_fs[1]);\n  p2 = gr_fold(p2, gr_fs[2]);\n"
+           "  " << TA << " base = gr_comb0(p1, p2);\n"
+           "  if (__syncthreads_or(lost)) {\n"
+           "    // out of polls: the offset straight from the input (the whole line before this tile)\n"
+           "    " << TA << " acc = " << ident << ";\n    const long long cend = cbeg;\n"
+           "    for (long long t0 = 0; t0 < cbeg; t0 += 1024) {\n      const long long c = t0 + threadIdx.x * 4;\n";
+    tile_loads("      ");
+    e.o << "#pragma unroll\n      for (int j = 0; j < 4; ++j) {\n        if (c + j < cend) {\n";
+    emit_scalar_program(e, g.prog, {ph.value}, tile_value, "0.0f", "t", "          ");
+    e.o << "          acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n        }\n      }\n    }\n"
+           "    base = gr_fold(acc, gr_fs[3]);\n  }\n";
+    {
+      const char* vt = ph.out_dtype == GR_F32 ? "f4u" : "i4u";
+      const std::string st = (g.nt & 8) ? "__builtin_nontemporal_store(ov, (GM " + std::string(vt) + "*)(tpo + c))" : "*(GM " + std::string(vt) + "*)(tpo + c) = ov";
+      e.o << "  if (whole) {\n#pragma unroll\n    for (int u = 0; u < " << TU << "; ++u) {\n      const int c = u * 1024 + threadIdx.x * 4;\n"
+             "      " << vt << " ov; for (int j = 0; j < 4; ++j) ov[j] = gr_comb0(base, v[u][j]); " << st << ";\n    }\n    return;\n  }\n";
+    }
+    e.o << "#pragma unroll\n  for (int u = 0; u < " << TU << "; ++u) {\n    const int c = u * 1024 + threadIdx.x * 4;\n";
+    {
+      const char* vt = ph.out_dtype == GR_F32 ? "f4u" : "i4u";
+      e.o << "    if (c + 4 <= clen) { " << vt << " ov; for (int j = 0; j < 4; ++j) ov[j] = gr_comb0(base, v[u][j]); "
+          << ((g.nt & 8) ? "__builtin_nontemporal_store(ov, (GM " + std::string(vt) + "*)(tpo + c))" : "*(GM " + std::string(vt) + "*)(tpo + c) = ov") << "; }\n"
+             "    else { for (int j = 0; j < 4; ++j) if (c + j < clen) tpo[c + j] = gr_comb0(base, v[u][j]); }\n  }\n}\n";
+    }
+    return;
+  }
+
   // ---- mode 0, kernel 1 of 3: chunk totals (only launched when a line has several chunks)
   kernel_head(e, "gr_scan_sums");
   head(true);

@@ -67,6 +67,7 @@ struct gr_ctx {
   int64_t opt_stage = 1;
   int64_t opt_plan_cache = 1;
   int64_t opt_scan_threads = 0, opt_scan_min_threads = 0;
+  int64_t opt_scan_one_pass = 1;
   uint64_t options_epoch = 0;  // bumped by every gr_ctx_set_option: part of a request's fingerprint
   uintptr_t dry_next = 0x100000;  // fake device addresses handed out by a dry run
 
@@ -92,7 +93,8 @@ struct gr_ctx {
   // run-time compilations in flight (signature -> job), see runtime.cpp
   struct CompileJob {
     std::string src, log, kernel;  // kernel: name of the entry point
-    bool combine = false, scan = false;  // the code object also holds a combine stage / the scan helpers
+    bool combine = false;  // the code object also holds a combine stage
+    int scan = 0;          // ... the helper kernels of a scan (1: chunk totals and offsets, 2: cell clearing of a one-pass scan)
     std::vector<char> code;
     bool ok = false;
     double ms = 0.0;

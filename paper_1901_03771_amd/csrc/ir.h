@@ -12,7 +12,7 @@
 #include <unordered_map>
 #include <vector>
 
-#include "../../include/grumpy_hip.h"
+#include "../../include/grumpy_hip_tuning.h"
 
 namespace gr {
 

@@ -474,7 +474,7 @@ void make_signature(GroupPlan* g) {
   for (int64_t v : {(int64_t)g->kind, (int64_t)g->rank, (int64_t)g->out_dtype, (int64_t)g->out_per_row, (int64_t)g->BX, (int64_t)g->BY,
                     (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads + 1024 * (int64_t)g->row_iters, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask + (((int64_t)g->tail) << 40) + (((int64_t)g->diag) << 44), (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
                     (int64_t)g->red_kept_rank, (int64_t)g->gemv_mode, (int64_t)g->LPR, (int64_t)g->KV, (int64_t)g->mat_group,
-                    (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode + 16 * (int64_t)g->scan_vec, (int64_t)g->out_unit, (int64_t)g->groups.size()})
+                    (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode + 16 * (int64_t)g->scan_vec + (g->scan_mode == 2 ? 256 * g->scan_chunk : 0) /* (a one-pass scan's tile size is compiled in) */, (int64_t)g->out_unit, (int64_t)g->groups.size()})
     put(s, v);
   for (const AccessGroup& ag : g->groups) {
     int64_t cls = (int64_t)ag.dtype;
@@ -773,6 +773,15 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       if (nch > 4096) { chunk = (((L + 4095) / 4096 + 1023) / 1024) * 1024; nch = (L + chunk - 1) / chunk; }
       g->scan_chunk = chunk;
       g->scan_nchunk = (int)nch;
+      // 4-byte running values: one pass over the input with chained tiles of 8192 elements
+      // (option "scan_one_pass" = 0 keeps the three kernels, which read the input twice)
+      // tiles of 8192 elements, 12288 for lines of 2^25 elements and more (measured; option values from 2 on: 1024-element blocks per tile)
+      const int64_t tile = 1024 * (c->opt_scan_one_pass >= 2 ? c->opt_scan_one_pass : (L >= ((int64_t)1 << 25) ? 12 : 8));
+      if (c->opt_scan_one_pass && p.out_dtype != GR_I64 && tile <= 16384 && (L + tile - 1) / tile <= (int64_t)1 << 24) {
+        g->scan_mode = 2;
+        g->scan_chunk = tile;
+        g->scan_nchunk = (int)((L + tile - 1) / tile);
+      }
     }
     // four neighbouring lines per thread where the innermost line dimension is contiguous in every
     // array read and in the output, holds a multiple of four, and all values are 32 bits wide
@@ -1346,7 +1355,7 @@ std::string describe_plan(const Plan& plan) {
       s << "]]";
     }
     if (g.kind == GroupKind::ROWRED) s << " phases=" << g.phases.size() << " row_threads=" << g.row_threads << " NP=" << g.NP << (g.row_iters > 1 ? " rows_per_group=" + std::to_string(g.row_iters) : std::string());
-    if (g.kind == GroupKind::SCAN) s << " mode=" << (g.scan_mode ? "thread-per-line" : "lanes-along-axis") << " lines=" << g.red_out << " length=" << g.red_len << " chunks=" << g.scan_nchunk;
+    if (g.kind == GroupKind::SCAN) s << " mode=" << (g.scan_mode == 2 ? "one-pass-tiles" : (g.scan_mode ? "thread-per-line" : "lanes-along-axis")) << " lines=" << g.red_out << " length=" << g.red_len << " chunks=" << g.scan_nchunk;
     if (g.kind == GroupKind::MAP) s << " tile=" << g.BY * g.VR << "x" << g.BX * 4 * g.UC << " patch=" << g.VR << "x" << g.UC * 4;
     s << '\n';
   }

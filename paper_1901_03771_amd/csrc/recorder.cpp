@@ -236,6 +236,7 @@ gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   else if (k == "plan_cache") ctx->opt_plan_cache = value;
   else if (k == "scan_threads") ctx->opt_scan_threads = value;
   else if (k == "scan_min_threads") ctx->opt_scan_min_threads = value;
+  else if (k == "scan_one_pass") ctx->opt_scan_one_pass = value;
   else return fail(ctx, GR_ERR_ARG, "unknown option '" + k + "'");
   return GR_OK;
 }
@@ -320,6 +321,16 @@ gr_status gr_unary(gr_ctx* ctx, gr_op op, gr_array a, gr_array* out) {
 
 gr_status gr_binary(gr_ctx* ctx, gr_op op, gr_array a, gr_array b, gr_array* out) {
   if (!ctx || !out) return GR_ERR_ARG;
+  if (op == GR_POW_INT) {
+    // x ** 2 with an integer scalar 2 is recorded as square(x), NumPy's own fast path; no other power
+    // is in the vocabulary
+    const Node* x = lookup(ctx, a);
+    const Node* e = lookup(ctx, b);
+    if (!x || !e) return fail(ctx, GR_ERR_HANDLE, "binary: bad handle");
+    if (e->kind != Kind::SCALAR || !e->is_int || e->value != 2.0 || x->kind == Kind::SCALAR)
+      return fail(ctx, GR_ERR_UNSUPPORTED, "binary: the only power recorded is array ** 2 with an integer scalar");
+    return gr_unary(ctx, GR_SQUARE, a, out);
+  }
   if (!is_binary(op)) return fail(ctx, GR_ERR_ARG, "binary: not a binary op");
   Node* x = lookup(ctx, a);
   Node* y = lookup(ctx, b);

@@ -223,14 +223,16 @@ static void disk_store(const std::string& path, const std::string& key, const st
 
 // What finish_kernel needs to know about a sub-graph: kept with a compilation job so that the
 // job can be collected without the plan that started it.
-static void kernel_entry_points(const GroupPlan& g, std::string* name, bool* combine, bool* scan) {
+// (scan: 0 = no scan, 1 = the code object also holds the chunk-total and offset kernels, 2 = the cell-clearing kernel
+// of a one-pass scan)
+static void kernel_entry_points(const GroupPlan& g, std::string* name, bool* combine, int* scan) {
   *name = kernel_name(g);
   *combine = (g.kind == GroupKind::GEMV && g.gemv_mode >= 1) || g.kind == GroupKind::REDUCE || g.kind == GroupKind::GEMM;
-  *scan = g.kind == GroupKind::SCAN;
+  *scan = g.kind == GroupKind::SCAN ? (g.scan_mode == 2 ? 2 : 1) : 0;
 }
 
 // Loads a code object and publishes the kernel in the in-memory cache.
-static gr_status finish_kernel(gr_ctx* c, const std::string& sig, const std::string& name, bool combine, bool scan,
+static gr_status finish_kernel(gr_ctx* c, const std::string& sig, const std::string& name, bool combine, int scan,
                                std::vector<char>&& code, gr_ctx::Kernel** out) {
   gr_ctx::Kernel k;
   k.code = std::move(code);
@@ -239,10 +241,11 @@ static gr_status finish_kernel(gr_ctx* c, const std::string& sig, const std::str
     GR_HIP(c, hipModuleLoadData(&k.module, k.code.data()));
     GR_HIP(c, hipModuleGetFunction(&k.fn, k.module, k.name.c_str()));
     if (combine) GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, (k.name + "_combine").c_str()));
-    if (scan) {
+    if (scan == 1) {
       GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, "gr_scan_sums"));
       GR_HIP(c, hipModuleGetFunction(&k.fn3, k.module, "gr_scan_offsets"));
     }
+    if (scan == 2) GR_HIP(c, hipModuleGetFunction(&k.fn2, k.module, "gr_scan_clear"));
   }
   auto ins = c->cache.emplace(sig, std::move(k));
   if (out) *out = &ins.first->second;
@@ -268,7 +271,8 @@ gr_status prepare_group(gr_ctx* c, GroupPlan& g) {
     c->stats.cache_misses++;
     c->stats.disk_hits++;
     std::string name;
-    bool combine, scan;
+    bool combine;
+    int scan;
     kernel_entry_points(g, &name, &combine, &scan);
     return finish_kernel(c, g.signature, name, combine, scan, std::move(code), nullptr);
   }
@@ -429,6 +433,8 @@ static size_t workspace_need(const GroupPlan& g) {
     case GroupKind::SCAN: {
       int64_t total = 1;
       for (int k2 = 0; k2 < g.rank; ++k2) total *= g.dims[k2];
+      if (g.scan_mode == 2)  // one 8-byte cell per tile and per group of 128 tiles
+        return total > 0 ? ((size_t)g.red_out * (size_t)g.scan_nchunk + (size_t)g.red_out * (size_t)((g.scan_nchunk + 127) / 128)) * 8 : 0;
       return g.scan_nchunk > 1 && total > 0 ? (size_t)g.red_out * (size_t)g.scan_nchunk * itemsize(g.out_dtype) : 0;
     }
     case GroupKind::GEMM: return g.slabs > 1 && g.M > 0 && g.N > 0 ? (size_t)g.slabs * (size_t)g.M * (size_t)g.N * sizeof(float) : 0;
@@ -520,6 +526,16 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       s[L.extra] = (uint64_t)g.red_out;
       s[L.extra + 1] = (uint64_t)g.scan_chunk;
       s[L.extra + 3] = (uint64_t)g.scan_nchunk;
+      if (g.scan_mode == 2) {
+        // one pass: clear the cells the tiles publish their totals in, then the chained tiles
+        gr_status wst = get_workspace(c, g, &ws);
+        if (wst != GR_OK) return wst;
+        s[L.extra + 2] = (uint64_t)(uintptr_t)ws;
+        const int64_t cells = g.red_out * g.scan_nchunk + g.red_out * ((g.scan_nchunk + 127) / 128);
+        gr_status st = launch(c, k->fn2, "gr_scan_clear", (cells + 255) / 256, s);
+        if (st != GR_OK) return st;
+        return launch(c, k->fn, k->name, g.red_out * g.scan_nchunk, s);
+      }
       if (g.scan_mode == 1) {
         // a thread per (line, chunk)
         const int64_t blocks = ((g.scan_vec ? g.red_out / 4 : g.red_out) * g.scan_nchunk + 255) / 256;

@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("GRUMPY_HIP_LIB", os.path.join(_HERE, "libgrumpy_hip.s
 
 GR_F32, GR_I32, GR_I64 = 0, 1, 2
 GR_NEG, GR_ABS, GR_EXP, GR_LOG, GR_SQRT, GR_SQUARE, GR_TANH, GR_ERF = range(8)
-GR_ADD, GR_SUB, GR_MUL, GR_DIV, GR_MAXIMUM, GR_MINIMUM = range(16, 22)
+GR_ADD, GR_SUB, GR_MUL, GR_DIV, GR_MAXIMUM, GR_MINIMUM, GR_POW_INT = range(16, 23)
 _UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "square": 5, "tanh": 6, "erf": 7}
 _BINARY = {"add": 16, "sub": 17, "mul": 18, "div": 19, "maximum": 20, "minimum": 21}
 _REDUCE = {"sum": 32, "max": 33, "min": 34}
@@ -584,9 +584,9 @@ def _binary_slow(op: int, a, b) -> Array:
 
 
 def _pow_slow(a, e) -> Array:
-    if isinstance(a, Array) and isinstance(e, int) and not isinstance(e, bool) and e == 2:
-        return _unary(GR_SQUARE, a)  # NumPy evaluates x**2 as square(x)
-    raise GrError(5, "only **2 is supported")
+    if isinstance(a, Array) and _is_int(e) and not isinstance(e, bool):
+        return _binary_slow(GR_POW_INT, a, e)  # the library records x ** 2 as square(x), as NumPy evaluates it
+    raise GrError(5, "only array ** integer is recorded")
 
 
 def _setitem_slow(a, key, value):

@@ -292,6 +292,33 @@ def test_scans(env, shape, axis):
     assert got.dtype == np.int64 and np.array_equal(got, ref)
 
 
+def test_one_pass_scans_tile_sizes_and_many_groups(env):
+    # long contiguous lines are scanned in one pass by chained tiles that publish their totals, 128 tiles to a
+    # group; small tiles (option values 2..16 = 1024-element blocks per tile) put more than 256 groups on a line,
+    # so that every loop of the offset collection takes more than one turn
+    gr, ctx, torch = env
+    c2 = gr.Context()
+    c2.set_option("interp", 0)
+    e2 = (gr, c2, torch)
+    n = (1 << 26) + 4099
+    x = np.abs(_rand((n,), 65)) + f32(0.01)
+    i = np.random.default_rng(66).integers(-2**31, 2**31 - 1, n, dtype=np.int64).astype(np.int32)
+    for blocks in (2, 5, 16, 0):
+        c2.set_option("scan_one_pass", blocks)
+        got, ref = run_both(e2, lambda xp, a: xp.cumsum(a, 0), dict(a=x))
+        assert_reduction(got, ref, what=f"cumsum of 2^26+4099 positive values, tile option {blocks}")   # positive terms: per element
+        got, ref = run_both(e2, lambda xp, a: xp.cummax(a, 0) - xp.cummin(a, 0), dict(a=i[:n // 2]))
+        assert np.array_equal(got, ref)
+    c2.set_option("scan_one_pass", 1)
+    # several lines, lengths that leave a ragged last tile, a fused producer, a strided source
+    a = _rand((7, 100_003), 67)
+    got, ref, scale = run_scaled(e2, lambda xp, a: xp.cumsum(a[:, 1::2] * 2.0 + 1.0, 1), dict(a=a))
+    assert_reduction(got, ref, what="one-pass scan of 7 strided lines", scale=scale)
+    plan = gr.cumsum(c2.array(torch.from_numpy(a).cuda()), 1).plan()
+    assert "one-pass-tiles" in plan
+    c2.close()
+
+
 def test_scan_closed_forms_and_consumers(env):
     gr, ctx, torch = env
     n = 5000

@@ -36,7 +36,7 @@ def groups(arr):
 
 # ------------------------------------------------------------------ the boundary --
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "grumpy_hip.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))) if h.endswith(".h"))
     declared = set(re.findall(r"^(?:gr_status|const char\*)\s+(gr_[a-z_0-9]+)\s*\(", header, flags=re.M))
     assert len(declared) > 25
     L = ctypes.CDLL(gr.LIB_PATH)
@@ -500,9 +500,17 @@ def test_scan_is_a_cut_and_checks_its_axis(ctx):
         with pytest.raises(gr.GrError) as ei:
             gr.cumsum(a, bad)
         assert ei.value.code == "GR_ERR_AXIS"
+    # a long contiguous line: one pass with chained tiles of 8192 elements (a kernel that clears the
+    # published totals, then the scan); with the option off, or for 8-byte running values, three kernels
     long_line = gr.cumsum(ctx.spec((1 << 22,)), 0)
-    assert "chunks=512" in long_line.plan()
-    assert "gr_scan_sums" in long_line.source(0) and "gr_scan_offsets" in long_line.source(0)
+    assert "mode=one-pass-tiles" in long_line.plan() and "chunks=512" in long_line.plan()
+    assert "gr_scan_clear" in long_line.source(0) and "gr_scan_sums" not in long_line.source(0)
+    as_i64 = gr.cumsum(ctx.spec((1 << 22,), gr.GR_I32), 0)
+    assert "mode=lanes-along-axis" in as_i64.plan() and "gr_scan_sums" in as_i64.source(0) and "gr_scan_offsets" in as_i64.source(0)
+    ctx.set_option("scan_one_pass", 0)
+    long_line = gr.cumsum(ctx.spec((1 << 22,)), 0)
+    assert "chunks=512" in long_line.plan() and "gr_scan_sums" in long_line.source(0) and "gr_scan_offsets" in long_line.source(0)
+    ctx.set_option("scan_one_pass", 1)
 
 
 def test_matrix_product_plans_and_compiles(ctx):
