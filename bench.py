@@ -432,10 +432,14 @@ def main():
         del ga, gb, gc
         jac_bytes = 4 * 8192 * 8192 + 4 * 8190 * 8190
         sweeps = 10
-        for label, owned in (("jacobi_8192", False), ("jacobi_owned_8192", True)):
-            # wrapped: the caller's tensor is the grid's storage; owned: the library's own copy (each sweep writes a
-            # second buffer, copies the border and swaps)
-            grid = ctx.array(torch.rand(8192, 8192, device="cuda"))
+        for label, owned in (("jacobi_8192", False), ("jacobi_lent_8192", None), ("jacobi_owned_8192", True)):
+            # wrapped: the caller's tensor is the grid's storage (stencil -> temporary -> copy back); lent: the caller
+            # lends a second tensor and the sweeps alternate between the two; owned: the library's own copy (each
+            # sweep writes a second buffer, copies the border once and swaps)
+            if owned is None:
+                grid = ctx.array(torch.rand(8192, 8192, device="cuda"), second=torch.empty(8192, 8192, device="cuda"))
+            else:
+                grid = ctx.array(torch.rand(8192, 8192, device="cuda"))
             if owned:
                 grid = grid.copy()
             ms, blocks = timed(lambda: wl.jacobi(gr, grid, sweeps), 10)

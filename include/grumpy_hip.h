@@ -191,6 +191,17 @@ const char* gr_last_error(gr_ctx* ctx);
 gr_status gr_array_from_device(gr_ctx* ctx, void* dptr, gr_dtype dtype, int ndim, const int64_t* shape,
                                const int64_t* strides_elems, gr_array* out);
 
+/* Lends the library a second device buffer for `a`, a C-contiguous array made by gr_array_from_device, of
+ * the same size (`bytes` = count * itemsize, not overlapping the first).  A slice assignment whose value reads
+ * the array's storage at shifted positions -- a stencil sweep, Listing 6 of the paper -- into a unit-step box
+ * covering at least 4/5 of the array then writes the new contents into the other of the two buffers, copies the
+ * cells outside the box once, and makes that buffer the array's storage: 8 bytes per element and sweep instead
+ * of the 16 of "evaluate into a temporary, copy back" (which remains what happens to wrapped memory without a
+ * second buffer).  From then on the array's contents are in ONE of the two buffers: gr_data_ptr says which
+ * after every assignment; the other holds the previous sweep's cells.  Both stay borrowed (never freed by the
+ * library) and must stay alive as long as the array. */
+gr_status gr_array_lend_buffer(gr_ctx* ctx, gr_array a, void* dptr2, size_t bytes);
+
 /* A Python-style number.  It has no element type of its own: in a binary op
  * it takes the array operand's type (rounded to binary32 first when it meets
  * f32; an integer-valued one may meet i32; a fractional one with i32 is

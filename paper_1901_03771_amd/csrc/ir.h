@@ -47,6 +47,10 @@ struct Node {
   // Second buffer of an array that stencil sweeps are assigned into (see gr_assign): same size as
   // `data`; outside the box [shadow_start, shadow_start + shadow_len) it holds the same cells.
   void* shadow = nullptr;
+  // A second buffer lent by the caller to a wrapped array (gr_array_lend_buffer): the one of the caller's two
+  // buffers that is not `data` right now.  It takes the place of a library-allocated second buffer in the
+  // sweeps above and is never freed by the library.
+  void* lent = nullptr;
   int64_t shadow_start[MAXD] = {0};
   int64_t shadow_len[MAXD] = {0};
 

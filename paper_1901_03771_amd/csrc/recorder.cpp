@@ -85,7 +85,7 @@ void node_maybe_free(gr_ctx* c, Node* n0) {
       if (heir) { heir->owns_data = true; heir->alloc_bytes = n->alloc_bytes; heir->cow_alias = false; }
       else ctx_free(c, n->data, n->alloc_bytes);
     }
-    if (n->shadow) ctx_free(c, n->shadow, n->alloc_bytes);
+    if (n->shadow && n->shadow != n->lent) ctx_free(c, n->shadow, n->alloc_bytes);
     if (n->kind == Kind::REDUCE || n->kind == Kind::DOT || n->kind == Kind::SCAN) forget_pending(c, n);
     c->nodes.erase(n->id);
     c->stats.nodes_alive--;

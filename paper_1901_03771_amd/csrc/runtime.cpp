@@ -957,7 +957,7 @@ gr_status gr_ctx_destroy(gr_ctx* ctx) {
   for (auto& kv : ctx->nodes) all.push_back(kv.second);
   for (Node* n : all) {
     if (n->owns_data && n->data) ctx_free(ctx, n->data, n->alloc_bytes);
-    if (n->shadow) ctx_free(ctx, n->shadow, n->alloc_bytes);
+    if (n->shadow && n->shadow != n->lent) ctx_free(ctx, n->shadow, n->alloc_bytes);
     delete n;
   }
   ctx->nodes.clear();
@@ -1115,7 +1115,7 @@ static gr_status copy_box(gr_ctx* ctx, gr_dtype dt, int nd, const int64_t* shape
 // The second buffer of `b` stops mirroring it as soon as `b` is written in any other way.
 static void drop_shadow(gr_ctx* ctx, Node* b) {
   if (!b->shadow) return;
-  ctx_free(ctx, b->shadow, b->alloc_bytes);
+  if (b->shadow != b->lent) ctx_free(ctx, b->shadow, b->alloc_bytes);  // (a lent buffer only stops being a mirror)
   b->shadow = nullptr;
 }
 
@@ -1124,7 +1124,7 @@ static void drop_shadow(gr_ctx* ctx, Node* b) {
 // storage at shifted positions (a stencil sweep) can be written into a second buffer, the rest
 // copied over, and the two buffers swapped: half the traffic of "evaluate, then copy".
 static bool swap_candidate(const Node* base, const Node* d, const OutSpec& spec, int64_t* start) {
-  if (!base->owns_data || base->cow_alias || base->offset != 0 || d->ndim != base->ndim) return false;
+  if ((!base->owns_data && !base->lent) || base->cow_alias || base->offset != 0 || d->ndim != base->ndim) return false;
   int64_t s = 1, rest = spec.base;
   for (int k = base->ndim - 1; k >= 0; --k) { if (base->strides[k] != s) return false; s *= base->shape[k]; }
   for (int k = 0; k < base->ndim; ++k) {
@@ -1139,6 +1139,23 @@ static bool swap_candidate(const Node* base, const Node* d, const OutSpec& spec,
 }
 
 }  // namespace gr
+
+extern "C" gr_status gr_array_lend_buffer(gr_ctx* ctx, gr_array a, void* dptr2, size_t bytes) {
+  if (!ctx) return GR_ERR_ARG;
+  Node* x = lookup(ctx, a);
+  if (!x) return fail(ctx, GR_ERR_HANDLE, "lend_buffer: bad handle");
+  if (x->kind != Kind::LEAF || !x->data || x->owns_data) return fail(ctx, GR_ERR_ARG, "lend_buffer: not an array made by gr_array_from_device");
+  int64_t s = 1;
+  for (int k = x->ndim - 1; k >= 0; --k) { if (x->shape[k] != 1 && x->strides[k] != s) return fail(ctx, GR_ERR_ARG, "lend_buffer: the array is not C-contiguous"); s *= x->shape[k]; }
+  const size_t need = (size_t)x->count() * itemsize(x->dtype);
+  if (x->offset != 0 || bytes != need || need == 0) return fail(ctx, GR_ERR_ARG, "lend_buffer: buffer size does not match the array");
+  if (!dptr2 || ((uintptr_t)dptr2) % itemsize(x->dtype)) return fail(ctx, GR_ERR_ARG, "lend_buffer: NULL or misaligned buffer");
+  const uintptr_t lo = (uintptr_t)x->data, lo2 = (uintptr_t)dptr2;
+  if (lo < lo2 + need && lo2 < lo + need) return fail(ctx, GR_ERR_ALIAS, "lend_buffer: the two buffers overlap");
+  drop_shadow(ctx, x);
+  x->lent = dptr2;
+  return GR_OK;
+}
 
 extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
   if (!ctx) return GR_ERR_ARG;
@@ -1241,10 +1258,11 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
       const size_t bytes = (size_t)b->count() * itemsize(b->dtype);
       // the buffer this array was swapped out of by the last sweep over the same box already holds
       // the cells outside the box: nothing to copy
-      bool mirrored = b->shadow != nullptr && bytes == b->alloc_bytes;
+      bool mirrored = b->shadow != nullptr && (b->shadow == b->lent || bytes == b->alloc_bytes);
       for (int k = 0; mirrored && k < b->ndim; ++k) mirrored = b->shadow_start[k] == start[k] && b->shadow_len[k] == d->shape[k];
       if (!mirrored) drop_shadow(ctx, b);
-      void* fresh = mirrored ? b->shadow : ctx_alloc(ctx, bytes);
+      // the second buffer: the mirror left by the last sweep, else the buffer the caller lent, else a new one
+      void* fresh = mirrored ? b->shadow : (b->lent ? b->lent : ctx_alloc(ctx, bytes));
       if (!fresh) return fail(ctx, GR_ERR_OOM, "allocator returned NULL");
       b->shadow = nullptr;
       Plan p2;
@@ -1270,10 +1288,11 @@ extern "C" gr_status gr_assign(gr_ctx* ctx, gr_array dst, gr_array value) {
         // the value may already be bound to the abandoned buffer: give it a buffer of its own first
         v = lookup(ctx, value);
         if (v && v->materialized && v->cow_alias && v->data == fresh) (void)unshare(ctx, value);
-        ctx_free(ctx, fresh, bytes);
+        if (fresh != b->lent) ctx_free(ctx, fresh, bytes);
         return st;
       }
       // the old buffer becomes the mirror: outside the box it equals the new one
+      if (b->lent) b->lent = b->data;  // the caller's two buffers trade places
       b->shadow = b->data;
       b->data = fresh;
       for (int k = 0; k < b->ndim; ++k) { b->shadow_start[k] = start[k]; b->shadow_len[k] = d->shape[k]; }

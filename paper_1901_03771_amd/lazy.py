@@ -35,7 +35,7 @@ STATUS = {0: "GR_OK", 1: "GR_ERR_HANDLE", 2: "GR_ERR_SHAPE", 3: "GR_ERR_DTYPE", 
 # every symbol include/grumpy_hip.h declares
 SYMBOLS = [
     "gr_ctx_create", "gr_ctx_destroy", "gr_ctx_set_stream", "gr_ctx_set_allocator", "gr_ctx_set_option", "gr_sync",
-    "gr_last_error", "gr_array_from_device", "gr_scalar", "gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose", "gr_reshape",
+    "gr_last_error", "gr_array_from_device", "gr_array_lend_buffer", "gr_scalar", "gr_unary", "gr_binary", "gr_binary_scalar", "gr_slice", "gr_transpose", "gr_reshape",
     "gr_reduce", "gr_scan", "gr_dot", "gr_materialize", "gr_materialize_into", "gr_materialize_into_static", "gr_static_scratch_bytes", "gr_program_create", "gr_program_run", "gr_program_destroy", "gr_assign", "gr_ndim", "gr_shape", "gr_dtype_of",
     "gr_is_materialized", "gr_data_ptr", "gr_retain", "gr_release", "gr_plan_describe", "gr_plan_source",
     "gr_plan_compile", "gr_compile_wait", "gr_stats", "gr_profile_reset", "gr_profile_read", "gr_stream_copy", "gr_stream_read",
@@ -88,6 +88,7 @@ def lib():
         "gr_reduce": [P, I, U64, PP(I), I, I, PP(U64)], "gr_dot": [P, U64, U64, PP(U64)],
         "gr_scan": [P, I, U64, I, PP(U64)],
         "gr_materialize": [P, U64], "gr_assign": [P, U64, U64], "gr_materialize_into": [P, U64, P, SZ],
+        "gr_array_lend_buffer": [P, U64, P, SZ],
         "gr_materialize_into_static": [P, U64, P, SZ], "gr_static_scratch_bytes": [PP(SZ)],
         "gr_program_create": [P, U64, PP(U64), I, PP(P)], "gr_program_run": [P, PP(P), P], "gr_program_destroy": [P],
         "gr_ndim": [P, U64, PP(I)], "gr_shape": [P, U64, PP(I64)], "gr_dtype_of": [P, U64, PP(I)],
@@ -248,8 +249,18 @@ class Context:
         a._owner = owner  # keeps the device memory of the leaf alive as long as the handle
         return a
 
-    def array(self, t) -> "Array":
-        """Wraps a torch tensor that lives on this context's GPU (borrowed, any strides)."""
+    def array(self, t, second=None) -> "Array":
+        """Wraps a torch tensor that lives on this context's GPU (borrowed, any strides).  ``second``: a second
+        tensor of the same shape lent to the library (gr_array_lend_buffer): stencil sweeps assigned into the array
+        then alternate between the two tensors instead of going through a temporary; ``Array.current(t, second)``
+        tells which of them holds the contents."""
+        if second is not None:
+            a = self.array(t)
+            if tuple(second.shape) != tuple(t.shape) or second.dtype != t.dtype or not second.is_contiguous():
+                raise ValueError("the second buffer must be a contiguous tensor of the same shape and element type")
+            self.check(lib().gr_array_lend_buffer(self._p, a.h, second.data_ptr(), second.numel() * second.element_size()))
+            a._owner = (t, second)
+            return a
         try:
             dt = _TORCH_DTYPES[t.dtype]
         except (KeyError, AttributeError):
@@ -421,6 +432,14 @@ class _ArrayMethods:
         st = (ctypes.c_int64 * 8)()
         self.ctx.check(lib().gr_data_ptr(self.ctx._p, self.h, ctypes.byref(p), st))
         return p.value or 0, tuple(int(st[i]) for i in range(self.ndim))
+
+    def current(self, *tensors):
+        """Which of the given tensors is this array's storage right now (after sweeps over a lent second buffer)."""
+        ptr, _ = self.data_ptr()
+        for t in tensors:
+            if t.data_ptr() == ptr:
+                return t
+        raise LookupError("the array's storage is none of the given tensors")
 
     def copy(self) -> "Array":
         """An evaluated array with storage of its own (allocated and owned by the library) holding

@@ -485,6 +485,39 @@ def test_jacobi_on_library_owned_storage_swaps_buffers(env):
         assert np.array_equal(grid.numpy(), og.numpy()), f"sweep {step}"
 
 
+def test_jacobi_on_wrapped_memory_with_a_lent_second_buffer(env):
+    # the caller lends a second tensor: sweeps alternate between the caller's two tensors (no temporary, no copy
+    # back); the array says which of them holds the grid, the other one holds the previous sweep
+    gr, ctx, torch = env
+    for shape, iters in [((151, 1234), 3), ((64, 4096), 4), ((12, 9), 2)]:
+        g0 = np.random.default_rng(270).random(shape).astype(f32)
+        t, t2 = torch.from_numpy(g0).cuda(), torch.full(shape, float("nan"), device="cuda")
+        grid = ctx.array(t, second=t2)
+        before = ctx.stats()
+        view = grid[1:-1]                                   # taken before the sweeps: follows the swaps
+        out = wl.jacobi(gr, grid, iters)
+        ref = wl.jacobi(ora, ora.array(g0), iters).numpy()
+        swaps = ctx.stats()["assign_swaps"] - before["assign_swaps"]
+        big = (shape[0] - 2) * (shape[1] - 2) * 5 >= shape[0] * shape[1] * 4
+        assert swaps == (iters if big else 0), (shape, swaps)
+        assert ctx.stats()["bytes_allocated"] == before["bytes_allocated"] or not big, "a sweep over lent buffers allocates nothing"
+        assert np.array_equal(out.numpy(), ref), f"jacobi with a lent buffer {shape}"
+        assert np.array_equal(view.numpy(), ref[1:-1])
+        cur = grid.current(t, t2)
+        assert np.array_equal(cur.cpu().numpy(), ref)
+        assert cur is (t2 if (big and iters % 2) else t)
+        # any other write ends the mirroring; the next sweep copies the border again and stays correct
+        top = _rand((1, shape[1]), 271)
+        grid[0:1] = ctx.array(torch.from_numpy(top).cuda())
+        og = ora.array(ref.copy())
+        og[0:1] = ora.array(top)
+        wl.jacobi(gr, grid, 1)
+        assert np.array_equal(grid.numpy(), wl.jacobi(ora, og, 1).numpy())
+    with pytest.raises(gr.GrError) as ei:
+        ctx.array(t, second=t)
+    assert ei.value.code == "GR_ERR_ALIAS"
+
+
 def test_assign_direct_in_place_and_strided_destinations(env):
     gr, ctx, torch = env
     a0 = _rand((40, 60), 71)
