@@ -198,6 +198,17 @@ static bool is_unary(int op) { return op >= GR_NEG && op <= GR_ERF; }
 static bool is_binary(int op) { return op >= GR_ADD && op <= GR_MINIMUM; }
 static bool is_reduce(int op) { return op >= GR_SUM && op <= GR_MIN; }
 
+// The integer a caller passed where the C ABI takes an enumeration.  Any int may arrive through the ABI, and reading
+// an enumeration object that holds a value outside its range is undefined behaviour in C++: the bits are copied out
+// and checked as an int before the argument is used with its own type.
+template <class E>
+static int enum_arg(const E& e) {
+  int v;
+  static_assert(sizeof(E) == sizeof(int), "enumerations of the ABI are int-sized");
+  std::memcpy(&v, &e, sizeof v);
+  return v;
+}
+
 }  // namespace gr
 
 using namespace gr;
@@ -254,7 +265,7 @@ gr_status gr_array_from_device(gr_ctx* ctx, void* dptr, gr_dtype dtype, int ndim
                                const int64_t* strides_elems, gr_array* out) {
   if (!ctx || !out) return GR_ERR_ARG;
   if (ndim < 0 || ndim > MAXD || (ndim > 0 && !shape)) return fail(ctx, GR_ERR_ARG, "from_device: bad rank or NULL shape");
-  if (dtype != GR_F32 && dtype != GR_I32 && dtype != GR_I64) return fail(ctx, GR_ERR_ARG, "from_device: bad dtype");
+  { const int dt = enum_arg(dtype); if (dt != GR_F32 && dt != GR_I32 && dt != GR_I64) return fail(ctx, GR_ERR_ARG, "from_device: bad dtype"); }
   int64_t n = 1;
   for (int d = 0; d < ndim; ++d)
     if (shape[d] < 0) return fail(ctx, GR_ERR_ARG, "from_device: negative extent");
@@ -302,7 +313,7 @@ gr_status gr_scalar(gr_ctx* ctx, double value, int is_integer, gr_array* out) {
 
 gr_status gr_unary(gr_ctx* ctx, gr_op op, gr_array a, gr_array* out) {
   if (!ctx || !out) return GR_ERR_ARG;
-  if (!is_unary(op)) return fail(ctx, GR_ERR_ARG, "unary: not a unary op");
+  if (!is_unary(enum_arg(op))) return fail(ctx, GR_ERR_ARG, "unary: not a unary op");
   Node* x = lookup(ctx, a);
   if (!x) return fail(ctx, GR_ERR_HANDLE, "unary: bad handle");
   if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "unary: operand is a bare scalar");
@@ -321,7 +332,7 @@ gr_status gr_unary(gr_ctx* ctx, gr_op op, gr_array a, gr_array* out) {
 
 gr_status gr_binary(gr_ctx* ctx, gr_op op, gr_array a, gr_array b, gr_array* out) {
   if (!ctx || !out) return GR_ERR_ARG;
-  if (op == GR_POW_INT) {
+  if (enum_arg(op) == GR_POW_INT) {
     // x ** 2 with an integer scalar 2 is recorded as square(x), NumPy's own fast path; no other power
     // is in the vocabulary
     const Node* x = lookup(ctx, a);
@@ -331,7 +342,7 @@ gr_status gr_binary(gr_ctx* ctx, gr_op op, gr_array a, gr_array b, gr_array* out
       return fail(ctx, GR_ERR_UNSUPPORTED, "binary: the only power recorded is array ** 2 with an integer scalar");
     return gr_unary(ctx, GR_SQUARE, a, out);
   }
-  if (!is_binary(op)) return fail(ctx, GR_ERR_ARG, "binary: not a binary op");
+  if (!is_binary(enum_arg(op))) return fail(ctx, GR_ERR_ARG, "binary: not a binary op");
   Node* x = lookup(ctx, a);
   Node* y = lookup(ctx, b);
   if (!x || !y) return fail(ctx, GR_ERR_HANDLE, "binary: bad handle");
@@ -387,6 +398,7 @@ gr_status gr_binary(gr_ctx* ctx, gr_op op, gr_array a, gr_array b, gr_array* out
 gr_status gr_binary_scalar(gr_ctx* ctx, gr_op op, gr_array a, double value, int is_integer, int scalar_on_left,
                            gr_array* out) {
   if (!ctx || !out) return GR_ERR_ARG;
+  if (!is_binary(enum_arg(op)) && enum_arg(op) != GR_POW_INT) return fail(ctx, GR_ERR_ARG, "binary: not a binary op");
   gr_array s = 0;
   gr_status st = gr_scalar(ctx, value, is_integer, &s);
   if (st != GR_OK) return st;
@@ -482,7 +494,7 @@ gr_status gr_reshape(gr_ctx* ctx, gr_array a, int ndim, const int64_t* shape, gr
 
 gr_status gr_reduce(gr_ctx* ctx, gr_op op, gr_array a, const int* axes, int naxes, int keepdims, gr_array* out) {
   if (!ctx || !out) return GR_ERR_ARG;
-  if (!is_reduce(op)) return fail(ctx, GR_ERR_ARG, "reduce: not a reduction op");
+  if (!is_reduce(enum_arg(op))) return fail(ctx, GR_ERR_ARG, "reduce: not a reduction op");
   Node* x = lookup(ctx, a);
   if (!x) return fail(ctx, GR_ERR_HANDLE, "reduce: bad handle");
   if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "reduce: operand is a bare scalar");
@@ -517,7 +529,7 @@ gr_status gr_reduce(gr_ctx* ctx, gr_op op, gr_array a, const int* axes, int naxe
 
 gr_status gr_scan(gr_ctx* ctx, gr_op op, gr_array a, int axis, gr_array* out) {
   if (!ctx || !out) return GR_ERR_ARG;
-  if (!is_reduce(op)) return fail(ctx, GR_ERR_ARG, "scan: not a scan op");
+  if (!is_reduce(enum_arg(op))) return fail(ctx, GR_ERR_ARG, "scan: not a scan op");
   Node* x = lookup(ctx, a);
   if (!x) return fail(ctx, GR_ERR_HANDLE, "scan: bad handle");
   if (x->kind == Kind::SCALAR) return fail(ctx, GR_ERR_UNSUPPORTED, "scan: operand is a bare scalar");
