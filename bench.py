@@ -30,14 +30,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
-ARGNAMES = {"blackscholes": ("S", "K", "T"), "chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
+ARGNAMES = {"cumsum": ("x",), "blackscholes": ("S", "K", "T"), "chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
             "stencil": ("I",), "logreg": ("X", "w", "y")}
 # kernel whose launches dominate each workload
-DOMINANT = {"blackscholes": "gr_map", "chain": "gr_map", "normalize": "gr_map", "softmax": "gr_rowred", "stencil": "gr_map", "logreg": "gr_gemv_pair"}
+DOMINANT = {"cumsum": "gr_scan", "blackscholes": "gr_map", "chain": "gr_map", "normalize": "gr_map", "softmax": "gr_rowred", "stencil": "gr_map", "logreg": "gr_gemv_pair"}
 
 
 def out_shape(name, p):
-    return {"chain": lambda: (p["n"],), "blackscholes": lambda: (p["n"],), "normalize": lambda: (p["rows"], p["cols"]), "softmax": lambda: (p["rows"], p["cols"]),
+    return {"chain": lambda: (p["n"],), "cumsum": lambda: (p["n"],), "blackscholes": lambda: (p["n"],), "normalize": lambda: (p["rows"], p["cols"]), "softmax": lambda: (p["rows"], p["cols"]),
             "stencil": lambda: (p["rows"] - 4, p["cols"] - 4), "logreg": lambda: (p["cols"],)}[name]()
 
 

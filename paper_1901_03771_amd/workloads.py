@@ -30,6 +30,7 @@ FULL = {
     "stencil": dict(rows=8192, cols=8192),
     "logreg": dict(rows=262144, cols=512),
     "blackscholes": dict(n=1 << 24),
+    "cumsum": dict(n=1 << 27),
 }
 SMALL = {
     "chain": dict(n=100_003),
@@ -38,8 +39,9 @@ SMALL = {
     "stencil": dict(rows=151, cols=1234),
     "logreg": dict(rows=3001, cols=200),
     "blackscholes": dict(n=70_001),
+    "cumsum": dict(n=300_001),
 }
-CONFIG_INDEX = {"chain": 0, "normalize": 1, "softmax": 2, "stencil": 3, "logreg": 4, "blackscholes": 5}
+CONFIG_INDEX = {"chain": 0, "normalize": 1, "softmax": 2, "stencil": 3, "logreg": 4, "blackscholes": 5, "cumsum": 6}
 
 
 def rng_for(name: str, salt: int = 0) -> np.random.Generator:
@@ -84,6 +86,8 @@ def make_inputs(name: str, salt: int = 0, **size) -> dict:
         # option parameters in the ranges commonly used for synthetic pricing benchmarks
         return dict(S=g.uniform(5.0, 30.0, n).astype(f32), K=g.uniform(1.0, 100.0, n).astype(f32),
                     T=g.uniform(0.25, 10.0, n).astype(f32))
+    if name == "cumsum":
+        return dict(x=g.random(p["n"], dtype=f32))
     raise KeyError(name)
 
 
@@ -127,7 +131,12 @@ def blackscholes(xp, S, K, T, r=0.02, sigma=0.30):
     return S * cdf1 - K * xp.exp(-r * T) * cdf2
 
 
-PROGRAMS = {"blackscholes": blackscholes, "chain": chain, "normalize": normalize, "softmax": softmax, "stencil": stencil, "logreg": logreg}
+def prefix_sum(xp, x):
+    """Running sum of a long vector: the map-scan primitive (Section 3.2) on its own."""
+    return xp.cumsum(x, 0)
+
+
+PROGRAMS = {"cumsum": prefix_sum, "blackscholes": blackscholes, "chain": chain, "normalize": normalize, "softmax": softmax, "stencil": stencil, "logreg": logreg}
 
 
 def unique_bytes(name: str, **size) -> int:
@@ -138,6 +147,8 @@ def unique_bytes(name: str, **size) -> int:
         return 12 * p["n"]
     if name == "blackscholes":
         return 16 * p["n"]
+    if name == "cumsum":
+        return 8 * p["n"]
     if name == "normalize":
         return 8 * p["rows"] * p["cols"] + 16 * p["cols"]
     if name == "softmax":
