@@ -1253,8 +1253,12 @@ def test_mean_and_layer_normalisation(env):
             got, ref, scale = run_scaled(env, lambda xp, x: getattr(xp, fn)(x, axis=axis, keepdims=keep), dict(x=x))
             assert got.shape == ref.shape
             assert_reduction(got, ref, what=f"{fn} over {axis}", scale=scale)
+            # the compositions behind mean/var/std/clip are written once in the binding and once in the oracle's Python
+            # face; NumPy's own routine (float64) is the third opinion that would catch a definition wrong on both sides
+            want = getattr(np, fn)(x.astype(np.float64), axis=axis, keepdims=keep)
+            assert np.allclose(got, want, rtol=2e-5, atol=0), (fn, axis)
     got, ref = run_both(env, lambda xp, x: xp.clip(x * 2.0, -0.5, 1.25), dict(x=x))
-    assert np.array_equal(got, ref)
+    assert np.array_equal(got, ref) and np.array_equal(got, np.clip(x * f32(2), f32(-0.5), f32(1.25)))
     got, ref, scale = run_scaled(env, layer_norm, dict(x=x))
     assert_reduction(got, ref, what="layer normalisation", scale=scale)   # x - mean(x) cancels where x is near the mean
     assert np.all(np.abs(got.mean(axis=1)) < 1e-5) and np.all(np.abs(got.var(axis=1) - 1.0) < 1e-3)
