@@ -409,12 +409,12 @@ def main():
         rooflines["cumsum_n2^27"] = hbm_roofline("gr_scan", 8 * n, ms * 1e3, blocks, 20)
         del xs, outn
         torch.cuda.empty_cache()
-        m2 = [torch.rand(8192, 8192, device="cuda") for _ in range(2)]
-        outm = torch.empty(8192, 8192, device="cuda")
+        m2 = [torch.rand(8192, 8192, device="cuda") for _ in range(3)]
+        outm = [torch.empty(8192, 8192, device="cuda") for _ in range(3)]   # rotated like the workloads' buffer sets
 
         def colscan():
             k[0] += 1
-            gr.cumsum(ctx.array(m2[k[0] % 2]), 0).materialize_into(outm)
+            gr.cumsum(ctx.array(m2[k[0] % 3]), 0).materialize_into(outm[k[0] % 3])
         ms, blocks = timed(colscan, 20)
         extras["cumsum_axis0_8192_GBps"] = round(8 * 8192 * 8192 / (ms * 1e-3) / 1e9, 1)
         extras["cumsum_axis0_8192_us"] = round(ms * 1e3, 1)

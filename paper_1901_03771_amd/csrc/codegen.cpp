@@ -45,12 +45,14 @@ bool nontemporal_group(const GroupPlan& g, int group) {
   if ((g.nt & 7) == 0 || ag.dtype == GR_I64) return false;
   if (g.kind == GroupKind::GEMV) return group == g.mat_group;
   if (g.kind == GroupKind::GEMM) return false;  // operand tiles are re-read by other workgroups: keep them cacheable
-  if (access_class(ag, g.rank - 1) != '1') return false;
+  // (tiles of neighbouring lines of a scan: lanes run along the innermost line dimension)
+  const int lane_dim = g.kind == GroupKind::SCAN && g.scan_mode == 3 ? g.rank - 2 : g.rank - 1;
+  if (access_class(ag, lane_dim) != '1') return false;
   if ((g.nt & 7) >= 2) return true;
   if (ag.deltas.size() > 1) return false;
   // read once = the operand follows every outer iteration dimension; one that is broadcast along
   // any of them is read again by other rows or planes and stays cacheable
-  for (int k = 0; k + 1 < g.rank; ++k) if (ag.structural_zero[k]) return false;
+  for (int k = 0; k < g.rank; ++k) if (k != lane_dim && ag.structural_zero[k]) return false;
   return true;
 }
 
@@ -1005,10 +1007,22 @@ void gen_scan(Em& e) {
     };
   };
   // common head: line index -> pointers
-  auto head = [&](bool per_block_line) {
-    e.o << "  const long long LINES = " << e.S(e.L.extra) << ", CH = " << e.S(e.L.extra + 1) << ", NCHUNK = " << e.S(e.L.extra + 3) << ";\n";
+  auto head = [&](int per_block_line) {
+    // (the chunk-count slot of a one-pass scan carries the poll limit in its upper half)
+    e.o << "  const long long LINES = " << e.S(e.L.extra) << ", CH = " << e.S(e.L.extra + 1) << ", NCHUNK = " << e.S(e.L.extra + 3) << " & 0xffffffffll;\n";
     e.o << "  const long long L = " << e.dim(sd) << ";\n";
-    if (per_block_line) e.o << "  const long long line = blockIdx.x / NCHUNK, chunk = blockIdx.x % NCHUNK;\n";
+    if (per_block_line == 2) {
+      // a workgroup per tile of W neighbouring lines: consecutive workgroups take neighbouring
+      // column blocks, all tiles of one position along the axis before the next
+      const int LX = g.BX, W = 4 * g.BX;
+      e.o << "  const long long D = " << e.dim(sd - 1) << ", NCB = (D + " << W - 1 << ") / " << W << ", NCHAIN = (LINES / D) * NCB;\n"
+             "  const long long chain = blockIdx.x % NCHAIN, chunk = blockIdx.x / NCHAIN;\n"
+             "  const long long cb = chain % NCB;\n"
+             "  const int lx = threadIdx.x % " << LX << ", ly = threadIdx.x / " << LX << ";\n"
+             "  const bool colok = cb * " << W << " + lx * 4 < D;\n"
+             "  const long long line = (chain / NCB) * D + (colok ? cb * " << W << " + lx * 4 : 0);\n";
+    }
+    else if (per_block_line) e.o << "  const long long line = blockIdx.x / NCHUNK, chunk = blockIdx.x % NCHUNK;\n";
     else if (g.scan_vec) e.o << "  const long long gt = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (gt >= (LINES / 4) * NCHUNK) return;\n"
                 "  const long long line = 4 * (gt % (LINES / 4)), chunk = gt / (LINES / 4);\n  (void)chunk;\n";  // four lines per thread
     else e.o << "  const long long gt = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (gt >= LINES * NCHUNK) return;\n"
@@ -1185,6 +1199,148 @@ void gen_scan(Em& e) {
   }
 
 
+  if (g.scan_mode == 3) {
+    // ---- mode 3: a scan along a non-contiguous axis with few lines, in ONE pass over the input.
+    // A workgroup owns a tile of R positions along the scanned axis by W = 4*BX neighbouring lines
+    // (the innermost line dimension is contiguous): BX lanes across the lines, each with four of
+    // them, LY = 256/BX lane groups along the axis, RPL consecutive positions per lane, one vector
+    // load per array and position.  The tile stays in registers: every lane scans its positions,
+    // the lane groups exchange their totals through LDS, the tile's totals (one per line) are
+    // published, and the offsets come from the tiles before it on the same lines.  Tiles of a
+    // chain (the same W lines) form groups of G; the last tile of a group also publishes the group's
+    // totals.  A line's offset in tile k of group q is
+    //     fold(totals of groups 0..q-1, then of the tiles of group q before k),
+    // taken by 256/W lanes per line in a fixed interleaved pattern and combined in lane order, so
+    // the association, and with it every float result, depends on the shape only.  Cells are
+    // 8-byte words (valid bit, value) written and read with relaxed agent-scope atomics; waits are
+    // bounded, and a workgroup that runs out of polls takes its offsets from the input itself, so
+    // every wave terminates whatever order tiles are dispatched in.  A small kernel clears the
+    // cells before every launch.
+    const int LX = g.BX, W = 4 * LX, LY = 256 / LX, RPL = (int)(g.scan_chunk / LY), R = (int)g.scan_chunk, P = 256 / W;
+    const int ld = sd - 1;
+    const char* V4 = ph.out_dtype == GR_F32 ? "f4" : "i4";
+    const std::string bits = ph.out_dtype == GR_F32 ? "__float_as_uint" : "(unsigned)";
+    const std::string unbits = ph.out_dtype == GR_F32 ? "__uint_as_float" : "(int)";
+    kernel_head(e, "gr_scan_clear");
+    e.o << "  const long long LINES = " << e.S(e.L.extra) << ", G = " << e.S(e.L.extra + 1) << ", NCHUNK = " << e.S(e.L.extra + 3) << " & 0xffffffffll;\n"
+           "  const long long D = " << e.dim(ld) << ", NCHAIN = (LINES / D) * ((D + " << W - 1 << ") / " << W << ");\n"
+           "  const long long n = NCHAIN * (NCHUNK + (NCHUNK + G - 1) / G) * " << W << ";\n"
+           "  GM unsigned long long* const w = (GM unsigned long long*)" << e.slot(e.L.extra + 2) << ";\n"
+           "  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (i < n) w[i] = 0ull;\n}\n";
+    e.o << "static __device__ __forceinline__ unsigned long long gr_poll(GM unsigned long long* p, unsigned& polls) {\n"
+           "  unsigned long long w = __hip_atomic_load((unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
+           "  while (!(w >> 32) && polls) { __builtin_amdgcn_s_sleep(2); --polls; w = __hip_atomic_load((unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }\n"
+           "  return w;\n}\n";
+    kernel_head(e, "gr_scan");
+    head(2);
+    e.o << "  const long long G = CH;\n";
+    e.o << "  __shared__ " << V4 << " gr_sm[" << LY << "][" << LX << "];\n  __shared__ " << TA << " gr_part[256];\n  __shared__ " << TA << " gr_base[" << W << "];\n";
+    e.o << "  const long long cbeg = chunk * " << R << ", j0 = cbeg + ly * " << RPL << ";\n";
+    e.o << "  const long long ostep = " << e.S(e.L.ocoef + sd) << ";\n";
+    e.o << "  " << TA << " v[" << RPL << "][4];\n";
+    // the values of the mapped expression at position jx of the lane's four lines
+    auto loads = [&](const std::string& jx, const std::string& sfx, const std::string& ind) {
+      for (size_t i = 0; i < g.prog.size(); ++i) {
+        const Instr& in = g.prog[i];
+        if (in.kind != IKind::LOAD) continue;
+        const AccessGroup& ag = g.groups[in.group];
+        std::ostringstream at;
+        at << "p" << in.group << " + 0";
+        for (int k = 0; k < sd; ++k) if (!ag.structural_zero[k] && in.delta[k]) at << " + " << in.delta[k] << (k == ld ? std::string("") : " * " + e.coef(in.group, k));
+        if (!ag.structural_zero[sd]) at << " + (" << jx << " + " << in.delta[sd] << ") * " << e.coef(in.group, sd);
+        if (ag.structural_zero[ld]) e.o << ind << "const " << cty(in.dtype) << " u" << i << sfx << " = (" << at.str() << ")[0];\n";
+        else e.o << ind << "const " << vty4(in.dtype) << " w" << i << sfx << " = " << e.ld(in.group, vty4(in.dtype), at.str()) << ";\n";
+      }
+    };
+    auto values = [&](const std::string& sfx, const std::string& ind, const std::function<std::string(int)>& dst) {
+      for (int c4 = 0; c4 < 4; ++c4) {
+        const std::string pre = "t" + std::to_string(c4) + sfx + "_";
+        emit_scalar_program(e, g.prog, {ph.value},
+                            [&](const Instr& in, int id) {
+                              const AccessGroup& ag = g.groups[in.group];
+                              if (ag.structural_zero[ld]) return "u" + std::to_string(id) + sfx;
+                              return "w" + std::to_string(id) + sfx + "[" + std::to_string(c4) + "]";
+                            },
+                            "0.0f", pre, ind);
+        e.o << ind << dst(c4) << " = " << pre << ph.value << ";\n";
+      }
+    };
+    // the whole tile first: RPL vector loads per array in flight per lane; a tile inside the array
+    // takes straight-line code without bounds checks
+    e.o << "  const bool whole = cbeg + " << R << " <= L && (cb + 1) * " << W << " <= D;\n";
+    e.o << "  if (whole) {\n";
+    for (int u = 0; u < RPL; ++u) loads("j0 + " + std::to_string(u), "_" + std::to_string(u), "    ");
+    for (int u = 0; u < RPL; ++u) { e.o << "    {\n"; values("_" + std::to_string(u), "      ", [&](int c4) { return "v[" + std::to_string(u) + "][" + std::to_string(c4) + "]"; }); e.o << "    }\n"; }
+    e.o << "  } else {\n#pragma unroll\n    for (int u = 0; u < " << RPL << "; ++u) {\n"
+           "      v[u][0] = v[u][1] = v[u][2] = v[u][3] = " << ident << ";\n"
+           "      if (colok && j0 + u < L) {\n";
+    loads("j0 + u", "", "        ");
+    values("", "        ", [&](int c4) { return "v[u][" + std::to_string(c4) + "]"; });
+    e.o << "      }\n    }\n  }\n";
+    // scan inside the tile: down a lane's positions, then the lane groups through LDS
+    e.o << "#pragma unroll\n  for (int u = 1; u < " << RPL << "; ++u)\n#pragma unroll\n    for (int c = 0; c < 4; ++c) v[u][c] = gr_comb0(v[u - 1][c], v[u][c]);\n";
+    e.o << "  { " << V4 << " t; t[0] = v[" << RPL - 1 << "][0]; t[1] = v[" << RPL - 1 << "][1]; t[2] = v[" << RPL - 1 << "][2]; t[3] = v[" << RPL - 1 << "][3]; gr_sm[ly][lx] = t; }\n"
+           "  __syncthreads();\n";
+    e.o << "  " << TA << " off[4] = {" << ident << ", " << ident << ", " << ident << ", " << ident << "};\n"
+           "  for (int q = 0; q < ly; ++q) { const " << V4 << " t = gr_sm[q][lx];\n#pragma unroll\n    for (int c = 0; c < 4; ++c) off[c] = gr_comb0(off[c], t[c]); }\n";
+    // publish the tile's totals, one cell per line
+    e.o << "  const long long NGROUP = (NCHUNK + G - 1) / G, grp = chunk / G, gfirst = grp * G;\n"
+           "  GM unsigned long long* const wq = (GM unsigned long long*)" << e.slot(e.L.extra + 2) << ";\n"
+           "  GM unsigned long long* const wa = wq + chain * NCHUNK * " << W << ";\n"
+           "  GM unsigned long long* const wg = wq + NCHAIN * NCHUNK * " << W << " + chain * NGROUP * " << W << ";\n"
+           "  if (threadIdx.x < " << W << ") {\n    " << TA << " tot = " << ident << ";\n"
+           "    for (int q = 0; q < " << LY << "; ++q) tot = gr_comb0(tot, ((" << TA << "*)gr_sm)[q * " << W << " + threadIdx.x]);\n"
+           "    __hip_atomic_store((unsigned long long*)(wa + chunk * " << W << " + threadIdx.x), (1ull << 32) | " << bits << "(tot), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n  }\n"
+           "  unsigned polls = (unsigned)(" << e.slot(e.L.extra + 3) << " >> 32);\n  int lost = 0;\n"
+           "  if (chunk == gfirst + G - 1 && threadIdx.x < " << W << ") {\n"
+           "    // last tile of a full group: the group's totals, for every later group\n"
+           "    " << TA << " acc = " << ident << ";\n"
+           "    for (long long q = gfirst; q < gfirst + G; q += 4) {\n      unsigned long long w[4];\n"
+           "#pragma unroll\n      for (int b = 0; b < 4; ++b) w[b] = __hip_atomic_load((unsigned long long*)(wa + (q + b) * " << W << " + threadIdx.x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
+           "#pragma unroll\n      for (int b = 0; b < 4; ++b) {\n"
+           "        if (!(w[b] >> 32)) w[b] = gr_poll(wa + (q + b) * " << W << " + threadIdx.x, polls);\n"
+           "        if (w[b] >> 32) acc = gr_comb0(acc, " << unbits << "((unsigned)w[b])); else lost = 1;\n      }\n    }\n"
+           "    if (!lost) __hip_atomic_store((unsigned long long*)(wg + grp * " << W << " + threadIdx.x), (1ull << 32) | " << bits << "(acc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
+           "  }\n"
+           "  {\n    const int col = threadIdx.x % " << W << ", part = threadIdx.x / " << W << ";\n"
+           "    const long long n = grp + (chunk - gfirst);\n    " << TA << " acc = " << ident << ";\n"
+           "    // (four cells asked for at a time: their latencies overlap; combined in index order all the same)\n"
+           "    for (long long i = part; i < n; i += " << 4 * P << ") {\n"
+           "      GM unsigned long long* cell[4];\n      unsigned long long w[4];\n"
+           "#pragma unroll\n      for (int b = 0; b < 4; ++b) {\n        const long long ib = i + b * " << P << ";\n"
+           "        cell[b] = ib < grp ? wg + ib * " << W << " + col : wa + (gfirst + ib - grp) * " << W << " + col;\n"
+           "        w[b] = ib < n ? __hip_atomic_load((unsigned long long*)cell[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;\n      }\n"
+           "#pragma unroll\n      for (int b = 0; b < 4; ++b) if (i + b * " << P << " < n) {\n"
+           "        if (!(w[b] >> 32)) w[b] = gr_poll(cell[b], polls);\n"
+           "        if (w[b] >> 32) acc = gr_comb0(acc, " << unbits << "((unsigned)w[b])); else lost = 1;\n      }\n    }\n"
+           "    gr_part[threadIdx.x] = acc;\n  }\n";
+    e.o << "  if (__syncthreads_or(lost)) {\n"
+           "    // out of polls: the offsets straight from the input (everything before this tile on its lines)\n"
+           "    " << TA << " acc[4] = {" << ident << ", " << ident << ", " << ident << ", " << ident << "};\n"
+           "    if (colok) for (long long j = ly; j < cbeg; j += " << LY << ") {\n      " << TA << " x[4];\n";
+    loads("j", "", "      ");
+    values("", "      ", [&](int c4) { return "x[" + std::to_string(c4) + "]"; });
+    e.o << "#pragma unroll\n      for (int c = 0; c < 4; ++c) acc[c] = gr_comb0(acc[c], x[c]);\n    }\n"
+           "    { " << V4 << " t; t[0] = acc[0]; t[1] = acc[1]; t[2] = acc[2]; t[3] = acc[3]; gr_sm[ly][lx] = t; }\n"
+           "    __syncthreads();\n"
+           "    if (threadIdx.x < " << W << ") {\n      " << TA << " b = " << ident << ";\n"
+           "      for (int q = 0; q < " << LY << "; ++q) b = gr_comb0(b, ((" << TA << "*)gr_sm)[q * " << W << " + threadIdx.x]);\n"
+           "      gr_base[threadIdx.x] = b;\n    }\n"
+           "  } else if (threadIdx.x < " << W << ") {\n    " << TA << " b = gr_part[threadIdx.x];\n";
+    for (int q = 1; q < P; ++q) e.o << "    b = gr_comb0(b, gr_part[" << q * W << " + threadIdx.x]);\n";
+    e.o << "    gr_base[threadIdx.x] = b;\n  }\n  __syncthreads();\n";
+    e.o << "#pragma unroll\n  for (int c = 0; c < 4; ++c) off[c] = gr_comb0(gr_base[lx * 4 + c], off[c]);\n";
+    {
+      const char* vt = ph.out_dtype == GR_F32 ? "f4u" : "i4u";
+      const std::string st = (g.nt & 8) ? "__builtin_nontemporal_store(ov, (GM " + std::string(vt) + "*)(po + (j0 + u) * ostep))" : "*(GM " + std::string(vt) + "*)(po + (j0 + u) * ostep) = ov";
+      e.o << "  if (whole) {\n#pragma unroll\n    for (int u = 0; u < " << RPL << "; ++u) {\n"
+             "      " << vt << " ov; for (int c = 0; c < 4; ++c) ov[c] = gr_comb0(off[c], v[u][c]); " << st << ";\n    }\n    return;\n  }\n";
+      e.o << "#pragma unroll\n  for (int u = 0; u < " << RPL << "; ++u) {\n"
+             "    if (colok && j0 + u < L) { " << vt << " ov; for (int c = 0; c < 4; ++c) ov[c] = gr_comb0(off[c], v[u][c]); " << st << "; }\n  }\n}\n";
+    }
+    return;
+  }
+
   if (g.scan_mode == 2) {
     // ---- mode 2: long contiguous lines in ONE pass over the input.  A workgroup owns a tile of TU x 1024
     // consecutive elements of a line, keeps it in registers, scans it, publishes the tile's total and
@@ -1201,7 +1357,7 @@ void gen_scan(Em& e) {
     const std::string bits = ph.out_dtype == GR_F32 ? "__float_as_uint" : "(unsigned)";
     const std::string unbits = ph.out_dtype == GR_F32 ? "__uint_as_float" : "(int)";
     kernel_head(e, "gr_scan_clear");
-    e.o << "  const long long LINES = " << e.S(e.L.extra) << ", NCHUNK = " << e.S(e.L.extra + 3) << ";\n"
+    e.o << "  const long long LINES = " << e.S(e.L.extra) << ", NCHUNK = " << e.S(e.L.extra + 3) << " & 0xffffffffll;\n"
            "  const long long n = LINES * NCHUNK + LINES * ((NCHUNK + 127) / 128);\n"   // one cell per tile and per group
            "  GM unsigned long long* const w = (GM unsigned long long*)" << e.slot(e.L.extra + 2) << ";\n"
            "  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (i < n) w[i] = 0ull;\n}\n";
@@ -1261,7 +1417,7 @@ void gen_scan(Em& e) {
            "  GM unsigned long long* const wa = wq + line * NCHUNK;\n"
            "  GM unsigned long long* const wg = wq + LINES * NCHUNK + line * NGROUP;\n"
            "  if (threadIdx.x == 0) __hip_atomic_store((unsigned long long*)(wa + chunk), (1ull << 32) | " << bits << "(carry), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
-           "  unsigned polls = 1u << 20;\n  int lost = 0;\n"
+           "  unsigned polls = (unsigned)(" << e.slot(e.L.extra + 3) << " >> 32);\n  int lost = 0;\n"
            "  if (chunk == gfirst + 127) {\n"
            "    // last tile of a full group: the group's total, for every later group\n"
            "    " << TA << " acc = " << ident << ";\n"

@@ -248,6 +248,7 @@ gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   else if (k == "scan_threads") ctx->opt_scan_threads = value;
   else if (k == "scan_min_threads") ctx->opt_scan_min_threads = value;
   else if (k == "scan_one_pass") ctx->opt_scan_one_pass = value;
+  else if (k == "scan_polls") { if (value < 0 || value > ((int64_t)1 << 24)) return fail(ctx, GR_ERR_ARG, "scan_polls: 0 to 2^24"); ctx->opt_scan_polls = value; }
   else return fail(ctx, GR_ERR_ARG, "unknown option '" + k + "'");
   return GR_OK;
 }

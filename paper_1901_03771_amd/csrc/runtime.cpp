@@ -228,7 +228,7 @@ static void disk_store(const std::string& path, const std::string& key, const st
 static void kernel_entry_points(const GroupPlan& g, std::string* name, bool* combine, int* scan) {
   *name = kernel_name(g);
   *combine = (g.kind == GroupKind::GEMV && g.gemv_mode >= 1) || g.kind == GroupKind::REDUCE || g.kind == GroupKind::GEMM;
-  *scan = g.kind == GroupKind::SCAN ? (g.scan_mode == 2 ? 2 : 1) : 0;
+  *scan = g.kind == GroupKind::SCAN ? (g.scan_mode >= 2 ? 2 : 1) : 0;
 }
 
 // Loads a code object and publishes the kernel in the in-memory cache.
@@ -425,6 +425,17 @@ static gr_status fill_args(gr_ctx* c, const GroupPlan& g, const ArgLayout& L, vo
   return GR_OK;
 }
 
+// One-pass scan along a non-contiguous axis: tiles of 4*BX neighbouring lines; per chain of tiles
+// one cell per line for every tile and for every group of `slabs` tiles.
+static int64_t scan_line_tile_chains(const GroupPlan& g) {
+  const int64_t D = g.dims[g.rank - 2], W = 4 * (int64_t)g.BX;
+  return D > 0 ? (g.red_out / D) * ((D + W - 1) / W) : 0;
+}
+static int64_t scan_line_tile_cells(const GroupPlan& g) {
+  const int64_t G = std::max(1, g.slabs);
+  return scan_line_tile_chains(g) * ((int64_t)g.scan_nchunk + ((int64_t)g.scan_nchunk + G - 1) / G) * 4 * (int64_t)g.BX;
+}
+
 // Device memory a sub-graph's kernels need beyond inputs and output: the first-stage partial
 // results of two-stage kernels.
 static size_t workspace_need(const GroupPlan& g) {
@@ -433,6 +444,7 @@ static size_t workspace_need(const GroupPlan& g) {
     case GroupKind::SCAN: {
       int64_t total = 1;
       for (int k2 = 0; k2 < g.rank; ++k2) total *= g.dims[k2];
+      if (g.scan_mode == 3) return total > 0 ? (size_t)scan_line_tile_cells(g) * 8 : 0;
       if (g.scan_mode == 2)  // one 8-byte cell per tile and per group of 128 tiles
         return total > 0 ? ((size_t)g.red_out * (size_t)g.scan_nchunk + (size_t)g.red_out * (size_t)((g.scan_nchunk + 127) / 128)) * 8 : 0;
       return g.scan_nchunk > 1 && total > 0 ? (size_t)g.red_out * (size_t)g.scan_nchunk * itemsize(g.out_dtype) : 0;
@@ -525,7 +537,17 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       for (int k2 = 0; k2 < g.rank; ++k2) s[L.ocoef + k2] = (uint64_t)g.out_coef[k2];
       s[L.extra] = (uint64_t)g.red_out;
       s[L.extra + 1] = (uint64_t)g.scan_chunk;
-      s[L.extra + 3] = (uint64_t)g.scan_nchunk;
+      s[L.extra + 3] = (uint64_t)g.scan_nchunk | (g.scan_mode >= 2 ? (uint64_t)c->opt_scan_polls << 32 : 0);
+      if (g.scan_mode == 3) {
+        // one pass over tiles of neighbouring lines: clear the cells, then the tiles
+        gr_status wst = get_workspace(c, g, &ws);
+        if (wst != GR_OK) return wst;
+        s[L.extra + 1] = (uint64_t)std::max(1, g.slabs);
+        s[L.extra + 2] = (uint64_t)(uintptr_t)ws;
+        gr_status st = launch(c, k->fn2, "gr_scan_clear", (scan_line_tile_cells(g) + 255) / 256, s);
+        if (st != GR_OK) return st;
+        return launch(c, k->fn, k->name, scan_line_tile_chains(g) * g.scan_nchunk, s);
+      }
       if (g.scan_mode == 2) {
         // one pass: clear the cells the tiles publish their totals in, then the chained tiles
         gr_status wst = get_workspace(c, g, &ws);

@@ -103,4 +103,8 @@ SCAN_CASES = [((1000,), 0), ((37, 211), 1), ((37, 211), 0), ((4, 5, 6), 1), ((4,
               ((1000, 300), 0), ((4100, 7), 0), ((3, 2000, 5), 1), ((129, 1), 0), ((70000, 2), 0),
               # batches of eight steps with a ragged tail: chunked (four lines per thread, one line per thread)
               # and in one pass over the lines (enough lines for that: 2^14 threads of four lines, 2^15 of one)
-              ((1003, 300), 0), ((1003, 301), 0), ((139, 65540), 0), ((131, 33001), 0), ((5, 143, 13108), 1)]
+              ((1003, 300), 0), ((1003, 301), 0), ((139, 65540), 0), ((131, 33001), 0), ((5, 143, 13108), 1),
+              # few lines, four to a lane: one pass over tiles of neighbouring lines kept in registers (several
+              # tiles and groups of tiles per chain, ragged last tile and last column block, outer dimensions,
+              # fewer lines than a tile is wide)
+              ((8200, 1028), 0), ((3, 2000, 520), 1), ((70000, 8), 0), ((5000, 12), 0), ((2, 131, 3, 64), 1), ((20000, 132), 0)]

@@ -319,6 +319,38 @@ def test_one_pass_scans_tile_sizes_and_many_groups(env):
     c2.close()
 
 
+def test_one_pass_scans_along_a_strided_axis(env):
+    # a scan along an axis that is not the contiguous one, with few lines: tiles of neighbouring lines stay in
+    # registers, publish their totals and collect their offsets from the tiles before them
+    gr, ctx, torch = env
+    c2 = gr.Context()
+    c2.set_option("interp", 0)
+    e2 = (gr, c2, torch)
+    a = _rand((4099, 1540), 68)
+    i = np.random.default_rng(69).integers(-2**31, 2**31 - 1, (4099, 1540), dtype=np.int64).astype(np.int32)
+    assert "one-pass-line-tiles" in gr.cumsum(c2.array(torch.from_numpy(a).cuda()), 0).plan()
+    assert "one-pass-line-tiles" in gr.cummax(c2.array(torch.from_numpy(i).cuda()), 0).plan()
+    # scan_polls 0: a tile that finds a total not yet published does not wait but recomputes its offsets from the
+    # input (the path that bounds every wait); same values, other association
+    for polls in (1 << 20, 0):
+        c2.set_option("scan_polls", polls)
+        got, ref, scale = run_scaled(e2, lambda xp, a: xp.cumsum(a[:, 4:] * 2.0 + a[:, :-4], 0), dict(a=a))
+        assert_reduction(got, ref, what=f"one-pass scan along axis 0, two shifted sources, poll limit {polls}", scale=scale)
+        got, ref = run_both(e2, lambda xp, a: xp.cumsum(abs(a) + 0.5, 0), dict(a=a))
+        assert_reduction(got, ref, what=f"one-pass scan along axis 0, positive terms, poll limit {polls}")   # per element
+        got, ref = run_both(e2, lambda xp, a: xp.cummax(a, 0) - xp.cummin(a, 0), dict(a=i))
+        assert np.array_equal(got, ref)
+        got, ref = run_both(e2, lambda xp, a: xp.cummin(a * a, 0), dict(a=i))   # wraps around; running minimum exact
+        assert np.array_equal(got, ref)
+    # one-pass results do not depend on timing: the same request twice gives the same bits
+    c2.set_option("scan_polls", 1 << 20)
+    t = c2.array(torch.from_numpy(a).cuda())
+    first = gr.cumsum(t * 1.5, 0).numpy()
+    for _ in range(3):
+        assert np.array_equal(gr.cumsum(t * 1.5, 0).numpy(), first)
+    c2.close()
+
+
 def test_scan_closed_forms_and_consumers(env):
     gr, ctx, torch = env
     n = 5000
