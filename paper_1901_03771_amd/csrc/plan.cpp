@@ -598,10 +598,30 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
   for (int k = 0; k + 2 < g->rank; ++k) outer *= g->dims[k];
   g->BX = std::min(256, std::max(1, next_pow2((C + 3) / 4)));
   if (c->opt_map_bx > 0 && c->opt_map_bx <= 256 && (c->opt_map_bx & (c->opt_map_bx - 1)) == 0) g->BX = std::min<int>(g->BX, (int)c->opt_map_bx);
-  g->BY = 256 / g->BX;
   bool shifted_rows = false;
   for (const AccessGroup& ag : g->groups)
     for (const auto& d : ag.deltas) if (g->rank >= 2 && d[g->rank - 2] != 0) shifted_rows = true;
+  // Programs without row-shifted views (pointwise and broadcast): a wave per 256 columns and the
+  // four waves of a workgroup on neighbouring row pairs, two rows per lane (measured on MI355X,
+  // normalize 8192^2: 83.0 us against 85.3 with 1024 columns by four rows per workgroup; stencils
+  // keep the wide tile, 96 us against 97-113)
+  // Only where every row piece of 256 columns is a run of whole 256-byte blocks in every array
+  // (rows of 1024 columns or more in multiples of 256, no views shifted along the columns, row
+  // strides in multiples of 64 elements): a narrow tile leaves the ends of unaligned pieces to
+  // other workgroups, and their partial lines cost more than the tile shape gains (x*row on
+  // 8192 x 8190: 113 us narrow, 95 us wide).
+  bool aligned = C >= 1024 && C % 256 == 0;
+  for (const AccessGroup& ag : g->groups) {
+    if (ag.structural_zero[g->rank - 1]) continue;
+    if (ag.deltas.size() != 1 || ag.coef[g->rank - 1] != 1 || ag.base % 64 != 0) aligned = false;
+    for (const auto& d : ag.deltas) if (d[g->rank - 1] != 0) aligned = false;
+    for (int k = 0; k + 1 < g->rank; ++k) if (!ag.structural_zero[k] && ag.coef[k] % 64 != 0) aligned = false;
+  }
+  for (int k = 0; k + 1 < g->rank; ++k) if (g->out_coef[k] % 64 != 0) aligned = false;
+  if (g->out_base % 64 != 0) aligned = false;
+  const bool narrow_tile = g->rank >= 2 && R > 1 && !shifted_rows && aligned && c->opt_map_bx == 0 && g->BX > 64;
+  if (narrow_tile) g->BX = 64;
+  g->BY = 256 / g->BX;
   auto tiles = [&](int vr, int uc) {
     int64_t tc = (int64_t)g->BX * 4 * uc, tr = (int64_t)g->BY * vr;
     return outer * ((C + tc - 1) / tc) * ((R + tr - 1) / tr);
@@ -610,7 +630,7 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
   if (g->rank == 1 || R == 1) {
     for (int uc : {4, 2}) if (tiles(1, uc) >= 2048) { g->UC = uc; break; }
   } else {
-    int want = 4;  // measured on MI355X: 4 rows per lane is the best patch for broadcast and stencil programs alike
+    int want = narrow_tile ? 2 : 4;  // measured on MI355X: 4 rows per lane is the best patch for stencil programs and for broadcast programs on wide tiles
     // (lanes whose patch sticks out of the array take the guarded point-by-point path: with few
     // rows the patch height has to divide them)
     for (int vr = want; vr >= 2; vr >>= 1)
