@@ -138,7 +138,7 @@ struct Em {
       case GR_SQRT: return "gr_sqrtf(" + x + ")";
       case GR_SQUARE: return "(" + x + " * " + x + ")";
       case GR_TANH: return "tanhf(" + x + ")";
-      case GR_ERF: return "erff(" + x + ")";
+      case GR_ERF: return "gr_erff(" + x + ")";
     }
     switch (op) {  // i32: two's-complement wrap-around through unsigned arithmetic
       case GR_NEG: return "((int)(0u - (unsigned)" + x + "))";
@@ -183,6 +183,13 @@ struct Em {
   static std::string zero(gr_dtype dt) { return dt == GR_F32 ? "0.0f" : (dt == GR_I64 ? "0ll" : "0"); }
 };
 
+// gr_erff, gr_divc: the text the interpreter kernels are compiled from as well
+#define GR_DEVICE_MATH_SOURCE(...) #__VA_ARGS__
+const char* const kDeviceMath =
+#include "device_math.h"
+    ;
+#undef GR_DEVICE_MATH_SOURCE
+
 void prelude(Em& e) {
   // every pointer the kernels dereference is a global-memory pointer (arguments arrive as
   // integers, so the address space has to be stated for global_load/global_store to be used)
@@ -216,6 +223,7 @@ void prelude(Em& e) {
          "  const float s = x * y, h = 0.5f * y;\n"
          "  const float t = __builtin_fmaf(__builtin_fmaf(-s, s, x), h, s);\n"
          "  return (x == 0.0f || x == __builtin_inff()) ? x : t;\n}\n"
+         << kDeviceMath << "\n"
          "static __device__ __forceinline__ float gr_xor(float v, int m) { return __shfl_xor(v, m, 64); }\n"
          "static __device__ __forceinline__ int gr_xor(int v, int m) { return __shfl_xor(v, m, 64); }\n"
          "static __device__ __forceinline__ long long gr_xor(long long v, int m) {\n"
@@ -266,7 +274,11 @@ void emit_scalar_program(Em& e, const std::vector<Instr>& prog, const std::vecto
       case IKind::LOAD: e.o << load_expr(in, (int)i); break;
       case IKind::CONST: e.o << e.cst(in.cslot); break;
       case IKind::UNARY: e.o << Em::unop(in.op, in.dtype, name(in.a)); break;
-      case IKind::BINARY: e.o << Em::binop(in.op, in.dtype, name(in.a), name(in.b)); break;
+      case IKind::BINARY:
+        // a quotient whose divisor is a scalar constant of the program: the same in every lane
+        if (in.op == GR_DIV && in.dtype == GR_F32 && in.b >= 0 && prog[in.b].kind == IKind::CONST) e.o << "gr_divc(" << name(in.a) << ", " << name(in.b) << ")";
+        else e.o << Em::binop(in.op, in.dtype, name(in.a), name(in.b));
+        break;
       case IKind::RED: e.o << "red" << in.phase; break;
       case IKind::ACC: e.o << acc_expr; break;
     }
@@ -626,7 +638,9 @@ void gen_rowred(Em& e) {
     switch (in.kind) {
       case IKind::CONST: return e.cst(in.cslot);
       case IKind::UNARY: return Em::unop(in.op, in.dtype, name(in.a, true));
-      case IKind::BINARY: return Em::binop(in.op, in.dtype, name(in.a, true), name(in.b, true));
+      case IKind::BINARY:
+        if (in.op == GR_DIV && in.dtype == GR_F32 && in.b >= 0 && g.prog[in.b].kind == IKind::CONST) return "gr_divc(" + name(in.a, true) + ", " + name(in.b, true) + ")";
+        return Em::binop(in.op, in.dtype, name(in.a, true), name(in.b, true));
       case IKind::RED: return "red" + std::to_string(in.phase);
       default: return "0";
     }

@@ -13,6 +13,11 @@
 
 #define GM __attribute__((address_space(1)))
 
+// gr_erff (and gr_divc, which agrees with the division below bit for bit): the text the generated kernels carry
+#define GR_DEVICE_MATH_SOURCE(...) __VA_ARGS__
+#include "device_math.h"
+#undef GR_DEVICE_MATH_SOURCE
+
 static __device__ __forceinline__ float gi_maxf(float a, float b) { return (a >= b || a != a) ? a : b; }
 static __device__ __forceinline__ float gi_minf(float a, float b) { return (a <= b || a != a) ? a : b; }
 
@@ -58,7 +63,7 @@ __global__ __launch_bounds__(256) void gr_interp_map_kernel(GrInterpArgs a) {
         case GI_FSQRT: r = __float_as_uint(sqrtf(fx)); break;
         case GI_FSQUARE: r = __float_as_uint(fx * fx); break;
         case GI_FTANH: r = __float_as_uint(tanhf(fx)); break;
-        case GI_FERF: r = __float_as_uint(erff(fx)); break;
+        case GI_FERF: r = __float_as_uint(gr_erff(fx)); break;
         case GI_FADD: r = __float_as_uint(fx + fy); break;
         case GI_FSUB: r = __float_as_uint(fx - fy); break;
         case GI_FMUL: r = __float_as_uint(fx * fy); break;
@@ -115,7 +120,7 @@ static __device__ __forceinline__ void gi_run(const GrInterpArgs& a, int pc, con
         case GI_FSQRT: r = __float_as_uint(sqrtf(fx)); break;
         case GI_FSQUARE: r = __float_as_uint(fx * fx); break;
         case GI_FTANH: r = __float_as_uint(tanhf(fx)); break;
-        case GI_FERF: r = __float_as_uint(erff(fx)); break;
+        case GI_FERF: r = __float_as_uint(gr_erff(fx)); break;
         case GI_FADD: r = __float_as_uint(fx + fy); break;
         case GI_FSUB: r = __float_as_uint(fx - fy); break;
         case GI_FMUL: r = __float_as_uint(fx * fy); break;

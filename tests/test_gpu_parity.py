@@ -182,6 +182,57 @@ def test_sqrt_of_every_float32(env):
     assert checked == (1 << 31) + (1 << 24) + ((1 << 32) - 0x81000000) // 256
 
 
+def test_erf_of_every_float32_below_four(env, env_interp):
+    # The generated kernels and the interpreter evaluate erf with a function of their own (two polynomial
+    # pieces and the hardware's power of two).  Against the oracle's erf (binary64, rounded once) for every
+    # float32 of magnitude below 4 -- from 4 on the result is 1 -- plus every 4096th pattern beyond, the
+    # infinities and NaNs: within 2 ulp, odd, +-1 beyond, NaN for NaN; and the interpreter returns the same bits.
+    gr, ctx, torch = env
+    worst = 0.0
+    step = 1 << 26
+    ranges = [(lo, min(lo + step, 0x40800000), 1) for lo in range(0, 0x40800000, step)] + [(0x40800000, 1 << 31, 4096)]
+    for lo, hi, stride in ranges:
+        bits = np.arange(lo, hi, stride, dtype=np.int64).astype(np.uint32)
+        x = bits.view(f32)
+        got = gr.erf(ctx.array(torch.from_numpy(x).cuda())).numpy()
+        ref = ora.erf(ora.array(x)).numpy()
+        nan = np.isnan(ref)
+        assert np.array_equal(np.isnan(got), nan)
+        err = np.abs(got.astype(np.float64) - ref.astype(np.float64)) / ulp_of(ref)
+        err[nan] = 0
+        worst = max(worst, float(err.max()))
+        assert err.max() <= 2.0, f"erf off by {err.max():.2f} ulp at bits 0x{int(bits[np.argmax(err)]):08x}"
+        neg = gr.erf(ctx.array(torch.from_numpy(-x).cuda())).numpy()
+        assert np.array_equal(neg[~nan], -got[~nan])
+        if lo == 0x3f000000 - (0x3f000000 % step) or stride > 1:   # the chunk around both pieces' meeting point, and the far range
+            gi, ci, _ = env_interp
+            again = gi.erf(ci.array(torch.from_numpy(x).cuda())).numpy()
+            assert np.array_equal(again.view(np.uint32), got.view(np.uint32)), "interpreter and generated kernel disagree on erf"
+    print(f"erf: worst error {worst:.3f} ulp")
+    x = np.array([0.0, -0.0, 4.0, 1e30, np.inf, -np.inf], f32)
+    got = gr.erf(ctx.array(torch.from_numpy(x).cuda())).numpy()
+    assert got.tolist()[2:] == [1.0, 1.0, 1.0, -1.0] and got[0] == 0 and np.signbit(got[1]) and not np.signbit(got[0])
+
+
+@pytest.mark.parametrize("c", [1.4142135623730951, 3.0, 0.1, 262144.0, 1e-12, 16777215.0, -7.0, 1.9999998807907104, 1e20, 1e-30, 3e38])
+def test_division_by_a_constant_for_every_float32(env, c):
+    # A quotient whose divisor is a scalar constant shares the refined reciprocal between a thread's
+    # quotients and skips scaling and fix-up where they cannot matter; the result must still be the
+    # correctly rounded quotient, bit for bit, for every float32 numerator (every 128th bit pattern per
+    # divisor here, every 8th for the square root of two; zeros, denormals, infinities and NaNs are among
+    # them): the oracle divides in IEEE arithmetic.
+    gr, ctx, torch = env
+    stride = 8 if c == 1.4142135623730951 else 128
+    step = 1 << 28
+    for lo in range(0, 1 << 32, step):
+        bits = np.arange(lo, lo + step, stride, dtype=np.int64).astype(np.uint32)
+        x = bits.view(f32)
+        got = (ctx.array(torch.from_numpy(x).cuda()) / c).numpy()
+        ref = (ora.array(x) / c).numpy()
+        same = (got.view(np.uint32) == ref.view(np.uint32)) | (np.isnan(ref) & np.isnan(got))
+        assert same.all(), f"x / {c!r} differs for bits 0x{int(bits[np.argmin(same)]):08x}: got {got[np.argmin(same)]!r}, IEEE {ref[np.argmin(same)]!r}"
+
+
 # ------------------------------------- full sizes, every element against the oracle --
 def test_normalize_full(env):
     gr, ctx, torch = env
