@@ -28,6 +28,8 @@ extern "C" {
  *   "gemm_bn"         width of the output tile of the matrix-product kernel: 32 or 128; 0 = 32 for
  *                     results of at most 96 columns and where the last 128-wide tile would be more
  *                     than half empty
+ *   "gemm_kstep"      values of k per step of the matrix-product kernel's main loop (one barrier per
+ *                     step): 16 (default), 32
  *   "nontemporal"     1 (default) = loads of arrays that are read once carry the non-temporal hint,
  *                     and so do the vector stores of a requested value of 192 MiB or more (not of
  *                     intermediate results of the request; except in kernels that read a transposed
@@ -42,17 +44,25 @@ extern "C" {
  *   "stage_diag"      1 (default) = kernels with such tiles take row blocks diagonally and give each
  *                     XCD a contiguous range of column blocks; 0 = row-major tile order
  *   "scan_min_threads", "scan_threads"
- *                     a scan along a non-contiguous axis gives each thread one line (four neighbouring
- *                     lines with dwordx4 loads); with fewer threads than scan_min_threads the lines
- *                     are cut into chunks so that about scan_threads threads run, at the price of a
- *                     second read of the input; 0 = 16384 / 65536 with dwordx4 loads, 32768 / 131072
- *                     with scalar loads
+ *                     a scan along a non-contiguous axis that does not qualify for one pass over tiles
+ *                     (see "scan_one_pass") gives each thread one line (four neighbouring lines with
+ *                     dwordx4 loads); with fewer threads than scan_min_threads the lines are cut into
+ *                     chunks so that about scan_threads threads run, at the price of a second read of
+ *                     the input; 0 = 16384 / 65536 with dwordx4 loads, 32768 / 131072 with scalar loads
+ *   "scan_polls"      polls a tile of a one-pass scan spends on each wait for a published total before
+ *                     it recomputes its offset from the input (default 2^20; 0 = never wait: every
+ *                     total that is not there yet is recomputed, which is how a test reaches that path)
  *   "scan_one_pass"   1 (default) = a scan of 4-byte values along a contiguous axis with few, long
  *                     lines (fewer than 512 lines of more than 32768 elements) reads its input once:
  *                     chained tiles that publish their totals (the map-scan primitive of Section 3.2
  *                     as a single kernel); 0 = chunk totals, a scan of the totals, then the chunks
  *                     with their offsets (three kernels, the input read twice); 2..16 = one pass
- *                     with tiles of that many 1024-element blocks
+ *                     with tiles of that many 1024-element blocks.  Any value but 0 also lets a scan
+ *                     of 4-byte values along a NON-contiguous axis (lines of 128 positions or more, the
+ *                     innermost line dimension contiguous and a multiple of four) read its input once:
+ *                     tiles of up to 256 neighbouring lines by up to 128 positions stay in registers,
+ *                     publish their totals per line and collect their offsets from the tiles before
+ *                     them; 0 = a thread per four lines, chunked as described above
  */
 
 /* dst[i] = src[i] for `bytes` bytes (multiple of 16; both device pointers,

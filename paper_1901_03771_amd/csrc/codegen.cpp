@@ -1708,7 +1708,17 @@ void gen_gemm(Em& e) {
   // own 32 rows): a 128-wide tile would spend the matrix cores on columns that do not exist.
   const int BN = g.BX == 32 ? 32 : 128;
   const int IB = BN == 128 ? 2 : 1, JB = IB;   // 32 x 32 blocks per wave along m and n
-  const int BP = BN + 4;                        // padded LDS row of the B tile
+  // padded LDS rows: k-major tiles of 128 (B: BN) floats.  An operand that is contiguous along k is
+  // transposed on its way into LDS by scalar writes, four k rows apart within a wave: a row pitch of
+  // 130 puts those rows eight banks apart (pitch 132: only two distinct bank offsets, every write a
+  // two-way conflict); an operand copied row by row with 16-byte writes needs a multiple of four.
+  // K advances in steps of KS = 16 (one barrier per step), or 32 on request (option "gemm_kstep";
+  // measured slower: 127 against 134 TFLOP/s on 4096^3).
+  const int KS = BN == 128 && g.UC == 2 ? 32 : 16;
+  const int TK = KS / 4;        // threads along k of an operand that is contiguous along k (four floats each)
+  const int NI = KS / 8;        // vector loads per thread and operand tile
+  const int AP = a_mode == 0 ? (KS == 32 ? 129 : 130) : 132;
+  const int BP = BN == 128 && b_mode == 1 ? (KS == 32 ? 129 : 130) : BN + 4;
   prelude(e);
   e.o << "typedef float f16v __attribute__((ext_vector_type(16)));\n";
   kernel_head(e, "gr_gemm");
@@ -1717,7 +1727,7 @@ void gen_gemm(Em& e) {
   e.o << "  const GM float* const A = q" << g.mat_group << "; const GM float* const B = q" << g.vec_group << ";\n";
   e.o << "  const long long am = " << e.coef(g.mat_group, 0) << ", ak = " << e.coef(g.mat_group, 1) << ", bk = " << e.coef(g.vec_group, 0)
       << ", bn = " << e.coef(g.vec_group, 1) << ";\n  (void)am; (void)ak; (void)bk; (void)bn;\n";
-  e.o << "  __shared__ float As[2][16][132];\n  __shared__ float Bs[2][16][" << BP << "];\n";
+  e.o << "  __shared__ float As[2][" << KS << "][" << AP << "];\n  __shared__ float Bs[2][" << KS << "][" << BP << "];\n";
   e.o << "  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;\n";
   if (BN == 128) e.o << "  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64, l32 = lane & 31, lh = lane >> 5;\n";
   else e.o << "  const int wm = wave * 32, wn = 0, l32 = lane & 31, lh = lane >> 5;\n";
@@ -1730,24 +1740,24 @@ void gen_gemm(Em& e) {
   e.o << "  const long long bm0 = (tile / tiles_n) * 128, bn0 = (tile % tiles_n) * " << BN << ";\n";
   e.o << "  const long long kbeg = split * KCH, KE = (kbeg + KCH < K) ? kbeg + KCH : K;\n";
   e.o << "  f16v acc[" << IB << "][" << JB << "];\n  for (int i = 0; i < " << IB << "; ++i) for (int j = 0; j < " << JB << "; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n";
-  e.o << "  float ra[8], rb[8];\n  (void)rb;\n";
+  e.o << "  float ra[" << 4 * NI << "], rb[" << 4 * NI << "];\n  (void)rb;\n";
   // --- global -> registers, per operand a guarded version (edge tiles, K tail) and an unguarded
   // one for tiles that lie inside the operand: straight-line loads that the compiler keeps in
   // flight under the matrix instructions of the previous step
   for (int guarded = 1; guarded >= 0; --guarded) {
     e.o << "  auto fetchA" << (guarded ? "_g" : "_u") << " = [&](long long k0) {\n";
     if (a_mode == 0) {
-      e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long row = bm0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n";
+      e.o << "    for (int i = 0; i < " << NI << "; ++i) {\n      const long long row = bm0 + tid / " << TK << " + " << 256 / TK << " * i, kk = k0 + (tid % " << TK << ") * 4;\n";
       if (guarded) e.o << "      if (row < M && kk + 4 <= KE) { const f4u w = *(const GM f4u*)(A + row * am + kk); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
                           "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (row < M && kk + j < KE) ? A[row * am + kk + j] : 0.0f; }\n    }\n";
       else e.o << "      const f4u w = *(const GM f4u*)(A + row * am + kk); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3];\n    }\n";
     } else if (a_mode == 1) {
-      e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, row = bm0 + (tid % 32) * 4;\n";
+      e.o << "    for (int i = 0; i < " << NI << "; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, row = bm0 + (tid % 32) * 4;\n";
       if (guarded) e.o << "      if (kk < KE && row + 4 <= M) { const f4u w = *(const GM f4u*)(A + kk * ak + row); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3]; }\n"
                           "      else { for (int j = 0; j < 4; ++j) ra[4*i+j] = (kk < KE && row + j < M) ? A[kk * ak + row + j] : 0.0f; }\n    }\n";
       else e.o << "      const f4u w = *(const GM f4u*)(A + kk * ak + row); ra[4*i] = w[0]; ra[4*i+1] = w[1]; ra[4*i+2] = w[2]; ra[4*i+3] = w[3];\n    }\n";
     } else {
-      e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; const long long row = bm0 + el % 128, kk = k0 + el / 128;\n";
+      e.o << "    for (int i = 0; i < " << 4 * NI << "; ++i) { const int el = tid + 256 * i; const long long row = bm0 + el % 128, kk = k0 + el / 128;\n";
       if (guarded) e.o << "      ra[i] = (row < M && kk < KE) ? A[row * am + kk * ak] : 0.0f; }\n";
       else e.o << "      ra[i] = A[row * am + kk * ak]; }\n";
     }
@@ -1758,53 +1768,92 @@ void gen_gemm(Em& e) {
       e.o << "    for (int i = 0; i < 2; ++i) { const int el = tid + 256 * i; const long long col = bn0 + el % 32, kk = k0 + el / 32;\n"
              "      rb[i] = (col < N && kk < KE) ? B[kk * bk + col * bn] : 0.0f; }\n";
     } else if (b_mode == 0) {
-      e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, col = bn0 + (tid % 32) * 4;\n";
+      e.o << "    for (int i = 0; i < " << NI << "; ++i) {\n      const long long kk = k0 + tid / 32 + 8 * i, col = bn0 + (tid % 32) * 4;\n";
       if (guarded) e.o << "      if (kk < KE && col + 4 <= N) { const f4u w = *(const GM f4u*)(B + kk * bk + col); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
                           "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (kk < KE && col + j < N) ? B[kk * bk + col + j] : 0.0f; }\n    }\n";
       else e.o << "      const f4u w = *(const GM f4u*)(B + kk * bk + col); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3];\n    }\n";
     } else if (b_mode == 1) {
-      e.o << "    for (int i = 0; i < 2; ++i) {\n      const long long col = bn0 + tid / 4 + 64 * i, kk = k0 + (tid % 4) * 4;\n";
+      e.o << "    for (int i = 0; i < " << NI << "; ++i) {\n      const long long col = bn0 + tid / " << TK << " + " << 256 / TK << " * i, kk = k0 + (tid % " << TK << ") * 4;\n";
       if (guarded) e.o << "      if (col < N && kk + 4 <= KE) { const f4u w = *(const GM f4u*)(B + col * bn + kk); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3]; }\n"
                           "      else { for (int j = 0; j < 4; ++j) rb[4*i+j] = (col < N && kk + j < KE) ? B[col * bn + kk + j] : 0.0f; }\n    }\n";
       else e.o << "      const f4u w = *(const GM f4u*)(B + col * bn + kk); rb[4*i] = w[0]; rb[4*i+1] = w[1]; rb[4*i+2] = w[2]; rb[4*i+3] = w[3];\n    }\n";
     } else {
-      e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; const long long col = bn0 + el % 128, kk = k0 + el / 128;\n";
+      e.o << "    for (int i = 0; i < " << 4 * NI << "; ++i) { const int el = tid + 256 * i; const long long col = bn0 + el % 128, kk = k0 + el / 128;\n";
       if (guarded) e.o << "      rb[i] = (col < N && kk < KE) ? B[kk * bk + col * bn] : 0.0f; }\n";
       else e.o << "      rb[i] = B[kk * bk + col * bn]; }\n";
     }
     e.o << "  };\n";
   }
-  // --- registers -> LDS (k-major tiles)
+  // --- registers -> LDS (k-major tiles), in pieces: a piece is what one of a thread's vector loads brought
+  // (four floats of A or of B).  The main loop puts one piece behind each of the last matrix
+  // instructions of a step, so that the LDS writes are issued while the matrix cores work; all of
+  // them in a row after the last matrix instruction cost a tenth of the kernel's time (measured).
+  std::vector<std::string> pieces;
+  for (int i = 0; i < NI; ++i) {
+    const std::string I = std::to_string(i);
+    if (a_mode == 0) pieces.push_back("for (int j = 0; j < 4; ++j) As[buf][(tid % " + std::to_string(TK) + ") * 4 + j][tid / " + std::to_string(TK) + " + " + std::to_string(256 / TK) + " * " + I + "] = ra[4*" + I + "+j];");
+    else if (a_mode == 1) pieces.push_back("for (int j = 0; j < 4; ++j) As[buf][tid / 32 + 8 * " + I + "][(tid % 32) * 4 + j] = ra[4*" + I + "+j];");
+    else pieces.push_back("for (int i = " + std::to_string(4 * i) + "; i < " + std::to_string(4 * i + 4) + "; ++i) { const int el = tid + 256 * i; As[buf][el / 128][el % 128] = ra[i]; }");
+  }
+  if (BN == 32) pieces.push_back("for (int i = 0; i < 2; ++i) { const int el = tid + 256 * i; Bs[buf][el / 32][el % 32] = rb[i]; }");
+  else for (int i = 0; i < NI; ++i) {
+    const std::string I = std::to_string(i);
+    if (b_mode == 0) pieces.push_back("for (int j = 0; j < 4; ++j) Bs[buf][tid / 32 + 8 * " + I + "][(tid % 32) * 4 + j] = rb[4*" + I + "+j];");
+    else if (b_mode == 1) pieces.push_back("for (int j = 0; j < 4; ++j) Bs[buf][(tid % " + std::to_string(TK) + ") * 4 + j][tid / " + std::to_string(TK) + " + " + std::to_string(256 / TK) + " * " + I + "] = rb[4*" + I + "+j];");
+    else pieces.push_back("for (int i = " + std::to_string(4 * i) + "; i < " + std::to_string(4 * i + 4) + "; ++i) { const int el = tid + 256 * i; Bs[buf][el / 128][el % 128] = rb[i]; }");
+  }
   e.o << "  auto stash = [&](int buf) {\n";
-  if (a_mode == 0) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) As[buf][(tid % 4) * 4 + j][tid / 4 + 64 * i] = ra[4*i+j];\n";
-  else if (a_mode == 1) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) As[buf][tid / 32 + 8 * i][(tid % 32) * 4 + j] = ra[4*i+j];\n";
-  else e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; As[buf][el / 128][el % 128] = ra[i]; }\n";
-  if (BN == 32) e.o << "    for (int i = 0; i < 2; ++i) { const int el = tid + 256 * i; Bs[buf][el / 32][el % 32] = rb[i]; }\n";
-  else if (b_mode == 0) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) Bs[buf][tid / 32 + 8 * i][(tid % 32) * 4 + j] = rb[4*i+j];\n";
-  else if (b_mode == 1) e.o << "    for (int i = 0; i < 2; ++i) for (int j = 0; j < 4; ++j) Bs[buf][(tid % 4) * 4 + j][tid / 4 + 64 * i] = rb[4*i+j];\n";
-  else e.o << "    for (int i = 0; i < 8; ++i) { const int el = tid + 256 * i; Bs[buf][el / 128][el % 128] = rb[i]; }\n";
+  for (const std::string& pc : pieces) e.o << "    " << pc << "\n";
   e.o << "  };\n";
-  e.o << "  auto step = [&](int cur) {\n#pragma unroll\n    for (int ks = 0; ks < 8; ++ks) {\n";
-  if (BN == 128)
-    e.o << "      const float a0 = As[cur][2 * ks + lh][wm + l32], a1 = As[cur][2 * ks + lh][wm + 32 + l32];\n"
-           "      const float b0 = Bs[cur][2 * ks + lh][wn + l32], b1 = Bs[cur][2 * ks + lh][wn + 32 + l32];\n"
-           "      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);\n"
-           "      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);\n"
-           "      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);\n"
-           "      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);\n    }\n  };\n";
-  else
-    e.o << "      const float a0 = As[cur][2 * ks + lh][wm + l32];\n"
+  if (BN == 128) {
+    // The operands of matrix-instruction group ks + 1 are read from LDS before the four matrix
+    // instructions of group ks are issued: the reads complete under 256 cycles of matrix work
+    // (measured on 4096^3: 127 -> 133.7 TFLOP/s), and one piece of the next tile goes to LDS behind
+    // each of the last matrix instructions of the step.  Scheduling barriers keep the order written
+    // here: the compiler's scheduler would sink the reads below the matrix instructions and gather
+    // the LDS writes at the end.  (A pure matrix-instruction loop reaches 155.6 TFLOP/s on this
+    // device.  Measured and not adopted: steps of 32 values of k, 127 TFLOP/s; two barriers per
+    // step with the LDS writes in the first half and the first operands of the next step read
+    // before the second barrier, 132.6; a second or third resident workgroup per compute unit,
+    // workgroups started half a step apart: no change.)
+    const int G = KS / 2;                                   // groups of four matrix instructions per step
+    const int first = G * 4 - 1 - (int)pieces.size();       // matrix instruction (0-based, of 4G) after which the first piece goes; none after the last
+    e.o << "  auto step = [&](int cur, bool more) {\n"
+           "    const int buf = cur ^ 1;\n"
+           "    float a0 = As[cur][lh][wm + l32], a1 = As[cur][lh][wm + 32 + l32];\n"
+           "    float b0 = Bs[cur][lh][wn + l32], b1 = Bs[cur][lh][wn + 32 + l32];\n";
+    for (int ks = 0; ks < G; ++ks) {
+      e.o << "    {\n      float na0 = 0.0f, na1 = 0.0f, nb0 = 0.0f, nb1 = 0.0f;\n";
+      if (ks < G - 1)
+        e.o << "      na0 = As[cur][" << 2 * ks + 2 << " + lh][wm + l32]; na1 = As[cur][" << 2 * ks + 2 << " + lh][wm + 32 + l32];\n"
+               "      nb0 = Bs[cur][" << 2 * ks + 2 << " + lh][wn + l32]; nb1 = Bs[cur][" << 2 * ks + 2 << " + lh][wn + 32 + l32];\n";
+      e.o << "      __builtin_amdgcn_sched_barrier(0);\n";
+      const char* mm[4] = {"acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);", "acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);",
+                           "acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);", "acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);"};
+      for (int m = 0; m < 4; ++m) {
+        e.o << "      " << mm[m] << "\n";
+        const int pi = ks * 4 + m - first;
+        if (pi >= 0 && pi < (int)pieces.size())
+          e.o << "      __builtin_amdgcn_sched_barrier(0);\n      if (more) { " << pieces[pi] << " }\n      __builtin_amdgcn_sched_barrier(0);\n";
+      }
+      e.o << "      a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;\n    }\n";
+    }
+    e.o << "  };\n";
+  } else
+    e.o << "  auto step = [&](int cur, bool more) {\n#pragma unroll\n    for (int ks = 0; ks < 8; ++ks) {\n"
+           "      const float a0 = As[cur][2 * ks + lh][wm + l32];\n"
            "      const float b0 = Bs[cur][2 * ks + lh][l32];\n"
-           "      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);\n    }\n  };\n";
-  e.o << "  const long long nkt = KE > kbeg ? (KE - kbeg + 15) / 16 : 0;\n  int cur = 0;\n";
+           "      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);\n    }\n"
+           "    if (more) stash(cur ^ 1);\n  };\n";
+  e.o << "  const long long nkt = KE > kbeg ? (KE - kbeg + " << KS - 1 << ") / " << KS << " : 0;\n  int cur = 0;\n";
   // workgroup-uniform choice between four loops: each operand unguarded where its tile is interior
-  e.o << "  const bool kfull = (KE - kbeg) % 16 == 0, a_in = kfull && bm0 + 128 <= M, b_in = kfull && bn0 + " << BN << " <= N;\n";
+  e.o << "  const bool kfull = (KE - kbeg) % " << KS << " == 0, a_in = kfull && bm0 + 128 <= M, b_in = kfull && bn0 + " << BN << " <= N;\n";
   auto loop = [&](const char* fa, const char* fb, const char* ind) {
     e.o << ind << "if (nkt > 0) { " << fa << "(kbeg); " << fb << "(kbeg); stash(0); }\n" << ind << "__syncthreads();\n"
         << ind << "for (long long kt = 0; kt < nkt; ++kt) {\n"
-        << ind << "  if (kt + 1 < nkt) { " << fa << "(kbeg + (kt + 1) * 16); " << fb << "(kbeg + (kt + 1) * 16); }\n"
-        << ind << "  step(cur);\n"
-        << ind << "  if (kt + 1 < nkt) stash(cur ^ 1);\n" << ind << "  __syncthreads();\n" << ind << "  cur ^= 1;\n" << ind << "}\n";
+        << ind << "  if (kt + 1 < nkt) { " << fa << "(kbeg + (kt + 1) * " << KS << "); " << fb << "(kbeg + (kt + 1) * " << KS << "); }\n"
+        << ind << "  step(cur, kt + 1 < nkt);\n"
+        << ind << "  __syncthreads();\n" << ind << "  cur ^= 1;\n" << ind << "}\n";
   };
   e.o << "  if (a_in && b_in) {\n";
   loop("fetchA_u", "fetchB_u", "    ");

@@ -907,6 +907,8 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     // 8192 x 512 x 520: 67 against 94 us; a full 128-wide tile costs about 0.3 of four 32-wide ones less)
     g->BX = (g->N <= 96 || ((g->N + 127) / 128) * 128 - g->N >= 64) ? 32 : 128;
     if (c->opt_gemm_bn == 32 || c->opt_gemm_bn == 128) g->BX = (int)c->opt_gemm_bn;
+    // k extent of one step of the main loop (one barrier per step): 16, or 32 on request
+    g->UC = (g->BX == 128 && c->opt_gemm_kstep == 32) ? 2 : 1;
     {
       const int64_t tiles = ((g->M + 127) / 128) * ((g->N + g->BX - 1) / g->BX);
       if (tiles > 0 && tiles < 192 && g->K >= 256) {

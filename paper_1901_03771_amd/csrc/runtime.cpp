@@ -591,8 +591,8 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       const int64_t bn = g.BX == 32 ? 32 : 128;
       const int64_t tiles = ((g.M + 127) / 128) * ((g.N + bn - 1) / bn);
       const int64_t nsplit = std::max(1, g.slabs);
-      // k extent of one split: a multiple of 16 that covers K in nsplit pieces
-      const int64_t kch = nsplit > 1 ? (((g.K + nsplit - 1) / nsplit + 15) / 16) * 16 : g.K;
+      // k extent of one split: a multiple of 32 (the longer of the two k steps) that covers K in nsplit pieces
+      const int64_t kch = nsplit > 1 ? (((g.K + nsplit - 1) / nsplit + 31) / 32) * 32 : g.K;
       s[L.extra + 3] = (uint64_t)nsplit;
       s[L.ocoef + 1] = (uint64_t)std::max<int64_t>(kch, 1);
       if (nsplit > 1) {
