@@ -314,7 +314,7 @@ void gen_map(Em& e) {
   e.o << "  const long long C = " << e.dim(cd) << ";\n";
   e.o << "  const long long R = " << (rank >= 2 ? e.dim(rd) : std::string("1")) << ";\n";
   // tile bookkeeping in 32-bit unsigned arithmetic (the grid has fewer than 2^31 tiles)
-  e.o << "  const unsigned nbx = (unsigned)((C + " << TC - 1 << ") / " << TC << "), nby = (unsigned)((R + " << TR - 1 << ") / " << TR << ");\n";
+  e.o << "  const unsigned nbx = (unsigned)((C + " << g.cphase + TC - 1 << ") / " << TC << "), nby = (unsigned)((R + " << TR - 1 << ") / " << TR << ");\n";
   e.o << "  unsigned tile = blockIdx.x;\n";
   if (g.xcd_remap) {
     // consecutive tiles go to the same XCD (workgroups are dealt round-robin over the 8 XCDs),
@@ -343,7 +343,7 @@ void gen_map(Em& e) {
     for (int k = rank - 3; k >= 0; --k) e.o << "  const long long i" << k << " = orem % (unsigned)" << e.dim(k) << "; orem /= (unsigned)" << e.dim(k) << ";\n";
   }
   e.o << "  const int tx = threadIdx.x % " << g.BX << ", ty = threadIdx.x / " << g.BX << ";\n";
-  e.o << "  const long long r0 = (long long)by * " << TR << " + ty * " << g.VR << ", c0 = (long long)bx * " << TC << " + tx * 4;\n";
+  e.o << "  const long long r0 = (long long)by * " << TR << " + ty * " << g.VR << ", c0 = (long long)bx * " << TC << " + tx * 4" << (g.cphase ? " - " + std::to_string(g.cphase) : std::string()) << ";\n";
   group_pointers(e, "  ");
   for (size_t gi = 0; gi < g.groups.size(); ++gi) {
     const AccessGroup& ag = g.groups[gi];
@@ -416,7 +416,7 @@ void gen_map(Em& e) {
     e.o << "  __syncthreads();\n";
   }
   // ---- lanes whose whole patch lies inside the array: straight-line ----
-  e.o << "  if (r0 + " << g.VR << " <= R && c0 + " << (g.UC - 1) * g.BX * 4 + 4 << " <= C) {\n";
+  e.o << "  if (r0 + " << g.VR << " <= R && c0 + " << (g.UC - 1) * g.BX * 4 + 4 << " <= C" << (g.cphase ? " && c0 >= 0" : "") << ") {\n";
   // group the contiguous loads of the patch program into vector loads
   std::map<int, std::string> load_name;  // instr -> expression
   {
@@ -523,7 +523,7 @@ void gen_map(Em& e) {
          "      for (int u = 0; u < " << g.UC << "; ++u)\n"
          "        for (int j = 0; j < 4; ++j) {\n"
          "          const long long cj = (long long)u * " << g.BX * 4 << " + j;\n"
-         "          if (r0 + v < R && c0 + cj < C) {\n";
+         "          if (r0 + v < R && c0 + cj < C" << (g.cphase ? " && c0 + cj >= 0" : "") << ") {\n";
   emit_scalar_program(e, g.prog1, {g.result1},
                       [&](const Instr& in, int) {
                         const AccessGroup& ag = g.groups[in.group];

@@ -180,6 +180,7 @@ struct GroupPlan {
   int row_threads = 64;                  // ROWRED: lanes cooperating on one row (64 or 256)
   int row_iters = 1;                     // ROWRED: rows a lane group takes in one launch (short rows, one value per row)
   bool xcd_remap = false;
+  int cphase = 0;     // map: lanes own columns 4k - cphase .. 4k - cphase + 3, so that their vector stores are 16-byte aligned in the output
   int stage_mask = 0;                    // MAP: access groups (bit per group) read through a transposing LDS tile
   int diag = 0;                          // MAP with staged operands: tile rows are taken diagonally (row block + column block)
   int tail = 0;                          // MAP: columns mod 4 of a narrow array (1..3): its last lanes get straight-line code too

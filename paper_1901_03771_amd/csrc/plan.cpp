@@ -472,7 +472,7 @@ void make_signature(GroupPlan* g) {
   std::string s;
   s.reserve(256 + 32 * (g->prog.size() + g->prog1.size()));
   for (int64_t v : {(int64_t)g->kind, (int64_t)g->rank, (int64_t)g->out_dtype, (int64_t)g->out_per_row, (int64_t)g->BX, (int64_t)g->BY,
-                    (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads + 1024 * (int64_t)g->row_iters, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask + (((int64_t)g->tail) << 40) + (((int64_t)g->diag) << 44), (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
+                    (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads + 1024 * (int64_t)g->row_iters, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask + (((int64_t)g->tail) << 40) + (((int64_t)g->diag) << 44) + (((int64_t)g->cphase) << 48), (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
                     (int64_t)g->red_kept_rank, (int64_t)g->gemv_mode, (int64_t)g->LPR, (int64_t)g->KV, (int64_t)g->mat_group,
                     (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode + 16 * (int64_t)g->scan_vec + (g->scan_mode >= 2 ? 256 * g->scan_chunk : 0) /* (a one-pass scan's tile size is compiled in) */, (int64_t)g->out_unit, (int64_t)g->groups.size()})
     put(s, v);
@@ -659,6 +659,16 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
   if (c->opt_map_rows > 0 && g->rank >= 2) g->VR = (int)std::min<int64_t>(c->opt_map_rows, 16);
   if (c->opt_map_chunks > 0) g->UC = (int)std::min<int64_t>(c->opt_map_chunks, 8);
   g->xcd_remap = shifted_rows;
+  // A strided destination (the box of a slice assignment, a stencil sweep writing the interior of a
+  // grid) may start off a 16-byte boundary while its rows are 16-byte multiples apart: lanes then own
+  // the column groups that are aligned in the OUTPUT (the first and the last group of a row are
+  // partial and take the guarded path), so that a wave's vector stores cover whole cache lines.
+  g->cphase = 0;
+  if (g->rank >= 2 && C >= 256 && g->out_unit && g->out_dtype != GR_I64 && !g->stage_mask && g->UC == 1 && c->opt_map_phase) {
+    bool rows_aligned = true;
+    for (int k = 0; k + 1 < g->rank; ++k) if (g->out_coef[k] % 4 != 0) rows_aligned = false;
+    if (rows_aligned) g->cphase = (int)(((g->out_base % 4) + 4) % 4);
+  }
   // Narrow arrays (points, pixels: a few columns): the lanes that own the last, incomplete group
   // of four columns are a large share of all lanes (all of them below four columns).  The kernel
   // is specialised on columns mod 4 and gives those lanes straight-line code as well.

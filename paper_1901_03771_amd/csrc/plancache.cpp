@@ -145,7 +145,7 @@ std::string dump(const std::vector<std::unique_ptr<GroupPlan>>& groups) {
       for (const ConstSlot& cs : g->consts) o << " c" << (int)cs.dtype << ":" << bits_of(cs.value);
       for (const Phase& p : g->phases) o << " ph" << p.op << "," << (int)p.in_dtype << "," << (int)p.out_dtype << "," << p.value << "," << (p.node ? p.node->id : 0);
       o << "\n out_base=" << g->out_base << " unit=" << g->out_unit << " dt=" << (int)g->out_dtype << " per_row=" << g->out_per_row << " sched=" << g->BX << ","
-        << g->BY << "," << g->VR << "," << g->UC << "," << g->NP << "," << g->row_threads << "," << g->row_iters << "," << g->xcd_remap << "," << g->stage_mask << "," << g->tail << "," << g->nt << ","
+        << g->BY << "," << g->VR << "," << g->UC << "," << g->NP << "," << g->row_threads << "," << g->row_iters << "," << g->xcd_remap << "," << g->cphase << "," << g->stage_mask << "," << g->tail << "," << g->nt << ","
         << g->red_mode << "," << g->red_vec << "," << g->red_out << "," << g->red_len << "," << g->red_kept_rank << "," << g->scan_mode << "," << g->scan_vec << ","
         << g->scan_chunk << "," << g->scan_nchunk << "," << g->gemv_mode << "," << g->M << "," << g->K << "," << g->N << "," << g->mat_group << ","
         << g->vec_group << "," << g->LPR << "," << g->KV << "," << g->slabs << "," << g->unroll << " result1=" << g->result1 << " prog1=" << g->prog1.size() << "\n";  // (prog / results of a map sub-graph are expanded on demand)

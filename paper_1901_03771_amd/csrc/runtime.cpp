@@ -506,7 +506,7 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       int64_t C = g.dims[g.rank - 1], R = g.rank >= 2 ? g.dims[g.rank - 2] : 1, outer = 1;
       for (int k2 = 0; k2 + 2 < g.rank; ++k2) outer *= g.dims[k2];
       int64_t TC = (int64_t)g.BX * 4 * g.UC, TR = (int64_t)g.BY * g.VR;
-      int64_t ntiles = outer * ((C + TC - 1) / TC) * ((R + TR - 1) / TR);
+      int64_t ntiles = outer * ((C + g.cphase + TC - 1) / TC) * ((R + TR - 1) / TR);
       int64_t grid = g.xcd_remap ? 8 * ((ntiles + 7) / 8) : ntiles;
       return launch(c, k->fn, k->name, grid, s);
     }
