@@ -9,6 +9,7 @@
 
 extern "C" int gr_launch_interp_map(void* stream, const GrInterpArgs* args, unsigned grid);
 extern "C" int gr_launch_interp_rowred(void* stream, const GrInterpRowArgs* args, unsigned grid);
+extern "C" int gr_launch_interp_gen(void* stream, const GrInterpGenArgs* args, unsigned grid);
 
 namespace gr {
 
@@ -186,6 +187,8 @@ static int encode_segment(const GroupPlan& g, const std::vector<Instr>& p, int w
     } else if (in.kind == IKind::RED) {
       if (in.phase < 0 || in.phase >= GR_INTERP_PHASES) return -1;
       op = GI_RED; xa = (unsigned)in.phase;
+    } else if (in.kind == IKind::ACC) {
+      op = GI_RED; xa = 0;   // the accumulated sum of a contraction reaches its epilogue as phase value 0
     } else if (in.kind == IKind::UNARY || in.kind == IKind::BINARY) {
       int oc = opcode(in);
       if (oc < 0 || in.a < 0 || slot[in.a] < 0) return -1;
@@ -246,6 +249,102 @@ bool interp_encode_rowred(const GroupPlan& g, void* out_ptr, GrInterpRowArgs* R,
   const int rb = 256 / R->lanes;
   *grid = (unsigned)((rows + rb - 1) / rb);
   return true;
+}
+
+// A reduction over any axes, a scan or a contraction with its epilogue (sub-graphs that are cuts
+// of their own) for the plain interpreter kernels.  Only sizes that keep the interpreter's run well
+// below a compilation are taken.
+bool interp_encode_gen(const GroupPlan& g, void* out_ptr, GrInterpGenArgs* G, unsigned* grid) {
+  if (g.pair || g.prog.empty()) return false;
+  std::memset(G, 0, sizeof *G);
+  const int pad = GR_INTERP_RANK - g.rank;
+  int ni = 0, nl = 0;
+  if (g.kind == GroupKind::REDUCE || g.kind == GroupKind::SCAN) {
+    if (g.phases.size() != 1) return false;
+    const Phase& ph = g.phases[0];
+    if (ph.in_dtype == GR_I64 || (ph.out_dtype == GR_I64 && !(ph.in_dtype == GR_I32 && ph.op == GR_SUM))) return false;
+    if (!encode_operands(g, &G->m)) return false;
+    G->op = ph.op == GR_SUM ? 0 : (ph.op == GR_MAX ? 1 : 2);
+    G->is_int = ph.in_dtype == GR_I32;
+    G->out_i64 = ph.out_dtype == GR_I64;
+    G->slot = encode_segment(g, g.prog, ph.value, &G->m, &ni, &nl);
+    if (G->slot < 0) return false;
+    G->m.n_instr = ni;
+    G->m.out = (unsigned long long)(uintptr_t)out_ptr;
+    int64_t total = 1;
+    for (int k = 0; k < g.rank; ++k) total *= g.dims[k];
+    if (total < 1 || total > (int64_t)1 << 28) return false;
+    if (g.kind == GroupKind::REDUCE) {
+      G->kind = GI_KIND_REDUCE;
+      G->first_reduced = pad + g.red_kept_rank;
+      G->nout = 1;
+      for (int k = 0; k < g.red_kept_rank; ++k) G->nout *= g.dims[k];
+      G->red_len = total / G->nout;
+      if (G->nout != g.red_out || G->nout > 0x7fffffffLL) return false;
+      // a workgroup per output: many outputs over a short strided range would crawl
+      if (G->nout > (int64_t)1 << 22) return false;
+      *grid = (unsigned)G->nout;
+      return true;
+    }
+    G->kind = GI_KIND_SCAN;
+    const int64_t L = g.dims[g.rank - 1];
+    G->red_len = L;
+    G->nout = total / std::max<int64_t>(L, 1);
+    if (L > (int64_t)1 << 21 || G->nout > 0x7fffffffLL) return false;   // a line is walked by one workgroup, 256 elements per step
+    for (int k = 0; k < g.rank; ++k) G->m.ocoef[k + pad] = g.out_coef[k];
+    *grid = (unsigned)G->nout;
+    return true;
+  }
+  if (g.kind != GroupKind::GEMV && g.kind != GroupKind::GEMM) return false;
+  if (g.out_dtype != GR_F32 || g.results.empty() || g.mat_group < 0 || g.vec_group < 0) return false;
+  const AccessGroup& mg = g.groups[g.mat_group];
+  const AccessGroup& vg = g.groups[g.vec_group];
+  if (mg.dtype != GR_F32 || vg.dtype != GR_F32 || !mg.leaf || !mg.leaf->data || !vg.leaf || !vg.leaf->data) return false;
+  if (!encode_operands(g, &G->m)) return false;
+  G->slot = encode_segment(g, g.prog, g.results[0], &G->m, &ni, &nl);
+  if (G->slot < 0) return false;
+  G->m.n_instr = ni;
+  G->m.out = (unsigned long long)(uintptr_t)out_ptr;
+  G->mat = (unsigned long long)(uintptr_t)mg.leaf->data + 4ull * (unsigned long long)mg.base;
+  G->vec = (unsigned long long)(uintptr_t)vg.leaf->data + 4ull * (unsigned long long)vg.base;
+  G->am = mg.coef[0]; G->ak = mg.coef[1];
+  G->M = g.M; G->K = g.K;
+  if (g.kind == GroupKind::GEMV) {
+    if (g.gemv_mode == 2 || g.M < 1 || g.M > 0x7fffffffLL || g.M * std::max<int64_t>(g.K, 1) > (int64_t)1 << 28) return false;
+    G->kind = GI_KIND_GEMV;
+    G->N = 1;
+    G->bk = vg.coef[1]; G->bn = 0;
+    *grid = (unsigned)g.M;
+    return true;
+  }
+  if (g.M < 1 || g.N < 1 || g.M * g.N > (int64_t)1 << 30 || g.M * g.N * std::max<int64_t>(g.K, 1) > (int64_t)1 << 36) return false;
+  G->kind = GI_KIND_GEMM;
+  G->N = g.N;
+  G->bk = vg.coef[0]; G->bn = vg.coef[1];
+  *grid = (unsigned)((g.M * g.N + 255) / 256);
+  return true;
+}
+
+gr_status interp_launch_gen(gr_ctx* c, const GrInterpGenArgs& G, unsigned grid) {
+  if (c->device < 0) { c->stats.kernel_launches++; c->stats.interp_launches++; return GR_OK; }  // dry run
+  static const char* const names[] = {"gr_interp_reduce", "gr_interp_scan", "gr_interp_gemv", "gr_interp_gemm"};
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (c->opt_profile) {
+    for (hipEvent_t* ev : {&e0, &e1}) {
+      if (!c->event_pool.empty()) { *ev = c->event_pool.back(); c->event_pool.pop_back(); }
+      else if (hipEventCreate(ev) != hipSuccess) return fail(c, GR_ERR_HIP, "hipEventCreate failed");
+    }
+    (void)hipEventRecord(e0, c->stream);
+  }
+  int e = gr_launch_interp_gen(c->stream, &G, grid);
+  if (e != 0) return fail(c, GR_ERR_HIP, std::string("interpreter launch -> ") + hipGetErrorName((hipError_t)e));
+  if (c->opt_profile) {
+    (void)hipEventRecord(e1, c->stream);
+    c->prof.push_back({names[G.kind], e0, e1});
+  }
+  c->stats.kernel_launches++;
+  c->stats.interp_launches++;
+  return GR_OK;
 }
 
 gr_status interp_launch_rowred(gr_ctx* c, const GrInterpRowArgs& R, unsigned grid) {

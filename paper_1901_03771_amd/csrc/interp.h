@@ -52,3 +52,26 @@ struct GrInterpRowArgs {
   int lanes;                                 // lanes per row and vec4 positions per lane: those of the generated kernel
   int positions;                             // (1, 2, 4, 8, 16, 64, 128 or 256 lanes)
 };
+
+// Sub-graphs that are cuts of their own -- a reduction over any axes, a scan, a contraction with
+// its pointwise epilogue -- through the interpreter: the value program (for a contraction: the
+// epilogue, which reads the accumulated sum as phase value 0) is byte code as above; the kernel
+// around it is chosen by `kind`.  Plain schedules (a workgroup per output, per line or per row, a
+// thread per element of a matrix product): they bridge the fraction of a second a compilation
+// takes.  Integer and max/min results are exact; a float sum is associated differently from the
+// generated kernel's (both are deterministic and within the same bound of the exact sum).
+enum { GI_KIND_REDUCE = 0, GI_KIND_SCAN, GI_KIND_GEMV, GI_KIND_GEMM };
+
+struct GrInterpGenArgs {
+  GrInterpArgs m;              // dims (right-aligned), operands, constants, code; out = first output element
+  int kind;
+  int slot;                    // LDS slot of the program's value
+  int op;                      // 0 sum, 1 max, 2 min
+  int is_int;                  // values are i32 (else f32)
+  int out_i64;                 // the running value / result is a 64-bit integer (sums of i32)
+  int first_reduced;           // reduce: dims [0, first_reduced) are kept, the rest is reduced (index into the right-aligned dims)
+  long long nout, red_len;     // reduce: outputs and reduced elements per output; scan: lines and line length
+  unsigned long long mat, vec; // contractions: byte addresses of element (0, 0) of both operands
+  long long am, ak, bk, bn;    // A[row * am + k * ak], B[k * bk + col * bn] (a vector operand: bn = 0)
+  long long M, N, K;
+};

@@ -223,6 +223,167 @@ __global__ __launch_bounds__(256) void gr_interp_rowred_kernel(GrInterpRowArgs A
   }
 }
 
+// ---- reductions over any axes, scans and contractions -------------------------------------------
+
+static __device__ __forceinline__ unsigned long long gi_identity64(int op, int is_int, int out_i64) {
+  if (out_i64) return op == 0 ? 0ull : (op == 1 ? 0x8000000000000000ull : 0x7fffffffffffffffull);
+  if (is_int) return op == 0 ? 0u : (op == 1 ? 0x80000000u : 0x7fffffffu);
+  return op == 0 ? 0u : (op == 1 ? 0xff800000u : 0x7f800000u);
+}
+
+// combine(x, y) on running values: 64-bit integers where the result is one (an i32 value entering
+// a sum is widened before), else 32-bit values in the low word
+static __device__ __forceinline__ unsigned long long gi_combine64(int op, int is_int, int out_i64, unsigned long long x, unsigned long long y) {
+  if (out_i64) {
+    const long long ix = (long long)x, iy = (long long)y;
+    return op == 0 ? x + y : (op == 1 ? (ix >= iy ? x : y) : (ix <= iy ? x : y));
+  }
+  return gi_combine(op, is_int, (unsigned)x, (unsigned)y);
+}
+
+static __device__ __forceinline__ unsigned long long gi_widen(int out_i64, unsigned v) {
+  return out_i64 ? (unsigned long long)(long long)(int)v : (unsigned long long)v;
+}
+
+// folds the 256 running values of a workgroup in a fixed tree; every lane returns the result
+static __device__ __forceinline__ unsigned long long gi_fold256(unsigned long long* sm, int op, int is_int, int out_i64, unsigned long long v) {
+  sm[threadIdx.x] = v;
+  __syncthreads();
+  for (int d = 128; d > 0; d >>= 1) {
+    if ((int)threadIdx.x < d) sm[threadIdx.x] = gi_combine64(op, is_int, out_i64, sm[threadIdx.x], sm[threadIdx.x + d]);
+    __syncthreads();
+  }
+  const unsigned long long r = sm[0];
+  __syncthreads();
+  return r;
+}
+
+// Reduction: a workgroup per output; its lanes take the reduced range 256 elements at a time.
+__global__ __launch_bounds__(256) void gr_interp_reduce_kernel(GrInterpGenArgs A) {
+  __shared__ unsigned vals[GR_INTERP_SLOTS * 256];
+  __shared__ unsigned long long sm[256];
+  constexpr int R = GR_INTERP_RANK, CD = R - 1;
+  const GrInterpArgs& a = A.m;
+  unsigned full[R];
+  {
+    unsigned long long rem = blockIdx.x;
+    for (int k = A.first_reduced - 1; k >= 0; --k) { const unsigned long long d = (unsigned long long)a.dims[k]; full[k] = (unsigned)(rem % d); rem /= d; }
+  }
+  unsigned* const my = vals + threadIdx.x;
+  const int op = A.op, is_int = A.is_int, w64 = A.out_i64;
+  unsigned long long acc = gi_identity64(op, is_int, w64);
+  for (long long r = threadIdx.x; r < A.red_len; r += 256) {
+    unsigned long long rem = (unsigned long long)r;
+    for (int k = CD; k >= A.first_reduced; --k) { const unsigned long long d = (unsigned long long)a.dims[k]; full[k] = (unsigned)(rem % d); rem /= d; }
+    gi_run(a, 0, a.n_instr, (long long)full[CD], full, my, nullptr);
+    acc = gi_combine64(op, is_int, w64, acc, gi_widen(w64, my[A.slot * 256]));
+  }
+  acc = gi_fold256(sm, op, is_int, w64, acc);
+  if (threadIdx.x == 0) {
+    if (w64) *(GM unsigned long long*)(a.out + 8ull * blockIdx.x) = acc;
+    else *(GM unsigned*)(a.out + 4ull * blockIdx.x) = (unsigned)acc;
+  }
+}
+
+// Inclusive scan along the last dimension: a workgroup per line, 256 elements at a time with a
+// running carry (a log-step scan of the 256 values in LDS).
+__global__ __launch_bounds__(256) void gr_interp_scan_kernel(GrInterpGenArgs A) {
+  __shared__ unsigned vals[GR_INTERP_SLOTS * 256];
+  __shared__ unsigned long long sm[2][256];
+  constexpr int R = GR_INTERP_RANK, CD = R - 1;
+  const GrInterpArgs& a = A.m;
+  unsigned idx[R];
+  {
+    unsigned long long rem = blockIdx.x;
+    for (int k = CD - 1; k >= 0; --k) { const unsigned long long d = (unsigned long long)a.dims[k]; idx[k] = (unsigned)(rem % d); rem /= d; }
+  }
+  long long obase = 0;
+  for (int k = 0; k < CD; ++k) obase += a.ocoef[k] * (long long)idx[k];
+  unsigned* const my = vals + threadIdx.x;
+  const int op = A.op, is_int = A.is_int, w64 = A.out_i64;
+  const unsigned long long idn = gi_identity64(op, is_int, w64);
+  unsigned long long carry = idn;
+  const long long L = A.red_len;
+  for (long long t0 = 0; t0 < L; t0 += 256) {
+    const long long c = t0 + threadIdx.x;
+    unsigned long long v = idn;
+    if (c < L) {
+      gi_run(a, 0, a.n_instr, c, idx, my, nullptr);
+      v = gi_widen(w64, my[A.slot * 256]);
+    }
+    int cur = 0;
+    sm[0][threadIdx.x] = v;
+    __syncthreads();
+    for (int d = 1; d < 256; d <<= 1) {
+      unsigned long long x = sm[cur][threadIdx.x];
+      if ((int)threadIdx.x >= d) x = gi_combine64(op, is_int, w64, sm[cur][threadIdx.x - d], x);
+      sm[cur ^ 1][threadIdx.x] = x;
+      cur ^= 1;
+      __syncthreads();
+    }
+    const unsigned long long incl = gi_combine64(op, is_int, w64, carry, sm[cur][threadIdx.x]);
+    const unsigned long long total = sm[cur][255];
+    if (c < L) {
+      const long long oo = obase + a.ocoef[CD] * c;
+      if (w64) *(GM unsigned long long*)(a.out + 8ull * (unsigned long long)oo) = incl;
+      else *(GM unsigned*)(a.out + 4ull * (unsigned long long)oo) = (unsigned)incl;
+    }
+    carry = gi_combine64(op, is_int, w64, carry, total);
+    __syncthreads();
+  }
+}
+
+// Matrix-vector contraction with epilogue: a workgroup per output row.
+__global__ __launch_bounds__(256) void gr_interp_gemv_kernel(GrInterpGenArgs A) {
+  __shared__ unsigned vals[GR_INTERP_SLOTS * 256];
+  __shared__ unsigned long long sm[256];
+  constexpr int R = GR_INTERP_RANK, CD = R - 1;
+  const GrInterpArgs& a = A.m;
+  const long long row = blockIdx.x;
+  const GM float* const Ar = (const GM float*)A.mat + row * A.am;
+  const GM float* const V = (const GM float*)A.vec;
+  float acc = 0.0f;
+  for (long long k = threadIdx.x; k < A.K; k += 256) acc = __builtin_fmaf(Ar[k * A.ak], V[k * A.bk], acc);
+  const unsigned sum = (unsigned)gi_fold256(sm, 0, 0, 0, (unsigned long long)__float_as_uint(acc));
+  if (threadIdx.x == 0) {
+    unsigned idx[R];
+    for (int k = 0; k < R; ++k) idx[k] = 0;
+    gi_run(a, 0, a.n_instr, row, idx, vals, &sum);
+    *(GM unsigned*)(a.out + 4ull * (unsigned long long)row) = vals[A.slot * 256];
+  }
+}
+
+// Matrix-matrix contraction with epilogue: a thread per element of the result, lanes along its rows' columns.
+__global__ __launch_bounds__(256) void gr_interp_gemm_kernel(GrInterpGenArgs A) {
+  __shared__ unsigned vals[GR_INTERP_SLOTS * 256];
+  constexpr int R = GR_INTERP_RANK, CD = R - 1;
+  const GrInterpArgs& a = A.m;
+  const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (o >= A.M * A.N) return;   // no barrier below
+  const long long row = o / A.N, col = o % A.N;
+  const GM float* const Ar = (const GM float*)A.mat + row * A.am;
+  const GM float* const Bc = (const GM float*)A.vec + col * A.bn;
+  float acc = 0.0f;
+  for (long long k = 0; k < A.K; ++k) acc = __builtin_fmaf(Ar[k * A.ak], Bc[k * A.bk], acc);
+  const unsigned sum = __float_as_uint(acc);
+  unsigned idx[R];
+  for (int k = 0; k < R; ++k) idx[k] = 0;
+  idx[CD - 1] = (unsigned)row;
+  unsigned* const my = vals + threadIdx.x;
+  gi_run(a, 0, a.n_instr, col, idx, my, &sum);
+  *(GM unsigned*)(a.out + 4ull * (unsigned long long)o) = my[A.slot * 256];
+}
+
+extern "C" int gr_launch_interp_gen(void* stream, const GrInterpGenArgs* args, unsigned grid) {
+  switch (args->kind) {
+    case GI_KIND_REDUCE: hipLaunchKernelGGL(gr_interp_reduce_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args); break;
+    case GI_KIND_SCAN: hipLaunchKernelGGL(gr_interp_scan_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args); break;
+    case GI_KIND_GEMV: hipLaunchKernelGGL(gr_interp_gemv_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args); break;
+    default: hipLaunchKernelGGL(gr_interp_gemm_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args); break;
+  }
+  return (int)hipGetLastError();
+}
+
 extern "C" int gr_launch_interp_rowred(void* stream, const GrInterpRowArgs* args, unsigned grid) {
   hipLaunchKernelGGL(gr_interp_rowred_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args);
   return (int)hipGetLastError();

@@ -30,6 +30,8 @@ bool interp_encode(const GroupPlan& g, void* out_ptr, GrInterpArgs* A, unsigned*
 gr_status interp_launch(gr_ctx* c, const GrInterpArgs& A, unsigned grid);
 bool interp_encode_rowred(const GroupPlan& g, void* out_ptr, GrInterpRowArgs* R, unsigned* grid);
 gr_status interp_launch_rowred(gr_ctx* c, const GrInterpRowArgs& R, unsigned grid);
+bool interp_encode_gen(const GroupPlan& g, void* out_ptr, GrInterpGenArgs* G, unsigned* grid);
+gr_status interp_launch_gen(gr_ctx* c, const GrInterpGenArgs& G, unsigned grid);
 
 static std::string hip_err(hipError_t e) { return std::string(hipGetErrorName(e)) + ": " + hipGetErrorString(e); }
 
@@ -722,7 +724,7 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
   c->stats.materialize_calls++;
   for (auto& gp : plan->groups) {
     if (c->static_mode) break;
-    if (no_compile || (c->opt_interp >= 2 && (gp->kind == GroupKind::MAP || gp->kind == GroupKind::ROWRED))) continue;  // no kernel wanted (yet)
+    if (no_compile || (c->opt_interp >= 2 && !gp->pair)) continue;  // no kernel wanted (yet)
     gr_status pst = prepare_group(c, *gp);
     if (pst != GR_OK) return pst;
   }
@@ -732,7 +734,7 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
     // A map sub-graph whose kernel is still in the compiler runs through the byte-code
     // interpreter instead of waiting; the job stays pending and a later request collects it.
     // (option "interp" = 2: every map sub-graph the interpreter covers, compiled or not)
-    const bool try_interp = (g.kind == GroupKind::MAP || g.kind == GroupKind::ROWRED) && !g.pair && !c->static_mode &&
+    const bool try_interp = !g.pair && !c->static_mode && !c->capture &&
                             (c->opt_interp >= 2 || (c->opt_interp == 1 && still_compiling(c, g)));
     if (no_compile) k = &dry_kernel;
     gr_status st = (try_interp || no_compile) ? GR_OK : compile_group(c, g, &k);
@@ -765,6 +767,13 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
         GrInterpRowArgs ra;
         if (interp_encode_rowred(g, outs[0], &ra, &igrid)) {
           st = interp_launch_rowred(c, ra, igrid);
+          interpreted = true;
+        }
+      } else if (g.kind != GroupKind::MAP && total > 0) {
+        // reductions over any axes, scans, contractions with their epilogues
+        GrInterpGenArgs ga;
+        if (interp_encode_gen(g, outs[0], &ga, &igrid)) {
+          st = interp_launch_gen(c, ga, igrid);
           interpreted = true;
         }
       }

@@ -1368,7 +1368,7 @@ def test_interpreter_small_configurations(env, env_interp, name):
     n0 = env_interp[1].stats()["interp_launches"]
     got, ref = run_both(env_interp, wl.PROGRAMS[name], arrays)
     if name == "logreg":
-        # no map or row-resident sub-graph here: contractions always wait for their kernels
+        # the two contractions share one pass over X in one generated kernel: that pair always waits for the compiler
         assert env_interp[1].stats()["interp_launches"] == n0
         assert_reduction(got, ref, what=name, scale=track.of(wl.PROGRAMS[name], arrays)[1])
         return
@@ -1418,6 +1418,74 @@ def test_interpreter_row_resident_reductions(env, env_interp, shape):
     nan_row.reshape(-1, shape[last])[0, shape[last] // 2] = np.nan
     got, ref = run_both(env_interp, lambda xp, a: xp.max(a, axis=last), dict(a=nan_row))
     assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(got[~np.isnan(got)], ref[~np.isnan(ref)])
+
+
+@pytest.mark.parametrize("shape,axis,keep", REDUCTION_CASES)
+def test_interpreter_reductions_over_any_axes(env_interp, shape, axis, keep):
+    # reductions that are cuts of their own (other axes, all axes, rows too long to stay resident) through the
+    # interpreter: a workgroup per output.  max/min and integer sums exact, float sums within the reduction bar.
+    gr, ctx, torch = env_interp
+    a = _rand(shape, 30)
+    i = np.random.default_rng(31).integers(-2**31, 2**31 - 1, shape, dtype=np.int64).astype(np.int32)
+    ctx.set_option("rowred_max_cols", 1)   # no reduction stays row-resident: all of them take the generic kernels
+    try:
+        n0 = ctx.stats()["interp_launches"]
+        for op in ("sum", "max", "min"):
+            got, ref, scale = run_scaled(env_interp, lambda xp, a: getattr(xp, op)(a * 1.5, axis=axis, keepdims=keep), dict(a=a))
+            assert got.shape == ref.shape
+            if op == "sum":
+                assert_reduction(got, ref, what=f"interpreted sum {shape} axis={axis}", scale=scale)
+            else:
+                assert np.array_equal(got, ref)
+        got, ref = run_both(env_interp, lambda xp, a: xp.sum(a, axis=axis, keepdims=keep), dict(a=i))
+        assert got.dtype == np.int64 and np.array_equal(got, ref)
+        got, ref = run_both(env_interp, lambda xp, a: xp.max(a, axis=axis, keepdims=keep) - xp.min(a * 3, axis=axis, keepdims=keep), dict(a=i))
+        assert np.array_equal(got, ref)
+        assert ctx.stats()["interp_launches"] >= n0 + 6, "the interpreter did not run"
+    finally:
+        ctx.set_option("rowred_max_cols", 16384)
+
+
+@pytest.mark.parametrize("shape,axis", [c for c in SCAN_CASES if int(np.prod(c[0])) <= 1 << 21])
+def test_interpreter_scans(env_interp, shape, axis):
+    gr, ctx, torch = env_interp
+    a = _rand(shape, 60)
+    n0 = ctx.stats()["interp_launches"]
+    got, ref, scale = run_scaled(env_interp, lambda xp, a: xp.cumsum(a * 0.5 + 1.0, axis), dict(a=a))
+    assert got.shape == ref.shape and got.dtype == ref.dtype
+    assert_reduction(got, ref, what=f"interpreted cumsum {shape} axis={axis}", scale=scale)
+    got, ref = run_both(env_interp, lambda xp, a: xp.cummax(a, axis) - xp.cummin(a, axis), dict(a=a))
+    assert np.array_equal(got, ref)
+    i = np.random.default_rng(61).integers(-2**31, 2**31 - 1, shape, dtype=np.int64).astype(np.int32)
+    got, ref = run_both(env_interp, lambda xp, a: xp.cumsum(a, axis), dict(a=i))
+    assert got.dtype == np.int64 and np.array_equal(got, ref)
+    assert ctx.stats()["interp_launches"] >= n0 + 4, "the interpreter did not run"
+
+
+def test_interpreter_contractions(env_interp):
+    gr, ctx, torch = env_interp
+    A = _rand((70, 130), 34)
+    v = _rand((130,), 35)
+    u = _rand((70,), 36)
+    n0 = ctx.stats()["interp_launches"]
+    for prog, what in DOT_CASES:
+        got, ref, scale = run_scaled(env_interp, prog, dict(A=A, v=v, u=u))
+        assert got.shape == ref.shape, what
+        assert_reduction(got, ref, what="interpreted " + what, scale=scale)
+    assert ctx.stats()["interp_launches"] > n0, "the interpreter did not run"
+    # matrix products with an epilogue, transposed operands, ragged sizes
+    P, Q, b = _rand((77, 130), 37), _rand((130, 45), 38), _rand((45,), 39)
+    for prog, what in [(lambda xp, P, Q, b: xp.maximum(P @ Q + b, 0.0), "dense layer"),
+                       (lambda xp, P, Q, b: xp.transpose(Q) @ xp.transpose(P), "both operands transposed"),
+                       (lambda xp, P, Q, b: xp.tanh((P * 2.0) @ Q) - b, "producer and epilogue")]:
+        n1 = ctx.stats()["interp_launches"]
+        got, ref, scale = run_scaled(env_interp, prog, dict(P=P, Q=Q, b=b))
+        assert_reduction(got, ref, what="interpreted matrix product, " + what, scale=scale)
+        assert ctx.stats()["interp_launches"] > n1
+    # the rectifier dense layer again after its kernel exists: same request, compiled path, same tolerance
+    arrays = wl.make_inputs("logreg", rows=3001, cols=200)
+    got, ref, scale = run_scaled(env_interp, logreg_residual, arrays)
+    assert_reduction(got, ref, what="interpreted row-dot with sigmoid epilogue", scale=scale)
 
 
 def test_interpreter_int32_and_strided_destinations(env_interp):
