@@ -283,9 +283,15 @@ bool interp_encode_gen(const GroupPlan& g, void* out_ptr, GrInterpGenArgs* G, un
       if (G->nout != g.red_out || G->nout > 0x7fffffffLL) return false;
       // a workgroup per output: many outputs over a short strided range would crawl
       if (G->nout > (int64_t)1 << 22) return false;
-      *grid = (unsigned)G->nout;
+      // few outputs over a long range: the range is cut into slices so that about 1024 workgroups run
+      // (the caller provides 8 bytes per slice and launches the combining kernel afterwards)
+      G->nsplit = 1;
+      if (G->nout < 512 && G->red_len >= 65536) G->nsplit = std::min<int64_t>(std::max<int64_t>(1, 1024 / G->nout), G->red_len / 16384);
+      if (G->nsplit < 1) G->nsplit = 1;
+      *grid = (unsigned)(G->nout * G->nsplit);
       return true;
     }
+    G->nsplit = 1;
     G->kind = GI_KIND_SCAN;
     const int64_t L = g.dims[g.rank - 1];
     G->red_len = L;
@@ -327,7 +333,7 @@ bool interp_encode_gen(const GroupPlan& g, void* out_ptr, GrInterpGenArgs* G, un
 
 gr_status interp_launch_gen(gr_ctx* c, const GrInterpGenArgs& G, unsigned grid) {
   if (c->device < 0) { c->stats.kernel_launches++; c->stats.interp_launches++; return GR_OK; }  // dry run
-  static const char* const names[] = {"gr_interp_reduce", "gr_interp_scan", "gr_interp_gemv", "gr_interp_gemm"};
+  static const char* const names[] = {"gr_interp_reduce", "gr_interp_scan", "gr_interp_gemv", "gr_interp_gemm", "gr_interp_combine"};
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (c->opt_profile) {
     for (hipEvent_t* ev : {&e0, &e1}) {

@@ -60,7 +60,7 @@ struct GrInterpRowArgs {
 // thread per element of a matrix product): they bridge the fraction of a second a compilation
 // takes.  Integer and max/min results are exact; a float sum is associated differently from the
 // generated kernel's (both are deterministic and within the same bound of the exact sum).
-enum { GI_KIND_REDUCE = 0, GI_KIND_SCAN, GI_KIND_GEMV, GI_KIND_GEMM };
+enum { GI_KIND_REDUCE = 0, GI_KIND_SCAN, GI_KIND_GEMV, GI_KIND_GEMM, GI_KIND_COMBINE };
 
 struct GrInterpGenArgs {
   GrInterpArgs m;              // dims (right-aligned), operands, constants, code; out = first output element
@@ -71,6 +71,8 @@ struct GrInterpGenArgs {
   int out_i64;                 // the running value / result is a 64-bit integer (sums of i32)
   int first_reduced;           // reduce: dims [0, first_reduced) are kept, the rest is reduced (index into the right-aligned dims)
   long long nout, red_len;     // reduce: outputs and reduced elements per output; scan: lines and line length
+  long long nsplit;            // reduce: workgroups per output (each takes a slice of the reduced range); > 1: partial results go to `partial`
+  unsigned long long partial;  // and a second launch (kind GI_KIND_COMBINE) folds them in slice order
   unsigned long long mat, vec; // contractions: byte addresses of element (0, 0) of both operands
   long long am, ak, bk, bn;    // A[row * am + k * ak], B[k * bk + col * bn] (a vector operand: bn = 0)
   long long M, N, K;

@@ -265,14 +265,17 @@ __global__ __launch_bounds__(256) void gr_interp_reduce_kernel(GrInterpGenArgs A
   constexpr int R = GR_INTERP_RANK, CD = R - 1;
   const GrInterpArgs& a = A.m;
   unsigned full[R];
+  const unsigned long long o = blockIdx.x / (unsigned long long)A.nsplit, sl = blockIdx.x % (unsigned long long)A.nsplit;
   {
-    unsigned long long rem = blockIdx.x;
+    unsigned long long rem = o;
     for (int k = A.first_reduced - 1; k >= 0; --k) { const unsigned long long d = (unsigned long long)a.dims[k]; full[k] = (unsigned)(rem % d); rem /= d; }
   }
   unsigned* const my = vals + threadIdx.x;
   const int op = A.op, is_int = A.is_int, w64 = A.out_i64;
   unsigned long long acc = gi_identity64(op, is_int, w64);
-  for (long long r = threadIdx.x; r < A.red_len; r += 256) {
+  const long long chunk = (A.red_len + A.nsplit - 1) / A.nsplit;
+  const long long rbeg = (long long)sl * chunk, rend = rbeg + chunk < A.red_len ? rbeg + chunk : A.red_len;
+  for (long long r = rbeg + threadIdx.x; r < rend; r += 256) {
     unsigned long long rem = (unsigned long long)r;
     for (int k = CD; k >= A.first_reduced; --k) { const unsigned long long d = (unsigned long long)a.dims[k]; full[k] = (unsigned)(rem % d); rem /= d; }
     gi_run(a, 0, a.n_instr, (long long)full[CD], full, my, nullptr);
@@ -280,8 +283,28 @@ __global__ __launch_bounds__(256) void gr_interp_reduce_kernel(GrInterpGenArgs A
   }
   acc = gi_fold256(sm, op, is_int, w64, acc);
   if (threadIdx.x == 0) {
-    if (w64) *(GM unsigned long long*)(a.out + 8ull * blockIdx.x) = acc;
-    else *(GM unsigned*)(a.out + 4ull * blockIdx.x) = (unsigned)acc;
+    if (A.nsplit > 1) *(GM unsigned long long*)(A.partial + 8ull * blockIdx.x) = acc;
+    else if (w64) *(GM unsigned long long*)(a.out + 8ull * o) = acc;
+    else *(GM unsigned*)(a.out + 4ull * o) = (unsigned)acc;
+  }
+}
+
+// Second stage of a split reduction: the slices' partial results of one output, folded in slice order.
+__global__ __launch_bounds__(256) void gr_interp_combine_kernel(GrInterpGenArgs A) {
+  __shared__ unsigned long long sm[256];
+  const int op = A.op, is_int = A.is_int, w64 = A.out_i64;
+  const unsigned long long o = blockIdx.x;
+  unsigned long long acc = gi_identity64(op, is_int, w64);
+  // lane l folds slices l * per .. l * per + per - 1 in order; the tree then joins neighbouring lanes
+  const long long per = (A.nsplit + 255) / 256;
+  for (long long q = 0; q < per; ++q) {
+    const long long sl = (long long)threadIdx.x * per + q;
+    if (sl < A.nsplit) acc = gi_combine64(op, is_int, w64, acc, *(const GM unsigned long long*)(A.partial + 8ull * (o * (unsigned long long)A.nsplit + (unsigned long long)sl)));
+  }
+  acc = gi_fold256(sm, op, is_int, w64, acc);
+  if (threadIdx.x == 0) {
+    if (w64) *(GM unsigned long long*)(A.m.out + 8ull * o) = acc;
+    else *(GM unsigned*)(A.m.out + 4ull * o) = (unsigned)acc;
   }
 }
 
@@ -378,6 +401,7 @@ extern "C" int gr_launch_interp_gen(void* stream, const GrInterpGenArgs* args, u
   switch (args->kind) {
     case GI_KIND_REDUCE: hipLaunchKernelGGL(gr_interp_reduce_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args); break;
     case GI_KIND_SCAN: hipLaunchKernelGGL(gr_interp_scan_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args); break;
+    case GI_KIND_COMBINE: hipLaunchKernelGGL(gr_interp_combine_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args); break;
     case GI_KIND_GEMV: hipLaunchKernelGGL(gr_interp_gemv_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args); break;
     default: hipLaunchKernelGGL(gr_interp_gemm_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, *args); break;
   }

@@ -773,7 +773,17 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
         // reductions over any axes, scans, contractions with their epilogues
         GrInterpGenArgs ga;
         if (interp_encode_gen(g, outs[0], &ga, &igrid)) {
+          void* part = nullptr;
+          const size_t part_bytes = ga.nsplit > 1 ? (size_t)igrid * 8 : 0;
+          if (part_bytes) part = ctx_alloc(c, part_bytes);
+          if (part_bytes && !part) ga.nsplit = 1, igrid = (unsigned)ga.nout;   // no room for partial results: one workgroup per output
+          ga.partial = (unsigned long long)(uintptr_t)part;
           st = interp_launch_gen(c, ga, igrid);
+          if (st == GR_OK && ga.nsplit > 1) {
+            ga.kind = GI_KIND_COMBINE;
+            st = interp_launch_gen(c, ga, (unsigned)ga.nout);
+          }
+          if (part) ctx_free(c, part, part_bytes);   // (the pool hands blocks out again in stream order)
           interpreted = true;
         }
       }

@@ -1488,6 +1488,23 @@ def test_interpreter_contractions(env_interp):
     assert_reduction(got, ref, what="interpreted row-dot with sigmoid epilogue", scale=scale)
 
 
+@pytest.mark.parametrize("shape,axis", [((1 << 22,), None), ((3, 1 << 20), 1), ((2049, 1025), None), ((70000, 3), 0)])
+def test_interpreter_split_reductions(env_interp, shape, axis):
+    # few outputs over a long range: the interpreter cuts the range into slices (one workgroup each) and a second
+    # launch folds the slices in order
+    gr, ctx, torch = env_interp
+    a = np.abs(_rand(shape, 50)) + f32(0.25)
+    for op in ("sum", "max", "min"):
+        got, ref = run_both(env_interp, lambda xp, a: getattr(xp, op)(xp.sqrt(a), axis=axis), dict(a=a))
+        if op == "sum":
+            assert_reduction(got, ref, what=f"interpreted {op} {shape} axis={axis}")    # positive terms: per element
+        else:
+            assert np.array_equal(got, ref)
+    i = np.random.default_rng(51).integers(-2**31, 2**31 - 1, shape, dtype=np.int64).astype(np.int32)
+    got, ref = run_both(env_interp, lambda xp, a: xp.sum(a, axis=axis), dict(a=i))
+    assert got.dtype == np.int64 and np.array_equal(got, ref)
+
+
 def test_interpreter_int32_and_strided_destinations(env_interp):
     gr, ctx, torch = env_interp
     g = np.random.default_rng(23)
