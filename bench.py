@@ -32,14 +32,14 @@ HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # vector instructions x lanes per second: 256 compute units, 64 lanes each, 2.4 GHz
 BLACKSCHOLES_VALU_PER_ELEMENT = 136            # SQ_INSTS_VALU per wave / 1024 elements per wave (profiles/gr_map_blackscholes_pmc.txt)
-ARGNAMES = {"cumsum": ("x",), "blackscholes": ("S", "K", "T"), "chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
+ARGNAMES = {"cumsum_axis0": ("X",), "cumsum": ("x",), "blackscholes": ("S", "K", "T"), "chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
             "stencil": ("I",), "logreg": ("X", "w", "y")}
 # kernel whose launches dominate each workload
-DOMINANT = {"cumsum": "gr_scan", "blackscholes": "gr_map", "chain": "gr_map", "normalize": "gr_map", "softmax": "gr_rowred", "stencil": "gr_map", "logreg": "gr_gemv_pair"}
+DOMINANT = {"cumsum_axis0": "gr_scan", "cumsum": "gr_scan", "blackscholes": "gr_map", "chain": "gr_map", "normalize": "gr_map", "softmax": "gr_rowred", "stencil": "gr_map", "logreg": "gr_gemv_pair"}
 
 
 def out_shape(name, p):
-    return {"chain": lambda: (p["n"],), "cumsum": lambda: (p["n"],), "blackscholes": lambda: (p["n"],), "normalize": lambda: (p["rows"], p["cols"]), "softmax": lambda: (p["rows"], p["cols"]),
+    return {"chain": lambda: (p["n"],), "cumsum": lambda: (p["n"],), "cumsum_axis0": lambda: (p["rows"], p["cols"]), "blackscholes": lambda: (p["n"],), "normalize": lambda: (p["rows"], p["cols"]), "softmax": lambda: (p["rows"], p["cols"]),
             "stencil": lambda: (p["rows"] - 4, p["cols"] - 4), "logreg": lambda: (p["cols"],)}[name]()
 
 

@@ -25,6 +25,7 @@ def _programs(gr, wl, ctx):
         "logreg": lambda p: dict(X=(p["rows"], p["cols"]), w=(p["cols"],), y=(p["rows"],)),
         "blackscholes": lambda p: dict(S=(p["n"],), K=(p["n"],), T=(p["n"],)),
         "cumsum": lambda p: dict(x=(p["n"],)),
+        "cumsum_axis0": lambda p: dict(X=(p["rows"], p["cols"])),
     }
     for name, prog in wl.PROGRAMS.items():
         for tag, sizes in (("full", wl.FULL[name]), ("small", wl.SMALL[name])):

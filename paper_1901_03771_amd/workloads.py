@@ -31,6 +31,7 @@ FULL = {
     "logreg": dict(rows=262144, cols=512),
     "blackscholes": dict(n=1 << 24),
     "cumsum": dict(n=1 << 27),
+    "cumsum_axis0": dict(rows=8192, cols=8192),
 }
 SMALL = {
     "chain": dict(n=100_003),
@@ -40,8 +41,9 @@ SMALL = {
     "logreg": dict(rows=3001, cols=200),
     "blackscholes": dict(n=70_001),
     "cumsum": dict(n=300_001),
+    "cumsum_axis0": dict(rows=1203, cols=516),
 }
-CONFIG_INDEX = {"chain": 0, "normalize": 1, "softmax": 2, "stencil": 3, "logreg": 4, "blackscholes": 5, "cumsum": 6}
+CONFIG_INDEX = {"chain": 0, "normalize": 1, "softmax": 2, "stencil": 3, "logreg": 4, "blackscholes": 5, "cumsum": 6, "cumsum_axis0": 7}
 
 
 def rng_for(name: str, salt: int = 0) -> np.random.Generator:
@@ -88,6 +90,8 @@ def make_inputs(name: str, salt: int = 0, **size) -> dict:
                     T=g.uniform(0.25, 10.0, n).astype(f32))
     if name == "cumsum":
         return dict(x=g.random(p["n"], dtype=f32))
+    if name == "cumsum_axis0":
+        return dict(X=g.random((p["rows"], p["cols"]), dtype=f32))
     raise KeyError(name)
 
 
@@ -136,7 +140,12 @@ def prefix_sum(xp, x):
     return xp.cumsum(x, 0)
 
 
-PROGRAMS = {"cumsum": prefix_sum, "blackscholes": blackscholes, "chain": chain, "normalize": normalize, "softmax": softmax, "stencil": stencil, "logreg": logreg}
+def prefix_sum_of_columns(xp, X):
+    """Running sums down the columns of a matrix: a scan along the axis that is not contiguous."""
+    return xp.cumsum(X, 0)
+
+
+PROGRAMS = {"cumsum_axis0": prefix_sum_of_columns, "cumsum": prefix_sum, "blackscholes": blackscholes, "chain": chain, "normalize": normalize, "softmax": softmax, "stencil": stencil, "logreg": logreg}
 
 
 def unique_bytes(name: str, **size) -> int:
@@ -149,6 +158,8 @@ def unique_bytes(name: str, **size) -> int:
         return 16 * p["n"]
     if name == "cumsum":
         return 8 * p["n"]
+    if name == "cumsum_axis0":
+        return 8 * p["rows"] * p["cols"]
     if name == "normalize":
         return 8 * p["rows"] * p["cols"] + 16 * p["cols"]
     if name == "softmax":
