@@ -125,15 +125,19 @@ gr_status gr_ctx_set_allocator(gr_ctx* ctx, void* (*alloc)(size_t bytes, void* u
  *                     same file format, written at build time for common
  *                     sub-graphs, never written at run time.
  *                     0 = in-memory cache only, no pack
- *   "interp"          1 (default) = a map sub-graph or a row-resident reduction
- *                     sub-graph whose kernel is still in the run-time compiler is
- *                     evaluated by a precompiled byte-code interpreter of the
- *                     point function instead of waiting (f32 / i32 programs
- *                     within fixed size limits; everything else waits as with
- *                     0); the compilation goes on in the background and later
- *                     requests use the compiled kernel; 0 = always wait for the
- *                     compiler; 2 = interpret every sub-graph the interpreter
- *                     covers (for testing it)
+ *   "interp"          1 (default) = a sub-graph whose kernel is still in the
+ *                     run-time compiler is evaluated by a precompiled byte-code
+ *                     interpreter of the point function instead of waiting (f32 /
+ *                     i32 programs within fixed size limits: maps, row-resident
+ *                     reductions, reductions over any axes, scans, contractions
+ *                     with their epilogues; everything else waits as with 0).
+ *                     Maps and row-resident reductions give the bits of the
+ *                     compiled kernel; a float sum of the other kinds is
+ *                     associated differently (integer, max and min results are
+ *                     exact).  The compilation goes on in the background and
+ *                     later requests use the compiled kernel; 0 = always wait for
+ *                     the compiler; 2 = interpret every sub-graph the
+ *                     interpreter covers (for testing it)
  *   "assign_swap"     1 (default) = gr_assign of a value that reads the
  *                     destination's storage at shifted positions (a stencil
  *                     sweep), into a unit-step box that covers at least 4/5 of
