@@ -129,15 +129,16 @@ bool interp_encode(const GroupPlan& g, void* out_ptr, GrInterpArgs* A, unsigned*
 }
 
 // Operand patterns, constants and extents of a sub-graph: what map and row-resident sub-graphs share.
-static bool encode_operands(const GroupPlan& g, GrInterpArgs* A) {
+static bool encode_operands(const GroupPlan& g, GrInterpArgs* A, const Node* fresh = nullptr, void* fresh_ptr = nullptr) {
   if (g.rank < 1 || g.rank > GR_INTERP_RANK || g.groups.size() > GR_INTERP_GROUPS || g.consts.size() > GR_INTERP_CONSTS) return false;
   const int pad = GR_INTERP_RANK - g.rank;
   for (int k = 0; k < GR_INTERP_RANK; ++k) A->dims[k] = 1;
   for (int k = 0; k < g.rank; ++k) A->dims[k + pad] = g.dims[k];
   for (size_t gi = 0; gi < g.groups.size(); ++gi) {
     const AccessGroup& ag = g.groups[gi];
-    if (ag.dtype == GR_I64 || !ag.leaf || !ag.leaf->data) return false;
-    A->gptr[gi] = (unsigned long long)(uintptr_t)ag.leaf->data + 4ull * (unsigned long long)ag.base;
+    void* const data = ag.leaf == fresh && fresh ? fresh_ptr : (ag.leaf ? ag.leaf->data : nullptr);
+    if (ag.dtype == GR_I64 || !data) return false;
+    A->gptr[gi] = (unsigned long long)(uintptr_t)data + 4ull * (unsigned long long)ag.base;
     for (int k = 0; k < g.rank; ++k) A->gcoef[gi][k + pad] = ag.structural_zero[k] ? 0 : ag.coef[k];
   }
   for (size_t i = 0; i < g.consts.size(); ++i) {
@@ -254,8 +255,11 @@ bool interp_encode_rowred(const GroupPlan& g, void* out_ptr, GrInterpRowArgs* R,
 // A reduction over any axes, a scan or a contraction with its epilogue (sub-graphs that are cuts
 // of their own) for the plain interpreter kernels.  Only sizes that keep the interpreter's run well
 // below a compilation are taken.
-bool interp_encode_gen(const GroupPlan& g, void* out_ptr, GrInterpGenArgs* G, unsigned* grid) {
-  if (g.pair || g.prog.empty()) return false;
+// (`half_of_pair`: `g` is one of the two contractions that the generated code runs as one kernel; the
+// interpreter takes them one after the other, and `fresh` / `fresh_ptr` name the first one's result,
+// which the second reads before the node has been given its buffer)
+bool interp_encode_gen(const GroupPlan& g, void* out_ptr, GrInterpGenArgs* G, unsigned* grid, bool half_of_pair, const Node* fresh, void* fresh_ptr) {
+  if ((g.pair && !half_of_pair) || g.prog.empty()) return false;
   std::memset(G, 0, sizeof *G);
   const int pad = GR_INTERP_RANK - g.rank;
   int ni = 0, nl = 0;
@@ -305,18 +309,19 @@ bool interp_encode_gen(const GroupPlan& g, void* out_ptr, GrInterpGenArgs* G, un
   if (g.out_dtype != GR_F32 || g.results.empty() || g.mat_group < 0 || g.vec_group < 0) return false;
   const AccessGroup& mg = g.groups[g.mat_group];
   const AccessGroup& vg = g.groups[g.vec_group];
-  if (mg.dtype != GR_F32 || vg.dtype != GR_F32 || !mg.leaf || !mg.leaf->data || !vg.leaf || !vg.leaf->data) return false;
-  if (!encode_operands(g, &G->m)) return false;
+  auto data_of = [&](const Node* leaf) -> void* { return leaf == fresh ? fresh_ptr : (leaf ? leaf->data : nullptr); };
+  if (mg.dtype != GR_F32 || vg.dtype != GR_F32 || !data_of(mg.leaf) || !data_of(vg.leaf)) return false;
+  if (!encode_operands(g, &G->m, fresh, fresh_ptr)) return false;
   G->slot = encode_segment(g, g.prog, g.results[0], &G->m, &ni, &nl);
   if (G->slot < 0) return false;
   G->m.n_instr = ni;
   G->m.out = (unsigned long long)(uintptr_t)out_ptr;
-  G->mat = (unsigned long long)(uintptr_t)mg.leaf->data + 4ull * (unsigned long long)mg.base;
-  G->vec = (unsigned long long)(uintptr_t)vg.leaf->data + 4ull * (unsigned long long)vg.base;
+  G->mat = (unsigned long long)(uintptr_t)data_of(mg.leaf) + 4ull * (unsigned long long)mg.base;
+  G->vec = (unsigned long long)(uintptr_t)data_of(vg.leaf) + 4ull * (unsigned long long)vg.base;
   G->am = mg.coef[0]; G->ak = mg.coef[1];
   G->M = g.M; G->K = g.K;
   if (g.kind == GroupKind::GEMV) {
-    if (g.gemv_mode == 2 || g.M < 1 || g.M > 0x7fffffffLL || g.M * std::max<int64_t>(g.K, 1) > (int64_t)1 << 28) return false;
+    if ((g.gemv_mode == 2 && !half_of_pair) || g.M < 1 || g.M > 0x7fffffffLL || g.M * std::max<int64_t>(g.K, 1) > (int64_t)1 << 28) return false;
     G->kind = GI_KIND_GEMV;
     G->N = 1;
     G->bk = vg.coef[1]; G->bn = 0;

@@ -30,7 +30,8 @@ bool interp_encode(const GroupPlan& g, void* out_ptr, GrInterpArgs* A, unsigned*
 gr_status interp_launch(gr_ctx* c, const GrInterpArgs& A, unsigned grid);
 bool interp_encode_rowred(const GroupPlan& g, void* out_ptr, GrInterpRowArgs* R, unsigned* grid);
 gr_status interp_launch_rowred(gr_ctx* c, const GrInterpRowArgs& R, unsigned grid);
-bool interp_encode_gen(const GroupPlan& g, void* out_ptr, GrInterpGenArgs* G, unsigned* grid);
+bool interp_encode_gen(const GroupPlan& g, void* out_ptr, GrInterpGenArgs* G, unsigned* grid, bool half_of_pair = false,
+                       const Node* fresh = nullptr, void* fresh_ptr = nullptr);
 gr_status interp_launch_gen(gr_ctx* c, const GrInterpGenArgs& G, unsigned grid);
 
 static std::string hip_err(hipError_t e) { return std::string(hipGetErrorName(e)) + ": " + hipGetErrorString(e); }
@@ -724,7 +725,7 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
   c->stats.materialize_calls++;
   for (auto& gp : plan->groups) {
     if (c->static_mode) break;
-    if (no_compile || (c->opt_interp >= 2 && !gp->pair)) continue;  // no kernel wanted (yet)
+    if (no_compile || c->opt_interp >= 2) continue;  // no kernel wanted (yet)
     gr_status pst = prepare_group(c, *gp);
     if (pst != GR_OK) return pst;
   }
@@ -734,7 +735,7 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
     // A map sub-graph whose kernel is still in the compiler runs through the byte-code
     // interpreter instead of waiting; the job stays pending and a later request collects it.
     // (option "interp" = 2: every map sub-graph the interpreter covers, compiled or not)
-    const bool try_interp = !g.pair && !c->static_mode && !c->capture &&
+    const bool try_interp = !c->static_mode && !c->capture &&
                             (c->opt_interp >= 2 || (c->opt_interp == 1 && still_compiling(c, g)));
     if (no_compile) k = &dry_kernel;
     gr_status st = (try_interp || no_compile) ? GR_OK : compile_group(c, g, &k);
@@ -759,7 +760,16 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
       unsigned igrid = 0;
       int64_t total = 1;
       for (int k2 = 0; k2 < g.rank; ++k2) total *= g.dims[k2];
-      if (total == 0 && g.kind == GroupKind::MAP) interpreted = true;  // nothing to compute
+      if (g.pair) {
+        // two contractions that share one generated kernel: the interpreter runs them one after the other
+        GrInterpGenArgs ga, gb;
+        unsigned grid_b = 0;
+        if (total > 0 && interp_encode_gen(g, outs[0], &ga, &igrid, true) && interp_encode_gen(*g.pair, outs[1], &gb, &grid_b, true, g.root, outs[0])) {
+          st = interp_launch_gen(c, ga, igrid);
+          if (st == GR_OK) st = interp_launch_gen(c, gb, grid_b);
+          interpreted = true;
+        }
+      } else if (total == 0 && g.kind == GroupKind::MAP) interpreted = true;  // nothing to compute
       else if (g.kind == GroupKind::MAP && interp_encode(g, outs[0], &ia, &igrid)) {
         st = interp_launch(c, ia, igrid);
         interpreted = true;

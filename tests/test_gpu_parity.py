@@ -1369,8 +1369,8 @@ def test_interpreter_small_configurations(env, env_interp, name):
     n0 = env_interp[1].stats()["interp_launches"]
     got, ref = run_both(env_interp, wl.PROGRAMS[name], arrays)
     if name == "logreg":
-        # the two contractions share one pass over X in one generated kernel: that pair always waits for the compiler
-        assert env_interp[1].stats()["interp_launches"] == n0
+        # the two contractions share one pass over X in one generated kernel; the interpreter takes them one after the other
+        assert env_interp[1].stats()["interp_launches"] == n0 + 2
         assert_reduction(got, ref, what=name, scale=track.of(wl.PROGRAMS[name], arrays)[1])
         return
     if name == "softmax":
