@@ -367,6 +367,15 @@ def test_one_pass_scans_tile_sizes_and_many_groups(env):
     assert_reduction(got, ref, what="one-pass scan of 7 strided lines", scale=scale)
     plan = gr.cumsum(c2.array(torch.from_numpy(a).cuda()), 1).plan()
     assert "one-pass-tiles" in plan
+    # scan_polls 0: a tile that finds a total not yet published recomputes its offset from the line itself (the path
+    # that bounds every wait), reached here from the host; a short line keeps the repeated reads cheap
+    c2.set_option("scan_polls", 0)
+    short = np.abs(_rand((300_001,), 70)) + f32(0.01)
+    got, ref = run_both(e2, lambda xp, a: xp.cumsum(a, 0), dict(a=short))
+    assert_reduction(got, ref, what="one-pass scan of 300001 positive values without waiting")
+    got, ref = run_both(e2, lambda xp, a: xp.cummax(a, 0) - xp.cummin(a, 0), dict(a=i[:300_001]))
+    assert np.array_equal(got, ref)
+    assert "one-pass-tiles" in gr.cumsum(c2.array(torch.from_numpy(short).cuda()), 0).plan()
     c2.close()
 
 
