@@ -1023,7 +1023,10 @@ void gen_scan(Em& e) {
   // common head: line index -> pointers
   auto head = [&](int per_block_line) {
     // (the chunk-count slot of a one-pass scan carries the poll limit in its upper half)
-    e.o << "  const long long LINES = " << e.S(e.L.extra) << ", CH = " << e.S(e.L.extra + 1) << ", NCHUNK = " << e.S(e.L.extra + 3) << " & 0xffffffffll;\n";
+    // (one-pass scans: the chunk slot carries, in its upper half, the tag that marks a cell as published by this launch)
+    if (g.scan_mode >= 2) e.o << "  const long long LINES = " << e.S(e.L.extra) << ", CH = " << e.S(e.L.extra + 1) << " & 0xffffffffll, NCHUNK = " << e.S(e.L.extra + 3) << " & 0xffffffffll;\n"
+                                 "  const unsigned EPOCH = (unsigned)(" << e.slot(e.L.extra + 1) << " >> 32);\n";
+    else e.o << "  const long long LINES = " << e.S(e.L.extra) << ", CH = " << e.S(e.L.extra + 1) << ", NCHUNK = " << e.S(e.L.extra + 3) << " & 0xffffffffll;\n";
     e.o << "  const long long L = " << e.dim(sd) << ";\n";
     if (per_block_line == 2) {
       // a workgroup per tile of W neighbouring lines: consecutive workgroups take neighbouring
@@ -1236,14 +1239,14 @@ void gen_scan(Em& e) {
     const std::string bits = ph.out_dtype == GR_F32 ? "__float_as_uint" : "(unsigned)";
     const std::string unbits = ph.out_dtype == GR_F32 ? "__uint_as_float" : "(int)";
     kernel_head(e, "gr_scan_clear");
-    e.o << "  const long long LINES = " << e.S(e.L.extra) << ", G = " << e.S(e.L.extra + 1) << ", NCHUNK = " << e.S(e.L.extra + 3) << " & 0xffffffffll;\n"
+    e.o << "  const long long LINES = " << e.S(e.L.extra) << ", G = " << e.S(e.L.extra + 1) << " & 0xffffffffll, NCHUNK = " << e.S(e.L.extra + 3) << " & 0xffffffffll;\n"
            "  const long long D = " << e.dim(ld) << ", NCHAIN = (LINES / D) * ((D + " << W - 1 << ") / " << W << ");\n"
            "  const long long n = NCHAIN * (NCHUNK + (NCHUNK + G - 1) / G) * " << W << ";\n"
            "  GM unsigned long long* const w = (GM unsigned long long*)" << e.slot(e.L.extra + 2) << ";\n"
            "  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (i < n) w[i] = 0ull;\n}\n";
-    e.o << "static __device__ __forceinline__ unsigned long long gr_poll(GM unsigned long long* p, unsigned& polls) {\n"
+    e.o << "static __device__ __forceinline__ unsigned long long gr_poll(GM unsigned long long* p, unsigned& polls, const unsigned tag) {\n"
            "  unsigned long long w = __hip_atomic_load((unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
-           "  while (!(w >> 32) && polls) { __builtin_amdgcn_s_sleep(2); --polls; w = __hip_atomic_load((unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }\n"
+           "  while ((unsigned)(w >> 32) != tag && polls) { __builtin_amdgcn_s_sleep(2); --polls; w = __hip_atomic_load((unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }\n"
            "  return w;\n}\n";
     kernel_head(e, "gr_scan");
     head(2);
@@ -1304,7 +1307,7 @@ void gen_scan(Em& e) {
            "  GM unsigned long long* const wg = wq + NCHAIN * NCHUNK * " << W << " + chain * NGROUP * " << W << ";\n"
            "  if (threadIdx.x < " << W << ") {\n    " << TA << " tot = " << ident << ";\n"
            "    for (int q = 0; q < " << LY << "; ++q) tot = gr_comb0(tot, ((" << TA << "*)gr_sm)[q * " << W << " + threadIdx.x]);\n"
-           "    __hip_atomic_store((unsigned long long*)(wa + chunk * " << W << " + threadIdx.x), (1ull << 32) | " << bits << "(tot), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n  }\n"
+           "    __hip_atomic_store((unsigned long long*)(wa + chunk * " << W << " + threadIdx.x), ((unsigned long long)EPOCH << 32) | " << bits << "(tot), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n  }\n"
            "  unsigned polls = (unsigned)(" << e.slot(e.L.extra + 3) << " >> 32);\n  int lost = 0;\n"
            "  if (chunk == gfirst + G - 1 && threadIdx.x < " << W << ") {\n"
            "    // last tile of a full group: the group's totals, for every later group\n"
@@ -1312,9 +1315,9 @@ void gen_scan(Em& e) {
            "    for (long long q = gfirst; q < gfirst + G; q += 4) {\n      unsigned long long w[4];\n"
            "#pragma unroll\n      for (int b = 0; b < 4; ++b) w[b] = __hip_atomic_load((unsigned long long*)(wa + (q + b) * " << W << " + threadIdx.x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
            "#pragma unroll\n      for (int b = 0; b < 4; ++b) {\n"
-           "        if (!(w[b] >> 32)) w[b] = gr_poll(wa + (q + b) * " << W << " + threadIdx.x, polls);\n"
-           "        if (w[b] >> 32) acc = gr_comb0(acc, " << unbits << "((unsigned)w[b])); else lost = 1;\n      }\n    }\n"
-           "    if (!lost) __hip_atomic_store((unsigned long long*)(wg + grp * " << W << " + threadIdx.x), (1ull << 32) | " << bits << "(acc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
+           "        if ((unsigned)(w[b] >> 32) != EPOCH) w[b] = gr_poll(wa + (q + b) * " << W << " + threadIdx.x, polls, EPOCH);\n"
+           "        if ((unsigned)(w[b] >> 32) == EPOCH) acc = gr_comb0(acc, " << unbits << "((unsigned)w[b])); else lost = 1;\n      }\n    }\n"
+           "    if (!lost) __hip_atomic_store((unsigned long long*)(wg + grp * " << W << " + threadIdx.x), ((unsigned long long)EPOCH << 32) | " << bits << "(acc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
            "  }\n"
            "  {\n    const int col = threadIdx.x % " << W << ", part = threadIdx.x / " << W << ";\n"
            "    const long long n = grp + (chunk - gfirst);\n    " << TA << " acc = " << ident << ";\n"
@@ -1325,8 +1328,8 @@ void gen_scan(Em& e) {
            "        cell[b] = ib < grp ? wg + ib * " << W << " + col : wa + (gfirst + ib - grp) * " << W << " + col;\n"
            "        w[b] = ib < n ? __hip_atomic_load((unsigned long long*)cell[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;\n      }\n"
            "#pragma unroll\n      for (int b = 0; b < 4; ++b) if (i + b * " << P << " < n) {\n"
-           "        if (!(w[b] >> 32)) w[b] = gr_poll(cell[b], polls);\n"
-           "        if (w[b] >> 32) acc = gr_comb0(acc, " << unbits << "((unsigned)w[b])); else lost = 1;\n      }\n    }\n"
+           "        if ((unsigned)(w[b] >> 32) != EPOCH) w[b] = gr_poll(cell[b], polls, EPOCH);\n"
+           "        if ((unsigned)(w[b] >> 32) == EPOCH) acc = gr_comb0(acc, " << unbits << "((unsigned)w[b])); else lost = 1;\n      }\n    }\n"
            "    gr_part[threadIdx.x] = acc;\n  }\n";
     e.o << "  if (__syncthreads_or(lost)) {\n"
            "    // out of polls: the offsets straight from the input (everything before this tile on its lines)\n"
@@ -1381,9 +1384,9 @@ void gen_scan(Em& e) {
            "  x = gr_comb0(GR_DPP(idn, x, 0x111, 0xf), x);\n  x = gr_comb0(GR_DPP(idn, x, 0x112, 0xf), x);\n"
            "  x = gr_comb0(GR_DPP(idn, x, 0x114, 0xf), x);\n  x = gr_comb0(GR_DPP(idn, x, 0x118, 0xf), x);\n"
            "  x = gr_comb0(GR_DPP(idn, x, 0x142, 0xa), x);\n  x = gr_comb0(GR_DPP(idn, x, 0x143, 0xc), x);\n  return x;\n}\n";
-    e.o << "static __device__ __forceinline__ unsigned long long gr_poll(GM unsigned long long* p, unsigned& polls) {\n"
+    e.o << "static __device__ __forceinline__ unsigned long long gr_poll(GM unsigned long long* p, unsigned& polls, const unsigned tag) {\n"
            "  unsigned long long w = __hip_atomic_load((unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
-           "  while (!(w >> 32) && polls) { __builtin_amdgcn_s_sleep(8); --polls; w = __hip_atomic_load((unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }\n"
+           "  while ((unsigned)(w >> 32) != tag && polls) { __builtin_amdgcn_s_sleep(8); --polls; w = __hip_atomic_load((unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }\n"
            "  return w;\n}\n";
     e.o << "static __device__ __forceinline__ " << TA << " gr_fold(" << TA << " x, " << TA << "* f) {\n"
            "  x = gr_lanes0(x);\n  if ((threadIdx.x & 63) == 0) f[threadIdx.x >> 6] = x;\n  __syncthreads();\n"
@@ -1430,19 +1433,19 @@ void gen_scan(Em& e) {
            "  GM unsigned long long* const wq = (GM unsigned long long*)" << e.slot(e.L.extra + 2) << ";\n"
            "  GM unsigned long long* const wa = wq + line * NCHUNK;\n"
            "  GM unsigned long long* const wg = wq + LINES * NCHUNK + line * NGROUP;\n"
-           "  if (threadIdx.x == 0) __hip_atomic_store((unsigned long long*)(wa + chunk), (1ull << 32) | " << bits << "(carry), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
+           "  if (threadIdx.x == 0) __hip_atomic_store((unsigned long long*)(wa + chunk), ((unsigned long long)EPOCH << 32) | " << bits << "(carry), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
            "  unsigned polls = (unsigned)(" << e.slot(e.L.extra + 3) << " >> 32);\n  int lost = 0;\n"
            "  if (chunk == gfirst + 127) {\n"
            "    // last tile of a full group: the group's total, for every later group\n"
            "    " << TA << " acc = " << ident << ";\n"
-           "    if (threadIdx.x < 128) { const unsigned long long w = gr_poll(wa + gfirst + threadIdx.x, polls); if (w >> 32) acc = " << unbits << "((unsigned)w); else lost = 1; }\n"
+           "    if (threadIdx.x < 128) { const unsigned long long w = gr_poll(wa + gfirst + threadIdx.x, polls, EPOCH); if ((unsigned)(w >> 32) == EPOCH) acc = " << unbits << "((unsigned)w); else lost = 1; }\n"
            "    const " << TA << " tot = gr_fold(acc, gr_fs[0]);\n"
-           "    if (!__syncthreads_or(lost) && threadIdx.x == 0) __hip_atomic_store((unsigned long long*)(wg + grp), (1ull << 32) | " << bits << "(tot), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
+           "    if (!__syncthreads_or(lost) && threadIdx.x == 0) __hip_atomic_store((unsigned long long*)(wg + grp), ((unsigned long long)EPOCH << 32) | " << bits << "(tot), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n"
            "  }\n"
            "  " << TA << " p1 = " << ident << ", p2 = " << ident << ";\n"
            "  // (first the earlier groups, then the earlier tiles of this group: measured faster than waiting for both at once)\n"
-           "  for (long long q = threadIdx.x; q < grp; q += 256) { const unsigned long long w = gr_poll(wg + q, polls); if (w >> 32) p1 = gr_comb0(p1, " << unbits << "((unsigned)w)); else lost = 1; }\n"
-           "  for (long long q = gfirst + threadIdx.x; q < chunk; q += 256) { const unsigned long long w = gr_poll(wa + q, polls); if (w >> 32) p2 = gr_comb0(p2, " << unbits << "((unsigned)w)); else lost = 1; }\n"
+           "  for (long long q = threadIdx.x; q < grp; q += 256) { const unsigned long long w = gr_poll(wg + q, polls, EPOCH); if ((unsigned)(w >> 32) == EPOCH) p1 = gr_comb0(p1, " << unbits << "((unsigned)w)); else lost = 1; }\n"
+           "  for (long long q = gfirst + threadIdx.x; q < chunk; q += 256) { const unsigned long long w = gr_poll(wa + q, polls, EPOCH); if ((unsigned)(w >> 32) == EPOCH) p2 = gr_comb0(p2, " << unbits << "((unsigned)w)); else lost = 1; }\n"
            "  p1 = gr_fold(p1, gr_fs[1]);\n  p2 = gr_fold(p2, gr_fs[2]);\n"
            "  " << TA << " base = gr_comb0(p1, p2);\n"
            "  if (__syncthreads_or(lost)) {\n"

@@ -112,6 +112,11 @@ struct gr_ctx {
   // workspace for two-stage kernels
   void* workspace = nullptr;
   size_t workspace_bytes = 0;
+  // cells in which the tiles of one-pass scans publish their totals: a buffer of their own whose cells carry
+  // the number of the launch that wrote them, so that no launch has to clear them first
+  void* scan_cells = nullptr;
+  size_t scan_cells_bytes = 0;
+  uint32_t scan_epoch = 0;
 
   // gr_materialize_into_static: this device's copy of the library's static device array, and the
   // part of it the running request has taken (static_mode is set for the duration of such a call)

@@ -490,6 +490,48 @@ static gr_status get_workspace(gr_ctx* c, const GroupPlan& g, void** ws) {
   return GR_OK;
 }
 
+// Cells of a one-pass scan.  Ordinarily they live in a buffer that only such scans use: every cell
+// carries the number of the launch that wrote it (the upper half of the 8-byte word), launches are
+// numbered per context and run in stream order, so a launch tells its own cells from stale ones
+// without anybody clearing them; the buffer is zeroed when it is (re)allocated and when the numbers
+// wrap.  `*tag` = 0 means: the caller has to clear the cells it gets (from the shared workspace)
+// and the launch uses tag 1 -- for requests that must not allocate, for requests recorded for
+// replay, and while the caller's stream is being captured into a HIP graph (a replay would repeat
+// the tag, and memset nodes are not recorded here).
+static gr_status scan_cells(gr_ctx* c, const GroupPlan& g, size_t need, void** cells, uint32_t* tag) {
+  *tag = 0;
+  bool plain = c->static_mode || c->capture != nullptr || c->device < 0;
+  if (!plain) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(c->stream, &cs) != hipSuccess) { (void)hipGetLastError(); plain = true; }
+    else if (cs != hipStreamCaptureStatusNone) plain = true;
+  }
+  if (plain) {
+    // while a caller captures the stream nothing may be allocated: the scans' own buffer serves if an
+    // earlier launch has made it large enough (its cells are cleared like any other; tag 1 is older
+    // than every launch number still to come)
+    if (!c->static_mode && !c->capture && c->device >= 0 && c->scan_cells && need <= c->scan_cells_bytes) { *cells = c->scan_cells; return GR_OK; }
+    return get_workspace(c, g, cells);
+  }
+  bool zero = false;
+  if (need > c->scan_cells_bytes) {
+    if (c->scan_cells) ctx_free(c, c->scan_cells, c->scan_cells_bytes);
+    const size_t bytes = std::max<size_t>(need, (size_t)1 << 20);
+    c->scan_cells = ctx_alloc(c, bytes);
+    c->scan_cells_bytes = c->scan_cells ? bytes : 0;
+    if (!c->scan_cells) return fail(c, GR_ERR_OOM, "allocation of the scan cells failed");
+    zero = true;
+  }
+  if (++c->scan_epoch == 0) zero = true;
+  if (zero) {
+    GR_HIP(c, hipMemsetAsync(c->scan_cells, 0, c->scan_cells_bytes, c->stream));
+    c->scan_epoch = 1;
+  }
+  *cells = c->scan_cells;
+  *tag = c->scan_epoch;
+  return GR_OK;
+}
+
 gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* out_ptr, void* pair_out_ptr) {
   ArgLayout L = arg_layout(g);
   ArgLayout L2;
@@ -541,25 +583,20 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       s[L.extra] = (uint64_t)g.red_out;
       s[L.extra + 1] = (uint64_t)g.scan_chunk;
       s[L.extra + 3] = (uint64_t)g.scan_nchunk | (g.scan_mode >= 2 ? (uint64_t)c->opt_scan_polls << 32 : 0);
-      if (g.scan_mode == 3) {
-        // one pass over tiles of neighbouring lines: clear the cells, then the tiles
-        gr_status wst = get_workspace(c, g, &ws);
+      if (g.scan_mode >= 2) {
+        // one pass: the tiles publish their totals in cells (cleared first unless they carry launch numbers)
+        uint32_t tag = 0;
+        gr_status wst = scan_cells(c, g, workspace_need(g), &ws, &tag);
         if (wst != GR_OK) return wst;
-        s[L.extra + 1] = (uint64_t)std::max(1, g.slabs);
+        const uint64_t low = g.scan_mode == 3 ? (uint64_t)std::max(1, g.slabs) : (uint64_t)g.scan_chunk;
+        s[L.extra + 1] = low | ((uint64_t)(tag ? tag : 1u) << 32);
         s[L.extra + 2] = (uint64_t)(uintptr_t)ws;
-        gr_status st = launch(c, k->fn2, "gr_scan_clear", (scan_line_tile_cells(g) + 255) / 256, s);
-        if (st != GR_OK) return st;
-        return launch(c, k->fn, k->name, scan_line_tile_chains(g) * g.scan_nchunk, s);
-      }
-      if (g.scan_mode == 2) {
-        // one pass: clear the cells the tiles publish their totals in, then the chained tiles
-        gr_status wst = get_workspace(c, g, &ws);
-        if (wst != GR_OK) return wst;
-        s[L.extra + 2] = (uint64_t)(uintptr_t)ws;
-        const int64_t cells = g.red_out * g.scan_nchunk + g.red_out * ((g.scan_nchunk + 127) / 128);
-        gr_status st = launch(c, k->fn2, "gr_scan_clear", (cells + 255) / 256, s);
-        if (st != GR_OK) return st;
-        return launch(c, k->fn, k->name, g.red_out * g.scan_nchunk, s);
+        const int64_t cells = g.scan_mode == 3 ? scan_line_tile_cells(g) : g.red_out * g.scan_nchunk + g.red_out * ((g.scan_nchunk + 127) / 128);
+        if (!tag) {
+          gr_status st = launch(c, k->fn2, "gr_scan_clear", (cells + 255) / 256, s);
+          if (st != GR_OK) return st;
+        }
+        return launch(c, k->fn, k->name, g.scan_mode == 3 ? scan_line_tile_chains(g) * g.scan_nchunk : g.red_out * g.scan_nchunk, s);
       }
       if (g.scan_mode == 1) {
         // a thread per (line, chunk)
@@ -1014,6 +1051,7 @@ gr_status gr_ctx_destroy(gr_ctx* ctx) {
   ctx->nodes.clear();
   while (!ctx->programs.empty()) program_free(ctx, ctx->programs.back());
   if (ctx->workspace) ctx_free(ctx, ctx->workspace, ctx->workspace_bytes);
+  if (ctx->scan_cells) ctx_free(ctx, ctx->scan_cells, ctx->scan_cells_bytes);
   for (auto& kv : ctx->cache) if (kv.second.module) (void)hipModuleUnload(kv.second.module);
   for (auto& p : ctx->prof) { (void)hipEventDestroy(p.e0); (void)hipEventDestroy(p.e1); }
   for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);

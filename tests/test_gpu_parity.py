@@ -411,6 +411,48 @@ def test_one_pass_scans_along_a_strided_axis(env):
     c2.close()
 
 
+def test_one_pass_scans_under_hip_graph_capture(env):
+    # The tiles of a one-pass scan tell their own published totals from stale ones by the launch number the cells
+    # carry; a captured launch would repeat its number on every replay, so while the caller's stream is being
+    # captured the cells are cleared by a kernel instead (no memset node).  Replays are interleaved with eager
+    # requests and synchronisations, and every replay is compared with the eager result of the same input.
+    gr, ctx, torch = env
+    c2 = gr.Context()
+    c2.set_option("interp", 0)
+    x = torch.rand(1 << 20, device="cuda")
+    m = torch.rand(2051, 520, device="cuda")
+    out_x, out_m = torch.empty_like(x), torch.empty_like(m)
+
+    def both():
+        gr.cumsum(c2.array(x) * 0.5, 0).materialize_into(out_x)
+        gr.cumsum(c2.array(m), 0).materialize_into(out_m)
+    both()                      # kernels compiled, the scans' cell buffer allocated
+    c2.compile_wait()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    c2.set_stream(side.cuda_stream)
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        both()
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    c2.set_stream(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        x.uniform_(0.0, 1.0 + rep)
+        m.uniform_(-1.0, 1.0 + rep)
+        both()                  # eager, between the replays: launch numbers move on
+        eager_x, eager_m = out_x.clone(), out_m.clone()
+        out_x.zero_(); out_m.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_x, eager_x) and torch.equal(out_m, eager_m), f"replay {rep} differs from the eager result"
+    c2.close()
+
+
 def test_scan_closed_forms_and_consumers(env):
     gr, ctx, torch = env
     n = 5000
