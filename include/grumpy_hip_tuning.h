@@ -56,7 +56,7 @@ extern "C" {
  *                     lines (fewer than 512 lines of more than 32768 elements) reads its input once:
  *                     chained tiles that publish their totals (the map-scan primitive of Section 3.2
  *                     as a single kernel); 0 = chunk totals, a scan of the totals, then the chunks
- *                     with their offsets (three kernels, the input read twice); 2..16 = one pass
+ *                     with their offsets (three kernels, the input read twice); 2..24 = one pass
  *                     with tiles of that many 1024-element blocks.  Any value but 0 also lets a scan
  *                     of 4-byte values along a NON-contiguous axis (lines of 128 positions or more, the
  *                     innermost line dimension contiguous and a multiple of four) read its input once:

@@ -805,9 +805,9 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       g->scan_nchunk = (int)nch;
       // 4-byte running values: one pass over the input with chained tiles of 8192 elements
       // (option "scan_one_pass" = 0 keeps the three kernels, which read the input twice)
-      // tiles of 8192 elements, 12288 for lines of 2^25 elements and more (measured; option values from 2 on: 1024-element blocks per tile)
-      const int64_t tile = 1024 * (c->opt_scan_one_pass >= 2 ? c->opt_scan_one_pass : (L >= ((int64_t)1 << 25) ? 12 : 8));
-      if (c->opt_scan_one_pass && p.out_dtype != GR_I64 && tile <= 16384 && (L + tile - 1) / tile <= (int64_t)1 << 24) {
+      // tiles of 8192 elements, 20480 for lines of 2^25 elements and more (measured: 2^27 elements 200 us with 12288, 192-195 with 16384, 188 with 20480, 207 with 24576; option values from 2 to 24: 1024-element blocks per tile)
+      const int64_t tile = 1024 * (c->opt_scan_one_pass >= 2 ? c->opt_scan_one_pass : (L >= ((int64_t)1 << 25) ? 20 : 8));
+      if (c->opt_scan_one_pass && p.out_dtype != GR_I64 && tile <= 24576 && (L + tile - 1) / tile <= (int64_t)1 << 24) {
         g->scan_mode = 2;
         g->scan_chunk = tile;
         g->scan_nchunk = (int)((L + tile - 1) / tile);
