@@ -32,14 +32,14 @@ HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # vector instructions x lanes per second: 256 compute units, 64 lanes each, 2.4 GHz
 BLACKSCHOLES_VALU_PER_ELEMENT = 136            # SQ_INSTS_VALU per wave / 1024 elements per wave (profiles/gr_map_blackscholes_pmc.txt)
-ARGNAMES = {"cumsum_axis0": ("X",), "cumsum": ("x",), "blackscholes": ("S", "K", "T"), "chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
+ARGNAMES = {"gemm": ("A", "B"), "cumsum_axis0": ("X",), "cumsum": ("x",), "blackscholes": ("S", "K", "T"), "chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
             "stencil": ("I",), "logreg": ("X", "w", "y")}
 # kernel whose launches dominate each workload
-DOMINANT = {"cumsum_axis0": "gr_scan", "cumsum": "gr_scan", "blackscholes": "gr_map", "chain": "gr_map", "normalize": "gr_map", "softmax": "gr_rowred", "stencil": "gr_map", "logreg": "gr_gemv_pair"}
+DOMINANT = {"gemm": "gr_gemm", "cumsum_axis0": "gr_scan", "cumsum": "gr_scan", "blackscholes": "gr_map", "chain": "gr_map", "normalize": "gr_map", "softmax": "gr_rowred", "stencil": "gr_map", "logreg": "gr_gemv_pair"}
 
 
 def out_shape(name, p):
-    return {"chain": lambda: (p["n"],), "cumsum": lambda: (p["n"],), "cumsum_axis0": lambda: (p["rows"], p["cols"]), "blackscholes": lambda: (p["n"],), "normalize": lambda: (p["rows"], p["cols"]), "softmax": lambda: (p["rows"], p["cols"]),
+    return {"gemm": lambda: (p["m"], p["n"]), "chain": lambda: (p["n"],), "cumsum": lambda: (p["n"],), "cumsum_axis0": lambda: (p["rows"], p["cols"]), "blackscholes": lambda: (p["n"],), "normalize": lambda: (p["rows"], p["cols"]), "softmax": lambda: (p["rows"], p["cols"]),
             "stencil": lambda: (p["rows"] - 4, p["cols"] - 4), "logreg": lambda: (p["cols"],)}[name]()
 
 
@@ -161,8 +161,10 @@ def cpu_baseline(name, target_cpu_s=20.0):
         return time.perf_counter() - t0, arrays
 
     def leg(threads, budget_core_s):
-        if name in ("chain", "blackscholes"):
+        if name in ("chain", "blackscholes", "cumsum"):
             size = dict(n=full["n"])
+        elif name == "gemm":
+            size = dict(m=128, k=full["k"], n=full["n"])
         else:
             size = dict(rows=64 if name != "logreg" else 4096, cols=full["cols"])
         t, arrays = run(size, threads)
@@ -256,6 +258,12 @@ def main():
     traffic, traffic_src = traffic_from_profiles(name)
     roofline = hbm_roofline(DOMINANT[name], algorithmic_bytes_per_launch(name, w.p), ms_per_step * 1e3, per_block, args.steps,
                             traffic=traffic, traffic_source=(traffic_src + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by the plain copy kernel; committed summary, not measured in this run)") if traffic_src else None)
+    if name == "gemm":  # a dense contraction: priced against the matrix cores, not against HBM
+        flops = 2 * w.p["m"] * w.p["k"] * w.p["n"]
+        tf = flops / (ms_per_step * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "gr_gemm", "achieved": round(tf, 1), "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tf / FP32_MFMA_PEAK_TFLOPS, 4), "launches": args.steps, "avg_launch_us": round(ms_per_step * 1e3, 1),
+                    "median_us": round(median(per_block), 1), "min_us": round(min(per_block), 1), "algorithmic_flops_per_launch": flops, "traffic": None}
     if not args.no_launch_events:
         ctx.set_option("profile", 1)
         ctx.profile_reset()

@@ -26,6 +26,7 @@ def _programs(gr, wl, ctx):
         "blackscholes": lambda p: dict(S=(p["n"],), K=(p["n"],), T=(p["n"],)),
         "cumsum": lambda p: dict(x=(p["n"],)),
         "cumsum_axis0": lambda p: dict(X=(p["rows"], p["cols"])),
+        "gemm": lambda p: dict(A=(p["m"], p["k"]), B=(p["k"], p["n"])),
     }
     for name, prog in wl.PROGRAMS.items():
         for tag, sizes in (("full", wl.FULL[name]), ("small", wl.SMALL[name])):

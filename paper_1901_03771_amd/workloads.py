@@ -32,6 +32,7 @@ FULL = {
     "blackscholes": dict(n=1 << 24),
     "cumsum": dict(n=1 << 27),
     "cumsum_axis0": dict(rows=8192, cols=8192),
+    "gemm": dict(m=4096, k=4096, n=4096),
 }
 SMALL = {
     "chain": dict(n=100_003),
@@ -42,8 +43,9 @@ SMALL = {
     "blackscholes": dict(n=70_001),
     "cumsum": dict(n=300_001),
     "cumsum_axis0": dict(rows=1203, cols=516),
+    "gemm": dict(m=515, k=1030, n=259),
 }
-CONFIG_INDEX = {"chain": 0, "normalize": 1, "softmax": 2, "stencil": 3, "logreg": 4, "blackscholes": 5, "cumsum": 6, "cumsum_axis0": 7}
+CONFIG_INDEX = {"chain": 0, "normalize": 1, "softmax": 2, "stencil": 3, "logreg": 4, "blackscholes": 5, "cumsum": 6, "cumsum_axis0": 7, "gemm": 8}
 
 
 def rng_for(name: str, salt: int = 0) -> np.random.Generator:
@@ -92,6 +94,8 @@ def make_inputs(name: str, salt: int = 0, **size) -> dict:
         return dict(x=g.random(p["n"], dtype=f32))
     if name == "cumsum_axis0":
         return dict(X=g.random((p["rows"], p["cols"]), dtype=f32))
+    if name == "gemm":
+        return dict(A=g.standard_normal((p["m"], p["k"]), dtype=f32), B=g.standard_normal((p["k"], p["n"]), dtype=f32))
     raise KeyError(name)
 
 
@@ -145,7 +149,12 @@ def prefix_sum_of_columns(xp, X):
     return xp.cumsum(X, 0)
 
 
-PROGRAMS = {"cumsum_axis0": prefix_sum_of_columns, "cumsum": prefix_sum, "blackscholes": blackscholes, "chain": chain, "normalize": normalize, "softmax": softmax, "stencil": stencil, "logreg": logreg}
+def matrix_product(xp, A, B):
+    """The dense contraction that the paper hands to a BLAS library (Section 2, the operations better left to libraries)."""
+    return A @ B
+
+
+PROGRAMS = {"gemm": matrix_product, "cumsum_axis0": prefix_sum_of_columns, "cumsum": prefix_sum, "blackscholes": blackscholes, "chain": chain, "normalize": normalize, "softmax": softmax, "stencil": stencil, "logreg": logreg}
 
 
 def unique_bytes(name: str, **size) -> int:
@@ -160,6 +169,8 @@ def unique_bytes(name: str, **size) -> int:
         return 8 * p["n"]
     if name == "cumsum_axis0":
         return 8 * p["rows"] * p["cols"]
+    if name == "gemm":
+        return 4 * (p["m"] * p["k"] + p["k"] * p["n"] + p["m"] * p["n"])
     if name == "normalize":
         return 8 * p["rows"] * p["cols"] + 16 * p["cols"]
     if name == "softmax":
