@@ -1693,6 +1693,139 @@ void gen_gemv_pair(Em& e, Em& e2) {
 
 // ---- GEMM (matrix cores) ----------------------------------------------------------
 
+using EpiLoad = std::function<std::string(const Instr&, int)>;
+void gemm_combine(Em& e, const EpiLoad& epi_load);
+
+// Matrix product of large operands in their natural layouts (left operand contiguous along k, right one
+// along n; M and N multiples of 256, K a multiple of 16): one workgroup per 256 x 256 tile of the result and
+// per compute unit, four waves with a 128 x 128 quarter each as 4 x 4 matrix-core blocks (256 accumulator
+// registers per lane).
+//   * Tiles of 16 values of k go from global memory straight into LDS (global_load_lds_dwordx4: lane L of a
+//     wave deposits its 16 bytes at M0 + 16 L, whatever address it loaded them from), two steps ahead, into a
+//     ring of three stages, so a step has one barrier, no staging registers and no LDS write instructions.
+//   * Left tile: 256 rows of 16 floats; the four 16-byte chunks of row m sit at chunk position c ^ (m / 4 % 4),
+//     which lets both the depositing wave (16 lanes = 4 rows x 4 chunks) and the reading one (16 lanes = 16
+//     rows, one chunk) touch every bank once.  A lane reads the four k values of a chunk with one ds_read_b128
+//     and feeds them to four matrix instructions: the instruction for element t of the chunks takes k = 4 h + t
+//     (+ 8 in the second half of the step) in half-wave h instead of k = 2 s + h.  Both operands use the same
+//     assignment, so every product is formed once; only the order of the additions differs.
+//   * Right tile: 16 rows of 256 floats with a pitch of 264 (rows 4 apart lie 32 banks apart).  Block j of a
+//     lane's four column blocks is column 4 r + j of the wave's 128 (r = lane % 32), so the four operands of a
+//     k come with one ds_read_b128 and a lane's results are four neighbouring columns (16-byte stores).
+//   * Per step and wave: 128 matrix instructions, 16 LDS reads, 8 direct loads, one barrier, each placed
+//     behind a fixed matrix instruction (scheduling barriers pin the order): with one wave per SIMD every
+//     instruction between two matrix instructions delays the second one, which is what bounds this kernel
+//     (measured on 4096^3, one variant each: staging through registers 137 TFLOP/s, direct loads 143, the
+//     same with addresses precomputed and 16-byte reads of the right operand 151; a loop of nothing but
+//     matrix instructions 154).
+// The direct loads are written as assembly: the compiler's own form of them makes it wait for every outstanding
+// LDS read before each use (it counts them as LDS traffic that may return out of order).  Their completion is
+// tracked by hand: vmcnt(8) before a step's barrier leaves only the eight loads of the newest tile in flight.
+void gemm_big_body(Em& e, const EpiLoad& epi_load) {
+  const GroupPlan& g = e.g;
+  const int ASTAGE = 4096, BROW = 264, STAGE = ASTAGE + 16 * BROW;   // floats
+  std::ostream& o = e.o;
+  o << "  __shared__ __attribute__((aligned(16))) float gr_lds[" << 3 * STAGE << "];\n"
+       "  typedef __attribute__((address_space(3))) float lfloat;\n"
+       "  typedef __attribute__((address_space(3))) f4 lf4;\n"
+       "  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;\n"
+       "  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;\n"
+       "  const long long tiles_n = N / 256;\n"
+       "  const long long bm0 = (blockIdx.x / tiles_n) * 256, bn0 = (blockIdx.x % tiles_n) * 256;\n"
+       "  f16v acc[4][4];\n"
+       "  for (int i = 0; i < 4; ++i) for (int j = 0; j < 4; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n"
+       "  const unsigned wv = __builtin_amdgcn_readfirstlane(wave);\n"
+       "  unsigned aoff[4], boff[4];\n"
+       "#pragma unroll\n"
+       "  for (int p = 0; p < 4; ++p) { const int m = 16 * (4 * wave + p) + lane / 4, c = (lane % 4) ^ ((m >> 2) & 3); aoff[p] = 4u * (unsigned)(m * am + 4 * c); }\n"
+       "#pragma unroll\n"
+       "  for (int p = 0; p < 4; ++p) boff[p] = 4u * (unsigned)((4 * wave + p) * bk + 4 * lane);\n"
+       "  // (uniform addresses, made visibly so: the operands of the loads below must be scalar registers)\n"
+       "  const unsigned long long a64 = (unsigned long long)(A + bm0 * am), b64 = (unsigned long long)(B + bn0);\n"
+       "  unsigned long long Ab = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(a64 >> 32)) << 32) | (unsigned)__builtin_amdgcn_readfirstlane((int)a64);\n"
+       "  unsigned long long Bb = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(b64 >> 32)) << 32) | (unsigned)__builtin_amdgcn_readfirstlane((int)b64);\n"
+       "  const unsigned long long bstep = 64ull * (unsigned long long)__builtin_amdgcn_readfirstlane((int)bk);\n"
+       "  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)gr_lds;\n"
+       "  const unsigned ldsa = lds0 + 4096u * wv, ldsb = lds0 + " << 4 * ASTAGE << "u + " << 16 * BROW << "u * wv;\n"
+       "  const lfloat* pa[3][2];\n"
+       "  const lfloat* pb[3];\n"
+       "#pragma unroll\n"
+       "  for (int st = 0; st < 3; ++st) {\n"
+       "#pragma unroll\n"
+       "    for (int hf = 0; hf < 2; ++hf) pa[st][hf] = (const lfloat*)gr_lds + st * " << STAGE << " + (wm + l32) * 16 + 4 * ((2 * hf + lh) ^ ((l32 >> 2) & 3));\n"
+       "    pb[st] = (const lfloat*)gr_lds + st * " << STAGE << " + " << ASTAGE << " + 4 * lh * " << BROW << " + wn + 4 * l32;\n"
+       "  }\n"
+       "  f4 aF[2][4];\n"
+       "  f4 bF[2];\n"
+       "  const long long nkt = K / 16;\n";
+  // piece p (0..3: blocks of 16 rows of the left tile, 4..7: rows of the right tile) of the tile at Ab / Bb into stage st
+  auto piece = [&](int st, int p, const char* ind) {
+    const int imm = p < 4 ? st * STAGE * 4 + 1024 * p : st * STAGE * 4 + 4 * BROW * (p - 4);
+    o << ind << "asm volatile(\"s_add_i32 m0, %2, " << imm << "\\n\\ts_nop 0\\n\\tglobal_load_lds_dwordx4 %0, %1\" : : \"v\"("
+      << (p < 4 ? "aoff[" : "boff[") << p % 4 << "]), \"s\"(" << (p < 4 ? "Ab" : "Bb") << "), \"s\"(" << (p < 4 ? "ldsa" : "ldsb") << ") : \"memory\");\n";
+  };
+  const char* SB = "__builtin_amdgcn_sched_barrier(0);\n";
+  // one step: stage st holds the current tile; the tile two steps on (at Ab / Bb) goes to stage (st + 2) % 3 if more2;
+  // the first operands of the next step are read behind the barrier if more1
+  auto step = [&](int st, bool more2, bool more1, const char* ind) {
+    const int st1 = (st + 1) % 3, st2 = (st + 2) % 3;
+    for (int s = 0; s < 8; ++s) {
+      if (s == 7)
+        // the next tile has landed (all but the newest eight loads are complete) and this wave's reads of the current one are done
+        o << ind << "__builtin_amdgcn_s_waitcnt(" << (more2 ? 0x0070 | 8 : 0x0070) << ");\n" << ind << "__builtin_amdgcn_s_barrier();\n";
+      for (int q = 0; q < 16; ++q) {
+        const int i = q >> 2, j = q & 3;
+        o << ind << SB << ind << "acc[" << i << "][" << j << "] = __builtin_amdgcn_mfma_f32_32x32x2f32(aF[" << (s >> 2) << "][" << i << "][" << (s & 3) << "], bF[" << (s & 1) << "][" << j
+          << "], acc[" << i << "][" << j << "], 0, 0, 0);\n" << ind << SB;
+        if (more2 && q == 1 && s < 7) piece(st2, s, ind);
+        if (more2 && s == 6 && q == 9) { piece(st2, 7, ind); o << ind << "Ab += 64; Bb += bstep;\n"; }
+        if (s < 7 && q == 4) o << ind << "bF[" << ((s + 1) & 1) << "] = *(const lf4*)(pb[" << st << "] + " << (8 * ((s + 1) >> 2) + ((s + 1) & 3)) * BROW << ");\n";
+        if (s == 1 && q >= 8 && q < 12) o << ind << "aF[1][" << q - 8 << "] = *(const lf4*)(pa[" << st << "][1] + " << (q - 8) * 512 << ");\n";
+        if (s == 7 && more1 && q < 4) o << ind << "aF[0][" << q << "] = *(const lf4*)(pa[" << st1 << "][0] + " << q * 512 << ");\n";
+        if (s == 7 && more1 && q == 4) o << ind << "bF[0] = *(const lf4*)(pb[" << st1 << "]);\n";
+      }
+    }
+  };
+  // prologue: tiles 0 and 1 (K >= 32)
+  for (int t = 0; t < 2; ++t) {
+    for (int p = 0; p < 8; ++p) piece(t, p, "  ");
+    o << "  Ab += 64; Bb += bstep;\n";
+  }
+  o << "  __builtin_amdgcn_s_waitcnt(" << (0x0F70 | 8) << ");\n  __builtin_amdgcn_s_barrier();\n"
+       "#pragma unroll\n  for (int i = 0; i < 4; ++i) aF[0][i] = *(const lf4*)(pa[0][0] + i * 512);\n"
+       "  bF[0] = *(const lf4*)(pb[0]);\n"
+       "  long long kt = 0;\n"
+       "  for (; kt + 5 <= nkt; kt += 3) {\n";
+  for (int st = 0; st < 3; ++st) step(st, true, true, "    ");
+  o << "  }\n"
+       "  // two, three or four steps are left, the first of them in stage 0\n"
+       "  if (nkt - kt == 2) {\n";
+  step(0, false, true, "    ");
+  step(1, false, false, "    ");
+  o << "  } else if (nkt - kt == 3) {\n";
+  step(0, true, true, "    ");
+  step(1, false, true, "    ");
+  step(2, false, false, "    ");
+  o << "  } else {\n";
+  step(0, true, true, "    ");
+  step(1, true, true, "    ");
+  step(2, false, true, "    ");
+  step(0, false, false, "    ");
+  o << "  }\n";
+  // epilogue on the accumulators: element q of block (i, j) is row wm + 32 i + 8 (q / 4) + 4 (lane / 32) + q % 4, column wn + 4 (lane % 32) + j
+  o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n"
+       "#pragma unroll\n  for (int i = 0; i < 4; ++i)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
+       "      const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4);\n"
+       "      f4 ov;\n"
+       "#pragma unroll\n      for (int j = 0; j < 4; ++j) {\n"
+       "        const long long col = bn0 + wn + 4 * l32 + j;\n"
+       "        const float cacc = acc[i][j][q];\n";
+  emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
+  o << "        ov[j] = t" << g.results[0] << ";\n      }\n"
+       "      *(GM f4u*)(out + row * N + bn0 + wn + 4 * l32) = ov;\n    }\n}\n";
+}
+
+
 // C = A.B for f32 on MFMA (v_mfma_f32_32x32x2_f32: f32 inputs, f32 accumulation), the one place
 // on this path that is a dense contraction.  A workgroup of four waves owns a 128x128 tile of
 // C; each wave a 64x64 quarter as 2x2 MFMA blocks (64 accumulator VGPRs).  K advances in steps
@@ -1730,6 +1863,21 @@ void gen_gemm(Em& e) {
   e.o << "  const GM float* const A = q" << g.mat_group << "; const GM float* const B = q" << g.vec_group << ";\n";
   e.o << "  const long long am = " << e.coef(g.mat_group, 0) << ", ak = " << e.coef(g.mat_group, 1) << ", bk = " << e.coef(g.vec_group, 0)
       << ", bn = " << e.coef(g.vec_group, 1) << ";\n  (void)am; (void)ak; (void)bk; (void)bn;\n";
+  const EpiLoad epi_load = [&](const Instr& in, int) {
+    const AccessGroup& eg = g.groups[in.group];
+    std::ostringstream s2;
+    s2 << e.qp << in.group << "[0";
+    if (!eg.structural_zero[0]) s2 << " + (row + " << in.delta[0] << ") * " << e.coef(in.group, 0);
+    if (!eg.structural_zero[1]) s2 << " + (col + " << in.delta[1] << ") * " << e.coef(in.group, 1);
+    s2 << "]";
+    return s2.str();
+  };
+  auto emit_combine = [&]() { gemm_combine(e, epi_load); };
+  if (g.BX == 256) {
+    gemm_big_body(e, epi_load);
+    emit_combine();
+    return;
+  }
   e.o << "  __shared__ float As[2][" << KS << "][" << AP << "];\n  __shared__ float Bs[2][" << KS << "][" << BP << "];\n";
   e.o << "  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;\n";
   if (BN == 128) e.o << "  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64, l32 = lane & 31, lh = lane >> 5;\n";
@@ -1878,17 +2026,14 @@ void gen_gemm(Em& e) {
   e.o << "#pragma unroll\n  for (int i = 0; i < " << IB << "; ++i)\n#pragma unroll\n  for (int j = 0; j < " << JB << "; ++j)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
          "      const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4), col = bn0 + wn + 32 * j + l32;\n"
          "      if (row < M && col < N) {\n        const float cacc = acc[i][j][q];\n";
-  auto epi_load = [&](const Instr& in, int) {
-    const AccessGroup& eg = g.groups[in.group];
-    std::ostringstream s2;
-    s2 << e.qp << in.group << "[0";
-    if (!eg.structural_zero[0]) s2 << " + (row + " << in.delta[0] << ") * " << e.coef(in.group, 0);
-    if (!eg.structural_zero[1]) s2 << " + (col + " << in.delta[1] << ") * " << e.coef(in.group, 1);
-    s2 << "]";
-    return s2.str();
-  };
   emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
   e.o << "        out[row * N + col] = t" << g.results[0] << ";\n      }\n    }\n}\n";
+  emit_combine();
+}
+
+// The second kernel of a matrix product whose K range is split over workgroups.
+void gemm_combine(Em& e, const EpiLoad& epi_load) {
+  const GroupPlan& g = e.g;
   // second stage of a split product: partial tiles added in split order, then the epilogue
   kernel_head(e, "gr_gemm_combine");
   e.o << "  const long long M = " << e.S(e.L.extra) << ", N = " << e.S(e.L.extra + 1) << ", NSPLIT = " << e.S(e.L.extra + 3) << ";\n";

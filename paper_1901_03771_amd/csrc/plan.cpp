@@ -926,6 +926,22 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
         if (ks >= 2) g->slabs = (int)std::min<int64_t>(ks, 256);
       }
     }
+    // Large products of operands in their natural layouts (rows of the left operand contiguous along k, rows of
+    // the right one along n): 256 x 256 tiles, one workgroup per compute unit, tiles loaded straight into LDS
+    // (BX = 256 selects that kernel).  It needs whole tiles and whole steps of 16 values of k, enough tiles to
+    // fill at least four fifths of the last round over the 256 compute units, and lane offsets of 32 bits.
+    {
+      const AccessGroup& ag = g->groups[g->mat_group];
+      const AccessGroup& bg = g->groups[g->vec_group];
+      const int64_t tiles = (g->M / 256) * (g->N / 256), rounds = (tiles + 255) / 256;
+      if (c->opt_gemm_big && c->opt_gemm_bn == 0 && g->slabs == 1 && g->M % 256 == 0 && g->N % 256 == 0 && g->K % 16 == 0 && g->K >= 32 &&
+          ag.coef[1] == 1 && bg.coef[1] == 1 && !ag.structural_zero[0] && !bg.structural_zero[0] &&
+          ag.coef[0] >= 16 && ag.coef[0] < ((int64_t)1 << 21) && bg.coef[0] >= 256 && bg.coef[0] < ((int64_t)1 << 24) &&
+          tiles >= 205 && tiles * 5 >= rounds * 256 * 4) {
+        g->BX = 256;
+        g->UC = 1;
+      }
+    }
   } else if (dot && !(dot == r && dot_as_reduce(dot) && c->opt_fusion)) {
     // ---- contraction with pointwise epilogue ------------------------------
     g->kind = GroupKind::GEMV;
@@ -1406,7 +1422,7 @@ std::string describe_plan(const Plan& plan) {
     first = true;
     for (const Node* n : g.leaves) { s << (first ? "" : ",") << n->id; first = false; }
     s << "] loads=" << [&] { int k = 0; for (const Instr& in : (g.kind == GroupKind::MAP ? g.prog1 : g.prog)) if (in.kind == IKind::LOAD) ++k; return k; }();
-    if (g.kind == GroupKind::GEMM) s << " M=" << g.M << " N=" << g.N << " K=" << g.K;
+    if (g.kind == GroupKind::GEMM) s << " M=" << g.M << " N=" << g.N << " K=" << g.K << " tile=" << (g.BX == 256 ? 256 : 128) << "x" << g.BX;
     if (g.kind == GroupKind::GEMV) s << " mode=" << (g.gemv_mode == 2 ? "row-dot+column-accumulate" : (g.gemv_mode ? "column-accumulate" : "row-dot")) << " M=" << g.M << " K=" << g.K;
     if (g.pair) {
       s << " fused-with=[root=" << g.pair->root->id << " members=[";

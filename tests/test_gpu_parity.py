@@ -815,6 +815,58 @@ def test_matrix_product_strided_and_chained(env):
     assert got.shape == (47, 80) and np.array_equal(got, ref)
 
 
+@pytest.mark.parametrize("K", [32, 48, 64, 80, 112])
+def test_large_matrix_product_every_element(env, K):
+    """The kernel for large products in natural layouts (256 x 256 tiles loaded straight into LDS), on small
+    integers: every sum is exact in float32 whatever the order of the additions, so all 2^24 results must
+    equal the oracle's.  K from two to seven steps of 16 covers every way its main loop ends."""
+    gr, ctx, torch = env
+    g = np.random.default_rng(400 + K)
+    X = g.integers(-3, 4, (4096, K)).astype(f32)
+    Y = g.integers(-3, 4, (K, 4096)).astype(f32)
+    dev, keep = to_dev(torch, ctx, dict(X=X, Y=Y))
+    assert "tile=256x256" in (dev["X"] @ dev["Y"]).plan()
+    got, ref = run_both(env, lambda xp, X, Y: X @ Y, dict(X=X, Y=Y))
+    assert np.array_equal(got, ref)
+
+
+def test_large_matrix_product_windows_epilogues_and_long_k(env):
+    gr, ctx, torch = env
+    g = np.random.default_rng(411)
+    # operands that are windows of larger arrays (rows of the windows start at any 4-byte offset), with an epilogue
+    # that reads a row vector, a column vector and a matrix: small integers again, every element compared
+    XA = g.integers(-3, 4, (4101, 150)).astype(f32)
+    YB = g.integers(-3, 4, (140, 4200)).astype(f32)
+    row = g.integers(-5, 6, (4096,)).astype(f32)
+    colv = g.integers(-5, 6, (4096, 1)).astype(f32)
+    Z = g.integers(-5, 6, (4096, 4096)).astype(f32)
+    prog = lambda xp, XA, YB, row, colv, Z: xp.maximum((XA[5:, 3:131] @ YB[7:135, 101:4197]) * 2.0 + row - colv, Z)
+    arrays = dict(XA=XA, YB=YB, row=row, colv=colv, Z=Z)
+    dev, keep = to_dev(torch, ctx, arrays)
+    assert "tile=256x256" in prog(gr, **dev).plan()
+    got, ref = run_both(env, prog, arrays)
+    assert got.shape == (4096, 4096) and np.array_equal(got, ref)
+    # 8192 x 2048 results (256 tiles, 8 per row of tiles), K = 4096 + 16, float data: sampled rows against the oracle
+    A, B, bias = _rand((8192, 4112), 412), _rand((4112, 2048), 413), _rand((2048,), 414)
+    dev, keep = to_dev(torch, ctx, dict(A=A, B=B, bias=bias))
+    expr = gr.tanh(dev["A"] @ dev["B"] * 0.05 + dev["bias"])
+    assert "tile=256x256" in expr.plan()
+    got = expr.numpy()
+    rows = np.unique(np.concatenate([np.arange(4), np.arange(8188, 8192), np.arange(254, 258), g.integers(0, 8192, 120)]))
+    sub = dict(A=np.ascontiguousarray(A[rows]), B=B, bias=bias)
+    ref, scale = track.of(lambda xp, A, B, bias: xp.tanh(A @ B * 0.05 + bias), sub)
+    assert_reduction(got[rows], ref, what="large product, K = 4112, tanh epilogue", scale=scale)
+    assert np.isfinite(got).all()
+    # the same product with the kernel switched off: equal within the bound, which shows the other kernel ran before
+    ctx.set_option("gemm_big", 0)
+    try:
+        expr = gr.tanh(dev["A"] @ dev["B"] * 0.05 + dev["bias"])
+        assert "tile=128x128" in expr.plan()
+        assert_reduction(expr.numpy()[rows], ref, what="large product, 128-wide kernel", scale=scale)
+    finally:
+        ctx.set_option("gemm_big", 1)
+
+
 def test_mnist_listing2(env):
     g = np.random.default_rng(37)
     arrays = dict(W=g.standard_normal((200, 10)).astype(f32), a=g.standard_normal(200).astype(f32), b=g.standard_normal(10).astype(f32))
