@@ -31,7 +31,7 @@ extern "C" {
  *   "gemm_kstep"      values of k per step of the matrix-product kernel's main loop (one barrier per
  *                     step): 16 (default), 32
  *   "gemm_big"        1 (default) = matrix products with M and N multiples of 256, K a multiple of 16, both
- *                     operands in their natural layouts and at least 205 tiles of 256 x 256 (filling four
+ *                     operands contiguous along one of their dimensions and at least 205 tiles of 256 x 256 (filling four
  *                     fifths of the last round over the compute units) use the kernel with one workgroup
  *                     per tile whose operand tiles go from global memory straight into LDS; 0 = the
  *                     128-wide kernel for every product

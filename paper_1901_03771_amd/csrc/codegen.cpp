@@ -1723,7 +1723,14 @@ void gemm_combine(Em& e, const EpiLoad& epi_load);
 // tracked by hand: vmcnt(8) before a step's barrier leaves only the eight loads of the newest tile in flight.
 void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   const GroupPlan& g = e.g;
-  const int ASTAGE = 4096, BROW = 264, STAGE = ASTAGE + 16 * BROW;   // floats
+  // An operand is either "k-contiguous" (kc: its tile is 256 rows of 16 k values, 16-byte chunks swizzled, a lane's
+  // 16-byte read holds four k of one row and serves four matrix instructions) or "row-contiguous" (its tile is 16 k
+  // rows of 256 values at a pitch of 264, a lane's read holds one k of four neighbouring rows = its four blocks).
+  struct Op { bool kc; const char* n; const char* ld; const char* org; int part; int size; };
+  const bool akc = g.groups[g.mat_group].coef[1] == 1, bkc = g.groups[g.vec_group].coef[1] != 1;
+  const int KC = 4096, RC = 16 * 264;
+  Op ops[2] = {{akc, "a", akc ? "am" : "ak", "bm0", 0, akc ? KC : RC}, {bkc, "b", bkc ? "bn" : "bk", "bn0", akc ? KC : RC, bkc ? KC : RC}};
+  const int STAGE = ops[0].size + ops[1].size;   // floats
   std::ostream& o = e.o;
   o << "  __shared__ __attribute__((aligned(16))) float gr_lds[" << 3 * STAGE << "];\n"
        "  typedef __attribute__((address_space(3))) float lfloat;\n"
@@ -1735,38 +1742,56 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
        "  f16v acc[4][4];\n"
        "  for (int i = 0; i < 4; ++i) for (int j = 0; j < 4; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n"
        "  const unsigned wv = __builtin_amdgcn_readfirstlane(wave);\n"
-       "  unsigned aoff[4], boff[4];\n"
-       "#pragma unroll\n"
-       "  for (int p = 0; p < 4; ++p) { const int m = 16 * (4 * wave + p) + lane / 4, c = (lane % 4) ^ ((m >> 2) & 3); aoff[p] = 4u * (unsigned)(m * am + 4 * c); }\n"
-       "#pragma unroll\n"
-       "  for (int p = 0; p < 4; ++p) boff[p] = 4u * (unsigned)((4 * wave + p) * bk + 4 * lane);\n"
-       "  // (uniform addresses, made visibly so: the operands of the loads below must be scalar registers)\n"
-       "  const unsigned long long a64 = (unsigned long long)(A + bm0 * am), b64 = (unsigned long long)(B + bn0);\n"
-       "  unsigned long long Ab = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(a64 >> 32)) << 32) | (unsigned)__builtin_amdgcn_readfirstlane((int)a64);\n"
-       "  unsigned long long Bb = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(b64 >> 32)) << 32) | (unsigned)__builtin_amdgcn_readfirstlane((int)b64);\n"
-       "  const unsigned long long bstep = 64ull * (unsigned long long)__builtin_amdgcn_readfirstlane((int)bk);\n"
-       "  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)gr_lds;\n"
-       "  const unsigned ldsa = lds0 + 4096u * wv, ldsb = lds0 + " << 4 * ASTAGE << "u + " << 16 * BROW << "u * wv;\n"
-       "  const lfloat* pa[3][2];\n"
-       "  const lfloat* pb[3];\n"
-       "#pragma unroll\n"
-       "  for (int st = 0; st < 3; ++st) {\n"
-       "#pragma unroll\n"
-       "    for (int hf = 0; hf < 2; ++hf) pa[st][hf] = (const lfloat*)gr_lds + st * " << STAGE << " + (wm + l32) * 16 + 4 * ((2 * hf + lh) ^ ((l32 >> 2) & 3));\n"
-       "    pb[st] = (const lfloat*)gr_lds + st * " << STAGE << " + " << ASTAGE << " + 4 * lh * " << BROW << " + wn + 4 * l32;\n"
-       "  }\n"
-       "  f4 aF[2][4];\n"
-       "  f4 bF[2];\n"
-       "  const long long nkt = K / 16;\n";
-  // piece p (0..3: blocks of 16 rows of the left tile, 4..7: rows of the right tile) of the tile at Ab / Bb into stage st
+       "  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)gr_lds;\n";
+  for (const Op& x : ops) {
+    const std::string n = x.n, w0 = x.n[0] == 'a' ? "wm" : "wn", X = x.n[0] == 'a' ? "A" : "B";
+    // direct loads: a uniform base (advanced every step; made visibly uniform, the operands of the loads must be scalar
+    // registers) plus a 32-bit byte offset per lane and piece
+    o << "  unsigned " << n << "off[4];\n#pragma unroll\n";
+    if (x.kc)
+      o << "  for (int p = 0; p < 4; ++p) { const int m = 16 * (4 * wave + p) + lane / 4, c = (lane % 4) ^ ((m >> 2) & 3); " << n << "off[p] = 4u * (unsigned)(m * " << x.ld << " + 4 * c); }\n"
+           "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << " * " << x.ld << ");\n"
+           "  const unsigned long long " << n << "step = 64ull;\n";
+    else
+      o << "  for (int p = 0; p < 4; ++p) " << n << "off[p] = 4u * (unsigned)((4 * wave + p) * " << x.ld << " + 4 * lane);\n"
+           "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << ");\n"
+           "  const unsigned long long " << n << "step = 64ull * (unsigned long long)__builtin_amdgcn_readfirstlane((int)" << x.ld << ");\n";
+    o << "  unsigned long long " << n << "base = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(" << n << "64 >> 32)) << 32) | (unsigned)__builtin_amdgcn_readfirstlane((int)" << n << "64);\n"
+         "  const unsigned " << n << "lds = lds0 + " << 4 * x.part << "u + " << (x.kc ? 4096 : 16 * 264) << "u * wv;\n";
+    // LDS read bases of this lane, per stage
+    if (x.kc)
+      o << "  const lfloat* " << n << "p[3][2];\n#pragma unroll\n  for (int st = 0; st < 3; ++st)\n#pragma unroll\n"
+           "    for (int hf = 0; hf < 2; ++hf) " << n << "p[st][hf] = (const lfloat*)gr_lds + st * " << STAGE << " + " << x.part << " + (" << w0 << " + l32) * 16 + 4 * ((2 * hf + lh) ^ ((l32 >> 2) & 3));\n"
+           "  f4 " << n << "F[2][4];\n";
+    else
+      o << "  const lfloat* " << n << "p[3];\n#pragma unroll\n  for (int st = 0; st < 3; ++st) " << n << "p[st] = (const lfloat*)gr_lds + st * " << STAGE << " + " << x.part << " + 4 * lh * 264 + " << w0 << " + 4 * l32;\n"
+           "  f4 " << n << "F[2];\n";
+  }
+  o << "  const long long nkt = K / 16;\n";
+  // piece p (0..3: the left tile, 4..7: the right tile) of the tile at the bases into stage st
   auto piece = [&](int st, int p, const char* ind) {
-    const int imm = p < 4 ? st * STAGE * 4 + 1024 * p : st * STAGE * 4 + 4 * BROW * (p - 4);
+    const Op& x = ops[p / 4];
+    const int imm = st * STAGE * 4 + (x.kc ? 1024 : 4 * 264) * (p % 4);
     o << ind << "asm volatile(\"s_add_i32 m0, %2, " << imm << "\\n\\ts_nop 0\\n\\tglobal_load_lds_dwordx4 %0, %1\" : : \"v\"("
-      << (p < 4 ? "aoff[" : "boff[") << p % 4 << "]), \"s\"(" << (p < 4 ? "Ab" : "Bb") << "), \"s\"(" << (p < 4 ? "ldsa" : "ldsb") << ") : \"memory\");\n";
+      << x.n << "off[" << p % 4 << "]), \"s\"(" << x.n << "base), \"s\"(" << x.n << "lds) : \"memory\");\n";
   };
+  const char* ADV = "abase += astep; bbase += bstep;\n";
   const char* SB = "__builtin_amdgcn_sched_barrier(0);\n";
-  // one step: stage st holds the current tile; the tile two steps on (at Ab / Bb) goes to stage (st + 2) % 3 if more2;
-  // the first operands of the next step are read behind the barrier if more1
+  // operand of matrix instruction (group s of the step, block i) and the LDS reads that provide it
+  auto val = [&](const Op& x, int s, int blk) {
+    std::ostringstream v;
+    if (x.kc) v << x.n << "F[" << (s >> 2) << "][" << blk << "][" << (s & 3) << "]";
+    else v << x.n << "F[" << (s & 1) << "][" << blk << "]";
+    return v.str();
+  };
+  auto read_kc = [&](const Op& x, int st, int hf, int blk, const char* ind) {
+    o << ind << x.n << "F[" << hf << "][" << blk << "] = *(const lf4*)(" << x.n << "p[" << st << "][" << hf << "] + " << blk * 512 << ");\n";
+  };
+  auto read_rc = [&](const Op& x, int st, int s, const char* ind) {
+    o << ind << x.n << "F[" << (s & 1) << "] = *(const lf4*)(" << x.n << "p[" << st << "] + " << (8 * (s >> 2) + (s & 3)) * 264 << ");\n";
+  };
+  // one step: stage st holds the current tile; the tile two steps on goes to stage (st + 2) % 3 if more2; the first
+  // operands of the next step are read behind the barrier if more1
   auto step = [&](int st, bool more2, bool more1, const char* ind) {
     const int st1 = (st + 1) % 3, st2 = (st + 2) % 3;
     for (int s = 0; s < 8; ++s) {
@@ -1775,26 +1800,36 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
         o << ind << "__builtin_amdgcn_s_waitcnt(" << (more2 ? 0x0070 | 8 : 0x0070) << ");\n" << ind << "__builtin_amdgcn_s_barrier();\n";
       for (int q = 0; q < 16; ++q) {
         const int i = q >> 2, j = q & 3;
-        o << ind << SB << ind << "acc[" << i << "][" << j << "] = __builtin_amdgcn_mfma_f32_32x32x2f32(aF[" << (s >> 2) << "][" << i << "][" << (s & 3) << "], bF[" << (s & 1) << "][" << j
-          << "], acc[" << i << "][" << j << "], 0, 0, 0);\n" << ind << SB;
+        o << ind << SB << ind << "acc[" << i << "][" << j << "] = __builtin_amdgcn_mfma_f32_32x32x2f32(" << val(ops[0], s, i) << ", " << val(ops[1], s, j)
+          << ", acc[" << i << "][" << j << "], 0, 0, 0);\n" << ind << SB;
         if (more2 && q == 1 && s < 7) piece(st2, s, ind);
-        if (more2 && s == 6 && q == 9) { piece(st2, 7, ind); o << ind << "Ab += 64; Bb += bstep;\n"; }
-        if (s < 7 && q == 4) o << ind << "bF[" << ((s + 1) & 1) << "] = *(const lf4*)(pb[" << st << "] + " << (8 * ((s + 1) >> 2) + ((s + 1) & 3)) * BROW << ");\n";
-        if (s == 1 && q >= 8 && q < 12) o << ind << "aF[1][" << q - 8 << "] = *(const lf4*)(pa[" << st << "][1] + " << (q - 8) * 512 << ");\n";
-        if (s == 7 && more1 && q < 4) o << ind << "aF[0][" << q << "] = *(const lf4*)(pa[" << st1 << "][0] + " << q * 512 << ");\n";
-        if (s == 7 && more1 && q == 4) o << ind << "bF[0] = *(const lf4*)(pb[" << st1 << "]);\n";
+        if (more2 && s == 6 && q == 9) { piece(st2, 7, ind); o << ind << ADV; }
+        for (int k = 0; k < 2; ++k) {
+          const Op& x = ops[k];
+          if (x.kc) {
+            // second half of the step: four reads behind matrix instructions 8..11 (left) / 12..15 (right) of group 1;
+            // first half of the next step: behind 0..3 / 5..8 of group 7
+            if (s == 1 && q >= 8 + 4 * k && q < 12 + 4 * k) read_kc(x, st, 1, q - 8 - 4 * k, ind);
+            if (s == 7 && more1 && q >= 5 * k && q < 4 + 5 * k) read_kc(x, st1, 0, q - 5 * k, ind);
+          } else {
+            if (s < 7 && q == 4 + 2 * k) read_rc(x, st, s + 1, ind);
+            if (s == 7 && more1 && q == 4 + 5 * k) read_rc(x, st1, 0, ind);
+          }
+        }
       }
     }
   };
   // prologue: tiles 0 and 1 (K >= 32)
   for (int t = 0; t < 2; ++t) {
     for (int p = 0; p < 8; ++p) piece(t, p, "  ");
-    o << "  Ab += 64; Bb += bstep;\n";
+    o << "  " << ADV;
   }
-  o << "  __builtin_amdgcn_s_waitcnt(" << (0x0F70 | 8) << ");\n  __builtin_amdgcn_s_barrier();\n"
-       "#pragma unroll\n  for (int i = 0; i < 4; ++i) aF[0][i] = *(const lf4*)(pa[0][0] + i * 512);\n"
-       "  bF[0] = *(const lf4*)(pb[0]);\n"
-       "  long long kt = 0;\n"
+  o << "  __builtin_amdgcn_s_waitcnt(" << (0x0F70 | 8) << ");\n  __builtin_amdgcn_s_barrier();\n";
+  for (const Op& x : ops) {
+    if (x.kc) for (int blk = 0; blk < 4; ++blk) read_kc(x, 0, 0, blk, "  ");
+    else read_rc(x, 0, 0, "  ");
+  }
+  o << "  long long kt = 0;\n"
        "  for (; kt + 5 <= nkt; kt += 3) {\n";
   for (int st = 0; st < 3; ++st) step(st, true, true, "    ");
   o << "  }\n"
@@ -1812,17 +1847,22 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   step(2, false, true, "    ");
   step(0, false, false, "    ");
   o << "  }\n";
-  // epilogue on the accumulators: element q of block (i, j) is row wm + 32 i + 8 (q / 4) + 4 (lane / 32) + q % 4, column wn + 4 (lane % 32) + j
+  // epilogue on the accumulators: element q of a block is its row rr = 8 (q / 4) + 4 (lane / 32) + q % 4 and column lane % 32;
+  // block i of a k-contiguous left operand holds rows wm + 32 i + rr, of a row-contiguous one rows wm + 4 rr + i; block j
+  // of a row-contiguous right operand holds column wn + 4 (lane % 32) + j (a lane's four results are neighbours: one
+  // 16-byte store), of a k-contiguous one column wn + 32 j + lane % 32
   o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n"
        "#pragma unroll\n  for (int i = 0; i < 4; ++i)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
-       "      const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4);\n"
+       "      const int rr = 8 * (q / 4) + 4 * lh + (q % 4);\n"
+       "      const long long row = bm0 + wm + " << (ops[0].kc ? "32 * i + rr" : "4 * rr + i") << ";\n"
        "      f4 ov;\n"
        "#pragma unroll\n      for (int j = 0; j < 4; ++j) {\n"
-       "        const long long col = bn0 + wn + 4 * l32 + j;\n"
+       "        const long long col = bn0 + wn + " << (ops[1].kc ? "32 * j + l32" : "4 * l32 + j") << ";\n"
        "        const float cacc = acc[i][j][q];\n";
   emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
-  o << "        ov[j] = t" << g.results[0] << ";\n      }\n"
-       "      *(GM f4u*)(out + row * N + bn0 + wn + 4 * l32) = ov;\n    }\n}\n";
+  if (ops[1].kc) o << "        out[row * N + col] = t" << g.results[0] << ";\n      }\n      (void)ov;\n    }\n}\n";
+  else o << "        ov[j] = t" << g.results[0] << ";\n      }\n"
+            "      *(GM f4u*)(out + row * N + bn0 + wn + 4 * l32) = ov;\n    }\n}\n";
 }
 
 

@@ -926,18 +926,25 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
         if (ks >= 2) g->slabs = (int)std::min<int64_t>(ks, 256);
       }
     }
-    // Large products of operands in their natural layouts (rows of the left operand contiguous along k, rows of
-    // the right one along n): 256 x 256 tiles, one workgroup per compute unit, tiles loaded straight into LDS
-    // (BX = 256 selects that kernel).  It needs whole tiles and whole steps of 16 values of k, enough tiles to
-    // fill at least four fifths of the last round over the 256 compute units, and lane offsets of 32 bits.
+    // Large products of operands that are contiguous along one of their two dimensions: 256 x 256 tiles, one
+    // workgroup per compute unit, tiles loaded straight into LDS (BX = 256 selects that kernel).  It needs whole
+    // tiles and whole steps of 16 values of k, enough tiles to fill at least four fifths of the last round over
+    // the 256 compute units, and lane offsets of 32 bits: an operand contiguous along k is loaded in rows of its
+    // other dimension (row stride below 2^21 elements), one contiguous along its other dimension in rows of k
+    // (stride below 2^24).
     {
       const AccessGroup& ag = g->groups[g->mat_group];
       const AccessGroup& bg = g->groups[g->vec_group];
       const int64_t tiles = (g->M / 256) * (g->N / 256), rounds = (tiles + 255) / 256;
+      auto fits = [](const AccessGroup& x, int kdim) {   // kdim: which of the operand's two dimensions is k
+        if (x.structural_zero[0] || x.structural_zero[1]) return false;
+        const int64_t sk = x.coef[kdim], so = x.coef[1 - kdim];
+        if (sk == 1 && so != 1) return so >= 16 && so < ((int64_t)1 << 21);
+        if (so == 1 && sk != 1) return sk >= 256 && sk < ((int64_t)1 << 24);
+        return false;
+      };
       if (c->opt_gemm_big && c->opt_gemm_bn == 0 && g->slabs == 1 && g->M % 256 == 0 && g->N % 256 == 0 && g->K % 16 == 0 && g->K >= 32 &&
-          ag.coef[1] == 1 && bg.coef[1] == 1 && !ag.structural_zero[0] && !bg.structural_zero[0] &&
-          ag.coef[0] >= 16 && ag.coef[0] < ((int64_t)1 << 21) && bg.coef[0] >= 256 && bg.coef[0] < ((int64_t)1 << 24) &&
-          tiles >= 205 && tiles * 5 >= rounds * 256 * 4) {
+          fits(ag, 1) && fits(bg, 0) && tiles >= 205 && tiles * 5 >= rounds * 256 * 4) {
         g->BX = 256;
         g->UC = 1;
       }

@@ -815,19 +815,25 @@ def test_matrix_product_strided_and_chained(env):
     assert got.shape == (47, 80) and np.array_equal(got, ref)
 
 
+@pytest.mark.parametrize("layout", ["nn", "tn", "nt", "tt"])
 @pytest.mark.parametrize("K", [32, 48, 64, 80, 112])
-def test_large_matrix_product_every_element(env, K):
-    """The kernel for large products in natural layouts (256 x 256 tiles loaded straight into LDS), on small
-    integers: every sum is exact in float32 whatever the order of the additions, so all 2^24 results must
-    equal the oracle's.  K from two to seven steps of 16 covers every way its main loop ends."""
+def test_large_matrix_product_every_element(env, K, layout):
+    """The kernel for large products (256 x 256 tiles loaded straight into LDS), on small integers: every sum is
+    exact in float32 whatever the order of the additions, so all 2^24 results must equal the oracle's.  K from two
+    to seven steps of 16 covers every way its main loop ends; "t" = that operand is the transposed view of an
+    array stored the other way round (its tile is loaded along the other dimension)."""
     gr, ctx, torch = env
     g = np.random.default_rng(400 + K)
     X = g.integers(-3, 4, (4096, K)).astype(f32)
     Y = g.integers(-3, 4, (K, 4096)).astype(f32)
-    dev, keep = to_dev(torch, ctx, dict(X=X, Y=Y))
-    assert "tile=256x256" in (dev["X"] @ dev["Y"]).plan()
-    got, ref = run_both(env, lambda xp, X, Y: X @ Y, dict(X=X, Y=Y))
-    assert np.array_equal(got, ref)
+    arrays = dict(X=np.ascontiguousarray(X.T) if layout[0] == "t" else X, Y=np.ascontiguousarray(Y.T) if layout[1] == "t" else Y)
+    prog = lambda xp, X, Y: (X.T if layout[0] == "t" else X) @ (Y.T if layout[1] == "t" else Y)
+    dev, keep = to_dev(torch, ctx, arrays)
+    assert "tile=256x256" in prog(gr, **dev).plan()
+    got, ref = run_both(env, prog, arrays)
+    assert got.shape == (4096, 4096) and np.array_equal(got, ref)
+    if layout == "nn":
+        assert np.array_equal(ref, (X.astype(np.float64) @ Y.astype(np.float64)).astype(f32)), "exact in any order"
 
 
 def test_large_matrix_product_windows_epilogues_and_long_k(env):
@@ -843,6 +849,11 @@ def test_large_matrix_product_windows_epilogues_and_long_k(env):
     prog = lambda xp, XA, YB, row, colv, Z: xp.maximum((XA[5:, 3:131] @ YB[7:135, 101:4197]) * 2.0 + row - colv, Z)
     arrays = dict(XA=XA, YB=YB, row=row, colv=colv, Z=Z)
     dev, keep = to_dev(torch, ctx, arrays)
+    assert "tile=256x256" in prog(gr, **dev).plan()
+    got, ref = run_both(env, prog, arrays)
+    assert got.shape == (4096, 4096) and np.array_equal(got, ref)
+    # both operands transposed windows (the left one loaded in rows of k, the right one in rows of n), column-vector epilogue
+    prog = lambda xp, XA, YB, row, colv, Z: (xp.transpose(YB[7:135, 101:4197], (1, 0)) @ xp.transpose(XA[5:, 3:131], (1, 0))) - colv
     assert "tile=256x256" in prog(gr, **dev).plan()
     got, ref = run_both(env, prog, arrays)
     assert got.shape == (4096, 4096) and np.array_equal(got, ref)
