@@ -1757,7 +1757,7 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
            "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << ");\n"
            "  const unsigned long long " << n << "step = 64ull * (unsigned long long)__builtin_amdgcn_readfirstlane((int)" << x.ld << ");\n";
     o << "  unsigned long long " << n << "base = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(" << n << "64 >> 32)) << 32) | (unsigned)__builtin_amdgcn_readfirstlane((int)" << n << "64);\n"
-         "  const unsigned " << n << "lds = lds0 + " << 4 * x.part << "u + " << (x.kc ? 4096 : 16 * 264) << "u * wv;\n";
+         "  unsigned " << n << "lds[3];\n#pragma unroll\n  for (int st = 0; st < 3; ++st) " << n << "lds[st] = lds0 + " << 4 * STAGE << "u * st + " << 4 * x.part << "u + " << (x.kc ? 4096 : 16 * 264) << "u * wv;\n";
     // LDS read bases of this lane, per stage
     if (x.kc)
       o << "  const lfloat* " << n << "p[3][2];\n#pragma unroll\n  for (int st = 0; st < 3; ++st)\n#pragma unroll\n"
@@ -1771,9 +1771,9 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   // piece p (0..3: the left tile, 4..7: the right tile) of the tile at the bases into stage st
   auto piece = [&](int st, int p, const char* ind) {
     const Op& x = ops[p / 4];
-    const int imm = st * STAGE * 4 + (x.kc ? 1024 : 4 * 264) * (p % 4);
+    const int imm = (x.kc ? 1024 : 4 * 264) * (p % 4);
     o << ind << "asm volatile(\"s_add_i32 m0, %2, " << imm << "\\n\\ts_nop 0\\n\\tglobal_load_lds_dwordx4 %0, %1\" : : \"v\"("
-      << x.n << "off[" << p % 4 << "]), \"s\"(" << x.n << "base), \"s\"(" << x.n << "lds) : \"memory\");\n";
+      << x.n << "off[" << p % 4 << "]), \"s\"(" << x.n << "base), \"s\"(" << x.n << "lds[" << st << "]) : \"memory\");\n";
   };
   const char* ADV = "abase += astep; bbase += bstep;\n";
   const char* SB = "__builtin_amdgcn_sched_barrier(0);\n";
@@ -1829,24 +1829,24 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
     if (x.kc) for (int blk = 0; blk < 4; ++blk) read_kc(x, 0, 0, blk, "  ");
     else read_rc(x, 0, 0, "  ");
   }
+  // the stages rotate through three roles (0: the tile of this step, 1: of the next one, 2: the target of this step's
+  // loads): the addresses are exchanged after every step, a handful of register moves per 128 matrix instructions
+  std::ostringstream rot;
+  for (const Op& x : ops) {
+    rot << "{ const unsigned t = " << x.n << "lds[0]; " << x.n << "lds[0] = " << x.n << "lds[1]; " << x.n << "lds[1] = " << x.n << "lds[2]; " << x.n << "lds[2] = t; }\n";
+    if (x.kc) rot << "    { const lfloat* const t0 = " << x.n << "p[0][0]; const lfloat* const t1 = " << x.n << "p[0][1]; " << x.n << "p[0][0] = " << x.n << "p[1][0]; " << x.n << "p[0][1] = " << x.n << "p[1][1]; "
+                  << x.n << "p[1][0] = " << x.n << "p[2][0]; " << x.n << "p[1][1] = " << x.n << "p[2][1]; " << x.n << "p[2][0] = t0; " << x.n << "p[2][1] = t1; }\n";
+    else rot << "    { const lfloat* const t0 = " << x.n << "p[0]; " << x.n << "p[0] = " << x.n << "p[1]; " << x.n << "p[1] = " << x.n << "p[2]; " << x.n << "p[2] = t0; }\n";
+    if (&x == &ops[0]) rot << "    ";
+  }
   o << "  long long kt = 0;\n"
-       "  for (; kt + 5 <= nkt; kt += 3) {\n";
-  for (int st = 0; st < 3; ++st) step(st, true, true, "    ");
-  o << "  }\n"
-       "  // two, three or four steps are left, the first of them in stage 0\n"
-       "  if (nkt - kt == 2) {\n";
-  step(0, false, true, "    ");
-  step(1, false, false, "    ");
-  o << "  } else if (nkt - kt == 3) {\n";
+       "  for (; kt + 2 < nkt; ++kt) {\n";
   step(0, true, true, "    ");
-  step(1, false, true, "    ");
-  step(2, false, false, "    ");
-  o << "  } else {\n";
-  step(0, true, true, "    ");
-  step(1, true, true, "    ");
-  step(2, false, true, "    ");
-  step(0, false, false, "    ");
-  o << "  }\n";
+  o << "    " << rot.str() << "  }\n"
+       "  // the last two steps load nothing\n";
+  step(0, false, true, "  ");
+  o << "  " << rot.str();
+  step(0, false, false, "  ");
   // epilogue on the accumulators: element q of a block is its row rr = 8 (q / 4) + 4 (lane / 32) + q % 4 and column lane % 32;
   // block i of a k-contiguous left operand holds rows wm + 32 i + rr, of a row-contiguous one rows wm + 4 rr + i; block j
   // of a row-contiguous right operand holds column wn + 4 (lane % 32) + j (a lane's four results are neighbours: one
