@@ -698,11 +698,14 @@ def test_generated_kernels_keep_their_values_in_registers(ctx, tmp_path):
     progs = {
         "gemm": heavy(X @ M2) + ctx.spec((512,)),
         "gemm narrow": heavy(X @ ctx.spec((1024, 32))),
+        "gemm, 256 x 256 tiles": heavy(X @ ctx.spec((1024, 4096))) + ctx.spec((4096,)),
+        "gemm, 256 x 256 tiles, transposed views": heavy(ctx.spec((1024, 4096)).T @ ctx.spec((4096, 1024)).T),
         "gemv": heavy(X @ V),
         "rowred": heavy(X - gr.max(X, axis=1, keepdims=True)) / gr.sum(heavy(X), axis=1, keepdims=True),
         "map": heavy(wl.stencil(gr, X)),
         "scan": gr.cumsum(heavy(X), 0),
     }
+    assert all("tile=256x256" in out.plan() for name, out in progs.items() if "256 x 256" in name)
     for name, out in progs.items():
         src = tmp_path / "k.hip"
         src.write_text("#include <hip/hip_runtime.h>\n" + out.source(0))
