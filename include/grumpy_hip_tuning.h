@@ -30,11 +30,11 @@ extern "C" {
  *                     than half empty
  *   "gemm_kstep"      values of k per step of the matrix-product kernel's main loop (one barrier per
  *                     step): 16 (default), 32
- *   "gemm_big"        1 (default) = matrix products with M and N multiples of 256, K a multiple of 16, both
- *                     operands contiguous along one of their dimensions and at least 205 tiles of 256 x 256 (filling four
- *                     fifths of the last round over the compute units) use the kernel with one workgroup
- *                     per tile whose operand tiles go from global memory straight into LDS; 0 = the
- *                     128-wide kernel for every product
+ *   "gemm_big"        1 (default) = matrix products whose operands are each contiguous along one of their
+ *                     dimensions, with K a multiple of 16 and a result that fills at least 85 % (65 % if M or
+ *                     N is not a multiple of 128) of its rounds of 256 x 256 tiles over the 256 compute units,
+ *                     use the kernel with one workgroup per tile whose operand tiles go from global memory
+ *                     straight into LDS; 0 = the 128-wide kernel for every product
  *   "nontemporal"     1 (default) = loads of arrays that are read once carry the non-temporal hint,
  *                     and so do the vector stores of a requested value of 192 MiB or more (not of
  *                     intermediate results of the request; except in kernels that read a transposed

@@ -1696,8 +1696,8 @@ void gen_gemv_pair(Em& e, Em& e2) {
 using EpiLoad = std::function<std::string(const Instr&, int)>;
 void gemm_combine(Em& e, const EpiLoad& epi_load);
 
-// Matrix product of large operands in their natural layouts (left operand contiguous along k, right one
-// along n; M and N multiples of 256, K a multiple of 16): one workgroup per 256 x 256 tile of the result and
+// Matrix product of large operands, each contiguous along one of its dimensions (K a multiple of 16; M and N need
+// not be multiples of 256: edge tiles load clamped rows and store only what exists): one workgroup per 256 x 256 tile of the result and
 // per compute unit, four waves with a 128 x 128 quarter each as 4 x 4 matrix-core blocks (256 accumulator
 // registers per lane).
 //   * Tiles of 16 values of k go from global memory straight into LDS (global_load_lds_dwordx4: lane L of a
@@ -1726,10 +1726,10 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   // An operand is either "k-contiguous" (kc: its tile is 256 rows of 16 k values, 16-byte chunks swizzled, a lane's
   // 16-byte read holds four k of one row and serves four matrix instructions) or "row-contiguous" (its tile is 16 k
   // rows of 256 values at a pitch of 264, a lane's read holds one k of four neighbouring rows = its four blocks).
-  struct Op { bool kc; const char* n; const char* ld; const char* org; int part; int size; };
+  struct Op { bool kc; const char* n; const char* ld; const char* org; const char* lim; int part; int size; };
   const bool akc = g.groups[g.mat_group].coef[1] == 1, bkc = g.groups[g.vec_group].coef[1] != 1;
   const int KC = 4096, RC = 16 * 264;
-  Op ops[2] = {{akc, "a", akc ? "am" : "ak", "bm0", 0, akc ? KC : RC}, {bkc, "b", bkc ? "bn" : "bk", "bn0", akc ? KC : RC, bkc ? KC : RC}};
+  Op ops[2] = {{akc, "a", akc ? "am" : "ak", "bm0", "M", 0, akc ? KC : RC}, {bkc, "b", bkc ? "bn" : "bk", "bn0", "N", akc ? KC : RC, bkc ? KC : RC}};
   const int STAGE = ops[0].size + ops[1].size;   // floats
   std::ostream& o = e.o;
   o << "  __shared__ __attribute__((aligned(16))) float gr_lds[" << 3 * STAGE << "];\n"
@@ -1737,7 +1737,7 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
        "  typedef __attribute__((address_space(3))) f4 lf4;\n"
        "  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;\n"
        "  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;\n"
-       "  const long long tiles_n = N / 256;\n"
+       "  const long long tiles_n = (N + 255) / 256;\n"
        "  const long long bm0 = (blockIdx.x / tiles_n) * 256, bn0 = (blockIdx.x % tiles_n) * 256;\n"
        "  f16v acc[4][4];\n"
        "  for (int i = 0; i < 4; ++i) for (int j = 0; j < 4; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n"
@@ -1749,11 +1749,14 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
     // registers) plus a 32-bit byte offset per lane and piece
     o << "  unsigned " << n << "off[4];\n#pragma unroll\n";
     if (x.kc)
-      o << "  for (int p = 0; p < 4; ++p) { const int m = 16 * (4 * wave + p) + lane / 4, c = (lane % 4) ^ ((m >> 2) & 3); " << n << "off[p] = 4u * (unsigned)(m * " << x.ld << " + 4 * c); }\n"
+      // (rows beyond the operand's edge read its last row: their results are never stored)
+      o << "  for (int p = 0; p < 4; ++p) { const int m = 16 * (4 * wave + p) + lane / 4, c = (lane % 4) ^ ((m >> 2) & 3); const long long last = " << x.lim << " - 1 - " << x.org
+        << "; " << n << "off[p] = 4u * (unsigned)((m < last ? m : last) * " << x.ld << " + 4 * c); }\n"
            "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << " * " << x.ld << ");\n"
            "  const unsigned long long " << n << "step = 64ull;\n";
     else
-      o << "  for (int p = 0; p < 4; ++p) " << n << "off[p] = 4u * (unsigned)((4 * wave + p) * " << x.ld << " + 4 * lane);\n"
+      // (groups of four beyond the operand's edge, whose extent is a multiple of four, read its last group)
+      o << "  for (int p = 0; p < 4; ++p) { const long long last = " << x.lim << " - 4 - " << x.org << "; " << n << "off[p] = 4u * (unsigned)((4 * wave + p) * " << x.ld << " + (4 * lane < last ? 4 * lane : last)); }\n"
            "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << ");\n"
            "  const unsigned long long " << n << "step = 64ull * (unsigned long long)__builtin_amdgcn_readfirstlane((int)" << x.ld << ");\n";
     o << "  unsigned long long " << n << "base = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(" << n << "64 >> 32)) << 32) | (unsigned)__builtin_amdgcn_readfirstlane((int)" << n << "64);\n"
@@ -1858,11 +1861,12 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
        "      f4 ov;\n"
        "#pragma unroll\n      for (int j = 0; j < 4; ++j) {\n"
        "        const long long col = bn0 + wn + " << (ops[1].kc ? "32 * j + l32" : "4 * l32 + j") << ";\n"
+       "        if (row < M && col < N) {\n"
        "        const float cacc = acc[i][j][q];\n";
   emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
-  if (ops[1].kc) o << "        out[row * N + col] = t" << g.results[0] << ";\n      }\n      (void)ov;\n    }\n}\n";
-  else o << "        ov[j] = t" << g.results[0] << ";\n      }\n"
-            "      *(GM f4u*)(out + row * N + bn0 + wn + 4 * l32) = ov;\n    }\n}\n";
+  if (ops[1].kc) o << "        out[row * N + col] = t" << g.results[0] << ";\n        }\n      }\n      (void)ov;\n    }\n}\n";
+  else o << "        ov[j] = t" << g.results[0] << ";\n        }\n      }\n"
+            "      if (row < M && bn0 + wn + 4 * l32 < N) *(GM f4u*)(out + row * N + bn0 + wn + 4 * l32) = ov;\n    }\n}\n";
 }
 
 

@@ -915,7 +915,11 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
     // columns of the output tile of one workgroup: 128, or 32 for narrow results and where the last
     // 128-wide tile would be more than half empty (measured, 65536 x 64 x 64: 14.5 us against 21.8 us;
     // 8192 x 512 x 520: 67 against 94 us; a full 128-wide tile costs about 0.3 of four 32-wide ones less)
-    g->BX = (g->N <= 96 || ((g->N + 127) / 128) * 128 - g->N >= 64) ? 32 : 128;
+    // (only where those empty columns are more than an eighth of the padded width: 4000 columns keep 128-wide tiles)
+    {
+      const int64_t padded = ((g->N + 127) / 128) * 128, pad = padded - g->N;
+      g->BX = (g->N <= 96 || (pad >= 64 && pad * 8 > padded)) ? 32 : 128;
+    }
     if (c->opt_gemm_bn == 32 || c->opt_gemm_bn == 128) g->BX = (int)c->opt_gemm_bn;
     // k extent of one step of the main loop (one barrier per step): 16, or 32 on request
     g->UC = (g->BX == 128 && c->opt_gemm_kstep == 32) ? 2 : 1;
@@ -927,24 +931,30 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       }
     }
     // Large products of operands that are contiguous along one of their two dimensions: 256 x 256 tiles, one
-    // workgroup per compute unit, tiles loaded straight into LDS (BX = 256 selects that kernel).  It needs whole
-    // tiles and whole steps of 16 values of k, enough tiles to fill at least four fifths of the last round over
-    // the 256 compute units, and lane offsets of 32 bits: an operand contiguous along k is loaded in rows of its
+    // workgroup per compute unit, tiles loaded straight into LDS (BX = 256 selects that kernel).  It needs
+    // whole steps of 16 values of k, a result that fills most of its rounds over the 256 compute units, and lane offsets
+    // of 32 bits: an operand contiguous along k is loaded in rows of its
     // other dimension (row stride below 2^21 elements), one contiguous along its other dimension in rows of k
     // (stride below 2^24).
     {
       const AccessGroup& ag = g->groups[g->mat_group];
       const AccessGroup& bg = g->groups[g->vec_group];
-      const int64_t tiles = (g->M / 256) * (g->N / 256), rounds = (tiles + 255) / 256;
-      auto fits = [](const AccessGroup& x, int kdim) {   // kdim: which of the operand's two dimensions is k
+      const int64_t tiles = ((g->M + 255) / 256) * ((g->N + 255) / 256), rounds = (tiles + 255) / 256;
+      // other: the extent of the operand's dimension that is not k (a multiple of four where that dimension is the
+      // contiguous one: its elements are loaded in groups of four)
+      auto fits = [](const AccessGroup& x, int kdim, int64_t other) {   // kdim: which of the operand's two dimensions is k
         if (x.structural_zero[0] || x.structural_zero[1]) return false;
         const int64_t sk = x.coef[kdim], so = x.coef[1 - kdim];
         if (sk == 1 && so != 1) return so >= 16 && so < ((int64_t)1 << 21);
-        if (so == 1 && sk != 1) return sk >= 256 && sk < ((int64_t)1 << 24);
+        if (so == 1 && sk != 1) return sk >= 256 && sk < ((int64_t)1 << 24) && other % 4 == 0;
         return false;
       };
-      if (c->opt_gemm_big && c->opt_gemm_bn == 0 && g->slabs == 1 && g->M % 256 == 0 && g->N % 256 == 0 && g->K % 16 == 0 && g->K >= 32 &&
-          fits(ag, 1) && fits(bg, 0) && tiles >= 205 && tiles * 5 >= rounds * 256 * 4) {
+      // Edge tiles are whole tiles of work: the result must fill 85 % of its rounds over the 256 compute units, 65 %
+      // where M or N is not a multiple of 128 (the 128-wide kernel's guarded edge tiles make it slower there; measured
+      // on 4000^3: 136 against 97 TFLOP/s, 8000^3: 144 against 114, 10000 x 4096 x 10000, seven rounds 85 % full: 126 against 117).
+      const int64_t need = (g->M % 128 == 0 && g->N % 128 == 0) ? 17 : 13;
+      if (c->opt_gemm_big && c->opt_gemm_bn == 0 && g->slabs == 1 && g->M >= 256 && g->N >= 256 && g->K % 16 == 0 && g->K >= 32 &&
+          fits(ag, 1, g->M) && fits(bg, 0, g->N) && g->M * g->N * 20 >= rounds * 256 * 65536 * need) {
         g->BX = 256;
         g->UC = 1;
       }

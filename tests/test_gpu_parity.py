@@ -836,6 +836,29 @@ def test_large_matrix_product_every_element(env, K, layout):
         assert np.array_equal(ref, (X.astype(np.float64) @ Y.astype(np.float64)).astype(f32)), "exact in any order"
 
 
+@pytest.mark.parametrize("layout,M,N", [("nn", 4000, 4000), ("tn", 3900, 4092), ("nt", 3999, 4001), ("tt", 4092, 3841), ("nn", 8191, 2048)])
+def test_large_matrix_product_with_ragged_edges(env, layout, M, N):
+    """Edge tiles of the 256 x 256-tile kernel load clamped rows and store only what exists: every element of
+    products of small integers (exact), with a row-vector epilogue that must not be read beyond the edge either."""
+    gr, ctx, torch = env
+    K = 80
+    g = np.random.default_rng(430 + M)
+    X = g.integers(-3, 4, (M, K)).astype(f32)
+    Y = g.integers(-3, 4, (K, N)).astype(f32)
+    row = g.integers(-5, 6, (N,)).astype(f32)
+    arrays = dict(X=np.ascontiguousarray(X.T) if layout[0] == "t" else X, Y=np.ascontiguousarray(Y.T) if layout[1] == "t" else Y, row=row)
+    prog = lambda xp, X, Y, row: (X.T if layout[0] == "t" else X) @ (Y.T if layout[1] == "t" else Y) + row
+    dev, keep = to_dev(torch, ctx, arrays)
+    assert "tile=256x256" in prog(gr, **dev).plan()
+    # the result goes into the middle of a larger buffer: nothing around it may change
+    buf = torch.full((M * N + 8192,), -77.0, device="cuda")
+    prog(gr, **dev).materialize_into(buf[4096:4096 + M * N].view(M, N))
+    ctx.sync()
+    ref = prog(ora, **{k: ora.array(v) for k, v in arrays.items()}).numpy()
+    assert np.array_equal(buf[4096:4096 + M * N].view(M, N).cpu().numpy(), ref)
+    assert bool((buf[:4096] == -77.0).all()) and bool((buf[4096 + M * N:] == -77.0).all())
+
+
 def test_large_matrix_product_windows_epilogues_and_long_k(env):
     gr, ctx, torch = env
     g = np.random.default_rng(411)
