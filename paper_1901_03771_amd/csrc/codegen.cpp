@@ -1854,19 +1854,21 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   // block i of a k-contiguous left operand holds rows wm + 32 i + rr, of a row-contiguous one rows wm + 4 rr + i; block j
   // of a row-contiguous right operand holds column wn + 4 (lane % 32) + j (a lane's four results are neighbours: one
   // 16-byte store), of a k-contiguous one column wn + 32 j + lane % 32
+  // Results beyond the edges of the matrix are computed like the others, from operands read at the clamped position,
+  // and not stored (no branch around the epilogue: sixty-four guarded copies of a large one made the register
+  // allocator spill).
   o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n"
        "#pragma unroll\n  for (int i = 0; i < 4; ++i)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
        "      const int rr = 8 * (q / 4) + 4 * lh + (q % 4);\n"
-       "      const long long row = bm0 + wm + " << (ops[0].kc ? "32 * i + rr" : "4 * rr + i") << ";\n"
+       "      const long long row_at = bm0 + wm + " << (ops[0].kc ? "32 * i + rr" : "4 * rr + i") << ", row = row_at < M ? row_at : M - 1;\n"
        "      f4 ov;\n"
        "#pragma unroll\n      for (int j = 0; j < 4; ++j) {\n"
-       "        const long long col = bn0 + wn + " << (ops[1].kc ? "32 * j + l32" : "4 * l32 + j") << ";\n"
-       "        if (row < M && col < N) {\n"
+       "        const long long col_at = bn0 + wn + " << (ops[1].kc ? "32 * j + l32" : "4 * l32 + j") << ", col = col_at < N ? col_at : N - 1;\n"
        "        const float cacc = acc[i][j][q];\n";
   emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
-  if (ops[1].kc) o << "        out[row * N + col] = t" << g.results[0] << ";\n        }\n      }\n      (void)ov;\n    }\n}\n";
-  else o << "        ov[j] = t" << g.results[0] << ";\n        }\n      }\n"
-            "      if (row < M && bn0 + wn + 4 * l32 < N) *(GM f4u*)(out + row * N + bn0 + wn + 4 * l32) = ov;\n    }\n}\n";
+  if (ops[1].kc) o << "        if (row_at < M && col_at < N) out[row * N + col] = t" << g.results[0] << ";\n      }\n      (void)ov;\n    }\n}\n";
+  else o << "        ov[j] = t" << g.results[0] << ";\n      }\n"
+            "      if (row_at < M && bn0 + wn + 4 * l32 < N) *(GM f4u*)(out + row * N + bn0 + wn + 4 * l32) = ov;\n    }\n}\n";
 }
 
 
