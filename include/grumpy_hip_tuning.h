@@ -31,10 +31,11 @@ extern "C" {
  *   "gemm_kstep"      values of k per step of the matrix-product kernel's main loop (one barrier per
  *                     step): 16 (default), 32
  *   "gemm_big"        1 (default) = matrix products whose operands are each contiguous along one of their
- *                     dimensions, with K a multiple of 16 and a result that fills at least 85 % (65 % if M or
- *                     N is not a multiple of 128) of its rounds of 256 x 256 tiles over the 256 compute units,
- *                     use the kernel with one workgroup per tile whose operand tiles go from global memory
- *                     straight into LDS; 0 = the 128-wide kernel for every product
+ *                     dimensions, with K a multiple of 16 and no split of K, use the kernels whose operand
+ *                     tiles go from global memory straight into LDS: 256 x 256 tiles, one workgroup per
+ *                     compute unit, where the result fills at least 85 % (65 % if M or N is not a multiple
+ *                     of 128) of its rounds over the 256 compute units, else 128 x 128 tiles; 0 = the kernel
+ *                     that stages tiles through registers for every product
  *   "nontemporal"     1 (default) = loads of arrays that are read once carry the non-temporal hint,
  *                     and so do the vector stores of a requested value of 192 MiB or more (not of
  *                     intermediate results of the request; except in kernels that read a transposed

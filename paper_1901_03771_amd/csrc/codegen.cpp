@@ -1723,64 +1723,76 @@ void gemm_combine(Em& e, const EpiLoad& epi_load);
 // tracked by hand: vmcnt(8) before a step's barrier leaves only the eight loads of the newest tile in flight.
 void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   const GroupPlan& g = e.g;
-  // An operand is either "k-contiguous" (kc: its tile is 256 rows of 16 k values, 16-byte chunks swizzled, a lane's
+  const int NB = g.BX / 64;          // matrix-core blocks per wave along each dimension: 4 (256 x 256 tiles) or 2 (128 x 128)
+  const int T = 64 * NB, G = NB * NB, P = 2 * NB;   // tile edge, matrix instructions per group, direct loads per wave and step
+  // An operand is either "k-contiguous" (kc: its tile is T rows of 16 k values, 16-byte chunks swizzled, a lane's
   // 16-byte read holds four k of one row and serves four matrix instructions) or "row-contiguous" (its tile is 16 k
-  // rows of 256 values at a pitch of 264, a lane's read holds one k of four neighbouring rows = its four blocks).
+  // rows of T values, a lane's read holds one k of NB neighbouring rows = its NB blocks).  Row-contiguous tiles of 256
+  // values have a pitch of 264 floats (one row per load instruction); those of 128 values lie in pairs of rows (one
+  // pair per load instruction) at a pitch of 272 per pair: rows four apart are 32 banks apart either way.
   struct Op { bool kc; const char* n; const char* ld; const char* org; const char* lim; int part; int size; };
   const bool akc = g.groups[g.mat_group].coef[1] == 1, bkc = g.groups[g.vec_group].coef[1] != 1;
-  const int KC = 4096, RC = 16 * 264;
+  const int KC = T * 16, RC = NB == 4 ? 16 * 264 : 8 * 272;
   Op ops[2] = {{akc, "a", akc ? "am" : "ak", "bm0", "M", 0, akc ? KC : RC}, {bkc, "b", bkc ? "bn" : "bk", "bn0", "N", akc ? KC : RC, bkc ? KC : RC}};
   const int STAGE = ops[0].size + ops[1].size;   // floats
+  auto rc_row = [&](int k) { return NB == 4 ? k * 264 : (k >> 1) * 272 + (k & 1) * 128; };   // offset of k row k of a row-contiguous tile (k without the half-wave's 4 h)
+  const char* RV = NB == 4 ? "f4" : "gr_f2";      // what a lane reads of a row-contiguous tile per k
   std::ostream& o = e.o;
   o << "  __shared__ __attribute__((aligned(16))) float gr_lds[" << 3 * STAGE << "];\n"
        "  typedef __attribute__((address_space(3))) float lfloat;\n"
        "  typedef __attribute__((address_space(3))) f4 lf4;\n"
+       "  typedef float gr_f2 __attribute__((ext_vector_type(2)));\n"
+       "  typedef gr_f2 gr_f2u __attribute__((aligned(4)));\n"
+       "  typedef __attribute__((address_space(3))) gr_f2 lgr_f2;\n"
        "  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;\n"
-       "  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;\n"
-       "  const long long tiles_n = (N + 255) / 256;\n"
-       "  const long long bm0 = (blockIdx.x / tiles_n) * 256, bn0 = (blockIdx.x % tiles_n) * 256;\n"
-       "  f16v acc[4][4];\n"
-       "  for (int i = 0; i < 4; ++i) for (int j = 0; j < 4; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n"
+       "  const int wm = (wave >> 1) * " << 32 * NB << ", wn = (wave & 1) * " << 32 * NB << ";\n"
+       "  const long long tiles_n = (N + " << T - 1 << ") / " << T << ";\n"
+       "  const long long bm0 = (blockIdx.x / tiles_n) * " << T << ", bn0 = (blockIdx.x % tiles_n) * " << T << ";\n"
+       "  f16v acc[" << NB << "][" << NB << "];\n"
+       "  for (int i = 0; i < " << NB << "; ++i) for (int j = 0; j < " << NB << "; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n"
        "  const unsigned wv = __builtin_amdgcn_readfirstlane(wave);\n"
        "  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) void*)gr_lds;\n";
   for (const Op& x : ops) {
     const std::string n = x.n, w0 = x.n[0] == 'a' ? "wm" : "wn", X = x.n[0] == 'a' ? "A" : "B";
     // direct loads: a uniform base (advanced every step; made visibly uniform, the operands of the loads must be scalar
     // registers) plus a 32-bit byte offset per lane and piece
-    o << "  unsigned " << n << "off[4];\n#pragma unroll\n";
+    o << "  unsigned " << n << "off[" << NB << "];\n#pragma unroll\n";
     if (x.kc)
       // (rows beyond the operand's edge read its last row: their results are never stored)
-      o << "  for (int p = 0; p < 4; ++p) { const int m = 16 * (4 * wave + p) + lane / 4, c = (lane % 4) ^ ((m >> 2) & 3); const long long last = " << x.lim << " - 1 - " << x.org
+      o << "  for (int p = 0; p < " << NB << "; ++p) { const int m = 16 * (" << NB << " * wave + p) + lane / 4, c = (lane % 4) ^ ((m >> 2) & 3); const long long last = " << x.lim << " - 1 - " << x.org
         << "; " << n << "off[p] = 4u * (unsigned)((m < last ? m : last) * " << x.ld << " + 4 * c); }\n"
            "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << " * " << x.ld << ");\n"
            "  const unsigned long long " << n << "step = 64ull;\n";
-    else
+    else {
       // (groups of four beyond the operand's edge, whose extent is a multiple of four, read its last group)
-      o << "  for (int p = 0; p < 4; ++p) { const long long last = " << x.lim << " - 4 - " << x.org << "; " << n << "off[p] = 4u * (unsigned)((4 * wave + p) * " << x.ld << " + (4 * lane < last ? 4 * lane : last)); }\n"
-           "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << ");\n"
+      if (NB == 4) o << "  for (int p = 0; p < 4; ++p) { const long long last = " << x.lim << " - 4 - " << x.org << "; " << n << "off[p] = 4u * (unsigned)((4 * wave + p) * " << x.ld << " + (4 * lane < last ? 4 * lane : last)); }\n";
+      else o << "  for (int p = 0; p < 2; ++p) { const long long last = " << x.lim << " - 4 - " << x.org << "; " << n << "off[p] = 4u * (unsigned)((2 * (2 * wave + p) + lane / 32) * " << x.ld << " + (4 * l32 < last ? 4 * l32 : last)); }\n";
+      o << "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << ");\n"
            "  const unsigned long long " << n << "step = 64ull * (unsigned long long)__builtin_amdgcn_readfirstlane((int)" << x.ld << ");\n";
+    }
+    const int wave_bytes = x.kc ? 1024 * NB : (NB == 4 ? 4 * 264 * 4 : 4 * 272 * 2);
     o << "  unsigned long long " << n << "base = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(" << n << "64 >> 32)) << 32) | (unsigned)__builtin_amdgcn_readfirstlane((int)" << n << "64);\n"
-         "  unsigned " << n << "lds[3];\n#pragma unroll\n  for (int st = 0; st < 3; ++st) " << n << "lds[st] = lds0 + " << 4 * STAGE << "u * st + " << 4 * x.part << "u + " << (x.kc ? 4096 : 16 * 264) << "u * wv;\n";
+         "  unsigned " << n << "lds[3];\n#pragma unroll\n  for (int st = 0; st < 3; ++st) " << n << "lds[st] = lds0 + " << 4 * STAGE << "u * st + " << 4 * x.part << "u + " << wave_bytes << "u * wv;\n";
     // LDS read bases of this lane, per stage
     if (x.kc)
       o << "  const lfloat* " << n << "p[3][2];\n#pragma unroll\n  for (int st = 0; st < 3; ++st)\n#pragma unroll\n"
            "    for (int hf = 0; hf < 2; ++hf) " << n << "p[st][hf] = (const lfloat*)gr_lds + st * " << STAGE << " + " << x.part << " + (" << w0 << " + l32) * 16 + 4 * ((2 * hf + lh) ^ ((l32 >> 2) & 3));\n"
-           "  f4 " << n << "F[2][4];\n";
+           "  f4 " << n << "F[2][" << NB << "];\n";
     else
-      o << "  const lfloat* " << n << "p[3];\n#pragma unroll\n  for (int st = 0; st < 3; ++st) " << n << "p[st] = (const lfloat*)gr_lds + st * " << STAGE << " + " << x.part << " + 4 * lh * 264 + " << w0 << " + 4 * l32;\n"
-           "  f4 " << n << "F[2];\n";
+      o << "  const lfloat* " << n << "p[3];\n#pragma unroll\n  for (int st = 0; st < 3; ++st) " << n << "p[st] = (const lfloat*)gr_lds + st * " << STAGE << " + " << x.part << " + " << rc_row(4) << " * lh + " << w0 << " + " << NB << " * l32;\n"
+           "  " << RV << " " << n << "F[2];\n";
   }
   o << "  const long long nkt = K / 16;\n";
-  // piece p (0..3: the left tile, 4..7: the right tile) of the tile at the bases into stage st
+  // piece p (0 .. NB - 1: the left tile, NB .. 2 NB - 1: the right tile) of the tile at the bases into the stage in role st
   auto piece = [&](int st, int p, const char* ind) {
-    const Op& x = ops[p / 4];
-    const int imm = (x.kc ? 1024 : 4 * 264) * (p % 4);
+    const Op& x = ops[p / NB];
+    const int imm = (x.kc ? 1024 : (NB == 4 ? 4 * 264 : 4 * 272)) * (p % NB);
     o << ind << "asm volatile(\"s_add_i32 m0, %2, " << imm << "\\n\\ts_nop 0\\n\\tglobal_load_lds_dwordx4 %0, %1\" : : \"v\"("
-      << x.n << "off[" << p % 4 << "]), \"s\"(" << x.n << "base), \"s\"(" << x.n << "lds[" << st << "]) : \"memory\");\n";
+      << x.n << "off[" << p % NB << "]), \"s\"(" << x.n << "base), \"s\"(" << x.n << "lds[" << st << "]) : \"memory\");\n";
   };
   const char* ADV = "abase += astep; bbase += bstep;\n";
   const char* SB = "__builtin_amdgcn_sched_barrier(0);\n";
-  // operand of matrix instruction (group s of the step, block i) and the LDS reads that provide it
+  // operand of a matrix instruction (group s of the step, block blk) and the LDS reads that provide it
   auto val = [&](const Op& x, int s, int blk) {
     std::ostringstream v;
     if (x.kc) v << x.n << "F[" << (s >> 2) << "][" << blk << "][" << (s & 3) << "]";
@@ -1791,32 +1803,33 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
     o << ind << x.n << "F[" << hf << "][" << blk << "] = *(const lf4*)(" << x.n << "p[" << st << "][" << hf << "] + " << blk * 512 << ");\n";
   };
   auto read_rc = [&](const Op& x, int st, int s, const char* ind) {
-    o << ind << x.n << "F[" << (s & 1) << "] = *(const lf4*)(" << x.n << "p[" << st << "] + " << (8 * (s >> 2) + (s & 3)) * 264 << ");\n";
+    o << ind << x.n << "F[" << (s & 1) << "] = *(const l" << RV << "*)(" << x.n << "p[" << st << "] + " << rc_row(8 * (s >> 2) + (s & 3)) << ");\n";
   };
-  // one step: stage st holds the current tile; the tile two steps on goes to stage (st + 2) % 3 if more2; the first
-  // operands of the next step are read behind the barrier if more1
-  auto step = [&](int st, bool more2, bool more1, const char* ind) {
-    const int st1 = (st + 1) % 3, st2 = (st + 2) % 3;
+  // One step.  Role 0 is the stage that holds the current tile; the tile two steps on goes to the stage in role 2 if more2;
+  // the first operands of the next step are read (from role 1) behind the barrier if more1.  Every load and LDS read
+  // sits behind a fixed matrix instruction of a fixed group.
+  auto step = [&](bool more2, bool more1, const char* ind) {
     for (int s = 0; s < 8; ++s) {
       if (s == 7)
-        // the next tile has landed (all but the newest eight loads are complete) and this wave's reads of the current one are done
-        o << ind << "__builtin_amdgcn_s_waitcnt(" << (more2 ? 0x0070 | 8 : 0x0070) << ");\n" << ind << "__builtin_amdgcn_s_barrier();\n";
-      for (int q = 0; q < 16; ++q) {
-        const int i = q >> 2, j = q & 3;
+        // the next tile has landed (all but the newest P loads are complete) and this wave's reads of the current one are done
+        o << ind << "__builtin_amdgcn_s_waitcnt(" << (more2 ? 0x0070 | P : 0x0070) << ");\n" << ind << "__builtin_amdgcn_s_barrier();\n";
+      for (int q = 0; q < G; ++q) {
+        const int i = q / NB, j = q % NB;
         o << ind << SB << ind << "acc[" << i << "][" << j << "] = __builtin_amdgcn_mfma_f32_32x32x2f32(" << val(ops[0], s, i) << ", " << val(ops[1], s, j)
           << ", acc[" << i << "][" << j << "], 0, 0, 0);\n" << ind << SB;
-        if (more2 && q == 1 && s < 7) piece(st2, s, ind);
-        if (more2 && s == 6 && q == 9) { piece(st2, 7, ind); o << ind << ADV; }
+        if (more2 && q == 1 && s < P && s < 7) piece(2, s, ind);
+        if (more2 && NB == 4 && s == 6 && q == 9) piece(2, 7, ind);
+        if (more2 && s == (NB == 4 ? 6 : 3) && q == (NB == 4 ? 9 : 1)) o << ind << ADV;
         for (int k = 0; k < 2; ++k) {
           const Op& x = ops[k];
           if (x.kc) {
-            // second half of the step: four reads behind matrix instructions 8..11 (left) / 12..15 (right) of group 1;
-            // first half of the next step: behind 0..3 / 5..8 of group 7
-            if (s == 1 && q >= 8 + 4 * k && q < 12 + 4 * k) read_kc(x, st, 1, q - 8 - 4 * k, ind);
-            if (s == 7 && more1 && q >= 5 * k && q < 4 + 5 * k) read_kc(x, st1, 0, q - 5 * k, ind);
+            // second half of the step: behind the last NB matrix instructions of group 1 (left) / 2 (right);
+            // first half of the next step: behind the first 2 NB of group 7
+            if (s == 1 + k && q >= G - NB) read_kc(x, 0, 1, q - (G - NB), ind);
+            if (s == 7 && more1 && q >= NB * k && q < NB + NB * k) read_kc(x, 1, 0, q - NB * k, ind);
           } else {
-            if (s < 7 && q == 4 + 2 * k) read_rc(x, st, s + 1, ind);
-            if (s == 7 && more1 && q == 4 + 5 * k) read_rc(x, st1, 0, ind);
+            if (s < 7 && q == NB + k) read_rc(x, 0, s + 1, ind);
+            if (s == 7 && more1 && q == NB + k) read_rc(x, 1, 0, ind);
           }
         }
       }
@@ -1824,16 +1837,16 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   };
   // prologue: tiles 0 and 1 (K >= 32)
   for (int t = 0; t < 2; ++t) {
-    for (int p = 0; p < 8; ++p) piece(t, p, "  ");
+    for (int p = 0; p < P; ++p) piece(t, p, "  ");
     o << "  " << ADV;
   }
-  o << "  __builtin_amdgcn_s_waitcnt(" << (0x0F70 | 8) << ");\n  __builtin_amdgcn_s_barrier();\n";
+  o << "  __builtin_amdgcn_s_waitcnt(" << (0x0F70 | P) << ");\n  __builtin_amdgcn_s_barrier();\n";
   for (const Op& x : ops) {
-    if (x.kc) for (int blk = 0; blk < 4; ++blk) read_kc(x, 0, 0, blk, "  ");
+    if (x.kc) for (int blk = 0; blk < NB; ++blk) read_kc(x, 0, 0, blk, "  ");
     else read_rc(x, 0, 0, "  ");
   }
   // the stages rotate through three roles (0: the tile of this step, 1: of the next one, 2: the target of this step's
-  // loads): the addresses are exchanged after every step, a handful of register moves per 128 matrix instructions
+  // loads): the addresses are exchanged after every step, a handful of register moves per step
   std::ostringstream rot;
   for (const Op& x : ops) {
     rot << "{ const unsigned t = " << x.n << "lds[0]; " << x.n << "lds[0] = " << x.n << "lds[1]; " << x.n << "lds[1] = " << x.n << "lds[2]; " << x.n << "lds[2] = t; }\n";
@@ -1844,31 +1857,31 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   }
   o << "  long long kt = 0;\n"
        "  for (; kt + 2 < nkt; ++kt) {\n";
-  step(0, true, true, "    ");
+  step(true, true, "    ");
   o << "    " << rot.str() << "  }\n"
        "  // the last two steps load nothing\n";
-  step(0, false, true, "  ");
+  step(false, true, "  ");
   o << "  " << rot.str();
-  step(0, false, false, "  ");
+  step(false, false, "  ");
   // epilogue on the accumulators: element q of a block is its row rr = 8 (q / 4) + 4 (lane / 32) + q % 4 and column lane % 32;
-  // block i of a k-contiguous left operand holds rows wm + 32 i + rr, of a row-contiguous one rows wm + 4 rr + i; block j
-  // of a row-contiguous right operand holds column wn + 4 (lane % 32) + j (a lane's four results are neighbours: one
-  // 16-byte store), of a k-contiguous one column wn + 32 j + lane % 32
+  // block i of a k-contiguous left operand holds rows wm + 32 i + rr, of a row-contiguous one rows wm + NB rr + i; block j
+  // of a row-contiguous right operand holds column wn + NB (lane % 32) + j (a lane's NB results are neighbours: one
+  // vector store), of a k-contiguous one column wn + 32 j + lane % 32.
   // Results beyond the edges of the matrix are computed like the others, from operands read at the clamped position,
   // and not stored (no branch around the epilogue: sixty-four guarded copies of a large one made the register
   // allocator spill).
   o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n"
-       "#pragma unroll\n  for (int i = 0; i < 4; ++i)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
+       "#pragma unroll\n  for (int i = 0; i < " << NB << "; ++i)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
        "      const int rr = 8 * (q / 4) + 4 * lh + (q % 4);\n"
-       "      const long long row_at = bm0 + wm + " << (ops[0].kc ? "32 * i + rr" : "4 * rr + i") << ", row = row_at < M ? row_at : M - 1;\n"
-       "      f4 ov;\n"
-       "#pragma unroll\n      for (int j = 0; j < 4; ++j) {\n"
-       "        const long long col_at = bn0 + wn + " << (ops[1].kc ? "32 * j + l32" : "4 * l32 + j") << ", col = col_at < N ? col_at : N - 1;\n"
+       "      const long long row_at = bm0 + wm + " << (ops[0].kc ? "32 * i + rr" : std::to_string(NB) + " * rr + i") << ", row = row_at < M ? row_at : M - 1;\n"
+       "      " << RV << " ov;\n"
+       "#pragma unroll\n      for (int j = 0; j < " << NB << "; ++j) {\n"
+       "        const long long col_at = bn0 + wn + " << (ops[1].kc ? "32 * j + l32" : std::to_string(NB) + " * l32 + j") << ", col = col_at < N ? col_at : N - 1;\n"
        "        const float cacc = acc[i][j][q];\n";
   emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
   if (ops[1].kc) o << "        if (row_at < M && col_at < N) out[row * N + col] = t" << g.results[0] << ";\n      }\n      (void)ov;\n    }\n}\n";
   else o << "        ov[j] = t" << g.results[0] << ";\n      }\n"
-            "      if (row_at < M && bn0 + wn + 4 * l32 < N) *(GM f4u*)(out + row * N + bn0 + wn + 4 * l32) = ov;\n    }\n}\n";
+            "      if (row_at < M && bn0 + wn + " << NB << " * l32 < N) *(GM " << RV << "u*)(out + row * N + bn0 + wn + " << NB << " * l32) = ov;\n    }\n}\n";
 }
 
 
@@ -1919,7 +1932,7 @@ void gen_gemm(Em& e) {
     return s2.str();
   };
   auto emit_combine = [&]() { gemm_combine(e, epi_load); };
-  if (g.BX == 256) {
+  if (g.VR == 2) {   // tiles loaded straight into LDS
     gemm_big_body(e, epi_load);
     emit_combine();
     return;

@@ -69,7 +69,7 @@ struct gr_ctx {
   int64_t opt_scan_threads = 0, opt_scan_min_threads = 0;
   int64_t opt_scan_one_pass = 1;
   int64_t opt_gemm_kstep = 0;
-  int64_t opt_gemm_big = 1;     // large matrix products in natural layouts: 256 x 256 tiles loaded straight into LDS
+  int64_t opt_gemm_big = 1;     // matrix products of operands contiguous along one dimension: tiles loaded straight into LDS
   int64_t opt_map_phase = 1;
   int64_t opt_scan_polls = 1 << 20;   // polls a tile of a one-pass scan spends on each wait before it recomputes its offset
   uint64_t options_epoch = 0;  // bumped by every gr_ctx_set_option: part of a request's fingerprint

@@ -946,16 +946,24 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
         if (x.structural_zero[0] || x.structural_zero[1]) return false;
         const int64_t sk = x.coef[kdim], so = x.coef[1 - kdim];
         if (sk == 1 && so != 1) return so >= 16 && so < ((int64_t)1 << 21);
-        if (so == 1 && sk != 1) return sk >= 256 && sk < ((int64_t)1 << 24) && other % 4 == 0;
+        if (so == 1 && sk != 1) return sk >= 128 && sk < ((int64_t)1 << 24) && other % 4 == 0;
         return false;
       };
       // Edge tiles are whole tiles of work: the result must fill 85 % of its rounds over the 256 compute units, 65 %
       // where M or N is not a multiple of 128 (the 128-wide kernel's guarded edge tiles make it slower there; measured
       // on 4000^3: 136 against 97 TFLOP/s, 8000^3: 144 against 114, 10000 x 4096 x 10000, seven rounds 85 % full: 126 against 117).
       const int64_t need = (g->M % 128 == 0 && g->N % 128 == 0) ? 17 : 13;
-      if (c->opt_gemm_big && c->opt_gemm_bn == 0 && g->slabs == 1 && g->M >= 256 && g->N >= 256 && g->K % 16 == 0 && g->K >= 32 &&
-          fits(ag, 1, g->M) && fits(bg, 0, g->N) && g->M * g->N * 20 >= rounds * 256 * 65536 * need) {
+      const bool direct = c->opt_gemm_big && c->opt_gemm_bn == 0 && g->slabs == 1 && g->K % 16 == 0 && g->K >= 32 && fits(ag, 1, g->M) && fits(bg, 0, g->N);
+      if (direct && g->M >= 256 && g->N >= 256 && g->M * g->N * 20 >= rounds * 256 * 65536 * need) {
         g->BX = 256;
+        g->VR = 2;   // (marks the kernels whose tiles go straight into LDS)
+        g->UC = 1;
+      } else if (direct && g->BX == 128 && g->M >= 128 && g->N >= 128) {
+        // the same kernel with 128 x 128 tiles (up to three workgroups per compute unit) where the large tiles would
+        // leave compute units idle: tiles are distributed like those of the 128-wide kernel, which it beats wherever
+        // it applies (measured: 2048^3 114 against 101 TFLOP/s, 3072^3 110 against 97, 4096 x 4096 x 2048 142 against 124,
+        // 2000^3 124 against 62, 4100 x 4096 x 4000 115 against 84)
+        g->VR = 2;
         g->UC = 1;
       }
     }
@@ -1439,7 +1447,7 @@ std::string describe_plan(const Plan& plan) {
     first = true;
     for (const Node* n : g.leaves) { s << (first ? "" : ",") << n->id; first = false; }
     s << "] loads=" << [&] { int k = 0; for (const Instr& in : (g.kind == GroupKind::MAP ? g.prog1 : g.prog)) if (in.kind == IKind::LOAD) ++k; return k; }();
-    if (g.kind == GroupKind::GEMM) s << " M=" << g.M << " N=" << g.N << " K=" << g.K << " tile=" << (g.BX == 256 ? 256 : 128) << "x" << g.BX;
+    if (g.kind == GroupKind::GEMM) s << " M=" << g.M << " N=" << g.N << " K=" << g.K << " tile=" << (g.BX == 256 ? 256 : 128) << "x" << g.BX << (g.VR == 2 ? " direct" : "");
     if (g.kind == GroupKind::GEMV) s << " mode=" << (g.gemv_mode == 2 ? "row-dot+column-accumulate" : (g.gemv_mode ? "column-accumulate" : "row-dot")) << " M=" << g.M << " K=" << g.K;
     if (g.pair) {
       s << " fused-with=[root=" << g.pair->root->id << " members=[";

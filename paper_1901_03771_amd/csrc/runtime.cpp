@@ -629,8 +629,8 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       s[L.extra + 1] = (uint64_t)g.N;
       s[L.extra + 2] = (uint64_t)g.K;
       const int64_t bn = g.BX == 32 ? 32 : 128;
-      // (BX = 256: the kernel for large products, one workgroup per 256 x 256 tile)
-      const int64_t tiles = g.BX == 256 ? ((g.M + 255) / 256) * ((g.N + 255) / 256) : ((g.M + 127) / 128) * ((g.N + bn - 1) / bn);
+      // (VR = 2: the kernels whose tiles go straight into LDS, one workgroup per BX x BX tile)
+      const int64_t tiles = g.VR == 2 ? ((g.M + g.BX - 1) / g.BX) * ((g.N + g.BX - 1) / g.BX) : ((g.M + 127) / 128) * ((g.N + bn - 1) / bn);
       const int64_t nsplit = std::max(1, g.slabs);
       // k extent of one split: a multiple of 32 (the longer of the two k steps) that covers K in nsplit pieces
       const int64_t kch = nsplit > 1 ? (((g.K + nsplit - 1) / nsplit + 31) / 32) * 32 : g.K;

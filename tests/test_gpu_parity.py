@@ -859,6 +859,27 @@ def test_large_matrix_product_with_ragged_edges(env, layout, M, N):
     assert bool((buf[:4096] == -77.0).all()) and bool((buf[4096 + M * N:] == -77.0).all())
 
 
+@pytest.mark.parametrize("layout,M,N,K", [("nn", 2048, 2048, 32), ("tn", 2048, 2048, 48), ("nt", 2048, 2048, 64), ("tt", 2048, 2048, 80),
+                                          ("nn", 1900, 2100, 112), ("tn", 2100, 1900, 32), ("nt", 1901, 2099, 48), ("tt", 2100, 1901, 64)])
+def test_matrix_product_with_128_wide_tiles_loaded_straight_into_lds(env, layout, M, N, K):
+    """The direct-to-LDS kernel with 128 x 128 tiles (products too small for 256 x 256 ones), small integers, every element."""
+    gr, ctx, torch = env
+    g = np.random.default_rng(450 + M + K)
+    X = g.integers(-3, 4, (M, K)).astype(f32)
+    Y = g.integers(-3, 4, (K, N)).astype(f32)
+    colv = g.integers(-5, 6, (M, 1)).astype(f32)
+    arrays = dict(X=np.ascontiguousarray(X.T) if layout[0] == "t" else X, Y=np.ascontiguousarray(Y.T) if layout[1] == "t" else Y, colv=colv)
+    prog = lambda xp, X, Y, colv: (X.T if layout[0] == "t" else X) @ (Y.T if layout[1] == "t" else Y) - colv
+    dev, keep = to_dev(torch, ctx, arrays)
+    assert "tile=128x128 direct" in prog(gr, **dev).plan()
+    buf = torch.full((M * N + 8192,), -77.0, device="cuda")
+    prog(gr, **dev).materialize_into(buf[4096:4096 + M * N].view(M, N))
+    ctx.sync()
+    ref = prog(ora, **{k: ora.array(v) for k, v in arrays.items()}).numpy()
+    assert np.array_equal(buf[4096:4096 + M * N].view(M, N).cpu().numpy(), ref)
+    assert bool((buf[:4096] == -77.0).all()) and bool((buf[4096 + M * N:] == -77.0).all())
+
+
 def test_large_matrix_product_windows_epilogues_and_long_k(env):
     gr, ctx, torch = env
     g = np.random.default_rng(411)
