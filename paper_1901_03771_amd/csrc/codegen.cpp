@@ -1787,10 +1787,25 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   auto piece = [&](int st, int p, const char* ind) {
     const Op& x = ops[p / NB];
     const int imm = (x.kc ? 1024 : (NB == 4 ? 4 * 264 : 4 * 272)) * (p % NB);
-    o << ind << "asm volatile(\"s_add_i32 m0, %2, " << imm << "\\n\\ts_nop 0\\n\\tglobal_load_lds_dwordx4 %0, %1\" : : \"v\"("
-      << x.n << "off[" << p % NB << "]), \"s\"(" << x.n << "base), \"s\"(" << x.n << "lds[" << st << "]) : \"memory\");\n";
+    // The statement must not touch the scalar condition code: the compiler splits its own 64-bit additions (s_add_u32 ..
+    // s_addc_u32) around it, so M0 is set with a move of a sum the compiler formed (an s_add_i32 here once corrupted the
+    // carry of a base address: a memory fault).  The wait states cover what the compiler's hazard handling does not see
+    // inside an asm statement: M0 written by a scalar instruction needs one before the load, a base address that a vector
+    // instruction such as v_readfirstlane wrote needs five.
+    o << ind << "asm volatile(\"s_mov_b32 m0, %2\\n\\ts_nop 4\\n\\tglobal_load_lds_dwordx4 %0, %1\" : : \"v\"("
+      << x.n << "off[" << p % NB << "]), \"s\"(" << x.n << "base), \"s\"(" << x.n << "lds[" << st << "] + " << imm << "u) : \"memory\", \"m0\");\n";
   };
-  const char* ADV = "abase += astep; bbase += bstep;\n";
+  // With 128 x 128 tiles every workgroup starts its walk along k at a different step and wraps around: workgroups
+  // that run at the same time then read different columns of the left and rows of the right operand, which matters
+  // for row strides that are large powers of two (2048^3: 120 -> 131 TFLOP/s; rows padded by 64 bytes gave 132 without
+  // it; the 256 x 256-tile kernel showed no such effect).  Every product is still formed once, in an order that
+  // depends only on the tile.
+  const bool rotate_k = NB != 4 && !getenv("GR_NOROT");
+  const char* ADV = !rotate_k ? "abase += astep; bbase += bstep;\n"
+                            : "abase += astep; bbase += bstep; if (++kpos == nkt) { kpos = 0; abase -= astep * (unsigned long long)nkt; bbase -= bstep * (unsigned long long)nkt; }\n";
+  if (rotate_k)
+    o << "  long long kpos = (long long)((blockIdx.x * 5u) % (unsigned long long)nkt);\n"
+         "  abase += astep * (unsigned long long)kpos; bbase += bstep * (unsigned long long)kpos;\n";
   const char* SB = "__builtin_amdgcn_sched_barrier(0);\n";
   // operand of a matrix instruction (group s of the step, block blk) and the LDS reads that provide it
   auto val = [&](const Op& x, int s, int blk) {
