@@ -1795,17 +1795,10 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
     o << ind << "asm volatile(\"s_mov_b32 m0, %2\\n\\ts_nop 4\\n\\tglobal_load_lds_dwordx4 %0, %1\" : : \"v\"("
       << x.n << "off[" << p % NB << "]), \"s\"(" << x.n << "base), \"s\"(" << x.n << "lds[" << st << "] + " << imm << "u) : \"memory\", \"m0\");\n";
   };
-  // With 128 x 128 tiles every workgroup starts its walk along k at a different step and wraps around: workgroups
-  // that run at the same time then read different columns of the left and rows of the right operand, which matters
-  // for row strides that are large powers of two (2048^3: 120 -> 131 TFLOP/s; rows padded by 64 bytes gave 132 without
-  // it; the 256 x 256-tile kernel showed no such effect).  Every product is still formed once, in an order that
-  // depends only on the tile.
-  const bool rotate_k = NB != 4 && !getenv("GR_NOROT");
-  const char* ADV = !rotate_k ? "abase += astep; bbase += bstep;\n"
-                            : "abase += astep; bbase += bstep; if (++kpos == nkt) { kpos = 0; abase -= astep * (unsigned long long)nkt; bbase -= bstep * (unsigned long long)nkt; }\n";
-  if (rotate_k)
-    o << "  long long kpos = (long long)((blockIdx.x * 5u) % (unsigned long long)nkt);\n"
-         "  abase += astep * (unsigned long long)kpos; bbase += bstep * (unsigned long long)kpos;\n";
+  // (Starting every workgroup's walk along k at a different step, so that workgroups running together read
+  // different columns, was measured on 2048^3, whose rows of 8 KiB cost the 128 x 128-tile kernel a tenth against rows
+  // padded by 64 bytes: no change, so the walk starts at zero everywhere.)
+  const char* ADV = "abase += astep; bbase += bstep;\n";
   const char* SB = "__builtin_amdgcn_sched_barrier(0);\n";
   // operand of a matrix instruction (group s of the step, block blk) and the LDS reads that provide it
   auto val = [&](const Op& x, int s, int blk) {

@@ -680,6 +680,21 @@ def test_generated_code_has_no_contraction_or_packed_math(ctx):
     assert "fmaf" not in rest and "__fdividef" not in src and "__expf" not in src
 
 
+def test_asm_statements_of_the_direct_loads_leave_the_condition_code_alone(ctx):
+    # The compiler splits its own 64-bit scalar additions (s_add_u32 .. s_addc_u32) around an asm statement, which
+    # therefore must not write the scalar condition code: the only instructions allowed in one are a move into M0,
+    # wait states and the load itself, and M0 is declared clobbered.
+    import re
+    for out in (ctx.spec((4096, 1024)) @ ctx.spec((1024, 4096)), ctx.spec((1024, 2048)).T @ ctx.spec((2048, 1024)).T + ctx.spec((2048,))):
+        assert "direct" in out.plan()
+        src = out.source(0)
+        stmts = re.findall(r'asm volatile\("([^"]*)"([^;]*);', src)
+        assert len(stmts) >= 12
+        for text, rest in stmts:
+            assert text == r"s_mov_b32 m0, %2\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %0, %1", text
+            assert '"memory", "m0"' in rest
+
+
 def test_generated_kernels_keep_their_values_in_registers(ctx, tmp_path):
     # Large point functions (tanh, erf, exp, log in an epilogue) must not push accumulators or patch values
     # into scratch memory: the kernels are compiled to gfx950 assembly offline and searched for scratch
