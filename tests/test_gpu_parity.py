@@ -880,6 +880,37 @@ def test_matrix_product_with_128_wide_tiles_loaded_straight_into_lds(env, layout
     assert bool((buf[:4096] == -77.0).all()) and bool((buf[4096 + M * N:] == -77.0).all())
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_direct_matrix_products_of_random_shapes(env, seed):
+    """Ten random products per seed, most of them through the kernels that load their tiles straight into LDS: ragged M and N, any of the
+    four layouts, operands that are windows of larger arrays, a bias along either dimension; small integers, every element."""
+    gr, ctx, torch = env
+    g = np.random.default_rng(470 + seed)
+    direct = 0
+    for case in range(10):
+        ta, tb = bool(g.integers(2)), bool(g.integers(2))
+        K = int(g.integers(2, 11)) * 16
+        # a row-contiguous operand needs a multiple of four along its other dimension
+        M = int(g.integers(32, 190)) * 4 if ta else int(g.integers(128, 760))
+        N = int(g.integers(32, 190)) * 4 if not tb else int(g.integers(128, 760))
+        om, ok_, on = (int(v) for v in g.integers(0, 9, 3))
+        XA = g.integers(-3, 4, ((K + ok_ + 3, M + om + 2) if ta else (M + om + 2, K + ok_ + 3))).astype(f32)
+        YB = g.integers(-3, 4, ((N + on + 1, K + ok_ + 5) if tb else (K + ok_ + 5, N + on + 1))).astype(f32)
+        bias = g.integers(-5, 6, (N,) if case % 2 else (M, 1)).astype(f32)
+
+        def prog(xp, XA, YB, bias):
+            A = xp.transpose(XA[ok_:ok_ + K, om:om + M], (1, 0)) if ta else XA[om:om + M, ok_:ok_ + K]
+            B = xp.transpose(YB[on:on + N, ok_:ok_ + K], (1, 0)) if tb else YB[ok_:ok_ + K, on:on + N]
+            return A @ B + bias
+
+        arrays = dict(XA=XA, YB=YB, bias=bias)
+        dev, keep = to_dev(torch, ctx, arrays)
+        direct += "direct" in prog(gr, **dev).plan()
+        got, ref = run_both(env, prog, arrays)
+        assert got.shape == (M, N) and np.array_equal(got, ref), (seed, case, M, N, K, ta, tb)
+    assert direct >= 3, "many of these shapes go to the direct kernels (results whose last 128 columns are mostly empty take 32-wide tiles)"
+
+
 def test_large_matrix_product_windows_epilogues_and_long_k(env):
     gr, ctx, torch = env
     g = np.random.default_rng(411)
