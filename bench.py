@@ -31,7 +31,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # vector instructions x lanes per second: 256 compute units, 64 lanes each, 2.4 GHz
-BLACKSCHOLES_VALU_PER_ELEMENT = 136            # SQ_INSTS_VALU per wave / 1024 elements per wave (profiles/gr_map_blackscholes_pmc.txt)
+BLACKSCHOLES_VALU_PER_ELEMENT = 124            # SQ_INSTS_VALU per wave / 1024 elements per wave (profiles/gr_map_blackscholes_pmc.txt)
 ARGNAMES = {"gemm": ("A", "B"), "cumsum_axis0": ("X",), "cumsum": ("x",), "blackscholes": ("S", "K", "T"), "chain": ("a", "b"), "normalize": ("X", "mu", "sigma", "gamma", "beta"), "softmax": ("X",),
             "stencil": ("I",), "logreg": ("X", "w", "y")}
 # kernel whose launches dominate each workload
@@ -335,15 +335,15 @@ def main():
             extras[label + "_us_per_step"] = round(us, 2)
             rooflines[label] = hbm_roofline(DOMINANT[oname], algorithmic_bytes_per_launch(oname, ow.p), us, blocks, k,
                                             **({"note": "12 MiB working set: resident in L2 / Infinity Cache, bound by launch rate and host work per step, not by HBM"} if small else {}),
-                                            **({"note": "ALU-bound: log, exp, sqrt, two erf and four IEEE divisions per element"} if oname == "blackscholes" else {}))
+                                            **({"note": "ALU-bound: log, exp, sqrt, two erf and four divisions per element"} if oname == "blackscholes" else {}))
             if oname == "blackscholes":
                 # Vector-ALU roofline: one vector instruction per lane and cycle on each of the 64 lanes of a compute
-                # unit (256 CUs at 2.4 GHz; packed FP32 is not used), against the 136 vector instructions per element
+                # unit (256 CUs at 2.4 GHz; packed FP32 is not used), against the 124 vector instructions per element
                 # that rocprofv3 counts for this kernel (profiles/gr_map_blackscholes_pmc.txt: SQ_INSTS_VALU per wave / 1024)
                 ops = BLACKSCHOLES_VALU_PER_ELEMENT * ow.p["n"] / (us * 1e-6) / 1e12
                 rooflines[label + "_alu"] = {"bound": "alu", "kernel": "gr_map", "achieved": round(ops, 2), "peak": VALU_PEAK_TLANEOPS, "unit": "T lane-instructions/s",
                                              "frac": round(ops / VALU_PEAK_TLANEOPS, 4), "valu_instructions_per_element": BLACKSCHOLES_VALU_PER_ELEMENT,
-                                             "note": "instruction count from the committed counter profile, time measured here; transcendental instructions issue at a quarter of the rate, so 100 % is out of reach"}
+                                             "note": "instruction count from the committed counter profile, time measured here; seven of the instructions per element are transcendental"}
             if small:
                 # the same request recorded once and replayed (gr_program_run): launches only
                 extras[label + "_host_wall_us_per_step"] = round(o_wall / k * 1e3, 2)

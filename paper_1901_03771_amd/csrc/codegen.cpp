@@ -133,8 +133,8 @@ struct Em {
     if (dt == GR_F32) switch (op) {
       case GR_NEG: return "(-" + x + ")";
       case GR_ABS: return "__builtin_fabsf(" + x + ")";
-      case GR_EXP: return "expf(" + x + ")";
-      case GR_LOG: return "logf(" + x + ")";
+      case GR_EXP: return "gr_expf(" + x + ")";
+      case GR_LOG: return "gr_logf(" + x + ")";
       case GR_SQRT: return "gr_sqrtf(" + x + ")";
       case GR_SQUARE: return "(" + x + " * " + x + ")";
       case GR_TANH: return "tanhf(" + x + ")";
@@ -208,7 +208,12 @@ void prelude(Em& e) {
          "static __device__ __forceinline__ long long gr_peel(long long& rem, long long d) {\n"
          "  if ((((unsigned long long)rem) | ((unsigned long long)d)) >> 32) { const long long i = rem % d; rem /= d; return i; }\n"
          "  const unsigned r = (unsigned)rem, dd = (unsigned)d, q = r / dd;\n  rem = q;\n  return r - q * dd;\n}\n"
-         "static __device__ __forceinline__ float gr_maxf(float a, float b) { return (a >= b || a != a) ? a : b; }\n"
+         // the math helpers' test for a rare argument somewhere in the wave and the barrier that keeps its
+         // block a branch; straight-line code in matrix-product kernels, whose epilogues run over up to
+         // 256 accumulators per lane and would spill around branches
+         << (e.g.kind == GroupKind::GEMM ? "#define GR_ANY_LANE(c) true\n#define GR_KEEP_BRANCH\n"
+                                         : "#define GR_ANY_LANE(c) (__builtin_amdgcn_ballot_w64(c) != 0ull)\n#define GR_KEEP_BRANCH __builtin_amdgcn_sched_barrier(0)\n")
+         << "static __device__ __forceinline__ float gr_maxf(float a, float b) { return (a >= b || a != a) ? a : b; }\n"
          "static __device__ __forceinline__ float gr_minf(float a, float b) { return (a <= b || a != a) ? a : b; }\n"
          // Correctly rounded square root in five instructions instead of the compiler's sixteen: the
          // hardware's reciprocal square root (1 ulp), then one Newton step on s = x*y with the residual
@@ -216,13 +221,19 @@ void prelude(Em& e) {
          // infinities, NaNs and negative numbers the result has the bits of the IEEE square root (all
          // 2^32 arguments are compared on the device by the test suite); below 2^-96 the residual would
          // underflow, so a wave in which any lane holds such an argument takes the library routine.
+         // Zeros and infinity are put right by a select that only a wave holding an argument outside
+         // [2^-96, inf) executes; other lanes of such a wave keep their value.
          "static __device__ __forceinline__ float gr_sqrtf(float x) {\n"
-         "  const bool tiny = __builtin_fabsf(x) < 0x1p-96f && x != 0.0f;\n"
-         "  if (__builtin_amdgcn_ballot_w64(tiny) != 0ull) return sqrtf(x);\n"
          "  const float y = __builtin_amdgcn_rsqf(x);\n"
          "  const float s = x * y, h = 0.5f * y;\n"
-         "  const float t = __builtin_fmaf(__builtin_fmaf(-s, s, x), h, s);\n"
-         "  return (x == 0.0f || x == __builtin_inff()) ? x : t;\n}\n"
+         "  float t = __builtin_fmaf(__builtin_fmaf(-s, s, x), h, s);\n"
+         "  if (GR_ANY_LANE(!(x >= 0x1p-96f && x < __builtin_inff()))) {\n"
+         "    GR_KEEP_BRANCH;\n"
+         "    const bool tiny = __builtin_fabsf(x) < 0x1p-96f && x != 0.0f;\n"
+         "    if (GR_ANY_LANE(tiny)) return sqrtf(x);\n"
+         "    t = (x == 0.0f || x == __builtin_inff()) ? x : t;\n"
+         "  }\n"
+         "  return t;\n}\n"
          << kDeviceMath << "\n"
          "static __device__ __forceinline__ float gr_xor(float v, int m) { return __shfl_xor(v, m, 64); }\n"
          "static __device__ __forceinline__ int gr_xor(int v, int m) { return __shfl_xor(v, m, 64); }\n"
@@ -1693,6 +1704,34 @@ void gen_gemv_pair(Em& e, Em& e2) {
 
 // ---- GEMM (matrix cores) ----------------------------------------------------------
 
+// The text fn writes to e.o, taken back out of the stream.
+template <class F>
+std::string captured(Em& e, F fn) {
+  const std::string before = e.o.str();
+  e.o.str("");
+  fn();
+  const std::string body = e.o.str();
+  e.o.str(before);
+  e.o.seekp(0, std::ios::end);
+  return body;
+}
+
+// body once per combination of the loop variables, each a constant of its block.  Accumulators are register
+// arrays, so every index into them has to be a constant or the array moves to scratch memory; the loops over them
+// are unrolled here, in the text, because the compiler drops "#pragma unroll" once the unrolled size passes a
+// threshold, which a long epilogue (tanh, erf, exp and log on 256 accumulators) does.
+void emit_unrolled(std::ostream& o, const std::vector<std::pair<const char*, int>>& loops, const std::string& body, const char* ind) {
+  std::vector<int> at(loops.size(), 0);
+  for (;;) {
+    o << ind << "{ constexpr int";
+    for (size_t k = 0; k < loops.size(); ++k) o << (k ? ", " : " ") << loops[k].first << " = " << at[k];
+    o << ";\n" << body << ind << "}\n";
+    size_t k = loops.size();
+    while (k > 0 && ++at[k - 1] == loops[k - 1].second) at[--k] = 0;
+    if (k == 0) return;
+  }
+}
+
 using EpiLoad = std::function<std::string(const Instr&, int)>;
 void gemm_combine(Em& e, const EpiLoad& epi_load);
 
@@ -1878,18 +1917,21 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   // Results beyond the edges of the matrix are computed like the others, from operands read at the clamped position,
   // and not stored (no branch around the epilogue: sixty-four guarded copies of a large one made the register
   // allocator spill).
-  o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n"
-       "#pragma unroll\n  for (int i = 0; i < " << NB << "; ++i)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
-       "      const int rr = 8 * (q / 4) + 4 * lh + (q % 4);\n"
-       "      const long long row_at = bm0 + wm + " << (ops[0].kc ? "32 * i + rr" : std::to_string(NB) + " * rr + i") << ", row = row_at < M ? row_at : M - 1;\n"
-       "      " << RV << " ov;\n"
-       "#pragma unroll\n      for (int j = 0; j < " << NB << "; ++j) {\n"
-       "        const long long col_at = bn0 + wn + " << (ops[1].kc ? "32 * j + l32" : std::to_string(NB) + " * l32 + j") << ", col = col_at < N ? col_at : N - 1;\n"
-       "        const float cacc = acc[i][j][q];\n";
-  emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
-  if (ops[1].kc) o << "        if (row_at < M && col_at < N) out[row * N + col] = t" << g.results[0] << ";\n      }\n      (void)ov;\n    }\n}\n";
-  else o << "        ov[j] = t" << g.results[0] << ";\n      }\n"
-            "      if (row_at < M && bn0 + wn + " << NB << " * l32 < N) *(GM " << RV << "u*)(out + row * N + bn0 + wn + " << NB << " * l32) = ov;\n    }\n}\n";
+  o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
+  const std::string body = captured(e, [&] {
+    o << "      const int rr = 8 * (q / 4) + 4 * lh + (q % 4);\n"
+         "      const long long row_at = bm0 + wm + " << (ops[0].kc ? "32 * i + rr" : std::to_string(NB) + " * rr + i") << ", row = row_at < M ? row_at : M - 1;\n"
+         "      " << RV << " ov;\n"
+         "#pragma unroll\n      for (int j = 0; j < " << NB << "; ++j) {\n"
+         "        const long long col_at = bn0 + wn + " << (ops[1].kc ? "32 * j + l32" : std::to_string(NB) + " * l32 + j") << ", col = col_at < N ? col_at : N - 1;\n"
+         "        const float cacc = acc[i][j][q];\n";
+    emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
+    if (ops[1].kc) o << "        if (row_at < M && col_at < N) out[row * N + col] = t" << g.results[0] << ";\n      }\n      (void)ov;\n";
+    else o << "        ov[j] = t" << g.results[0] << ";\n      }\n"
+              "      if (row_at < M && bn0 + wn + " << NB << " * l32 < N) *(GM " << RV << "u*)(out + row * N + bn0 + wn + " << NB << " * l32) = ov;\n";
+  });
+  emit_unrolled(o, {{"i", NB}, {"q", 16}}, body, "    ");
+  o << "}\n";
 }
 
 
@@ -2088,13 +2130,18 @@ void gen_gemm(Em& e) {
          "#pragma unroll\n    for (int i = 0; i < " << IB << "; ++i)\n#pragma unroll\n    for (int j = 0; j < " << JB << "; ++j)\n#pragma unroll\n      for (int q = 0; q < 16; ++q) {\n"
          "        const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4), col = bn0 + wn + 32 * j + l32;\n"
          "        if (row < M && col < N) ws[row * N + col] = acc[i][j][q];\n      }\n    return;\n  }\n";
-  // (all three loops unrolled: an index of acc that is not a constant would move the accumulators
-  // to scratch memory, which a large epilogue such as tanh otherwise provokes)
-  e.o << "#pragma unroll\n  for (int i = 0; i < " << IB << "; ++i)\n#pragma unroll\n  for (int j = 0; j < " << JB << "; ++j)\n#pragma unroll\n    for (int q = 0; q < 16; ++q) {\n"
-         "      const long long row = bm0 + wm + 32 * i + 8 * (q / 4) + 4 * lh + (q % 4), col = bn0 + wn + 32 * j + l32;\n"
-         "      if (row < M && col < N) {\n        const float cacc = acc[i][j][q];\n";
-  emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
-  e.o << "        out[row * N + col] = t" << g.results[0] << ";\n      }\n    }\n}\n";
+  // (an index of acc that is not a constant would move the accumulators to scratch memory: the loops over blocks
+  // and over groups of four elements are unrolled in the text, the four elements of a group by the compiler)
+  const std::string body = captured(e, [&] {
+    e.o << "#pragma unroll\n      for (int ql = 0; ql < 4; ++ql) {\n"
+           "      const int q = 4 * qh + ql;\n"
+           "      const long long row = bm0 + wm + 32 * i + 8 * qh + 4 * lh + ql, col = bn0 + wn + 32 * j + l32;\n"
+           "      if (row < M && col < N) {\n        const float cacc = acc[i][j][q];\n";
+    emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
+    e.o << "        out[row * N + col] = t" << g.results[0] << ";\n      }\n      }\n";
+  });
+  emit_unrolled(e.o, {{"i", IB}, {"j", JB}, {"qh", 4}}, body, "    ");
+  e.o << "}\n";
   emit_combine();
 }
 

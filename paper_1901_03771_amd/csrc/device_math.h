@@ -25,6 +25,24 @@
 // 2^-80 <= |x| <= 2^80 in every lane of the wave, so that quotient and residuals are normal
 // numbers far from overflow -- the remaining steps are the same multiply and four fused
 // multiply-adds, hence the same correctly rounded quotient.  Any other wave takes x / c.
+//
+// gr_expf(x), gr_logf(x): exponential and natural logarithm in binary32 on the hardware's power of
+// two and binary logarithm (v_exp_f32, v_log_f32, one ulp each), within 2 ulp of the exact value.
+//   exp: x log2(e) as an unevaluated sum p + e (log2(e) split into a binary32 head and tail, the
+//        product's rounding error recovered with a fused multiply-add), n = round(p),
+//        result = 2^((p - n) + e) scaled by 2^n (denormal results come out of the scaling);
+//        0 below ln(2^-150), infinity from ln(2^128 (1 - 2^-25)) on.
+//   log: log2(x) ln(2) with ln(2) as head and tail the same way; denormal arguments are scaled by
+//        2^32 first (the instruction flushes them) and 32 is taken off the binary logarithm;
+//        log(0) = -inf, log(x < 0) = NaN, log(inf) = inf.
+// The selects that serve the rare arguments (a huge |x|, a denormal, zero, a negative number) run
+// only in a wave that holds such an argument: they leave every other lane's value as it is, so a
+// value never depends on its neighbours.  The device library's versions run them for every element.
+// The including file defines the test and the branch: GR_ANY_LANE(c) as "c holds in some lane of
+// the wave" (a ballot) and GR_KEEP_BRANCH as a scheduling barrier, which emits nothing and keeps
+// the compiler from turning a short conditional block back into unconditional selects; a kernel
+// that wants straight-line code (the epilogue of a matrix product over hundreds of accumulators,
+// where branches cost registers) defines them as true and as nothing.
 GR_DEVICE_MATH_SOURCE(
 static __device__ __forceinline__ float gr_erff(float x) {
   const float a = __builtin_fabsf(x);
@@ -45,6 +63,31 @@ static __device__ __forceinline__ float gr_erff(float x) {
   q = __builtin_fmaf(q, ac, -0x1.a0cd3cp+0f);
   const float large = __builtin_copysignf(1.0f - __builtin_amdgcn_exp2f(q * ac), x);
   return a >= 0.75f ? large : small;
+}
+static __device__ __forceinline__ float gr_expf(float x) {
+  const float p = x * 0x1.715476p+0f;
+  const float e = __builtin_fmaf(x, 0x1.4ae0cp-26f, __builtin_fmaf(x, 0x1.715476p+0f, -p));
+  const float n = __builtin_rintf(p);
+  float r = __builtin_ldexpf(__builtin_amdgcn_exp2f((p - n) + e), (int)n);
+  if (GR_ANY_LANE(!(__builtin_fabsf(x) <= 87.0f))) {
+    GR_KEEP_BRANCH;
+    r = x < -0x1.9fe368p+6f ? 0.0f : r;
+    r = x > 0x1.62e42ep+6f ? __builtin_inff() : r;
+  }
+  return r;
+}
+static __device__ __forceinline__ float gr_logf(float x) {
+  if (!GR_ANY_LANE(!__builtin_amdgcn_classf(x, 0x100))) {
+    const float y = __builtin_amdgcn_logf(x);
+    const float p = y * 0x1.62e43p-1f;
+    return p + __builtin_fmaf(y, -0x1.05c61p-29f, __builtin_fmaf(y, 0x1.62e43p-1f, -p));
+  }
+  const bool tiny = x < 0x1p-126f;
+  const float y0 = __builtin_amdgcn_logf(tiny ? x * 0x1p+32f : x);
+  const float y = tiny ? y0 - 32.0f : y0;
+  const float p = y * 0x1.62e43p-1f;
+  const float r = p + __builtin_fmaf(y, -0x1.05c61p-29f, __builtin_fmaf(y, 0x1.62e43p-1f, -p));
+  return __builtin_fabsf(y0) < __builtin_inff() ? r : y0;
 }
 static __device__ __forceinline__ float gr_divc(float x, float c) {
   const unsigned cb = __float_as_uint(c) & 0x7fffffffu;

@@ -14,6 +14,8 @@
 #define GM __attribute__((address_space(1)))
 
 // gr_erff (and gr_divc, which agrees with the division below bit for bit): the text the generated kernels carry
+#define GR_ANY_LANE(c) (__builtin_amdgcn_ballot_w64(c) != 0ull)
+#define GR_KEEP_BRANCH __builtin_amdgcn_sched_barrier(0)
 #define GR_DEVICE_MATH_SOURCE(...) __VA_ARGS__
 #include "device_math.h"
 #undef GR_DEVICE_MATH_SOURCE
@@ -58,8 +60,8 @@ __global__ __launch_bounds__(256) void gr_interp_map_kernel(GrInterpArgs a) {
       switch (op) {
         case GI_FNEG: r = __float_as_uint(-fx); break;
         case GI_FABS: r = __float_as_uint(__builtin_fabsf(fx)); break;
-        case GI_FEXP: r = __float_as_uint(expf(fx)); break;
-        case GI_FLOG: r = __float_as_uint(logf(fx)); break;
+        case GI_FEXP: r = __float_as_uint(gr_expf(fx)); break;
+        case GI_FLOG: r = __float_as_uint(gr_logf(fx)); break;
         case GI_FSQRT: r = __float_as_uint(sqrtf(fx)); break;
         case GI_FSQUARE: r = __float_as_uint(fx * fx); break;
         case GI_FTANH: r = __float_as_uint(tanhf(fx)); break;
@@ -115,8 +117,8 @@ static __device__ __forceinline__ void gi_run(const GrInterpArgs& a, int pc, con
       switch (op) {
         case GI_FNEG: r = __float_as_uint(-fx); break;
         case GI_FABS: r = __float_as_uint(__builtin_fabsf(fx)); break;
-        case GI_FEXP: r = __float_as_uint(expf(fx)); break;
-        case GI_FLOG: r = __float_as_uint(logf(fx)); break;
+        case GI_FEXP: r = __float_as_uint(gr_expf(fx)); break;
+        case GI_FLOG: r = __float_as_uint(gr_logf(fx)); break;
         case GI_FSQRT: r = __float_as_uint(sqrtf(fx)); break;
         case GI_FSQUARE: r = __float_as_uint(fx * fx); break;
         case GI_FTANH: r = __float_as_uint(tanhf(fx)); break;

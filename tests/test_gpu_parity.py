@@ -214,6 +214,76 @@ def test_erf_of_every_float32_below_four(env, env_interp):
     assert got.tolist()[2:] == [1.0, 1.0, 1.0, -1.0] and got[0] == 0 and np.signbit(got[1]) and not np.signbit(got[0])
 
 
+def _ulp_errors_of_a_unary(env, env_interp, fn, ranges, interp_ranges=()):
+    # fn of every bit pattern in ranges [(lo, hi, stride)] on the device against the oracle (binary64, rounded
+    # once): NaN for NaN, infinities and zeros exact, the rest measured in ulp; the worst error is returned.
+    gr, ctx, torch = env
+    worst, at = 0.0, 0
+    for lo, hi, stride in ranges:
+        for c0 in range(lo, hi, stride << 26):
+            bits = np.arange(c0, min(hi, c0 + (stride << 26)), stride, dtype=np.int64).astype(np.uint32)
+            x = bits.view(f32)
+            got = getattr(gr, fn)(ctx.array(torch.from_numpy(x).cuda())).numpy()
+            ref = getattr(ora, fn)(ora.array(x)).numpy()
+            nan = np.isnan(ref)
+            assert np.array_equal(np.isnan(got), nan), f"{fn}: NaN pattern differs in [0x{c0:08x}, ...)"
+            exact = np.isinf(ref) | (ref == 0)
+            assert np.array_equal(got[exact], ref[exact]), f"{fn}: infinities or zeros differ in [0x{c0:08x}, ...)"
+            with np.errstate(invalid="ignore"):
+                err = np.abs(got.astype(np.float64) - ref.astype(np.float64)) / ulp_of(ref)
+            err[nan | exact] = 0
+            if err.max() > worst:
+                worst, at = float(err.max()), int(bits[np.argmax(err)])
+            if (lo, hi, stride) in interp_ranges:
+                gi, ci, _ = env_interp
+                again = getattr(gi, fn)(ci.array(torch.from_numpy(x).cuda())).numpy()
+                assert np.array_equal(again.view(np.uint32), got.view(np.uint32)), f"interpreter and generated kernel disagree on {fn}"
+    return worst, at
+
+
+def _values_do_not_depend_on_the_neighbours(env, fn, x, odd_one):
+    # the same values in waves that hold only ordinary arguments and in waves that each hold a rare one
+    gr, ctx, torch = env
+    alone = getattr(gr, fn)(ctx.array(torch.from_numpy(x).cuda())).numpy()
+    mixed = x.copy()
+    mixed[::37] = odd_one
+    both = getattr(gr, fn)(ctx.array(torch.from_numpy(mixed).cuda())).numpy()
+    keep = np.ones(x.size, bool)
+    keep[::37] = False
+    assert np.array_equal(alone.view(np.uint32)[keep], both.view(np.uint32)[keep]), f"{fn}: a value depends on its neighbours"
+
+
+def test_exp_of_every_float32(env, env_interp):
+    # The generated kernels and the interpreter evaluate exp with a function of their own (the hardware's
+    # power of two on an argument reduced in extended precision).  Against the oracle's exp for every 8th
+    # float32 of magnitude up to 104 (beyond, the result is 0 or infinity), every pattern where the result is
+    # denormal or about to overflow, every 4096th pattern beyond, infinities and NaNs: within 2 ulp, 0 and
+    # infinity exactly where the correctly rounded result is 0 or infinity.
+    top = 0x42D00000                      # 104.0
+    near = [(0x42AD0000, top, 1), (0x80000000 + 0x42AD0000, 0x80000000 + top, 1)]
+    ranges = [(0, 0x42AD0000, 8), (0x80000000, 0x80000000 + 0x42AD0000, 8)] + near + [(top, 1 << 31, 4096), (0x80000000 + top, 1 << 32, 4096)]
+    worst, at = _ulp_errors_of_a_unary(env, env_interp, "exp", ranges, interp_ranges=near)
+    print(f"exp: worst error {worst:.3f} ulp at bits 0x{at:08x}")
+    assert worst <= 2.0, f"exp off by {worst:.2f} ulp at bits 0x{at:08x}"
+    x = np.random.default_rng(5).uniform(-87, 87, 1 << 16).astype(f32)
+    for odd_one in (1000.0, -1000.0, -95.0, np.nan, np.inf):
+        _values_do_not_depend_on_the_neighbours(env, "exp", x, odd_one)
+
+
+def test_log_of_every_float32(env, env_interp):
+    # The same for log (the hardware's binary logarithm times ln 2 in extended precision): every 16th positive
+    # normal float32, every pattern within 2^20 of 1.0, every denormal, zeros, infinity, NaNs and every 4096th
+    # negative pattern (NaN): within 2 ulp; -inf at zero, +inf at infinity.
+    near = [(0x3F800000 - (1 << 20), 0x3F800000 + (1 << 20), 1), (0, 0x00800000 + 4096, 1)]
+    ranges = [(0x00800000, 0x7F800000, 16)] + near + [(0x7F800000 - 4096, 0x7F800000 + 4096, 1), (0x7F800000, 1 << 31, 4096), (0x80000000, 1 << 32, 4096)]
+    worst, at = _ulp_errors_of_a_unary(env, env_interp, "log", ranges, interp_ranges=near)
+    print(f"log: worst error {worst:.3f} ulp at bits 0x{at:08x}")
+    assert worst <= 2.0, f"log off by {worst:.2f} ulp at bits 0x{at:08x}"
+    x = np.exp(np.random.default_rng(6).uniform(-80, 80, 1 << 16)).astype(f32)
+    for odd_one in (0.0, -1.0, 1e-40, np.nan, np.inf):
+        _values_do_not_depend_on_the_neighbours(env, "log", x, odd_one)
+
+
 @pytest.mark.parametrize("c", [1.4142135623730951, 3.0, 0.1, 262144.0, 1e-12, 16777215.0, -7.0, 1.9999998807907104, 1e20, 1e-30, 3e38])
 def test_division_by_a_constant_for_every_float32(env, c):
     # A quotient whose divisor is a scalar constant shares the refined reciprocal between a thread's
