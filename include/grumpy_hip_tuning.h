@@ -30,8 +30,11 @@ extern "C" {
  *                     than half empty
  *   "gemm_kstep"      values of k per step of the matrix-product kernel's main loop (one barrier per
  *                     step): 16 (default), 32
+ *   "gemm_split"      workgroups per output tile of a matrix product, each accumulating a part of K into
+ *                     a partial tile that a second kernel combines in a fixed order: 1 .. 256; 0 (default) =
+ *                     chosen by the planner (more than one only for fewer than 192 output tiles and K >= 256)
  *   "gemm_big"        1 (default) = matrix products whose operands are each contiguous along one of their
- *                     dimensions, with K a multiple of 16 and no split of K, use the kernels whose operand
+ *                     dimensions, with K a multiple of 16 (and of every split of K at least 32), use the kernels whose operand
  *                     tiles go from global memory straight into LDS: 256 x 256 tiles, one workgroup per
  *                     compute unit, where the result fills at least 85 % (65 % if M or N is not a multiple
  *                     of 128) of its rounds over the 256 compute units, else 128 x 128 tiles; 0 = the kernel

@@ -1777,6 +1777,7 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   auto rc_row = [&](int k) { return NB == 4 ? k * 264 : (k >> 1) * 272 + (k & 1) * 128; };   // offset of k row k of a row-contiguous tile (k without the half-wave's 4 h)
   const char* RV = NB == 4 ? "f4" : "gr_f2";      // what a lane reads of a row-contiguous tile per k
   std::ostream& o = e.o;
+  const bool split = g.slabs > 1;
   o << "  __shared__ __attribute__((aligned(16))) float gr_lds[" << 3 * STAGE << "];\n"
        "  typedef __attribute__((address_space(3))) float lfloat;\n"
        "  typedef __attribute__((address_space(3))) f4 lf4;\n"
@@ -1785,8 +1786,13 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
        "  typedef __attribute__((address_space(3))) gr_f2 lgr_f2;\n"
        "  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;\n"
        "  const int wm = (wave >> 1) * " << 32 * NB << ", wn = (wave & 1) * " << 32 * NB << ";\n"
-       "  const long long tiles_n = (N + " << T - 1 << ") / " << T << ";\n"
-       "  const long long bm0 = (blockIdx.x / tiles_n) * " << T << ", bn0 = (blockIdx.x % tiles_n) * " << T << ";\n"
+       "  const long long tiles_n = (N + " << T - 1 << ") / " << T << ";\n";
+  // split K (few output tiles, a long contraction): workgroup (tile, split) accumulates the steps of k in [kbeg, KE),
+  // a whole number of steps and at least two by the planner's choice, and leaves its partial tile in a workspace
+  if (split) o << "  const long long tiles = tiles_n * ((M + " << T - 1 << ") / " << T << "), tile = blockIdx.x % tiles, split = blockIdx.x / tiles;\n"
+                  "  const long long kbeg = split * " << e.S(e.L.ocoef + 1) << ", KE = kbeg + " << e.S(e.L.ocoef + 1) << " < K ? kbeg + " << e.S(e.L.ocoef + 1) << " : K;\n";
+  else o << "  const long long tile = blockIdx.x, kbeg = 0, KE = K;\n";
+  o << "  const long long bm0 = (tile / tiles_n) * " << T << ", bn0 = (tile % tiles_n) * " << T << ";\n"
        "  f16v acc[" << NB << "][" << NB << "];\n"
        "  for (int i = 0; i < " << NB << "; ++i) for (int j = 0; j < " << NB << "; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;\n"
        "  const unsigned wv = __builtin_amdgcn_readfirstlane(wave);\n"
@@ -1800,13 +1806,13 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
       // (rows beyond the operand's edge read its last row: their results are never stored)
       o << "  for (int p = 0; p < " << NB << "; ++p) { const int m = 16 * (" << NB << " * wave + p) + lane / 4, c = (lane % 4) ^ ((m >> 2) & 3); const long long last = " << x.lim << " - 1 - " << x.org
         << "; " << n << "off[p] = 4u * (unsigned)((m < last ? m : last) * " << x.ld << " + 4 * c); }\n"
-           "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << " * " << x.ld << ");\n"
+           "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << " * " << x.ld << " + kbeg);\n"
            "  const unsigned long long " << n << "step = 64ull;\n";
     else {
       // (groups of four beyond the operand's edge, whose extent is a multiple of four, read its last group)
       if (NB == 4) o << "  for (int p = 0; p < 4; ++p) { const long long last = " << x.lim << " - 4 - " << x.org << "; " << n << "off[p] = 4u * (unsigned)((4 * wave + p) * " << x.ld << " + (4 * lane < last ? 4 * lane : last)); }\n";
       else o << "  for (int p = 0; p < 2; ++p) { const long long last = " << x.lim << " - 4 - " << x.org << "; " << n << "off[p] = 4u * (unsigned)((2 * (2 * wave + p) + lane / 32) * " << x.ld << " + (4 * l32 < last ? 4 * l32 : last)); }\n";
-      o << "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << ");\n"
+      o << "  const unsigned long long " << n << "64 = (unsigned long long)(" << X << " + " << x.org << " + kbeg * " << x.ld << ");\n"
            "  const unsigned long long " << n << "step = 64ull * (unsigned long long)__builtin_amdgcn_readfirstlane((int)" << x.ld << ");\n";
     }
     const int wave_bytes = x.kc ? 1024 * NB : (NB == 4 ? 4 * 264 * 4 : 4 * 272 * 2);
@@ -1821,7 +1827,7 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
       o << "  const lfloat* " << n << "p[3];\n#pragma unroll\n  for (int st = 0; st < 3; ++st) " << n << "p[st] = (const lfloat*)gr_lds + st * " << STAGE << " + " << x.part << " + " << rc_row(4) << " * lh + " << w0 << " + " << NB << " * l32;\n"
            "  " << RV << " " << n << "F[2];\n";
   }
-  o << "  const long long nkt = K / 16;\n";
+  o << "  const long long nkt = (KE - kbeg) / 16;\n";
   // piece p (0 .. NB - 1: the left tile, NB .. 2 NB - 1: the right tile) of the tile at the bases into the stage in role st
   auto piece = [&](int st, int p, const char* ind) {
     const Op& x = ops[p / NB];
@@ -1917,7 +1923,8 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
   // Results beyond the edges of the matrix are computed like the others, from operands read at the clamped position,
   // and not stored (no branch around the epilogue: sixty-four guarded copies of a large one made the register
   // allocator spill).
-  o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
+  if (split) o << "  GM float* const out = (GM float*)" << e.slot(e.L.ocoef) << " + split * M * N;\n";   // the partial tile; gr_gemm_combine applies the epilogue
+  else o << "  GM float* const out = (GM float*)" << e.slot(e.L.out) << ";\n";
   const std::string body = captured(e, [&] {
     o << "      const int rr = 8 * (q / 4) + 4 * lh + (q % 4);\n"
          "      const long long row_at = bm0 + wm + " << (ops[0].kc ? "32 * i + rr" : std::to_string(NB) + " * rr + i") << ", row = row_at < M ? row_at : M - 1;\n"
@@ -1925,9 +1932,10 @@ void gemm_big_body(Em& e, const EpiLoad& epi_load) {
          "#pragma unroll\n      for (int j = 0; j < " << NB << "; ++j) {\n"
          "        const long long col_at = bn0 + wn + " << (ops[1].kc ? "32 * j + l32" : std::to_string(NB) + " * l32 + j") << ", col = col_at < N ? col_at : N - 1;\n"
          "        const float cacc = acc[i][j][q];\n";
-    emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        ");
-    if (ops[1].kc) o << "        if (row_at < M && col_at < N) out[row * N + col] = t" << g.results[0] << ";\n      }\n      (void)ov;\n";
-    else o << "        ov[j] = t" << g.results[0] << ";\n      }\n"
+    std::string res = "cacc";
+    if (!split) { emit_scalar_program(e, g.prog, g.results, epi_load, "cacc", "t", "        "); res = "t" + std::to_string(g.results[0]); }
+    if (ops[1].kc) o << "        if (row_at < M && col_at < N) out[row * N + col] = " << res << ";\n      }\n      (void)ov;\n";
+    else o << "        ov[j] = " << res << ";\n      }\n"
               "      if (row_at < M && bn0 + wn + " << NB << " * l32 < N) *(GM " << RV << "u*)(out + row * N + bn0 + wn + " << NB << " * l32) = ov;\n";
   });
   emit_unrolled(o, {{"i", NB}, {"q", 16}}, body, "    ");

@@ -69,6 +69,7 @@ struct gr_ctx {
   int64_t opt_scan_threads = 0, opt_scan_min_threads = 0;
   int64_t opt_scan_one_pass = 1;
   int64_t opt_gemm_kstep = 0;
+  int64_t opt_gemm_split = 0;   // matrix product: workgroups per output tile along K (0 = chosen by the planner)
   int64_t opt_gemm_big = 1;     // matrix products of operands contiguous along one dimension: tiles loaded straight into LDS
   int64_t opt_map_phase = 1;
   int64_t opt_scan_polls = 1 << 20;   // polls a tile of a one-pass scan spends on each wait before it recomputes its offset
@@ -124,6 +125,7 @@ struct gr_ctx {
   unsigned char* static_base = nullptr;
   size_t static_cap = 0, static_used = 0;
   bool static_mode = false;
+  bool plan_static = false;     // the request being planned is one of those: the planner keeps optional partial results within the array
 
   // gr_program_create: the request being recorded instead of executed, and the programs alive
   gr_program* capture = nullptr;

@@ -140,6 +140,13 @@ struct ConstSlot {
   double value;
 };
 
+// k extent of one split of a matrix product whose K range is divided over nsplit workgroups per output tile:
+// a multiple of 32 (the longer of the two k steps of the kernels) that covers K in nsplit pieces; the last
+// piece is what remains and may be short or empty.
+inline int64_t gemm_split_extent(int64_t K, int64_t nsplit) {
+  return nsplit > 1 ? (((K + nsplit - 1) / nsplit + 31) / 32) * 32 : K;
+}
+
 // One sub-graph of the ordered list of Algorithm 1, ready for code generation.
 struct GroupPlan {
   GroupKind kind = GroupKind::MAP;

@@ -929,6 +929,7 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
         int64_t ks = std::min<int64_t>(512 / tiles, g->K / 128);
         if (ks >= 2) g->slabs = (int)std::min<int64_t>(ks, 256);
       }
+      if (c->opt_gemm_split >= 1) g->slabs = (int)std::min<int64_t>(std::min<int64_t>(c->opt_gemm_split, 256), std::max<int64_t>(1, g->K / 32));
     }
     // Large products of operands that are contiguous along one of their two dimensions: 256 x 256 tiles, one
     // workgroup per compute unit, tiles loaded straight into LDS (BX = 256 selects that kernel).  It needs
@@ -953,16 +954,41 @@ static gr_status build_group(gr_ctx* c, Planner& pl, Node* r, GroupPlan* g, std:
       // where M or N is not a multiple of 128 (the 128-wide kernel's guarded edge tiles make it slower there; measured
       // on 4000^3: 136 against 97 TFLOP/s, 8000^3: 144 against 114, 10000 x 4096 x 10000, seven rounds 85 % full: 126 against 117).
       const int64_t need = (g->M % 128 == 0 && g->N % 128 == 0) ? 17 : 13;
-      const bool direct = c->opt_gemm_big && c->opt_gemm_bn == 0 && g->slabs == 1 && g->K % 16 == 0 && g->K >= 32 && fits(ag, 1, g->M) && fits(bg, 0, g->N);
-      if (direct && g->M >= 256 && g->N >= 256 && g->M * g->N * 20 >= rounds * 256 * 65536 * need) {
+      const bool direct = c->opt_gemm_big && c->opt_gemm_bn == 0 && g->K % 16 == 0 && g->K >= 32 && fits(ag, 1, g->M) && fits(bg, 0, g->N);
+      // (with K split over workgroups every split has to hold whole steps of k and at least two of them: the last one is the shortest)
+      const bool split_ok = g->slabs == 1 || g->K - (g->slabs - 1) * gemm_split_extent(g->K, g->slabs) >= 32;
+      if (direct && g->slabs == 1 && g->M >= 256 && g->N >= 256 && g->M * g->N * 20 >= rounds * 256 * 65536 * need) {
         g->BX = 256;
         g->VR = 2;   // (marks the kernels whose tiles go straight into LDS)
         g->UC = 1;
-      } else if (direct && g->BX == 128 && g->M >= 128 && g->N >= 128) {
-        // the same kernel with 128 x 128 tiles (up to three workgroups per compute unit) where the large tiles would
-        // leave compute units idle: tiles are distributed like those of the 128-wide kernel, which it beats wherever
-        // it applies (measured: 2048^3 114 against 101 TFLOP/s, 3072^3 110 against 97, 4096 x 4096 x 2048 142 against 124,
-        // 2000^3 124 against 62, 4100 x 4096 x 4000 115 against 84)
+      } else if (direct && g->BX == 128 && g->M >= 128 && g->N >= 128 && c->opt_gemm_split == 0) {
+        // The same kernel with 128 x 128 tiles, up to three workgroups per compute unit, and K divided over `slabs`
+        // workgroups per tile where that fills the compute units more evenly or at all.  The count is the one with the
+        // lowest cost in a model fitted to measurements (microseconds): rounds of 256 workgroups times the steps of one
+        // workgroup at 0.95 per step (1.1 where compute units hold a single workgroup, which has nobody to overlap its
+        // barriers with), plus, for a split product, 6 for the second launch and the traffic of the partial tiles at
+        // 5 TB/s.  A larger count has to beat a smaller one by 3 %.  Every split holds at least 128 values of k, the last
+        // one at least two steps; the partial tiles stay below 1 GiB (within the static scratch array for a request that must not
+        // allocate).
+        // (measured, split chosen / one workgroup per tile / the kernel that stages through registers with its own
+        // split: 1024^3 30 / 68 / 38 us, 1536^3 77 / 98 / 90, 3072^3 442 / 525 / 598, 8192 x 256 x 8192 273 / 499 / 306,
+        // 1024 x 1024 x 8192 139 / 493 / 159, 512 x 512 x 16384 80 / 976 / 89)
+        const int64_t tiles128 = ((g->M + 127) / 128) * ((g->N + 127) / 128);
+        const int64_t room = c->plan_static ? (int64_t)(c->static_cap / sizeof(float)) : (int64_t)1 << 28;   // floats of partial tiles
+        double best = 0;
+        int best_ks = 0;
+        for (int ks = 1; ks <= 64; ++ks) {
+          const int64_t kch = gemm_split_extent(g->K, ks);
+          if (ks > 1 && (kch < 128 || g->K - (ks - 1) * kch < 32 || (int64_t)ks * g->M * g->N > room)) continue;
+          const int64_t wgs = tiles128 * ks, rnd = (wgs + 255) / 256, steps = (kch + 15) / 16;
+          const double cost = (double)rnd * (double)steps * (wgs <= 256 ? 1.1 : 0.95) + (ks > 1 ? 6.0 + (double)ks * (double)g->M * (double)g->N * 8.0 / 5e6 : 0.0);
+          if (best_ks == 0 || cost < best * 0.97) { best = cost; best_ks = ks; }
+        }
+        g->slabs = best_ks;
+        g->VR = 2;
+        g->UC = 1;
+      } else if (direct && split_ok && g->BX == 128 && g->M >= 128 && g->N >= 128) {
+        // (a number of workgroups per tile set by option "gemm_split")
         g->VR = 2;
         g->UC = 1;
       }
@@ -1448,6 +1474,7 @@ std::string describe_plan(const Plan& plan) {
     for (const Node* n : g.leaves) { s << (first ? "" : ",") << n->id; first = false; }
     s << "] loads=" << [&] { int k = 0; for (const Instr& in : (g.kind == GroupKind::MAP ? g.prog1 : g.prog)) if (in.kind == IKind::LOAD) ++k; return k; }();
     if (g.kind == GroupKind::GEMM) s << " M=" << g.M << " N=" << g.N << " K=" << g.K << " tile=" << (g.BX == 256 ? 256 : 128) << "x" << g.BX << (g.VR == 2 ? " direct" : "");
+    if (g.kind == GroupKind::GEMM && g.slabs > 1) s << " split=" << g.slabs;
     if (g.kind == GroupKind::GEMV) s << " mode=" << (g.gemv_mode == 2 ? "row-dot+column-accumulate" : (g.gemv_mode ? "column-accumulate" : "row-dot")) << " M=" << g.M << " K=" << g.K;
     if (g.pair) {
       s << " fused-with=[root=" << g.pair->root->id << " members=[";

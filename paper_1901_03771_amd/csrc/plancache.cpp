@@ -62,6 +62,7 @@ bool fingerprint(gr_ctx* c, Node* root, const OutSpec* out, Walk* w) {
   std::vector<int64_t>& k = w->key;
   k.reserve(nodes.size() * 12 + 32);
   k.push_back((int64_t)c->options_epoch);
+  k.push_back((int64_t)c->plan_static);
   k.push_back((int64_t)nodes.size());
   if (out) {
     k.push_back(1);

@@ -232,6 +232,7 @@ gr_status gr_ctx_set_option(gr_ctx* ctx, const char* key, int64_t value) {
   else if (k == "rowred_rows") ctx->opt_rowred_rows = value;
   else if (k == "gemm_bn") ctx->opt_gemm_bn = value;
   else if (k == "gemm_kstep") ctx->opt_gemm_kstep = value;
+  else if (k == "gemm_split") ctx->opt_gemm_split = value;
   else if (k == "gemm_big") ctx->opt_gemm_big = value;
   else if (k == "map_phase") ctx->opt_map_phase = value;
   else if (k == "pool_limit") ctx->opt_pool_limit = value;

@@ -632,8 +632,7 @@ gr_status launch_group(gr_ctx* c, const GroupPlan& g, gr_ctx::Kernel* k, void* o
       // (VR = 2: the kernels whose tiles go straight into LDS, one workgroup per BX x BX tile)
       const int64_t tiles = g.VR == 2 ? ((g.M + g.BX - 1) / g.BX) * ((g.N + g.BX - 1) / g.BX) : ((g.M + 127) / 128) * ((g.N + bn - 1) / bn);
       const int64_t nsplit = std::max(1, g.slabs);
-      // k extent of one split: a multiple of 32 (the longer of the two k steps) that covers K in nsplit pieces
-      const int64_t kch = nsplit > 1 ? (((g.K + nsplit - 1) / nsplit + 31) / 32) * 32 : g.K;
+      const int64_t kch = gemm_split_extent(g.K, nsplit);
       s[L.extra + 3] = (uint64_t)nsplit;
       s[L.ocoef + 1] = (uint64_t)std::max<int64_t>(kch, 1);
       if (nsplit > 1) {

@@ -70,7 +70,9 @@ extern "C" gr_status gr_materialize_into_static(gr_ctx* ctx, gr_array a, void* d
   }
   if (!ctx->static_base) return fail(ctx, GR_ERR_HIP, "materialize_into_static: the static scratch array has no address on this device");
   Plan plan;  // (host memory only)
+  ctx->plan_static = true;
   gr_status st = make_plan(ctx, x, &plan);
+  ctx->plan_static = false;
   if (st != GR_OK) return st;
   ctx->static_mode = true;
   ctx->static_used = 0;  // every call starts at the beginning of the array: calls that overlap on one GPU race

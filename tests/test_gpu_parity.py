@@ -950,6 +950,37 @@ def test_matrix_product_with_128_wide_tiles_loaded_straight_into_lds(env, layout
     assert bool((buf[:4096] == -77.0).all()) and bool((buf[4096 + M * N:] == -77.0).all())
 
 
+@pytest.mark.parametrize("layout,M,N,K,split", [("nn", 384, 256, 1040, 0), ("tn", 300, 380, 2048, 0), ("nt", 257, 384, 4112, 0), ("tt", 1000, 252, 512, 0),
+                                                ("nn", 640, 512, 1024, 0), ("nn", 256, 256, 96, 2), ("tn", 512, 376, 464, 3), ("nt", 2049, 2048, 304, 5),
+                                                ("tt", 1500, 1300, 96, 3), ("nn", 129, 252, 16384, 0)])
+def test_matrix_products_with_k_divided_over_direct_workgroups(env, layout, M, N, K, split):
+    """Few output tiles and a long contraction: several workgroups per 128 x 128 tile, each loading its part of K straight into
+    LDS and leaving a partial tile that a second kernel adds up in a fixed order before the epilogue (a bias and a product with
+    a third array here).  The planner's own choice of the count and counts set by option, whose last part is shorter than
+    the others; small integers, every element, written into the middle of a guarded buffer."""
+    gr, ctx, torch = env
+    g = np.random.default_rng(520 + M + K)
+    X = g.integers(-3, 4, (M, K)).astype(f32)
+    Y = g.integers(-3, 4, (K, N)).astype(f32)
+    arrays = dict(X=np.ascontiguousarray(X.T) if layout[0] == "t" else X, Y=np.ascontiguousarray(Y.T) if layout[1] == "t" else Y,
+                  rowv=g.integers(-5, 6, (N,)).astype(f32), Z=g.integers(-2, 3, (M, N)).astype(f32))
+    prog = lambda xp, X, Y, rowv, Z: ((X.T if layout[0] == "t" else X) @ (Y.T if layout[1] == "t" else Y) + rowv) * Z
+    ctx.set_option("gemm_split", split)
+    try:
+        dev, keep = to_dev(torch, ctx, arrays)
+        plan = prog(gr, **dev).plan()
+        assert "tile=128x128 direct split=" in plan, plan
+        if split: assert f"split={split}" in plan
+        buf = torch.full((M * N + 8192,), -77.0, device="cuda")
+        prog(gr, **dev).materialize_into(buf[4096:4096 + M * N].view(M, N))
+        ctx.sync()
+    finally:
+        ctx.set_option("gemm_split", 0)
+    ref = prog(ora, **{k: ora.array(v) for k, v in arrays.items()}).numpy()
+    assert np.array_equal(buf[4096:4096 + M * N].view(M, N).cpu().numpy(), ref)
+    assert bool((buf[:4096] == -77.0).all()) and bool((buf[4096 + M * N:] == -77.0).all())
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_direct_matrix_products_of_random_shapes(env, seed):
     """Ten random products per seed, most of them through the kernels that load their tiles straight into LDS: ragged M and N, any of the
