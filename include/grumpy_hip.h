@@ -288,8 +288,10 @@ gr_status gr_materialize_into(gr_ctx* ctx, gr_array a, void* dptr, size_t bytes)
  *     holds its own copy until the process ends).  A request that needs more is refused with
  *     GR_ERR_OOM before anything is launched; the message names both sizes.
  *   - Every kernel of the request must already be loaded on this context (loading a code
- *     object allocates): call gr_plan_compile(ctx, a), or evaluate a request of the same
- *     structure with gr_materialize / gr_materialize_into, once beforehand.  Otherwise
+ *     object allocates): call gr_plan_compile(ctx, a) once beforehand.  Evaluating a request
+ *     of the same structure with gr_materialize / gr_materialize_into also serves, unless the
+ *     planner picks other kernels when partial results have to fit the static array (a matrix
+ *     product whose K it would otherwise divide over more workgroups than fit).  Otherwise
  *     GR_ERR_UNSUPPORTED, nothing launched.  Option "profile" is ignored by this call.
  *   - Results of earlier sub-graphs exist only while the request runs: after the call those
  *     arrays are unevaluated again (and can be evaluated later); only `a` keeps its value, in
@@ -371,8 +373,9 @@ gr_status gr_plan_describe(gr_ctx* ctx, gr_array a, char* buf, size_t cap, size_
 gr_status gr_plan_source(gr_ctx* ctx, gr_array a, int index, char* buf, size_t cap, size_t* needed);
 
 /* Compiles every sub-graph of the plan for gfx950 without running it (works
- * without a device); returns GR_ERR_COMPILE with the compiler log in
- * gr_last_error on failure. */
+ * without a device), and the kernels that gr_materialize_into_static would use
+ * for the same request where they differ; returns GR_ERR_COMPILE with the
+ * compiler log in gr_last_error on failure. */
 gr_status gr_plan_compile(gr_ctx* ctx, gr_array a);
 
 /* Blocks until every run-time compilation started by earlier requests has

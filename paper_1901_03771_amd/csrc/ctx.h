@@ -92,6 +92,7 @@ struct gr_ctx {
     hipFunction_t fn3 = nullptr;  // scan of the chunk totals
     std::vector<char> code;
     std::string name;
+    size_t src_hash = 0;          // of the source text it was compiled from (compared in the self-checking mode)
   };
   std::unordered_map<std::string, Kernel> cache;
 

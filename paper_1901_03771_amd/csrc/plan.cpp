@@ -472,7 +472,7 @@ void make_signature(GroupPlan* g) {
   std::string s;
   s.reserve(256 + 32 * (g->prog.size() + g->prog1.size()));
   for (int64_t v : {(int64_t)g->kind, (int64_t)g->rank, (int64_t)g->out_dtype, (int64_t)g->out_per_row, (int64_t)g->BX, (int64_t)g->BY,
-                    (int64_t)g->VR, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads + 1024 * (int64_t)g->row_iters, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask + (((int64_t)g->tail) << 40) + (((int64_t)g->diag) << 44) + (((int64_t)g->cphase) << 48), (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
+                    (int64_t)g->VR + (g->kind == GroupKind::GEMM && g->VR == 2 && g->slabs > 1 ? 1024 : 0) /* (the direct-to-LDS product kernels compile the split of K in or out) */, (int64_t)g->UC, (int64_t)g->NP, (int64_t)g->row_threads + 1024 * (int64_t)g->row_iters, (int64_t)g->xcd_remap + 2 * (int64_t)g->stage_mask + (((int64_t)g->tail) << 40) + (((int64_t)g->diag) << 44) + (((int64_t)g->cphase) << 48), (int64_t)g->red_mode + 16 * (int64_t)g->red_vec,
                     (int64_t)g->red_kept_rank, (int64_t)g->gemv_mode, (int64_t)g->LPR, (int64_t)g->KV, (int64_t)g->mat_group,
                     (int64_t)g->vec_group, (int64_t)g->nt, (int64_t)g->unroll, (int64_t)g->scan_mode + 16 * (int64_t)g->scan_vec + (g->scan_mode >= 2 ? 256 * g->scan_chunk : 0) /* (a one-pass scan's tile size is compiled in) */, (int64_t)g->out_unit, (int64_t)g->groups.size()})
     put(s, v);

@@ -236,10 +236,11 @@ static void kernel_entry_points(const GroupPlan& g, std::string* name, bool* com
 
 // Loads a code object and publishes the kernel in the in-memory cache.
 static gr_status finish_kernel(gr_ctx* c, const std::string& sig, const std::string& name, bool combine, int scan,
-                               std::vector<char>&& code, gr_ctx::Kernel** out) {
+                               std::vector<char>&& code, const std::string& src, gr_ctx::Kernel** out) {
   gr_ctx::Kernel k;
   k.code = std::move(code);
   k.name = name;
+  k.src_hash = std::hash<std::string>()(src);
   if (c->device >= 0) {
     GR_HIP(c, hipModuleLoadData(&k.module, k.code.data()));
     GR_HIP(c, hipModuleGetFunction(&k.fn, k.module, k.name.c_str()));
@@ -277,7 +278,7 @@ gr_status prepare_group(gr_ctx* c, GroupPlan& g) {
     bool combine;
     int scan;
     kernel_entry_points(g, &name, &combine, &scan);
-    return finish_kernel(c, g.signature, name, combine, scan, std::move(code), nullptr);
+    return finish_kernel(c, g.signature, name, combine, scan, std::move(code), src, nullptr);
   }
   bound_pending(c);
   auto job = std::make_shared<gr_ctx::CompileJob>();
@@ -306,7 +307,7 @@ static gr_status collect_job(gr_ctx* c, const std::string& sig, gr_ctx::Kernel**
   }
   disk_store(disk_path(c, job->src), job->src, job->code);
   if (!load) return GR_OK;
-  return finish_kernel(c, sig, job->kernel, job->combine, job->scan, std::move(job->code), out);
+  return finish_kernel(c, sig, job->kernel, job->combine, job->scan, std::move(job->code), job->src, out);
 }
 
 gr_status collect_all_jobs(gr_ctx* c, bool load) {
@@ -349,6 +350,14 @@ gr_status compile_group(gr_ctx* c, GroupPlan& g, gr_ctx::Kernel** out) {
   if (it != c->cache.end()) {
     c->stats.cache_hits++;
     *out = &it->second;
+    if (c->opt_plan_cache >= 2) {
+      // self-checking mode: the signature has to determine the source; a plan whose source differs from the one
+      // its cached kernel was compiled from would run a kernel written for other assumptions
+      gr_status est = expand_patch(c, &g);
+      if (est != GR_OK) return est;
+      if (std::hash<std::string>()(generate_source(g)) != it->second.src_hash)
+        return fail(c, GR_ERR_UNSUPPORTED, "kernel cache: this sub-graph's source differs from the source its signature was compiled from (" + kernel_name(g) + ")");
+    }
     return GR_OK;
   }
   gr_status st = prepare_group(c, g);
@@ -1479,19 +1488,30 @@ gr_status gr_plan_compile(gr_ctx* ctx, gr_array a) {
   if (!ctx) return GR_ERR_ARG;
   Node* x = lookup(ctx, a);
   if (!x) return fail(ctx, GR_ERR_HANDLE, "plan_compile: bad handle");
-  Plan plan;
-  gr_status st = make_plan(ctx, x, &plan);
-  if (st != GR_OK) return st;
-  for (auto& g : plan.groups) {
-    st = prepare_group(ctx, *g);
-    if (st != GR_OK) break;
+  // twice: as gr_materialize would plan the request, and as the entry point that must not allocate would (the planner
+  // then keeps optional partial results within the static scratch array, which can select other kernels)
+  gr_status st = GR_OK;
+  std::string first;
+  for (int pass = 0; pass < 2 && st == GR_OK; ++pass) {
+    Plan plan;
+    ctx->plan_static = pass == 1;
+    st = make_plan(ctx, x, &plan);
+    ctx->plan_static = false;
+    if (st != GR_OK) return st;
+    const std::string text = describe_plan(plan);
+    if (pass == 0) first = text;
+    else if (text == first) { clear_planned(&plan); break; }   // the same plan: nothing more to compile
+    for (auto& g : plan.groups) {
+      st = prepare_group(ctx, *g);
+      if (st != GR_OK) break;
+    }
+    for (auto& g : plan.groups) {
+      if (st != GR_OK) break;
+      gr_ctx::Kernel* k = nullptr;
+      st = compile_group(ctx, *g, &k);
+    }
+    clear_planned(&plan);
   }
-  for (auto& g : plan.groups) {
-    if (st != GR_OK) break;
-    gr_ctx::Kernel* k = nullptr;
-    st = compile_group(ctx, *g, &k);
-  }
-  clear_planned(&plan);
   return st;
 }
 

@@ -663,6 +663,28 @@ def test_async_and_serial_compilation_agree(ctx):
     c2.close()
 
 
+def test_kernel_signature_determines_the_source(ctx):
+    # Kernels are cached by a signature of the sub-graph, not by their text.  In the self-checking mode a cache hit
+    # regenerates the source and compares it with the one the cached kernel was compiled from: variants of a matrix
+    # product that differ only in how the planner runs them (K divided over workgroups or not, tiles loaded straight
+    # into LDS or staged through registers, narrow tiles) must not share a signature unless they share their text.
+    # (A product without a split once found the kernel of a split one under its signature and wrote its partial tile
+    # through a workspace pointer that nobody had set.)
+    ctx.set_option("plan_cache", 2)
+    ctx.set_option("disk_cache", 0)
+    seen = set()
+    for big, split, bn in [(1, 1, 0), (1, 2, 0), (1, 1, 0), (1, 3, 0), (0, 2, 0), (0, 1, 0), (1, 2, 0), (0, 1, 32), (1, 1, 0)]:
+        for k, v in (("gemm_big", big), ("gemm_split", split), ("gemm_bn", bn)):
+            ctx.set_option(k, v)
+        out = ctx.spec((512, 384)) @ ctx.spec((384, 512)) + ctx.spec((512,))
+        out.compile()                      # fails with "source differs" if a signature stands for two texts
+        seen.add(out.source(0))
+    assert len(seen) == 4 and ctx.stats()["cache_misses"] == 4
+    for k in ("gemm_split", "gemm_bn"):
+        ctx.set_option(k, 0)
+    ctx.set_option("gemm_big", 1)
+
+
 def test_generated_code_has_no_contraction_or_packed_math(ctx):
     src = wl.chain(gr, ctx.spec((4096,)), ctx.spec((4096,))).source(0)
     # the only fused multiply-adds are inside the math helpers: two in the square root (its Newton step needs the

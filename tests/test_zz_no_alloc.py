@@ -81,6 +81,24 @@ def test_static_entry_refuses_what_it_cannot_serve():
     assert L.gr_materialize_into_static(ctx._p, lazy.h, out.data_ptr(), out.numel() * 4) == 0
     want = gr.cumsum(gr.tanh(a) * 3.0 + gr.erf(a), 0).torch()
     assert torch.equal(out, want)
+    # a matrix product whose K the planner divides over three workgroups per tile (28 MiB of partial tiles): planned for
+    # this entry point it keeps one workgroup per tile and needs nothing beyond inputs and output; gr_plan_compile
+    # prepares that kernel too (small integers: the order of the additions does not show)
+    g = np.random.default_rng(404)
+    A = torch.from_numpy(g.integers(-3, 4, (1536, 1536)).astype(f32)).cuda()
+    B = torch.from_numpy(g.integers(-3, 4, (1536, 1536)).astype(f32)).cuda()
+    lazy = ctx.array(A) @ ctx.array(B)
+    assert "direct split=3" in lazy.plan()
+    want = torch.empty(1536, 1536, device="cuda")
+    lazy.materialize_into(want)
+    lazy = ctx.array(A) @ ctx.array(B)
+    got = torch.full((1536, 1536), float("nan"), device="cuda")
+    assert gr.STATUS[L.gr_materialize_into_static(ctx._p, lazy.h, got.data_ptr(), got.numel() * 4)] == "GR_ERR_UNSUPPORTED"
+    lazy.compile()
+    before = ctx.stats()
+    assert L.gr_materialize_into_static(ctx._p, lazy.h, got.data_ptr(), got.numel() * 4) == 0, ctx.last_error()
+    assert ctx.stats()["bytes_allocated"] == before["bytes_allocated"] and ctx.stats()["kernel_launches"] == before["kernel_launches"] + 1
+    assert torch.equal(got, want)
     # an intermediate result beyond the 16 MiB of the static array: refused with both sizes named
     big = ctx.array(torch.ones((5 << 20,), device="cuda"))
     lazy = gr.sum(gr.cumsum(big, 0))                         # the prefix sums (20 MiB) are stored for the sum
