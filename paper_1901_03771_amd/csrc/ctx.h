@@ -95,6 +95,7 @@ struct gr_ctx {
     size_t src_hash = 0;          // of the source text it was compiled from (compared in the self-checking mode)
   };
   std::unordered_map<std::string, Kernel> cache;
+  std::unordered_map<std::string, size_t> dry_sources;  // signature -> hash of its source, kept by dry runs in the self-checking mode
 
   // run-time compilations in flight (signature -> job), see runtime.cpp
   struct CompileJob {

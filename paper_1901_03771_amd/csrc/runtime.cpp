@@ -784,6 +784,18 @@ gr_status execute_plan(gr_ctx* c, Plan* plan, Node* root, void* user_out, bool c
     const bool try_interp = !c->static_mode && !c->capture &&
                             (c->opt_interp >= 2 || (c->opt_interp == 1 && still_compiling(c, g)));
     if (no_compile) k = &dry_kernel;
+    if (no_compile && c->opt_plan_cache >= 2) {
+      // self-checking dry run: nothing is compiled, but the source is generated and has to be the one that any
+      // earlier sub-graph with this signature produced (the kernel cache is keyed by the signature)
+      gr_status est = expand_patch(c, &g);
+      if (est != GR_OK) { static_unbind(c, plan); return est; }
+      const size_t h = std::hash<std::string>()(generate_source(g));
+      auto ins = c->dry_sources.emplace(g.signature, h);
+      if (!ins.second && ins.first->second != h) {
+        static_unbind(c, plan);
+        return fail(c, GR_ERR_UNSUPPORTED, "kernel cache: this sub-graph's source differs from the source of an earlier one with the same signature (" + kernel_name(g) + ")");
+      }
+    }
     gr_status st = (try_interp || no_compile) ? GR_OK : compile_group(c, g, &k);
     if (st != GR_OK) { static_unbind(c, plan); return st; }
     // output buffers: the caller's for the requested root, the allocator's otherwise

@@ -685,6 +685,31 @@ def test_kernel_signature_determines_the_source(ctx):
     ctx.set_option("gemm_big", 1)
 
 
+def test_signatures_determine_sources_over_random_products_and_options():
+    # The same invariant without compiling anything: a dry run in the self-checking mode generates the source of
+    # every sub-graph it would launch and compares it with the source of any earlier sub-graph of the same signature.
+    # Four hundred matrix products: random extents (K a multiple of 16 or not), layouts, epilogues and planner options.
+    c = gr.Context(device=-1)
+    c.set_option("dry_run", 2)
+    c.set_option("plan_cache", 2)
+    g = np.random.default_rng(77)
+    for case in range(400):
+        c.set_option("gemm_split", int(g.choice([0, 0, 0, 1, 2, 3, 7])))
+        c.set_option("gemm_big", int(g.choice([1, 1, 0])))
+        c.set_option("gemm_bn", int(g.choice([0, 0, 0, 32, 128])))
+        M, N = (int(v) for v in g.choice([64, 128, 200, 256, 516, 1024, 2048, 4096], 2))
+        K = int(g.choice([32, 48, 100, 256, 1040, 4096]))
+        A = c.spec((K, M)).T if g.integers(2) else c.spec((M, K))
+        B = c.spec((N, K)).T if g.integers(2) else c.spec((K, N))
+        out = A @ B
+        if g.integers(2): out = gr.tanh(out + c.spec((N,)))
+        if g.integers(3) == 0: out = out * c.spec((M, N))
+        out.materialize()
+    del A, B, out
+    assert c.stats()["nodes_alive"] == 0
+    c.close()
+
+
 def test_generated_code_has_no_contraction_or_packed_math(ctx):
     src = wl.chain(gr, ctx.spec((4096,)), ctx.spec((4096,))).source(0)
     # the only fused multiply-adds are inside the math helpers: two in the square root (its Newton step needs the
