@@ -29,6 +29,9 @@ def env():
     from paper_1901_03771_amd import lazy as gr
     ctx = gr.Context()
     ctx.set_option("interp", 0)   # these tests are about the generated kernels: always wait for the compiler
+    # self-checking mode: every remembered plan is compared with a fresh one, and every kernel-cache hit with the source
+    # that the sub-graph would generate now (a kernel is found by a signature that has to determine its text)
+    ctx.set_option("plan_cache", 2)
     ora.set_threads(min(16, os.cpu_count() or 1))
     yield gr, ctx, torch
     ctx.sync()
