@@ -993,7 +993,9 @@ def test_direct_matrix_products_of_random_shapes(env, seed):
     direct = 0
     for case in range(10):
         ta, tb = bool(g.integers(2)), bool(g.integers(2))
-        K = int(g.integers(2, 11)) * 16
+        # (every third product has a contraction long enough for the planner to divide it over workgroups, or a count set by option)
+        K = int(g.integers(2, 11)) * 16 if case % 3 else int(g.integers(16, 48)) * 16
+        ctx.set_option("gemm_split", 0 if case % 3 else int(g.choice([0, 0, 2, 3])))
         # a row-contiguous operand needs a multiple of four along its other dimension
         M = int(g.integers(32, 190)) * 4 if ta else int(g.integers(128, 760))
         N = int(g.integers(32, 190)) * 4 if not tb else int(g.integers(128, 760))
@@ -1012,6 +1014,7 @@ def test_direct_matrix_products_of_random_shapes(env, seed):
         direct += "direct" in prog(gr, **dev).plan()
         got, ref = run_both(env, prog, arrays)
         assert got.shape == (M, N) and np.array_equal(got, ref), (seed, case, M, N, K, ta, tb)
+    ctx.set_option("gemm_split", 0)
     assert direct >= 3, "many of these shapes go to the direct kernels (results whose last 128 columns are mostly empty take 32-wide tiles)"
 
 
