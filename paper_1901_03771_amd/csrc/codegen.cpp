@@ -893,41 +893,62 @@ void gen_reduce(Em& e) {
     const char* jb = multi ? "jbeg4" : "jbeg";
     const char* je = multi ? "jend4" : "jend";
     e.o << "  long long j = " << jb << " + 4 * (long long)threadIdx.x;\n  {\n    " << T << " acc1 = acc, acc2 = acc, acc3 = acc;\n";
-    e.o << "#pragma unroll 2\n    for (; j + 4 <= " << je << "; j += 1024) {\n";
-    if (multi) {
-      e.o << "      long long jrem = j;\n";
-      for (int k = rank - 1; k >= kr; --k) {
-        if (k == kr) e.o << "      const long long i" << k << " = jrem;\n";
-        else e.o << "      const long long i" << k << " = gr_peel(jrem, " << e.dim(k) << ");\n";
+    // Four vector loads per array in flight: the loop body is written out four times here, all loads first, because the
+    // compiler cannot unroll a loop with a remainder once the body holds a wave-wide vote (the math helpers' tests for
+    // rare arguments), and one load in flight per lane leaves HBM waiting (measured on sum(sqrt(x)) over 2^27 elements).
+    // Every accumulator still takes its elements in increasing order of j: the same sums as a loop of single steps.
+    const int U = 4;
+    auto emit_loads = [&](int u, const char* ind) {
+      const std::string su = "_" + std::to_string(u), jx = "(j + " + std::to_string(1024 * u) + ")";
+      if (multi) {
+        e.o << ind << "long long jrem" << su << " = " << jx << ";\n";
+        for (int k = rank - 1; k >= kr; --k) {
+          if (k == kr) e.o << ind << "const long long i" << k << su << " = jrem" << su << ";\n";
+          else e.o << ind << "const long long i" << k << su << " = gr_peel(jrem" << su << ", " << e.dim(k) << ");\n";
+        }
+      } else e.o << ind << "const long long i" << kr << su << " = " << jx << ";\n";
+      for (size_t i = 0; i < g.prog.size(); ++i) {
+        const Instr& in = g.prog[i];
+        if (in.kind != IKind::LOAD) continue;
+        const AccessGroup& ag = g.groups[in.group];
+        std::ostringstream base;
+        base << "p" << in.group << " + 0";
+        for (int k = 0; k < kr; ++k) if (!ag.structural_zero[k] && in.delta[k]) base << " + " << in.delta[k] << " * " << e.coef(in.group, k);
+        for (int k = kr; k < rank; ++k) {
+          if (ag.structural_zero[k]) continue;
+          if (k == rd) base << " + i" << k << su << " + " << in.delta[k];
+          else base << " + (i" << k << su << " + " << in.delta[k] << ") * " << e.coef(in.group, k);
+        }
+        if (ag.structural_zero[rd]) e.o << ind << "const " << cty(in.dtype) << " u" << i << su << " = (" << base.str() << ")[0];\n";
+        else e.o << ind << "const " << vty4(in.dtype) << " w" << i << su << " = " << e.ld(in.group, vty4(in.dtype), base.str()) << ";\n";
       }
-    } else e.o << "      const long long i" << kr << " = j;\n";
-    for (size_t i = 0; i < g.prog.size(); ++i) {
-      const Instr& in = g.prog[i];
-      if (in.kind != IKind::LOAD) continue;
-      const AccessGroup& ag = g.groups[in.group];
-      std::ostringstream base;
-      base << "p" << in.group << " + 0";
-      for (int k = 0; k < kr; ++k) if (!ag.structural_zero[k] && in.delta[k]) base << " + " << in.delta[k] << " * " << e.coef(in.group, k);
-      for (int k = kr; k < rank; ++k) {
-        if (ag.structural_zero[k]) continue;
-        if (k == rd) base << " + i" << k << " + " << in.delta[k];
-        else base << " + (i" << k << " + " << in.delta[k] << ") * " << e.coef(in.group, k);
+    };
+    auto emit_compute = [&](int u, const std::string& ind) {
+      const std::string su = "_" + std::to_string(u);
+      e.o << ind << "{\n";
+      for (int k = rank - 1; k >= kr; --k) e.o << ind << "  const long long i" << k << " = i" << k << su << "; (void)i" << k << ";\n";
+      for (int c4 = 0; c4 < 4; ++c4) {
+        const std::string pre = "v" + std::to_string(c4) + "_";
+        emit_scalar_program(e, g.prog, {ph.value},
+                            [&](const Instr& in, int id) {
+                              const AccessGroup& ag = g.groups[in.group];
+                              if (ag.structural_zero[rd]) return "u" + std::to_string(id) + su;
+                              return "w" + std::to_string(id) + su + "[" + std::to_string(c4) + "]";
+                            },
+                            "0.0f", pre, (ind + "  ").c_str());
+        const std::string a = c4 == 0 ? "acc" : "acc" + std::to_string(c4);
+        e.o << ind << "  " << a << " = " << Em::combine(ph, a, pre + std::to_string(ph.value)) << ";\n";
       }
-      if (ag.structural_zero[rd]) e.o << "      const " << cty(in.dtype) << " u" << i << " = (" << base.str() << ")[0];\n";
-      else e.o << "      const " << vty4(in.dtype) << " w" << i << " = " << e.ld(in.group, vty4(in.dtype), base.str()) << ";\n";
-    }
-    for (int c4 = 0; c4 < 4; ++c4) {
-      const std::string pre = "v" + std::to_string(c4) + "_";
-      emit_scalar_program(e, g.prog, {ph.value},
-                          [&](const Instr& in, int id) {
-                            const AccessGroup& ag = g.groups[in.group];
-                            if (ag.structural_zero[rd]) return "u" + std::to_string(id);
-                            return "w" + std::to_string(id) + "[" + std::to_string(c4) + "]";
-                          },
-                          "0.0f", pre, "      ");
-      const std::string a = c4 == 0 ? "acc" : "acc" + std::to_string(c4);
-      e.o << "      " << a << " = " << Em::combine(ph, a, pre + std::to_string(ph.value)) << ";\n";
-    }
+      e.o << ind << "}\n";
+    };
+    e.o << "    for (; j + " << 4 + 1024 * (U - 1) << " <= " << je << "; j += " << 1024 * U << ") {\n";
+    for (int u = 0; u < U; ++u) emit_loads(u, "      ");
+    e.o << "      __builtin_amdgcn_sched_barrier(0);\n";   // (or the scheduler waits for the first load before it issues the others)
+    for (int u = 0; u < U; ++u) emit_compute(u, "      ");
+    e.o << "    }\n";
+    e.o << "    for (; j + 4 <= " << je << "; j += 1024) {\n";
+    emit_loads(0, "      ");
+    emit_compute(0, "      ");
     e.o << "    }\n    acc = gr_comb0(gr_comb0(acc, acc1), gr_comb0(acc2, acc3));\n  }\n";
     e.o << "  for (; j < " << je << "; ++j) {\n";   // at most one lane still has (fewer than four) elements
   } else if (g.red_mode == 0) e.o << "#pragma unroll 4\n  for (long long j = jbeg; j < jend; ++j) {\n";
@@ -957,10 +978,10 @@ void gen_reduce(Em& e) {
   e.o << "  GM " << T << "* const dst = NSPLIT > 1 ? (GM " << T << "*)" << e.slot(e.L.extra + 2) << " + split * NOUT : (GM " << T << "*)" << e.slot(e.L.out) << ";\n";
   if (g.red_mode == 1) {
     e.o << "  acc = gr_lanes0(acc);\n"
-           "  { " << T << "* sm = (" << T << "*)gr_sm;\n"
-           "    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;\n"
-           "    __syncthreads();\n"
-           "    acc = gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3])); }\n"
+           "  " << T << "* const sm = (" << T << "*)gr_sm;\n"
+           "  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;\n"
+           "  __syncthreads();\n"
+           "  acc = gr_comb0(gr_comb0(sm[0], sm[1]), gr_comb0(sm[2], sm[3]));\n"
            "  if (threadIdx.x == 0) dst[o] = acc;\n";
   } else {
     e.o << "  dst[o] = acc;\n";
