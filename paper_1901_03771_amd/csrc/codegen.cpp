@@ -850,40 +850,58 @@ void gen_reduce(Em& e) {
   if (g.red_mode == 0 && g.red_vec) {
     // four consecutive outputs per thread: one dwordx4 per array and reduced element
     const int kd = kr - 1;
-    e.o << "  " << T << " acc1 = acc, acc2 = acc, acc3 = acc;\n#pragma unroll 4\n  for (long long j = jbeg; j < jend; ++j) {\n";
-    if (rank > kr) {
-      e.o << "    long long jrem = j;\n";
-      for (int k = rank - 1; k >= kr; --k) {
-        if (k == kr) e.o << "    const long long i" << k << " = jrem;\n";
-        else e.o << "    const long long i" << k << " = gr_peel(jrem, " << e.dim(k) << ");\n";
+    // (four steps of j written out with all loads first, like the loop of the workgroup-per-chunk kernels below:
+    // "#pragma unroll 4" is dropped by the compiler when the body holds a wave-wide vote)
+    e.o << "  " << T << " acc1 = acc, acc2 = acc, acc3 = acc;\n";
+    auto loads0 = [&](int u, const char* ind) {
+      const std::string su = "_" + std::to_string(u);
+      if (rank > kr) {
+        e.o << ind << "long long jrem" << su << " = j + " << u << ";\n";
+        for (int k = rank - 1; k >= kr; --k) {
+          if (k == kr) e.o << ind << "const long long i" << k << su << " = jrem" << su << ";\n";
+          else e.o << ind << "const long long i" << k << su << " = gr_peel(jrem" << su << ", " << e.dim(k) << ");\n";
+        }
       }
-    }
-    for (size_t i = 0; i < g.prog.size(); ++i) {
-      const Instr& in = g.prog[i];
-      if (in.kind != IKind::LOAD) continue;
-      const AccessGroup& ag = g.groups[in.group];
-      std::ostringstream at;
-      at << "p" << in.group << " + 0";
-      for (int k = 0; k < rank; ++k) {
-        if (ag.structural_zero[k]) continue;
-        if (k >= kr) at << " + (i" << k << " + " << in.delta[k] << ") * " << e.coef(in.group, k);
-        else if (in.delta[k]) at << " + " << in.delta[k] << (k == kd ? std::string("") : " * " + e.coef(in.group, k));
+      for (size_t i = 0; i < g.prog.size(); ++i) {
+        const Instr& in = g.prog[i];
+        if (in.kind != IKind::LOAD) continue;
+        const AccessGroup& ag = g.groups[in.group];
+        std::ostringstream at;
+        at << "p" << in.group << " + 0";
+        for (int k = 0; k < rank; ++k) {
+          if (ag.structural_zero[k]) continue;
+          if (k >= kr) at << " + (i" << k << su << " + " << in.delta[k] << ") * " << e.coef(in.group, k);
+          else if (in.delta[k]) at << " + " << in.delta[k] << (k == kd ? std::string("") : " * " + e.coef(in.group, k));
+        }
+        if (ag.structural_zero[kd]) e.o << ind << "const " << cty(in.dtype) << " u" << i << su << " = (" << at.str() << ")[0];\n";
+        else e.o << ind << "const " << vty4(in.dtype) << " w" << i << su << " = " << e.ld(in.group, vty4(in.dtype), at.str()) << ";\n";
       }
-      if (ag.structural_zero[kd]) e.o << "    const " << cty(in.dtype) << " u" << i << " = (" << at.str() << ")[0];\n";
-      else e.o << "    const " << vty4(in.dtype) << " w" << i << " = " << e.ld(in.group, vty4(in.dtype), at.str()) << ";\n";
-    }
-    for (int c4 = 0; c4 < 4; ++c4) {
-      const std::string pre = "v" + std::to_string(c4) + "_";
-      emit_scalar_program(e, g.prog, {ph.value},
-                          [&](const Instr& in, int id) {
-                            const AccessGroup& ag = g.groups[in.group];
-                            if (ag.structural_zero[kd]) return "u" + std::to_string(id);
-                            return "w" + std::to_string(id) + "[" + std::to_string(c4) + "]";
-                          },
-                          "0.0f", pre, "    ");
-      const std::string a = c4 == 0 ? "acc" : "acc" + std::to_string(c4);
-      e.o << "    " << a << " = " << Em::combine(ph, a, pre + std::to_string(ph.value)) << ";\n";
-    }
+    };
+    auto compute0 = [&](int u, const std::string& ind) {
+      const std::string su = "_" + std::to_string(u);
+      e.o << ind << "{\n";
+      for (int k = rank - 1; k >= kr; --k) e.o << ind << "  const long long i" << k << " = i" << k << su << "; (void)i" << k << ";\n";
+      for (int c4 = 0; c4 < 4; ++c4) {
+        const std::string pre = "v" + std::to_string(c4) + "_";
+        emit_scalar_program(e, g.prog, {ph.value},
+                            [&](const Instr& in, int id) {
+                              const AccessGroup& ag = g.groups[in.group];
+                              if (ag.structural_zero[kd]) return "u" + std::to_string(id) + su;
+                              return "w" + std::to_string(id) + su + "[" + std::to_string(c4) + "]";
+                            },
+                            "0.0f", pre, ind + "  ");
+        const std::string a = c4 == 0 ? "acc" : "acc" + std::to_string(c4);
+        e.o << ind << "  " << a << " = " << Em::combine(ph, a, pre + std::to_string(ph.value)) << ";\n";
+      }
+      e.o << ind << "}\n";
+    };
+    e.o << "  long long j = jbeg;\n  for (; j + 4 <= jend; j += 4) {\n";
+    for (int u = 0; u < 4; ++u) loads0(u, "    ");
+    e.o << "    __builtin_amdgcn_sched_barrier(0);\n";
+    for (int u = 0; u < 4; ++u) compute0(u, "    ");
+    e.o << "  }\n  for (; j < jend; ++j) {\n";
+    loads0(0, "    ");
+    compute0(0, "    ");
     e.o << "  }\n";
     e.o << "  GM " << T << "* const dst = NSPLIT > 1 ? (GM " << T << "*)" << e.slot(e.L.extra + 2) << " + split * NOUT : (GM " << T << "*)" << e.slot(e.L.out) << ";\n";
     e.o << "  dst[o] = acc; dst[o + 1] = acc1; dst[o + 2] = acc2; dst[o + 3] = acc3;\n}\n";
@@ -951,8 +969,46 @@ void gen_reduce(Em& e) {
     emit_compute(0, "      ");
     e.o << "    }\n    acc = gr_comb0(gr_comb0(acc, acc1), gr_comb0(acc2, acc3));\n  }\n";
     e.o << "  for (; j < " << je << "; ++j) {\n";   // at most one lane still has (fewer than four) elements
-  } else if (g.red_mode == 0) e.o << "#pragma unroll 4\n  for (long long j = jbeg; j < jend; ++j) {\n";
-  else e.o << "#pragma unroll 4\n  for (long long j = jbeg + threadIdx.x; j < jend; j += 256) {\n";
+  } else {
+    // one element per step (of a thread, or of each of a workgroup's 256 threads): four steps written out with their
+    // loads first, for the same reason as above; the accumulator takes the elements in the order of j
+    const int STEP = g.red_mode == 0 ? 1 : 256;
+    auto idx = [&](const std::string& su, const std::string& jx, const char* ind) {
+      if (rank > kr) {
+        e.o << ind << "long long jrem" << su << " = " << jx << ";\n";
+        for (int k = rank - 1; k >= kr; --k) {
+          if (k == kr) e.o << ind << "const long long i" << k << su << " = jrem" << su << ";\n";
+          else e.o << ind << "const long long i" << k << su << " = gr_peel(jrem" << su << ", " << e.dim(k) << ");\n";
+        }
+      }
+    };
+    e.o << "  long long j = " << (g.red_mode == 0 ? "jbeg" : "jbeg + threadIdx.x") << ";\n  for (; j + " << 3 * STEP << " < jend; j += " << 4 * STEP << ") {\n";
+    for (int u = 0; u < 4; ++u) {
+      const std::string su = "_" + std::to_string(u);
+      idx(su, "j + " + std::to_string(u * STEP), "    ");
+      for (size_t i = 0; i < g.prog.size(); ++i) {
+        const Instr& in = g.prog[i];
+        if (in.kind != IKind::LOAD) continue;
+        const AccessGroup& ag = g.groups[in.group];
+        e.o << "    const " << cty(in.dtype) << " l" << i << su << " = p" << in.group << "[0";
+        for (int k = 0; k < rank; ++k) {
+          if (ag.structural_zero[k]) continue;
+          if (k >= kr) e.o << " + (i" << k << su << " + " << in.delta[k] << ") * " << e.coef(in.group, k);
+          else if (in.delta[k]) e.o << " + " << in.delta[k] << " * " << e.coef(in.group, k);
+        }
+        e.o << "];\n";
+      }
+    }
+    e.o << "    __builtin_amdgcn_sched_barrier(0);\n";
+    for (int u = 0; u < 4; ++u) {
+      const std::string su = "_" + std::to_string(u);
+      e.o << "    {\n";
+      for (int k = rank - 1; k >= kr; --k) e.o << "      const long long i" << k << " = i" << k << su << "; (void)i" << k << ";\n";
+      emit_scalar_program(e, g.prog, {ph.value}, [&](const Instr&, int id) { return "l" + std::to_string(id) + su; }, "0.0f", "t", "      ");
+      e.o << "      acc = " << Em::combine(ph, "acc", "t" + std::to_string(ph.value)) << ";\n    }\n";
+    }
+    e.o << "  }\n  for (; j < jend; j += " << STEP << ") {\n";
+  }
   if (rank > kr) {
     e.o << "    long long jrem = j;\n";
     for (int k = rank - 1; k >= kr; --k) {
