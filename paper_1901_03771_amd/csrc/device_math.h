@@ -42,7 +42,8 @@
 // the wave" (a ballot) and GR_KEEP_BRANCH as a scheduling barrier, which emits nothing and keeps
 // the compiler from turning a short conditional block back into unconditional selects; a kernel
 // that wants straight-line code (the epilogue of a matrix product over hundreds of accumulators,
-// where branches cost registers) defines them as true and as nothing.
+// where branches cost registers; an epilogue inside a loop that the compiler should pipeline)
+// defines them as true and as nothing.
 GR_DEVICE_MATH_SOURCE(
 static __device__ __forceinline__ float gr_erff(float x) {
   const float a = __builtin_fabsf(x);
@@ -93,7 +94,7 @@ static __device__ __forceinline__ float gr_divc(float x, float c) {
   const unsigned cb = __float_as_uint(c) & 0x7fffffffu;
   const unsigned xb = __float_as_uint(x) & 0x7fffffffu;
   const bool plain = cb - 0x2b800000u <= 0x28000000u && xb - 0x17800000u <= 0x50000000u;
-  if (__builtin_amdgcn_ballot_w64(!plain) != 0ull) return x / c;
+  if (GR_ANY_LANE(!plain)) return x / c;
   const float y0 = __builtin_amdgcn_rcpf(c);
   const float y = __builtin_fmaf(__builtin_fmaf(-c, y0, 1.0f), y0, y0);
   const float q0 = x * y;
