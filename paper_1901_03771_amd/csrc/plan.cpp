@@ -621,6 +621,15 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
   if (g->out_base % 64 != 0) aligned = false;
   const bool narrow_tile = g->rank >= 2 && R > 1 && !shifted_rows && aligned && c->opt_map_bx == 0 && g->BX > 64;
   if (narrow_tile) g->BX = 64;
+  // Views shifted by at most one row up and down (a five-point sweep): 512 columns by four rows per workgroup, two
+  // rows per lane (measured on MI355X against 1024 columns by four rows with four rows per lane, right-hand side of a
+  // Jacobi sweep: 8192^2 92.5 against 97.6 us, 16384 x 4096 93.5 against 104.2, 4096 x 16384 92.6 against 96.8,
+  // 4096^2 30.4 against 31.2, 8190^2 90.9 against 91.7; taller stencils keep the wide tile, within 1-3 % either way)
+  int64_t row_lo = 0, row_hi = 0;
+  for (const AccessGroup& ag : g->groups)
+    for (const auto& d : ag.deltas) if (g->rank >= 2) { row_lo = std::min(row_lo, d[g->rank - 2]); row_hi = std::max(row_hi, d[g->rank - 2]); }
+  const bool low_stencil = shifted_rows && row_hi - row_lo <= 2 && c->opt_map_bx == 0 && g->BX == 256;
+  if (low_stencil) g->BX = 128;
   g->BY = 256 / g->BX;
   auto tiles = [&](int vr, int uc) {
     int64_t tc = (int64_t)g->BX * 4 * uc, tr = (int64_t)g->BY * vr;
@@ -630,7 +639,7 @@ void choose_map_schedule(gr_ctx* c, GroupPlan* g) {
   if (g->rank == 1 || R == 1) {
     for (int uc : {4, 2}) if (tiles(1, uc) >= 2048) { g->UC = uc; break; }
   } else {
-    int want = narrow_tile ? 2 : 4;  // measured on MI355X: 4 rows per lane is the best patch for stencil programs and for broadcast programs on wide tiles
+    int want = narrow_tile || low_stencil ? 2 : 4;  // measured on MI355X: 4 rows per lane is the best patch for tall stencil programs and for broadcast programs on wide tiles
     // (lanes whose patch sticks out of the array take the guarded point-by-point path: with few
     // rows the patch height has to divide them)
     for (int vr = want; vr >= 2; vr >>= 1)
